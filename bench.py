@@ -1,0 +1,252 @@
+#!/usr/bin/env python3
+"""Benchmark of the LoLA layer on one MI355X.
+
+Headline figure (the JSON line's `value`): tokens/s per layer of the 8B-shaped generation step,
+batch 64, every sequence's memories initialised by prefilling 32768 seeded N(0,1) tokens; one
+"step" is one `lola_decode_step` call over the whole batch (window eviction, self-recall scoring,
+top-lambda reselection, state fold, outputs).  The calls cycle over `--layers` independent copies
+of the layer state so that the working set (about 80 MiB per layer) is streamed from HBM rather
+than served from the 256 MB last-level cache, as it would be in a 32-layer model.
+
+Also reported in the same line: `roofline` (algorithmic bytes of one decode launch over its
+measured duration, against 8 TB/s), `prefill` (8B-shaped chunked prefill, B=4 x 4096 tokens:
+tokens/s per layer and algorithmic TFLOP/s against the bf16 MFMA peak) and `cpu_baseline` (the
+CPU oracle timed on a bounded sample of the same decode workload on this machine's cores).
+
+Everything is synthetic and seeded (see workloads.py); inputs are resident in HBM before the
+timed region starts.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def decode_alg_bytes(sh, out_bytes):
+    """Bytes one generation step must move per (sequence, kv head), from the layer's definition:
+    read window and sparse K,V and the slot indices, read and write H, read and write s, read the
+    new pair, write it to its ring slot, write one sparse slot (pair + index), read the group's
+    queries, write their outputs."""
+    e = 2  # bf16
+    d, D, eta, lam, g = sh.d, sh.D, sh.eta, sh.lam, sh.g
+    per_stream = (2 * eta * d * e + 2 * lam * d * e + lam * 4 + 2 * D * d * 4 + 2 * D * 4 + 2 * d * e + 2 * d * e
+                  + (2 * d * e + 4) + g * d * e + g * d * out_bytes)
+    weights = (sh.Hq + sh.Hkv) * d * sh.m * e
+    return per_stream, per_stream * sh.B * sh.Hkv + weights
+
+
+def prefill_alg_flops(sh):
+    """Multiply-adds x 2 of one chunk of one stream in steady state, from the equations."""
+    g, C_, d, D, m, lam, eta = sh.g, sh.C, sh.d, sh.D, sh.m, sh.lam, sh.eta
+    nq, nE, nk = g * C_, lam + C_, lam + eta + C_
+    per_chunk = 2 * (nq * d * m + nE * d * m + 2 * nq * nk * d + nq * D * d + nE * D * d + C_ * D * d)
+    return per_chunk, per_chunk * (sh.T // C_) * sh.B * sh.Hkv
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1024)
+    ap.add_argument("--warmup", type=int, default=32)
+    ap.add_argument("--layers", type=int, default=32, help="independent layer-state copies cycled by the decode loop")
+    ap.add_argument("--prefill-tokens", type=int, default=32768, help="tokens prefilled per sequence before decoding")
+    ap.add_argument("--prefill-reps", type=int, default=5)
+    ap.add_argument("--skip-prefill", action="store_true")
+    ap.add_argument("--skip-cpu", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the layer shards over (batch, kv head) with no exchange, and this "
+              "build has no multi-GPU path; run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workloads as wl
+    from paper_2505_23666_amd import binding as lb
+
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    sh = wl.scaled(4, T=args.prefill_tokens)
+    K, W, L = args.steps, args.warmup, args.layers
+
+    def to_dev(x):
+        return torch.from_numpy(wl.bf16_bits(x).view(np.int16)).to(dev).view(torch.bfloat16)
+
+    Wq, Wk = wl.weights(sh)
+    dWq, dWk = to_dev(Wq), to_dev(Wk)
+
+    # ---- state initialisation: update-only prefill of every sequence, 8 sequences at a time ----
+    t0 = time.time()
+    layers = [lb.LolaLayer(sh.B, sh.Hq, sh.Hkv, sh.d, sh.D, sh.eta, sh.lam, sh.C, dtype="bf16", out_dtype="f32", device=dev)
+              for _ in range(L)]
+    n_tok = (K + W + L - 1) // L
+    qd = np.empty((n_tok, sh.B, sh.Hq, sh.d), np.float32)
+    kd = np.empty((n_tok, sh.B, sh.Hkv, sh.d), np.float32)
+    vd = np.empty((n_tok, sh.B, sh.Hkv, sh.d), np.float32)
+    grp = 8
+    sub = lb.LolaLayer(grp, sh.Hq, sh.Hkv, sh.d, sh.D, sh.eta, sh.lam, sh.C, dtype="bf16", out_dtype="f32", device=dev)
+    fields = ("H", "s", "win_k", "win_v", "sp_k", "sp_v", "sp_idx", "sp_count", "n_tokens")
+    shd = wl.scaled(4, T=args.prefill_tokens, n_decode=n_tok)
+    prefill_ms = 0.0
+    for g0 in range(0, sh.B, grp):
+        with ThreadPoolExecutor(8) as ex:
+            seqs = list(ex.map(lambda b: wl.decode_batch_sequence(shd, b), range(g0, g0 + grp)))
+        kp = to_dev(np.stack([s[0] for s in seqs]))
+        vp = to_dev(np.stack([s[1] for s in seqs]))
+        for i, s in enumerate(seqs):
+            qd[:, g0 + i], kd[:, g0 + i], vd[:, g0 + i] = s[2], s[3], s[4]
+        sub.reset()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        sub.prefill(None, kp, vp, None, dWk)
+        e1.record()
+        torch.cuda.synchronize()
+        prefill_ms += e0.elapsed_time(e1)
+        for name in fields:
+            getattr(layers[0], name)[g0:g0 + grp].copy_(getattr(sub, name))
+        del kp, vp
+    for l in range(1, L):
+        for name in fields:
+            getattr(layers[l], name).copy_(getattr(layers[0], name))
+    torch.cuda.synchronize()
+    log(f"[setup] {sh.B} sequences x {sh.T} tokens prefilled (update-only) in {prefill_ms:.1f} ms GPU time; "
+        f"{L} layer copies; {time.time() - t0:.1f}s wall")
+    state0 = {name: getattr(layers[0], name).clone() for name in fields} if not args.skip_cpu else None
+
+    dq, dk, dv = to_dev(qd), to_dev(kd), to_dev(vd)
+    outs = [torch.empty((sh.B, sh.Hq, sh.d), dtype=torch.float32, device=dev) for _ in range(L)]
+
+    # ---- decode loop: pre-marshalled calls so that the host does not gate the launches ----
+    fn = lb.lib().lola_decode_step
+    stream = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    vp_ = lambda t: C.c_void_p(t.data_ptr())
+    calls = []
+    for i in range(K + W):
+        l, t = i % L, i // L
+        calls.append((C.byref(layers[l].cfg), C.byref(layers[l].st), vp_(dq[t]), vp_(dk[t]), vp_(dv[t]), vp_(dWq), vp_(dWk),
+                      vp_(outs[l]), stream))
+    for i in range(W):
+        rc = fn(*calls[i])
+        assert rc == 0, rc
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t_wall = time.perf_counter()
+    ev0.record()
+    for i in range(W, W + K):
+        rc = fn(*calls[i])
+        if rc != 0:
+            raise RuntimeError(f"lola_decode_step failed: {rc}")
+    ev1.record()
+    torch.cuda.synchronize()
+    t_wall = time.perf_counter() - t_wall
+    gpu_ms = ev0.elapsed_time(ev1)
+    ms_per_step = t_wall * 1e3 / K
+    value = sh.B * K / t_wall
+    per_stream, per_launch = decode_alg_bytes(sh, 4)
+    launch_us = gpu_ms * 1e3 / K      # one kernel launch per step
+    achieved = per_launch / (launch_us * 1e-6) / 1e9
+    log(f"[decode] {K} steps: wall {t_wall * 1e3:.1f} ms, gpu {gpu_ms:.1f} ms, {launch_us:.2f} us/launch, "
+        f"{value / 1e6:.3f} M tokens/s/layer, {achieved:.0f} GB/s algorithmic")
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", "decode_8b_b64_hbm_traffic.md")
+    if os.path.exists(tfile):
+        for line in open(tfile):
+            if line.startswith("traffic_bytes_per_launch:"):
+                traffic = float(line.split(":")[1])
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "kernel": lb.lola_kernel_path(layers[0].cfg, 1) + " decode", "launch_us": round(launch_us, 3),
+                "alg_bytes_per_launch": per_launch}
+
+    # ---- prefill leg (configuration 3) ----
+    prefill = None
+    if not args.skip_prefill:
+        del layers[1:], calls
+        torch.cuda.empty_cache()
+        s3 = wl.CONFIGS[3]
+        W3q, W3k = wl.weights(s3)
+        q3, k3, v3, _ = wl.sequence_inputs(s3)
+        lay = lb.LolaLayer(s3.B, s3.Hq, s3.Hkv, s3.d, s3.D, s3.eta, s3.lam, s3.C, dtype="bf16", out_dtype="f32", device=dev)
+        a = [to_dev(x) for x in (q3, k3, v3, W3q, W3k)]
+        out3 = torch.empty((s3.B, s3.Hq, s3.T, s3.d), dtype=torch.float32, device=dev)
+        times = []
+        for r in range(args.prefill_reps + 1):
+            lay.reset()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            lay.prefill(*a, out=out3)
+            e1.record()
+            torch.cuda.synchronize()
+            if r > 0:
+                times.append(e0.elapsed_time(e1))
+        ms = float(np.mean(times))
+        _, flops = prefill_alg_flops(s3)
+        tf = flops / (ms * 1e-3) / 1e12
+        prefill = {"workload": "configs[2]: 8B-shape prefill B=4 T=4096 eta=64 lambda=128 C=64 bf16",
+                   "tokens_per_s_per_layer": round(s3.B * s3.T / (ms * 1e-3), 1), "ms_per_call": round(ms, 3),
+                   "roofline": {"bound": "mfma", "achieved": round(tf, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 5), "traffic": None,
+                                "alg_flops_per_call": flops, "kernel": lb.lola_kernel_path(lay.cfg, 0) + " prefill"}}
+        log(f"[prefill] {ms:.2f} ms per call, {prefill['tokens_per_s_per_layer'] / 1e6:.3f} M tokens/s/layer, {tf:.2f} TFLOP/s algorithmic")
+        del lay, a, out3
+
+    # ---- CPU baseline: the oracle on a sample of the same decode workload ----
+    cpu = None
+    if not args.skip_cpu:
+        from oracle import lola_oracle as orc
+        n_seq = 8
+        o = orc.Oracle(n_seq, sh.Hq, sh.Hkv, sh.d, sh.D, sh.eta, sh.lam, sh.C)
+        hs = {n: (state0[n][:n_seq].float() if state0[n].dtype == torch.bfloat16 else state0[n][:n_seq]).cpu().numpy() for n in fields}
+        ntk = int(hs["n_tokens"][0, 0])
+        for b in range(n_seq):
+            o.set_n_tokens(b, ntk)
+            for h in range(sh.Hkv):
+                cnt = int(hs["sp_count"][b, h])
+                wtok = np.arange(max(0, ntk - sh.eta), ntk)
+                o.set_stream(b * sh.Hkv + h, hs["H"][b, h], hs["s"][b, h], hs["sp_k"][b, h, :cnt], hs["sp_v"][b, h, :cnt],
+                             hs["sp_idx"][b, h, :cnt], hs["win_k"][b, h][wtok % sh.eta], hs["win_v"][b, h][wtok % sh.eta], wtok)
+        run = lambda t: o.decode_step(qd[t, :n_seq], kd[t, :n_seq], vd[t, :n_seq], Wq, Wk)
+        t1 = time.perf_counter(); run(0); run(1); per = (time.perf_counter() - t1) / 2
+        n_steps = int(max(2, min(n_tok - 2, args.cpu_seconds / max(per, 1e-6))))
+        t1 = time.perf_counter()
+        for t in range(2, 2 + n_steps):
+            run(t)
+        dt = time.perf_counter() - t1
+        cpu = {"value": round(n_seq * n_steps / dt, 2), "unit": "tokens/s/layer", "cores": orc.num_threads(), "kind": "oracle",
+               "sample": f"{n_steps} generation steps of {n_seq} of the 64 sequences ({n_seq * sh.Hkv} streams), started from the "
+                         f"GPU's post-prefill state; {dt:.1f}s"}
+        log(f"[cpu] oracle: {cpu['value']} tokens/s/layer on {cpu['cores']} threads")
+
+    line = {
+        "metric": "LoLA layer tokens/s (prefill & decode, 8B shape) + % HBM/MFMA peak",
+        "value": round(value, 1), "unit": "tokens/s/layer", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "configs[3]: 8B-shape decode, batch 64, 32 q / 8 kv heads, head_dim 128, feat_dim 128, "
+                               f"eta 64, lambda 128, bf16 K/V + fp32 H/s, states prefilled with {sh.T} tokens, "
+                               f"{L} layer-state copies cycled", "global_batch": sh.B, "prefill_tokens": sh.T, "layer_copies": L},
+        "roofline": roofline, "cpu_baseline": cpu, "prefill": prefill,
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

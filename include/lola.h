@@ -1,0 +1,136 @@
+/*
+ * lola.h - C ABI of the MI355X (gfx950) implementation of one LoLA attention layer
+ * (LoLA: Low-Rank Linear Attention with Sparse Caching, arxiv 2505.23666).
+ *
+ * The library owns no memory and never synchronises: every pointer below is a DEVICE pointer
+ * (unless marked host) to caller-owned, contiguous, row-major memory aligned to 16 bytes, and
+ * every call only enqueues kernels on `stream` (a hipStream_t passed as void*; NULL is the
+ * default stream).  Arguments are validated on the host before anything is launched; on error a
+ * negative lola_status is returned and nothing has been enqueued.  Calls on distinct states are
+ * independent; calls on one state must be ordered by the caller (same stream, or events).
+ *
+ * Notation (paper, Sec. 2-3): B batch, Hq query heads, Hkv key/value heads (Hq % Hkv == 0, query
+ * head h reads kv head h / (Hq/Hkv)), d = head_dim = d_k = d_v, D = feat_dim (phi: R^d -> R^D,
+ * D even, m = D/2 learned projections), eta = window, lambda = sparse_budget, C = chunk.
+ * One "stream of memories" exists per (batch, kv head): the recurrent state (H, s), the sliding
+ * window (last min(n, eta) pairs) and the sparse cache (<= lambda pairs with the largest
+ * self-recall error).  Invariant at every call boundary: each of the n tokens seen so far lives in
+ * exactly one of window, sparse cache, or (H, s).
+ */
+#ifndef LOLA_H
+#define LOLA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LOLA_OK = 0,
+    LOLA_ERR_NULL = -1,        /* a required pointer is NULL */
+    LOLA_ERR_SHAPE = -2,       /* a size is out of range or inconsistent */
+    LOLA_ERR_DTYPE = -3,       /* unknown dtype / phi_kind value */
+    LOLA_ERR_ALIGN = -4,       /* a pointer is not 16-byte aligned */
+    LOLA_ERR_UNSUPPORTED = -5, /* valid request this build has no kernel for */
+    LOLA_ERR_WORKSPACE = -6,   /* workspace missing or smaller than the stated minimum */
+    LOLA_ERR_HIP = -7          /* a HIP launch reported an error */
+} lola_status;
+
+enum { LOLA_F32 = 0, LOLA_BF16 = 1 };
+/* Feature map, Sec. 2.3 eq. (feature_map): z = W^T x in R^m.
+ * LOLA_PHI_EXP is the paper's form [exp(z), exp(-z)]; LOLA_PHI_SOFTMAX is the bounded form
+ * [softmax(z), softmax(-z)] the benchmark configurations prescribe. */
+enum { LOLA_PHI_SOFTMAX = 0, LOLA_PHI_EXP = 1 };
+
+typedef struct {
+    int32_t batch, n_q_heads, n_kv_heads;
+    int32_t head_dim;      /* d: 32, 64, 128 or 256 */
+    int32_t feat_dim;      /* D: even, 2..512 */
+    int32_t window;        /* eta >= 0 */
+    int32_t sparse_budget; /* lambda >= 0 */
+    int32_t chunk;         /* C >= 1, prefill only */
+    int32_t dtype;         /* LOLA_F32 | LOLA_BF16: storage type of q, k, v, Wq, Wk and cached K, V */
+    int32_t out_dtype;     /* LOLA_F32 | LOLA_BF16: storage type of `out` */
+    int32_t phi_kind;      /* LOLA_PHI_SOFTMAX | LOLA_PHI_EXP */
+    float softmax_scale;   /* logit scale; <= 0 selects 1/sqrt(head_dim) (Sec. 2.1) */
+} lola_config;
+
+/* The memories of a layer.  H and s are always fp32 (Sec. 2.2, eq. recurrent_update). */
+typedef struct {
+    float *H;          /* [B, Hkv, D, d]      H = sum over folded pairs of phi(k) v^T */
+    float *s;          /* [B, Hkv, D]         s = sum over folded pairs of phi(k) */
+    void *win_k;       /* [B, Hkv, eta, d]    ring buffer: token t sits in slot t % eta */
+    void *win_v;       /* [B, Hkv, eta, d] */
+    void *sp_k;        /* [B, Hkv, lambda, d] sparse cache, slots [0, sp_count) in use, unordered */
+    void *sp_v;        /* [B, Hkv, lambda, d] */
+    int32_t *sp_idx;   /* [B, Hkv, lambda]    token index held by each slot, -1 = empty */
+    int32_t *sp_count; /* [B, Hkv] */
+    int64_t *n_tokens; /* [B, Hkv]            tokens consumed so far (equal across kv heads of a sequence) */
+} lola_state;
+
+/* Bytes of each state field in the order of the struct (host output, 9 entries); returns their
+ * sum, or 0 if the configuration is invalid. */
+size_t lola_state_bytes(const lola_config *cfg, size_t field_bytes[9]);
+
+/* Workspace of lola_prefill for T tokens: returns the size with which all chunks are processed in
+ * one pass; *min_bytes (host, may be NULL) receives the smallest size accepted (the chunks are then
+ * processed in several passes).  0 if the configuration is invalid.  with_outputs = 0 sizes the
+ * update-only call (q == out == NULL). */
+size_t lola_prefill_workspace_bytes(const lola_config *cfg, int32_t T, int32_t with_outputs, size_t *min_bytes);
+
+/* Empty memories: H = 0, s = 0, window and sparse cache empty (appendix "Algorithm Pseudo-Code",
+ * init).  Cached K, V rows are zeroed too so that a state is a deterministic function of its inputs. */
+lola_status lola_state_init(const lola_config *cfg, const lola_state *st, void *stream);
+
+/*
+ * Chunkwise prefill of T >= 0 tokens per sequence (Sec. 3 "Chunkwise Inference"; appendix
+ * update_chunk).  For each chunk of C tokens (the last may be shorter):
+ *   1. every query t of the chunk, every query head:
+ *        y_t = [phi(q_t)^T H + sum_i exp(scale q_t.k_i) v_i] / [phi(q_t)^T s + sum_i exp(scale q_t.k_i)]
+ *      with i over the sparse cache, the window and the tokens <= t of the chunk, all memories as
+ *      they stood when the chunk began (Sec. 3, y_t equation with the chunk sharing one state);
+ *   2. the chunk joins the window; the pairs that no longer fit in eta are, together with the
+ *      sparse cache, scored by self-recall error ||phi(k)^T H / phi(k)^T s - v||_2 (eq. score, with
+ *      the state before this update; recall = 0 while nothing was folded); the lambda largest stay
+ *      in the sparse cache (ties: lower token index stays), the rest are folded:
+ *      H += phi(k) v^T, s += phi(k).  While the candidates number <= lambda all are cached unscored.
+ * q   [B, Hq, T, d], k, v [B, Hkv, T, d], out [B, Hq, T, d] (out_dtype), Wq [Hq, d, m], Wk [Hkv, d, m].
+ * q == out == NULL updates the memories without producing outputs (Wq is then ignored).
+ * sel_trace: NULL, or int32 [B, Hkv, ceil(T/C), lambda] receiving the token indices held by the
+ *   sparse cache after each chunk's update (slot order, -1 = empty slot).
+ * workspace: see lola_prefill_workspace_bytes.  Contents are scratch; calls sharing a workspace
+ *   must be ordered.
+ * May be called repeatedly (the memories carry over) and be followed by lola_decode_step.
+ * Token indices are int32: n_tokens + T must stay below 2^31.
+ */
+lola_status lola_prefill(const lola_config *cfg, const lola_state *st,
+                         const void *q, const void *k, const void *v,
+                         const void *Wq, const void *Wk, int32_t T, void *out,
+                         int32_t *sel_trace, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * One generation step for every sequence (Sec. 3, E_t / G_t / S_t / y_t equations; appendix
+ * update + attend).  Order: (1) the new pair enters the window; once the window holds more than
+ * eta pairs the oldest leaves; (2) the leaving pair and the sparse cache form the eligible set,
+ * scored and cut to lambda exactly as in lola_prefill step 2 (a single pair is folded in steady
+ * state); (3) the outputs of all query heads are computed with the updated memories, the window
+ * including the new token.
+ * q [B, Hq, d], k, v [B, Hkv, d], out [B, Hq, d] (out_dtype).
+ */
+lola_status lola_decode_step(const lola_config *cfg, const lola_state *st,
+                             const void *q, const void *k, const void *v,
+                             const void *Wq, const void *Wk, void *out, void *stream);
+
+/* Human-readable name of a status code (host string, never NULL). */
+const char *lola_status_str(lola_status s);
+
+/* Name of the kernel family the given call would use ("generic", "mfma"); host string.
+ * which: 0 = lola_prefill, 1 = lola_decode_step. */
+const char *lola_kernel_path(const lola_config *cfg, int32_t which);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LOLA_H */

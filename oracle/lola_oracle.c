@@ -42,6 +42,9 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 
 #ifndef ORC_REAL
 #define ORC_REAL double
@@ -578,3 +581,12 @@ int64_t orc_cache_elems(int64_t t, int64_t eta, int64_t lambda, int64_t dk, int6
 }
 
 int orc_real_bytes(void) { return (int)sizeof(real); }
+
+/* threads the parallel loops over streams will use (for reporting the CPU baseline) */
+int orc_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

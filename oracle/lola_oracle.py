@@ -73,6 +73,7 @@ def _lib(real: str) -> C.CDLL:
         L.orc_cache_elems.restype = i64
         L.orc_cache_elems.argtypes = [i64] * 6 + [C.c_int]
         L.orc_real_bytes.restype = C.c_int
+        L.orc_num_threads.restype = C.c_int
         _libs[real] = L
     return _libs[real]
 
@@ -86,6 +87,10 @@ def _f32(a, shape=None):
 
 def _ptr(a):
     return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def num_threads() -> int:
+    return int(_lib("f64").orc_num_threads())
 
 
 def cache_elems(t, eta, lam, dk, dv, D, two_chunks=True) -> int:

@@ -1,0 +1,618 @@
+// Shape-generic kernels of the LoLA layer: plain fp32 FMA arithmetic, any supported shape, both
+// storage types.  They are the reference path on the GPU (fp32 mode, unusual shapes) and the
+// structure the MFMA kernels specialise: a per-stream sequential "scan" that evolves the memories
+// chunk by chunk and leaves per-chunk snapshots, and a chunk-parallel "attend" that produces the
+// outputs from those snapshots.
+//
+// Paper passages: feature map Sec. 2.3 eq. (feature_map); self-recall error Sec. 3 eq. (score);
+// eligible set / top-lambda / fold Sec. 3 (E_t, G_t, S_t, H_t equations); output Sec. 3 (y_t
+// equation); chunk schedule Sec. 3 "Chunkwise Inference".
+#pragma once
+#include "lola_common.h"
+
+namespace lola {
+namespace generic {
+
+constexpr int NT = 256;          // threads per workgroup
+constexpr int NW = NT / WAVE;    // wavefronts per workgroup
+
+__device__ __forceinline__ float block_sum(float v, float *red) {
+    v = wave_sum(v);
+    if ((threadIdx.x % WAVE) == 0) red[threadIdx.x / WAVE] = v;
+    __syncthreads();
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < NW; i++) t += red[i];
+    __syncthreads();
+    return t;
+}
+__device__ __forceinline__ float block_max(float v, float *red) {
+    v = wave_max(v);
+    if ((threadIdx.x % WAVE) == 0) red[threadIdx.x / WAVE] = v;
+    __syncthreads();
+    float t = red[0];
+#pragma unroll
+    for (int i = 1; i < NW; i++) t = fmaxf(t, red[i]);
+    __syncthreads();
+    return t;
+}
+
+// phi of R rows.  xs [R][d] (LDS, fp32 copies of the stored vectors), W [d][m] (global), result
+// ph [R][D] (LDS).  Workgroup-wide; ends with a barrier.
+template <typename T>
+__device__ void phi_rows(const Dims &dm, const T *W, const float *xs, float *ph, int R) {
+    const int tid = threadIdx.x, d = dm.d, m = dm.m, D = dm.D;
+    for (int p = tid; p < R * m; p += NT) {
+        int r = p / m, j = p - r * m;
+        const float *x = xs + r * d;
+        float z = 0.f;
+        for (int i = 0; i < d; i++) z = fmaf(ldf(W, (size_t)i * m + j), x[i], z);
+        ph[r * D + j] = z;
+    }
+    __syncthreads();
+    const int w = tid / WAVE, lane = tid % WAVE;
+    for (int r = w; r < R; r += NW) {
+        float *row = ph + r * D;
+        if (dm.phi_kind == 1) {
+            for (int j = lane; j < m; j += WAVE) {
+                float z = row[j];
+                row[j] = expf(z);
+                row[m + j] = expf(-z);
+            }
+        } else {
+            float zmax = -INFINITY, zmin = INFINITY;
+            for (int j = lane; j < m; j += WAVE) {
+                float z = row[j];
+                zmax = fmaxf(zmax, z);
+                zmin = fminf(zmin, z);
+            }
+            zmax = wave_max(zmax);
+            zmin = wave_min(zmin);
+            float sp = 0.f, sn = 0.f;
+            for (int j = lane; j < m; j += WAVE) {
+                float z = row[j];
+                float ep = expf(z - zmax), en = expf(zmin - z);
+                row[j] = ep;
+                row[m + j] = en;
+                sp += ep;
+                sn += en;
+            }
+            sp = wave_sum(sp);
+            sn = wave_sum(sn);
+            for (int j = lane; j < m; j += WAVE) {
+                row[j] = row[j] / sp;
+                row[m + j] = row[m + j] / sn;
+            }
+        }
+    }
+    __syncthreads();
+}
+
+// Self-recall error of R pairs against (H, s): ph [R][D], vs [R][d] in LDS; err [R][d], den [R] LDS
+// scratch; score_out[r] = || ph_r^T H / ph_r^T s - v_r ||_2 (recall = 0 while ph_r^T s == 0).
+__device__ void score_rows(const Dims &dm, const float *H, const float *s, const float *ph, const float *vs,
+                           float *err, float *den, float *score_out, int R) {
+    const int tid = threadIdx.x, d = dm.d, D = dm.D;
+    const int w = tid / WAVE, lane = tid % WAVE;
+    for (int r = w; r < R; r += NW) {
+        float a = 0.f;
+        for (int f = lane; f < D; f += WAVE) a = fmaf(ph[r * D + f], s[f], a);
+        a = wave_sum(a);
+        if (lane == 0) den[r] = a;
+    }
+    __syncthreads();
+    const int c = tid % d, rg = tid / d, nrg = NT / d;
+    for (int r = rg; r < R; r += nrg) {
+        const float *p = ph + r * D;
+        float acc = 0.f;
+        for (int f = 0; f < D; f++) acc = fmaf(p[f], H[(size_t)f * d + c], acc);
+        float dn = den[r];
+        float pred = dn > 0.f ? acc / dn : 0.f;
+        float e = pred - vs[r * d + c];
+        err[r * d + c] = e * e;
+    }
+    __syncthreads();
+    for (int r = w; r < R; r += NW) {
+        float a = 0.f;
+        for (int c2 = lane; c2 < d; c2 += WAVE) a += err[r * d + c2];
+        a = wave_sum(a);
+        if (lane == 0) score_out[r] = sqrtf(a);
+    }
+    __syncthreads();
+}
+
+// ---------------------------------------------------------------------------------------------
+// state init
+// ---------------------------------------------------------------------------------------------
+__global__ void fill_u32_kernel(uint32_t *p, size_t n, uint32_t val) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) p[i] = val;
+}
+
+// ---------------------------------------------------------------------------------------------
+// decode: one workgroup per (batch, kv head)
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+struct DecodeArgs {
+    Dims dm;
+    State<T> st;
+    const T *q, *k, *v, *Wq, *Wk;
+    void *out;
+    int R;          // rows scored per tile
+};
+
+template <typename T, typename TO>
+__global__ __launch_bounds__(NT) void decode_kernel(DecodeArgs<T> a) {
+    extern __shared__ float smem[];
+    const Dims &dm = a.dm;
+    const int tid = threadIdx.x, d = dm.d, D = dm.D, m = dm.m, eta = dm.eta, lam = dm.lam, R = a.R;
+    const int si = blockIdx.x, b = si / dm.Hkv, h = si % dm.Hkv;
+    float *xs = smem;                  // [R][d]
+    float *ph = xs + R * d;            // [R][D]
+    float *vs = ph + R * D;            // [R][d]
+    float *err = vs + R * d;           // [R][d]
+    float *den = err + R * d;          // [R]
+    float *score = den + R;            // [lam + 1]
+    float *pk = score + (lam + 1);     // [d] leaving pair
+    float *pv = pk + d;                // [d]
+    float *pw = pv + d;                // [lam + eta] softmax weights
+    float *red = pw + (lam + eta);     // [NW * 3]
+    __shared__ int sh_drop;
+
+    float *H = a.st.H + (size_t)si * D * d;
+    float *s = a.st.s + (size_t)si * D;
+    T *win_k = a.st.win_k + (size_t)si * eta * d, *win_v = a.st.win_v + (size_t)si * eta * d;
+    T *sp_k = a.st.sp_k + (size_t)si * lam * d, *sp_v = a.st.sp_v + (size_t)si * lam * d;
+    int32_t *sp_idx = a.st.sp_idx + (size_t)si * lam;
+    const T *Wk = a.Wk + (size_t)h * d * m;
+    const T *knew = a.k + (size_t)si * d, *vnew = a.v + (size_t)si * d;
+
+    const int64_t tok = a.st.n_tokens[si];
+    const bool popped = tok >= (int64_t)eta;
+    const int slot = eta > 0 ? (int)(tok % eta) : 0;
+    const int32_t pidx = (int32_t)(tok - eta);
+    int spc = a.st.sp_count[si];
+
+    // 1. the new pair enters the window (ring slot tok % eta); the pair it displaces leaves
+    if (popped) {
+        for (int i = tid; i < d; i += NT) {
+            pk[i] = eta > 0 ? ldf(win_k, (size_t)slot * d + i) : ldf(knew, i);
+            pv[i] = eta > 0 ? ldf(win_v, (size_t)slot * d + i) : ldf(vnew, i);
+        }
+    }
+    __syncthreads();
+    if (eta > 0) {
+        for (int i = tid; i < d; i += NT) {
+            win_k[(size_t)slot * d + i] = knew[i];
+            win_v[(size_t)slot * d + i] = vnew[i];
+        }
+    }
+
+    // 2. eligible set = sparse cache + leaving pair
+    if (popped) {
+        if (spc < lam) {
+            for (int i = tid; i < d; i += NT) {
+                stf(sp_k, (size_t)spc * d + i, pk[i]);
+                stf(sp_v, (size_t)spc * d + i, pv[i]);
+            }
+            if (tid == 0) { sp_idx[spc] = pidx; a.st.sp_count[si] = spc + 1; }
+            spc += 1;
+        } else {
+            int drop = 0;   // candidate index: < lam a sparse slot, == lam the leaving pair
+            if (lam > 0) {
+                for (int t0 = 0; t0 <= lam; t0 += R) {
+                    int nr = min(R, lam + 1 - t0);
+                    for (int p = tid; p < nr * d; p += NT) {
+                        int r = p / d, i = p - r * d, e = t0 + r;
+                        xs[p] = e < lam ? ldf(sp_k, (size_t)e * d + i) : pk[i];
+                        vs[p] = e < lam ? ldf(sp_v, (size_t)e * d + i) : pv[i];
+                    }
+                    __syncthreads();
+                    phi_rows(dm, Wk, xs, ph, nr);
+                    score_rows(dm, H, s, ph, vs, err, den, score + t0, nr);
+                }
+                // the pair that goes: smallest score, ties -> the larger token index goes
+                if (tid < WAVE) {
+                    float bs = INFINITY; int bi = -1, be = 0;
+                    for (int e = tid; e <= lam; e += WAVE) {
+                        float sc = score[e]; int ix = e < lam ? sp_idx[e] : pidx;
+                        if (sc < bs || (sc == bs && ix > bi)) { bs = sc; bi = ix; be = e; }
+                    }
+                    for (int o = WAVE / 2; o > 0; o >>= 1) {
+                        float os = __shfl_xor(bs, o, WAVE); int oi = __shfl_xor(bi, o, WAVE), oe = __shfl_xor(be, o, WAVE);
+                        if (os < bs || (os == bs && oi > bi)) { bs = os; bi = oi; be = oe; }
+                    }
+                    if (tid == 0) sh_drop = be;
+                }
+                __syncthreads();
+                drop = sh_drop;
+            }
+            // fold the dropped pair: H += phi(k) v^T, s += phi(k)
+            for (int i = tid; i < d; i += NT) {
+                xs[i] = drop < lam ? ldf(sp_k, (size_t)drop * d + i) : pk[i];
+                vs[i] = drop < lam ? ldf(sp_v, (size_t)drop * d + i) : pv[i];
+            }
+            __syncthreads();
+            phi_rows(dm, Wk, xs, ph, 1);
+            for (int idx = tid; idx < D * d; idx += NT) {
+                int f = idx / d, c = idx - f * d;
+                H[idx] = fmaf(ph[f], vs[c], H[idx]);
+            }
+            for (int f = tid; f < D; f += NT) s[f] += ph[f];
+            __syncthreads();
+            if (drop < lam) {   // the leaving pair takes the freed slot
+                for (int i = tid; i < d; i += NT) {
+                    stf(sp_k, (size_t)drop * d + i, pk[i]);
+                    stf(sp_v, (size_t)drop * d + i, pv[i]);
+                }
+                if (tid == 0) sp_idx[drop] = pidx;
+            }
+        }
+    }
+    __syncthreads();
+
+    // 3. outputs of the group's query heads with the updated memories
+    const int wn = (int)min((int64_t)eta, tok + 1);
+    const int nk = spc + wn;
+    TO *out = (TO *)a.out;
+    for (int r = 0; r < dm.g; r++) {
+        const int hq = h * dm.g + r;
+        const T *qrow = a.q + ((size_t)b * dm.Hq + hq) * d;
+        for (int i = tid; i < d; i += NT) xs[i] = ldf(qrow, i);
+        __syncthreads();
+        phi_rows(dm, a.Wq + (size_t)hq * d * m, xs, ph, 1);
+        float lmax = 0.f;     // m = max(0, max logit): the linear terms carry weight exp(-m) <= 1
+        for (int i = tid; i < nk; i += NT) {
+            const T *kr = i < spc ? sp_k + (size_t)i * d : win_k + (size_t)(i - spc) * d;
+            float dot = 0.f;
+            for (int j = 0; j < d; j++) dot = fmaf(xs[j], ldf(kr, j), dot);
+            dot *= dm.scale;
+            pw[i] = dot;
+            lmax = fmaxf(lmax, dot);
+        }
+        lmax = block_max(lmax, red);
+        float psum = 0.f;
+        for (int i = tid; i < nk; i += NT) {
+            float p = expf(pw[i] - lmax);
+            pw[i] = p;
+            psum += p;
+        }
+        psum = block_sum(psum, red);
+        float lden = 0.f;
+        for (int f = tid; f < D; f += NT) lden = fmaf(ph[f], s[f], lden);
+        lden = block_sum(lden, red);
+        const float elin = expf(-lmax);
+        const int c = tid % d, part = tid / d, nparts = NT / d;
+        float num = 0.f;
+        for (int i = part; i < nk; i += nparts) {
+            const T *vr = i < spc ? sp_v + (size_t)i * d : win_v + (size_t)(i - spc) * d;
+            num = fmaf(pw[i], ldf(vr, c), num);
+        }
+        float lin = 0.f;
+        for (int f = part; f < D; f += nparts) lin = fmaf(ph[f], H[(size_t)f * d + c], lin);
+        num = fmaf(elin, lin, num);
+        err[part * d + c] = num;
+        __syncthreads();
+        if (tid < d) {
+            float t = 0.f;
+            for (int p = 0; p < nparts; p++) t += err[p * d + tid];
+            stf(out, ((size_t)b * dm.Hq + hq) * d + tid, t / (psum + elin * lden));
+        }
+        __syncthreads();
+    }
+    if (tid == 0) a.st.n_tokens[si] = tok + 1;
+}
+
+// ---------------------------------------------------------------------------------------------
+// prefill
+// ---------------------------------------------------------------------------------------------
+// Rows of one stream during a prefill call are addressed by a "virtual row":
+//   [0, lam)            copy of the sparse cache as it stood at entry,
+//   [lam, lam + eta)    copy of the entry window, chronological, right-aligned,
+//   P + i               token i of this call (P = lam + eta);
+// token t (t >= a0 - eta, a0 = tokens consumed before the call) sits at row P + (t - a0).
+template <typename T>
+struct PrefillArgs {
+    Dims dm;
+    State<T> st;
+    const T *q, *k, *v, *Wq, *Wk;
+    void *out;
+    int T_tokens, n_chunks;   // of the whole call
+    int j0, j1;               // chunk range of this pass
+    T *prefK, *prefV;         // [B*Hkv][P][d]
+    int32_t *sp_row;          // [B*Hkv][lam] virtual row held by each sparse slot
+    float *phiE;              // [B*Hkv][lam + C][D] features of the eligible set (scan scratch)
+    float *snapH, *snapS;     // [B*Hkv][S][D][d], [B*Hkv][S][D]: state at the entry of each chunk of the pass
+    int32_t *snapG;           // [B*Hkv][S][lam]: virtual rows of the sparse cache at chunk entry, -1 = empty
+    int S;                    // chunks per pass (snapshot capacity)
+    int want_out;             // 0: update only (no snapshots)
+    int32_t *sel_trace;       // [B*Hkv][n_chunks][lam] or NULL
+    int R;                    // rows per scoring tile
+    int QT;                   // queries per attend tile
+};
+
+template <typename T>
+__global__ __launch_bounds__(NT) void prefix_kernel(PrefillArgs<T> a) {
+    const Dims &dm = a.dm;
+    const int si = blockIdx.x, tid = threadIdx.x, d = dm.d, eta = dm.eta, lam = dm.lam, P = lam + eta;
+    const int64_t a0 = a.st.n_tokens[si];
+    T *pK = a.prefK + (size_t)si * P * d, *pV = a.prefV + (size_t)si * P * d;
+    const T *sp_k = a.st.sp_k + (size_t)si * lam * d, *sp_v = a.st.sp_v + (size_t)si * lam * d;
+    const T *win_k = a.st.win_k + (size_t)si * eta * d, *win_v = a.st.win_v + (size_t)si * eta * d;
+    for (int p = tid; p < lam * d; p += NT) { pK[p] = sp_k[p]; pV[p] = sp_v[p]; }
+    for (int s = tid; s < lam; s += NT) a.sp_row[(size_t)si * lam + s] = s;
+    const int nw = (int)min((int64_t)eta, a0);
+    for (int p = tid; p < nw * d; p += NT) {
+        int back = p / d + 1, i = p % d;          // token a0 - back
+        int slot = (int)((a0 - back) % eta);
+        size_t row = (size_t)(P - back);
+        pK[row * d + i] = win_k[(size_t)slot * d + i];
+        pV[row * d + i] = win_v[(size_t)slot * d + i];
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(NT) void finalize_kernel(PrefillArgs<T> a) {
+    const Dims &dm = a.dm;
+    const int si = blockIdx.x, tid = threadIdx.x, d = dm.d, eta = dm.eta;
+    const int64_t a0 = a.st.n_tokens[si];
+    const int Tn = a.T_tokens;
+    T *win_k = a.st.win_k + (size_t)si * eta * d, *win_v = a.st.win_v + (size_t)si * eta * d;
+    const T *k = a.k + (size_t)si * Tn * d, *v = a.v + (size_t)si * Tn * d;
+    const int first = max(0, Tn - eta);       // tokens of this call that end in the window
+    for (int p = tid; p < (Tn - first) * d; p += NT) {
+        int i = first + p / d, c = p % d;
+        int slot = (int)((a0 + i) % eta);
+        win_k[(size_t)slot * d + c] = k[(size_t)i * d + c];
+        win_v[(size_t)slot * d + c] = v[(size_t)i * d + c];
+    }
+    __syncthreads();
+    if (tid == 0) a.st.n_tokens[si] = a0 + Tn;
+}
+
+// Sequential evolution of one stream's memories over the chunks [j0, j1).
+template <typename T>
+__global__ __launch_bounds__(NT) void scan_kernel(PrefillArgs<T> a) {
+    extern __shared__ float smem[];
+    const Dims &dm = a.dm;
+    const int tid = threadIdx.x, d = dm.d, D = dm.D, m = dm.m, eta = dm.eta, lam = dm.lam, C = dm.C, R = a.R;
+    const int P = lam + eta, nEmax = lam + C;
+    const int si = blockIdx.x, h = si % dm.Hkv;
+    float *xs = smem;                   // [R][d]
+    float *ph = xs + R * d;             // [R][D]
+    float *vs = ph + R * D;             // [R][d]
+    float *err = vs + R * d;            // [R][d]
+    float *den = err + R * d;           // [R]
+    float *score = den + R;             // [nEmax]
+    int *cidx = (int *)(score + nEmax); // [nEmax] token index of each candidate
+    int *keep = cidx + nEmax;           // [nEmax]
+    int *flist = keep + nEmax;          // [nEmax] candidates to fold
+    int *eslot = flist + nEmax;         // [C] destination slot of each entrant
+    int *ecand = eslot + C;             // [C] candidate index of each entrant
+    __shared__ int sh_nf, sh_ne;
+
+    float *H = a.st.H + (size_t)si * D * d;
+    float *s = a.st.s + (size_t)si * D;
+    T *sp_k = a.st.sp_k + (size_t)si * lam * d, *sp_v = a.st.sp_v + (size_t)si * lam * d;
+    int32_t *sp_idx = a.st.sp_idx + (size_t)si * lam;
+    int32_t *sp_row = a.sp_row + (size_t)si * lam;
+    float *phiE = a.phiE + (size_t)si * nEmax * D;
+    const T *Wk = a.Wk + (size_t)h * d * m;
+    const T *pK = a.prefK + (size_t)si * P * d, *pV = a.prefV + (size_t)si * P * d;
+    const T *kc = a.k + (size_t)si * a.T_tokens * d, *vc = a.v + (size_t)si * a.T_tokens * d;
+    const int64_t a0 = a.st.n_tokens[si];
+    int spc = a.st.sp_count[si];
+
+    for (int j = a.j0; j < a.j1; j++) {
+        const int cl = min(C, a.T_tokens - j * C);
+        const int64_t aj = a0 + (int64_t)j * C;
+        if (a.want_out) {   // snapshot of the memories the chunk's queries read
+            const size_t sj = (size_t)si * a.S + (j - a.j0);
+            float *sH = a.snapH + sj * D * d, *sS = a.snapS + sj * D;
+            int32_t *sG = a.snapG + sj * lam;
+            for (int idx = tid; idx < D * d; idx += NT) sH[idx] = H[idx];
+            for (int f = tid; f < D; f += NT) sS[f] = s[f];
+            for (int sl = tid; sl < lam; sl += NT) sG[sl] = sl < spc ? sp_row[sl] : -1;
+        }
+        // tokens leaving the window once the chunk has joined it
+        const int64_t lo = max((int64_t)0, aj - eta), hi = max((int64_t)0, aj + cl - eta);
+        const int n_ev = (int)(hi - lo);
+        const int vrow0 = P + (int)(lo - a0);
+        if (n_ev > 0 && spc + n_ev <= lam) {
+            // warm-up: everything is cached, nothing scored
+            for (int p = tid; p < n_ev * d; p += NT) {
+                int e = p / d, i = p - e * d, vr = vrow0 + e;
+                const T *ksrc = vr < P ? pK + (size_t)vr * d : kc + (size_t)(vr - P) * d;
+                const T *vsrc = vr < P ? pV + (size_t)vr * d : vc + (size_t)(vr - P) * d;
+                sp_k[(size_t)(spc + e) * d + i] = ksrc[i];
+                sp_v[(size_t)(spc + e) * d + i] = vsrc[i];
+            }
+            for (int e = tid; e < n_ev; e += NT) { sp_idx[spc + e] = (int32_t)(lo + e); sp_row[spc + e] = vrow0 + e; }
+            spc += n_ev;
+            __syncthreads();
+        } else if (n_ev > 0) {
+            const int nE = spc + n_ev;
+            for (int t0 = 0; t0 < nE; t0 += R) {
+                int nr = min(R, nE - t0);
+                for (int p = tid; p < nr * d; p += NT) {
+                    int r = p / d, i = p - r * d, e = t0 + r;
+                    if (e < spc) {
+                        xs[p] = ldf(sp_k, (size_t)e * d + i);
+                        vs[p] = ldf(sp_v, (size_t)e * d + i);
+                    } else {
+                        int vr = vrow0 + (e - spc);
+                        xs[p] = vr < P ? ldf(pK, (size_t)vr * d + i) : ldf(kc, (size_t)(vr - P) * d + i);
+                        vs[p] = vr < P ? ldf(pV, (size_t)vr * d + i) : ldf(vc, (size_t)(vr - P) * d + i);
+                    }
+                }
+                __syncthreads();
+                phi_rows(dm, Wk, xs, ph, nr);
+                for (int p = tid; p < nr * D; p += NT) phiE[(size_t)t0 * D + p] = ph[p];
+                score_rows(dm, H, s, ph, vs, err, den, score + t0, nr);
+            }
+            for (int e = tid; e < nE; e += NT) cidx[e] = e < spc ? sp_idx[e] : (int)(lo + (e - spc));
+            __syncthreads();
+            // rank by (score descending, token index ascending); the first lam stay
+            for (int e = tid; e < nE; e += NT) {
+                float sc = score[e]; int ix = cidx[e], rank = 0;
+                for (int o = 0; o < nE; o++) {
+                    float so = score[o];
+                    rank += (so > sc || (so == sc && cidx[o] < ix)) ? 1 : 0;
+                }
+                keep[e] = rank < lam;
+            }
+            __syncthreads();
+            if (tid == 0) {
+                int nf = 0, ne = 0, nfree = 0;
+                for (int e = 0; e < nE; e++) if (!keep[e]) flist[nf++] = e;
+                // free slots: those of leaving cache entries, then the never-used tail
+                for (int e = spc; e < nE; e++) if (keep[e]) ecand[ne++] = e;
+                for (int e = 0; e < spc && nfree < ne; e++) if (!keep[e]) eslot[nfree++] = e;
+                for (int sl = spc; sl < lam && nfree < ne; sl++) eslot[nfree++] = sl;
+                sh_nf = nf; sh_ne = ne;
+            }
+            __syncthreads();
+            const int nf = sh_nf, ne = sh_ne;
+            // fold: H += sum phi(k) v^T, s += sum phi(k) over the pairs that do not stay
+            for (int idx = tid; idx < D * d; idx += NT) {
+                int f = idx / d, c = idx - f * d;
+                float acc = 0.f;
+                for (int x = 0; x < nf; x++) {
+                    int e = flist[x];
+                    float val;
+                    if (e < spc) val = ldf(sp_v, (size_t)e * d + c);
+                    else { int vr = vrow0 + (e - spc); val = vr < P ? ldf(pV, (size_t)vr * d + c) : ldf(vc, (size_t)(vr - P) * d + c); }
+                    acc = fmaf(phiE[(size_t)e * D + f], val, acc);
+                }
+                H[idx] += acc;
+            }
+            for (int f = tid; f < D; f += NT) {
+                float acc = 0.f;
+                for (int x = 0; x < nf; x++) acc += phiE[(size_t)flist[x] * D + f];
+                s[f] += acc;
+            }
+            __syncthreads();
+            // compaction: entrants overwrite the slots that were freed
+            for (int p = tid; p < ne * d; p += NT) {
+                int x = p / d, i = p - x * d;
+                int vr = vrow0 + (ecand[x] - spc), sl = eslot[x];
+                const T *ksrc = vr < P ? pK + (size_t)vr * d : kc + (size_t)(vr - P) * d;
+                const T *vsrc = vr < P ? pV + (size_t)vr * d : vc + (size_t)(vr - P) * d;
+                sp_k[(size_t)sl * d + i] = ksrc[i];
+                sp_v[(size_t)sl * d + i] = vsrc[i];
+            }
+            for (int x = tid; x < ne; x += NT) {
+                sp_idx[eslot[x]] = cidx[ecand[x]];
+                sp_row[eslot[x]] = vrow0 + (ecand[x] - spc);
+            }
+            spc = lam;
+            __syncthreads();
+        }
+        if (a.sel_trace) {
+            int32_t *tr = a.sel_trace + ((size_t)si * a.n_chunks + j) * lam;
+            for (int sl = tid; sl < lam; sl += NT) tr[sl] = sl < spc ? sp_idx[sl] : -1;
+        }
+        __syncthreads();
+    }
+    if (tid == 0) a.st.sp_count[si] = spc;
+}
+
+// Outputs of one chunk of one query head from the snapshot taken at the chunk's entry.
+template <typename T, typename TO>
+__global__ __launch_bounds__(NT) void attend_kernel(PrefillArgs<T> a) {
+    extern __shared__ float smem[];
+    const Dims &dm = a.dm;
+    const int tid = threadIdx.x, d = dm.d, D = dm.D, m = dm.m, eta = dm.eta, lam = dm.lam, C = dm.C, QT = a.QT;
+    const int P = lam + eta, nkmax = lam + eta + C;
+    const int jj = blockIdx.x, j = a.j0 + jj, hq = blockIdx.y, b = blockIdx.z;
+    const int h = hq / dm.g, si = b * dm.Hkv + h;
+    float *qs = smem;                 // [QT][d]
+    float *phq = qs + QT * d;         // [QT][D]
+    float *pw = phq + QT * D;         // [QT][nkmax]
+    float *rmax = pw + QT * nkmax;    // [QT]
+    float *rsum = rmax + QT;          // [QT]
+    float *rlin = rsum + QT;          // [QT]
+
+    const int64_t a0 = a.st.n_tokens[si];
+    const int Tn = a.T_tokens;
+    const int cl = min(C, Tn - j * C);
+    const int64_t aj = a0 + (int64_t)j * C;
+    const int64_t lo = max((int64_t)0, aj - eta);
+    const int vrow0 = P + (int)(lo - a0);
+    const int nwin = (int)(aj + cl - lo);          // window at entry + the whole chunk
+    const int nk = lam + nwin;
+    const size_t sj = (size_t)si * a.S + jj;
+    const float *Hj = a.snapH + sj * D * d, *sjv = a.snapS + sj * D;
+    const int32_t *G = a.snapG + sj * lam;
+    const T *pK = a.prefK + (size_t)si * P * d, *pV = a.prefV + (size_t)si * P * d;
+    const T *kc = a.k + (size_t)si * Tn * d, *vc = a.v + (size_t)si * Tn * d;
+    const T *qh = a.q + (((size_t)b * dm.Hq + hq) * Tn + (size_t)j * C) * d;
+    TO *oh = (TO *)a.out + (((size_t)b * dm.Hq + hq) * Tn + (size_t)j * C) * d;
+    const T *Wq = a.Wq + (size_t)hq * d * m;
+    const int w = tid / WAVE, lane = tid % WAVE;
+
+    for (int i0 = 0; i0 < cl; i0 += QT) {
+        const int nq = min(QT, cl - i0);
+        for (int p = tid; p < nq * d; p += NT) qs[p] = ldf(qh, (size_t)i0 * d + p);
+        __syncthreads();
+        phi_rows(dm, Wq, qs, phq, nq);
+        // logits; a key is visible to query i iff it is cached, in the entry window, or a chunk token <= i
+        for (int p = tid; p < nq * nk; p += NT) {
+            int qi = p / nk, key = p - qi * nk;
+            int vr; bool ok;
+            if (key < lam) { vr = G[key]; ok = vr >= 0; }
+            else { int x = key - lam; vr = vrow0 + x; ok = (lo + x) <= (aj + i0 + qi); }
+            float l = -INFINITY;
+            if (ok) {
+                const T *kr = vr < P ? pK + (size_t)vr * d : kc + (size_t)(vr - P) * d;
+                const float *qv = qs + qi * d;
+                float dot = 0.f;
+                for (int c = 0; c < d; c++) dot = fmaf(qv[c], ldf(kr, c), dot);
+                l = dot * dm.scale;
+            }
+            pw[qi * nkmax + key] = l;
+        }
+        __syncthreads();
+        for (int qi = w; qi < nq; qi += NW) {
+            float *row = pw + qi * nkmax;
+            float mx = 0.f;
+            for (int key = lane; key < nk; key += WAVE) mx = fmaxf(mx, row[key]);
+            mx = wave_max(mx);
+            float sum = 0.f;
+            for (int key = lane; key < nk; key += WAVE) {
+                float p = expf(row[key] - mx);    // exp(-inf) = 0 for masked keys
+                row[key] = p;
+                sum += p;
+            }
+            sum = wave_sum(sum);
+            float lin = 0.f;
+            for (int f = lane; f < D; f += WAVE) lin = fmaf(phq[qi * D + f], sjv[f], lin);
+            lin = wave_sum(lin);
+            if (lane == 0) { rmax[qi] = mx; rsum[qi] = sum; rlin[qi] = lin; }
+        }
+        __syncthreads();
+        const int c = tid % d, part = tid / d, nparts = NT / d;
+        for (int qi = part; qi < nq; qi += nparts) {
+            const float *row = pw + qi * nkmax;
+            float num = 0.f;
+            for (int key = 0; key < nk; key++) {
+                float p = row[key];
+                if (p != 0.f) {
+                    int vr = key < lam ? G[key] : vrow0 + (key - lam);
+                    float val = vr < P ? ldf(pV, (size_t)vr * d + c) : ldf(vc, (size_t)(vr - P) * d + c);
+                    num = fmaf(p, val, num);
+                }
+            }
+            float lin = 0.f;
+            const float *pq = phq + qi * D;
+            for (int f = 0; f < D; f++) lin = fmaf(pq[f], Hj[(size_t)f * d + c], lin);
+            const float elin = expf(-rmax[qi]);
+            stf(oh, (size_t)(i0 + qi) * d + c, fmaf(elin, lin, num) / (rsum[qi] + elin * rlin[qi]));
+        }
+        __syncthreads();
+    }
+}
+
+}  // namespace generic
+}  // namespace lola

@@ -1,0 +1,276 @@
+// C ABI of the LoLA layer library (see include/lola.h): host-side validation, workspace carving
+// and kernel dispatch.  Nothing here allocates or synchronises.
+#include "../../include/lola.h"
+#include "generic_kernels.h"
+
+using namespace lola;
+
+namespace {
+
+constexpr size_t ALIGN = 256;
+inline size_t up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
+inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+inline size_t esize(int dtype) { return dtype == LOLA_BF16 ? 2 : 4; }
+
+constexpr size_t LDS_LIMIT = 64 * 1024 - 256;   // static workgroup limit minus the kernels' few static words
+
+lola_status check_config(const lola_config *c) {
+    if (!c) return LOLA_ERR_NULL;
+    if (c->dtype != LOLA_F32 && c->dtype != LOLA_BF16) return LOLA_ERR_DTYPE;
+    if (c->out_dtype != LOLA_F32 && c->out_dtype != LOLA_BF16) return LOLA_ERR_DTYPE;
+    if (c->phi_kind != LOLA_PHI_SOFTMAX && c->phi_kind != LOLA_PHI_EXP) return LOLA_ERR_DTYPE;
+    if (c->batch < 1 || c->n_kv_heads < 1 || c->n_q_heads < c->n_kv_heads || c->n_q_heads % c->n_kv_heads)
+        return LOLA_ERR_SHAPE;
+    if (c->head_dim != 32 && c->head_dim != 64 && c->head_dim != 128 && c->head_dim != 256) return LOLA_ERR_SHAPE;
+    if (c->feat_dim < 2 || c->feat_dim > 512 || (c->feat_dim & 1)) return LOLA_ERR_SHAPE;
+    if (c->window < 0 || c->sparse_budget < 0 || c->chunk < 1) return LOLA_ERR_SHAPE;
+    if (c->window > 4096 || c->sparse_budget > 4096 || c->chunk > 1024) return LOLA_ERR_SHAPE;
+    if ((long long)c->batch * c->n_kv_heads > (1ll << 24)) return LOLA_ERR_SHAPE;
+    return LOLA_OK;
+}
+
+Dims make_dims(const lola_config *c) {
+    Dims dm;
+    dm.B = c->batch; dm.Hq = c->n_q_heads; dm.Hkv = c->n_kv_heads; dm.g = dm.Hq / dm.Hkv;
+    dm.d = c->head_dim; dm.D = c->feat_dim; dm.m = dm.D / 2;
+    dm.eta = c->window; dm.lam = c->sparse_budget; dm.C = c->chunk;
+    dm.phi_kind = c->phi_kind;
+    dm.scale = c->softmax_scale > 0.f ? c->softmax_scale : 1.0f / sqrtf((float)c->head_dim);
+    return dm;
+}
+
+lola_status check_state(const lola_config *c, const lola_state *st) {
+    if (!st || !st->H || !st->s || !st->sp_count || !st->n_tokens) return LOLA_ERR_NULL;
+    if (c->window > 0 && (!st->win_k || !st->win_v)) return LOLA_ERR_NULL;
+    if (c->sparse_budget > 0 && (!st->sp_k || !st->sp_v || !st->sp_idx)) return LOLA_ERR_NULL;
+    const void *ps[] = {st->H, st->s, st->win_k, st->win_v, st->sp_k, st->sp_v, st->sp_idx, st->sp_count, st->n_tokens};
+    for (const void *p : ps) if (p && misaligned(p)) return LOLA_ERR_ALIGN;
+    return LOLA_OK;
+}
+
+template <typename T>
+State<T> make_state(const lola_state *st) {
+    State<T> s;
+    s.H = st->H; s.s = st->s;
+    s.win_k = (T *)st->win_k; s.win_v = (T *)st->win_v; s.sp_k = (T *)st->sp_k; s.sp_v = (T *)st->sp_v;
+    s.sp_idx = st->sp_idx; s.sp_count = st->sp_count; s.n_tokens = st->n_tokens;
+    return s;
+}
+
+// rows per scoring tile of the generic kernels: as many as fit next to `fixed_floats` in LDS
+int score_tile_rows(const Dims &dm, size_t fixed_floats) {
+    size_t per_row = (size_t)(3 * dm.d + dm.D + 1);
+    size_t avail = LDS_LIMIT / 4;
+    int rmin = generic::NT / dm.d > 1 ? generic::NT / dm.d : 1;
+    if (avail < fixed_floats + per_row * rmin) return 0;
+    size_t r = (avail - fixed_floats) / per_row;
+    if (r > 32) r = 32;
+    return (int)r < rmin ? 0 : (int)r;
+}
+size_t decode_fixed_floats(const Dims &dm) { return (size_t)(dm.lam + 1) + 2 * dm.d + (dm.lam + dm.eta) + 3 * generic::NW + 8; }
+size_t scan_fixed_floats(const Dims &dm) { return (size_t)4 * (dm.lam + dm.C) + 2 * dm.C + 8; }
+int attend_tile_queries(const Dims &dm) {
+    size_t per_q = (size_t)dm.d + dm.D + (dm.lam + dm.eta + dm.C) + 3;
+    size_t q = (LDS_LIMIT / 4) / per_q;
+    if (q > 16) q = 16;
+    return (int)q;
+}
+
+struct PrefillPlan {
+    size_t off_prefK, off_prefV, off_sp_row, off_phiE, off_snap;   // byte offsets
+    size_t snap_bytes_per_chunk;                                    // all streams, one chunk
+    size_t fixed_bytes;
+};
+PrefillPlan plan_prefill(const lola_config *c, int with_outputs) {
+    const size_t ns = (size_t)c->batch * c->n_kv_heads, es = esize(c->dtype);
+    const size_t P = (size_t)c->sparse_budget + c->window, d = c->head_dim, D = c->feat_dim, lam = c->sparse_budget;
+    PrefillPlan p;
+    size_t off = 0;
+    p.off_prefK = off; off += up(ns * P * d * es);
+    p.off_prefV = off; off += up(ns * P * d * es);
+    p.off_sp_row = off; off += up(ns * lam * 4);
+    p.off_phiE = off; off += up(ns * (lam + c->chunk) * D * 4);
+    p.off_snap = off;
+    p.fixed_bytes = off;
+    p.snap_bytes_per_chunk = with_outputs ? up(ns * D * d * 4) + up(ns * D * 4) + up(ns * (lam ? lam : 1) * 4) : 0;
+    return p;
+}
+
+#define LAUNCH_CHECK() do { if (hipGetLastError() != hipSuccess) return LOLA_ERR_HIP; } while (0)
+
+template <typename T>
+lola_status run_decode(const lola_config *c, const lola_state *st, const void *q, const void *k, const void *v,
+                       const void *Wq, const void *Wk, void *out, hipStream_t stream) {
+    generic::DecodeArgs<T> a;
+    a.dm = make_dims(c);
+    a.st = make_state<T>(st);
+    a.q = (const T *)q; a.k = (const T *)k; a.v = (const T *)v; a.Wq = (const T *)Wq; a.Wk = (const T *)Wk;
+    a.out = out;
+    const size_t fixed = decode_fixed_floats(a.dm);
+    a.R = score_tile_rows(a.dm, fixed);
+    if (a.R <= 0) return LOLA_ERR_UNSUPPORTED;
+    const size_t lds = 4 * (fixed + (size_t)a.R * (3 * a.dm.d + a.dm.D + 1));
+    dim3 grid(a.dm.B * a.dm.Hkv), block(generic::NT);
+    if (c->out_dtype == LOLA_F32) hipLaunchKernelGGL((generic::decode_kernel<T, float>), grid, block, lds, stream, a);
+    else hipLaunchKernelGGL((generic::decode_kernel<T, bf16_t>), grid, block, lds, stream, a);
+    LAUNCH_CHECK();
+    return LOLA_OK;
+}
+
+template <typename T>
+lola_status run_prefill(const lola_config *c, const lola_state *st, const void *q, const void *k, const void *v,
+                        const void *Wq, const void *Wk, int32_t Tn, void *out, int32_t *sel_trace,
+                        void *workspace, size_t workspace_bytes, hipStream_t stream) {
+    generic::PrefillArgs<T> a;
+    a.dm = make_dims(c);
+    a.st = make_state<T>(st);
+    a.q = (const T *)q; a.k = (const T *)k; a.v = (const T *)v; a.Wq = (const T *)Wq; a.Wk = (const T *)Wk;
+    a.out = out;
+    a.T_tokens = Tn;
+    a.n_chunks = (Tn + a.dm.C - 1) / a.dm.C;
+    a.want_out = q != nullptr;
+    a.sel_trace = sel_trace;
+    const PrefillPlan p = plan_prefill(c, a.want_out);
+    char *ws = (char *)workspace;
+    a.prefK = (T *)(ws + p.off_prefK); a.prefV = (T *)(ws + p.off_prefV);
+    a.sp_row = (int32_t *)(ws + p.off_sp_row);
+    a.phiE = (float *)(ws + p.off_phiE);
+    int S = a.n_chunks > 0 ? a.n_chunks : 1;
+    if (a.want_out) {
+        size_t room = (workspace_bytes - p.fixed_bytes) / p.snap_bytes_per_chunk;
+        if (room < 1) return LOLA_ERR_WORKSPACE;
+        if ((size_t)S > room) S = (int)room;
+    }
+    a.S = S;
+    const size_t ns = (size_t)a.dm.B * a.dm.Hkv, D = a.dm.D, d = a.dm.d, lam = a.dm.lam;
+    char *snap = ws + p.off_snap;
+    a.snapH = (float *)snap;
+    a.snapS = (float *)(snap + up(ns * S * D * d * 4));
+    a.snapG = (int32_t *)(snap + up(ns * S * D * d * 4) + up(ns * S * D * 4));
+    // the three snapshot regions are each rounded up per pass, which never exceeds S * snap_bytes_per_chunk
+
+    const size_t scan_fixed = scan_fixed_floats(a.dm);
+    a.R = score_tile_rows(a.dm, scan_fixed);
+    a.QT = attend_tile_queries(a.dm);
+    if (a.R <= 0 || (a.want_out && a.QT <= 0)) return LOLA_ERR_UNSUPPORTED;
+    const size_t lds_scan = 4 * (scan_fixed + (size_t)a.R * (3 * d + D + 1));
+    const size_t lds_att = 4 * ((size_t)a.QT * (d + D + (lam + a.dm.eta + a.dm.C) + 3));
+    dim3 block(generic::NT), gs((unsigned)ns);
+
+    hipLaunchKernelGGL((generic::prefix_kernel<T>), gs, block, 0, stream, a);
+    LAUNCH_CHECK();
+    for (int j0 = 0; j0 < a.n_chunks; j0 += S) {
+        a.j0 = j0;
+        a.j1 = j0 + S < a.n_chunks ? j0 + S : a.n_chunks;
+        hipLaunchKernelGGL((generic::scan_kernel<T>), gs, block, lds_scan, stream, a);
+        LAUNCH_CHECK();
+        if (a.want_out) {
+            dim3 ga((unsigned)(a.j1 - a.j0), (unsigned)a.dm.Hq, (unsigned)a.dm.B);
+            if (c->out_dtype == LOLA_F32) hipLaunchKernelGGL((generic::attend_kernel<T, float>), ga, block, lds_att, stream, a);
+            else hipLaunchKernelGGL((generic::attend_kernel<T, bf16_t>), ga, block, lds_att, stream, a);
+            LAUNCH_CHECK();
+        }
+    }
+    hipLaunchKernelGGL((generic::finalize_kernel<T>), gs, block, 0, stream, a);
+    LAUNCH_CHECK();
+    return LOLA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t lola_state_bytes(const lola_config *c, size_t fb[9]) {
+    if (check_config(c) != LOLA_OK) return 0;
+    const size_t ns = (size_t)c->batch * c->n_kv_heads, es = esize(c->dtype);
+    const size_t d = c->head_dim, D = c->feat_dim, eta = c->window, lam = c->sparse_budget;
+    size_t f[9] = {ns * D * d * 4, ns * D * 4, ns * eta * d * es, ns * eta * d * es, ns * lam * d * es,
+                   ns * lam * d * es, ns * lam * 4, ns * 4, ns * 8};
+    size_t tot = 0;
+    for (int i = 0; i < 9; i++) { if (fb) fb[i] = f[i]; tot += f[i]; }
+    return tot;
+}
+
+size_t lola_prefill_workspace_bytes(const lola_config *c, int32_t T, int32_t with_outputs, size_t *min_bytes) {
+    if (check_config(c) != LOLA_OK || T < 0) return 0;
+    const PrefillPlan p = plan_prefill(c, with_outputs);
+    size_t nch = ((size_t)T + c->chunk - 1) / c->chunk;
+    if (nch < 1) nch = 1;
+    if (min_bytes) *min_bytes = p.fixed_bytes + p.snap_bytes_per_chunk;
+    return p.fixed_bytes + nch * p.snap_bytes_per_chunk;
+}
+
+lola_status lola_state_init(const lola_config *c, const lola_state *st, void *stream) {
+    lola_status rc = check_config(c);
+    if (rc != LOLA_OK) return rc;
+    rc = check_state(c, st);
+    if (rc != LOLA_OK) return rc;
+    size_t fb[9];
+    lola_state_bytes(c, fb);
+    void *ptrs[9] = {st->H, st->s, st->win_k, st->win_v, st->sp_k, st->sp_v, st->sp_idx, st->sp_count, st->n_tokens};
+    for (int i = 0; i < 9; i++) {
+        if (!ptrs[i] || fb[i] == 0) continue;
+        size_t n = fb[i] / 4;   // every field is a multiple of 4 bytes (head_dim is even)
+        unsigned blocks = (unsigned)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
+        hipLaunchKernelGGL(generic::fill_u32_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream,
+                           (uint32_t *)ptrs[i], n, i == 6 ? 0xFFFFFFFFu : 0u);
+        LAUNCH_CHECK();
+    }
+    return LOLA_OK;
+}
+
+lola_status lola_prefill(const lola_config *c, const lola_state *st, const void *q, const void *k, const void *v,
+                         const void *Wq, const void *Wk, int32_t T, void *out, int32_t *sel_trace,
+                         void *workspace, size_t workspace_bytes, void *stream) {
+    lola_status rc = check_config(c);
+    if (rc != LOLA_OK) return rc;
+    rc = check_state(c, st);
+    if (rc != LOLA_OK) return rc;
+    if (T < 0) return LOLA_ERR_SHAPE;
+    if ((q == nullptr) != (out == nullptr)) return LOLA_ERR_NULL;
+    if (!k || !v || !Wk || (q && !Wq)) return LOLA_ERR_NULL;
+    const void *ps[] = {q, k, v, Wq, Wk, out, sel_trace, workspace};
+    for (const void *p : ps) if (p && misaligned(p)) return LOLA_ERR_ALIGN;
+    size_t need_min = 0;
+    lola_prefill_workspace_bytes(c, T, q != nullptr, &need_min);
+    if (!workspace || workspace_bytes < need_min) return LOLA_ERR_WORKSPACE;
+    if (T == 0) return LOLA_OK;
+    if (c->dtype == LOLA_F32)
+        return run_prefill<float>(c, st, q, k, v, Wq, Wk, T, out, sel_trace, workspace, workspace_bytes, (hipStream_t)stream);
+    return run_prefill<bf16_t>(c, st, q, k, v, Wq, Wk, T, out, sel_trace, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+lola_status lola_decode_step(const lola_config *c, const lola_state *st, const void *q, const void *k, const void *v,
+                             const void *Wq, const void *Wk, void *out, void *stream) {
+    lola_status rc = check_config(c);
+    if (rc != LOLA_OK) return rc;
+    rc = check_state(c, st);
+    if (rc != LOLA_OK) return rc;
+    if (!q || !k || !v || !Wq || !Wk || !out) return LOLA_ERR_NULL;
+    const void *ps[] = {q, k, v, Wq, Wk, out};
+    for (const void *p : ps) if (misaligned(p)) return LOLA_ERR_ALIGN;
+    if (c->dtype == LOLA_F32) return run_decode<float>(c, st, q, k, v, Wq, Wk, out, (hipStream_t)stream);
+    return run_decode<bf16_t>(c, st, q, k, v, Wq, Wk, out, (hipStream_t)stream);
+}
+
+const char *lola_status_str(lola_status s) {
+    switch (s) {
+        case LOLA_OK: return "ok";
+        case LOLA_ERR_NULL: return "required pointer is NULL";
+        case LOLA_ERR_SHAPE: return "size out of range or inconsistent";
+        case LOLA_ERR_DTYPE: return "unknown dtype or phi_kind";
+        case LOLA_ERR_ALIGN: return "pointer not 16-byte aligned";
+        case LOLA_ERR_UNSUPPORTED: return "no kernel for this configuration";
+        case LOLA_ERR_WORKSPACE: return "workspace missing or too small";
+        case LOLA_ERR_HIP: return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+const char *lola_kernel_path(const lola_config *c, int32_t which) {
+    (void)which;
+    if (check_config(c) != LOLA_OK) return "invalid";
+    return "generic";
+}
+
+}  // extern "C"

@@ -1,0 +1,167 @@
+"""Helpers of the GPU parity tests: upload seeded inputs, run the HIP path through the C ABI,
+run the oracle on the same bits, compare.
+
+Comparison rule (one number per output row, i.e. per token and head):
+    err = max_j |y_gpu - y_oracle| / max(max_j |y_oracle|, 1e-6)
+Tolerance: 2e-3 with bf16 storage and fp32 accumulation, 1e-5 with fp32 storage.  H and s are
+compared per stream in the same way.  Sparse-cache index sets must be identical wherever the
+oracle's margin between the lambda-th and (lambda+1)-th score exceeds 1e-4; inside that band
+the oracle adopts the GPU's choice (and counts it) so that later steps stay comparable.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import workloads as wl
+from oracle import lola_oracle as orc
+from paper_2505_23666_amd import binding as lb
+
+TOL = {"bf16": 2e-3, "f32": 1e-5}
+TIE_EPS = 1e-4
+DEV = "cuda:0"
+
+
+def to_dev(x: np.ndarray, dtype: str) -> torch.Tensor:
+    """float32 host array (values representable in `dtype`) -> device tensor of the storage type."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    if dtype == "bf16":
+        bits = torch.from_numpy(wl.bf16_bits(x).view(np.int16))
+        return bits.to(DEV).view(torch.bfloat16)
+    return torch.from_numpy(x).to(DEV)
+
+
+def row_rel_err(y_gpu: np.ndarray, y_or: np.ndarray) -> np.ndarray:
+    num = np.abs(y_gpu.astype(np.float64) - y_or).max(axis=-1)
+    den = np.maximum(np.abs(y_or).max(axis=-1), 1e-6)
+    return num / den
+
+
+def stream_rel_err(a_gpu: np.ndarray, a_or: np.ndarray, n_lead: int = 2) -> np.ndarray:
+    g = a_gpu.astype(np.float64).reshape(a_gpu.shape[:n_lead] + (-1,))
+    o = a_or.reshape(a_or.shape[:n_lead] + (-1,))
+    return np.abs(g - o).max(-1) / np.maximum(np.abs(o).max(-1), 1e-6)
+
+
+def make_layer(sh: wl.Shape, out_dtype="f32", B=None, **kw) -> lb.LolaLayer:
+    return lb.LolaLayer(B or sh.B, sh.Hq, sh.Hkv, sh.d, sh.D, sh.eta, sh.lam, sh.C, dtype=sh.dtype,
+                        out_dtype=out_dtype, device=DEV, **kw)
+
+
+def make_oracle(sh: wl.Shape, B=None, **kw) -> orc.Oracle:
+    return orc.Oracle(B or sh.B, sh.Hq, sh.Hkv, sh.d, sh.D, sh.eta, sh.lam, sh.C, **kw)
+
+
+def sorted_sets(idx: np.ndarray) -> np.ndarray:
+    """sort each slot list ascending with the -1 padding last (as the oracle reports it)"""
+    x = idx.astype(np.int64).copy()
+    x[x < 0] = np.iinfo(np.int64).max
+    x.sort(axis=-1)
+    x[x == np.iinfo(np.int64).max] = -1
+    return x.astype(np.int32)
+
+
+def gpu_state_np(layer: lb.LolaLayer, bsel=None, hsel=None) -> dict:
+    """Host copies of the memories, optionally restricted to some sequences / kv heads."""
+    names = ("H", "s", "win_k", "win_v", "sp_k", "sp_v", "sp_idx", "sp_count", "n_tokens")
+    out = {}
+    for n in names:
+        t = getattr(layer, n)
+        if bsel is not None:
+            t = t[list(bsel)]
+        if hsel is not None:
+            t = t[:, list(hsel)]
+        out[n] = (t.float() if t.dtype == torch.bfloat16 else t).cpu().numpy()
+    return out
+
+
+def subset_inputs(sh: wl.Shape, q, k, v, Wq, Wk, bsel=None, hsel=None):
+    """Slices of the inputs that feed the chosen sequences / kv heads (streams are independent)."""
+    bs = list(bsel) if bsel is not None else list(range(k.shape[0]))
+    hs = list(hsel) if hsel is not None else list(range(sh.Hkv))
+    hq = [h * sh.g + r for h in hs for r in range(sh.g)]
+    ix = np.ix_(bs, hq)
+    qq = None if q is None else np.ascontiguousarray(q[ix])
+    ik = np.ix_(bs, hs)
+    return qq, np.ascontiguousarray(k[ik]), np.ascontiguousarray(v[ik]), np.ascontiguousarray(Wq[hq]), np.ascontiguousarray(Wk[hs]), bs, hs, hq
+
+
+def check_state(g: dict, o: orc.Oracle, tol: float):
+    """H, s, sparse index sets, cached K/V rows by token index, window rows, counters."""
+    eH, es = stream_rel_err(g["H"], o.H), stream_rel_err(g["s"], o.s)
+    assert eH.max() <= tol, f"H rel err {eH.max():.3e}"
+    assert es.max() <= tol, f"s rel err {es.max():.3e}"
+    np.testing.assert_array_equal(sorted_sets(g["sp_idx"]), o.sparse_idx)
+    cnt = g["sp_count"]
+    np.testing.assert_array_equal(cnt, (o.sparse_idx >= 0).sum(-1))
+    assert (g["n_tokens"] == o.n_tokens(0)).all()
+    raw = g["sp_idx"]
+    for si in range(o.B * o.Hkv):
+        b, h = divmod(si, o.Hkv)
+        ok, ov, oi = o.pairs(si, 0)
+        order = {int(t): r for r, t in enumerate(oi)}
+        for slot in range(cnt[b, h]):
+            r = order[int(raw[b, h, slot])]
+            assert np.array_equal(g["sp_k"][b, h, slot], ok[r].astype(np.float32))
+            assert np.array_equal(g["sp_v"][b, h, slot], ov[r].astype(np.float32))
+        ok, ov, oi = o.pairs(si, 1)
+        for r, t in enumerate(oi):
+            slot = int(t) % o.eta
+            assert np.array_equal(g["win_k"][b, h, slot], ok[r].astype(np.float32))
+            assert np.array_equal(g["win_v"][b, h, slot], ov[r].astype(np.float32))
+    return float(eH.max()), float(es.max())
+
+
+def prefill_parity(sh: wl.Shape, q, k, v, Wq, Wk, layer=None, oracle=None, with_outputs=True, workspace_limit=None,
+                   out_dtype="f32", bsel=None, hsel=None, layer_kw=None):
+    """One prefill call on both sides (the oracle possibly on a subset of the streams);
+    returns (layer, oracle, report)."""
+    tol = TOL[sh.dtype] + (2.0 ** -8 if out_dtype == "bf16" else 0.0)
+    layer = layer or make_layer(sh, out_dtype=out_dtype, B=k.shape[0], **(layer_kw or {}))
+    dq = to_dev(q, sh.dtype) if with_outputs else None
+    dk, dv = to_dev(k, sh.dtype), to_dev(v, sh.dtype)
+    dWq, dWk = to_dev(Wq, sh.dtype), to_dev(Wk, sh.dtype)
+    out, trace = layer.prefill(dq, dk, dv, dWq, dWk, trace=True, workspace_limit=workspace_limit)
+    torch.cuda.synchronize()
+    oq, ok_, ov, oWq, oWk, bs, hs, hq = subset_inputs(sh, q if with_outputs else None, k, v, Wq, Wk, bsel, hsel)
+    if oracle is None:
+        okw = dict(layer_kw or {})
+        oracle = orc.Oracle(len(bs), len(hq), len(hs), sh.d, sh.D, sh.eta, sh.lam, sh.C,
+                            phi_kind=okw.get("phi_kind", 0), scale=okw.get("scale", 0.0))
+    trace = trace.cpu().numpy()[np.ix_(bs, hs)] if sh.lam > 0 else None
+    y_or = oracle.prefill(oq, ok_, ov, oWq if with_outputs else None, oWk, force_sel=trace, tie_eps=TIE_EPS)
+    st = oracle.stats()
+    rep = dict(st)
+    assert st["mismatch"] == 0, f"sparse-cache sets differ outside the tie band: {st}"
+    if with_outputs:
+        err = row_rel_err(out[bs][:, hq].float().cpu().numpy(), y_or)
+        rep["max_out_err"] = float(err.max())
+        assert err.max() <= tol, f"output rel err {err.max():.3e} > {tol}"
+    rep["H_err"], rep["s_err"] = check_state(gpu_state_np(layer, bs, hs), oracle, TOL[sh.dtype])
+    return layer, oracle, rep
+
+
+def decode_parity(sh: wl.Shape, layer, oracle, qd, kd, vd, Wq, Wk, out_dtype="f32", bsel=None, hsel=None, check_every=1):
+    """Generation steps; qd [n,B,Hq,d], kd, vd [n,B,Hkv,d] (host float32).  Every step's outputs and
+    selection are compared on the oracle's streams."""
+    tol = TOL[sh.dtype] + (2.0 ** -8 if out_dtype == "bf16" else 0.0)
+    n = qd.shape[0]
+    bs = list(bsel) if bsel is not None else list(range(kd.shape[1]))
+    hs = list(hsel) if hsel is not None else list(range(sh.Hkv))
+    hq = [h * sh.g + r for h in hs for r in range(sh.g)]
+    dWq, dWk = to_dev(Wq, sh.dtype), to_dev(Wk, sh.dtype)
+    dq, dk, dv = to_dev(qd, sh.dtype), to_dev(kd, sh.dtype), to_dev(vd, sh.dtype)
+    oWq, oWk = np.ascontiguousarray(Wq[hq]), np.ascontiguousarray(Wk[hs])
+    worst = 0.0
+    for i in range(n):
+        out = layer.decode_step(dq[i], dk[i], dv[i], dWq, dWk)
+        sel = layer.sp_idx[bs][:, hs].cpu().numpy() if sh.lam > 0 else None
+        y_or = oracle.decode_step(qd[i][np.ix_(bs, hq)], kd[i][np.ix_(bs, hs)], vd[i][np.ix_(bs, hs)], oWq, oWk,
+                                  force_sel=sel, tie_eps=TIE_EPS)
+        err = row_rel_err(out[bs][:, hq].float().cpu().numpy(), y_or).max()
+        worst = max(worst, float(err))
+        assert err <= tol, f"decode step {i}: output rel err {err:.3e} > {tol}"
+    st = oracle.stats()
+    assert st["mismatch"] == 0, f"sparse-cache sets differ outside the tie band: {st}"
+    eH, es = check_state(gpu_state_np(layer, bs, hs), oracle, TOL[sh.dtype])
+    return {"max_out_err": worst, "H_err": eH, "s_err": es, **st}

@@ -1,0 +1,83 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, sizes the state and workspace as documented, and rejects bad arguments before
+anything is launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2505_23666_amd import binding as lb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(lb.LIB_PATH):
+        from paper_2505_23666_amd import build
+        build.build_library()
+    return lb.lib()
+
+
+def cfg(**kw):
+    base = dict(batch=2, n_q_heads=8, n_kv_heads=2, head_dim=128, feat_dim=128, window=64, sparse_budget=128,
+                chunk=64, dtype=lb.LOLA_BF16, out_dtype=lb.LOLA_F32, phi_kind=0, softmax_scale=0.0)
+    base.update(kw)
+    return lb.LolaConfig(**base)
+
+
+def test_exports_every_declared_symbol(L):
+    header = open(os.path.join(ROOT, "include", "lola.h")).read()
+    declared = set(re.findall(r"\b(lola_[a-z_]+)\s*\(", header))
+    assert declared == set(lb.EXPORTS)
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_state_bytes(L):
+    tot, fb = lb.lola_state_bytes(cfg())
+    ns = 4
+    assert fb == [ns * 128 * 128 * 4, ns * 128 * 4, ns * 64 * 128 * 2, ns * 64 * 128 * 2, ns * 128 * 128 * 2,
+                  ns * 128 * 128 * 2, ns * 128 * 4, ns * 4, ns * 8]
+    assert tot == sum(fb)
+    assert lb.lola_state_bytes(cfg(head_dim=100))[0] == 0
+    assert lb.lola_state_bytes(cfg(feat_dim=127))[0] == 0
+    assert lb.lola_state_bytes(cfg(n_q_heads=7))[0] == 0
+
+
+def test_workspace_bytes_monotone(L):
+    full, mn = lb.lola_prefill_workspace_bytes(cfg(), 4096, True)
+    full2, mn2 = lb.lola_prefill_workspace_bytes(cfg(), 8192, True)
+    assert mn == mn2 and full2 > full > mn > 0
+    upd, mnu = lb.lola_prefill_workspace_bytes(cfg(), 4096, False)
+    assert upd == mnu < mn
+
+
+def test_status_strings(L):
+    for code in range(-7, 1):
+        assert L.lola_status_str(code)
+    assert lb.lola_kernel_path(cfg(), 0) in ("generic", "mfma")
+
+
+def test_arguments_rejected_before_launch(L):
+    """Every call below must return an error from host-side validation (no GPU is present here)."""
+    c = cfg()
+    fake = 0x1000  # aligned, never dereferenced on the host
+    st = lb.LolaState(*([fake] * 9))
+    bad_st = lb.LolaState(*([fake] * 8 + [None]))
+    f = lambda *a: L.lola_decode_step(*a)
+    vp = C.c_void_p
+    assert f(C.byref(c), C.byref(bad_st), vp(fake), vp(fake), vp(fake), vp(fake), vp(fake), vp(fake), None) == -1
+    assert f(C.byref(c), C.byref(st), None, vp(fake), vp(fake), vp(fake), vp(fake), vp(fake), None) == -1
+    assert f(C.byref(c), C.byref(st), vp(fake + 4), vp(fake), vp(fake), vp(fake), vp(fake), vp(fake), None) == -4
+    assert f(C.byref(cfg(dtype=7)), C.byref(st), vp(fake), vp(fake), vp(fake), vp(fake), vp(fake), vp(fake), None) == -3
+    assert f(C.byref(cfg(window=-1)), C.byref(st), vp(fake), vp(fake), vp(fake), vp(fake), vp(fake), vp(fake), None) == -2
+    p = lambda cc, s, q, k, out, T, ws, wsb: L.lola_prefill(C.byref(cc), C.byref(s), q, k, vp(fake), vp(fake), vp(fake), T, out,
+                                                           None, ws, wsb, None)
+    assert p(c, st, vp(fake), vp(fake), None, 64, vp(fake), 1 << 40) == -1          # q without out
+    assert p(c, st, vp(fake), None, vp(fake), 64, vp(fake), 1 << 40) == -1          # k missing
+    assert p(c, st, vp(fake), vp(fake), vp(fake), -1, vp(fake), 1 << 40) == -2      # negative T
+    assert p(c, st, vp(fake), vp(fake), vp(fake), 64, None, 0) == -6                 # no workspace
+    assert p(c, st, vp(fake), vp(fake), vp(fake), 64, vp(fake), 1024) == -6          # workspace too small
+    assert L.lola_state_init(C.byref(c), C.byref(bad_st), None) == -1

@@ -1,0 +1,227 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle on the same seeded inputs.
+
+Small cases compare every output element, every state element and every selection; the
+full-size configurations compare every element on all streams the oracle can finish in
+reasonable time (stated per test) and the whole state of those streams.
+"""
+import os
+import sys
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+import parity as P
+from oracle import lola_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def rand_case(seed, B, Hq, Hkv, d, D, N, dtype, wscale=1.0):
+    g = wl.rng(seed, 5)
+    q = wl.store(g.standard_normal((B, Hq, N, d), dtype=np.float32), dtype)
+    k = wl.store(g.standard_normal((B, Hkv, N, d), dtype=np.float32), dtype)
+    v = wl.store(g.standard_normal((B, Hkv, N, d), dtype=np.float32), dtype)
+    Wq = wl.store((wscale * g.standard_normal((Hq, d, D // 2), dtype=np.float32) / np.sqrt(d)).astype(np.float32), dtype)
+    Wk = wl.store((wscale * g.standard_normal((Hkv, d, D // 2), dtype=np.float32) / np.sqrt(d)).astype(np.float32), dtype)
+    return q, k, v, Wq, Wk
+
+
+def steps(q, k, v, t0, n):
+    tr = lambda a: np.ascontiguousarray(a[:, :, t0:t0 + n].transpose(2, 0, 1, 3))
+    return tr(q), tr(k), tr(v)
+
+
+# ---------------------------------------------------------------------------------------------
+# configuration 1 in full: fp32, prefill of 256 tokens then 32 generation steps
+# ---------------------------------------------------------------------------------------------
+def test_config1_tiny_fp32_prefill_then_decode():
+    sh = wl.CONFIGS[1]
+    Wq, Wk = wl.weights(sh)
+    q, k, v, _ = wl.sequence_inputs(sh)
+    T = sh.T
+    layer, o, rep = P.prefill_parity(sh, q[:, :, :T], k[:, :, :T], v[:, :, :T], Wq, Wk)
+    say("config1 prefill", rep)
+    rep = P.decode_parity(sh, layer, o, *steps(q, k, v, T, sh.n_decode), Wq, Wk)
+    say("config1 decode", rep)
+    assert rep["scored"] > 0
+
+
+# ---------------------------------------------------------------------------------------------
+# edge cases: ragged tails, empty memories, degenerate sizes, both storage types, both phi kinds
+# ---------------------------------------------------------------------------------------------
+EDGE = [
+    # name            dtype  B Hq Hkv  d    D  eta lam  C    T  nd
+    ("ragged_tail",   "f32", 2, 4, 2, 32,  16,  8,  6,  8,  77, 5),
+    ("chunk_lt_win",  "f32", 1, 2, 1, 32,  24, 12,  5,  4,  50, 4),
+    ("chunk_gt_win",  "bf16", 1, 2, 2, 64, 32,  5,  7, 16,  70, 9),
+    ("no_window",     "f32", 1, 2, 1, 32,  16,  0,  4,  8,  40, 6),
+    ("no_sparse",     "bf16", 2, 2, 2, 64, 64,  8,  0,  8,  64, 6),
+    ("no_caches",     "f32", 1, 1, 1, 32,   8,  0,  0,  4,  19, 5),
+    ("short_T",       "bf16", 1, 4, 1, 128, 64, 64, 32, 64,  9, 70),
+    ("warmup_partial", "f32", 1, 1, 1, 32,  16,  4, 10,  8,  64, 3),
+    ("head256",       "bf16", 1, 2, 1, 256, 128, 16, 16, 16, 96, 4),
+    ("wide_features", "f32", 1, 1, 1, 64, 256, 16,  8, 16,  80, 3),
+    ("gqa8",          "bf16", 1, 8, 1, 64, 128, 16, 24, 16, 128, 4),
+]
+
+
+@pytest.mark.parametrize("case", EDGE, ids=[c[0] for c in EDGE])
+def test_edge_cases(case):
+    name, dtype, B, Hq, Hkv, d, D, eta, lam, C, T, nd = case
+    say("edge", case)
+    sh = wl.Shape(name, dtype, B, Hq, Hkv, d, D, T, eta, lam, C, seed=0)
+    q, k, v, Wq, Wk = rand_case(100 + len(name), B, Hq, Hkv, d, D, T + nd, dtype)
+    layer, o, rep = P.prefill_parity(sh, q[:, :, :T], k[:, :, :T], v[:, :, :T], Wq, Wk)
+    rep2 = P.decode_parity(sh, layer, o, *steps(q, k, v, T, nd), Wq, Wk)
+    say("  ", rep, rep2)
+
+
+def test_decode_from_empty_state():
+    sh = wl.Shape("cold", "bf16", 2, 4, 2, 64, 32, T=0, eta=6, lam=5, C=8, seed=0)
+    q, k, v, Wq, Wk = rand_case(7, 2, 4, 2, 64, 32, 40, "bf16")
+    layer, o = P.make_layer(sh), P.make_oracle(sh)
+    rep = P.decode_parity(sh, layer, o, *steps(q, k, v, 0, 40), Wq, Wk)
+    say("cold decode", rep)
+
+
+def test_exp_feature_map():
+    sh = wl.Shape("expphi", "f32", 1, 2, 1, 32, 16, T=64, eta=8, lam=6, C=8, seed=0)
+    q, k, v, Wq, Wk = rand_case(8, 1, 2, 1, 32, 16, 70, "f32", wscale=0.5)
+    kw = dict(phi_kind=orc.PHI_EXP)
+    layer, o, rep = P.prefill_parity(sh, q[:, :, :64], k[:, :, :64], v[:, :, :64], Wq, Wk, layer_kw=kw)
+    rep2 = P.decode_parity(sh, layer, o, *steps(q, k, v, 64, 6), Wq, Wk)
+    say("exp phi", rep, rep2)
+
+
+def test_resume_and_multipass_workspace():
+    """prefill(T1); prefill(T2) == prefill(T1+T2) on the GPU too, with a workspace that forces
+    several passes, and an update-only call in between matches the oracle's."""
+    sh = wl.Shape("resume", "bf16", 2, 4, 2, 64, 64, T=0, eta=16, lam=12, C=16, seed=0)
+    q, k, v, Wq, Wk = rand_case(9, 2, 4, 2, 64, 64, 16 * 11 + 5, "bf16")
+    cuts = [0, 48, 48 + 64, 16 * 11 + 5]
+    layer, o = None, None
+    for i in range(3):
+        a, b = cuts[i], cuts[i + 1]
+        layer, o, rep = P.prefill_parity(sh, q[:, :, a:b], k[:, :, a:b], v[:, :, a:b], Wq, Wk, layer=layer, oracle=o,
+                                         with_outputs=(i != 1), workspace_limit=0 if i == 2 else None)
+        say("resume part", i, rep)
+    # one call over everything gives the same memories
+    one = P.make_layer(sh)
+    one.prefill(P.to_dev(q, "bf16"), P.to_dev(k, "bf16"), P.to_dev(v, "bf16"), P.to_dev(Wq, "bf16"), P.to_dev(Wk, "bf16"))
+    torch.cuda.synchronize()
+    assert torch.equal(P.torch.sort(one.sp_idx, -1).values, torch.sort(layer.sp_idx, -1).values)
+    assert torch.allclose(one.H, layer.H, rtol=1e-5, atol=1e-6)
+
+
+def test_bf16_outputs():
+    sh = wl.scaled(2, T=256)
+    Wq, Wk = wl.weights(sh)
+    q, k, v, _ = wl.sequence_inputs(sh)
+    _, _, rep = P.prefill_parity(sh, q, k, v, Wq, Wk, out_dtype="bf16")
+    say("bf16 out", rep)
+
+
+def test_run_to_run_determinism():
+    sh = wl.scaled(3, B=1, T=512)
+    Wq, Wk = wl.weights(sh)
+    q, k, v, _ = wl.sequence_inputs(sh)
+    outs = []
+    for _ in range(2):
+        layer = P.make_layer(sh)
+        out = layer.prefill(P.to_dev(q, sh.dtype), P.to_dev(k, sh.dtype), P.to_dev(v, sh.dtype), P.to_dev(Wq, sh.dtype), P.to_dev(Wk, sh.dtype))
+        torch.cuda.synchronize()
+        outs.append((out.clone(), layer.H.clone(), layer.sp_idx.clone()))
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+
+
+# ---------------------------------------------------------------------------------------------
+# the benchmark configurations at full size
+# ---------------------------------------------------------------------------------------------
+def test_config2_1b_prefill_full():
+    sh = wl.CONFIGS[2]
+    Wq, Wk = wl.weights(sh)
+    q, k, v, _ = wl.sequence_inputs(sh)
+    t = time.time()
+    _, _, rep = P.prefill_parity(sh, q, k, v, Wq, Wk)
+    say("config2 full (all 8 streams, all 4096 x 32 output rows)", rep, f"{time.time() - t:.1f}s")
+    assert rep["scored"] == 8 * (4096 // 64 - 2)
+
+
+def test_config3_8b_prefill_full():
+    sh = wl.CONFIGS[3]
+    Wq, Wk = wl.weights(sh)
+    q, k, v, _ = wl.sequence_inputs(sh)
+    t = time.time()
+    _, _, rep = P.prefill_parity(sh, q, k, v, Wq, Wk)
+    say("config3 full (all 32 streams, all outputs)", rep, f"{time.time() - t:.1f}s")
+
+
+def test_config5_recall_64k_full():
+    """T = 65536 on the GPU for all 8 kv heads; the oracle follows 3 of them (all their outputs)."""
+    sh = wl.CONFIGS[5]
+    Wq, Wk = wl.weights(sh)
+    q, k, v, ex = wl.sequence_inputs(sh)
+    t = time.time()
+    layer, o, rep = P.prefill_parity(sh, q, k, v, Wq, Wk, hsel=[0, 3, 7])
+    pos = set(int(p) for p in ex["planted_pos"])
+    g_frac = np.mean([len(pos & set(layer.sp_idx[0, h].cpu().numpy().tolist())) / len(pos) for h in range(sh.Hkv)])
+    o_frac = np.mean([len(pos & set(o.sparse_idx[0, h].tolist())) / len(pos) for h in range(3)])
+    say("config5 full", rep, f"planted kept: gpu {g_frac:.3f} (8 heads) oracle {o_frac:.3f} (3 heads)", f"{time.time() - t:.1f}s")
+
+
+def test_config4_decode_batch64_full():
+    """Batch 64, each sequence prefilled with 32768 tokens (update-only call), then generation
+    steps.  The oracle follows sequences 0, 21, 42, 63 end to end (prefill + every step)."""
+    sh = wl.CONFIGS[4]
+    n_steps = int(os.environ.get("LOLA_TEST_DECODE_STEPS", "256"))
+    bsel = [0, 21, 42, 63]
+    Wq, Wk = wl.weights(sh)
+    layer = P.make_layer(sh)
+    o = orc.Oracle(len(bsel), sh.Hq, sh.Hkv, sh.d, sh.D, sh.eta, sh.lam, sh.C)
+    dWk = P.to_dev(Wk, sh.dtype)
+    qd = np.empty((n_steps, sh.B, sh.Hq, sh.d), np.float32)
+    kd = np.empty((n_steps, sh.B, sh.Hkv, sh.d), np.float32)
+    vd = np.empty((n_steps, sh.B, sh.Hkv, sh.d), np.float32)
+    # the GPU prefills the batch in groups of 8 sequences (bounds host memory); the state tensors of
+    # a group are views into the batch-64 layer
+    t = time.time()
+    from concurrent.futures import ThreadPoolExecutor
+    grp = 8
+    sub = P.make_layer(sh, B=grp)
+    ok_, ov_ = {}, {}
+    for g0 in range(0, sh.B, grp):
+        with ThreadPoolExecutor(8) as ex:
+            seqs = list(ex.map(lambda b: wl.decode_batch_sequence(sh, b), range(g0, g0 + grp)))
+        kp = np.stack([s[0] for s in seqs]); vp = np.stack([s[1] for s in seqs])
+        for i, s in enumerate(seqs):
+            qd[:, g0 + i], kd[:, g0 + i], vd[:, g0 + i] = s[2][:n_steps], s[3][:n_steps], s[4][:n_steps]
+            if g0 + i in bsel:
+                ok_[g0 + i], ov_[g0 + i] = s[0], s[1]
+        sub.reset()
+        _, trace = sub.prefill(None, P.to_dev(kp, sh.dtype), P.to_dev(vp, sh.dtype), None, dWk, trace=True)
+        torch.cuda.synchronize()
+        for name in ("H", "s", "win_k", "win_v", "sp_k", "sp_v", "sp_idx", "sp_count", "n_tokens"):
+            getattr(layer, name)[g0:g0 + grp].copy_(getattr(sub, name))
+        for b in bsel:
+            if g0 <= b < g0 + grp:
+                ok_[b] = (ok_[b], trace[b - g0].cpu().numpy())
+        say(f"  prefilled sequences {g0}..{g0 + grp - 1}  {time.time() - t:.1f}s")
+    # oracle prefill of the followed sequences, adopting near-ties from the GPU trace
+    kp = np.stack([ok_[b][0] for b in bsel]); vp = np.stack([ov_[b] for b in bsel])
+    tr = np.stack([ok_[b][1] for b in bsel])
+    o.prefill(None, kp, vp, None, Wk, force_sel=tr, tie_eps=P.TIE_EPS)
+    st = o.stats()
+    say("config4 oracle prefill", st, f"{time.time() - t:.1f}s")
+    assert st["mismatch"] == 0
+    P.check_state(P.gpu_state_np(layer, bsel), o, P.TOL[sh.dtype])
+    rep = P.decode_parity(sh, layer, o, qd, kd, vd, Wq, Wk, bsel=bsel)
+    say(f"config4 decode x{n_steps} (sequences {bsel}, every step)", rep, f"{time.time() - t:.1f}s")
