@@ -2,6 +2,7 @@
 // and kernel dispatch.  Nothing here allocates or synchronises.
 #include "../../include/lola.h"
 #include "generic_kernels.h"
+#include "decode_mfma.h"
 
 using namespace lola;
 
@@ -76,6 +77,8 @@ int attend_tile_queries(const Dims &dm) {
     return (int)q;
 }
 
+#define LAUNCH_CHECK() do { if (hipGetLastError() != hipSuccess) return LOLA_ERR_HIP; } while (0)
+
 struct PrefillPlan {
     size_t off_prefK, off_prefV, off_sp_row, off_phiE, off_snap;   // byte offsets
     size_t snap_bytes_per_chunk;                                    // all streams, one chunk
@@ -96,7 +99,38 @@ PrefillPlan plan_prefill(const lola_config *c, int with_outputs) {
     return p;
 }
 
-#define LAUNCH_CHECK() do { if (hipGetLastError() != hipSuccess) return LOLA_ERR_HIP; } while (0)
+
+// The fused MFMA generation step covers the Llama-8B head shape with bf16 storage.
+bool fast_decode_ok(const lola_config *c) {
+    return c->dtype == LOLA_BF16 && c->head_dim == 128 && c->feat_dim == 128 && c->window == 64 &&
+           (c->sparse_budget == 128 || c->sparse_budget == 64) && c->n_q_heads / c->n_kv_heads == 4;
+}
+
+template <int LAM, typename TO>
+lola_status launch_fast_decode(const lola_config *c, const lola_state *st, const void *q, const void *k, const void *v,
+                               const void *Wq, const void *Wk, void *out, hipStream_t stream) {
+    fast::DecodeFastArgs<TO> a;
+    a.st = make_state<bf16_t>(st);
+    a.q = (const bf16_t *)q; a.k = (const bf16_t *)k; a.v = (const bf16_t *)v;
+    a.Wq = (const bf16_t *)Wq; a.Wk = (const bf16_t *)Wk;
+    a.out = (TO *)out;
+    a.Hq = c->n_q_heads; a.Hkv = c->n_kv_heads;
+    a.scale = make_dims(c).scale;
+    a.phi_kind = c->phi_kind;
+    hipLaunchKernelGGL((fast::decode_fast_kernel<LAM, 64, 4, TO>), dim3(c->batch * c->n_kv_heads), dim3(256), 0, stream, a);
+    LAUNCH_CHECK();
+    return LOLA_OK;
+}
+
+lola_status run_fast_decode(const lola_config *c, const lola_state *st, const void *q, const void *k, const void *v,
+                            const void *Wq, const void *Wk, void *out, hipStream_t stream) {
+    const bool f32o = c->out_dtype == LOLA_F32;
+    if (c->sparse_budget == 128)
+        return f32o ? launch_fast_decode<128, float>(c, st, q, k, v, Wq, Wk, out, stream)
+                    : launch_fast_decode<128, bf16_t>(c, st, q, k, v, Wq, Wk, out, stream);
+    return f32o ? launch_fast_decode<64, float>(c, st, q, k, v, Wq, Wk, out, stream)
+                : launch_fast_decode<64, bf16_t>(c, st, q, k, v, Wq, Wk, out, stream);
+}
 
 template <typename T>
 lola_status run_decode(const lola_config *c, const lola_state *st, const void *q, const void *k, const void *v,
@@ -250,6 +284,7 @@ lola_status lola_decode_step(const lola_config *c, const lola_state *st, const v
     const void *ps[] = {q, k, v, Wq, Wk, out};
     for (const void *p : ps) if (misaligned(p)) return LOLA_ERR_ALIGN;
     if (c->dtype == LOLA_F32) return run_decode<float>(c, st, q, k, v, Wq, Wk, out, (hipStream_t)stream);
+    if (fast_decode_ok(c)) return run_fast_decode(c, st, q, k, v, Wq, Wk, out, (hipStream_t)stream);
     return run_decode<bf16_t>(c, st, q, k, v, Wq, Wk, out, (hipStream_t)stream);
 }
 
@@ -268,8 +303,8 @@ const char *lola_status_str(lola_status s) {
 }
 
 const char *lola_kernel_path(const lola_config *c, int32_t which) {
-    (void)which;
     if (check_config(c) != LOLA_OK) return "invalid";
+    if (which == 1 && fast_decode_ok(c)) return "mfma";
     return "generic";
 }
 

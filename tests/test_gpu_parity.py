@@ -92,6 +92,21 @@ def test_decode_from_empty_state():
     say("cold decode", rep)
 
 
+@pytest.mark.parametrize("lam,phi_kind", [(128, 0), (64, 0), (128, 1)])
+def test_8b_shape_decode_from_cold_start(lam, phi_kind):
+    """The fused generation kernel through all its regimes: window filling, cache warm-up (pairs
+    appended unscored), then steady state with scoring, fold and in-place slot replacement."""
+    sh = wl.Shape("cold8b", "bf16", 2, 8, 2, 128, 128, T=0, eta=64, lam=lam, C=64, seed=0)
+    n = 64 + lam + 60
+    q, k, v, Wq, Wk = rand_case(31 + lam, 2, 8, 2, 128, 128, n, "bf16", wscale=0.5 if phi_kind else 1.0)
+    kw = dict(phi_kind=phi_kind)
+    layer = P.make_layer(sh, **kw)
+    o = P.make_oracle(sh, **kw)
+    rep = P.decode_parity(sh, layer, o, *steps(q, k, v, 0, n), Wq, Wk)
+    say("8B-shape cold decode", lam, phi_kind, rep)
+    assert rep["scored"] == 4 * 60
+
+
 def test_exp_feature_map():
     sh = wl.Shape("expphi", "f32", 1, 2, 1, 32, 16, T=64, eta=8, lam=6, C=8, seed=0)
     q, k, v, Wq, Wk = rand_case(8, 1, 2, 1, 32, 16, 70, "f32", wscale=0.5)
