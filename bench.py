@@ -90,7 +90,7 @@ def main():
         return torch.from_numpy(wl.bf16_bits(x).view(np.int16)).to(dev).view(torch.bfloat16)
 
     Wq, Wk = wl.weights(sh)
-    dWq, dWk = to_dev(Wq), to_dev(Wk)
+    dWq, dWk = to_dev(Wq.transpose(0, 2, 1)), to_dev(Wk.transpose(0, 2, 1))   # library layout [H, m, d]
 
     # ---- state initialisation: update-only prefill of every sequence, 8 sequences at a time ----
     t0 = time.time()
@@ -184,7 +184,7 @@ def main():
         W3q, W3k = wl.weights(s3)
         q3, k3, v3, _ = wl.sequence_inputs(s3)
         lay = lb.LolaLayer(s3.B, s3.Hq, s3.Hkv, s3.d, s3.D, s3.eta, s3.lam, s3.C, dtype="bf16", out_dtype="f32", device=dev)
-        a = [to_dev(x) for x in (q3, k3, v3, W3q, W3k)]
+        a = [to_dev(x) for x in (q3, k3, v3, W3q.transpose(0, 2, 1), W3k.transpose(0, 2, 1))]
         out3 = torch.empty((s3.B, s3.Hq, s3.T, s3.d), dtype=torch.float32, device=dev)
         times = []
         for r in range(args.prefill_reps + 1):
@@ -221,7 +221,7 @@ def main():
             for h in range(sh.Hkv):
                 cnt = int(hs["sp_count"][b, h])
                 wtok = np.arange(max(0, ntk - sh.eta), ntk)
-                o.set_stream(b * sh.Hkv + h, hs["H"][b, h], hs["s"][b, h], hs["sp_k"][b, h, :cnt], hs["sp_v"][b, h, :cnt],
+                o.set_stream(b * sh.Hkv + h, hs["H"][b, h].T, hs["s"][b, h], hs["sp_k"][b, h, :cnt], hs["sp_v"][b, h, :cnt],
                              hs["sp_idx"][b, h, :cnt], hs["win_k"][b, h][wtok % sh.eta], hs["win_v"][b, h][wtok % sh.eta], wtok)
         run = lambda t: o.decode_step(qd[t, :n_seq], kd[t, :n_seq], vd[t, :n_seq], Wq, Wk)
         t1 = time.perf_counter(); run(0); run(1); per = (time.perf_counter() - t1) / 2

@@ -59,7 +59,9 @@ typedef struct {
 
 /* The memories of a layer.  H and s are always fp32 (Sec. 2.2, eq. recurrent_update). */
 typedef struct {
-    float *H;          /* [B, Hkv, D, d]      H = sum over folded pairs of phi(k) v^T */
+    float *H;          /* [B, Hkv, d, D]      H^T: H[c][f] = sum over folded pairs of v[c] phi(k)[f]
+                          (stored value-major so that the feature index, which every read contracts
+                          over, is contiguous) */
     float *s;          /* [B, Hkv, D]         s = sum over folded pairs of phi(k) */
     void *win_k;       /* [B, Hkv, eta, d]    ring buffer: token t sits in slot t % eta */
     void *win_v;       /* [B, Hkv, eta, d] */
@@ -96,7 +98,8 @@ lola_status lola_state_init(const lola_config *cfg, const lola_state *st, void *
  *      the state before this update; recall = 0 while nothing was folded); the lambda largest stay
  *      in the sparse cache (ties: lower token index stays), the rest are folded:
  *      H += phi(k) v^T, s += phi(k).  While the candidates number <= lambda all are cached unscored.
- * q   [B, Hq, T, d], k, v [B, Hkv, T, d], out [B, Hq, T, d] (out_dtype), Wq [Hq, d, m], Wk [Hkv, d, m].
+ * q   [B, Hq, T, d], k, v [B, Hkv, T, d], out [B, Hq, T, d] (out_dtype), Wq [Hq, m, d], Wk [Hkv, m, d]:
+ *   row j of a head's matrix is the projection vector w_j of eq. (feature_map), so z_j = w_j . x.
  * q == out == NULL updates the memories without producing outputs (Wq is then ignored).
  * sel_trace: NULL, or int32 [B, Hkv, ceil(T/C), lambda] receiving the token indices held by the
  *   sparse cache after each chunk's update (slot order, -1 = empty slot).

@@ -126,7 +126,7 @@ class LolaLayer:
         if tot == 0:
             raise LolaError("invalid configuration")
         tdt, dev = _TORCH_DT[self.dt], self.device
-        self.H = torch.empty((B, Hkv, D, d), dtype=torch.float32, device=dev)
+        self.H = torch.empty((B, Hkv, d, D), dtype=torch.float32, device=dev)   # H^T, see lola.h
         self.s = torch.empty((B, Hkv, D), dtype=torch.float32, device=dev)
         self.win_k = torch.empty((B, Hkv, eta, d), dtype=tdt, device=dev)
         self.win_v = torch.empty((B, Hkv, eta, d), dtype=tdt, device=dev)

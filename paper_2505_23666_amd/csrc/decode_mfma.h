@@ -1,17 +1,18 @@
-// Fused single-token generation step for the 8B/1B head shapes on gfx950: one workgroup of four
+// Fused single-token generation step for the 8B head shape on gfx950: one workgroup of four
 // wavefronts per (sequence, kv head), two workgroups resident per compute unit.
 //
 // What one launch does per stream (paper Sec. 3: E_t, G_t, S_t, H_t and y_t equations):
 //   - the new pair replaces the oldest one in the window ring; the displaced pair p leaves;
-//   - phi of the lambda cached keys (bf16 MFMA, exact products, fp32 accumulate, fp32 softmax),
-//     recall phi(k)^T H / phi(k)^T s of all lambda + 1 eligible pairs with H held ONCE in LDS as
-//     fp32 (operands split into bf16 high + low parts: three MFMAs per product, ~2^-17 relative),
-//     squared self-recall error, arg-min (ties: larger token index goes);
-//   - rank-1 fold of the dropped pair into H (in LDS) and s, H written back once;
+//   - phi of the lambda cached keys and of p (bf16 MFMA, exact products, fp32 accumulate, fp32
+//     softmax), recall phi(k)^T H / phi(k)^T s of all lambda + 1 eligible pairs: every wavefront keeps
+//     32 rows of H^T in registers (fp32, plus bf16 high + low parts as MFMA operands), the feature
+//     vectors are shared through LDS as bf16 high + low parts (three MFMAs per product, ~2^-17
+//     relative); squared self-recall error, arg-min (ties: larger token index goes);
+//   - rank-1 fold of the dropped pair into the fp32 registers, written back once; s likewise;
 //   - the dropped slot is overwritten in place by p (cache compaction);
 //   - outputs of the G query heads: softmax weights over cache + window with m = max(0, max logit),
-//     linear read-out phi(q)^T H taken from the same pass over H and corrected by the rank-1 term,
-//     shared normaliser.
+//     sum_i p_i v_i on MFMA from values staged in LDS, linear read-out phi(q)^T H taken from the
+//     same pass over H and corrected by the rank-1 term, shared normaliser.
 // H is read from HBM once and written once; cached K rows are read once, cached V rows twice
 // (second time from cache).
 //
@@ -28,19 +29,16 @@ namespace lola {
 namespace fast {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
-__device__ __forceinline__ bf16x8 ld_bf16x8(const bf16_t *p) {
-    uint4 u = *reinterpret_cast<const uint4 *>(p);
-    return __builtin_bit_cast(bf16x8, u);
-}
-__device__ __forceinline__ bf16x8 zero_bf16x8() {
-    uint4 u = make_uint4(0, 0, 0, 0);
-    return __builtin_bit_cast(bf16x8, u);
-}
+__device__ __forceinline__ bf16x8 as_bf16x8(uint4 u) { return __builtin_bit_cast(bf16x8, u); }
+__device__ __forceinline__ bf16x8 ld_bf16x8(const bf16_t *p) { return as_bf16x8(*reinterpret_cast<const uint4 *>(p)); }
+__device__ __forceinline__ bf16x8 zero_bf16x8() { return as_bf16x8(make_uint4(0, 0, 0, 0)); }
 // x = hi + lo + O(2^-17 |x|), both parts bf16
 __device__ __forceinline__ void split8(const float x[8], bf16x8 &hi, bf16x8 &lo) {
 #pragma unroll
@@ -50,7 +48,45 @@ __device__ __forceinline__ void split8(const float x[8], bf16x8 &hi, bf16x8 &lo)
         lo[e] = (__bf16)(x[e] - (float)h);
     }
 }
-__device__ __forceinline__ float bf_bits_to_f(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+__device__ __forceinline__ float bf_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf_hi(uint32_t u) { return __uint_as_float(u & 0xFFFF0000u); }
+__device__ __forceinline__ float dot2bf(uint32_t a, uint32_t b, float c) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), c, false);
+}
+// exchange with the lane 16 / 32 positions away (gfx950 row swaps): r0 and r1 are this lane's value and its partner's
+__device__ __forceinline__ void swap16(float v, float &r0, float &r1) {
+    auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    r0 = __uint_as_float(r[0]); r1 = __uint_as_float(r[1]);
+}
+__device__ __forceinline__ void swap32(float v, float &r0, float &r1) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    r0 = __uint_as_float(r[0]); r1 = __uint_as_float(r[1]);
+}
+// reductions over the four lanes that share l % 16
+__device__ __forceinline__ float grp_sum(float v) { float x, y; swap16(v, x, y); v = x + y; swap32(v, x, y); return x + y; }
+__device__ __forceinline__ float grp_max(float v) { float x, y; swap16(v, x, y); v = fmaxf(x, y); swap32(v, x, y); return fmaxf(x, y); }
+__device__ __forceinline__ float grp_min(float v) { float x, y; swap16(v, x, y); v = fminf(x, y); swap32(v, x, y); return fminf(x, y); }
+// reductions over the whole wavefront
+__device__ __forceinline__ float wsum(float v) {
+    v += __shfl_xor(v, 1, WAVE); v += __shfl_xor(v, 2, WAVE); v += __shfl_xor(v, 4, WAVE); v += __shfl_xor(v, 8, WAVE);
+    return grp_sum(v);
+}
+__device__ __forceinline__ float wmax(float v) {
+    v = fmaxf(v, __shfl_xor(v, 1, WAVE)); v = fmaxf(v, __shfl_xor(v, 2, WAVE));
+    v = fmaxf(v, __shfl_xor(v, 4, WAVE)); v = fmaxf(v, __shfl_xor(v, 8, WAVE));
+    return grp_max(v);
+}
+__device__ __forceinline__ float wmin(float v) { return -wmax(-v); }
+__device__ __forceinline__ float fexp2(float x) { return __builtin_amdgcn_exp2f(x); }
+constexpr float LOG2E = 1.4426950408889634f;
+
+#ifdef LOLA_TIMING
+extern __device__ long long lola_timing[];
+extern __device__ long long lola_stagger_ticks;
+#define LOLA_STAMP(k) do { if (threadIdx.x == 0) lola_timing[blockIdx.x * 16 + (k)] = wall_clock64(); } while (0)
+#else
+#define LOLA_STAMP(k) do { } while (0)
+#endif
 
 template <typename TO>
 struct DecodeFastArgs {
@@ -62,41 +98,86 @@ struct DecodeFastArgs {
     int phi_kind;
 };
 
-// DH = head_dim = 128, feature dim D = 128 (M = 64 projections), LAM multiple of 16 (<= 128 here),
+// phi of 16 vectors from their projections held in the C layout of the projection GEMM: lane (column r16,
+// group g4) holds z[16*mt + 4*g4 + i] in zt[mt][i]; the other three lanes of the column hold the rest.
+// Returns the lane's 16 positive-half and 16 negative-half features (same index pattern).
+__device__ __forceinline__ void phi_from_z(const f32x4 zt[4], int phi_kind, float pp[16], float pn[16]) {
+    if (phi_kind == 1) {
+#pragma unroll
+        for (int x = 0; x < 16; x++) { const float zs = zt[x >> 2][x & 3] * LOG2E; pp[x] = fexp2(zs); pn[x] = fexp2(-zs); }
+        return;
+    }
+    float zmax = zt[0][0], zmin = zt[0][0];
+#pragma unroll
+    for (int x = 1; x < 16; x++) { zmax = fmaxf(zmax, zt[x >> 2][x & 3]); zmin = fminf(zmin, zt[x >> 2][x & 3]); }
+    zmax = grp_max(zmax); zmin = grp_min(zmin);
+    const float cp = -zmax * LOG2E, cn = zmin * LOG2E;
+    float sp = 0.f, sn = 0.f;
+#pragma unroll
+    for (int x = 0; x < 16; x++) {
+        const float zz = zt[x >> 2][x & 3];
+        pp[x] = fexp2(fmaf(zz, LOG2E, cp)); pn[x] = fexp2(fmaf(zz, -LOG2E, cn));
+        sp += pp[x]; sn += pn[x];
+    }
+    sp = grp_sum(sp); sn = grp_sum(sn);
+    const float ip = 1.0f / sp, in_ = 1.0f / sn;
+#pragma unroll
+    for (int x = 0; x < 16; x++) { pp[x] *= ip; pn[x] *= in_; }
+}
+
+// DH = head_dim = 128, feature dim D = 128 (M = 64 projections), LAM multiple of 64 (<= 128 here),
 // ETA = 64, G = query heads per kv head (<= 4).
+//
+// LDS plan (about 78 KB, two workgroups per compute unit):
+//   PB   64 KB  bf16 high and low parts of phi of the cached keys, [key][feature chunk] with the 16-byte chunk index
+//               XOR-ed by key % 16 so that operand stores and loads are bank-conflict free.  After the recall GEMM
+//               the same bytes hold the value rows [key][c] (row stride 130 bf16) and the softmax weights as bf16
+//               high + low parts.
+//   PX    4 KB  the same for the "extra tile": row 0 the leaving key, rows 1..G the queries.
+//   the rest    small per-stream vectors.
+// H^T never goes through LDS: wavefront w owns its rows 32w .. 32w+31 (output columns of the recall GEMM).
 template <int LAM, int ETA, int G, typename TO>
 __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> a) {
     constexpr int DH = 128, M = 64, D = 128;
     constexpr int NKT = LAM / 16;          // key tiles of the sparse cache
-    constexpr int TPW = (NKT + 3) / 4;     // key tiles per wavefront
+    constexpr int TPW = NKT / 4;           // key tiles whose phi a wavefront computes
     constexpr int NWT = ETA / 16;          // window tiles
     constexpr int KP = LAM;                // position of the leaving pair in the logit / score arrays
     constexpr int KW = LAM + 1;            // first window position
     constexpr int NKEY = LAM + 1 + ETA;
-    static_assert(LAM % 16 == 0 && ETA % 16 == 0 && G >= 1 && G <= 4 && NKT <= 8 && NWT <= 4, "shape");
+    constexpr int NKS = (NKEY + 31) / 32;  // k-steps of the value read-out
+    constexpr int KPAD = NKS * 32;
+    constexpr int VLS = 130;               // row stride (bf16) of the staged values
+    constexpr int XR = 8;                  // rows reserved for the extra tile (1 + G used)
+    static_assert(NKT % 4 == 0 && ETA % 16 == 0 && G >= 1 && G <= 4 && NKT <= 8 && NWT <= 4, "shape");
+    constexpr int PB_ELEMS = (2 * LAM * D > KPAD * VLS + 2 * G * KPAD) ? 2 * LAM * D : ((KPAD * VLS + 2 * G * KPAD + 7) / 8) * 8;
 
-    __shared__ __attribute__((aligned(16))) float Hs[D * DH];   // fp32 H, column index XOR-swizzled by feature bit 2
-    __shared__ float s_l[D];
-    __shared__ float score2[LAM + 1];
-    __shared__ float errX[4];
-    __shared__ float lg[G][NKEY];          // logits, then softmax weights
-    __shared__ float phiX[1 + G][D];       // row 0: phi of the leaving key; rows 1..G: phi of the queries
+    __shared__ __attribute__((aligned(16))) uint16_t PB[PB_ELEMS];      // [0, LAM*D): high parts, [LAM*D, 2*LAM*D): low parts
+    __shared__ __attribute__((aligned(16))) uint16_t PX[2 * XR * D];
+    __shared__ __attribute__((aligned(16))) float s_l[D];
+    __shared__ float rden_l[LAM + 1];      // 1 / (phi(k)^T s) per eligible pair (0 while nothing was folded)
+    __shared__ float part[4][LAM + 1];     // squared-error partial sums, one row per wavefront (32 value columns each)
+    __shared__ float lg[G][NKEY];          // logits
     __shared__ float lin[G][DH];           // phi(q)^T H (state before the fold)
     __shared__ float denq[G], dotqf[G], psum_s[G], elin_s[G];
-    __shared__ float phif[D], vf[DH];      // the folded pair
-    __shared__ float pkf[DH], pvf[DH];     // the leaving pair
-    __shared__ uint16_t pkb[DH], pvb[DH];
+    __shared__ __attribute__((aligned(16))) float phif[D];
+    __shared__ float vf[DH];               // the folded pair
+    __shared__ float pvf[DH];              // value of the leaving pair
+    __shared__ __attribute__((aligned(16))) uint32_t qb[G][DH / 2];   // query rows, raw bf16 pairs
+    __shared__ __attribute__((aligned(16))) uint16_t pkb[DH];
+    __shared__ __attribute__((aligned(16))) uint16_t pvb[DH];
     __shared__ int idx_l[LAM];
-    __shared__ int sh_drop;
+    uint16_t *Vl = PB;                                                  // [KPAD][VLS] after the recall GEMM
+    uint16_t *Ph = PB + KPAD * VLS, *Pl = Ph + G * KPAD;               // [G][KPAD] weights, high / low parts
 
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r16 = lane & 15, g4 = lane >> 4;
     const int si = blockIdx.x, b = si / a.Hkv, h = si - b * a.Hkv;
-    float *Hg = a.st.H + (size_t)si * D * DH;
+    float *Hg = a.st.H + (size_t)si * D * DH;     // H^T [DH][D]
     float *sg = a.st.s + (size_t)si * D;
     bf16_t *win_k = a.st.win_k + (size_t)si * ETA * DH, *win_v = a.st.win_v + (size_t)si * ETA * DH;
     bf16_t *sp_k = a.st.sp_k + (size_t)si * LAM * DH, *sp_v = a.st.sp_v + (size_t)si * LAM * DH;
     int32_t *sp_idx = a.st.sp_idx + (size_t)si * LAM;
-    const bf16_t *Wk = a.Wk + (size_t)h * DH * M;
+    const bf16_t *Wk = a.Wk + (size_t)h * M * DH;            // [M][DH], row j = w_j
     const bf16_t *knew = a.k + (size_t)si * DH, *vnew = a.v + (size_t)si * DH;
     const bf16_t *qg = a.q + ((size_t)b * a.Hq + (size_t)h * G) * DH;   // G consecutive query rows
 
@@ -108,262 +189,326 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     const int pidx = (int)(tok - ETA);
     const int wn = (int)min((int64_t)ETA, tok + 1);   // window pairs after the push
 
-    // ---- stage 0: small per-stream vectors; the leaving pair is read before its slot is overwritten
-    if (tid < D) { s_l[tid] = sg[tid]; }
-    if (tid < LAM) idx_l[tid] = sp_idx[tid];
-    if (popped && tid < DH) {
-        uint16_t kb = win_k[(size_t)slot * DH + tid].x, vb = win_v[(size_t)slot * DH + tid].x;
-        pkb[tid] = kb; pvb[tid] = vb;
-        pkf[tid] = bf_bits_to_f(kb); pvf[tid] = bf_bits_to_f(vb);
+#ifdef LOLA_TIMING
+    if (lola_stagger_ticks > 0 && blockIdx.x >= gridDim.x / 2) {
+        const long long t0 = wall_clock64();
+        while (wall_clock64() - t0 < lola_stagger_ticks) __builtin_amdgcn_s_sleep(8);
     }
+#endif
+    LOLA_STAMP(0);
+#ifdef LOLA_TIMING
+    if (threadIdx.x == 0) lola_timing[blockIdx.x * 16 + 13] = clock64();
+#endif
+    // ---- stage 0: loads are requested in the order in which they are consumed (they complete in order): the small
+    // per-stream vectors that the first barrier waits for, then the operands of the projections, then the window keys
+    const uint4 q_ld = (tid >= 64 && tid < 64 + G * 16) ? reinterpret_cast<const uint4 *>(qg)[tid - 64] : make_uint4(0, 0, 0, 0);
+    const float4 s_ld = tid < D / 4 ? reinterpret_cast<const float4 *>(sg)[tid] : make_float4(0.f, 0.f, 0.f, 0.f);
+    const int idx_ld = tid < LAM ? sp_idx[tid] : 0;
+    uint4 p_ld = make_uint4(0, 0, 0, 0);
+    if (popped && tid < 32)   // 16 threads fetch the leaving key row, 16 the value row (16 bytes each)
+        p_ld = reinterpret_cast<const uint4 *>(tid < 16 ? win_k + (size_t)slot * DH : win_v + (size_t)slot * DH)[tid & 15];
+    // row `lane` of this wavefront's W_q (projection on the vector ALUs, lane = projection index)
+    uint4 wq[16];
+    {
+        const bf16_t *Wq = a.Wq + (((size_t)h * G + (w < G ? w : 0)) * M + lane) * DH;
+#pragma unroll
+        for (int it = 0; it < 16; it++) wq[it] = reinterpret_cast<const uint4 *>(Wq)[it];
+    }
+    // W_k as MFMA A operand (row = projection, k = input index): [projection tile][k-step]
+    bf16x8 AW[4][4];
+#pragma unroll
+    for (int mt = 0; mt < 4; mt++)
+#pragma unroll
+        for (int ks = 0; ks < 4; ks++) AW[mt][ks] = ld_bf16x8(Wk + (size_t)(16 * mt + r16) * DH + 32 * ks + 8 * g4);
+    // cached key rows of this wavefront's tiles, already in MFMA B-operand form (column = key, k = input index)
+    bf16x8 BK[TPW][4];
+#pragma unroll
+    for (int t = 0; t < TPW; t++)
+#pragma unroll
+        for (int ks = 0; ks < 4; ks++) BK[t][ks] = ld_bf16x8(sp_k + (size_t)(16 * (w + 4 * t) + r16) * DH + 32 * ks + 8 * g4);
+    // window keys of this wavefront's tile; the ring slot of the new token is taken from the input
+    bf16x8 BWin[4];
+    {
+        const int row = 16 * (w < NWT ? w : 0) + r16;
+        const bf16_t *src = row == slot ? knew : win_k + (size_t)row * DH;
+#pragma unroll
+        for (int ks = 0; ks < 4; ks++) BWin[ks] = ld_bf16x8(src + 32 * ks + 8 * g4);
+    }
+    LOLA_STAMP(9);
+    if (tid < D / 4) reinterpret_cast<float4 *>(s_l)[tid] = s_ld;
+    if (tid < LAM) idx_l[tid] = idx_ld;
+    if (popped && tid < 32) {
+        reinterpret_cast<uint4 *>(tid < 16 ? pkb : pvb)[tid & 15] = p_ld;
+        if (tid >= 16) {
+            float *d = pvf + 8 * (tid & 15);
+            d[0] = bf_lo(p_ld.x); d[1] = bf_hi(p_ld.x); d[2] = bf_lo(p_ld.y); d[3] = bf_hi(p_ld.y);
+            d[4] = bf_lo(p_ld.z); d[5] = bf_hi(p_ld.z); d[6] = bf_lo(p_ld.w); d[7] = bf_hi(p_ld.w);
+        }
+    }
+    if (tid >= 64 && tid < 64 + G * 16) reinterpret_cast<uint4 *>(qb)[tid - 64] = q_ld;
+    if (tid >= 128 && tid < 128 + 2 * XR * D / 8) reinterpret_cast<uint4 *>(PX)[tid - 128] = make_uint4(0, 0, 0, 0);
     __syncthreads();
+    LOLA_STAMP(1);
+    // the new pair takes the ring slot of the pair that leaves (read above)
     if (tid < 16) reinterpret_cast<uint4 *>(win_k + (size_t)slot * DH)[tid] = reinterpret_cast<const uint4 *>(knew)[tid];
     else if (tid < 32) reinterpret_cast<uint4 *>(win_v + (size_t)slot * DH)[tid - 16] = reinterpret_cast<const uint4 *>(vnew)[tid - 16];
 
     // ---- query rows as MFMA A operand (rows >= G are zero)
     bf16x8 AQ[4];
 #pragma unroll
-    for (int ks = 0; ks < 4; ks++) AQ[ks] = r16 < G ? ld_bf16x8(qg + (size_t)r16 * DH + 32 * ks + 8 * g4) : zero_bf16x8();
+    for (int ks = 0; ks < 4; ks++)
+        AQ[ks] = r16 < G ? as_bf16x8(*reinterpret_cast<const uint4 *>(&qb[r16][16 * ks + 4 * g4])) : zero_bf16x8();
 
-    // ---- stage 1a: phi of the queries (and of the leaving key) on the vector ALUs, one vector per wavefront
-    // lane j computes projection j; W reads are coalesced along j
-    if (steady) {
-        for (int r = w; r < 1 + G; r += 4) {
-            // r < G: query r (row r + 1 of phiX); r == G: the leaving key (row 0)
-            const bf16_t *W = r < G ? a.Wq + ((size_t)h * G + r) * DH * M : Wk;
-            float z = 0.f;
-            if (r < G) {
-                const bf16_t *x = qg + (size_t)r * DH;
-#pragma unroll 8
-                for (int i = 0; i < DH; i++) z = fmaf(ldf(W, (size_t)i * M + lane), ldf(x, i), z);
-            } else {
-#pragma unroll 8
-                for (int i = 0; i < DH; i++) z = fmaf(ldf(W, (size_t)i * M + lane), pkf[i], z);
-            }
-            float pp, pn;
-            if (a.phi_kind == 1) { pp = __expf(z); pn = __expf(-z); }
-            else {
-                float zmax = wave_max(z), zmin = wave_min(z);
-                float ep = __expf(z - zmax), en = __expf(zmin - z);
-                pp = ep / wave_sum(ep); pn = en / wave_sum(en);
-            }
-            const int row = r < G ? r + 1 : 0;
-            phiX[row][lane] = pp; phiX[row][M + lane] = pn;
-            float dn = wave_sum(pp * s_l[lane] + pn * s_l[M + lane]);
-            if (lane == 0) { if (r < G) denq[r] = dn; else errX[0] = dn; }   // errX[0] temporarily carries the leaving key's denominator
-        }
-    }
-    // logit of the leaving key (it is attended if it stays in the cache)
-    if (popped) {
-        for (int r = w; r < G; r += 4) {
-            const bf16_t *x = qg + (size_t)r * DH;
-            float dot = ldf(x, lane) * pkf[lane] + ldf(x, lane + 64) * pkf[lane + 64];
-            dot = wave_sum(dot);
-            if (lane == 0) lg[r][KP] = dot * a.scale;
-        }
-    }
-
-    // ---- stage 1b: per key tile: logits (Q K^T) and, in steady state, phi(K) -> B operands of the recall GEMM
-    bf16x8 AW[4][4];
-    if (steady) {
-#pragma unroll
-        for (int mt = 0; mt < 4; mt++)
-#pragma unroll
-            for (int ks = 0; ks < 4; ks++) {
-                bf16x8 t;
-#pragma unroll
-                for (int e = 0; e < 8; e++) {
-                    uint16_t bits = Wk[(size_t)(32 * ks + 8 * g4 + e) * M + 16 * mt + r16].x;
-                    t[e] = __builtin_bit_cast(__bf16, bits);
-                }
-                AW[mt][ks] = t;
-            }
-    }
-    bf16x8 Bhi[TPW][4], Blo[TPW][4];
-    float rden[TPW];
+    // ---- logits of this wavefront's cached-key tiles and window tile (Q K^T)
 #pragma unroll
     for (int t = 0; t < TPW; t++) {
-        const int tile = w + 4 * t;
-        rden[t] = 0.f;
-        if (tile < NKT) {
-            const int key = 16 * tile + r16;
-            bf16x8 BK[4];
-#pragma unroll
-            for (int ks = 0; ks < 4; ks++) BK[ks] = ld_bf16x8(sp_k + (size_t)key * DH + 32 * ks + 8 * g4);
-            f32x4 accL = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int ks = 0; ks < 4; ks++) accL = mfma16(AQ[ks], BK[ks], accL);
-            if (g4 == 0) {
-#pragma unroll
-                for (int i = 0; i < G; i++) lg[i][key] = accL[i] * a.scale;
-            }
-            if (steady) {
-                f32x4 z[4];
-#pragma unroll
-                for (int mt = 0; mt < 4; mt++) {
-                    z[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int ks = 0; ks < 4; ks++) z[mt] = mfma16(AW[mt][ks], BK[ks], z[mt]);
-                }
-                // lane holds z[key][16*mt + 4*g4 + i]; the other three lane groups hold the rest of the row
-                float pp[16], pn[16];
-                if (a.phi_kind == 1) {
-#pragma unroll
-                    for (int x = 0; x < 16; x++) { float zz = z[x >> 2][x & 3]; pp[x] = __expf(zz); pn[x] = __expf(-zz); }
-                } else {
-                    float zmax = z[0][0], zmin = z[0][0];
-#pragma unroll
-                    for (int x = 1; x < 16; x++) { zmax = fmaxf(zmax, z[x >> 2][x & 3]); zmin = fminf(zmin, z[x >> 2][x & 3]); }
-                    zmax = fmaxf(zmax, __shfl_xor(zmax, 16, WAVE)); zmax = fmaxf(zmax, __shfl_xor(zmax, 32, WAVE));
-                    zmin = fminf(zmin, __shfl_xor(zmin, 16, WAVE)); zmin = fminf(zmin, __shfl_xor(zmin, 32, WAVE));
-                    float sp = 0.f, sn = 0.f;
-#pragma unroll
-                    for (int x = 0; x < 16; x++) {
-                        float zz = z[x >> 2][x & 3];
-                        pp[x] = __expf(zz - zmax); pn[x] = __expf(zmin - zz);
-                        sp += pp[x]; sn += pn[x];
-                    }
-                    sp += __shfl_xor(sp, 16, WAVE); sp += __shfl_xor(sp, 32, WAVE);
-                    sn += __shfl_xor(sn, 16, WAVE); sn += __shfl_xor(sn, 32, WAVE);
-                    const float ip = 1.0f / sp, in_ = 1.0f / sn;
-#pragma unroll
-                    for (int x = 0; x < 16; x++) { pp[x] *= ip; pn[x] *= in_; }
-                }
-                float dn = 0.f;
-#pragma unroll
-                for (int x = 0; x < 16; x++) {
-                    const int f = 16 * (x >> 2) + 4 * g4 + (x & 3);
-                    dn = fmaf(pp[x], s_l[f], dn);
-                    dn = fmaf(pn[x], s_l[M + f], dn);
-                }
-                dn += __shfl_xor(dn, 16, WAVE); dn += __shfl_xor(dn, 32, WAVE);
-                rden[t] = dn > 0.f ? 1.0f / dn : 0.f;
-                // feature order of the recall GEMM: ks 0,1 -> positive half (mt 0,1 / 2,3), ks 2,3 -> negative half
-                split8(&pp[0], Bhi[t][0], Blo[t][0]);
-                split8(&pp[8], Bhi[t][1], Blo[t][1]);
-                split8(&pn[0], Bhi[t][2], Blo[t][2]);
-                split8(&pn[8], Bhi[t][3], Blo[t][3]);
-            }
-        }
-    }
-    // window logits: one tile per wavefront; the ring slot of the new token is taken from the input
-    if (w < NWT) {
-        const int row = 16 * w + r16;
-        const bf16_t *src = row == slot ? knew : win_k + (size_t)row * DH;
         f32x4 accL = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int ks = 0; ks < 4; ks++) accL = mfma16(AQ[ks], ld_bf16x8(src + 32 * ks + 8 * g4), accL);
+        for (int ks = 0; ks < 4; ks++) accL = mfma16(AQ[ks], BK[t][ks], accL);
+        if (g4 == 0) {
+#pragma unroll
+            for (int i = 0; i < G; i++) lg[i][16 * (w + 4 * t) + r16] = accL[i] * a.scale;
+        }
+    }
+    // window logits: one tile per wavefront
+    if (w < NWT) {
+        const int row = 16 * w + r16;
+        f32x4 accL = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < 4; ks++) accL = mfma16(AQ[ks], BWin[ks], accL);
         if (g4 == 0) {
 #pragma unroll
             for (int i = 0; i < G; i++) lg[i][KW + row] = accL[i] * a.scale;
         }
     }
 
-    int drop = -1;   // candidate that is folded: < LAM a cache slot, == LAM the leaving pair, -1 none
+    LOLA_STAMP(10);
+    // ---- stage 1a: phi of this wavefront's query: z_lane = w_lane . q; stored as bf16 high + low parts in the
+    // operand layout of the recall GEMM (row w + 1 of the extra tile)
+    if (steady && w < G) {
+        float z = 0.f;
+#pragma unroll
+        for (int it = 0; it < 16; it++) {
+            const uint4 xv = reinterpret_cast<const uint4 *>(qb[w])[it];
+            z = dot2bf(wq[it].x, xv.x, z); z = dot2bf(wq[it].y, xv.y, z);
+            z = dot2bf(wq[it].z, xv.z, z); z = dot2bf(wq[it].w, xv.w, z);
+        }
+        float pp, pn;
+        if (a.phi_kind == 1) { pp = fexp2(z * LOG2E); pn = fexp2(-z * LOG2E); }
+        else {
+            const float zmax = wmax(z), zmin = wmin(z);
+            const float ep = fexp2((z - zmax) * LOG2E), en = fexp2((zmin - z) * LOG2E);
+            pp = ep / wsum(ep); pn = en / wsum(en);
+        }
+        const float dn = wsum(fmaf(pp, s_l[lane], pn * s_l[M + lane]));
+        if (lane == 0) denq[w] = dn;
+        // feature f sits in chunk (f / 32) * 4 + (f / 4) % 4, element 4 * ((f / 16) % 2) + f % 4
+        const int row = w + 1;
+#pragma unroll
+        for (int half = 0; half < 2; half++) {
+            const int f = half * M + lane;
+            const float val = half ? pn : pp;
+            const int addr = row * D + (((((f >> 5) << 2) | ((f >> 2) & 3)) ^ row) << 3) + (((f >> 4) & 1) << 2) + (f & 3);
+            const __bf16 hi = (__bf16)val;
+            PX[addr] = __builtin_bit_cast(uint16_t, hi);
+            PX[XR * D + addr] = __builtin_bit_cast(uint16_t, (__bf16)(val - (float)hi));
+        }
+    }
+    // logit of the leaving key (it is attended if it stays in the cache)
+    if (popped) {
+        for (int r = w; r < G; r += 4) {
+            float dot = wsum(dot2bf(qb[r][lane], reinterpret_cast<const uint32_t *>(pkb)[lane], 0.f));
+            if (lane == 0) lg[r][KP] = dot * a.scale;
+        }
+    }
+
+    LOLA_STAMP(11);
+    // ---- H^T rows of this wavefront are requested now and stay in registers until the fold writes them back:
+    // lane (r16, g4) holds, for column tile ct and k-step ks, H^T[32w + 16ct + r16][32ks + 16 half + 4 g4 + 0..3]
+    // (named scalars rather than an array: arrays of this size end up in scratch memory)
+#define LOLA_HREP(X) X(0, 0, 0) X(0, 0, 1) X(0, 1, 0) X(0, 1, 1) X(0, 2, 0) X(0, 2, 1) X(0, 3, 0) X(0, 3, 1) \
+                     X(1, 0, 0) X(1, 0, 1) X(1, 1, 0) X(1, 1, 1) X(1, 2, 0) X(1, 2, 1) X(1, 3, 0) X(1, 3, 1)
+#define LOLA_HADDR(ct, ks, hf) ((size_t)(32 * w + 16 * ct + r16) * D + 32 * ks + 16 * hf + 4 * g4)
+#define LOLA_HDECL(ct, ks, hf) float4 hreg##ct##ks##hf = make_float4(0.f, 0.f, 0.f, 0.f);
+#define LOLA_HLOAD(ct, ks, hf) hreg##ct##ks##hf = *reinterpret_cast<const float4 *>(Hg + LOLA_HADDR(ct, ks, hf));
+    LOLA_HREP(LOLA_HDECL)
+    if (steady) { LOLA_HREP(LOLA_HLOAD) }
+
+    // ---- stage 1b: logits Q K^T of this wavefront's key tiles; in steady state z^T = W_k K^T -> phi -> LDS.
+    // Wavefront 0 also projects the leaving key (a tile with one real column).
+    f32x4 zt[TPW + 1][4];
     if (steady) {
-        // ---- stage 2: recall of all eligible pairs: P^T = H^T Phi^T, H from LDS
-        // cached values in the C layout of P^T: lane (key r16, group g4) needs v[key][16*mt + 4*g4 + 0..3]
-        uint2 vreg[TPW][8];
+        bf16x8 BP[4];
 #pragma unroll
-        for (int t = 0; t < TPW; t++) {
-            const int tile = w + 4 * t;
-            if (tile < NKT) {
+        for (int ks = 0; ks < 4; ks++)
+            BP[ks] = (w == 0 && r16 == 0) ? as_bf16x8(*reinterpret_cast<const uint4 *>(&pkb[32 * ks + 8 * g4])) : zero_bf16x8();
 #pragma unroll
-                for (int mt = 0; mt < 8; mt++)
-                    vreg[t][mt] = *reinterpret_cast<const uint2 *>(sp_v + (size_t)(16 * tile + r16) * DH + 16 * mt + 4 * g4);
-            }
-        }
-        // H -> LDS (coalesced float4 reads, swizzled so that the four lane groups of an A-operand read hit distinct banks)
-#pragma unroll 4
-        for (int r = 0; r < (D * DH / 4) / 256; r++) {
-            const int idx4 = tid + 256 * r, f = idx4 >> 5, c = (idx4 & 31) << 2;
-            float4 val = reinterpret_cast<const float4 *>(Hg)[idx4];
-            *reinterpret_cast<float4 *>(&Hs[f * DH + (c ^ (((f >> 2) & 1) << 4))]) = val;
-        }
-        __syncthreads();
-        const float denP = errX[0];
-        const float rdenX = denP > 0.f ? 1.0f / denP : 0.f;
-        // B operands of the extra tile: row 0 the leaving key, rows 1..G the queries
-        bf16x8 BXhi[4], BXlo[4];
-#pragma unroll
-        for (int ks = 0; ks < 4; ks++) {
-            float x[8];
-#pragma unroll
-            for (int e = 0; e < 8; e++) x[e] = r16 <= G ? phiX[r16][32 * ks + 16 * (e >> 2) + 4 * g4 + (e & 3)] : 0.f;
-            split8(x, BXhi[ks], BXlo[ks]);
-        }
-        float err[TPW], errP = 0.f;
-#pragma unroll
-        for (int t = 0; t < TPW; t++) err[t] = 0.f;
-        const int swz = (g4 & 1) << 4;
-#pragma unroll
-        for (int mt = 0; mt < 8; mt++) {
-            const bool doX = (mt >> 1) == w;     // the extra tile's eight column tiles are shared out, two per wavefront
-            f32x4 acc[TPW], accX = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int t = 0; t < TPW; t++) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
-            const int c = (16 * mt + r16) ^ swz;
-#pragma unroll
-            for (int ks = 0; ks < 4; ks++) {
-                float x[8];
-#pragma unroll
-                for (int e = 0; e < 8; e++) x[e] = Hs[(32 * ks + 16 * (e >> 2) + 4 * g4 + (e & 3)) * DH + c];
-                bf16x8 Ahi, Alo;
-                split8(x, Ahi, Alo);
-#pragma unroll
-                for (int t = 0; t < TPW; t++) {
-                    if (w + 4 * t < NKT) {
-                        acc[t] = mfma16(Ahi, Bhi[t][ks], acc[t]);
-                        acc[t] = mfma16(Ahi, Blo[t][ks], acc[t]);
-                        acc[t] = mfma16(Alo, Bhi[t][ks], acc[t]);
-                    }
-                }
-                if (doX) {
-                    accX = mfma16(Ahi, BXhi[ks], accX);
-                    accX = mfma16(Ahi, BXlo[ks], accX);
-                    accX = mfma16(Alo, BXhi[ks], accX);
-                }
-            }
+        for (int mt = 0; mt < 4; mt++) {
 #pragma unroll
             for (int t = 0; t < TPW; t++) {
-                if (w + 4 * t < NKT) {
-                    const uint2 vv = vreg[t][mt];
-                    const float v0 = __uint_as_float(vv.x << 16), v1 = __uint_as_float(vv.x & 0xFFFF0000u);
-                    const float v2 = __uint_as_float(vv.y << 16), v3 = __uint_as_float(vv.y & 0xFFFF0000u);
-                    float e0 = fmaf(acc[t][0], rden[t], -v0), e1 = fmaf(acc[t][1], rden[t], -v1);
-                    float e2 = fmaf(acc[t][2], rden[t], -v2), e3 = fmaf(acc[t][3], rden[t], -v3);
-                    err[t] = fmaf(e0, e0, err[t]); err[t] = fmaf(e1, e1, err[t]);
-                    err[t] = fmaf(e2, e2, err[t]); err[t] = fmaf(e3, e3, err[t]);
-                }
+                zt[t][mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < 4; ks++) zt[t][mt] = mfma16(AW[mt][ks], BK[t][ks], zt[t][mt]);
             }
-            if (doX) {
-                const int c0 = 16 * mt + 4 * g4;
-                if (r16 == 0) {
+            zt[TPW][mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            if (w == 0) {
 #pragma unroll
-                    for (int i = 0; i < 4; i++) { float e = fmaf(accX[i], rdenX, -pvf[c0 + i]); errP = fmaf(e, e, errP); }
-                } else if (r16 <= G) {
+                for (int ks = 0; ks < 4; ks++) zt[TPW][mt] = mfma16(AW[mt][ks], BP[ks], zt[TPW][mt]);
+            }
+        }
+    }
+    LOLA_STAMP(12);
+    if (steady) {
 #pragma unroll
-                    for (int i = 0; i < 4; i++) lin[r16 - 1][c0 + i] = accX[i];
+        for (int t = 0; t <= TPW; t++) {
+            if (t < TPW || w == 0) {
+                // t < TPW: cached keys, rows of PB; t == TPW (wavefront 0): the leaving key, row 0 of the extra tile
+                const int row = t < TPW ? 16 * (w + 4 * t) + r16 : 0;
+                float pp[16], pn[16];
+                phi_from_z(zt[t], a.phi_kind, pp, pn);
+                float dn = 0.f;
+#pragma unroll
+                for (int mt = 0; mt < 4; mt++) {
+                    const float4 sp4 = *reinterpret_cast<const float4 *>(&s_l[16 * mt + 4 * g4]);
+                    const float4 sn4 = *reinterpret_cast<const float4 *>(&s_l[M + 16 * mt + 4 * g4]);
+                    dn = fmaf(pp[4 * mt], sp4.x, dn); dn = fmaf(pp[4 * mt + 1], sp4.y, dn);
+                    dn = fmaf(pp[4 * mt + 2], sp4.z, dn); dn = fmaf(pp[4 * mt + 3], sp4.w, dn);
+                    dn = fmaf(pn[4 * mt], sn4.x, dn); dn = fmaf(pn[4 * mt + 1], sn4.y, dn);
+                    dn = fmaf(pn[4 * mt + 2], sn4.z, dn); dn = fmaf(pn[4 * mt + 3], sn4.w, dn);
+                }
+                dn = grp_sum(dn);
+                // feature order of the recall GEMM: ks 0,1 -> positive half (mt 0,1 / 2,3), ks 2,3 -> negative half;
+                // the lane's eight values of a k-step are exactly chunk 4 ks + g4 of the row
+                bf16x8 hi[4], lo[4];
+                split8(&pp[0], hi[0], lo[0]); split8(&pp[8], hi[1], lo[1]);
+                split8(&pn[0], hi[2], lo[2]); split8(&pn[8], hi[3], lo[3]);
+                if (t < TPW) {
+                    if (g4 == 0) rden_l[row] = dn > 0.f ? 1.0f / dn : 0.f;
+#pragma unroll
+                    for (int ks = 0; ks < 4; ks++) {
+                        const int addr = row * D + (((4 * ks + g4) ^ r16) << 3);
+                        *reinterpret_cast<uint4 *>(&PB[addr]) = __builtin_bit_cast(uint4, hi[ks]);
+                        *reinterpret_cast<uint4 *>(&PB[LAM * D + addr]) = __builtin_bit_cast(uint4, lo[ks]);
+                    }
+                } else if (r16 == 0) {
+                    if (g4 == 0) rden_l[KP] = dn > 0.f ? 1.0f / dn : 0.f;
+#pragma unroll
+                    for (int ks = 0; ks < 4; ks++) {
+                        const int addr = ((4 * ks + g4) << 3);   // row 0: no swizzle
+                        *reinterpret_cast<uint4 *>(&PX[addr]) = __builtin_bit_cast(uint4, hi[ks]);
+                        *reinterpret_cast<uint4 *>(&PX[XR * D + addr]) = __builtin_bit_cast(uint4, lo[ks]);
+                    }
                 }
             }
         }
-        __syncthreads();   // errX[0] (the leaving key's denominator) has been read by everyone
+    }
+    LOLA_STAMP(2);
+    // value rows for the read-out are requested as soon as registers allow (after the recall GEMM in steady state);
+    // they go to LDS once the feature tile is free
+    constexpr int NVIT = KPAD * (DH / 8) / 256;
+    static_assert(KPAD * (DH / 8) % 256 == 0, "value staging is an exact number of passes");
+    uint4 vst[NVIT];
+    auto load_values = [&]() {
 #pragma unroll
-        for (int t = 0; t < TPW; t++) {
-            float e = err[t];
-            e += __shfl_xor(e, 16, WAVE); e += __shfl_xor(e, 32, WAVE);
-            if (g4 == 0 && w + 4 * t < NKT) score2[16 * (w + 4 * t) + r16] = e;
+        for (int it = 0; it < NVIT; it++) {
+            const int o = tid + 256 * it, key = o >> 4, c8 = o & 15;
+            vst[it] = make_uint4(0, 0, 0, 0);
+            if (key < NKEY && key != KP) {
+                const bf16_t *src;
+                if (key < LAM) src = sp_v + (size_t)key * DH;
+                else { const int row = key - KW; src = row == slot ? vnew : win_v + (size_t)row * DH; }
+                vst[it] = reinterpret_cast<const uint4 *>(src)[c8];
+            } else if (key == KP && popped) {
+                vst[it] = reinterpret_cast<const uint4 *>(pvb)[c8];
+            }
         }
-        errP += __shfl_xor(errP, 16, WAVE); errP += __shfl_xor(errP, 32, WAVE);
-        if (lane == 0) errX[w] = errP;
+    };
+    int drop = -1;   // candidate that is folded: < LAM a cache slot, == LAM the leaving pair, -1 none
+    if (steady) {
+        // ---- stage 2: recall of all eligible pairs: P^T = H^T Phi^T; A = this wavefront's rows of H^T (bf16 high +
+        // low parts made here), B = feature vectors from LDS
+        bf16x8 Ahi[2][4], Alo[2][4];
+#define LOLA_HSPLIT(ct, ks, hf) { const float4 v = hreg##ct##ks##hf; \
+            const __bf16 h0 = (__bf16)v.x, h1 = (__bf16)v.y, h2 = (__bf16)v.z, h3 = (__bf16)v.w; \
+            Ahi[ct][ks][4 * hf] = h0; Ahi[ct][ks][4 * hf + 1] = h1; Ahi[ct][ks][4 * hf + 2] = h2; Ahi[ct][ks][4 * hf + 3] = h3; \
+            Alo[ct][ks][4 * hf] = (__bf16)(v.x - (float)h0); Alo[ct][ks][4 * hf + 1] = (__bf16)(v.y - (float)h1); \
+            Alo[ct][ks][4 * hf + 2] = (__bf16)(v.z - (float)h2); Alo[ct][ks][4 * hf + 3] = (__bf16)(v.w - (float)h3); }
+        LOLA_HREP(LOLA_HSPLIT)
+#undef LOLA_HSPLIT
+        __syncthreads();   // feature vectors and denominators of all eligible pairs are in LDS
+        LOLA_STAMP(3);
+        // Key tiles 0..NKT-1 are the cache slots; tile NKT is the extra tile (column 0: the leaving key, columns 1..G:
+        // the queries, whose "recall" numerators are the linear read-out).  C layout: lane (column r16, group g4)
+        // holds rows c = 32w + 16ct + 4 g4 + i.  The cached values v[key][c..c+3] are requested one tile ahead.
+        uint2 vnext[2];
+#pragma unroll
+        for (int ct = 0; ct < 2; ct++) vnext[ct] = *reinterpret_cast<const uint2 *>(sp_v + (size_t)r16 * DH + 32 * w + 16 * ct + 4 * g4);
+#pragma unroll
+        for (int kt = 0; kt <= NKT; kt++) {
+            uint2 vcur[2] = {vnext[0], vnext[1]};
+            if (kt + 1 < NKT) {
+#pragma unroll
+                for (int ct = 0; ct < 2; ct++)
+                    vnext[ct] = *reinterpret_cast<const uint2 *>(sp_v + (size_t)(16 * (kt + 1) + r16) * DH + 32 * w + 16 * ct + 4 * g4);
+            }
+            const uint16_t *bh = kt < NKT ? PB + (16 * kt + r16) * D : PX + (r16 < XR ? r16 : 0) * D;
+            const uint16_t *bl = kt < NKT ? bh + LAM * D : bh + XR * D;
+            const int swz = kt < NKT ? r16 : (r16 < XR ? r16 : 0);
+            f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}}, acc2[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+            for (int ks = 0; ks < 4; ks++) {
+                const int off = ((4 * ks + g4) ^ swz) << 3;
+                const bf16x8 Bh = as_bf16x8(*reinterpret_cast<const uint4 *>(bh + off));
+                const bf16x8 Bl = as_bf16x8(*reinterpret_cast<const uint4 *>(bl + off));
+#pragma unroll
+                for (int ct = 0; ct < 2; ct++) acc[ct] = mfma16(Ahi[ct][ks], Bh, acc[ct]);
+#pragma unroll
+                for (int ct = 0; ct < 2; ct++) acc2[ct] = mfma16(Ahi[ct][ks], Bl, acc2[ct]);
+#pragma unroll
+                for (int ct = 0; ct < 2; ct++) acc2[ct] = mfma16(Alo[ct][ks], Bh, acc2[ct]);
+            }
+            if (kt < NKT) {
+                const float rd = rden_l[16 * kt + r16];
+                float e2 = 0.f;
+#pragma unroll
+                for (int ct = 0; ct < 2; ct++) {
+                    const f32x4 p = acc[ct] + acc2[ct];
+                    const uint2 vv = vcur[ct];
+                    const float e0 = fmaf(p[0], rd, -bf_lo(vv.x)), e1 = fmaf(p[1], rd, -bf_hi(vv.x));
+                    const float e2_ = fmaf(p[2], rd, -bf_lo(vv.y)), e3 = fmaf(p[3], rd, -bf_hi(vv.y));
+                    e2 = fmaf(e0, e0, e2); e2 = fmaf(e1, e1, e2); e2 = fmaf(e2_, e2_, e2); e2 = fmaf(e3, e3, e2);
+                }
+                e2 = grp_sum(e2);
+                if (g4 == 0) part[w][16 * kt + r16] = e2;
+            } else {
+                const float rd = rden_l[KP];
+                float e2 = 0.f;
+#pragma unroll
+                for (int ct = 0; ct < 2; ct++) {
+                    const f32x4 p = acc[ct] + acc2[ct];
+                    const int c0 = 32 * w + 16 * ct + 4 * g4;
+                    if (r16 == 0) {
+#pragma unroll
+                        for (int i = 0; i < 4; i++) { const float e = fmaf(p[i], rd, -pvf[c0 + i]); e2 = fmaf(e, e, e2); }
+                    } else if (r16 <= G) {
+#pragma unroll
+                        for (int i = 0; i < 4; i++) lin[r16 - 1][c0 + i] = p[i];
+                    }
+                }
+                e2 = grp_sum(e2);
+                if (lane == 0) part[w][KP] = e2;
+            }
+        }
+        LOLA_STAMP(4);
         __syncthreads();
-
+        load_values();
         // ---- stage 3: the pair that leaves the cache: smallest error, ties -> larger token index
-        if (w == 0) {
+        // (every wavefront does the same search, which saves a barrier)
+        {
             float bs = INFINITY; int bi = -1, be = 0;
             for (int e = lane; e <= LAM; e += WAVE) {
-                float sc = e < LAM ? score2[e] : errX[0] + errX[1] + errX[2] + errX[3];
-                int ix = e < LAM ? idx_l[e] : pidx;
+                const float sc = part[0][e] + part[1][e] + part[2][e] + part[3][e];
+                const int ix = e < LAM ? idx_l[e] : pidx;
                 if (sc < bs || (sc == bs && ix > bi)) { bs = sc; bi = ix; be = e; }
             }
 #pragma unroll
@@ -371,30 +516,17 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
                 float os = __shfl_xor(bs, o, WAVE); int oi = __shfl_xor(bi, o, WAVE), oe = __shfl_xor(be, o, WAVE);
                 if (os < bs || (os == bs && oi > bi)) { bs = os; bi = oi; be = oe; }
             }
-            if (lane == 0) sh_drop = be;
+            drop = be;
         }
-        __syncthreads();
-        drop = sh_drop;
-        // phi and v of the folded pair
-        if (drop < LAM) {
-            const int tile = drop >> 4;
-            if ((tile & 3) == w && r16 == (drop & 15)) {
-                const int t = tile >> 2;
-#pragma unroll
-                for (int tt = 0; tt < TPW; tt++) {
-                    if (tt == t) {
-#pragma unroll
-                        for (int ks = 0; ks < 4; ks++)
-#pragma unroll
-                            for (int e = 0; e < 8; e++)
-                                phif[32 * ks + 16 * (e >> 2) + 4 * g4 + (e & 3)] = (float)Bhi[tt][ks][e] + (float)Blo[tt][ks][e];
-                    }
-                }
-            }
-            if (tid < DH) vf[tid] = ldf(sp_v, (size_t)drop * DH + tid);
-        } else {
-            if (tid < D) phif[tid] = phiX[0][tid];
-            if (tid < DH) vf[tid] = pvf[tid];
+        LOLA_STAMP(5);
+        // phi and v of the folded pair (phi from its bf16 high + low parts)
+        if (tid < D) {
+            const int f = tid;
+            const int chunk = ((f >> 5) << 2) | ((f >> 2) & 3), el = (((f >> 4) & 1) << 2) + (f & 3);
+            const uint16_t *bh = drop < LAM ? PB + drop * D + ((chunk ^ (drop & 15)) << 3) + el : PX + (chunk << 3) + el;
+            const uint16_t *bl = drop < LAM ? bh + LAM * D : bh + XR * D;
+            phif[f] = bf_lo(*bh) + bf_lo(*bl);
+            vf[f] = drop < LAM ? ldf(sp_v, (size_t)drop * DH + f) : pvf[f];
         }
         __syncthreads();
         // the leaving pair takes the freed slot (in-place compaction)
@@ -403,116 +535,126 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
             else if (tid < 32) reinterpret_cast<uint4 *>(sp_v + (size_t)drop * DH)[tid - 16] = reinterpret_cast<const uint4 *>(pvb)[tid - 16];
             else if (tid == 32) sp_idx[drop] = pidx;
         }
-        // fold: H += phi_f v_f^T (written back once), s += phi_f
-#pragma unroll 4
-        for (int r = 0; r < (D * DH / 4) / 256; r++) {
-            const int idx4 = tid + 256 * r, f = idx4 >> 5, c = (idx4 & 31) << 2;
-            float4 hv = *reinterpret_cast<const float4 *>(&Hs[f * DH + (c ^ (((f >> 2) & 1) << 4))]);
-            const float pf = phif[f];
-            hv.x = fmaf(pf, vf[c], hv.x); hv.y = fmaf(pf, vf[c + 1], hv.y);
-            hv.z = fmaf(pf, vf[c + 2], hv.z); hv.w = fmaf(pf, vf[c + 3], hv.w);
-            reinterpret_cast<float4 *>(Hg)[idx4] = hv;
-        }
+        // fold: H^T += v_f phi_f^T on the fp32 registers, written back once; s += phi_f
+#define LOLA_HFOLD(ct, ks, hf) { const float vc = vf[32 * w + 16 * ct + r16]; \
+            const float4 pf = *reinterpret_cast<const float4 *>(&phif[32 * ks + 16 * hf + 4 * g4]); \
+            hreg##ct##ks##hf.x = fmaf(pf.x, vc, hreg##ct##ks##hf.x); hreg##ct##ks##hf.y = fmaf(pf.y, vc, hreg##ct##ks##hf.y); \
+            hreg##ct##ks##hf.z = fmaf(pf.z, vc, hreg##ct##ks##hf.z); hreg##ct##ks##hf.w = fmaf(pf.w, vc, hreg##ct##ks##hf.w); \
+            *reinterpret_cast<float4 *>(Hg + LOLA_HADDR(ct, ks, hf)) = hreg##ct##ks##hf; }
+        LOLA_HREP(LOLA_HFOLD)
+#undef LOLA_HFOLD
         if (tid < D) sg[tid] = s_l[tid] + phif[tid];
+        // phi(q) . phi_f for the rank-1 correction of the linear read-out
         for (int r = w; r < G; r += 4) {
-            float dq = wave_sum(phiX[r + 1][lane] * phif[lane] + phiX[r + 1][lane + 64] * phif[lane + 64]);
-            if (lane == 0) dotqf[r] = dq;
+            float acc = 0.f;
+#pragma unroll
+            for (int half = 0; half < 2; half++) {
+                const int f = half * M + lane, row = r + 1;
+                const int addr = row * D + (((((f >> 5) << 2) | ((f >> 2) & 3)) ^ row) << 3) + (((f >> 4) & 1) << 2) + (f & 3);
+                acc = fmaf(bf_lo(PX[addr]) + bf_lo(PX[XR * D + addr]), phif[f], acc);
+            }
+            acc = wsum(acc);
+            if (lane == 0) dotqf[r] = acc;
         }
-    } else if (popped) {
+    } else {
+        load_values();
+    }
+#undef LOLA_HDECL
+#undef LOLA_HLOAD
+#undef LOLA_HADDR
+#undef LOLA_HREP
+    if (!steady && popped) {
         // cache not full yet: the leaving pair is appended, nothing is scored (spc < LAM)
         if (tid < 16) reinterpret_cast<uint4 *>(sp_k + (size_t)spc * DH)[tid] = reinterpret_cast<const uint4 *>(pkb)[tid];
         else if (tid < 32) reinterpret_cast<uint4 *>(sp_v + (size_t)spc * DH)[tid - 16] = reinterpret_cast<const uint4 *>(pvb)[tid - 16];
         else if (tid == 32) { sp_idx[spc] = pidx; a.st.sp_count[si] = spc + 1; }
     }
-    __syncthreads();
+    LOLA_STAMP(6);
 
-    // ---- stage 4: softmax weights (one query per wavefront), m = max(0, max logit)
+    // ---- stage 4: value rows into LDS (the feature tile is no longer needed): [key][c], key order = logit order; rows
+    // past the last key are zero.  The cached value row of the dropped slot may be mid-overwrite: its weight is 0.
+#pragma unroll
+    for (int it = 0; it < NVIT; it++) {
+        const int o = tid + 256 * it, key = o >> 4, c8 = o & 15;
+        uint32_t *dst = reinterpret_cast<uint32_t *>(Vl + key * VLS + 8 * c8);
+        dst[0] = vst[it].x; dst[1] = vst[it].y; dst[2] = vst[it].z; dst[3] = vst[it].w;
+    }
+    // softmax weights (one query per wavefront), m = max(0, max logit); written as bf16 high + low parts
     for (int r = w; r < G; r += 4) {
+        float l[(KPAD + 63) / 64];
         float mx = 0.f;
-        for (int key = lane; key < NKEY; key += WAVE) {
-            bool ok;
+#pragma unroll
+        for (int x = 0; x < (KPAD + 63) / 64; x++) {
+            const int key = lane + 64 * x;
+            bool ok = false;
             if (key < LAM) ok = key < spc && key != drop;
             else if (key == KP) ok = popped && drop != LAM;
-            else ok = (key - KW) < wn;
-            float l = ok ? lg[r][key] : -INFINITY;
-            lg[r][key] = l;
-            mx = fmaxf(mx, l);
+            else if (key < NKEY) ok = (key - KW) < wn;
+            l[x] = ok ? lg[r][key] : -INFINITY;
+            mx = fmaxf(mx, l[x]);
         }
-        mx = wave_max(mx);
+        mx = wmax(mx);
         float sum = 0.f;
-        for (int key = lane; key < NKEY; key += WAVE) {
-            float p = __expf(lg[r][key] - mx);
-            lg[r][key] = p;
+#pragma unroll
+        for (int x = 0; x < (KPAD + 63) / 64; x++) {
+            const int key = lane + 64 * x;
+            const float p = fexp2((l[x] - mx) * LOG2E);
             sum += p;
+            if (key < KPAD) {
+                const __bf16 ph = (__bf16)p;
+                Ph[r * KPAD + key] = __builtin_bit_cast(uint16_t, ph);
+                Pl[r * KPAD + key] = __builtin_bit_cast(uint16_t, (__bf16)(p - (float)ph));
+            }
         }
-        sum = wave_sum(sum);
-        if (lane == 0) { psum_s[r] = sum; elin_s[r] = __expf(-mx); }
+        sum = wsum(sum);
+        if (lane == 0) { psum_s[r] = sum; elin_s[r] = fexp2(-mx * LOG2E); }
     }
     __syncthreads();
+    LOLA_STAMP(7);
 
-    // ---- stage 5: sum_i p_i v_i on the vector ALUs: thread (column group cg, row group rg), rows rg + 16 it
-    float accv[G][8];
-#pragma unroll
-    for (int r = 0; r < G; r++)
-#pragma unroll
-        for (int x = 0; x < 8; x++) accv[r][x] = 0.f;
+    // ---- stage 5: out[q][c] = sum_key p[q][key] v[key][c] on MFMA: A = weights (rows = queries), B = staged values
+    // (column c, k = key); each wavefront owns 32 output columns
     {
-        const int cg = tid & 15, rg = tid >> 4;
-        for (int key = rg; key < NKEY; key += 16) {
-            float p[G];
-            bool any = false;
+        f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
-            for (int r = 0; r < G; r++) { p[r] = lg[r][key]; any |= p[r] != 0.f; }
-            if (!any) continue;
-            float vals[8];
-            if (key == KP) {
-#pragma unroll
-                for (int x = 0; x < 8; x++) vals[x] = pvf[8 * cg + x];
-            } else {
-                const bf16_t *src;
-                if (key < LAM) src = sp_v + (size_t)key * DH;
-                else { const int row = key - KW; src = row == slot ? vnew : win_v + (size_t)row * DH; }
-                const uint4 u = reinterpret_cast<const uint4 *>(src)[cg];
-                vals[0] = __uint_as_float(u.x << 16); vals[1] = __uint_as_float(u.x & 0xFFFF0000u);
-                vals[2] = __uint_as_float(u.y << 16); vals[3] = __uint_as_float(u.y & 0xFFFF0000u);
-                vals[4] = __uint_as_float(u.z << 16); vals[5] = __uint_as_float(u.z & 0xFFFF0000u);
-                vals[6] = __uint_as_float(u.w << 16); vals[7] = __uint_as_float(u.w & 0xFFFF0000u);
+        for (int ks = 0; ks < NKS; ks++) {
+            bf16x8 Aph = zero_bf16x8(), Apl = zero_bf16x8();
+            if (r16 < G) {
+                Aph = as_bf16x8(*reinterpret_cast<const uint4 *>(&Ph[r16 * KPAD + 32 * ks + 8 * g4]));
+                Apl = as_bf16x8(*reinterpret_cast<const uint4 *>(&Pl[r16 * KPAD + 32 * ks + 8 * g4]));
             }
 #pragma unroll
-            for (int r = 0; r < G; r++)
+            for (int nt = 0; nt < 2; nt++) {
+                const int c = 16 * (2 * w + nt) + r16;
+                bf16x8 Bv;
 #pragma unroll
-                for (int x = 0; x < 8; x++) accv[r][x] = fmaf(p[r], vals[x], accv[r][x]);
+                for (int e = 0; e < 8; e++) Bv[e] = __builtin_bit_cast(__bf16, Vl[(32 * ks + 8 * g4 + e) * VLS + c]);
+                acc[nt] = mfma16(Aph, Bv, acc[nt]);
+                acc[nt] = mfma16(Apl, Bv, acc[nt]);
+            }
         }
-    }
-    // reduce over the four row groups of a wavefront, then over wavefronts through LDS (reusing the H tile)
+        if (g4 == 0) {
 #pragma unroll
-    for (int r = 0; r < G; r++)
+            for (int nt = 0; nt < 2; nt++) {
+                const int c = 16 * (2 * w + nt) + r16;
 #pragma unroll
-        for (int x = 0; x < 8; x++) {
-            float t = accv[r][x];
-            t += __shfl_xor(t, 16, WAVE); t += __shfl_xor(t, 32, WAVE);
-            accv[r][x] = t;
+                for (int r = 0; r < G; r++) {
+                    float num = acc[nt][r], den = psum_s[r];
+                    if (steady) {
+                        const float el = elin_s[r];
+                        num = fmaf(el, fmaf(dotqf[r], vf[c], lin[r][c]), num);
+                        den = fmaf(el, denq[r] + dotqf[r], den);
+                    }
+                    stf(a.out, ((size_t)b * a.Hq + (size_t)h * G + r) * DH + c, num / den);
+                }
+            }
         }
-    float *part = Hs;   // [4 wavefronts][G][DH]
-    if (g4 == 0) {
-#pragma unroll
-        for (int r = 0; r < G; r++)
-#pragma unroll
-            for (int x = 0; x < 8; x++) part[(w * G + r) * DH + 8 * r16 + x] = accv[r][x];
-    }
-    __syncthreads();
-    for (int o = tid; o < G * DH; o += 256) {
-        const int r = o / DH, c = o - r * DH;
-        float num = part[(0 * G + r) * DH + c] + part[(1 * G + r) * DH + c] + part[(2 * G + r) * DH + c] + part[(3 * G + r) * DH + c];
-        float den = psum_s[r];
-        if (steady) {
-            const float el = elin_s[r];
-            num = fmaf(el, fmaf(dotqf[r], vf[c], lin[r][c]), num);
-            den = fmaf(el, denq[r] + dotqf[r], den);
-        }
-        stf(a.out, ((size_t)b * a.Hq + (size_t)h * G + r) * DH + c, num / den);
     }
     if (tid == 0) a.st.n_tokens[si] = tok + 1;
+    LOLA_STAMP(8);
+#ifdef LOLA_TIMING
+    if (threadIdx.x == 0) lola_timing[blockIdx.x * 16 + 14] = clock64();
+#endif
 }
 
 }  // namespace fast

@@ -37,7 +37,7 @@ __device__ __forceinline__ float block_max(float v, float *red) {
     return t;
 }
 
-// phi of R rows.  xs [R][d] (LDS, fp32 copies of the stored vectors), W [d][m] (global), result
+// phi of R rows.  xs [R][d] (LDS, fp32 copies of the stored vectors), W [m][d] (global, row j = w_j), result
 // ph [R][D] (LDS).  Workgroup-wide; ends with a barrier.
 template <typename T>
 __device__ void phi_rows(const Dims &dm, const T *W, const float *xs, float *ph, int R) {
@@ -46,7 +46,7 @@ __device__ void phi_rows(const Dims &dm, const T *W, const float *xs, float *ph,
         int r = p / m, j = p - r * m;
         const float *x = xs + r * d;
         float z = 0.f;
-        for (int i = 0; i < d; i++) z = fmaf(ldf(W, (size_t)i * m + j), x[i], z);
+        for (int i = 0; i < d; i++) z = fmaf(ldf(W, (size_t)j * d + i), x[i], z);
         ph[r * D + j] = z;
     }
     __syncthreads();
@@ -88,7 +88,7 @@ __device__ void phi_rows(const Dims &dm, const T *W, const float *xs, float *ph,
     __syncthreads();
 }
 
-// Self-recall error of R pairs against (H, s): ph [R][D], vs [R][d] in LDS; err [R][d], den [R] LDS
+// Self-recall error of R pairs against (H, s), H stored transposed [d][D]: ph [R][D], vs [R][d] in LDS; err [R][d], den [R] LDS
 // scratch; score_out[r] = || ph_r^T H / ph_r^T s - v_r ||_2 (recall = 0 while ph_r^T s == 0).
 __device__ void score_rows(const Dims &dm, const float *H, const float *s, const float *ph, const float *vs,
                            float *err, float *den, float *score_out, int R) {
@@ -105,7 +105,7 @@ __device__ void score_rows(const Dims &dm, const float *H, const float *s, const
     for (int r = rg; r < R; r += nrg) {
         const float *p = ph + r * D;
         float acc = 0.f;
-        for (int f = 0; f < D; f++) acc = fmaf(p[f], H[(size_t)f * d + c], acc);
+        for (int f = 0; f < D; f++) acc = fmaf(p[f], H[(size_t)c * D + f], acc);
         float dn = den[r];
         float pred = dn > 0.f ? acc / dn : 0.f;
         float e = pred - vs[r * d + c];
@@ -236,7 +236,7 @@ __global__ __launch_bounds__(NT) void decode_kernel(DecodeArgs<T> a) {
             __syncthreads();
             phi_rows(dm, Wk, xs, ph, 1);
             for (int idx = tid; idx < D * d; idx += NT) {
-                int f = idx / d, c = idx - f * d;
+                int c = idx / D, f = idx - c * D;
                 H[idx] = fmaf(ph[f], vs[c], H[idx]);
             }
             for (int f = tid; f < D; f += NT) s[f] += ph[f];
@@ -290,7 +290,7 @@ __global__ __launch_bounds__(NT) void decode_kernel(DecodeArgs<T> a) {
             num = fmaf(pw[i], ldf(vr, c), num);
         }
         float lin = 0.f;
-        for (int f = part; f < D; f += nparts) lin = fmaf(ph[f], H[(size_t)f * d + c], lin);
+        for (int f = part; f < D; f += nparts) lin = fmaf(ph[f], H[(size_t)c * D + f], lin);
         num = fmaf(elin, lin, num);
         err[part * d + c] = num;
         __syncthreads();
@@ -476,7 +476,7 @@ __global__ __launch_bounds__(NT) void scan_kernel(PrefillArgs<T> a) {
             const int nf = sh_nf, ne = sh_ne;
             // fold: H += sum phi(k) v^T, s += sum phi(k) over the pairs that do not stay
             for (int idx = tid; idx < D * d; idx += NT) {
-                int f = idx / d, c = idx - f * d;
+                int c = idx / D, f = idx - c * D;
                 float acc = 0.f;
                 for (int x = 0; x < nf; x++) {
                     int e = flist[x];
@@ -606,7 +606,7 @@ __global__ __launch_bounds__(NT) void attend_kernel(PrefillArgs<T> a) {
             }
             float lin = 0.f;
             const float *pq = phq + qi * D;
-            for (int f = 0; f < D; f++) lin = fmaf(pq[f], Hj[(size_t)f * d + c], lin);
+            for (int f = 0; f < D; f++) lin = fmaf(pq[f], Hj[(size_t)c * D + f], lin);
             const float elin = expf(-rmax[qi]);
             stf(oh, (size_t)(i0 + qi) * d + c, fmaf(elin, lin, num) / (rsum[qi] + elin * rlin[qi]));
         }

@@ -6,6 +6,18 @@
 
 using namespace lola;
 
+#ifdef LOLA_TIMING
+// development build only: per-workgroup phase time stamps of the fused decode kernel
+__device__ long long lola::fast::lola_timing[4096 * 16];
+__device__ long long lola::fast::lola_stagger_ticks = 0;
+extern "C" int lola_debug_set_stagger(long long ticks) {
+    return (int)hipMemcpyToSymbol(HIP_SYMBOL(lola::fast::lola_stagger_ticks), &ticks, sizeof(ticks));
+}
+extern "C" int lola_debug_read_timing(long long *host, size_t n) {
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(lola::fast::lola_timing), n * sizeof(long long));
+}
+#endif
+
 namespace {
 
 constexpr size_t ALIGN = 256;

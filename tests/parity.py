@@ -31,6 +31,11 @@ def to_dev(x: np.ndarray, dtype: str) -> torch.Tensor:
     return torch.from_numpy(x).to(DEV)
 
 
+def w_to_dev(W: np.ndarray, dtype: str) -> torch.Tensor:
+    """[H, d, m] (as drawn and as the oracle reads it) -> the library's [H, m, d] (row j = w_j)."""
+    return to_dev(np.ascontiguousarray(W.transpose(0, 2, 1)), dtype)
+
+
 def row_rel_err(y_gpu: np.ndarray, y_or: np.ndarray) -> np.ndarray:
     num = np.abs(y_gpu.astype(np.float64) - y_or).max(axis=-1)
     den = np.maximum(np.abs(y_or).max(axis=-1), 1e-6)
@@ -72,6 +77,7 @@ def gpu_state_np(layer: lb.LolaLayer, bsel=None, hsel=None) -> dict:
         if hsel is not None:
             t = t[:, list(hsel)]
         out[n] = (t.float() if t.dtype == torch.bfloat16 else t).cpu().numpy()
+    out["H"] = np.ascontiguousarray(out["H"].transpose(0, 1, 3, 2))   # the library stores H^T [d, D]
     return out
 
 
@@ -120,7 +126,7 @@ def prefill_parity(sh: wl.Shape, q, k, v, Wq, Wk, layer=None, oracle=None, with_
     layer = layer or make_layer(sh, out_dtype=out_dtype, B=k.shape[0], **(layer_kw or {}))
     dq = to_dev(q, sh.dtype) if with_outputs else None
     dk, dv = to_dev(k, sh.dtype), to_dev(v, sh.dtype)
-    dWq, dWk = to_dev(Wq, sh.dtype), to_dev(Wk, sh.dtype)
+    dWq, dWk = w_to_dev(Wq, sh.dtype), w_to_dev(Wk, sh.dtype)
     out, trace = layer.prefill(dq, dk, dv, dWq, dWk, trace=True, workspace_limit=workspace_limit)
     torch.cuda.synchronize()
     oq, ok_, ov, oWq, oWk, bs, hs, hq = subset_inputs(sh, q if with_outputs else None, k, v, Wq, Wk, bsel, hsel)
@@ -149,7 +155,7 @@ def decode_parity(sh: wl.Shape, layer, oracle, qd, kd, vd, Wq, Wk, out_dtype="f3
     bs = list(bsel) if bsel is not None else list(range(kd.shape[1]))
     hs = list(hsel) if hsel is not None else list(range(sh.Hkv))
     hq = [h * sh.g + r for h in hs for r in range(sh.g)]
-    dWq, dWk = to_dev(Wq, sh.dtype), to_dev(Wk, sh.dtype)
+    dWq, dWk = w_to_dev(Wq, sh.dtype), w_to_dev(Wk, sh.dtype)
     dq, dk, dv = to_dev(qd, sh.dtype), to_dev(kd, sh.dtype), to_dev(vd, sh.dtype)
     oWq, oWk = np.ascontiguousarray(Wq[hq]), np.ascontiguousarray(Wk[hs])
     worst = 0.0

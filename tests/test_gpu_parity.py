@@ -130,7 +130,7 @@ def test_resume_and_multipass_workspace():
         say("resume part", i, rep)
     # one call over everything gives the same memories
     one = P.make_layer(sh)
-    one.prefill(P.to_dev(q, "bf16"), P.to_dev(k, "bf16"), P.to_dev(v, "bf16"), P.to_dev(Wq, "bf16"), P.to_dev(Wk, "bf16"))
+    one.prefill(P.to_dev(q, "bf16"), P.to_dev(k, "bf16"), P.to_dev(v, "bf16"), P.w_to_dev(Wq, "bf16"), P.w_to_dev(Wk, "bf16"))
     torch.cuda.synchronize()
     assert torch.equal(P.torch.sort(one.sp_idx, -1).values, torch.sort(layer.sp_idx, -1).values)
     assert torch.allclose(one.H, layer.H, rtol=1e-5, atol=1e-6)
@@ -151,7 +151,7 @@ def test_run_to_run_determinism():
     outs = []
     for _ in range(2):
         layer = P.make_layer(sh)
-        out = layer.prefill(P.to_dev(q, sh.dtype), P.to_dev(k, sh.dtype), P.to_dev(v, sh.dtype), P.to_dev(Wq, sh.dtype), P.to_dev(Wk, sh.dtype))
+        out = layer.prefill(P.to_dev(q, sh.dtype), P.to_dev(k, sh.dtype), P.to_dev(v, sh.dtype), P.w_to_dev(Wq, sh.dtype), P.w_to_dev(Wk, sh.dtype))
         torch.cuda.synchronize()
         outs.append((out.clone(), layer.H.clone(), layer.sp_idx.clone()))
     for a, b in zip(*outs):
@@ -202,7 +202,7 @@ def test_config4_decode_batch64_full():
     Wq, Wk = wl.weights(sh)
     layer = P.make_layer(sh)
     o = orc.Oracle(len(bsel), sh.Hq, sh.Hkv, sh.d, sh.D, sh.eta, sh.lam, sh.C)
-    dWk = P.to_dev(Wk, sh.dtype)
+    dWk = P.w_to_dev(Wk, sh.dtype)
     qd = np.empty((n_steps, sh.B, sh.Hq, sh.d), np.float32)
     kd = np.empty((n_steps, sh.B, sh.Hkv, sh.d), np.float32)
     vd = np.empty((n_steps, sh.B, sh.Hkv, sh.d), np.float32)
