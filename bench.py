@@ -71,6 +71,8 @@ def main():
     ap.add_argument("--skip-prefill", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one 256 MiB device copy (known traffic, calibrates the HBM byte counters under rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the layer shards over (batch, kv head) with no exchange, and this "
@@ -164,6 +166,12 @@ def main():
     achieved = per_launch / (launch_us * 1e-6) / 1e9
     log(f"[decode] {K} steps: wall {t_wall * 1e3:.1f} ms, gpu {gpu_ms:.1f} ms, {launch_us:.2f} us/launch, "
         f"{value / 1e6:.3f} M tokens/s/layer, {achieved:.0f} GB/s algorithmic")
+    if args.calib_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     traffic = None
     tfile = os.path.join(ROOT, "profiles", "decode_8b_b64_hbm_traffic.md")
     if os.path.exists(tfile):
@@ -223,9 +231,14 @@ def main():
                 wtok = np.arange(max(0, ntk - sh.eta), ntk)
                 o.set_stream(b * sh.Hkv + h, hs["H"][b, h].T, hs["s"][b, h], hs["sp_k"][b, h, :cnt], hs["sp_v"][b, h, :cnt],
                              hs["sp_idx"][b, h, :cnt], hs["win_k"][b, h][wtok % sh.eta], hs["win_v"][b, h][wtok % sh.eta], wtok)
-        run = lambda t: o.decode_step(qd[t, :n_seq], kd[t, :n_seq], vd[t, :n_seq], Wq, Wk)
+        # the sample needs more steps than the GPU loop generated: draw a longer decode tail for these sequences
+        n_cpu = 2048
+        shc = wl.scaled(4, T=64, n_decode=n_cpu)
+        tails = [wl.decode_batch_sequence(shc, 5000 + b) for b in range(n_seq)]
+        cq = np.stack([t[2] for t in tails], 1); ck = np.stack([t[3] for t in tails], 1); cv = np.stack([t[4] for t in tails], 1)
+        run = lambda t: o.decode_step(cq[t], ck[t], cv[t], Wq, Wk)
         t1 = time.perf_counter(); run(0); run(1); per = (time.perf_counter() - t1) / 2
-        n_steps = int(max(2, min(n_tok - 2, args.cpu_seconds / max(per, 1e-6))))
+        n_steps = int(max(2, min(n_cpu - 2, args.cpu_seconds / max(per, 1e-6))))
         t1 = time.perf_counter()
         for t in range(2, 2 + n_steps):
             run(t)
