@@ -330,6 +330,7 @@ struct PrefillArgs {
     int32_t *sel_trace;       // [B*Hkv][n_chunks][lam] or NULL
     int R;                    // rows per scoring tile
     int QT;                   // queries per attend tile
+    int snap_split;           // 1: H snapshots are written as bf16 high + low parts in MFMA operand order (D = d = 128)
 };
 
 template <typename T>
@@ -411,7 +412,21 @@ __global__ __launch_bounds__(NT) void scan_kernel(PrefillArgs<T> a) {
             const size_t sj = (size_t)si * a.S + (j - a.j0);
             float *sH = a.snapH + sj * D * d, *sS = a.snapS + sj * D;
             int32_t *sG = a.snapG + sj * lam;
-            for (int idx = tid; idx < D * d; idx += NT) sH[idx] = H[idx];
+            if (a.snap_split) {
+                // [part][c][16-byte chunk][element]: feature f sits in chunk (f/32)*4 + (f/4)%4, element 4*((f/16)%2) + f%4
+                uint16_t *s16 = reinterpret_cast<uint16_t *>(sH);
+                for (int idx = tid; idx < D * d; idx += NT) {
+                    const int c = idx / D, f = idx - c * D;
+                    const float x = H[idx];
+                    const uint16_t hi = f32_to_bf16_bits(x);
+                    const float r = x - __uint_as_float(((uint32_t)hi) << 16);
+                    const int pos = c * D + (((((f >> 5) << 2) | ((f >> 2) & 3))) << 3) + ((((f >> 4) & 1) << 2) | (f & 3));
+                    s16[pos] = hi;
+                    s16[D * d + pos] = f32_to_bf16_bits(r);
+                }
+            } else {
+                for (int idx = tid; idx < D * d; idx += NT) sH[idx] = H[idx];
+            }
             for (int f = tid; f < D; f += NT) sS[f] = s[f];
             for (int sl = tid; sl < lam; sl += NT) sG[sl] = sl < spc ? sp_row[sl] : -1;
         }

@@ -1,8 +1,10 @@
 // C ABI of the LoLA layer library (see include/lola.h): host-side validation, workspace carving
 // and kernel dispatch.  Nothing here allocates or synchronises.
 #include "../../include/lola.h"
+#include <type_traits>
 #include "generic_kernels.h"
 #include "decode_mfma.h"
+#include "prefill_mfma.h"
 
 using namespace lola;
 
@@ -118,6 +120,13 @@ bool fast_decode_ok(const lola_config *c) {
            (c->sparse_budget == 128 || c->sparse_budget == 64) && c->n_q_heads / c->n_kv_heads == 4;
 }
 
+// The MFMA output kernel of the prefill covers the same head shape with chunk = window = 64.
+bool fast_attend_ok(const lola_config *c) {
+    return c->dtype == LOLA_BF16 && c->head_dim == 128 && c->feat_dim == 128 && c->window == 64 && c->chunk == 64 &&
+           (c->sparse_budget == 64 || c->sparse_budget == 128 || c->sparse_budget == 256) &&
+           c->n_q_heads / c->n_kv_heads == 4;
+}
+
 template <int LAM, typename TO>
 lola_status launch_fast_decode(const lola_config *c, const lola_state *st, const void *q, const void *k, const void *v,
                                const void *Wq, const void *Wk, void *out, hipStream_t stream) {
@@ -198,6 +207,8 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
     const size_t scan_fixed = scan_fixed_floats(a.dm);
     a.R = score_tile_rows(a.dm, scan_fixed);
     a.QT = attend_tile_queries(a.dm);
+    const bool fast_att = a.want_out && fast_attend_ok(c);
+    a.snap_split = fast_att ? 1 : 0;
     if (a.R <= 0 || (a.want_out && a.QT <= 0)) return LOLA_ERR_UNSUPPORTED;
     const size_t lds_scan = 4 * (scan_fixed + (size_t)a.R * (3 * d + D + 1));
     const size_t lds_att = 4 * ((size_t)a.QT * (d + D + (lam + a.dm.eta + a.dm.C) + 3));
@@ -212,6 +223,17 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
         LAUNCH_CHECK();
         if (a.want_out) {
             dim3 ga((unsigned)(a.j1 - a.j0), (unsigned)a.dm.Hq, (unsigned)a.dm.B);
+            if constexpr (std::is_same<T, bf16_t>::value) {
+                if (fast_att) {
+                    const bool f32o = c->out_dtype == LOLA_F32;
+#define LOLA_ATT(LAMV) do { if (f32o) hipLaunchKernelGGL((fast::attend_fast_kernel<LAMV, float>), ga, dim3(256), 0, stream, a); \
+                            else hipLaunchKernelGGL((fast::attend_fast_kernel<LAMV, bf16_t>), ga, dim3(256), 0, stream, a); } while (0)
+                    if (c->sparse_budget == 64) LOLA_ATT(64); else if (c->sparse_budget == 128) LOLA_ATT(128); else LOLA_ATT(256);
+#undef LOLA_ATT
+                    LAUNCH_CHECK();
+                    continue;
+                }
+            }
             if (c->out_dtype == LOLA_F32) hipLaunchKernelGGL((generic::attend_kernel<T, float>), ga, block, lds_att, stream, a);
             else hipLaunchKernelGGL((generic::attend_kernel<T, bf16_t>), ga, block, lds_att, stream, a);
             LAUNCH_CHECK();
@@ -317,6 +339,7 @@ const char *lola_status_str(lola_status s) {
 const char *lola_kernel_path(const lola_config *c, int32_t which) {
     if (check_config(c) != LOLA_OK) return "invalid";
     if (which == 1 && fast_decode_ok(c)) return "mfma";
+    if (which == 0 && fast_attend_ok(c)) return "generic scan + mfma attend";
     return "generic";
 }
 
