@@ -372,14 +372,14 @@ __global__ __launch_bounds__(NT) void finalize_kernel(PrefillArgs<T> a) {
     if (tid == 0) a.st.n_tokens[si] = a0 + Tn;
 }
 
-// Sequential evolution of one stream's memories over the chunks [j0, j1).
+// One chunk of the sequential evolution of a stream's memories, all state in global memory (H^T, s, cache) except the
+// sparse-cache fill count `spc`, which the caller carries.  Workgroup-wide (NT threads); `smem` is scratch LDS.
 template <typename T>
-__global__ __launch_bounds__(NT) void scan_kernel(PrefillArgs<T> a) {
-    extern __shared__ float smem[];
+__device__ void scan_chunk(const PrefillArgs<T> &a, const int si, const int j, int &spc, float *smem) {
     const Dims &dm = a.dm;
     const int tid = threadIdx.x, d = dm.d, D = dm.D, m = dm.m, eta = dm.eta, lam = dm.lam, C = dm.C, R = a.R;
     const int P = lam + eta, nEmax = lam + C;
-    const int si = blockIdx.x, h = si % dm.Hkv;
+    const int h = si % dm.Hkv;
     float *xs = smem;                   // [R][d]
     float *ph = xs + R * d;             // [R][D]
     float *vs = ph + R * D;             // [R][d]
@@ -403,9 +403,9 @@ __global__ __launch_bounds__(NT) void scan_kernel(PrefillArgs<T> a) {
     const T *pK = a.prefK + (size_t)si * P * d, *pV = a.prefV + (size_t)si * P * d;
     const T *kc = a.k + (size_t)si * a.T_tokens * d, *vc = a.v + (size_t)si * a.T_tokens * d;
     const int64_t a0 = a.st.n_tokens[si];
-    int spc = a.st.sp_count[si];
 
-    for (int j = a.j0; j < a.j1; j++) {
+    {
+
         const int cl = min(C, a.T_tokens - j * C);
         const int64_t aj = a0 + (int64_t)j * C;
         if (a.want_out) {   // snapshot of the memories the chunk's queries read
@@ -530,7 +530,16 @@ __global__ __launch_bounds__(NT) void scan_kernel(PrefillArgs<T> a) {
         }
         __syncthreads();
     }
-    if (tid == 0) a.st.sp_count[si] = spc;
+}
+
+// Sequential evolution of one stream's memories over the chunks [j0, j1).
+template <typename T>
+__global__ __launch_bounds__(NT) void scan_kernel(PrefillArgs<T> a) {
+    extern __shared__ float smem[];
+    const int si = blockIdx.x;
+    int spc = a.st.sp_count[si];
+    for (int j = a.j0; j < a.j1; j++) scan_chunk(a, si, j, spc, smem);
+    if (threadIdx.x == 0) a.st.sp_count[si] = spc;
 }
 
 // Outputs of one chunk of one query head from the snapshot taken at the chunk's entry.

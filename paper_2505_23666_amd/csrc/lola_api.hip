@@ -209,6 +209,7 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
     a.QT = attend_tile_queries(a.dm);
     const bool fast_att = a.want_out && fast_attend_ok(c);
     a.snap_split = fast_att ? 1 : 0;
+    if (fast_attend_ok(c) && a.R > 32) a.R = 32;   // the fused scan lends the generic per-chunk routine the LDS of its phi tile
     if (a.R <= 0 || (a.want_out && a.QT <= 0)) return LOLA_ERR_UNSUPPORTED;
     const size_t lds_scan = 4 * (scan_fixed + (size_t)a.R * (3 * d + D + 1));
     const size_t lds_att = 4 * ((size_t)a.QT * (d + D + (lam + a.dm.eta + a.dm.C) + 3));
@@ -219,7 +220,16 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
     for (int j0 = 0; j0 < a.n_chunks; j0 += S) {
         a.j0 = j0;
         a.j1 = j0 + S < a.n_chunks ? j0 + S : a.n_chunks;
-        hipLaunchKernelGGL((generic::scan_kernel<T>), gs, block, lds_scan, stream, a);
+        bool scanned = false;
+        if constexpr (std::is_same<T, bf16_t>::value) {
+            if (fast_attend_ok(c)) {   // same shape conditions as the output kernel
+                if (c->sparse_budget == 64) hipLaunchKernelGGL((fast::scan_fast_kernel<64>), gs, dim3(256), 0, stream, a);
+                else if (c->sparse_budget == 128) hipLaunchKernelGGL((fast::scan_fast_kernel<128>), gs, dim3(256), 0, stream, a);
+                else hipLaunchKernelGGL((fast::scan_fast_kernel<256>), gs, dim3(256), 0, stream, a);
+                scanned = true;
+            }
+        }
+        if (!scanned) hipLaunchKernelGGL((generic::scan_kernel<T>), gs, block, lds_scan, stream, a);
         LAUNCH_CHECK();
         if (a.want_out) {
             dim3 ga((unsigned)(a.j1 - a.j0), (unsigned)a.dm.Hq, (unsigned)a.dm.B);
@@ -339,7 +349,7 @@ const char *lola_status_str(lola_status s) {
 const char *lola_kernel_path(const lola_config *c, int32_t which) {
     if (check_config(c) != LOLA_OK) return "invalid";
     if (which == 1 && fast_decode_ok(c)) return "mfma";
-    if (which == 0 && fast_attend_ok(c)) return "generic scan + mfma attend";
+    if (which == 0 && fast_attend_ok(c)) return "mfma";
     return "generic";
 }
 

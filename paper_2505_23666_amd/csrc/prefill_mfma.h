@@ -220,5 +220,356 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
     }
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// Sequential state evolution of the prefill (paper Sec. 3 "Chunkwise Inference": after each chunk the
+// oldest chunk leaves the window; it and the sparse cache are scored by self-recall error, the top
+// lambda stay, the rest are folded) for the 8B head shape: one workgroup of four wavefronts per
+// (sequence, kv head), persistent over the chunks of a pass.
+//
+// H^T lives in registers for the whole pass (wavefront w owns rows 32w .. 32w+31 as fp32, re-split
+// into bf16 high + low MFMA operands once per chunk); s lives in LDS.  Per regular chunk (a full
+// chunk, a full window behind it, a full cache):
+//   1. snapshot of H^T (operand order, high/low parts), s and the cache's row list for the output kernel;
+//   2. phi of the lambda + 64 candidates (tiles shared out over the wavefronts) -> LDS and a global
+//      scratch copy; recall GEMM P^T = H^T Phi^T and squared error against the candidates' values;
+//   3. rank by counting (score descending, token index ascending), the first lambda stay;
+//   4. fold of the 64 others on MFMA: H[f][c] += sum_e phi_e[f] v_e[c] accumulates directly into the
+//      registers that hold H^T (its C layout is the recall GEMM's A layout), operands gathered
+//      through LDS in transposed order; s += sum_e phi_e;
+//   5. in-place compaction: the entrants' K, V rows overwrite the slots of the leavers.
+// Any other chunk (warm-up while the cache fills, the first chunks of a sequence, a ragged last chunk)
+// goes through the generic per-chunk routine on the state in global memory.
+template <int LAM>
+__global__ __launch_bounds__(256, 1) void scan_fast_kernel(generic::PrefillArgs<bf16_t> a) {
+    constexpr int DH = 128, M = 64, D = 128, C = 64, ETA = 64;
+    constexpr int P = LAM + ETA, NE = LAM + C, NTILE = NE / 16, TB = 12, RB = TB * 16;
+    __shared__ __attribute__((aligned(16))) uint16_t PB[2 * RB * D];    // phi of one batch of candidates: high parts, low parts
+    __shared__ __attribute__((aligned(16))) uint16_t PT[2 * D * C];     // phi^T of the folded pairs [part][f][e']
+    __shared__ __attribute__((aligned(16))) uint16_t VT[DH * C];        // v^T of the folded pairs [c][e']
+    __shared__ __attribute__((aligned(16))) float s_l[D];
+    __shared__ float rden_l[NE];
+    __shared__ float part[4][NE];
+    __shared__ __attribute__((aligned(16))) uint32_t score[NE];   // bit pattern of the squared error: for values >= 0 (and NaN) its integer order is a total order
+    __shared__ __attribute__((aligned(16))) int cidx[NE];
+    __shared__ int keep[NE];
+    __shared__ int flist[C], ecand[C], eslot[C];
+    static_assert(2 * RB * D * 2 >= 4 * (4 * NE + 2 * C + 8 + 32 * (3 * DH + D + 1)), "the generic per-chunk routine borrows the phi tile as scratch (tiles of <= 32 rows)");
+
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r16 = lane & 15, g4 = lane >> 4;
+    const int si = blockIdx.x, h = si % a.dm.Hkv;
+    float *Hg = a.st.H + (size_t)si * D * DH;
+    float *sg = a.st.s + (size_t)si * D;
+    bf16_t *sp_k = a.st.sp_k + (size_t)si * LAM * DH, *sp_v = a.st.sp_v + (size_t)si * LAM * DH;
+    int32_t *sp_idx = a.st.sp_idx + (size_t)si * LAM;
+    int32_t *sp_row = a.sp_row + (size_t)si * LAM;
+    uint16_t *phiE = reinterpret_cast<uint16_t *>(a.phiE + (size_t)si * NE * D);   // [e][part][128] bf16, operand order
+    const bf16_t *Wk = a.Wk + (size_t)h * M * DH;
+    const bf16_t *pK = a.prefK + (size_t)si * P * DH, *pV = a.prefV + (size_t)si * P * DH;
+    const bf16_t *kc = a.k + (size_t)si * a.T_tokens * DH, *vc = a.v + (size_t)si * a.T_tokens * DH;
+    const int64_t a0 = a.st.n_tokens[si];
+    int spc = a.st.sp_count[si];
+
+    // W_k as MFMA A operand for the whole pass
+    bf16x8 AW[4][4];
+#pragma unroll
+    for (int mt = 0; mt < 4; mt++)
+#pragma unroll
+        for (int ks = 0; ks < 4; ks++) AW[mt][ks] = ld_bf16x8(Wk + (size_t)(16 * mt + r16) * DH + 32 * ks + 8 * g4);
+
+    // H^T rows 32w + 16ct + r16, features 32ks + 16hf + 4g4 + 0..3
+#define LOLA_SREP(X) X(0, 0, 0) X(0, 0, 1) X(0, 1, 0) X(0, 1, 1) X(0, 2, 0) X(0, 2, 1) X(0, 3, 0) X(0, 3, 1) \
+                     X(1, 0, 0) X(1, 0, 1) X(1, 1, 0) X(1, 1, 1) X(1, 2, 0) X(1, 2, 1) X(1, 3, 0) X(1, 3, 1)
+#define LOLA_SADDR(ct, ks, hf) ((size_t)(32 * w + 16 * ct + r16) * D + 32 * ks + 16 * hf + 4 * g4)
+#define LOLA_SDECL(ct, ks, hf) f32x4 hreg##ct##ks##hf = {0.f, 0.f, 0.f, 0.f};
+#define LOLA_SLOAD(ct, ks, hf) hreg##ct##ks##hf = *reinterpret_cast<const f32x4 *>(Hg + LOLA_SADDR(ct, ks, hf));
+#define LOLA_SSTORE(ct, ks, hf) *reinterpret_cast<f32x4 *>(Hg + LOLA_SADDR(ct, ks, hf)) = hreg##ct##ks##hf;
+    LOLA_SREP(LOLA_SDECL)
+    bool h_in_regs = false;
+
+    for (int j = a.j0; j < a.j1; j++) {
+        const int cl = min(C, a.T_tokens - j * C);
+        const int64_t aj = a0 + (int64_t)j * C;
+        const bool regular = cl == C && aj >= ETA && spc == LAM;
+        if (!regular) {
+            if (h_in_regs) {
+                LOLA_SREP(LOLA_SSTORE)
+                if (tid < D) sg[tid] = s_l[tid];
+                h_in_regs = false;
+                __threadfence();
+                __syncthreads();
+            }
+            generic::scan_chunk(a, si, j, spc, reinterpret_cast<float *>(PB));
+            __threadfence();
+            __syncthreads();
+            continue;
+        }
+        if (!h_in_regs) {
+            LOLA_SREP(LOLA_SLOAD)
+            if (tid < D) s_l[tid] = sg[tid];
+            h_in_regs = true;
+            __syncthreads();
+        }
+        const int vrow_c = P + j * C;           // virtual row of the chunk's first token
+        // source rows of candidate e: a cache slot, or one of the 64 rows before the chunk
+        auto krow = [&](int e) -> const bf16_t * {
+            if (e < LAM) return sp_k + (size_t)e * DH;
+            const int vr = vrow_c - ETA + (e - LAM);
+            return vr < P ? pK + (size_t)vr * DH : kc + (size_t)(vr - P) * DH;
+        };
+        auto vrow = [&](int e) -> const bf16_t * {
+            if (e < LAM) return sp_v + (size_t)e * DH;
+            const int vr = vrow_c - ETA + (e - LAM);
+            return vr < P ? pV + (size_t)vr * DH : vc + (size_t)(vr - P) * DH;
+        };
+
+        // ---- 1. operands of the recall GEMM from the fp32 registers; snapshot for the output kernel
+        bf16x8 Ahi[2][4], Alo[2][4];
+#define LOLA_SSPLIT(ct, ks, hf) { const f32x4 v = hreg##ct##ks##hf; \
+            const __bf16 h0 = (__bf16)v[0], h1 = (__bf16)v[1], h2 = (__bf16)v[2], h3 = (__bf16)v[3]; \
+            Ahi[ct][ks][4 * hf] = h0; Ahi[ct][ks][4 * hf + 1] = h1; Ahi[ct][ks][4 * hf + 2] = h2; Ahi[ct][ks][4 * hf + 3] = h3; \
+            Alo[ct][ks][4 * hf] = (__bf16)(v[0] - (float)h0); Alo[ct][ks][4 * hf + 1] = (__bf16)(v[1] - (float)h1); \
+            Alo[ct][ks][4 * hf + 2] = (__bf16)(v[2] - (float)h2); Alo[ct][ks][4 * hf + 3] = (__bf16)(v[3] - (float)h3); }
+        LOLA_SREP(LOLA_SSPLIT)
+#undef LOLA_SSPLIT
+        if (a.want_out) {
+            const size_t sj = (size_t)si * a.S + (j - a.j0);
+            uint16_t *s16 = reinterpret_cast<uint16_t *>(a.snapH) + sj * (2 * D * DH);
+#pragma unroll
+            for (int ct = 0; ct < 2; ct++)
+#pragma unroll
+                for (int ks = 0; ks < 4; ks++) {
+                    const int off = (32 * w + 16 * ct + r16) * D + ((4 * ks + g4) << 3);
+                    *reinterpret_cast<uint4 *>(s16 + off) = __builtin_bit_cast(uint4, Ahi[ct][ks]);
+                    *reinterpret_cast<uint4 *>(s16 + D * DH + off) = __builtin_bit_cast(uint4, Alo[ct][ks]);
+                }
+            if (tid < D / 4) reinterpret_cast<float4 *>(a.snapS + sj * D)[tid] = reinterpret_cast<const float4 *>(s_l)[tid];
+            for (int sl = tid; sl < LAM; sl += 256) a.snapG[sj * LAM + sl] = sp_row[sl];
+        }
+
+        // ---- 2. phi of the candidates and their recall error, in batches of TB tiles
+#pragma unroll 1
+        for (int t0 = 0; t0 < NTILE; t0 += TB) {
+            const int t1 = min(NTILE, t0 + TB);
+#pragma unroll 1
+            for (int t = t0 + w; t < t1; t += 4) {
+                const int e = 16 * t + r16;
+                const bf16_t *kr = krow(e);
+                bf16x8 BK[4];
+#pragma unroll
+                for (int ks = 0; ks < 4; ks++) BK[ks] = ld_bf16x8(kr + 32 * ks + 8 * g4);
+                f32x4 zt[4];
+#pragma unroll
+                for (int mt = 0; mt < 4; mt++) {
+                    zt[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int ks = 0; ks < 4; ks++) zt[mt] = mfma16(AW[mt][ks], BK[ks], zt[mt]);
+                }
+                float pp[16], pn[16];
+                phi_from_z(zt, a.dm.phi_kind, pp, pn);
+                float dn = 0.f;
+#pragma unroll
+                for (int mt = 0; mt < 4; mt++) {
+                    const float4 sp4 = *reinterpret_cast<const float4 *>(&s_l[16 * mt + 4 * g4]);
+                    const float4 sn4 = *reinterpret_cast<const float4 *>(&s_l[M + 16 * mt + 4 * g4]);
+                    dn = fmaf(pp[4 * mt], sp4.x, dn); dn = fmaf(pp[4 * mt + 1], sp4.y, dn);
+                    dn = fmaf(pp[4 * mt + 2], sp4.z, dn); dn = fmaf(pp[4 * mt + 3], sp4.w, dn);
+                    dn = fmaf(pn[4 * mt], sn4.x, dn); dn = fmaf(pn[4 * mt + 1], sn4.y, dn);
+                    dn = fmaf(pn[4 * mt + 2], sn4.z, dn); dn = fmaf(pn[4 * mt + 3], sn4.w, dn);
+                }
+                dn = grp_sum(dn);
+                if (g4 == 0) {
+                    rden_l[e] = dn > 0.f ? 1.0f / dn : 0.f;
+                    cidx[e] = e < LAM ? sp_idx[e] : (int)(aj - ETA + (e - LAM));
+                }
+                bf16x8 hi[4], lo[4];
+                split8(&pp[0], hi[0], lo[0]); split8(&pp[8], hi[1], lo[1]);
+                split8(&pn[0], hi[2], lo[2]); split8(&pn[8], hi[3], lo[3]);
+                const int rl = e - 16 * t0;
+#pragma unroll
+                for (int ks = 0; ks < 4; ks++) {
+                    const int addr = rl * D + (((4 * ks + g4) ^ r16) << 3);
+                    *reinterpret_cast<uint4 *>(&PB[addr]) = __builtin_bit_cast(uint4, hi[ks]);
+                    *reinterpret_cast<uint4 *>(&PB[RB * D + addr]) = __builtin_bit_cast(uint4, lo[ks]);
+                    *reinterpret_cast<uint4 *>(phiE + (size_t)e * 2 * D + ((4 * ks + g4) << 3)) = __builtin_bit_cast(uint4, hi[ks]);
+                    *reinterpret_cast<uint4 *>(phiE + (size_t)e * 2 * D + D + ((4 * ks + g4) << 3)) = __builtin_bit_cast(uint4, lo[ks]);
+                }
+            }
+            __syncthreads();
+            // recall GEMM for the batch: A = this wavefront's rows of H^T, B = phi from LDS; lane (candidate r16, group g4)
+            // holds rows c = 32w + 16ct + 4 g4 + i and needs the candidate's values at those columns
+#pragma unroll 1
+            for (int t = t0; t < t1; t++) {
+                const int e = 16 * t + r16, rl = e - 16 * t0;
+                const bf16_t *vr = vrow(e);
+                uint2 vv[2];
+#pragma unroll
+                for (int ct = 0; ct < 2; ct++) vv[ct] = *reinterpret_cast<const uint2 *>(vr + 32 * w + 16 * ct + 4 * g4);
+                f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}}, acc2[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+                for (int ks = 0; ks < 4; ks++) {
+                    const int addr = rl * D + (((4 * ks + g4) ^ r16) << 3);
+                    const bf16x8 Bh = as_bf16x8(*reinterpret_cast<const uint4 *>(&PB[addr]));
+                    const bf16x8 Bl = as_bf16x8(*reinterpret_cast<const uint4 *>(&PB[RB * D + addr]));
+#pragma unroll
+                    for (int ct = 0; ct < 2; ct++) acc[ct] = mfma16(Ahi[ct][ks], Bh, acc[ct]);
+#pragma unroll
+                    for (int ct = 0; ct < 2; ct++) acc2[ct] = mfma16(Ahi[ct][ks], Bl, acc2[ct]);
+#pragma unroll
+                    for (int ct = 0; ct < 2; ct++) acc2[ct] = mfma16(Alo[ct][ks], Bh, acc2[ct]);
+                }
+                const float rd = rden_l[e];
+                float es = 0.f;
+#pragma unroll
+                for (int ct = 0; ct < 2; ct++) {
+                    const f32x4 p = acc[ct] + acc2[ct];
+                    const float e0 = fmaf(p[0], rd, -bf_lo(vv[ct].x)), e1 = fmaf(p[1], rd, -bf_hi(vv[ct].x));
+                    const float e2 = fmaf(p[2], rd, -bf_lo(vv[ct].y)), e3 = fmaf(p[3], rd, -bf_hi(vv[ct].y));
+                    es = fmaf(e0, e0, es); es = fmaf(e1, e1, es); es = fmaf(e2, e2, es); es = fmaf(e3, e3, es);
+                }
+                es = grp_sum(es);
+                if (g4 == 0) part[w][e] = es;
+            }
+            __syncthreads();
+        }
+
+        // ---- 3. rank by (score descending, token index ascending); the first LAM stay
+        for (int e = tid; e < NE; e += 256)
+            score[e] = __float_as_uint(part[0][e] + part[1][e] + part[2][e] + part[3][e]) & 0x7FFFFFFFu;
+        __syncthreads();
+        for (int e = tid; e < NE; e += 256) {
+            const uint32_t sc = score[e];
+            const int ix = cidx[e];
+            int rank = 0;
+            for (int o = 0; o < NE; o += 4) {
+                const uint4 so = *reinterpret_cast<const uint4 *>(&score[o]);
+                const int4 io = *reinterpret_cast<const int4 *>(&cidx[o]);
+                rank += (so.x > sc || (so.x == sc && io.x < ix)) ? 1 : 0;
+                rank += (so.y > sc || (so.y == sc && io.y < ix)) ? 1 : 0;
+                rank += (so.z > sc || (so.z == sc && io.z < ix)) ? 1 : 0;
+                rank += (so.w > sc || (so.w == sc && io.w < ix)) ? 1 : 0;
+            }
+            keep[e] = rank < LAM;
+        }
+        __syncthreads();
+        // lists (one wavefront, ballots): candidates to fold; entrants paired with the slots of the leavers
+        if (w == 0) {
+            int nf = 0, nen = 0, nlv = 0;
+            for (int e0 = 0; e0 < NE; e0 += 64) {
+                const int e = e0 + lane;
+                const bool kp = e < NE && keep[e];
+                const bool fo = e < NE && !kp, en = kp && e >= LAM, lv = fo && e < LAM;
+                const unsigned long long mf = __ballot(fo), me = __ballot(en), ml = __ballot(lv);
+                const unsigned long long below = (1ull << lane) - 1ull;
+                if (fo) flist[nf + __popcll(mf & below)] = e;
+                if (en) ecand[nen + __popcll(me & below)] = e;
+                if (lv) eslot[nlv + __popcll(ml & below)] = e;
+                nf += __popcll(mf); nen += __popcll(me); nlv += __popcll(ml);
+            }
+        }
+        __syncthreads();
+        // exactly LAM stay, so 64 are folded and entrants and leavers pair up; count the entrants again for the copy
+        int ne = 0;
+        for (int e = LAM; e < NE; e++) ne += keep[e];
+
+        // ---- 4. fold: operands of the folded pairs transposed into LDS, then H[f][c] += sum_e phi_e[f] v_e[c]
+        {
+            uint4 pv4[8];
+#pragma unroll
+            for (int it = 0; it < 8; it++) {
+                const int o = tid + 256 * it, ep = o >> 5, rem = o & 31;
+                pv4[it] = *reinterpret_cast<const uint4 *>(phiE + (size_t)flist[ep] * 2 * D + (rem >> 4) * D + ((rem & 15) << 3));
+            }
+            uint4 vv4[4];
+#pragma unroll
+            for (int it = 0; it < 4; it++) {
+                const int o = tid + 256 * it, ep = o >> 4, ch = o & 15;
+                vv4[it] = reinterpret_cast<const uint4 *>(vrow(flist[ep]))[ch];
+            }
+#pragma unroll
+            for (int it = 0; it < 8; it++) {
+                const int o = tid + 256 * it, ep = o >> 5, rem = o & 31, pt = rem >> 4, ch = rem & 15;
+                const uint32_t u[4] = {pv4[it].x, pv4[it].y, pv4[it].z, pv4[it].w};
+#pragma unroll
+                for (int x = 0; x < 8; x++) {
+                    const int f = 32 * (ch >> 2) + 16 * (x >> 2) + 4 * (ch & 3) + (x & 3);
+                    PT[pt * D * C + f * C + ((((ep >> 3) ^ ((f ^ (f >> 3)) & 7))) << 3) + (ep & 7)] =
+                        (uint16_t)((x & 1) ? (u[x >> 1] >> 16) : (u[x >> 1] & 0xFFFFu));
+                }
+            }
+#pragma unroll
+            for (int it = 0; it < 4; it++) {
+                const int o = tid + 256 * it, ep = o >> 4, ch = o & 15;
+                const uint32_t u[4] = {vv4[it].x, vv4[it].y, vv4[it].z, vv4[it].w};
+#pragma unroll
+                for (int x = 0; x < 8; x++) {
+                    const int c = 8 * ch + x;
+                    VT[c * C + ((((ep >> 3) ^ ((c ^ (c >> 3)) & 7))) << 3) + (ep & 7)] =
+                        (uint16_t)((x & 1) ? (u[x >> 1] >> 16) : (u[x >> 1] & 0xFFFFu));
+                }
+            }
+        }
+        __syncthreads();
+        {
+            bf16x8 Bv[2][2];
+#pragma unroll
+            for (int ct = 0; ct < 2; ct++)
+#pragma unroll
+                for (int k2 = 0; k2 < 2; k2++) {
+                    const int c = 32 * w + 16 * ct + r16;
+                    Bv[ct][k2] = as_bf16x8(*reinterpret_cast<const uint4 *>(&VT[c * C + (((4 * k2 + g4) ^ ((c ^ (c >> 3)) & 7)) << 3)]));
+                }
+#define LOLA_SFOLD(ct, ks, hf) { const int f = 16 * (2 * ks + hf) + r16; \
+            _Pragma("unroll") for (int pt = 0; pt < 2; pt++) \
+            _Pragma("unroll") for (int k2 = 0; k2 < 2; k2++) { \
+                const bf16x8 Ap = as_bf16x8(*reinterpret_cast<const uint4 *>(&PT[pt * D * C + f * C + (((4 * k2 + g4) ^ ((f ^ (f >> 3)) & 7)) << 3)])); \
+                hreg##ct##ks##hf = mfma16(Ap, Bv[ct][k2], hreg##ct##ks##hf); } }
+            LOLA_SREP(LOLA_SFOLD)
+#undef LOLA_SFOLD
+            if (tid < D) {
+                const int f = tid;
+                float acc = 0.f;
+#pragma unroll
+                for (int pt = 0; pt < 2; pt++)
+#pragma unroll
+                    for (int ch = 0; ch < 8; ch++) {
+                        const uint4 u = *reinterpret_cast<const uint4 *>(&PT[pt * D * C + f * C + (ch << 3)]);
+                        acc += bf_lo(u.x) + bf_hi(u.x) + bf_lo(u.y) + bf_hi(u.y) + bf_lo(u.z) + bf_hi(u.z) + bf_lo(u.w) + bf_hi(u.w);
+                    }
+                s_l[f] += acc;
+            }
+        }
+        // ---- 5. compaction: entrants take the leavers' slots (all reads of the old rows are done: barrier above)
+        for (int o = tid; o < ne * 32; o += 256) {
+            const int x = o >> 5, rem = o & 31, kv = rem >> 4, ch = rem & 15;
+            const int e = ecand[x], sl = eslot[x];
+            const bf16_t *src = kv ? vrow(e) : krow(e);
+            bf16_t *dst = (kv ? sp_v : sp_k) + (size_t)sl * DH;
+            reinterpret_cast<uint4 *>(dst)[ch] = reinterpret_cast<const uint4 *>(src)[ch];
+        }
+        for (int x = tid; x < ne; x += 256) {
+            const int e = ecand[x], sl = eslot[x];
+            sp_idx[sl] = cidx[e];
+            sp_row[sl] = vrow_c - ETA + (e - LAM);
+        }
+        __threadfence();
+        __syncthreads();
+        if (a.sel_trace) {
+            int32_t *tr = a.sel_trace + ((size_t)si * a.n_chunks + j) * LAM;
+            for (int sl = tid; sl < LAM; sl += 256) tr[sl] = sp_idx[sl];
+        }
+    }
+    if (h_in_regs) {
+        LOLA_SREP(LOLA_SSTORE)
+        if (tid < D) sg[tid] = s_l[tid];
+    }
+    if (tid == 0) a.st.sp_count[si] = spc;
+#undef LOLA_SREP
+#undef LOLA_SADDR
+#undef LOLA_SDECL
+#undef LOLA_SLOAD
+#undef LOLA_SSTORE
+}
+
 }  // namespace fast
 }  // namespace lola

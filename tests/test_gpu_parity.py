@@ -136,6 +136,26 @@ def test_resume_and_multipass_workspace():
     assert torch.allclose(one.H, layer.H, rtol=1e-5, atol=1e-6)
 
 
+@pytest.mark.parametrize("lam,phi_kind", [(64, 0), (128, 1), (256, 0)])
+def test_8b_shape_resume_ragged_multipass(lam, phi_kind):
+    """The MFMA prefill kernels (8B head shape) across call boundaries that are not chunk-aligned:
+    the second call starts mid-chunk (its chunks are regular again but offset), the third is
+    update-only with a ragged tail, the last runs in several workspace passes."""
+    sh = wl.scaled(3, B=1, T=64 * 14 + 29, lam=lam)
+    Wq, Wk = wl.weights(sh)
+    if phi_kind:     # keep exp(+-z) in a moderate range
+        Wq, Wk = wl.store(0.5 * Wq, sh.dtype), wl.store(0.5 * Wk, sh.dtype)
+    q, k, v, _ = wl.sequence_inputs(sh)
+    cuts = [0, 64 * 5 + 3, 64 * 8 + 3, 64 * 10 + 40, sh.T]
+    layer, o = None, None
+    for i in range(4):
+        a, b = cuts[i], cuts[i + 1]
+        layer, o, rep = P.prefill_parity(sh, q[:, :, a:b], k[:, :, a:b], v[:, :, a:b], Wq, Wk, layer=layer, oracle=o,
+                                         with_outputs=(i != 2), workspace_limit=0 if i == 3 else None,
+                                         layer_kw=dict(phi_kind=phi_kind))
+        say("8b resume part", i, rep)
+
+
 def test_bf16_outputs():
     sh = wl.scaled(2, T=256)
     Wq, Wk = wl.weights(sh)
