@@ -228,11 +228,15 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
 // (sequence, kv head), persistent over the chunks of a pass.
 //
 // H^T lives in registers for the whole pass (wavefront w owns rows 32w .. 32w+31 as fp32, re-split
-// into bf16 high + low MFMA operands once per chunk); s lives in LDS.  Per regular chunk (a full
-// chunk, a full window behind it, a full cache):
+// into bf16 high + low MFMA operands once per chunk); s lives in LDS.  With lambda <= 128 the features
+// of the cached keys stay in LDS from chunk to chunk as well (a cache slot keeps its row; an entrant's
+// row is copied into the slot it takes), so a regular chunk only computes phi of the 64 pairs that
+// leave the window, and the key and value rows of those pairs are requested one chunk ahead.
+// Per regular chunk (a full chunk, a full window behind it, a full cache):
 //   1. snapshot of H^T (operand order, high/low parts), s and the cache's row list for the output kernel;
-//   2. phi of the lambda + 64 candidates (tiles shared out over the wavefronts) -> LDS and a global
-//      scratch copy; recall GEMM P^T = H^T Phi^T and squared error against the candidates' values;
+//   2. phi of the candidates not yet in LDS; recall GEMM P^T = H^T Phi^T for all lambda + 64 candidates,
+//      with s riding along as one more row (phi.s, the recall's denominator), and per candidate the
+//      three sums  |P|^2, P.v, |v|^2  from which  |P/(phi.s) - v|^2  follows;
 //   3. rank by counting (score descending, token index ascending), the first lambda stay;
 //   4. fold of the 64 others on MFMA: H[f][c] += sum_e phi_e[f] v_e[c] accumulates directly into the
 //      registers that hold H^T (its C layout is the recall GEMM's A layout), operands gathered
@@ -240,18 +244,26 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
 //   5. in-place compaction: the entrants' K, V rows overwrite the slots of the leavers.
 // Any other chunk (warm-up while the cache fills, the first chunks of a sequence, a ragged last chunk)
 // goes through the generic per-chunk routine on the state in global memory.
+
+// Chunk swizzle of the transposed fold operands: three bits of the row index r, chosen among the bits that differ
+// between the rows one wavefront writes at once (r2, r3, r5) and between the rows it reads at once (r0 .. r3).
+__device__ __forceinline__ int tswz(int r) { return ((((r >> 5) ^ r) & 1) << 2) | ((r >> 2) & 3); }
+
 template <int LAM>
 __global__ __launch_bounds__(256, 1) void scan_fast_kernel(generic::PrefillArgs<bf16_t> a) {
     constexpr int DH = 128, M = 64, D = 128, C = 64, ETA = 64;
-    constexpr int P = LAM + ETA, NE = LAM + C, NTILE = NE / 16, TB = 12, RB = TB * 16;
-    __shared__ __attribute__((aligned(16))) uint16_t PB[2 * RB * D];    // phi of one batch of candidates: high parts, low parts
+    constexpr int P = LAM + ETA, NE = LAM + C, NTILE = NE / 16, TB = LAM > 128 ? 10 : 12, RB = TB * 16;
+    constexpr int TPW = (TB + 3) / 4, NK = NE / 64, TC = LAM / 16;
+    constexpr bool PERSIST = NTILE <= TB;   // one batch: the candidates' features all fit in LDS and the cache's part stays there
+    static_assert(NE % 64 == 0, "candidates are ranked 64 per register");
+    __shared__ __attribute__((aligned(16))) uint16_t PB[2 * RB * D];    // phi of (a batch of) candidates: high parts, low parts
     __shared__ __attribute__((aligned(16))) uint16_t PT[2 * D * C];     // phi^T of the folded pairs [part][f][e']
     __shared__ __attribute__((aligned(16))) uint16_t VT[DH * C];        // v^T of the folded pairs [c][e']
     __shared__ __attribute__((aligned(16))) float s_l[D];
-    __shared__ float rden_l[NE];
-    __shared__ float part[4][NE];
-    __shared__ __attribute__((aligned(16))) uint32_t score[NE];   // bit pattern of the squared error: for values >= 0 (and NaN) its integer order is a total order
-    __shared__ __attribute__((aligned(16))) int cidx[NE];
+    __shared__ float dn_l[NE];               // phi(k).s
+    __shared__ float part[3][4][NE];         // per wavefront: |P|^2, P.v, |v|^2 over its 32 value columns
+    __shared__ __attribute__((aligned(16))) unsigned long long key[NE];
+    __shared__ int cidx[NE];
     __shared__ int keep[NE];
     __shared__ int flist[C], ecand[C], eslot[C];
     static_assert(2 * RB * D * 2 >= 4 * (4 * NE + 2 * C + 8 + 32 * (3 * DH + D + 1)), "the generic per-chunk routine borrows the phi tile as scratch (tiles of <= 32 rows)");
@@ -286,6 +298,13 @@ __global__ __launch_bounds__(256, 1) void scan_fast_kernel(generic::PrefillArgs<
 #define LOLA_SSTORE(ct, ks, hf) *reinterpret_cast<f32x4 *>(Hg + LOLA_SADDR(ct, ks, hf)) = hreg##ct##ks##hf;
     LOLA_SREP(LOLA_SDECL)
     bool h_in_regs = false;
+    bool phi_valid = false;     // PERSIST: rows [0, LAM) of PB hold phi of the cache slots, and BKn / vvn the rows requested ahead
+    bf16x8 BKn[4];              // key rows of this wavefront's tile of the pairs that leave the window in the next chunk
+    uint2 vvn[4][2];            // their values at this wavefront's columns
+#pragma unroll
+    for (int ks = 0; ks < 4; ks++) BKn[ks] = zero_bf16x8();
+#pragma unroll
+    for (int u = 0; u < 4; u++) { vvn[u][0] = make_uint2(0, 0); vvn[u][1] = make_uint2(0, 0); }
 
     for (int j = a.j0; j < a.j1; j++) {
         const int cl = min(C, a.T_tokens - j * C);
@@ -300,6 +319,7 @@ __global__ __launch_bounds__(256, 1) void scan_fast_kernel(generic::PrefillArgs<
                 __syncthreads();
             }
             generic::scan_chunk(a, si, j, spc, reinterpret_cast<float *>(PB));
+            phi_valid = false;
             __threadfence();
             __syncthreads();
             continue;
@@ -310,6 +330,13 @@ __global__ __launch_bounds__(256, 1) void scan_fast_kernel(generic::PrefillArgs<
             h_in_regs = true;
             __syncthreads();
         }
+        if (j == a.j1 - 1) LOLA_STAMP(0);
+        // The lane coordinates are made opaque once per chunk: everything derived from them (LDS and global
+        // addresses of every phase) is then recomputed inside the loop instead of being hoisted out of it as
+        // hundreds of loop-invariant registers, which the register file cannot hold next to H^T.
+        int tl_ = threadIdx.x;
+        asm volatile("" : "+v"(tl_));
+        const int tid = tl_, lane = tid & 63, r16 = lane & 15, g4 = lane >> 4, w = __builtin_amdgcn_readfirstlane(tid >> 6);
         const int vrow_c = P + j * C;           // virtual row of the chunk's first token
         // source rows of candidate e: a cache slot, or one of the 64 rows before the chunk
         auto krow = [&](int e) -> const bf16_t * {
@@ -322,9 +349,12 @@ __global__ __launch_bounds__(256, 1) void scan_fast_kernel(generic::PrefillArgs<
             const int vr = vrow_c - ETA + (e - LAM);
             return vr < P ? pV + (size_t)vr * DH : vc + (size_t)(vr - P) * DH;
         };
+        const bool have_phi = PERSIST && phi_valid;
+        const int tfirst = have_phi ? TC : 0;   // first tile whose phi is computed in this chunk
 
-        // ---- 1. operands of the recall GEMM from the fp32 registers; snapshot for the output kernel
-        bf16x8 Ahi[2][4], Alo[2][4];
+        // ---- 1. operands of the recall GEMM from the fp32 registers (H^T, and s as one more row held by the lanes
+        // of row 0); the snapshot for the output kernel is stored further down
+        bf16x8 Ahi[2][4], Alo[2][4], Ash[4], Asl[4];
 #define LOLA_SSPLIT(ct, ks, hf) { const f32x4 v = hreg##ct##ks##hf; \
             const __bf16 h0 = (__bf16)v[0], h1 = (__bf16)v[1], h2 = (__bf16)v[2], h3 = (__bf16)v[3]; \
             Ahi[ct][ks][4 * hf] = h0; Ahi[ct][ks][4 * hf + 1] = h1; Ahi[ct][ks][4 * hf + 2] = h2; Ahi[ct][ks][4 * hf + 3] = h3; \
@@ -332,133 +362,217 @@ __global__ __launch_bounds__(256, 1) void scan_fast_kernel(generic::PrefillArgs<
             Alo[ct][ks][4 * hf + 2] = (__bf16)(v[2] - (float)h2); Alo[ct][ks][4 * hf + 3] = (__bf16)(v[3] - (float)h3); }
         LOLA_SREP(LOLA_SSPLIT)
 #undef LOLA_SSPLIT
-        if (a.want_out) {
-            const size_t sj = (size_t)si * a.S + (j - a.j0);
-            uint16_t *s16 = reinterpret_cast<uint16_t *>(a.snapH) + sj * (2 * D * DH);
 #pragma unroll
-            for (int ct = 0; ct < 2; ct++)
+        for (int ks = 0; ks < 4; ks++) {
+            float sv[8];
 #pragma unroll
-                for (int ks = 0; ks < 4; ks++) {
-                    const int off = (32 * w + 16 * ct + r16) * D + ((4 * ks + g4) << 3);
-                    *reinterpret_cast<uint4 *>(s16 + off) = __builtin_bit_cast(uint4, Ahi[ct][ks]);
-                    *reinterpret_cast<uint4 *>(s16 + D * DH + off) = __builtin_bit_cast(uint4, Alo[ct][ks]);
-                }
-            if (tid < D / 4) reinterpret_cast<float4 *>(a.snapS + sj * D)[tid] = reinterpret_cast<const float4 *>(s_l)[tid];
-            for (int sl = tid; sl < LAM; sl += 256) a.snapG[sj * LAM + sl] = sp_row[sl];
+            for (int hf = 0; hf < 2; hf++) {
+                const float4 s4 = *reinterpret_cast<const float4 *>(&s_l[32 * ks + 16 * hf + 4 * g4]);
+                sv[4 * hf] = s4.x; sv[4 * hf + 1] = s4.y; sv[4 * hf + 2] = s4.z; sv[4 * hf + 3] = s4.w;
+            }
+            split8(sv, Ash[ks], Asl[ks]);
+            if (r16 != 0) { Ash[ks] = zero_bf16x8(); Asl[ks] = zero_bf16x8(); }
         }
+        for (int e = tid; e < NE; e += 256) cidx[e] = e < LAM ? sp_idx[e] : (int)(aj - ETA + (e - LAM));
 
-        // ---- 2. phi of the candidates and their recall error, in batches of TB tiles
+        if (j == a.j1 - 1) LOLA_STAMP(1);
+        // ---- 2. phi of the candidates and their recall error, in batches of TB tiles.  All global loads of a
+        // batch are requested up front in the order of their use: key rows, then the candidates' values for the
+        // recall epilogue, then the rows wanted by the next chunk; the snapshot stores follow once phi is done, so
+        // that they drain while the recall GEMM runs out of LDS and registers.
 #pragma unroll 1
         for (int t0 = 0; t0 < NTILE; t0 += TB) {
             const int t1 = min(NTILE, t0 + TB);
-#pragma unroll 1
-            for (int t = t0 + w; t < t1; t += 4) {
-                const int e = 16 * t + r16;
-                const bf16_t *kr = krow(e);
-                bf16x8 BK[4];
+            const int tp = max(t0, tfirst);      // wavefront w computes phi of tiles tp + w, tp + w + 4, ...
+            bf16x8 BK[TPW][4];
 #pragma unroll
-                for (int ks = 0; ks < 4; ks++) BK[ks] = ld_bf16x8(kr + 32 * ks + 8 * g4);
-                f32x4 zt[4];
+            for (int u = 0; u < TPW; u++) {
+                const int t = tp + w + 4 * u;
+                if (u == 0 && have_phi) {
 #pragma unroll
-                for (int mt = 0; mt < 4; mt++) {
-                    zt[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+                    for (int ks = 0; ks < 4; ks++) BK[0][ks] = BKn[ks];
+                } else if (t < t1) {
+                    const bf16_t *kr = krow(16 * t + r16);
 #pragma unroll
-                    for (int ks = 0; ks < 4; ks++) zt[mt] = mfma16(AW[mt][ks], BK[ks], zt[mt]);
-                }
-                float pp[16], pn[16];
-                phi_from_z(zt, a.dm.phi_kind, pp, pn);
-                float dn = 0.f;
-#pragma unroll
-                for (int mt = 0; mt < 4; mt++) {
-                    const float4 sp4 = *reinterpret_cast<const float4 *>(&s_l[16 * mt + 4 * g4]);
-                    const float4 sn4 = *reinterpret_cast<const float4 *>(&s_l[M + 16 * mt + 4 * g4]);
-                    dn = fmaf(pp[4 * mt], sp4.x, dn); dn = fmaf(pp[4 * mt + 1], sp4.y, dn);
-                    dn = fmaf(pp[4 * mt + 2], sp4.z, dn); dn = fmaf(pp[4 * mt + 3], sp4.w, dn);
-                    dn = fmaf(pn[4 * mt], sn4.x, dn); dn = fmaf(pn[4 * mt + 1], sn4.y, dn);
-                    dn = fmaf(pn[4 * mt + 2], sn4.z, dn); dn = fmaf(pn[4 * mt + 3], sn4.w, dn);
-                }
-                dn = grp_sum(dn);
-                if (g4 == 0) {
-                    rden_l[e] = dn > 0.f ? 1.0f / dn : 0.f;
-                    cidx[e] = e < LAM ? sp_idx[e] : (int)(aj - ETA + (e - LAM));
-                }
-                bf16x8 hi[4], lo[4];
-                split8(&pp[0], hi[0], lo[0]); split8(&pp[8], hi[1], lo[1]);
-                split8(&pn[0], hi[2], lo[2]); split8(&pn[8], hi[3], lo[3]);
-                const int rl = e - 16 * t0;
-#pragma unroll
-                for (int ks = 0; ks < 4; ks++) {
-                    const int addr = rl * D + (((4 * ks + g4) ^ r16) << 3);
-                    *reinterpret_cast<uint4 *>(&PB[addr]) = __builtin_bit_cast(uint4, hi[ks]);
-                    *reinterpret_cast<uint4 *>(&PB[RB * D + addr]) = __builtin_bit_cast(uint4, lo[ks]);
-                    *reinterpret_cast<uint4 *>(phiE + (size_t)e * 2 * D + ((4 * ks + g4) << 3)) = __builtin_bit_cast(uint4, hi[ks]);
-                    *reinterpret_cast<uint4 *>(phiE + (size_t)e * 2 * D + D + ((4 * ks + g4) << 3)) = __builtin_bit_cast(uint4, lo[ks]);
+                    for (int ks = 0; ks < 4; ks++) BK[u][ks] = ld_bf16x8(kr + 32 * ks + 8 * g4);
                 }
             }
+            uint2 vv[TB][2];
+#pragma unroll
+            for (int u = 0; u < TB; u++) {
+                if (PERSIST && u >= TC && have_phi) {
+                    vv[u][0] = vvn[u >= TC ? u - TC : 0][0]; vv[u][1] = vvn[u >= TC ? u - TC : 0][1];
+                } else if (t0 + u < t1) {
+                    const bf16_t *vr = vrow(16 * (t0 + u) + r16);
+#pragma unroll
+                    for (int ct = 0; ct < 2; ct++) vv[u][ct] = *reinterpret_cast<const uint2 *>(vr + 32 * w + 16 * ct + 4 * g4);
+                }
+            }
+            if (PERSIST) {   // this chunk's own pairs leave the window in the next chunk
+                const bf16_t *kr = kc + (size_t)(j * C + 16 * w + r16) * DH;
+#pragma unroll
+                for (int ks = 0; ks < 4; ks++) BKn[ks] = ld_bf16x8(kr + 32 * ks + 8 * g4);
+#pragma unroll
+                for (int u = 0; u < 4; u++) {
+                    const bf16_t *vr = vc + (size_t)(j * C + 16 * u + r16) * DH;
+#pragma unroll
+                    for (int ct = 0; ct < 2; ct++) vvn[u][ct] = *reinterpret_cast<const uint2 *>(vr + 32 * w + 16 * ct + 4 * g4);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < TPW; u++) {
+                const int t = tp + w + 4 * u;
+                if (t < t1) {
+                    const int e = 16 * t + r16;
+                    f32x4 zt[4];
+#pragma unroll
+                    for (int mt = 0; mt < 4; mt++) {
+                        zt[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                        for (int ks = 0; ks < 4; ks++) zt[mt] = mfma16(AW[mt][ks], BK[u][ks], zt[mt]);
+                    }
+                    float pp[16], pn[16];
+                    phi_from_z(zt, a.dm.phi_kind, pp, pn);
+                    bf16x8 hi[4], lo[4];
+                    split8(&pp[0], hi[0], lo[0]); split8(&pp[8], hi[1], lo[1]);
+                    split8(&pn[0], hi[2], lo[2]); split8(&pn[8], hi[3], lo[3]);
+                    const int rl = e - 16 * t0;
+#pragma unroll
+                    for (int ks = 0; ks < 4; ks++) {
+                        const int addr = rl * D + (((4 * ks + g4) ^ r16) << 3);
+                        *reinterpret_cast<uint4 *>(&PB[addr]) = __builtin_bit_cast(uint4, hi[ks]);
+                        *reinterpret_cast<uint4 *>(&PB[RB * D + addr]) = __builtin_bit_cast(uint4, lo[ks]);
+                        if (!PERSIST) {   // several batches: the fold finds earlier batches' features in global scratch
+                            *reinterpret_cast<uint4 *>(phiE + (size_t)e * 2 * D + ((4 * ks + g4) << 3)) = __builtin_bit_cast(uint4, hi[ks]);
+                            *reinterpret_cast<uint4 *>(phiE + (size_t)e * 2 * D + D + ((4 * ks + g4) << 3)) = __builtin_bit_cast(uint4, lo[ks]);
+                        }
+                    }
+                }
+            }
+            if (a.want_out && t0 == 0) {
+                const size_t sj = (size_t)si * a.S + (j - a.j0);
+                uint16_t *s16 = reinterpret_cast<uint16_t *>(a.snapH) + sj * (2 * D * DH);
+#pragma unroll
+                for (int ct = 0; ct < 2; ct++)
+#pragma unroll
+                    for (int ks = 0; ks < 4; ks++) {
+                        const int off = (32 * w + 16 * ct + r16) * D + ((4 * ks + g4) << 3);
+                        *reinterpret_cast<uint4 *>(s16 + off) = __builtin_bit_cast(uint4, Ahi[ct][ks]);
+                        *reinterpret_cast<uint4 *>(s16 + D * DH + off) = __builtin_bit_cast(uint4, Alo[ct][ks]);
+                    }
+                if (tid < D / 4) reinterpret_cast<float4 *>(a.snapS + sj * D)[tid] = reinterpret_cast<const float4 *>(s_l)[tid];
+                for (int sl = tid; sl < LAM; sl += 256) a.snapG[sj * LAM + sl] = sp_row[sl];
+            }
+            if (j == a.j1 - 1 && t0 == 0) LOLA_STAMP(2);
             __syncthreads();
+            if (j == a.j1 - 1 && t0 == 0) LOLA_STAMP(3);
             // recall GEMM for the batch: A = this wavefront's rows of H^T, B = phi from LDS; lane (candidate r16, group g4)
-            // holds rows c = 32w + 16ct + 4 g4 + i and needs the candidate's values at those columns
-#pragma unroll 1
-            for (int t = t0; t < t1; t++) {
-                const int e = 16 * t + r16, rl = e - 16 * t0;
-                const bf16_t *vr = vrow(e);
-                uint2 vv[2];
+            // holds rows c = 32w + 16ct + 4 g4 + i and pairs them with the candidate's values at those columns.
+            // Tile t's denominators come from wavefront t % 4 (A = s in row 0, zeros below).
+            // (operands of the next tile are read from LDS before this tile's MFMAs; the scheduling fence keeps the
+            // compiler from hoisting the reads of all tiles at once, which would not fit the register file)
+            bf16x8 Bc[8], Bn[8];
 #pragma unroll
-                for (int ct = 0; ct < 2; ct++) vv[ct] = *reinterpret_cast<const uint2 *>(vr + 32 * w + 16 * ct + 4 * g4);
-                f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}}, acc2[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-#pragma unroll
-                for (int ks = 0; ks < 4; ks++) {
-                    const int addr = rl * D + (((4 * ks + g4) ^ r16) << 3);
-                    const bf16x8 Bh = as_bf16x8(*reinterpret_cast<const uint4 *>(&PB[addr]));
-                    const bf16x8 Bl = as_bf16x8(*reinterpret_cast<const uint4 *>(&PB[RB * D + addr]));
-#pragma unroll
-                    for (int ct = 0; ct < 2; ct++) acc[ct] = mfma16(Ahi[ct][ks], Bh, acc[ct]);
-#pragma unroll
-                    for (int ct = 0; ct < 2; ct++) acc2[ct] = mfma16(Ahi[ct][ks], Bl, acc2[ct]);
-#pragma unroll
-                    for (int ct = 0; ct < 2; ct++) acc2[ct] = mfma16(Alo[ct][ks], Bh, acc2[ct]);
-                }
-                const float rd = rden_l[e];
-                float es = 0.f;
-#pragma unroll
-                for (int ct = 0; ct < 2; ct++) {
-                    const f32x4 p = acc[ct] + acc2[ct];
-                    const float e0 = fmaf(p[0], rd, -bf_lo(vv[ct].x)), e1 = fmaf(p[1], rd, -bf_hi(vv[ct].x));
-                    const float e2 = fmaf(p[2], rd, -bf_lo(vv[ct].y)), e3 = fmaf(p[3], rd, -bf_hi(vv[ct].y));
-                    es = fmaf(e0, e0, es); es = fmaf(e1, e1, es); es = fmaf(e2, e2, es); es = fmaf(e3, e3, es);
-                }
-                es = grp_sum(es);
-                if (g4 == 0) part[w][e] = es;
+            for (int ks = 0; ks < 4; ks++) {
+                const int addr = r16 * D + (((4 * ks + g4) ^ r16) << 3);
+                Bc[ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(&PB[addr]));
+                Bc[4 + ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(&PB[RB * D + addr]));
             }
+#pragma unroll
+            for (int u = 0; u < TB; u++) {
+                if (t0 + u < t1) {
+                    const int e = 16 * (t0 + u) + r16;
+                    if (u + 1 < TB && t0 + u + 1 < t1) {
+#pragma unroll
+                        for (int ks = 0; ks < 4; ks++) {
+                            const int addr = (16 * (u + 1) + r16) * D + (((4 * ks + g4) ^ r16) << 3);
+                            Bn[ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(&PB[addr]));
+                            Bn[4 + ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(&PB[RB * D + addr]));
+                        }
+                    }
+                    f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}}, acc2[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+                    for (int ks = 0; ks < 4; ks++) {
+#pragma unroll
+                        for (int ct = 0; ct < 2; ct++) acc[ct] = mfma16(Ahi[ct][ks], Bc[ks], acc[ct]);
+#pragma unroll
+                        for (int ct = 0; ct < 2; ct++) acc2[ct] = mfma16(Ahi[ct][ks], Bc[4 + ks], acc2[ct]);
+#pragma unroll
+                        for (int ct = 0; ct < 2; ct++) acc2[ct] = mfma16(Alo[ct][ks], Bc[ks], acc2[ct]);
+                    }
+                    if (((t0 + u) & 3) == w) {
+                        f32x4 ds = {0.f, 0.f, 0.f, 0.f}, ds2 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                        for (int ks = 0; ks < 4; ks++) {
+                            ds = mfma16(Ash[ks], Bc[ks], ds);
+                            ds2 = mfma16(Ash[ks], Bc[4 + ks], ds2);
+                            ds2 = mfma16(Asl[ks], Bc[ks], ds2);
+                        }
+                        if (g4 == 0) dn_l[e] = ds[0] + ds2[0];
+                    }
+                    float sa = 0.f, sb = 0.f, sc = 0.f;
+#pragma unroll
+                    for (int ct = 0; ct < 2; ct++) {
+                        const f32x4 p = acc[ct] + acc2[ct];
+                        const float v0 = bf_lo(vv[u][ct].x), v1 = bf_hi(vv[u][ct].x), v2 = bf_lo(vv[u][ct].y), v3 = bf_hi(vv[u][ct].y);
+                        sa = fmaf(p[0], p[0], sa); sa = fmaf(p[1], p[1], sa); sa = fmaf(p[2], p[2], sa); sa = fmaf(p[3], p[3], sa);
+                        sb = fmaf(p[0], v0, sb); sb = fmaf(p[1], v1, sb); sb = fmaf(p[2], v2, sb); sb = fmaf(p[3], v3, sb);
+                        sc = fmaf(v0, v0, sc); sc = fmaf(v1, v1, sc); sc = fmaf(v2, v2, sc); sc = fmaf(v3, v3, sc);
+                    }
+                    sa = grp_sum(sa); sb = grp_sum(sb); sc = grp_sum(sc);
+                    if (g4 == 0) { part[0][w][e] = sa; part[1][w][e] = sb; part[2][w][e] = sc; }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int x = 0; x < 8; x++) Bc[x] = Bn[x];
+                }
+            }
+            if (j == a.j1 - 1 && t0 == 0) LOLA_STAMP(4);
             __syncthreads();
         }
 
-        // ---- 3. rank by (score descending, token index ascending); the first LAM stay
-        for (int e = tid; e < NE; e += 256)
-            score[e] = __float_as_uint(part[0][e] + part[1][e] + part[2][e] + part[3][e]) & 0x7FFFFFFFu;
-        __syncthreads();
+        if (j == a.j1 - 1) LOLA_STAMP(5);
+        // ---- 3. rank by (score descending, token index ascending); the first LAM stay.  The squared error is
+        // |P|^2 / (phi.s)^2 - 2 P.v / (phi.s) + |v|^2 (recall = 0 while phi.s = 0, i.e. nothing folded yet).  Both
+        // criteria are packed into one 64-bit key (the bit pattern of a float >= 0 orders like an integer), so the
+        // keys are distinct and exactly LAM candidates have fewer than LAM keys above theirs.
         for (int e = tid; e < NE; e += 256) {
-            const uint32_t sc = score[e];
-            const int ix = cidx[e];
-            int rank = 0;
-            for (int o = 0; o < NE; o += 4) {
-                const uint4 so = *reinterpret_cast<const uint4 *>(&score[o]);
-                const int4 io = *reinterpret_cast<const int4 *>(&cidx[o]);
-                rank += (so.x > sc || (so.x == sc && io.x < ix)) ? 1 : 0;
-                rank += (so.y > sc || (so.y == sc && io.y < ix)) ? 1 : 0;
-                rank += (so.z > sc || (so.z == sc && io.z < ix)) ? 1 : 0;
-                rank += (so.w > sc || (so.w == sc && io.w < ix)) ? 1 : 0;
-            }
-            keep[e] = rank < LAM;
+            const float dn = dn_l[e], rd = dn > 0.f ? 1.0f / dn : 0.f;
+            const float sa = part[0][0][e] + part[0][1][e] + part[0][2][e] + part[0][3][e];
+            const float sb = part[1][0][e] + part[1][1][e] + part[1][2][e] + part[1][3][e];
+            const float sc = part[2][0][e] + part[2][1][e] + part[2][2][e] + part[2][3][e];
+            const float sq = fmaxf(fmaf(rd * rd, sa, fmaf(-2.0f * rd, sb, sc)), 0.f);
+            key[e] = ((unsigned long long)(__float_as_uint(sq) & 0x7FFFFFFFu) << 32) | (uint32_t)(0x7FFFFFFF - cidx[e]);
         }
         __syncthreads();
+        {
+            // every wavefront holds all keys (NK per lane) and ranks 16 lanes' worth of each register: the candidate's
+            // key is broadcast, compared by all lanes, and the votes are counted on the scalar unit
+            unsigned long long kreg[NK];
+#pragma unroll
+            for (int x = 0; x < NK; x++) kreg[x] = key[64 * x + lane];
+#pragma unroll
+            for (int x = 0; x < NK; x++) {
+                const uint32_t klo = (uint32_t)kreg[x], khi = (uint32_t)(kreg[x] >> 32);
+#pragma unroll 4
+                for (int l = 16 * w; l < 16 * w + 16; l++) {
+                    const unsigned long long ke = ((unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)khi, l) << 32) |
+                                                  (uint32_t)__builtin_amdgcn_readlane((int)klo, l);
+                    int cnt = 0;
+#pragma unroll
+                    for (int y = 0; y < NK; y++) cnt += __popcll(__ballot(kreg[y] > ke));
+                    if (lane == 0) keep[64 * x + l] = cnt < LAM;
+                }
+            }
+        }
+        __syncthreads();
+        if (j == a.j1 - 1) LOLA_STAMP(6);
         // lists (one wavefront, ballots): candidates to fold; entrants paired with the slots of the leavers
         if (w == 0) {
             int nf = 0, nen = 0, nlv = 0;
             for (int e0 = 0; e0 < NE; e0 += 64) {
                 const int e = e0 + lane;
-                const bool kp = e < NE && keep[e];
-                const bool fo = e < NE && !kp, en = kp && e >= LAM, lv = fo && e < LAM;
+                const bool kp = keep[e];
+                const bool fo = !kp, en = kp && e >= LAM, lv = fo && e < LAM;
                 const unsigned long long mf = __ballot(fo), me = __ballot(en), ml = __ballot(lv);
                 const unsigned long long below = (1ull << lane) - 1ull;
                 if (fo) flist[nf + __popcll(mf & below)] = e;
@@ -471,58 +585,88 @@ __global__ __launch_bounds__(256, 1) void scan_fast_kernel(generic::PrefillArgs<
         // exactly LAM stay, so 64 are folded and entrants and leavers pair up; count the entrants again for the copy
         int ne = 0;
         for (int e = LAM; e < NE; e++) ne += keep[e];
+        if (j == a.j1 - 1) LOLA_STAMP(7);
 
-        // ---- 4. fold: operands of the folded pairs transposed into LDS, then H[f][c] += sum_e phi_e[f] v_e[c]
+        // ---- 4. fold: operands of the folded pairs transposed into LDS, then H[f][c] += sum_e phi_e[f] v_e[c].
+        // Each thread takes two folded pairs (e', e'+1) and one 16-byte piece of their rows and writes eight 32-bit
+        // words (column pair e', e'+1 of eight rows of the transposed tile).  Within a wavefront the lanes cover 16
+        // pieces x 4 column pairs; the 16-byte column chunk of a row is XOR-ed with three row bits chosen so that
+        // these writes fall on all banks (two lanes per bank) and the 128-bit operand reads of the MFMAs below
+        // on all eight chunks evenly.
         {
-            uint4 pv4[8];
-#pragma unroll
-            for (int it = 0; it < 8; it++) {
-                const int o = tid + 256 * it, ep = o >> 5, rem = o & 31;
-                pv4[it] = *reinterpret_cast<const uint4 *>(phiE + (size_t)flist[ep] * 2 * D + (rem >> 4) * D + ((rem & 15) << 3));
-            }
-            uint4 vv4[4];
+            const int ch = tid & 15, pairpos = (tid >> 4) & 3, wl = w;
+            uint4 pa[4], pb[4], va[2], vb[2];
+            const int pt = wl & 1;
 #pragma unroll
             for (int it = 0; it < 4; it++) {
-                const int o = tid + 256 * it, ep = o >> 4, ch = o & 15;
-                vv4[it] = reinterpret_cast<const uint4 *>(vrow(flist[ep]))[ch];
-            }
-#pragma unroll
-            for (int it = 0; it < 8; it++) {
-                const int o = tid + 256 * it, ep = o >> 5, rem = o & 31, pt = rem >> 4, ch = rem & 15;
-                const uint32_t u[4] = {pv4[it].x, pv4[it].y, pv4[it].z, pv4[it].w};
-#pragma unroll
-                for (int x = 0; x < 8; x++) {
-                    const int f = 32 * (ch >> 2) + 16 * (x >> 2) + 4 * (ch & 3) + (x & 3);
-                    PT[pt * D * C + f * C + ((((ep >> 3) ^ ((f ^ (f >> 3)) & 7))) << 3) + (ep & 7)] =
-                        (uint16_t)((x & 1) ? (u[x >> 1] >> 16) : (u[x >> 1] & 0xFFFFu));
+                const int ep = 8 * ((wl >> 1) + 2 * it) + 2 * pairpos;
+                const int ea = flist[ep], eb = flist[ep + 1];
+                if (PERSIST) {
+                    pa[it] = *reinterpret_cast<const uint4 *>(&PB[pt * RB * D + ea * D + ((ch ^ (ea & 15)) << 3)]);
+                    pb[it] = *reinterpret_cast<const uint4 *>(&PB[pt * RB * D + eb * D + ((ch ^ (eb & 15)) << 3)]);
+                } else {
+                    pa[it] = *reinterpret_cast<const uint4 *>(phiE + (size_t)ea * 2 * D + pt * D + (ch << 3));
+                    pb[it] = *reinterpret_cast<const uint4 *>(phiE + (size_t)eb * 2 * D + pt * D + (ch << 3));
                 }
             }
 #pragma unroll
-            for (int it = 0; it < 4; it++) {
-                const int o = tid + 256 * it, ep = o >> 4, ch = o & 15;
-                const uint32_t u[4] = {vv4[it].x, vv4[it].y, vv4[it].z, vv4[it].w};
+            for (int it = 0; it < 2; it++) {
+                const int ep = 8 * (wl + 4 * it) + 2 * pairpos;
+                va[it] = reinterpret_cast<const uint4 *>(vrow(flist[ep]))[ch];
+                vb[it] = reinterpret_cast<const uint4 *>(vrow(flist[ep + 1]))[ch];
+            }
+            // feature held by element x of piece ch (operand order): 32 (ch / 4) + 16 (x / 4) + 4 (ch % 4) + x % 4
 #pragma unroll
-                for (int x = 0; x < 8; x++) {
-                    const int c = 8 * ch + x;
-                    VT[c * C + ((((ep >> 3) ^ ((c ^ (c >> 3)) & 7))) << 3) + (ep & 7)] =
-                        (uint16_t)((x & 1) ? (u[x >> 1] >> 16) : (u[x >> 1] & 0xFFFFu));
+            for (int x = 0; x < 8; x++) {
+                const int f = 32 * (ch >> 2) + 16 * (x >> 2) + 4 * (ch & 3) + (x & 3);
+                const int bx = pt * D * C + f * C + ((((wl >> 1) ^ tswz(f))) << 3) + 2 * pairpos;
+#pragma unroll
+                for (int it = 0; it < 4; it++) {
+                    const uint32_t ua = (&pa[it].x)[x >> 1], ub = (&pb[it].x)[x >> 1];
+                    const uint32_t wv = (x & 1) ? ((ua >> 16) | (ub & 0xFFFF0000u)) : ((ua & 0xFFFFu) | (ub << 16));
+                    *reinterpret_cast<uint32_t *>(&PT[bx ^ (it << 4)]) = wv;
+                }
+            }
+#pragma unroll
+            for (int x = 0; x < 8; x++) {
+                const int c = 8 * ch + x;
+                const int bx = c * C + (((wl ^ tswz(c))) << 3) + 2 * pairpos;
+#pragma unroll
+                for (int it = 0; it < 2; it++) {
+                    const uint32_t ua = (&va[it].x)[x >> 1], ub = (&vb[it].x)[x >> 1];
+                    const uint32_t wv = (x & 1) ? ((ua >> 16) | (ub & 0xFFFF0000u)) : ((ua & 0xFFFFu) | (ub << 16));
+                    *reinterpret_cast<uint32_t *>(&VT[bx ^ (it << 5)]) = wv;
                 }
             }
         }
+        if (j == a.j1 - 1) LOLA_STAMP(8);
         __syncthreads();
+        if (j == a.j1 - 1) LOLA_STAMP(9);
         {
+            // compaction, first half: the entrants' rows are requested now and stored after the fold (all reads of
+            // the leavers' rows were completed before the barrier above)
+            uint4 cp[8];
+#pragma unroll
+            for (int it = 0; it < 8; it++) {
+                const int o = tid + 256 * it;
+                if (o < ne * 32) {
+                    const int x = o >> 5, rem = o & 31;
+                    const int e = ecand[x];
+                    cp[it] = reinterpret_cast<const uint4 *>((rem >> 4) ? vrow(e) : krow(e))[rem & 15];
+                }
+            }
             bf16x8 Bv[2][2];
 #pragma unroll
             for (int ct = 0; ct < 2; ct++)
 #pragma unroll
                 for (int k2 = 0; k2 < 2; k2++) {
                     const int c = 32 * w + 16 * ct + r16;
-                    Bv[ct][k2] = as_bf16x8(*reinterpret_cast<const uint4 *>(&VT[c * C + (((4 * k2 + g4) ^ ((c ^ (c >> 3)) & 7)) << 3)]));
+                    Bv[ct][k2] = as_bf16x8(*reinterpret_cast<const uint4 *>(&VT[c * C + (((4 * k2 + g4) ^ tswz(c)) << 3)]));
                 }
 #define LOLA_SFOLD(ct, ks, hf) { const int f = 16 * (2 * ks + hf) + r16; \
             _Pragma("unroll") for (int pt = 0; pt < 2; pt++) \
             _Pragma("unroll") for (int k2 = 0; k2 < 2; k2++) { \
-                const bf16x8 Ap = as_bf16x8(*reinterpret_cast<const uint4 *>(&PT[pt * D * C + f * C + (((4 * k2 + g4) ^ ((f ^ (f >> 3)) & 7)) << 3)])); \
+                const bf16x8 Ap = as_bf16x8(*reinterpret_cast<const uint4 *>(&PT[pt * D * C + f * C + (((4 * k2 + g4) ^ tswz(f)) << 3)])); \
                 hreg##ct##ks##hf = mfma16(Ap, Bv[ct][k2], hreg##ct##ks##hf); } }
             LOLA_SREP(LOLA_SFOLD)
 #undef LOLA_SFOLD
@@ -538,22 +682,40 @@ __global__ __launch_bounds__(256, 1) void scan_fast_kernel(generic::PrefillArgs<
                     }
                 s_l[f] += acc;
             }
-        }
-        // ---- 5. compaction: entrants take the leavers' slots (all reads of the old rows are done: barrier above)
-        for (int o = tid; o < ne * 32; o += 256) {
-            const int x = o >> 5, rem = o & 31, kv = rem >> 4, ch = rem & 15;
-            const int e = ecand[x], sl = eslot[x];
-            const bf16_t *src = kv ? vrow(e) : krow(e);
-            bf16_t *dst = (kv ? sp_v : sp_k) + (size_t)sl * DH;
-            reinterpret_cast<uint4 *>(dst)[ch] = reinterpret_cast<const uint4 *>(src)[ch];
+            if (j == a.j1 - 1) LOLA_STAMP(10);
+            // ---- 5. compaction, second half: entrants take the leavers' slots, in the state and (their features) in LDS
+#pragma unroll
+            for (int it = 0; it < 8; it++) {
+                const int o = tid + 256 * it;
+                if (o < ne * 32) {
+                    const int x = o >> 5, rem = o & 31;
+                    bf16_t *dst = ((rem >> 4) ? sp_v : sp_k) + (size_t)eslot[x] * DH;
+                    reinterpret_cast<uint4 *>(dst)[rem & 15] = cp[it];
+                }
+            }
+            if (PERSIST) {
+#pragma unroll
+                for (int it = 0; it < 8; it++) {
+                    const int o = tid + 256 * it;
+                    if (o < ne * 32) {
+                        const int x = o >> 5, rem = o & 31, pt = rem >> 4, ch = rem & 15;
+                        const int e = ecand[x], sl = eslot[x];
+                        const uint4 val = *reinterpret_cast<const uint4 *>(&PB[pt * RB * D + e * D + ((ch ^ (e & 15)) << 3)]);
+                        *reinterpret_cast<uint4 *>(&PB[pt * RB * D + sl * D + ((ch ^ (sl & 15)) << 3)]) = val;
+                    }
+                }
+            }
         }
         for (int x = tid; x < ne; x += 256) {
             const int e = ecand[x], sl = eslot[x];
             sp_idx[sl] = cidx[e];
             sp_row[sl] = vrow_c - ETA + (e - LAM);
         }
+        phi_valid = PERSIST;
+        if (j == a.j1 - 1) LOLA_STAMP(11);
         __threadfence();
         __syncthreads();
+        if (j == a.j1 - 1) LOLA_STAMP(12);
         if (a.sel_trace) {
             int32_t *tr = a.sel_trace + ((size_t)si * a.n_chunks + j) * LAM;
             for (int sl = tid; sl < LAM; sl += 256) tr[sl] = sp_idx[sl];
