@@ -32,6 +32,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
@@ -39,13 +40,22 @@ __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 u) { return __builtin_bit_cast(bf16x8, u); }
 __device__ __forceinline__ bf16x8 ld_bf16x8(const bf16_t *p) { return as_bf16x8(*reinterpret_cast<const uint4 *>(p)); }
 __device__ __forceinline__ bf16x8 zero_bf16x8() { return as_bf16x8(make_uint4(0, 0, 0, 0)); }
-// x = hi + lo + O(2^-17 |x|), both parts bf16
+// x = hi + lo + O(2^-17 |x|), both parts bf16.  Two values are rounded by one packed conversion; the residual
+// x - hi is one bf16 dot product each (hi . (-1, 0) + x, exact: the difference of a float and its bf16 rounding is a
+// float).  The two selector constants are kept in registers the compiler cannot fold: as literals of the dot
+// instruction (-1, 0) comes out wrong on this toolchain.
 __device__ __forceinline__ void split8(const float x[8], bf16x8 &hi, bf16x8 &lo) {
+    uint32_t c0 = 0x0000BF80u, c1 = 0xBF800000u;
+    asm volatile("" : "+s"(c0), "+s"(c1));
+    const bf16x2 m0 = __builtin_bit_cast(bf16x2, c0), m1 = __builtin_bit_cast(bf16x2, c1);
 #pragma unroll
-    for (int e = 0; e < 8; e++) {
-        __bf16 h = (__bf16)x[e];
-        hi[e] = h;
-        lo[e] = (__bf16)(x[e] - (float)h);
+    for (int p = 0; p < 4; p++) {
+        const f32x2 v = {x[2 * p], x[2 * p + 1]};
+        const bf16x2 h = __builtin_convertvector(v, bf16x2);
+        const f32x2 r = {__builtin_amdgcn_fdot2_f32_bf16(h, m0, v[0], false), __builtin_amdgcn_fdot2_f32_bf16(h, m1, v[1], false)};
+        const bf16x2 l = __builtin_convertvector(r, bf16x2);
+        hi[2 * p] = h[0]; hi[2 * p + 1] = h[1];
+        lo[2 * p] = l[0]; lo[2 * p + 1] = l[1];
     }
 }
 __device__ __forceinline__ float bf_lo(uint32_t u) { return __uint_as_float(u << 16); }
@@ -249,10 +259,6 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     if (tid >= 128 && tid < 128 + 2 * XR * D / 8) reinterpret_cast<uint4 *>(PX)[tid - 128] = make_uint4(0, 0, 0, 0);
     __syncthreads();
     LOLA_STAMP(1);
-    // the new pair takes the ring slot of the pair that leaves (read above)
-    if (tid < 16) reinterpret_cast<uint4 *>(win_k + (size_t)slot * DH)[tid] = reinterpret_cast<const uint4 *>(knew)[tid];
-    else if (tid < 32) reinterpret_cast<uint4 *>(win_v + (size_t)slot * DH)[tid - 16] = reinterpret_cast<const uint4 *>(vnew)[tid - 16];
-
     // ---- query rows as MFMA A operand (rows >= G are zero)
     bf16x8 AQ[4];
 #pragma unroll
@@ -558,6 +564,7 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
         }
     } else {
         load_values();
+        __syncthreads();   // logits of all wavefronts are in LDS (the steady path has passed barriers of its own)
     }
 #undef LOLA_HDECL
 #undef LOLA_HLOAD
@@ -650,6 +657,10 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
             }
         }
     }
+    // the new pair takes the ring slot of the pair that left (read in stage 0).  Done last: a load-then-store waits
+    // for every load the wavefront has in flight.
+    if (tid < 16) reinterpret_cast<uint4 *>(win_k + (size_t)slot * DH)[tid] = reinterpret_cast<const uint4 *>(knew)[tid];
+    else if (tid < 32) reinterpret_cast<uint4 *>(win_v + (size_t)slot * DH)[tid - 16] = reinterpret_cast<const uint4 *>(vnew)[tid - 16];
     if (tid == 0) a.st.n_tokens[si] = tok + 1;
     LOLA_STAMP(8);
 #ifdef LOLA_TIMING
