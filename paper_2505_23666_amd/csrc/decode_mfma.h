@@ -76,15 +76,43 @@ __device__ __forceinline__ void swap32(float v, float &r0, float &r1) {
 __device__ __forceinline__ float grp_sum(float v) { float x, y; swap16(v, x, y); v = x + y; swap32(v, x, y); return x + y; }
 __device__ __forceinline__ float grp_max(float v) { float x, y; swap16(v, x, y); v = fmaxf(x, y); swap32(v, x, y); return fmaxf(x, y); }
 __device__ __forceinline__ float grp_min(float v) { float x, y; swap16(v, x, y); v = fminf(x, y); swap32(v, x, y); return fminf(x, y); }
-// reductions over the whole wavefront
+// reductions over the whole wavefront: four data-parallel-primitive steps inside each row of 16 lanes (swap
+// neighbours, swap pairs, mirror each half, mirror the row: every lane ends with the row's result), then the
+// two row swaps above
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
+}
 __device__ __forceinline__ float wsum(float v) {
-    v += __shfl_xor(v, 1, WAVE); v += __shfl_xor(v, 2, WAVE); v += __shfl_xor(v, 4, WAVE); v += __shfl_xor(v, 8, WAVE);
+    v += dpp_f<0xB1>(v); v += dpp_f<0x4E>(v); v += dpp_f<0x141>(v); v += dpp_f<0x140>(v);
     return grp_sum(v);
 }
 __device__ __forceinline__ float wmax(float v) {
-    v = fmaxf(v, __shfl_xor(v, 1, WAVE)); v = fmaxf(v, __shfl_xor(v, 2, WAVE));
-    v = fmaxf(v, __shfl_xor(v, 4, WAVE)); v = fmaxf(v, __shfl_xor(v, 8, WAVE));
+    v = fmaxf(v, dpp_f<0xB1>(v)); v = fmaxf(v, dpp_f<0x4E>(v)); v = fmaxf(v, dpp_f<0x141>(v)); v = fmaxf(v, dpp_f<0x140>(v));
     return grp_max(v);
+}
+// smallest 64-bit key of the wavefront, in every lane
+__device__ __forceinline__ unsigned long long wmin_u64(unsigned long long k) {
+#define LOLA_KSTEP(CTRL) { const unsigned long long o = ((unsigned long long)dpp_u<CTRL>((uint32_t)(k >> 32)) << 32) | dpp_u<CTRL>((uint32_t)k); k = o < k ? o : k; }
+    LOLA_KSTEP(0xB1) LOLA_KSTEP(0x4E) LOLA_KSTEP(0x141) LOLA_KSTEP(0x140)
+#undef LOLA_KSTEP
+    {
+        auto h = __builtin_amdgcn_permlane16_swap((uint32_t)(k >> 32), (uint32_t)(k >> 32), false, false);
+        auto l = __builtin_amdgcn_permlane16_swap((uint32_t)k, (uint32_t)k, false, false);
+        const unsigned long long x = ((unsigned long long)h[0] << 32) | l[0], y = ((unsigned long long)h[1] << 32) | l[1];
+        k = x < y ? x : y;
+    }
+    {
+        auto h = __builtin_amdgcn_permlane32_swap((uint32_t)(k >> 32), (uint32_t)(k >> 32), false, false);
+        auto l = __builtin_amdgcn_permlane32_swap((uint32_t)k, (uint32_t)k, false, false);
+        const unsigned long long x = ((unsigned long long)h[0] << 32) | l[0], y = ((unsigned long long)h[1] << 32) | l[1];
+        k = x < y ? x : y;
+    }
+    return k;
 }
 __device__ __forceinline__ float wmin(float v) { return -wmax(-v); }
 __device__ __forceinline__ float fexp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -214,9 +242,6 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     const uint4 q_ld = (tid >= 64 && tid < 64 + G * 16) ? reinterpret_cast<const uint4 *>(qg)[tid - 64] : make_uint4(0, 0, 0, 0);
     const float4 s_ld = tid < D / 4 ? reinterpret_cast<const float4 *>(sg)[tid] : make_float4(0.f, 0.f, 0.f, 0.f);
     const int idx_ld = tid < LAM ? sp_idx[tid] : 0;
-    uint4 p_ld = make_uint4(0, 0, 0, 0);
-    if (popped && tid < 32)   // 16 threads fetch the leaving key row, 16 the value row (16 bytes each)
-        p_ld = reinterpret_cast<const uint4 *>(tid < 16 ? win_k + (size_t)slot * DH : win_v + (size_t)slot * DH)[tid & 15];
     // row `lane` of this wavefront's W_q (projection on the vector ALUs, lane = projection index)
     uint4 wq[16];
     {
@@ -236,6 +261,11 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     for (int t = 0; t < TPW; t++)
 #pragma unroll
         for (int ks = 0; ks < 4; ks++) BK[t][ks] = ld_bf16x8(sp_k + (size_t)(16 * (w + 4 * t) + r16) * DH + 32 * ks + 8 * g4);
+    // (everything requested so far is independent of the token counter, whose own load is still on its way; the
+    // ring slot enters only from here on)
+    uint4 p_ld = make_uint4(0, 0, 0, 0);
+    if (popped && tid < 32)   // 16 threads fetch the leaving key row, 16 the value row (16 bytes each)
+        p_ld = reinterpret_cast<const uint4 *>(tid < 16 ? win_k + (size_t)slot * DH : win_v + (size_t)slot * DH)[tid & 15];
     // window keys of this wavefront's tile; the ring slot of the new token is taken from the input
     bf16x8 BWin[4];
     {
@@ -511,18 +541,18 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
         // ---- stage 3: the pair that leaves the cache: smallest error, ties -> larger token index
         // (every wavefront does the same search, which saves a barrier)
         {
-            float bs = INFINITY; int bi = -1, be = 0;
+            // one 64-bit key per candidate: the bits of the squared error (>= 0, so they order like an integer), then
+            // the reversed token index; the smallest key is the pair to fold and keys are distinct
+            unsigned long long kb = ~0ull; int be = 0;
             for (int e = lane; e <= LAM; e += WAVE) {
                 const float sc = part[0][e] + part[1][e] + part[2][e] + part[3][e];
                 const int ix = e < LAM ? idx_l[e] : pidx;
-                if (sc < bs || (sc == bs && ix > bi)) { bs = sc; bi = ix; be = e; }
+                const unsigned long long ke = ((unsigned long long)(__float_as_uint(sc) & 0x7FFFFFFFu) << 32) | (uint32_t)(0x7FFFFFFF - ix);
+                if (ke < kb) { kb = ke; be = e; }
             }
-#pragma unroll
-            for (int o = WAVE / 2; o > 0; o >>= 1) {
-                float os = __shfl_xor(bs, o, WAVE); int oi = __shfl_xor(bi, o, WAVE), oe = __shfl_xor(be, o, WAVE);
-                if (os < bs || (os == bs && oi > bi)) { bs = os; bi = oi; be = oe; }
-            }
-            drop = be;
+            const unsigned long long kmin = wmin_u64(kb);
+            const unsigned long long owner = __ballot(kb == kmin);
+            drop = __builtin_amdgcn_readlane(be, (int)__builtin_ctzll(owner));
         }
         LOLA_STAMP(5);
         // phi and v of the folded pair (phi from its bf16 high + low parts)
