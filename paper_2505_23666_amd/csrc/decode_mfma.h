@@ -242,19 +242,19 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     const uint4 q_ld = (tid >= 64 && tid < 64 + G * 16) ? reinterpret_cast<const uint4 *>(qg)[tid - 64] : make_uint4(0, 0, 0, 0);
     const float4 s_ld = tid < D / 4 ? reinterpret_cast<const float4 *>(sg)[tid] : make_float4(0.f, 0.f, 0.f, 0.f);
     const int idx_ld = tid < LAM ? sp_idx[tid] : 0;
-    // row `lane` of this wavefront's W_q (projection on the vector ALUs, lane = projection index)
+    // W_q of this wavefront's query head, read as whole 1 KB pieces: piece `it` holds projections 4 it .. 4 it + 3, lane l
+    // the 8 inputs 8 (l % 16) .. of projection 4 it + l / 16 (each row's dot product is finished by a row reduction)
     uint4 wq[16];
     {
-        const bf16_t *Wq = a.Wq + (((size_t)h * G + (w < G ? w : 0)) * M + lane) * DH;
+        const bf16_t *Wq = a.Wq + ((size_t)h * G + (w < G ? w : 0)) * M * DH;
 #pragma unroll
-        for (int it = 0; it < 16; it++) wq[it] = reinterpret_cast<const uint4 *>(Wq)[it];
+        for (int it = 0; it < 16; it++) wq[it] = reinterpret_cast<const uint4 *>(Wq)[64 * it + lane];
     }
-    // W_k as MFMA A operand (row = projection, k = input index): [projection tile][k-step]
-    bf16x8 AW[4][4];
+    // W_k crosses the cache hierarchy once per workgroup: each wavefront fetches a quarter (16 projections, 4 KB,
+    // whole lines) and the MFMA A operands are read back from LDS, where the feature tile is not in use yet
+    uint4 wk_ld[4];
 #pragma unroll
-    for (int mt = 0; mt < 4; mt++)
-#pragma unroll
-        for (int ks = 0; ks < 4; ks++) AW[mt][ks] = ld_bf16x8(Wk + (size_t)(16 * mt + r16) * DH + 32 * ks + 8 * g4);
+    for (int it = 0; it < 4; it++) wk_ld[it] = reinterpret_cast<const uint4 *>(Wk)[256 * w + 64 * it + lane];
     // cached key rows of this wavefront's tiles, already in MFMA B-operand form (column = key, k = input index)
     bf16x8 BK[TPW][4];
 #pragma unroll
@@ -287,8 +287,22 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     }
     if (tid >= 64 && tid < 64 + G * 16) reinterpret_cast<uint4 *>(qb)[tid - 64] = q_ld;
     if (tid >= 128 && tid < 128 + 2 * XR * D / 8) reinterpret_cast<uint4 *>(PX)[tid - 128] = make_uint4(0, 0, 0, 0);
+    // W_k staging: row j = projection, 16-byte piece p at position p ^ (j % 16) (the swizzle of the feature tile)
+#pragma unroll
+    for (int it = 0; it < 4; it++) {
+        const int j = 16 * w + 4 * it + (lane >> 4), pc = lane & 15;
+        *reinterpret_cast<uint4 *>(&PB[j * DH + ((pc ^ (j & 15)) << 3)]) = wk_ld[it];
+    }
     __syncthreads();
     LOLA_STAMP(1);
+    // W_k as MFMA A operand (row = projection, k = input index): [projection tile][k-step]
+    bf16x8 AW[4][4];
+#pragma unroll
+    for (int mt = 0; mt < 4; mt++)
+#pragma unroll
+        for (int ks = 0; ks < 4; ks++)
+            AW[mt][ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(&PB[(16 * mt + r16) * DH + (((4 * ks + g4) ^ r16) << 3)]));
+    __syncthreads();   // every wavefront holds its operands: the staging area may become the feature tile
     // ---- query rows as MFMA A operand (rows >= G are zero)
     bf16x8 AQ[4];
 #pragma unroll
@@ -319,16 +333,20 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     }
 
     LOLA_STAMP(10);
-    // ---- stage 1a: phi of this wavefront's query: z_lane = w_lane . q; stored as bf16 high + low parts in the
-    // operand layout of the recall GEMM (row w + 1 of the extra tile)
+    // ---- stage 1a: phi of this wavefront's query; stored as bf16 high + low parts in the operand layout of the
+    // recall GEMM (row w + 1 of the extra tile).  Each 1 KB piece of W_q yields four projections: eight products per
+    // lane, then a reduction over the 16 lanes of a row; lane (r16, g4) keeps projection j = 4 r16 + g4.
     if (steady && w < G) {
+        const uint4 xq = reinterpret_cast<const uint4 *>(qb[w])[lane & 15];
         float z = 0.f;
 #pragma unroll
         for (int it = 0; it < 16; it++) {
-            const uint4 xv = reinterpret_cast<const uint4 *>(qb[w])[it];
-            z = dot2bf(wq[it].x, xv.x, z); z = dot2bf(wq[it].y, xv.y, z);
-            z = dot2bf(wq[it].z, xv.z, z); z = dot2bf(wq[it].w, xv.w, z);
+            float pz = dot2bf(wq[it].x, xq.x, 0.f); pz = dot2bf(wq[it].y, xq.y, pz);
+            pz = dot2bf(wq[it].z, xq.z, pz); pz = dot2bf(wq[it].w, xq.w, pz);
+            pz += dpp_f<0xB1>(pz); pz += dpp_f<0x4E>(pz); pz += dpp_f<0x141>(pz); pz += dpp_f<0x140>(pz);
+            if (r16 == it) z = pz;
         }
+        const int j = 4 * r16 + g4;
         float pp, pn;
         if (a.phi_kind == 1) { pp = fexp2(z * LOG2E); pn = fexp2(-z * LOG2E); }
         else {
@@ -336,13 +354,13 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
             const float ep = fexp2((z - zmax) * LOG2E), en = fexp2((zmin - z) * LOG2E);
             pp = ep / wsum(ep); pn = en / wsum(en);
         }
-        const float dn = wsum(fmaf(pp, s_l[lane], pn * s_l[M + lane]));
+        const float dn = wsum(fmaf(pp, s_l[j], pn * s_l[M + j]));
         if (lane == 0) denq[w] = dn;
         // feature f sits in chunk (f / 32) * 4 + (f / 4) % 4, element 4 * ((f / 16) % 2) + f % 4
         const int row = w + 1;
 #pragma unroll
         for (int half = 0; half < 2; half++) {
-            const int f = half * M + lane;
+            const int f = half * M + j;
             const float val = half ? pn : pp;
             const int addr = row * D + (((((f >> 5) << 2) | ((f >> 2) & 3)) ^ row) << 3) + (((f >> 4) & 1) << 2) + (f & 3);
             const __bf16 hi = (__bf16)val;
