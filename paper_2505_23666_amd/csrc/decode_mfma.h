@@ -205,6 +205,7 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     __shared__ __attribute__((aligned(16))) uint16_t pkb[DH];
     __shared__ __attribute__((aligned(16))) uint16_t pvb[DH];
     __shared__ int idx_l[LAM];
+    __shared__ __attribute__((aligned(16))) float zx[M];   // projections of the leaving key
     uint16_t *Vl = PB;                                                  // [KPAD][VLS] after the recall GEMM
     uint16_t *Ph = PB + KPAD * VLS, *Pl = Ph + G * KPAD;               // [G][KPAD] weights, high / low parts
 
@@ -242,6 +243,11 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     const uint4 q_ld = (tid >= 64 && tid < 64 + G * 16) ? reinterpret_cast<const uint4 *>(qg)[tid - 64] : make_uint4(0, 0, 0, 0);
     const float4 s_ld = tid < D / 4 ? reinterpret_cast<const float4 *>(sg)[tid] : make_float4(0.f, 0.f, 0.f, 0.f);
     const int idx_ld = tid < LAM ? sp_idx[tid] : 0;
+    // W_k crosses the cache hierarchy once per workgroup: each wavefront fetches a quarter (16 projections, 4 KB,
+    // whole lines) and the MFMA A operands are read back from LDS, where the feature tile is not in use yet
+    uint4 wk_ld[4];
+#pragma unroll
+    for (int it = 0; it < 4; it++) wk_ld[it] = reinterpret_cast<const uint4 *>(Wk)[256 * w + 64 * it + lane];
     // W_q of this wavefront's query head, read as whole 1 KB pieces: piece `it` holds projections 4 it .. 4 it + 3, lane l
     // the 8 inputs 8 (l % 16) .. of projection 4 it + l / 16 (each row's dot product is finished by a row reduction)
     uint4 wq[16];
@@ -250,11 +256,6 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
 #pragma unroll
         for (int it = 0; it < 16; it++) wq[it] = reinterpret_cast<const uint4 *>(Wq)[64 * it + lane];
     }
-    // W_k crosses the cache hierarchy once per workgroup: each wavefront fetches a quarter (16 projections, 4 KB,
-    // whole lines) and the MFMA A operands are read back from LDS, where the feature tile is not in use yet
-    uint4 wk_ld[4];
-#pragma unroll
-    for (int it = 0; it < 4; it++) wk_ld[it] = reinterpret_cast<const uint4 *>(Wk)[256 * w + 64 * it + lane];
     // cached key rows of this wavefront's tiles, already in MFMA B-operand form (column = key, k = input index)
     bf16x8 BK[TPW][4];
 #pragma unroll
@@ -387,6 +388,19 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
 #define LOLA_HLOAD(ct, ks, hf) hreg##ct##ks##hf = *reinterpret_cast<const float4 *>(Hg + LOLA_HADDR(ct, ks, hf));
     LOLA_HREP(LOLA_HDECL)
     if (steady) { LOLA_HREP(LOLA_HLOAD) }
+    // cached values at this wavefront's value columns, wanted by the recall epilogue of every key tile: requested here,
+    // right behind the state, so that their trip from HBM overlaps the feature map
+    // (the first half of the tiles; the second half is requested when the recall GEMM starts and has four tiles' worth
+    // of matrix work to arrive)
+    constexpr int NKE = NKT / 2;
+    uint2 vrec[NKT][2];
+#pragma unroll
+    for (int kt = 0; kt < NKT; kt++)
+#pragma unroll
+        for (int ct = 0; ct < 2; ct++) {
+            vrec[kt][ct] = make_uint2(0, 0);
+            if (steady && kt < NKE) vrec[kt][ct] = *reinterpret_cast<const uint2 *>(sp_v + (size_t)(16 * kt + r16) * DH + 32 * w + 16 * ct + 4 * g4);
+        }
 
     // ---- stage 1b: logits Q K^T of this wavefront's key tiles; in steady state z^T = W_k K^T -> phi -> LDS.
     // Wavefront 0 also projects the leaving key (a tile with one real column).
@@ -414,45 +428,62 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     LOLA_STAMP(12);
     if (steady) {
 #pragma unroll
-        for (int t = 0; t <= TPW; t++) {
-            if (t < TPW || w == 0) {
-                // t < TPW: cached keys, rows of PB; t == TPW (wavefront 0): the leaving key, row 0 of the extra tile
-                const int row = t < TPW ? 16 * (w + 4 * t) + r16 : 0;
-                float pp[16], pn[16];
-                phi_from_z(zt[t], a.phi_kind, pp, pn);
-                float dn = 0.f;
+        for (int t = 0; t < TPW; t++) {
+            // cached keys, rows of PB
+            const int row = 16 * (w + 4 * t) + r16;
+            float pp[16], pn[16];
+            phi_from_z(zt[t], a.phi_kind, pp, pn);
+            float dn = 0.f;
 #pragma unroll
-                for (int mt = 0; mt < 4; mt++) {
-                    const float4 sp4 = *reinterpret_cast<const float4 *>(&s_l[16 * mt + 4 * g4]);
-                    const float4 sn4 = *reinterpret_cast<const float4 *>(&s_l[M + 16 * mt + 4 * g4]);
-                    dn = fmaf(pp[4 * mt], sp4.x, dn); dn = fmaf(pp[4 * mt + 1], sp4.y, dn);
-                    dn = fmaf(pp[4 * mt + 2], sp4.z, dn); dn = fmaf(pp[4 * mt + 3], sp4.w, dn);
-                    dn = fmaf(pn[4 * mt], sn4.x, dn); dn = fmaf(pn[4 * mt + 1], sn4.y, dn);
-                    dn = fmaf(pn[4 * mt + 2], sn4.z, dn); dn = fmaf(pn[4 * mt + 3], sn4.w, dn);
-                }
-                dn = grp_sum(dn);
-                // feature order of the recall GEMM: ks 0,1 -> positive half (mt 0,1 / 2,3), ks 2,3 -> negative half;
-                // the lane's eight values of a k-step are exactly chunk 4 ks + g4 of the row
-                bf16x8 hi[4], lo[4];
-                split8(&pp[0], hi[0], lo[0]); split8(&pp[8], hi[1], lo[1]);
-                split8(&pn[0], hi[2], lo[2]); split8(&pn[8], hi[3], lo[3]);
-                if (t < TPW) {
-                    if (g4 == 0) rden_l[row] = dn > 0.f ? 1.0f / dn : 0.f;
+            for (int mt = 0; mt < 4; mt++) {
+                const float4 sp4 = *reinterpret_cast<const float4 *>(&s_l[16 * mt + 4 * g4]);
+                const float4 sn4 = *reinterpret_cast<const float4 *>(&s_l[M + 16 * mt + 4 * g4]);
+                dn = fmaf(pp[4 * mt], sp4.x, dn); dn = fmaf(pp[4 * mt + 1], sp4.y, dn);
+                dn = fmaf(pp[4 * mt + 2], sp4.z, dn); dn = fmaf(pp[4 * mt + 3], sp4.w, dn);
+                dn = fmaf(pn[4 * mt], sn4.x, dn); dn = fmaf(pn[4 * mt + 1], sn4.y, dn);
+                dn = fmaf(pn[4 * mt + 2], sn4.z, dn); dn = fmaf(pn[4 * mt + 3], sn4.w, dn);
+            }
+            dn = grp_sum(dn);
+            // feature order of the recall GEMM: ks 0,1 -> positive half (mt 0,1 / 2,3), ks 2,3 -> negative half;
+            // the lane's eight values of a k-step are exactly chunk 4 ks + g4 of the row
+            bf16x8 hi[4], lo[4];
+            split8(&pp[0], hi[0], lo[0]); split8(&pp[8], hi[1], lo[1]);
+            split8(&pn[0], hi[2], lo[2]); split8(&pn[8], hi[3], lo[3]);
+            if (g4 == 0) rden_l[row] = dn > 0.f ? 1.0f / dn : 0.f;
 #pragma unroll
-                    for (int ks = 0; ks < 4; ks++) {
-                        const int addr = row * D + (((4 * ks + g4) ^ r16) << 3);
-                        *reinterpret_cast<uint4 *>(&PB[addr]) = __builtin_bit_cast(uint4, hi[ks]);
-                        *reinterpret_cast<uint4 *>(&PB[LAM * D + addr]) = __builtin_bit_cast(uint4, lo[ks]);
-                    }
-                } else if (r16 == 0) {
-                    if (g4 == 0) rden_l[KP] = dn > 0.f ? 1.0f / dn : 0.f;
+            for (int ks = 0; ks < 4; ks++) {
+                const int addr = row * D + (((4 * ks + g4) ^ r16) << 3);
+                *reinterpret_cast<uint4 *>(&PB[addr]) = __builtin_bit_cast(uint4, hi[ks]);
+                *reinterpret_cast<uint4 *>(&PB[LAM * D + addr]) = __builtin_bit_cast(uint4, lo[ks]);
+            }
+        }
+        if (w == 0) {
+            // the leaving key (row 0 of the extra tile): its 64 projections sit in the four lanes of column 0; spread
+            // over the wavefront (one projection per lane) the feature map costs a few wave reductions instead of a
+            // whole tile's worth of arithmetic on 15 unused columns
+            if (r16 == 0) {
 #pragma unroll
-                    for (int ks = 0; ks < 4; ks++) {
-                        const int addr = ((4 * ks + g4) << 3);   // row 0: no swizzle
-                        *reinterpret_cast<uint4 *>(&PX[addr]) = __builtin_bit_cast(uint4, hi[ks]);
-                        *reinterpret_cast<uint4 *>(&PX[XR * D + addr]) = __builtin_bit_cast(uint4, lo[ks]);
-                    }
-                }
+                for (int mt = 0; mt < 4; mt++)
+                    *reinterpret_cast<float4 *>(&zx[16 * mt + 4 * g4]) = make_float4(zt[TPW][mt][0], zt[TPW][mt][1], zt[TPW][mt][2], zt[TPW][mt][3]);
+            }
+            const float z = zx[lane];
+            float pp, pn;
+            if (a.phi_kind == 1) { pp = fexp2(z * LOG2E); pn = fexp2(-z * LOG2E); }
+            else {
+                const float zmax = wmax(z), zmin = wmin(z);
+                const float ep = fexp2((z - zmax) * LOG2E), en = fexp2((zmin - z) * LOG2E);
+                pp = ep / wsum(ep); pn = en / wsum(en);
+            }
+            const float dn = wsum(fmaf(pp, s_l[lane], pn * s_l[M + lane]));
+            if (lane == 0) rden_l[KP] = dn > 0.f ? 1.0f / dn : 0.f;
+#pragma unroll
+            for (int half = 0; half < 2; half++) {
+                const int f = half * M + lane;
+                const float val = half ? pn : pp;
+                const int addr = ((((f >> 5) << 2) | ((f >> 2) & 3)) << 3) + (((f >> 4) & 1) << 2) + (f & 3);   // row 0: no swizzle
+                const __bf16 hi = (__bf16)val;
+                PX[addr] = __builtin_bit_cast(uint16_t, hi);
+                PX[XR * D + addr] = __builtin_bit_cast(uint16_t, (__bf16)(val - (float)hi));
             }
         }
     }
@@ -493,22 +524,21 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
         LOLA_STAMP(3);
         // Key tiles 0..NKT-1 are the cache slots; tile NKT is the extra tile (column 0: the leaving key, columns 1..G:
         // the queries, whose "recall" numerators are the linear read-out).  C layout: lane (column r16, group g4)
-        // holds rows c = 32w + 16ct + 4 g4 + i.  The cached values v[key][c..c+3] are requested one tile ahead.
-        uint2 vnext[2];
+        // holds rows c = 32w + 16ct + 4 g4 + i.
 #pragma unroll
-        for (int ct = 0; ct < 2; ct++) vnext[ct] = *reinterpret_cast<const uint2 *>(sp_v + (size_t)r16 * DH + 32 * w + 16 * ct + 4 * g4);
+        for (int kt = NKE; kt < NKT; kt++)
+#pragma unroll
+            for (int ct = 0; ct < 2; ct++)
+                vrec[kt][ct] = *reinterpret_cast<const uint2 *>(sp_v + (size_t)(16 * kt + r16) * DH + 32 * w + 16 * ct + 4 * g4);
 #pragma unroll
         for (int kt = 0; kt <= NKT; kt++) {
-            uint2 vcur[2] = {vnext[0], vnext[1]};
-            if (kt + 1 < NKT) {
-#pragma unroll
-                for (int ct = 0; ct < 2; ct++)
-                    vnext[ct] = *reinterpret_cast<const uint2 *>(sp_v + (size_t)(16 * (kt + 1) + r16) * DH + 32 * w + 16 * ct + 4 * g4);
-            }
             const uint16_t *bh = kt < NKT ? PB + (16 * kt + r16) * D : PX + (r16 < XR ? r16 : 0) * D;
             const uint16_t *bl = kt < NKT ? bh + LAM * D : bh + XR * D;
             const int swz = kt < NKT ? r16 : (r16 < XR ? r16 : 0);
+            // three passes (high x high, high x low, low x high), each with accumulators of its own: six independent
+            // chains keep the matrix pipe from waiting on its own results
             f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}}, acc2[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+            f32x4 acc3[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
             for (int ks = 0; ks < 4; ks++) {
                 const int off = ((4 * ks + g4) ^ swz) << 3;
@@ -519,15 +549,17 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
 #pragma unroll
                 for (int ct = 0; ct < 2; ct++) acc2[ct] = mfma16(Ahi[ct][ks], Bl, acc2[ct]);
 #pragma unroll
-                for (int ct = 0; ct < 2; ct++) acc2[ct] = mfma16(Alo[ct][ks], Bh, acc2[ct]);
+                for (int ct = 0; ct < 2; ct++) acc3[ct] = mfma16(Alo[ct][ks], Bh, acc3[ct]);
             }
+#pragma unroll
+            for (int ct = 0; ct < 2; ct++) acc2[ct] += acc3[ct];
             if (kt < NKT) {
                 const float rd = rden_l[16 * kt + r16];
                 float e2 = 0.f;
 #pragma unroll
                 for (int ct = 0; ct < 2; ct++) {
                     const f32x4 p = acc[ct] + acc2[ct];
-                    const uint2 vv = vcur[ct];
+                    const uint2 vv = vrec[kt < NKT ? kt : 0][ct];
                     const float e0 = fmaf(p[0], rd, -bf_lo(vv.x)), e1 = fmaf(p[1], rd, -bf_hi(vv.x));
                     const float e2_ = fmaf(p[2], rd, -bf_lo(vv.y)), e3 = fmaf(p[3], rd, -bf_hi(vv.y));
                     e2 = fmaf(e0, e0, e2); e2 = fmaf(e1, e1, e2); e2 = fmaf(e2_, e2_, e2); e2 = fmaf(e3, e3, e2);
