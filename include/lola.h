@@ -88,7 +88,8 @@ lola_status lola_state_init(const lola_config *cfg, const lola_state *st, void *
 
 /*
  * Chunkwise prefill of T >= 0 tokens per sequence (Sec. 3 "Chunkwise Inference"; appendix
- * update_chunk).  For each chunk of C tokens (the last may be shorter):
+ * update_chunk).  T == 0 returns LOLA_OK without looking at the token or workspace pointers.
+ * For each chunk of C tokens (the last may be shorter):
  *   1. every query t of the chunk, every query head:
  *        y_t = [phi(q_t)^T H + sum_i exp(scale q_t.k_i) v_i] / [phi(q_t)^T s + sum_i exp(scale q_t.k_i)]
  *      with i over the sparse cache, the window and the tokens <= t of the chunk, all memories as

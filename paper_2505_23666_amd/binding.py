@@ -142,6 +142,11 @@ class LolaLayer:
         with torch.cuda.device(self.device):
             lola_state_init(self.cfg, self.st)
 
+    @property
+    def lola_path(self):
+        """Kernel families (prefill, generation step) this configuration runs on."""
+        return lola_kernel_path(self.cfg, 0), lola_kernel_path(self.cfg, 1)
+
     def reset(self):
         with torch.cuda.device(self.device):
             lola_state_init(self.cfg, self.st)

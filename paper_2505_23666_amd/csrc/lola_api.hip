@@ -305,6 +305,7 @@ lola_status lola_prefill(const lola_config *c, const lola_state *st, const void 
     rc = check_state(c, st);
     if (rc != LOLA_OK) return rc;
     if (T < 0) return LOLA_ERR_SHAPE;
+    if (T == 0) return LOLA_OK;   // nothing to read or write: the token pointers are not looked at
     if ((q == nullptr) != (out == nullptr)) return LOLA_ERR_NULL;
     if (!k || !v || !Wk || (q && !Wq)) return LOLA_ERR_NULL;
     const void *ps[] = {q, k, v, Wq, Wk, out, sel_trace, workspace};
@@ -312,7 +313,6 @@ lola_status lola_prefill(const lola_config *c, const lola_state *st, const void 
     size_t need_min = 0;
     lola_prefill_workspace_bytes(c, T, q != nullptr, &need_min);
     if (!workspace || workspace_bytes < need_min) return LOLA_ERR_WORKSPACE;
-    if (T == 0) return LOLA_OK;
     if (c->dtype == LOLA_F32)
         return run_prefill<float>(c, st, q, k, v, Wq, Wk, T, out, sel_trace, workspace, workspace_bytes, (hipStream_t)stream);
     return run_prefill<bf16_t>(c, st, q, k, v, Wq, Wk, T, out, sel_trace, workspace, workspace_bytes, (hipStream_t)stream);

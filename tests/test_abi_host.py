@@ -80,4 +80,5 @@ def test_arguments_rejected_before_launch(L):
     assert p(c, st, vp(fake), vp(fake), vp(fake), -1, vp(fake), 1 << 40) == -2      # negative T
     assert p(c, st, vp(fake), vp(fake), vp(fake), 64, None, 0) == -6                 # no workspace
     assert p(c, st, vp(fake), vp(fake), vp(fake), 64, vp(fake), 1024) == -6          # workspace too small
+    assert p(c, st, None, None, None, 0, None, 0) == 0                                # T = 0: nothing is touched
     assert L.lola_state_init(C.byref(c), C.byref(bad_st), None) == -1

@@ -164,6 +164,44 @@ def test_bf16_outputs():
     say("bf16 out", rep)
 
 
+def test_bf16_outputs_on_the_mfma_kernels():
+    """bf16 output storage through the MFMA prefill and generation-step kernels (8B head shape)."""
+    sh = wl.scaled(3, B=1, T=64 * 5, n_decode=6)
+    Wq, Wk = wl.weights(sh)
+    q, k, v, _ = wl.sequence_inputs(sh)
+    T = sh.T
+    layer, o, rep = P.prefill_parity(sh, q[:, :, :T], k[:, :, :T], v[:, :, :T], Wq, Wk, out_dtype="bf16")
+    rep2 = P.decode_parity(sh, layer, o, *steps(q, k, v, T, sh.n_decode), Wq, Wk, out_dtype="bf16")
+    say("bf16 out, mfma kernels", rep, rep2)
+    assert layer.lola_path == ("mfma", "mfma")
+
+
+def test_empty_prefill_call_changes_nothing():
+    """T = 0 is accepted and leaves the memories as they were (checked bit for bit)."""
+    sh = wl.scaled(3, B=1, T=64 * 4)
+    Wq, Wk = wl.weights(sh)
+    q, k, v, _ = wl.sequence_inputs(sh)
+    layer, o, _ = P.prefill_parity(sh, q, k, v, Wq, Wk)
+    before = [getattr(layer, n).clone() for n in ("H", "s", "win_k", "win_v", "sp_k", "sp_v", "sp_idx", "sp_count", "n_tokens")]
+    e = torch.empty((sh.B, sh.Hkv, 0, sh.d), dtype=torch.bfloat16, device=layer.device)
+    eq = torch.empty((sh.B, sh.Hq, 0, sh.d), dtype=torch.bfloat16, device=layer.device)
+    out = layer.prefill(eq, e, e.clone(), P.w_to_dev(Wq, sh.dtype), P.w_to_dev(Wk, sh.dtype))
+    torch.cuda.synchronize()
+    assert out.shape == (sh.B, sh.Hq, 0, sh.d)
+    for a, n in zip(before, ("H", "s", "win_k", "win_v", "sp_k", "sp_v", "sp_idx", "sp_count", "n_tokens")):
+        assert torch.equal(a, getattr(layer, n)), n
+
+
+def test_maximum_sizes_generic_family():
+    """Largest head and feature dimensions the interface admits (d = 256, D = 512), with a cache larger than the
+    window and a chunk that is not a divisor of anything."""
+    sh = wl.Shape("maxdims", "bf16", 1, 2, 1, 256, 512, T=75, eta=12, lam=20, C=10, seed=0)
+    q, k, v, Wq, Wk = rand_case(77, 1, 2, 1, 256, 512, 75 + 4, "bf16")
+    layer, o, rep = P.prefill_parity(sh, q[:, :, :75], k[:, :, :75], v[:, :, :75], Wq, Wk)
+    rep2 = P.decode_parity(sh, layer, o, *steps(q, k, v, 75, 4), Wq, Wk)
+    say("max dims", rep, rep2)
+
+
 def test_run_to_run_determinism():
     sh = wl.scaled(3, B=1, T=512)
     Wq, Wk = wl.weights(sh)
