@@ -262,9 +262,9 @@ __global__ __launch_bounds__(256, 1) void scan_fast_kernel(generic::PrefillArgs<
     __shared__ __attribute__((aligned(16))) float s_l[D];
     __shared__ float dn_l[NE];               // phi(k).s
     __shared__ float part[3][4][NE];         // per wavefront: |P|^2, P.v, |v|^2 over its 32 value columns
-    __shared__ __attribute__((aligned(16))) unsigned long long key[NE];
+    __shared__ uint32_t skey[NE];            // bit patterns of the squared errors
     __shared__ int cidx[NE];
-    __shared__ int keep[NE];
+    __shared__ int ne_s;
     __shared__ int flist[C], ecand[C], eslot[C];
     static_assert(2 * RB * D * 2 >= 4 * (4 * NE + 2 * C + 8 + 32 * (3 * DH + D + 1)), "the generic per-chunk routine borrows the phi tile as scratch (tiles of <= 32 rows)");
 
@@ -531,48 +531,58 @@ __global__ __launch_bounds__(256, 1) void scan_fast_kernel(generic::PrefillArgs<
         }
 
         if (j == a.j1 - 1) LOLA_STAMP(5);
-        // ---- 3. rank by (score descending, token index ascending); the first LAM stay.  The squared error is
-        // |P|^2 / (phi.s)^2 - 2 P.v / (phi.s) + |v|^2 (recall = 0 while phi.s = 0, i.e. nothing folded yet).  Both
-        // criteria are packed into one 64-bit key (the bit pattern of a float >= 0 orders like an integer), so the
-        // keys are distinct and exactly LAM candidates have fewer than LAM keys above theirs.
+        // ---- 3. selection: the 64 candidates with the smallest squared error are folded (order: score descending,
+        // token index ascending, the first LAM stay).  The squared error is |P|^2 / (phi.s)^2 - 2 P.v / (phi.s) + |v|^2
+        // (recall = 0 while phi.s = 0, i.e. nothing folded yet); the bit pattern of a float >= 0 orders like an integer.
         for (int e = tid; e < NE; e += 256) {
             const float dn = dn_l[e], rd = dn > 0.f ? 1.0f / dn : 0.f;
             const float sa = part[0][0][e] + part[0][1][e] + part[0][2][e] + part[0][3][e];
             const float sb = part[1][0][e] + part[1][1][e] + part[1][2][e] + part[1][3][e];
             const float sc = part[2][0][e] + part[2][1][e] + part[2][2][e] + part[2][3][e];
             const float sq = fmaxf(fmaf(rd * rd, sa, fmaf(-2.0f * rd, sb, sc)), 0.f);
-            key[e] = ((unsigned long long)(__float_as_uint(sq) & 0x7FFFFFFFu) << 32) | (uint32_t)(0x7FFFFFFF - cidx[e]);
-        }
-        __syncthreads();
-        {
-            // every wavefront holds all keys (NK per lane) and ranks 16 lanes' worth of each register: the candidate's
-            // key is broadcast, compared by all lanes, and the votes are counted on the scalar unit
-            unsigned long long kreg[NK];
-#pragma unroll
-            for (int x = 0; x < NK; x++) kreg[x] = key[64 * x + lane];
-#pragma unroll
-            for (int x = 0; x < NK; x++) {
-                const uint32_t klo = (uint32_t)kreg[x], khi = (uint32_t)(kreg[x] >> 32);
-#pragma unroll 4
-                for (int l = 16 * w; l < 16 * w + 16; l++) {
-                    const unsigned long long ke = ((unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)khi, l) << 32) |
-                                                  (uint32_t)__builtin_amdgcn_readlane((int)klo, l);
-                    int cnt = 0;
-#pragma unroll
-                    for (int y = 0; y < NK; y++) cnt += __popcll(__ballot(kreg[y] > ke));
-                    if (lane == 0) keep[64 * x + l] = cnt < LAM;
-                }
-            }
+            skey[e] = __float_as_uint(sq) & 0x7FFFFFFFu;
         }
         __syncthreads();
         if (j == a.j1 - 1) LOLA_STAMP(6);
-        // lists (one wavefront, ballots): candidates to fold; entrants paired with the slots of the leavers
+        // One wavefront holds all scores (NK per lane) and finds the 64th smallest by building it bit by bit: a trial
+        // value is kept when fewer than 64 scores lie below it (votes counted on the scalar unit).  Scores equal to
+        // the threshold are folded too if that makes exactly 64; otherwise (exact ties across the cut) the same search
+        // over their token indices picks the largest ones.  The lists follow from the fold predicate by ballots:
+        // candidates to fold; entrants paired with the slots of the leavers.
         if (w == 0) {
+            uint32_t sb[NK]; int ix[NK];
+#pragma unroll
+            for (int x = 0; x < NK; x++) { sb[x] = skey[64 * x + lane]; ix[x] = cidx[64 * x + lane]; }
+            uint32_t thr = 0;
+#pragma unroll 1
+            for (int bit = 30; bit >= 0; bit--) {
+                const uint32_t trial = thr | (1u << bit);
+                int c = 0;
+#pragma unroll
+                for (int x = 0; x < NK; x++) c += __popcll(__ballot(sb[x] < trial));
+                if (c < C) thr = trial;
+            }
+            int n_lt = 0, n_eq = 0;
+#pragma unroll
+            for (int x = 0; x < NK; x++) { n_lt += __popcll(__ballot(sb[x] < thr)); n_eq += __popcll(__ballot(sb[x] == thr)); }
+            const int need = C - n_lt;      // 1 <= need <= n_eq
+            uint32_t imin = 0;              // ties are folded from token index imin upwards
+            if (n_eq != need) {
+#pragma unroll 1
+                for (int bit = 30; bit >= 0; bit--) {
+                    const uint32_t trial = imin | (1u << bit);
+                    int c = 0;
+#pragma unroll
+                    for (int x = 0; x < NK; x++) c += __popcll(__ballot(sb[x] == thr && (uint32_t)ix[x] >= trial));
+                    if (c >= need) imin = trial;
+                }
+            }
             int nf = 0, nen = 0, nlv = 0;
-            for (int e0 = 0; e0 < NE; e0 += 64) {
-                const int e = e0 + lane;
-                const bool kp = keep[e];
-                const bool fo = !kp, en = kp && e >= LAM, lv = fo && e < LAM;
+#pragma unroll
+            for (int x = 0; x < NK; x++) {
+                const int e = 64 * x + lane;
+                const bool fo = sb[x] < thr || (sb[x] == thr && (uint32_t)ix[x] >= imin);
+                const bool en = !fo && e >= LAM, lv = fo && e < LAM;
                 const unsigned long long mf = __ballot(fo), me = __ballot(en), ml = __ballot(lv);
                 const unsigned long long below = (1ull << lane) - 1ull;
                 if (fo) flist[nf + __popcll(mf & below)] = e;
@@ -580,11 +590,11 @@ __global__ __launch_bounds__(256, 1) void scan_fast_kernel(generic::PrefillArgs<
                 if (lv) eslot[nlv + __popcll(ml & below)] = e;
                 nf += __popcll(mf); nen += __popcll(me); nlv += __popcll(ml);
             }
+            if (lane == 0) ne_s = nen;
         }
         __syncthreads();
-        // exactly LAM stay, so 64 are folded and entrants and leavers pair up; count the entrants again for the copy
-        int ne = 0;
-        for (int e = LAM; e < NE; e++) ne += keep[e];
+        // exactly 64 are folded, so entrants and leavers pair up
+        const int ne = ne_s;
         if (j == a.j1 - 1) LOLA_STAMP(7);
 
         // ---- 4. fold: operands of the folded pairs transposed into LDS, then H[f][c] += sum_e phi_e[f] v_e[c].
@@ -663,13 +673,22 @@ __global__ __launch_bounds__(256, 1) void scan_fast_kernel(generic::PrefillArgs<
                     const int c = 32 * w + 16 * ct + r16;
                     Bv[ct][k2] = as_bf16x8(*reinterpret_cast<const uint4 *>(&VT[c * C + (((4 * k2 + g4) ^ tswz(c)) << 3)]));
                 }
-#define LOLA_SFOLD(ct, ks, hf) { const int f = 16 * (2 * ks + hf) + r16; \
-            _Pragma("unroll") for (int pt = 0; pt < 2; pt++) \
-            _Pragma("unroll") for (int k2 = 0; k2 < 2; k2++) { \
-                const bf16x8 Ap = as_bf16x8(*reinterpret_cast<const uint4 *>(&PT[pt * D * C + f * C + (((4 * k2 + g4) ^ tswz(f)) << 3)])); \
-                hreg##ct##ks##hf = mfma16(Ap, Bv[ct][k2], hreg##ct##ks##hf); } }
-            LOLA_SREP(LOLA_SFOLD)
-#undef LOLA_SFOLD
+            // per feature tile (16 features): four A operands (high / low part x two k-steps) serve both value tiles of
+            // the wavefront; the operands of the next tile are read from LDS before this tile's MFMAs are issued
+            bf16x8 Ac[4], An[4];
+#define LOLA_SFA(dst, mt) _Pragma("unroll") for (int x = 0; x < 4; x++) { const int f = 16 * (mt) + r16; \
+                dst[x] = as_bf16x8(*reinterpret_cast<const uint4 *>(&PT[(x >> 1) * D * C + f * C + (((4 * (x & 1) + g4) ^ tswz(f)) << 3)])); }
+            LOLA_SFA(Ac, 0)
+#define LOLA_SFOLD2(ks, hf) { if (2 * ks + hf + 1 < 8) { LOLA_SFA(An, 2 * ks + hf + 1) } \
+            _Pragma("unroll") for (int x = 0; x < 4; x++) { \
+                hreg0##ks##hf = mfma16(Ac[x], Bv[0][x & 1], hreg0##ks##hf); \
+                hreg1##ks##hf = mfma16(Ac[x], Bv[1][x & 1], hreg1##ks##hf); } \
+            __builtin_amdgcn_sched_barrier(0); \
+            _Pragma("unroll") for (int x = 0; x < 4; x++) Ac[x] = An[x]; }
+            LOLA_SFOLD2(0, 0) LOLA_SFOLD2(0, 1) LOLA_SFOLD2(1, 0) LOLA_SFOLD2(1, 1)
+            LOLA_SFOLD2(2, 0) LOLA_SFOLD2(2, 1) LOLA_SFOLD2(3, 0) LOLA_SFOLD2(3, 1)
+#undef LOLA_SFOLD2
+#undef LOLA_SFA
             if (tid < D) {
                 const int f = tid;
                 float acc = 0.f;
