@@ -331,6 +331,7 @@ struct PrefillArgs {
     int R;                    // rows per scoring tile
     int QT;                   // queries per attend tile
     int snap_split;           // 1: H snapshots are written as bf16 high + low parts in MFMA operand order (D = d = 128)
+    uint16_t *phiK;           // [B*Hkv][S][C][2][D] phi of the pass's keys, bf16 high + low parts (MFMA state-evolution kernel only)
 };
 
 template <typename T>
@@ -413,14 +414,18 @@ __device__ void scan_chunk(const PrefillArgs<T> &a, const int si, const int j, i
             float *sH = a.snapH + sj * D * d, *sS = a.snapS + sj * D;
             int32_t *sG = a.snapG + sj * lam;
             if (a.snap_split) {
-                // [part][c][16-byte chunk][element]: feature f sits in chunk (f/32)*4 + (f/4)%4, element 4*((f/16)%2) + f%4
+                // feature f sits in 16-byte piece (f/32)*4 + (f/4)%4, element 4*((f/16)%2) + f%4 of its row; pieces are
+                // ordered [part][row block of 32][row tile of 16][piece / 4][16 (piece % 4) + row % 16] (the order in
+                // which the MFMA kernels hold them, one contiguous 1 KB per wavefront store)
                 uint16_t *s16 = reinterpret_cast<uint16_t *>(sH);
                 for (int idx = tid; idx < D * d; idx += NT) {
                     const int c = idx / D, f = idx - c * D;
                     const float x = H[idx];
                     const uint16_t hi = f32_to_bf16_bits(x);
                     const float r = x - __uint_as_float(((uint32_t)hi) << 16);
-                    const int pos = c * D + (((((f >> 5) << 2) | ((f >> 2) & 3))) << 3) + ((((f >> 4) & 1) << 2) | (f & 3));
+                    const int piece = ((f >> 5) << 2) | ((f >> 2) & 3);
+                    const int pos = ((((((c >> 5) * 2 + ((c >> 4) & 1)) * 4 + (piece >> 2)) * 64) + 16 * (piece & 3) + (c & 15)) << 3) +
+                                    ((((f >> 4) & 1) << 2) | (f & 3));
                     s16[pos] = hi;
                     s16[D * d + pos] = f32_to_bf16_bits(r);
                 }

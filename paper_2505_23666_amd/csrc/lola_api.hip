@@ -93,9 +93,23 @@ int attend_tile_queries(const Dims &dm) {
 
 #define LAUNCH_CHECK() do { if (hipGetLastError() != hipSuccess) return LOLA_ERR_HIP; } while (0)
 
+// The fused MFMA generation step covers the Llama-8B head shape with bf16 storage.
+bool fast_decode_ok(const lola_config *c) {
+    return c->dtype == LOLA_BF16 && c->head_dim == 128 && c->feat_dim == 128 && c->window == 64 &&
+           (c->sparse_budget == 128 || c->sparse_budget == 64) && c->n_q_heads / c->n_kv_heads == 4;
+}
+
+// The MFMA output kernel of the prefill covers the same head shape with chunk = window = 64.
+bool fast_attend_ok(const lola_config *c) {
+    return c->dtype == LOLA_BF16 && c->head_dim == 128 && c->feat_dim == 128 && c->window == 64 && c->chunk == 64 &&
+           (c->sparse_budget == 64 || c->sparse_budget == 128 || c->sparse_budget == 256) &&
+           c->n_q_heads / c->n_kv_heads == 4;
+}
+
 struct PrefillPlan {
     size_t off_prefK, off_prefV, off_sp_row, off_phiE, off_snap;   // byte offsets
-    size_t snap_bytes_per_chunk;                                    // all streams, one chunk
+    size_t snap_bytes_per_chunk;                                    // all streams, one chunk (snapshots + phi of its keys)
+    size_t phik_bytes_per_chunk;
     size_t fixed_bytes;
 };
 PrefillPlan plan_prefill(const lola_config *c, int with_outputs) {
@@ -110,22 +124,11 @@ PrefillPlan plan_prefill(const lola_config *c, int with_outputs) {
     p.off_snap = off;
     p.fixed_bytes = off;
     p.snap_bytes_per_chunk = with_outputs ? up(ns * D * d * 4) + up(ns * D * 4) + up(ns * (lam ? lam : 1) * 4) : 0;
+    p.phik_bytes_per_chunk = fast_attend_ok(c) ? up(ns * (size_t)c->chunk * D * 4) : 0;   // phi of the chunk's keys, two bf16 parts
+    p.snap_bytes_per_chunk += p.phik_bytes_per_chunk;
     return p;
 }
 
-
-// The fused MFMA generation step covers the Llama-8B head shape with bf16 storage.
-bool fast_decode_ok(const lola_config *c) {
-    return c->dtype == LOLA_BF16 && c->head_dim == 128 && c->feat_dim == 128 && c->window == 64 &&
-           (c->sparse_budget == 128 || c->sparse_budget == 64) && c->n_q_heads / c->n_kv_heads == 4;
-}
-
-// The MFMA output kernel of the prefill covers the same head shape with chunk = window = 64.
-bool fast_attend_ok(const lola_config *c) {
-    return c->dtype == LOLA_BF16 && c->head_dim == 128 && c->feat_dim == 128 && c->window == 64 && c->chunk == 64 &&
-           (c->sparse_budget == 64 || c->sparse_budget == 128 || c->sparse_budget == 256) &&
-           c->n_q_heads / c->n_kv_heads == 4;
-}
 
 template <int LAM, typename TO>
 lola_status launch_fast_decode(const lola_config *c, const lola_state *st, const void *q, const void *k, const void *v,
@@ -191,7 +194,7 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
     a.sp_row = (int32_t *)(ws + p.off_sp_row);
     a.phiE = (float *)(ws + p.off_phiE);
     int S = a.n_chunks > 0 ? a.n_chunks : 1;
-    if (a.want_out) {
+    if (p.snap_bytes_per_chunk > 0) {
         size_t room = (workspace_bytes - p.fixed_bytes) / p.snap_bytes_per_chunk;
         if (room < 1) return LOLA_ERR_WORKSPACE;
         if ((size_t)S > room) S = (int)room;
@@ -202,6 +205,11 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
     a.snapH = (float *)snap;
     a.snapS = (float *)(snap + up(ns * S * D * d * 4));
     a.snapG = (int32_t *)(snap + up(ns * S * D * d * 4) + up(ns * S * D * 4));
+    a.phiK = nullptr;
+    if (p.phik_bytes_per_chunk > 0) {   // behind the snapshot regions (absent in an update-only call)
+        const size_t snaps = a.want_out ? up(ns * S * D * d * 4) + up(ns * S * D * 4) + up(ns * S * (lam ? lam : 1) * 4) : 0;
+        a.phiK = (uint16_t *)(snap + snaps);
+    }
     // the three snapshot regions are each rounded up per pass, which never exceeds S * snap_bytes_per_chunk
 
     const size_t scan_fixed = scan_fixed_floats(a.dm);
@@ -223,6 +231,8 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
         bool scanned = false;
         if constexpr (std::is_same<T, bf16_t>::value) {
             if (fast_attend_ok(c)) {   // same shape conditions as the output kernel
+                hipLaunchKernelGGL(fast::phi_k_kernel, dim3((unsigned)(a.j1 - a.j0), (unsigned)ns), dim3(256), 0, stream, a);
+                LAUNCH_CHECK();
                 if (c->sparse_budget == 64) hipLaunchKernelGGL((fast::scan_fast_kernel<64>), gs, dim3(256), 0, stream, a);
                 else if (c->sparse_budget == 128) hipLaunchKernelGGL((fast::scan_fast_kernel<128>), gs, dim3(256), 0, stream, a);
                 else hipLaunchKernelGGL((fast::scan_fast_kernel<256>), gs, dim3(256), 0, stream, a);
@@ -275,6 +285,9 @@ size_t lola_prefill_workspace_bytes(const lola_config *c, int32_t T, int32_t wit
     size_t nch = ((size_t)T + c->chunk - 1) / c->chunk;
     if (nch < 1) nch = 1;
     if (min_bytes) *min_bytes = p.fixed_bytes + p.snap_bytes_per_chunk;
+    // an update-only call keeps no snapshots; its per-chunk scratch (features of the keys) is only an accelerator, so
+    // the recommended size stops at 64 chunks per pass
+    if (!with_outputs && nch > 64) nch = 64;
     return p.fixed_bytes + nch * p.snap_bytes_per_chunk;
 }
 

@@ -72,7 +72,9 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
         for (int it = 0; it < 4; it++) hv[it] = reinterpret_cast<const uint4 *>(Hsnap)[tid + 256 * (4 * p4 + it)];
 #pragma unroll
         for (int it = 0; it < 4; it++) {
-            const int o = tid + 256 * (4 * p4 + it), part = o >> 11, rem = o & 2047, c = rem >> 4, ch = rem & 15;
+            // snapshot order: [part][row block of 32][row tile of 16][k-step][lane = 16 (piece % 4) + row % 16]
+            const int o = tid + 256 * (4 * p4 + it), part = o >> 11;
+            const int c = 32 * ((o >> 9) & 3) + 16 * ((o >> 8) & 1) + (o & 15), ch = 4 * ((o >> 6) & 3) + ((o >> 4) & 3);
             *reinterpret_cast<uint4 *>(&L[part * DH * D + c * D + ((ch ^ (c & 15)) << 3)]) = hv[it];
         }
     }
@@ -245,6 +247,40 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
 // Any other chunk (warm-up while the cache fills, the first chunks of a sequence, a ragged last chunk)
 // goes through the generic per-chunk routine on the state in global memory.
 
+// phi of the keys of every chunk of a pass (Sec. 2.3 eq. feature_map), chunk-parallel: grid (chunk of the pass, stream),
+// one 16-key tile per wavefront.  The serial state evolution below then only reads these rows (bf16 high + low parts,
+// features in operand order) when the chunk's pairs leave the window one chunk later.
+__global__ __launch_bounds__(256) void phi_k_kernel(generic::PrefillArgs<bf16_t> a) {
+    constexpr int DH = 128, M = 64, D = 128, C = 64;
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r16 = lane & 15, g4 = lane >> 4;
+    const int jj = blockIdx.x, j = a.j0 + jj, si = blockIdx.y, h = si % a.dm.Hkv;
+    const int row = 16 * w + r16, tok = j * C + row;
+    const bf16_t *Wk = a.Wk + (size_t)h * M * DH;
+    const bf16_t *kr = a.k + ((size_t)si * a.T_tokens + tok) * DH;
+    bf16x8 BK[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ks++) BK[ks] = tok < a.T_tokens ? ld_bf16x8(kr + 32 * ks + 8 * g4) : zero_bf16x8();
+    f32x4 zt[4];
+#pragma unroll
+    for (int mt = 0; mt < 4; mt++) {
+        zt[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < 4; ks++)
+            zt[mt] = mfma16(ld_bf16x8(Wk + (size_t)(16 * mt + r16) * DH + 32 * ks + 8 * g4), BK[ks], zt[mt]);
+    }
+    float pp[16], pn[16];
+    phi_from_z(zt, a.dm.phi_kind, pp, pn);
+    bf16x8 hi[4], lo[4];
+    split8(&pp[0], hi[0], lo[0]); split8(&pp[8], hi[1], lo[1]);
+    split8(&pn[0], hi[2], lo[2]); split8(&pn[8], hi[3], lo[3]);
+    uint16_t *dst = a.phiK + (((size_t)si * a.S + jj) * C + row) * 2 * D;
+#pragma unroll
+    for (int ks = 0; ks < 4; ks++) {
+        *reinterpret_cast<uint4 *>(dst + ((4 * ks + g4) << 3)) = __builtin_bit_cast(uint4, hi[ks]);
+        *reinterpret_cast<uint4 *>(dst + D + ((4 * ks + g4) << 3)) = __builtin_bit_cast(uint4, lo[ks]);
+    }
+}
+
 // Chunk swizzle of the transposed fold operands: three bits of the row index r, chosen among the bits that differ
 // between the rows one wavefront writes at once (r2, r3, r5) and between the rows it reads at once (r0 .. r3).
 __device__ __forceinline__ int tswz(int r) { return ((((r >> 5) ^ r) & 1) << 2) | ((r >> 2) & 3); }
@@ -298,11 +334,11 @@ __global__ __launch_bounds__(256, 1) void scan_fast_kernel(generic::PrefillArgs<
 #define LOLA_SSTORE(ct, ks, hf) *reinterpret_cast<f32x4 *>(Hg + LOLA_SADDR(ct, ks, hf)) = hreg##ct##ks##hf;
     LOLA_SREP(LOLA_SDECL)
     bool h_in_regs = false;
-    bool phi_valid = false;     // PERSIST: rows [0, LAM) of PB hold phi of the cache slots, and BKn / vvn the rows requested ahead
-    bf16x8 BKn[4];              // key rows of this wavefront's tile of the pairs that leave the window in the next chunk
+    bool phi_valid = false;     // PERSIST: rows [0, LAM) of PB hold phi of the cache slots, and PHn / vvn the rows requested ahead
+    uint4 PHn[8];               // phi (high pieces, then low pieces) of this wavefront's tile of the pairs that leave the window in the next chunk
     uint2 vvn[4][2];            // their values at this wavefront's columns
 #pragma unroll
-    for (int ks = 0; ks < 4; ks++) BKn[ks] = zero_bf16x8();
+    for (int x = 0; x < 8; x++) PHn[x] = make_uint4(0, 0, 0, 0);
 #pragma unroll
     for (int u = 0; u < 4; u++) { vvn[u][0] = make_uint2(0, 0); vvn[u][1] = make_uint2(0, 0); }
 
@@ -350,7 +386,9 @@ __global__ __launch_bounds__(256, 1) void scan_fast_kernel(generic::PrefillArgs<
             return vr < P ? pV + (size_t)vr * DH : vc + (size_t)(vr - P) * DH;
         };
         const bool have_phi = PERSIST && phi_valid;
-        const int tfirst = have_phi ? TC : 0;   // first tile whose phi is computed in this chunk
+        const int tfirst = have_phi ? NTILE : 0;   // first tile whose phi is computed in this chunk (none if the cache's
+                                                   // rows are in LDS: the leaving pairs' rows were computed by the parallel
+                                                   // feature kernel and requested one chunk ahead)
 
         // ---- 1. operands of the recall GEMM from the fp32 registers (H^T, and s as one more row held by the lanes
         // of row 0); the snapshot for the output kernel is stored further down
@@ -388,10 +426,7 @@ __global__ __launch_bounds__(256, 1) void scan_fast_kernel(generic::PrefillArgs<
 #pragma unroll
             for (int u = 0; u < TPW; u++) {
                 const int t = tp + w + 4 * u;
-                if (u == 0 && have_phi) {
-#pragma unroll
-                    for (int ks = 0; ks < 4; ks++) BK[0][ks] = BKn[ks];
-                } else if (t < t1) {
+                if (t < t1) {
                     const bf16_t *kr = krow(16 * t + r16);
 #pragma unroll
                     for (int ks = 0; ks < 4; ks++) BK[u][ks] = ld_bf16x8(kr + 32 * ks + 8 * g4);
@@ -408,10 +443,22 @@ __global__ __launch_bounds__(256, 1) void scan_fast_kernel(generic::PrefillArgs<
                     for (int ct = 0; ct < 2; ct++) vv[u][ct] = *reinterpret_cast<const uint2 *>(vr + 32 * w + 16 * ct + 4 * g4);
                 }
             }
-            if (PERSIST) {   // this chunk's own pairs leave the window in the next chunk
-                const bf16_t *kr = kc + (size_t)(j * C + 16 * w + r16) * DH;
+            if (PERSIST && have_phi) {   // the rows requested one chunk ago take their place behind the cache's rows
+                const int rl = LAM + 16 * w + r16;
 #pragma unroll
-                for (int ks = 0; ks < 4; ks++) BKn[ks] = ld_bf16x8(kr + 32 * ks + 8 * g4);
+                for (int ks = 0; ks < 4; ks++) {
+                    const int addr = rl * D + (((4 * ks + g4) ^ r16) << 3);
+                    *reinterpret_cast<uint4 *>(&PB[addr]) = PHn[ks];
+                    *reinterpret_cast<uint4 *>(&PB[RB * D + addr]) = PHn[4 + ks];
+                }
+            }
+            if (PERSIST) {   // this chunk's own pairs leave the window in the next chunk
+                const uint16_t *ph = a.phiK + (((size_t)si * a.S + (j - a.j0)) * C + 16 * w + r16) * 2 * D;
+#pragma unroll
+                for (int ks = 0; ks < 4; ks++) {
+                    PHn[ks] = *reinterpret_cast<const uint4 *>(ph + ((4 * ks + g4) << 3));
+                    PHn[4 + ks] = *reinterpret_cast<const uint4 *>(ph + D + ((4 * ks + g4) << 3));
+                }
 #pragma unroll
                 for (int u = 0; u < 4; u++) {
                     const bf16_t *vr = vc + (size_t)(j * C + 16 * u + r16) * DH;
@@ -456,7 +503,8 @@ __global__ __launch_bounds__(256, 1) void scan_fast_kernel(generic::PrefillArgs<
                 for (int ct = 0; ct < 2; ct++)
 #pragma unroll
                     for (int ks = 0; ks < 4; ks++) {
-                        const int off = (32 * w + 16 * ct + r16) * D + ((4 * ks + g4) << 3);
+                        // one contiguous 1 KB piece per store: [row block w][row tile ct][k-step][lane]
+                        const int off = (((w * 2 + ct) * 4 + ks) * 64 + lane) << 3;
                         *reinterpret_cast<uint4 *>(s16 + off) = __builtin_bit_cast(uint4, Ahi[ct][ks]);
                         *reinterpret_cast<uint4 *>(s16 + D * DH + off) = __builtin_bit_cast(uint4, Alo[ct][ks]);
                     }

@@ -50,8 +50,14 @@ def test_workspace_bytes_monotone(L):
     full, mn = lb.lola_prefill_workspace_bytes(cfg(), 4096, True)
     full2, mn2 = lb.lola_prefill_workspace_bytes(cfg(), 8192, True)
     assert mn == mn2 and full2 > full > mn > 0
+    # an update-only call keeps no snapshots; on the MFMA path it still has per-chunk scratch (features of the keys),
+    # recommended for at most 64 chunks per pass
     upd, mnu = lb.lola_prefill_workspace_bytes(cfg(), 4096, False)
-    assert upd == mnu < mn
+    upd2, _ = lb.lola_prefill_workspace_bytes(cfg(), 1 << 20, False)
+    assert mnu < mn and mnu <= upd == upd2 < full
+    gen = cfg(head_dim=64)      # generic kernels: nothing per chunk
+    updg, mnug = lb.lola_prefill_workspace_bytes(gen, 4096, False)
+    assert updg == mnug > 0
 
 
 def test_status_strings(L):
