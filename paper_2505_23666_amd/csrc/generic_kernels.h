@@ -332,6 +332,9 @@ struct PrefillArgs {
     int QT;                   // queries per attend tile
     int snap_split;           // 1: H snapshots are written as bf16 high + low parts in MFMA operand order (D = d = 128)
     uint16_t *phiK;           // [B*Hkv][S][C][2][D] phi of the pass's keys, bf16 high + low parts (MFMA state-evolution kernel only)
+    int scan_mode;            // scan_kernel: 0 all chunks of the pass; 1 stop at the first regular chunk (a full chunk with a full
+                              // window behind it and a full cache: the MFMA kernel's case) and note it in next_j; 2 continue from next_j
+    int32_t *next_j;          // [B*Hkv] hand-over of the chunk position between the kernels of a pass
 };
 
 template <typename T>
@@ -543,8 +546,19 @@ __global__ __launch_bounds__(NT) void scan_kernel(PrefillArgs<T> a) {
     extern __shared__ float smem[];
     const int si = blockIdx.x;
     int spc = a.st.sp_count[si];
-    for (int j = a.j0; j < a.j1; j++) scan_chunk(a, si, j, spc, smem);
-    if (threadIdx.x == 0) a.st.sp_count[si] = spc;
+    int j = a.scan_mode == 2 ? a.next_j[si] : a.j0;
+    const int64_t a0 = a.st.n_tokens[si];
+    for (; j < a.j1; j++) {
+        if (a.scan_mode == 1) {
+            const int cl = min(a.dm.C, a.T_tokens - j * a.dm.C);
+            if (cl == a.dm.C && a0 + (int64_t)j * a.dm.C >= a.dm.eta && spc == a.dm.lam) break;
+        }
+        scan_chunk(a, si, j, spc, smem);
+    }
+    if (threadIdx.x == 0) {
+        a.st.sp_count[si] = spc;
+        if (a.scan_mode == 1) a.next_j[si] = j;
+    }
 }
 
 // Outputs of one chunk of one query head from the snapshot taken at the chunk's entry.

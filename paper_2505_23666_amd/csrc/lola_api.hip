@@ -107,7 +107,7 @@ bool fast_attend_ok(const lola_config *c) {
 }
 
 struct PrefillPlan {
-    size_t off_prefK, off_prefV, off_sp_row, off_phiE, off_snap;   // byte offsets
+    size_t off_prefK, off_prefV, off_sp_row, off_phiE, off_next, off_snap;   // byte offsets
     size_t snap_bytes_per_chunk;                                    // all streams, one chunk (snapshots + phi of its keys)
     size_t phik_bytes_per_chunk;
     size_t fixed_bytes;
@@ -121,6 +121,7 @@ PrefillPlan plan_prefill(const lola_config *c, int with_outputs) {
     p.off_prefV = off; off += up(ns * P * d * es);
     p.off_sp_row = off; off += up(ns * lam * 4);
     p.off_phiE = off; off += up(ns * (lam + c->chunk) * D * 4);
+    p.off_next = off; off += up(ns * 4);
     p.off_snap = off;
     p.fixed_bytes = off;
     p.snap_bytes_per_chunk = with_outputs ? up(ns * D * d * 4) + up(ns * D * 4) + up(ns * (lam ? lam : 1) * 4) : 0;
@@ -193,6 +194,8 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
     a.prefK = (T *)(ws + p.off_prefK); a.prefV = (T *)(ws + p.off_prefV);
     a.sp_row = (int32_t *)(ws + p.off_sp_row);
     a.phiE = (float *)(ws + p.off_phiE);
+    a.next_j = (int32_t *)(ws + p.off_next);
+    a.scan_mode = 0;
     int S = a.n_chunks > 0 ? a.n_chunks : 1;
     if (p.snap_bytes_per_chunk > 0) {
         size_t room = (workspace_bytes - p.fixed_bytes) / p.snap_bytes_per_chunk;
@@ -217,7 +220,6 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
     a.QT = attend_tile_queries(a.dm);
     const bool fast_att = a.want_out && fast_attend_ok(c);
     a.snap_split = fast_att ? 1 : 0;
-    if (fast_attend_ok(c) && a.R > 32) a.R = 32;   // the fused scan lends the generic per-chunk routine the LDS of its phi tile
     if (a.R <= 0 || (a.want_out && a.QT <= 0)) return LOLA_ERR_UNSUPPORTED;
     const size_t lds_scan = 4 * (scan_fixed + (size_t)a.R * (3 * d + D + 1));
     const size_t lds_att = 4 * ((size_t)a.QT * (d + D + (lam + a.dm.eta + a.dm.C) + 3));
@@ -231,16 +233,29 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
         bool scanned = false;
         if constexpr (std::is_same<T, bf16_t>::value) {
             if (fast_attend_ok(c)) {   // same shape conditions as the output kernel
+                // features of the pass's keys (chunk-parallel); then the serial evolution in three legs that hand the
+                // chunk position over in next_j: generic kernel until the first regular chunk, MFMA kernel over the
+                // regular chunks, generic kernel for what is left (a ragged last chunk)
                 hipLaunchKernelGGL(fast::phi_k_kernel, dim3((unsigned)(a.j1 - a.j0), (unsigned)ns), dim3(256), 0, stream, a);
                 LAUNCH_CHECK();
-                if (c->sparse_budget == 64) hipLaunchKernelGGL((fast::scan_fast_kernel<64>), gs, dim3(256), 0, stream, a);
-                else if (c->sparse_budget == 128) hipLaunchKernelGGL((fast::scan_fast_kernel<128>), gs, dim3(256), 0, stream, a);
-                else hipLaunchKernelGGL((fast::scan_fast_kernel<256>), gs, dim3(256), 0, stream, a);
+                a.scan_mode = 1;
+                hipLaunchKernelGGL((generic::scan_kernel<T>), gs, block, lds_scan, stream, a);
+                LAUNCH_CHECK();
+                if (c->sparse_budget == 64) hipLaunchKernelGGL((fast::scan_fast_kernel<64>), gs, dim3(512), 0, stream, a);
+                else if (c->sparse_budget == 128) hipLaunchKernelGGL((fast::scan_fast_kernel<128>), gs, dim3(512), 0, stream, a);
+                else hipLaunchKernelGGL((fast::scan_fast_kernel<256>), gs, dim3(512), 0, stream, a);
+                LAUNCH_CHECK();
+                a.scan_mode = 2;
+                hipLaunchKernelGGL((generic::scan_kernel<T>), gs, block, lds_scan, stream, a);
+                LAUNCH_CHECK();
+                a.scan_mode = 0;
                 scanned = true;
             }
         }
-        if (!scanned) hipLaunchKernelGGL((generic::scan_kernel<T>), gs, block, lds_scan, stream, a);
-        LAUNCH_CHECK();
+        if (!scanned) {
+            hipLaunchKernelGGL((generic::scan_kernel<T>), gs, block, lds_scan, stream, a);
+            LAUNCH_CHECK();
+        }
         if (a.want_out) {
             dim3 ga((unsigned)(a.j1 - a.j0), (unsigned)a.dm.Hq, (unsigned)a.dm.B);
             if constexpr (std::is_same<T, bf16_t>::value) {

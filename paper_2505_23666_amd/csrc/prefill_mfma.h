@@ -226,26 +226,27 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
 // ---------------------------------------------------------------------------------------------
 // Sequential state evolution of the prefill (paper Sec. 3 "Chunkwise Inference": after each chunk the
 // oldest chunk leaves the window; it and the sparse cache are scored by self-recall error, the top
-// lambda stay, the rest are folded) for the 8B head shape: one workgroup of four wavefronts per
-// (sequence, kv head), persistent over the chunks of a pass.
+// lambda stay, the rest are folded) for the 8B head shape: one workgroup of eight wavefronts per
+// (sequence, kv head), persistent over the regular chunks of a pass (a full chunk, a full window behind
+// it, a full cache).  Chunks before the first regular one (cache still filling, first chunks of a
+// sequence) and a ragged last chunk are handled by the generic kernel in launches of their own; the
+// chunk position is handed over in a per-stream counter.
 //
-// H^T lives in registers for the whole pass (wavefront w owns rows 32w .. 32w+31 as fp32, re-split
+// H^T lives in registers for the whole pass (wavefront w owns rows 16w .. 16w+15 as fp32, re-split
 // into bf16 high + low MFMA operands once per chunk); s lives in LDS.  With lambda <= 128 the features
 // of the cached keys stay in LDS from chunk to chunk as well (a cache slot keeps its row; an entrant's
-// row is copied into the slot it takes), so a regular chunk only computes phi of the 64 pairs that
-// leave the window, and the key and value rows of those pairs are requested one chunk ahead.
-// Per regular chunk (a full chunk, a full window behind it, a full cache):
+// row is copied into the slot it takes); the features of the 64 pairs that leave the window come from
+// the chunk-parallel feature kernel below and are requested one chunk ahead, like their values.
+// Per chunk:
 //   1. snapshot of H^T (operand order, high/low parts), s and the cache's row list for the output kernel;
-//   2. phi of the candidates not yet in LDS; recall GEMM P^T = H^T Phi^T for all lambda + 64 candidates,
-//      with s riding along as one more row (phi.s, the recall's denominator), and per candidate the
-//      three sums  |P|^2, P.v, |v|^2  from which  |P/(phi.s) - v|^2  follows;
-//   3. rank by counting (score descending, token index ascending), the first lambda stay;
+//   2. recall GEMM P^T = H^T Phi^T for all lambda + 64 candidates, with s riding along as one more row
+//      (phi.s, the recall's denominator), and per candidate the three sums  |P|^2, P.v, |v|^2  from which
+//      |P/(phi.s) - v|^2  follows;
+//   3. selection: the 64th smallest score by a bitwise search on the scalar unit, the lists by ballots;
 //   4. fold of the 64 others on MFMA: H[f][c] += sum_e phi_e[f] v_e[c] accumulates directly into the
 //      registers that hold H^T (its C layout is the recall GEMM's A layout), operands gathered
-//      through LDS in transposed order; s += sum_e phi_e;
+//      through LDS in transposed order; s += sum_e phi_e (the same operands times a vector of ones);
 //   5. in-place compaction: the entrants' K, V rows overwrite the slots of the leavers.
-// Any other chunk (warm-up while the cache fills, the first chunks of a sequence, a ragged last chunk)
-// goes through the generic per-chunk routine on the state in global memory.
 
 // phi of the keys of every chunk of a pass (Sec. 2.3 eq. feature_map), chunk-parallel: grid (chunk of the pass, stream),
 // one 16-key tile per wavefront.  The serial state evolution below then only reads these rows (bf16 high + low parts,
@@ -286,25 +287,26 @@ __global__ __launch_bounds__(256) void phi_k_kernel(generic::PrefillArgs<bf16_t>
 __device__ __forceinline__ int tswz(int r) { return ((((r >> 5) ^ r) & 1) << 2) | ((r >> 2) & 3); }
 
 template <int LAM>
-__global__ __launch_bounds__(256, 1) void scan_fast_kernel(generic::PrefillArgs<bf16_t> a) {
-    constexpr int DH = 128, M = 64, D = 128, C = 64, ETA = 64;
+__global__ __launch_bounds__(512, 1) void scan_fast_kernel(generic::PrefillArgs<bf16_t> a) {
+    constexpr int DH = 128, M = 64, D = 128, C = 64, ETA = 64, NW = 8, NTH = 512;
     constexpr int P = LAM + ETA, NE = LAM + C, NTILE = NE / 16, TB = LAM > 128 ? 10 : 12, RB = TB * 16;
-    constexpr int TPW = (TB + 3) / 4, NK = NE / 64, TC = LAM / 16;
+    constexpr int TPW = (TB + NW - 1) / NW, NK = NE / 64, TC = LAM / 16;
     constexpr bool PERSIST = NTILE <= TB;   // one batch: the candidates' features all fit in LDS and the cache's part stays there
-    static_assert(NE % 64 == 0, "candidates are ranked 64 per register");
+    static_assert(NE % 64 == 0, "candidates are selected 64 per register");
     __shared__ __attribute__((aligned(16))) uint16_t PB[2 * RB * D];    // phi of (a batch of) candidates: high parts, low parts
     __shared__ __attribute__((aligned(16))) uint16_t PT[2 * D * C];     // phi^T of the folded pairs [part][f][e']
     __shared__ __attribute__((aligned(16))) uint16_t VT[DH * C];        // v^T of the folded pairs [c][e']
     __shared__ __attribute__((aligned(16))) float s_l[D];
     __shared__ float dn_l[NE];               // phi(k).s
-    __shared__ float part[3][4][NE];         // per wavefront: |P|^2, P.v, |v|^2 over its 32 value columns
     __shared__ uint32_t skey[NE];            // bit patterns of the squared errors
     __shared__ int cidx[NE];
     __shared__ int ne_s;
     __shared__ int flist[C], ecand[C], eslot[C];
-    static_assert(2 * RB * D * 2 >= 4 * (4 * NE + 2 * C + 8 + 32 * (3 * DH + D + 1)), "the generic per-chunk routine borrows the phi tile as scratch (tiles of <= 32 rows)");
+    // per wavefront: |P|^2, P.v, |v|^2 over its 16 value columns; lives in the transposed tile, which is idle until the selection is done
+    float (*part)[NW][NE] = reinterpret_cast<float (*)[NW][NE]>(PT);
+    static_assert(3 * NW * NE * 4 <= 2 * D * C * 2, "the partial sums fit the transposed tile");
 
-    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r16 = lane & 15, g4 = lane >> 4;
+    const int tid0 = threadIdx.x, w0 = tid0 >> 6;
     const int si = blockIdx.x, h = si % a.dm.Hkv;
     float *Hg = a.st.H + (size_t)si * D * DH;
     float *sg = a.st.s + (size_t)si * D;
@@ -316,54 +318,31 @@ __global__ __launch_bounds__(256, 1) void scan_fast_kernel(generic::PrefillArgs<
     const bf16_t *pK = a.prefK + (size_t)si * P * DH, *pV = a.prefV + (size_t)si * P * DH;
     const bf16_t *kc = a.k + (size_t)si * a.T_tokens * DH, *vc = a.v + (size_t)si * a.T_tokens * DH;
     const int64_t a0 = a.st.n_tokens[si];
-    int spc = a.st.sp_count[si];
+    const int spc = a.st.sp_count[si];
+    int j = a.next_j[si];
 
-    // W_k as MFMA A operand for the whole pass
-    bf16x8 AW[4][4];
-#pragma unroll
-    for (int mt = 0; mt < 4; mt++)
-#pragma unroll
-        for (int ks = 0; ks < 4; ks++) AW[mt][ks] = ld_bf16x8(Wk + (size_t)(16 * mt + r16) * DH + 32 * ks + 8 * g4);
-
-    // H^T rows 32w + 16ct + r16, features 32ks + 16hf + 4g4 + 0..3
-#define LOLA_SREP(X) X(0, 0, 0) X(0, 0, 1) X(0, 1, 0) X(0, 1, 1) X(0, 2, 0) X(0, 2, 1) X(0, 3, 0) X(0, 3, 1) \
-                     X(1, 0, 0) X(1, 0, 1) X(1, 1, 0) X(1, 1, 1) X(1, 2, 0) X(1, 2, 1) X(1, 3, 0) X(1, 3, 1)
-#define LOLA_SADDR(ct, ks, hf) ((size_t)(32 * w + 16 * ct + r16) * D + 32 * ks + 16 * hf + 4 * g4)
-#define LOLA_SDECL(ct, ks, hf) f32x4 hreg##ct##ks##hf = {0.f, 0.f, 0.f, 0.f};
-#define LOLA_SLOAD(ct, ks, hf) hreg##ct##ks##hf = *reinterpret_cast<const f32x4 *>(Hg + LOLA_SADDR(ct, ks, hf));
-#define LOLA_SSTORE(ct, ks, hf) *reinterpret_cast<f32x4 *>(Hg + LOLA_SADDR(ct, ks, hf)) = hreg##ct##ks##hf;
+    // H^T row 16w + r16, features 32ks + 16hf + 4g4 + 0..3
+#define LOLA_SREP(X) X(0, 0) X(0, 1) X(1, 0) X(1, 1) X(2, 0) X(2, 1) X(3, 0) X(3, 1)
+#define LOLA_SADDR(ks, hf) ((size_t)(16 * w0 + (tid0 & 15)) * D + 32 * ks + 16 * hf + 4 * ((tid0 & 63) >> 4))
+#define LOLA_SDECL(ks, hf) f32x4 hreg##ks##hf = {0.f, 0.f, 0.f, 0.f};
+#define LOLA_SLOAD(ks, hf) hreg##ks##hf = *reinterpret_cast<const f32x4 *>(Hg + LOLA_SADDR(ks, hf));
+#define LOLA_SSTORE(ks, hf) *reinterpret_cast<f32x4 *>(Hg + LOLA_SADDR(ks, hf)) = hreg##ks##hf;
     LOLA_SREP(LOLA_SDECL)
-    bool h_in_regs = false;
+    bool started = false;
     bool phi_valid = false;     // PERSIST: rows [0, LAM) of PB hold phi of the cache slots, and PHn / vvn the rows requested ahead
-    uint4 PHn[8];               // phi (high pieces, then low pieces) of this wavefront's tile of the pairs that leave the window in the next chunk
-    uint2 vvn[4][2];            // their values at this wavefront's columns
+    uint4 PHn[4];               // this thread's pieces of phi of the pairs that leave the window in the next chunk
+    uint2 vvn[4];               // their values at this wavefront's columns
 #pragma unroll
-    for (int x = 0; x < 8; x++) PHn[x] = make_uint4(0, 0, 0, 0);
-#pragma unroll
-    for (int u = 0; u < 4; u++) { vvn[u][0] = make_uint2(0, 0); vvn[u][1] = make_uint2(0, 0); }
+    for (int x = 0; x < 4; x++) { PHn[x] = make_uint4(0, 0, 0, 0); vvn[x] = make_uint2(0, 0); }
 
-    for (int j = a.j0; j < a.j1; j++) {
+    for (; j < a.j1; j++) {
         const int cl = min(C, a.T_tokens - j * C);
         const int64_t aj = a0 + (int64_t)j * C;
-        const bool regular = cl == C && aj >= ETA && spc == LAM;
-        if (!regular) {
-            if (h_in_regs) {
-                LOLA_SREP(LOLA_SSTORE)
-                if (tid < D) sg[tid] = s_l[tid];
-                h_in_regs = false;
-                __threadfence();
-                __syncthreads();
-            }
-            generic::scan_chunk(a, si, j, spc, reinterpret_cast<float *>(PB));
-            phi_valid = false;
-            __threadfence();
-            __syncthreads();
-            continue;
-        }
-        if (!h_in_regs) {
+        if (!(cl == C && aj >= ETA && spc == LAM)) break;   // not a regular chunk: the generic kernel takes over
+        if (!started) {
             LOLA_SREP(LOLA_SLOAD)
-            if (tid < D) s_l[tid] = sg[tid];
-            h_in_regs = true;
+            if (tid0 < D) s_l[tid0] = sg[tid0];
+            started = true;
             __syncthreads();
         }
         if (j == a.j1 - 1) LOLA_STAMP(0);
@@ -385,19 +364,17 @@ __global__ __launch_bounds__(256, 1) void scan_fast_kernel(generic::PrefillArgs<
             const int vr = vrow_c - ETA + (e - LAM);
             return vr < P ? pV + (size_t)vr * DH : vc + (size_t)(vr - P) * DH;
         };
-        const bool have_phi = PERSIST && phi_valid;
-        const int tfirst = have_phi ? NTILE : 0;   // first tile whose phi is computed in this chunk (none if the cache's
-                                                   // rows are in LDS: the leaving pairs' rows were computed by the parallel
-                                                   // feature kernel and requested one chunk ahead)
+        const bool have_phi = PERSIST && phi_valid;   // the cache's rows are in LDS and the leaving pairs' rows (from the
+                                                      // parallel feature kernel) were requested one chunk ahead
 
         // ---- 1. operands of the recall GEMM from the fp32 registers (H^T, and s as one more row held by the lanes
         // of row 0); the snapshot for the output kernel is stored further down
-        bf16x8 Ahi[2][4], Alo[2][4], Ash[4], Asl[4];
-#define LOLA_SSPLIT(ct, ks, hf) { const f32x4 v = hreg##ct##ks##hf; \
+        bf16x8 Ahi[4], Alo[4], Ash[4], Asl[4];
+#define LOLA_SSPLIT(ks, hf) { const f32x4 v = hreg##ks##hf; \
             const __bf16 h0 = (__bf16)v[0], h1 = (__bf16)v[1], h2 = (__bf16)v[2], h3 = (__bf16)v[3]; \
-            Ahi[ct][ks][4 * hf] = h0; Ahi[ct][ks][4 * hf + 1] = h1; Ahi[ct][ks][4 * hf + 2] = h2; Ahi[ct][ks][4 * hf + 3] = h3; \
-            Alo[ct][ks][4 * hf] = (__bf16)(v[0] - (float)h0); Alo[ct][ks][4 * hf + 1] = (__bf16)(v[1] - (float)h1); \
-            Alo[ct][ks][4 * hf + 2] = (__bf16)(v[2] - (float)h2); Alo[ct][ks][4 * hf + 3] = (__bf16)(v[3] - (float)h3); }
+            Ahi[ks][4 * hf] = h0; Ahi[ks][4 * hf + 1] = h1; Ahi[ks][4 * hf + 2] = h2; Ahi[ks][4 * hf + 3] = h3; \
+            Alo[ks][4 * hf] = (__bf16)(v[0] - (float)h0); Alo[ks][4 * hf + 1] = (__bf16)(v[1] - (float)h1); \
+            Alo[ks][4 * hf + 2] = (__bf16)(v[2] - (float)h2); Alo[ks][4 * hf + 3] = (__bf16)(v[3] - (float)h3); }
         LOLA_SREP(LOLA_SSPLIT)
 #undef LOLA_SSPLIT
 #pragma unroll
@@ -411,72 +388,51 @@ __global__ __launch_bounds__(256, 1) void scan_fast_kernel(generic::PrefillArgs<
             split8(sv, Ash[ks], Asl[ks]);
             if (r16 != 0) { Ash[ks] = zero_bf16x8(); Asl[ks] = zero_bf16x8(); }
         }
-        for (int e = tid; e < NE; e += 256) cidx[e] = e < LAM ? sp_idx[e] : (int)(aj - ETA + (e - LAM));
+        for (int e = tid; e < NE; e += NTH) cidx[e] = e < LAM ? sp_idx[e] : (int)(aj - ETA + (e - LAM));
 
         if (j == a.j1 - 1) LOLA_STAMP(1);
-        // ---- 2. phi of the candidates and their recall error, in batches of TB tiles.  All global loads of a
-        // batch are requested up front in the order of their use: key rows, then the candidates' values for the
-        // recall epilogue, then the rows wanted by the next chunk; the snapshot stores follow once phi is done, so
-        // that they drain while the recall GEMM runs out of LDS and registers.
+        // ---- 2. phi of the candidates and their recall error, in batches of TB tiles.  Global loads of a batch are
+        // requested up front: the candidates' values for the recall epilogue, then the rows wanted by the next chunk; the
+        // snapshot stores follow, so that they drain while the recall GEMM runs out of LDS and registers.
 #pragma unroll 1
         for (int t0 = 0; t0 < NTILE; t0 += TB) {
             const int t1 = min(NTILE, t0 + TB);
-            const int tp = max(t0, tfirst);      // wavefront w computes phi of tiles tp + w, tp + w + 4, ...
-            bf16x8 BK[TPW][4];
-#pragma unroll
-            for (int u = 0; u < TPW; u++) {
-                const int t = tp + w + 4 * u;
-                if (t < t1) {
-                    const bf16_t *kr = krow(16 * t + r16);
-#pragma unroll
-                    for (int ks = 0; ks < 4; ks++) BK[u][ks] = ld_bf16x8(kr + 32 * ks + 8 * g4);
-                }
-            }
-            uint2 vv[TB][2];
+            uint2 vv[TB];
 #pragma unroll
             for (int u = 0; u < TB; u++) {
                 if (PERSIST && u >= TC && have_phi) {
-                    vv[u][0] = vvn[u >= TC ? u - TC : 0][0]; vv[u][1] = vvn[u >= TC ? u - TC : 0][1];
+                    vv[u] = vvn[u >= TC ? u - TC : 0];
                 } else if (t0 + u < t1) {
-                    const bf16_t *vr = vrow(16 * (t0 + u) + r16);
-#pragma unroll
-                    for (int ct = 0; ct < 2; ct++) vv[u][ct] = *reinterpret_cast<const uint2 *>(vr + 32 * w + 16 * ct + 4 * g4);
+                    vv[u] = *reinterpret_cast<const uint2 *>(vrow(16 * (t0 + u) + r16) + 16 * w + 4 * g4);
                 }
             }
-            if (PERSIST && have_phi) {   // the rows requested one chunk ago take their place behind the cache's rows
-                const int rl = LAM + 16 * w + r16;
+            if (have_phi) {   // the rows requested one chunk ago take their place behind the cache's rows
 #pragma unroll
-                for (int ks = 0; ks < 4; ks++) {
-                    const int addr = rl * D + (((4 * ks + g4) ^ r16) << 3);
-                    *reinterpret_cast<uint4 *>(&PB[addr]) = PHn[ks];
-                    *reinterpret_cast<uint4 *>(&PB[RB * D + addr]) = PHn[4 + ks];
+                for (int it = 0; it < 4; it++) {
+                    const int o = tid + NTH * it, row = o >> 5, pt = (o >> 4) & 1, pc = o & 15;
+                    *reinterpret_cast<uint4 *>(&PB[pt * RB * D + (LAM + row) * D + ((pc ^ (row & 15)) << 3)]) = PHn[it];
                 }
-            }
-            if (PERSIST) {   // this chunk's own pairs leave the window in the next chunk
-                const uint16_t *ph = a.phiK + (((size_t)si * a.S + (j - a.j0)) * C + 16 * w + r16) * 2 * D;
+            } else {
+                // phi of the batch's tiles (first regular chunk of a pass, or a cache too large to stay in LDS):
+                // wavefront w takes tiles t0 + w, t0 + w + 8
+                bf16x8 AW[4][4];
 #pragma unroll
-                for (int ks = 0; ks < 4; ks++) {
-                    PHn[ks] = *reinterpret_cast<const uint4 *>(ph + ((4 * ks + g4) << 3));
-                    PHn[4 + ks] = *reinterpret_cast<const uint4 *>(ph + D + ((4 * ks + g4) << 3));
-                }
+                for (int mt = 0; mt < 4; mt++)
 #pragma unroll
-                for (int u = 0; u < 4; u++) {
-                    const bf16_t *vr = vc + (size_t)(j * C + 16 * u + r16) * DH;
-#pragma unroll
-                    for (int ct = 0; ct < 2; ct++) vvn[u][ct] = *reinterpret_cast<const uint2 *>(vr + 32 * w + 16 * ct + 4 * g4);
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < TPW; u++) {
-                const int t = tp + w + 4 * u;
-                if (t < t1) {
+                    for (int ks = 0; ks < 4; ks++) AW[mt][ks] = ld_bf16x8(Wk + (size_t)(16 * mt + r16) * DH + 32 * ks + 8 * g4);
+#pragma unroll 1
+                for (int t = t0 + w; t < t1; t += NW) {
                     const int e = 16 * t + r16;
+                    const bf16_t *kr = krow(e);
+                    bf16x8 BK[4];
+#pragma unroll
+                    for (int ks = 0; ks < 4; ks++) BK[ks] = ld_bf16x8(kr + 32 * ks + 8 * g4);
                     f32x4 zt[4];
 #pragma unroll
                     for (int mt = 0; mt < 4; mt++) {
                         zt[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                        for (int ks = 0; ks < 4; ks++) zt[mt] = mfma16(AW[mt][ks], BK[u][ks], zt[mt]);
+                        for (int ks = 0; ks < 4; ks++) zt[mt] = mfma16(AW[mt][ks], BK[ks], zt[mt]);
                     }
                     float pp[16], pn[16];
                     phi_from_z(zt, a.dm.phi_kind, pp, pn);
@@ -496,29 +452,35 @@ __global__ __launch_bounds__(256, 1) void scan_fast_kernel(generic::PrefillArgs<
                     }
                 }
             }
+            if (PERSIST) {   // this chunk's own pairs leave the window in the next chunk
+                const uint4 *ph = reinterpret_cast<const uint4 *>(a.phiK + ((size_t)si * a.S + (j - a.j0)) * C * 2 * D);
+#pragma unroll
+                for (int it = 0; it < 4; it++) PHn[it] = ph[tid + NTH * it];
+#pragma unroll
+                for (int u = 0; u < 4; u++)
+                    vvn[u] = *reinterpret_cast<const uint2 *>(vc + (size_t)(j * C + 16 * u + r16) * DH + 16 * w + 4 * g4);
+            }
             if (a.want_out && t0 == 0) {
                 const size_t sj = (size_t)si * a.S + (j - a.j0);
                 uint16_t *s16 = reinterpret_cast<uint16_t *>(a.snapH) + sj * (2 * D * DH);
 #pragma unroll
-                for (int ct = 0; ct < 2; ct++)
-#pragma unroll
-                    for (int ks = 0; ks < 4; ks++) {
-                        // one contiguous 1 KB piece per store: [row block w][row tile ct][k-step][lane]
-                        const int off = (((w * 2 + ct) * 4 + ks) * 64 + lane) << 3;
-                        *reinterpret_cast<uint4 *>(s16 + off) = __builtin_bit_cast(uint4, Ahi[ct][ks]);
-                        *reinterpret_cast<uint4 *>(s16 + D * DH + off) = __builtin_bit_cast(uint4, Alo[ct][ks]);
-                    }
+                for (int ks = 0; ks < 4; ks++) {
+                    // one contiguous 1 KB piece per store: [row tile w][k-step][lane]
+                    const int off = ((w * 4 + ks) * 64 + lane) << 3;
+                    *reinterpret_cast<uint4 *>(s16 + off) = __builtin_bit_cast(uint4, Ahi[ks]);
+                    *reinterpret_cast<uint4 *>(s16 + D * DH + off) = __builtin_bit_cast(uint4, Alo[ks]);
+                }
                 if (tid < D / 4) reinterpret_cast<float4 *>(a.snapS + sj * D)[tid] = reinterpret_cast<const float4 *>(s_l)[tid];
-                for (int sl = tid; sl < LAM; sl += 256) a.snapG[sj * LAM + sl] = sp_row[sl];
+                for (int sl = tid; sl < LAM; sl += NTH) a.snapG[sj * LAM + sl] = sp_row[sl];
             }
             if (j == a.j1 - 1 && t0 == 0) LOLA_STAMP(2);
             __syncthreads();
             if (j == a.j1 - 1 && t0 == 0) LOLA_STAMP(3);
-            // recall GEMM for the batch: A = this wavefront's rows of H^T, B = phi from LDS; lane (candidate r16, group g4)
-            // holds rows c = 32w + 16ct + 4 g4 + i and pairs them with the candidate's values at those columns.
-            // Tile t's denominators come from wavefront t % 4 (A = s in row 0, zeros below).
-            // (operands of the next tile are read from LDS before this tile's MFMAs; the scheduling fence keeps the
-            // compiler from hoisting the reads of all tiles at once, which would not fit the register file)
+            // recall GEMM for the batch: A = this wavefront's 16 rows of H^T, B = phi from LDS; lane (candidate r16,
+            // group g4) holds rows c = 16w + 4 g4 + i and pairs them with the candidate's values at those columns.
+            // Tile t's denominators come from wavefront t % 8 (A = s in row 0, zeros below).  Operands of the next
+            // tile are read from LDS before this tile's MFMAs; the scheduling fence keeps the compiler from hoisting
+            // the reads of all tiles at once.
             bf16x8 Bc[8], Bn[8];
 #pragma unroll
             for (int ks = 0; ks < 4; ks++) {
@@ -538,35 +500,29 @@ __global__ __launch_bounds__(256, 1) void scan_fast_kernel(generic::PrefillArgs<
                             Bn[4 + ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(&PB[RB * D + addr]));
                         }
                     }
-                    f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}}, acc2[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+                    f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acc2 = {0.f, 0.f, 0.f, 0.f}, acc3 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                     for (int ks = 0; ks < 4; ks++) {
-#pragma unroll
-                        for (int ct = 0; ct < 2; ct++) acc[ct] = mfma16(Ahi[ct][ks], Bc[ks], acc[ct]);
-#pragma unroll
-                        for (int ct = 0; ct < 2; ct++) acc2[ct] = mfma16(Ahi[ct][ks], Bc[4 + ks], acc2[ct]);
-#pragma unroll
-                        for (int ct = 0; ct < 2; ct++) acc2[ct] = mfma16(Alo[ct][ks], Bc[ks], acc2[ct]);
+                        acc = mfma16(Ahi[ks], Bc[ks], acc);
+                        acc2 = mfma16(Ahi[ks], Bc[4 + ks], acc2);
+                        acc3 = mfma16(Alo[ks], Bc[ks], acc3);
                     }
-                    if (((t0 + u) & 3) == w) {
-                        f32x4 ds = {0.f, 0.f, 0.f, 0.f}, ds2 = {0.f, 0.f, 0.f, 0.f};
+                    if (((t0 + u) & (NW - 1)) == w) {
+                        f32x4 ds = {0.f, 0.f, 0.f, 0.f}, ds2 = {0.f, 0.f, 0.f, 0.f}, ds3 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                         for (int ks = 0; ks < 4; ks++) {
                             ds = mfma16(Ash[ks], Bc[ks], ds);
                             ds2 = mfma16(Ash[ks], Bc[4 + ks], ds2);
-                            ds2 = mfma16(Asl[ks], Bc[ks], ds2);
+                            ds3 = mfma16(Asl[ks], Bc[ks], ds3);
                         }
-                        if (g4 == 0) dn_l[e] = ds[0] + ds2[0];
+                        if (g4 == 0) dn_l[e] = ds[0] + (ds2[0] + ds3[0]);
                     }
-                    float sa = 0.f, sb = 0.f, sc = 0.f;
-#pragma unroll
-                    for (int ct = 0; ct < 2; ct++) {
-                        const f32x4 p = acc[ct] + acc2[ct];
-                        const float v0 = bf_lo(vv[u][ct].x), v1 = bf_hi(vv[u][ct].x), v2 = bf_lo(vv[u][ct].y), v3 = bf_hi(vv[u][ct].y);
-                        sa = fmaf(p[0], p[0], sa); sa = fmaf(p[1], p[1], sa); sa = fmaf(p[2], p[2], sa); sa = fmaf(p[3], p[3], sa);
-                        sb = fmaf(p[0], v0, sb); sb = fmaf(p[1], v1, sb); sb = fmaf(p[2], v2, sb); sb = fmaf(p[3], v3, sb);
-                        sc = fmaf(v0, v0, sc); sc = fmaf(v1, v1, sc); sc = fmaf(v2, v2, sc); sc = fmaf(v3, v3, sc);
-                    }
+                    const f32x4 p = acc + (acc2 + acc3);
+                    const float v0 = bf_lo(vv[u].x), v1 = bf_hi(vv[u].x), v2 = bf_lo(vv[u].y), v3 = bf_hi(vv[u].y);
+                    float sa = p[0] * p[0], sb = p[0] * v0, sc = v0 * v0;
+                    sa = fmaf(p[1], p[1], sa); sa = fmaf(p[2], p[2], sa); sa = fmaf(p[3], p[3], sa);
+                    sb = fmaf(p[1], v1, sb); sb = fmaf(p[2], v2, sb); sb = fmaf(p[3], v3, sb);
+                    sc = fmaf(v1, v1, sc); sc = fmaf(v2, v2, sc); sc = fmaf(v3, v3, sc);
                     sa = grp_sum(sa); sb = grp_sum(sb); sc = grp_sum(sc);
                     if (g4 == 0) { part[0][w][e] = sa; part[1][w][e] = sb; part[2][w][e] = sc; }
                     __builtin_amdgcn_sched_barrier(0);
@@ -582,11 +538,11 @@ __global__ __launch_bounds__(256, 1) void scan_fast_kernel(generic::PrefillArgs<
         // ---- 3. selection: the 64 candidates with the smallest squared error are folded (order: score descending,
         // token index ascending, the first LAM stay).  The squared error is |P|^2 / (phi.s)^2 - 2 P.v / (phi.s) + |v|^2
         // (recall = 0 while phi.s = 0, i.e. nothing folded yet); the bit pattern of a float >= 0 orders like an integer.
-        for (int e = tid; e < NE; e += 256) {
-            const float dn = dn_l[e], rd = dn > 0.f ? 1.0f / dn : 0.f;
-            const float sa = part[0][0][e] + part[0][1][e] + part[0][2][e] + part[0][3][e];
-            const float sb = part[1][0][e] + part[1][1][e] + part[1][2][e] + part[1][3][e];
-            const float sc = part[2][0][e] + part[2][1][e] + part[2][2][e] + part[2][3][e];
+        for (int e = tid; e < NE; e += NTH) {
+            const float dn = dn_l[e], rd = dn > 0.f ? __builtin_amdgcn_rcpf(dn) : 0.f;
+            float sa = 0.f, sb = 0.f, sc = 0.f;
+#pragma unroll
+            for (int x = 0; x < NW; x++) { sa += part[0][x][e]; sb += part[1][x][e]; sc += part[2][x][e]; }
             const float sq = fmaxf(fmaf(rd * rd, sa, fmaf(-2.0f * rd, sb, sc)), 0.f);
             skey[e] = __float_as_uint(sq) & 0x7FFFFFFFu;
         }
@@ -602,13 +558,21 @@ __global__ __launch_bounds__(256, 1) void scan_fast_kernel(generic::PrefillArgs<
 #pragma unroll
             for (int x = 0; x < NK; x++) { sb[x] = skey[64 * x + lane]; ix[x] = cidx[64 * x + lane]; }
             uint32_t thr = 0;
-#pragma unroll 1
-            for (int bit = 30; bit >= 0; bit--) {
-                const uint32_t trial = thr | (1u << bit);
+            {   // bit 30 alone, then two bits per step (three trial values counted side by side)
                 int c = 0;
 #pragma unroll
-                for (int x = 0; x < NK; x++) c += __popcll(__ballot(sb[x] < trial));
-                if (c < C) thr = trial;
+                for (int x = 0; x < NK; x++) c += __popcll(__ballot(sb[x] < (1u << 30)));
+                if (c < C) thr = 1u << 30;
+            }
+#pragma unroll 1
+            for (int bit = 28; bit >= 0; bit -= 2) {
+                const uint32_t t1 = thr | (1u << bit), t2 = thr | (2u << bit), t3 = thr | (3u << bit);
+                int c1 = 0, c2 = 0, c3 = 0;
+#pragma unroll
+                for (int x = 0; x < NK; x++) {
+                    c1 += __popcll(__ballot(sb[x] < t1)); c2 += __popcll(__ballot(sb[x] < t2)); c3 += __popcll(__ballot(sb[x] < t3));
+                }
+                thr = c3 < C ? t3 : (c2 < C ? t2 : (c1 < C ? t1 : thr));
             }
             int n_lt = 0, n_eq = 0;
 #pragma unroll
@@ -652,12 +616,11 @@ __global__ __launch_bounds__(256, 1) void scan_fast_kernel(generic::PrefillArgs<
         // these writes fall on all banks (two lanes per bank) and the 128-bit operand reads of the MFMAs below
         // on all eight chunks evenly.
         {
-            const int ch = tid & 15, pairpos = (tid >> 4) & 3, wl = w;
-            uint4 pa[4], pb[4], va[2], vb[2];
-            const int pt = wl & 1;
+            const int ch = tid & 15, pairpos = (tid >> 4) & 3, pt = w & 1;
+            uint4 pa[2], pb[2], va, vb;
 #pragma unroll
-            for (int it = 0; it < 4; it++) {
-                const int ep = 8 * ((wl >> 1) + 2 * it) + 2 * pairpos;
+            for (int it = 0; it < 2; it++) {
+                const int ep = 8 * ((w >> 1) + 4 * it) + 2 * pairpos;
                 const int ea = flist[ep], eb = flist[ep + 1];
                 if (PERSIST) {
                     pa[it] = *reinterpret_cast<const uint4 *>(&PB[pt * RB * D + ea * D + ((ch ^ (ea & 15)) << 3)]);
@@ -667,34 +630,30 @@ __global__ __launch_bounds__(256, 1) void scan_fast_kernel(generic::PrefillArgs<
                     pb[it] = *reinterpret_cast<const uint4 *>(phiE + (size_t)eb * 2 * D + pt * D + (ch << 3));
                 }
             }
-#pragma unroll
-            for (int it = 0; it < 2; it++) {
-                const int ep = 8 * (wl + 4 * it) + 2 * pairpos;
-                va[it] = reinterpret_cast<const uint4 *>(vrow(flist[ep]))[ch];
-                vb[it] = reinterpret_cast<const uint4 *>(vrow(flist[ep + 1]))[ch];
+            {
+                const int ep = 8 * w + 2 * pairpos;
+                va = reinterpret_cast<const uint4 *>(vrow(flist[ep]))[ch];
+                vb = reinterpret_cast<const uint4 *>(vrow(flist[ep + 1]))[ch];
             }
             // feature held by element x of piece ch (operand order): 32 (ch / 4) + 16 (x / 4) + 4 (ch % 4) + x % 4
 #pragma unroll
             for (int x = 0; x < 8; x++) {
                 const int f = 32 * (ch >> 2) + 16 * (x >> 2) + 4 * (ch & 3) + (x & 3);
-                const int bx = pt * D * C + f * C + ((((wl >> 1) ^ tswz(f))) << 3) + 2 * pairpos;
+                const int bx = pt * D * C + f * C + ((((w >> 1) ^ tswz(f))) << 3) + 2 * pairpos;
 #pragma unroll
-                for (int it = 0; it < 4; it++) {
+                for (int it = 0; it < 2; it++) {
                     const uint32_t ua = (&pa[it].x)[x >> 1], ub = (&pb[it].x)[x >> 1];
                     const uint32_t wv = (x & 1) ? ((ua >> 16) | (ub & 0xFFFF0000u)) : ((ua & 0xFFFFu) | (ub << 16));
-                    *reinterpret_cast<uint32_t *>(&PT[bx ^ (it << 4)]) = wv;
+                    *reinterpret_cast<uint32_t *>(&PT[bx ^ (it << 5)]) = wv;
                 }
             }
 #pragma unroll
             for (int x = 0; x < 8; x++) {
                 const int c = 8 * ch + x;
-                const int bx = c * C + (((wl ^ tswz(c))) << 3) + 2 * pairpos;
-#pragma unroll
-                for (int it = 0; it < 2; it++) {
-                    const uint32_t ua = (&va[it].x)[x >> 1], ub = (&vb[it].x)[x >> 1];
-                    const uint32_t wv = (x & 1) ? ((ua >> 16) | (ub & 0xFFFF0000u)) : ((ua & 0xFFFFu) | (ub << 16));
-                    *reinterpret_cast<uint32_t *>(&VT[bx ^ (it << 5)]) = wv;
-                }
+                const int bx = c * C + (((w ^ tswz(c))) << 3) + 2 * pairpos;
+                const uint32_t ua = (&va.x)[x >> 1], ub = (&vb.x)[x >> 1];
+                const uint32_t wv = (x & 1) ? ((ua >> 16) | (ub & 0xFFFF0000u)) : ((ua & 0xFFFFu) | (ub << 16));
+                *reinterpret_cast<uint32_t *>(&VT[bx]) = wv;
             }
         }
         if (j == a.j1 - 1) LOLA_STAMP(8);
@@ -703,57 +662,50 @@ __global__ __launch_bounds__(256, 1) void scan_fast_kernel(generic::PrefillArgs<
         {
             // compaction, first half: the entrants' rows are requested now and stored after the fold (all reads of
             // the leavers' rows were completed before the barrier above)
-            uint4 cp[8];
+            uint4 cp[4];
 #pragma unroll
-            for (int it = 0; it < 8; it++) {
-                const int o = tid + 256 * it;
+            for (int it = 0; it < 4; it++) {
+                const int o = tid + NTH * it;
                 if (o < ne * 32) {
                     const int x = o >> 5, rem = o & 31;
                     const int e = ecand[x];
                     cp[it] = reinterpret_cast<const uint4 *>((rem >> 4) ? vrow(e) : krow(e))[rem & 15];
                 }
             }
-            bf16x8 Bv[2][2];
+            bf16x8 Bv[2];
 #pragma unroll
-            for (int ct = 0; ct < 2; ct++)
-#pragma unroll
-                for (int k2 = 0; k2 < 2; k2++) {
-                    const int c = 32 * w + 16 * ct + r16;
-                    Bv[ct][k2] = as_bf16x8(*reinterpret_cast<const uint4 *>(&VT[c * C + (((4 * k2 + g4) ^ tswz(c)) << 3)]));
-                }
-            // per feature tile (16 features): four A operands (high / low part x two k-steps) serve both value tiles of
-            // the wavefront; the operands of the next tile are read from LDS before this tile's MFMAs are issued
+            for (int k2 = 0; k2 < 2; k2++) {
+                const int c = 16 * w + r16;
+                Bv[k2] = as_bf16x8(*reinterpret_cast<const uint4 *>(&VT[c * C + (((4 * k2 + g4) ^ tswz(c)) << 3)]));
+            }
+            // per feature tile (16 features): four A operands (high / low part x two k-steps); the operands of the next
+            // tile are read from LDS before this tile's MFMAs are issued
             bf16x8 Ac[4], An[4];
 #define LOLA_SFA(dst, mt) _Pragma("unroll") for (int x = 0; x < 4; x++) { const int f = 16 * (mt) + r16; \
                 dst[x] = as_bf16x8(*reinterpret_cast<const uint4 *>(&PT[(x >> 1) * D * C + f * C + (((4 * (x & 1) + g4) ^ tswz(f)) << 3)])); }
             LOLA_SFA(Ac, 0)
+            // s += sum of the folded features: feature tile w's operands times a vector of ones, by wavefront w
+            const bf16x8 ones = as_bf16x8(make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u));
+            f32x4 sacc = {0.f, 0.f, 0.f, 0.f};
 #define LOLA_SFOLD2(ks, hf) { if (2 * ks + hf + 1 < 8) { LOLA_SFA(An, 2 * ks + hf + 1) } \
-            _Pragma("unroll") for (int x = 0; x < 4; x++) { \
-                hreg0##ks##hf = mfma16(Ac[x], Bv[0][x & 1], hreg0##ks##hf); \
-                hreg1##ks##hf = mfma16(Ac[x], Bv[1][x & 1], hreg1##ks##hf); } \
+            _Pragma("unroll") for (int x = 0; x < 4; x++) hreg##ks##hf = mfma16(Ac[x], Bv[x & 1], hreg##ks##hf); \
+            if (2 * ks + hf == w) { _Pragma("unroll") for (int x = 0; x < 4; x++) sacc = mfma16(Ac[x], ones, sacc); } \
             __builtin_amdgcn_sched_barrier(0); \
             _Pragma("unroll") for (int x = 0; x < 4; x++) Ac[x] = An[x]; }
-            LOLA_SFOLD2(0, 0) LOLA_SFOLD2(0, 1) LOLA_SFOLD2(1, 0) LOLA_SFOLD2(1, 1)
-            LOLA_SFOLD2(2, 0) LOLA_SFOLD2(2, 1) LOLA_SFOLD2(3, 0) LOLA_SFOLD2(3, 1)
+            LOLA_SREP(LOLA_SFOLD2)
 #undef LOLA_SFOLD2
 #undef LOLA_SFA
-            if (tid < D) {
-                const int f = tid;
-                float acc = 0.f;
-#pragma unroll
-                for (int pt = 0; pt < 2; pt++)
-#pragma unroll
-                    for (int ch = 0; ch < 8; ch++) {
-                        const uint4 u = *reinterpret_cast<const uint4 *>(&PT[pt * D * C + f * C + (ch << 3)]);
-                        acc += bf_lo(u.x) + bf_hi(u.x) + bf_lo(u.y) + bf_hi(u.y) + bf_lo(u.z) + bf_hi(u.z) + bf_lo(u.w) + bf_hi(u.w);
-                    }
-                s_l[f] += acc;
+            if (r16 == 0) {   // column 0 of the result tile: features 16w + 4 g4 + 0..3
+                float4 *sp = reinterpret_cast<float4 *>(&s_l[16 * w + 4 * g4]);
+                float4 sv = *sp;
+                sv.x += sacc[0]; sv.y += sacc[1]; sv.z += sacc[2]; sv.w += sacc[3];
+                *sp = sv;
             }
             if (j == a.j1 - 1) LOLA_STAMP(10);
             // ---- 5. compaction, second half: entrants take the leavers' slots, in the state and (their features) in LDS
 #pragma unroll
-            for (int it = 0; it < 8; it++) {
-                const int o = tid + 256 * it;
+            for (int it = 0; it < 4; it++) {
+                const int o = tid + NTH * it;
                 if (o < ne * 32) {
                     const int x = o >> 5, rem = o & 31;
                     bf16_t *dst = ((rem >> 4) ? sp_v : sp_k) + (size_t)eslot[x] * DH;
@@ -762,8 +714,8 @@ __global__ __launch_bounds__(256, 1) void scan_fast_kernel(generic::PrefillArgs<
             }
             if (PERSIST) {
 #pragma unroll
-                for (int it = 0; it < 8; it++) {
-                    const int o = tid + 256 * it;
+                for (int it = 0; it < 4; it++) {
+                    const int o = tid + NTH * it;
                     if (o < ne * 32) {
                         const int x = o >> 5, rem = o & 31, pt = rem >> 4, ch = rem & 15;
                         const int e = ecand[x], sl = eslot[x];
@@ -773,26 +725,25 @@ __global__ __launch_bounds__(256, 1) void scan_fast_kernel(generic::PrefillArgs<
                 }
             }
         }
-        for (int x = tid; x < ne; x += 256) {
+        for (int x = tid; x < ne; x += NTH) {
             const int e = ecand[x], sl = eslot[x];
             sp_idx[sl] = cidx[e];
             sp_row[sl] = vrow_c - ETA + (e - LAM);
         }
         phi_valid = PERSIST;
         if (j == a.j1 - 1) LOLA_STAMP(11);
-        __threadfence();
-        __syncthreads();
+        __syncthreads();   // (workgroup scope is enough: only this workgroup reads the stream's memories before the kernel ends)
         if (j == a.j1 - 1) LOLA_STAMP(12);
         if (a.sel_trace) {
             int32_t *tr = a.sel_trace + ((size_t)si * a.n_chunks + j) * LAM;
-            for (int sl = tid; sl < LAM; sl += 256) tr[sl] = sp_idx[sl];
+            for (int sl = tid; sl < LAM; sl += NTH) tr[sl] = sp_idx[sl];
         }
     }
-    if (h_in_regs) {
+    if (started) {
         LOLA_SREP(LOLA_SSTORE)
-        if (tid < D) sg[tid] = s_l[tid];
+        if (tid0 < D) sg[tid0] = s_l[tid0];
     }
-    if (tid == 0) a.st.sp_count[si] = spc;
+    if (tid0 == 0) a.next_j[si] = j;
 #undef LOLA_SREP
 #undef LOLA_SADDR
 #undef LOLA_SDECL
