@@ -421,16 +421,22 @@ __device__ void scan_chunk(const PrefillArgs<T> &a, const int si, const int j, i
                 // ordered [part][row block of 32][row tile of 16][piece / 4][16 (piece % 4) + row % 16] (the order in
                 // which the MFMA kernels hold them, one contiguous 1 KB per wavefront store)
                 uint16_t *s16 = reinterpret_cast<uint16_t *>(sH);
-                for (int idx = tid; idx < D * d; idx += NT) {
-                    const int c = idx / D, f = idx - c * D;
-                    const float x = H[idx];
-                    const uint16_t hi = f32_to_bf16_bits(x);
-                    const float r = x - __uint_as_float(((uint32_t)hi) << 16);
-                    const int piece = ((f >> 5) << 2) | ((f >> 2) & 3);
-                    const int pos = ((((((c >> 5) * 2 + ((c >> 4) & 1)) * 4 + (piece >> 2)) * 64) + 16 * (piece & 3) + (c & 15)) << 3) +
-                                    ((((f >> 4) & 1) << 2) | (f & 3));
-                    s16[pos] = hi;
-                    s16[D * d + pos] = f32_to_bf16_bits(r);
+                for (int pi = tid; pi < D * d / 8; pi += NT) {   // one 16-byte piece (8 features of one row) per step
+                    const int c = pi >> 4, piece = pi & 15;
+                    const float *src = H + (size_t)c * D + 32 * (piece >> 2) + 4 * (piece & 3);
+                    const float4 lo4 = *reinterpret_cast<const float4 *>(src), hi4 = *reinterpret_cast<const float4 *>(src + 16);
+                    const float x[8] = {lo4.x, lo4.y, lo4.z, lo4.w, hi4.x, hi4.y, hi4.z, hi4.w};
+                    uint32_t ph[4], pl[4];
+#pragma unroll
+                    for (int e = 0; e < 4; e++) {
+                        const uint16_t h0 = f32_to_bf16_bits(x[2 * e]), h1 = f32_to_bf16_bits(x[2 * e + 1]);
+                        const float r0 = x[2 * e] - __uint_as_float(((uint32_t)h0) << 16), r1 = x[2 * e + 1] - __uint_as_float(((uint32_t)h1) << 16);
+                        ph[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+                        pl[e] = (uint32_t)f32_to_bf16_bits(r0) | ((uint32_t)f32_to_bf16_bits(r1) << 16);
+                    }
+                    const int pos = (((((c >> 5) * 2 + ((c >> 4) & 1)) * 4 + (piece >> 2)) * 64) + 16 * (piece & 3) + (c & 15)) << 3;
+                    *reinterpret_cast<uint4 *>(s16 + pos) = make_uint4(ph[0], ph[1], ph[2], ph[3]);
+                    *reinterpret_cast<uint4 *>(s16 + D * d + pos) = make_uint4(pl[0], pl[1], pl[2], pl[3]);
                 }
             } else {
                 for (int idx = tid; idx < D * d; idx += NT) sH[idx] = H[idx];
