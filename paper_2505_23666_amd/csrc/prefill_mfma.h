@@ -564,22 +564,27 @@ __global__ __launch_bounds__(512, 1) void scan_fast_kernel(generic::PrefillArgs<
                 for (int x = 0; x < NK; x++) c += __popcll(__ballot(sb[x] < (1u << 30)));
                 if (c < C) thr = 1u << 30;
             }
+            uint32_t cut = 0;               // != 0: exactly 64 scores lie below it, the search can stop there
 #pragma unroll 1
-            for (int bit = 28; bit >= 0; bit -= 2) {
+            for (int bit = 28; bit >= 0 && cut == 0; bit -= 2) {
                 const uint32_t t1 = thr | (1u << bit), t2 = thr | (2u << bit), t3 = thr | (3u << bit);
                 int c1 = 0, c2 = 0, c3 = 0;
 #pragma unroll
                 for (int x = 0; x < NK; x++) {
                     c1 += __popcll(__ballot(sb[x] < t1)); c2 += __popcll(__ballot(sb[x] < t2)); c3 += __popcll(__ballot(sb[x] < t3));
                 }
+                cut = c1 == C ? t1 : (c2 == C ? t2 : (c3 == C ? t3 : 0u));
                 thr = c3 < C ? t3 : (c2 < C ? t2 : (c1 < C ? t1 : thr));
             }
             int n_lt = 0, n_eq = 0;
+            if (cut != 0) { thr = cut; n_lt = C; }   // everything below the cut is folded, nothing at or above it
+            else {
 #pragma unroll
-            for (int x = 0; x < NK; x++) { n_lt += __popcll(__ballot(sb[x] < thr)); n_eq += __popcll(__ballot(sb[x] == thr)); }
-            const int need = C - n_lt;      // 1 <= need <= n_eq
-            uint32_t imin = 0;              // ties are folded from token index imin upwards
-            if (n_eq != need) {
+                for (int x = 0; x < NK; x++) { n_lt += __popcll(__ballot(sb[x] < thr)); n_eq += __popcll(__ballot(sb[x] == thr)); }
+            }
+            const int need = C - n_lt;      // ties at the threshold to fold: 0 after an early stop, else 1 <= need <= n_eq
+            uint32_t imin = need == 0 ? 0xFFFFFFFFu : 0u;   // ties are folded from token index imin upwards
+            if (need != 0 && n_eq != need) {
 #pragma unroll 1
                 for (int bit = 30; bit >= 0; bit--) {
                     const uint32_t trial = imin | (1u << bit);
