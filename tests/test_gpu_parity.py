@@ -202,6 +202,46 @@ def test_maximum_sizes_generic_family():
     say("max dims", rep, rep2)
 
 
+def test_paper_scale_cache_parameters():
+    """Cache parameters of the paper's long-context runs (window = sparse budget = 256, feature dimension 2 d): the
+    generic kernels, every output, state element and selection against the oracle."""
+    sh = wl.Shape("paperscale", "bf16", 1, 4, 1, 128, 256, T=64 * 14 + 9, eta=256, lam=256, C=64, seed=0)
+    q, k, v, Wq, Wk = rand_case(211, 1, 4, 1, 128, 256, sh.T + 3, "bf16")
+    layer, o, rep = P.prefill_parity(sh, q[:, :, :sh.T], k[:, :, :sh.T], v[:, :, :sh.T], Wq, Wk)
+    rep2 = P.decode_parity(sh, layer, o, *steps(q, k, v, sh.T, 3), Wq, Wk)
+    say("paper-scale cache", rep, rep2)
+    assert rep["scored"] > 0
+
+
+def test_random_small_shapes():
+    """Twenty seeded random shapes (both storage types, both feature maps, odd chunk / window / budget
+    combinations, ragged lengths, GQA groups 1..4): prefill in two calls, then generation steps."""
+    g = wl.rng(424242, 0)
+    for case in range(20):
+        dtype = "bf16" if case % 2 else "f32"
+        d = int(g.choice([32, 64, 128]))
+        D = int(g.choice([8, 16, 32, 64, 128]))
+        Hkv = int(g.integers(1, 3)); grp = int(g.integers(1, 5)); Hq = Hkv * grp
+        B = int(g.integers(1, 3))
+        eta = int(g.integers(0, 20)); lam = int(g.integers(0, 20)); C_ = int(g.integers(1, 24))
+        T = int(g.integers(1, 90)); nd = int(g.integers(1, 6))
+        kind = int(case % 5 == 0)
+        say("random shape", case, dict(dtype=dtype, B=B, Hq=Hq, Hkv=Hkv, d=d, D=D, eta=eta, lam=lam, C=C_, T=T, nd=nd, kind=kind))
+        sh = wl.Shape(f"rnd{case}", dtype, B, Hq, Hkv, d, D, T, eta, lam, C_, seed=0)
+        q, k, v, Wq, Wk = rand_case(5000 + case, B, Hq, Hkv, d, D, T + nd, dtype, wscale=0.5 if kind else 1.0)
+        kw = dict(phi_kind=kind)
+        cut = T // 2
+        layer, o = None, None
+        for a_, b_ in ((0, cut), (cut, T)):
+            if b_ > a_:
+                layer, o, rep = P.prefill_parity(sh, q[:, :, a_:b_], k[:, :, a_:b_], v[:, :, a_:b_], Wq, Wk, layer=layer,
+                                                 oracle=o, layer_kw=kw)
+        if layer is None:
+            layer, o = P.make_layer(sh, **kw), P.make_oracle(sh, **kw)
+        rep2 = P.decode_parity(sh, layer, o, *steps(q, k, v, T, nd), Wq, Wk)
+        say("   ", rep2)
+
+
 def test_run_to_run_determinism():
     sh = wl.scaled(3, B=1, T=512)
     Wq, Wk = wl.weights(sh)
