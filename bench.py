@@ -185,36 +185,44 @@ def main():
 
     # ---- prefill leg (configuration 3) ----
     prefill = None
+    prefill_1b = None
     if not args.skip_prefill:
         del layers[1:], calls
         torch.cuda.empty_cache()
-        s3 = wl.CONFIGS[3]
-        W3q, W3k = wl.weights(s3)
-        q3, k3, v3, _ = wl.sequence_inputs(s3)
-        lay = lb.LolaLayer(s3.B, s3.Hq, s3.Hkv, s3.d, s3.D, s3.eta, s3.lam, s3.C, dtype="bf16", out_dtype="f32", device=dev)
-        a = [to_dev(x) for x in (q3, k3, v3, W3q.transpose(0, 2, 1), W3k.transpose(0, 2, 1))]
-        out3 = torch.empty((s3.B, s3.Hq, s3.T, s3.d), dtype=torch.float32, device=dev)
-        times = []
-        for r in range(args.prefill_reps + 1):
-            lay.reset()
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            lay.prefill(*a, out=out3)
-            e1.record()
-            torch.cuda.synchronize()
-            if r > 0:
-                times.append(e0.elapsed_time(e1))
-        ms = float(np.mean(times))
-        _, flops = prefill_alg_flops(s3)
-        tf = flops / (ms * 1e-3) / 1e12
-        prefill = {"workload": "configs[2]: 8B-shape prefill B=4 T=4096 eta=64 lambda=128 C=64 bf16",
-                   "tokens_per_s_per_layer": round(s3.B * s3.T / (ms * 1e-3), 1), "ms_per_call": round(ms, 3),
+
+        def prefill_leg(cid, label):
+            """Times lola_prefill (with outputs) on one of the prefill configurations."""
+            sc = wl.CONFIGS[cid]
+            Wq_, Wk_ = wl.weights(sc)
+            q_, k_, v_, _ = wl.sequence_inputs(sc)
+            lay = lb.LolaLayer(sc.B, sc.Hq, sc.Hkv, sc.d, sc.D, sc.eta, sc.lam, sc.C, dtype="bf16", out_dtype="f32", device=dev)
+            a_ = [to_dev(x) for x in (q_, k_, v_, Wq_.transpose(0, 2, 1), Wk_.transpose(0, 2, 1))]
+            out_ = torch.empty((sc.B, sc.Hq, sc.T, sc.d), dtype=torch.float32, device=dev)
+            times = []
+            for r in range(args.prefill_reps + 1):
+                lay.reset()
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                lay.prefill(*a_, out=out_)
+                e1.record()
+                torch.cuda.synchronize()
+                if r > 0:
+                    times.append(e0.elapsed_time(e1))
+            ms = float(np.mean(times))
+            _, flops = prefill_alg_flops(sc)
+            tf = flops / (ms * 1e-3) / 1e12
+            res = {"workload": label,
+                   "tokens_per_s_per_layer": round(sc.B * sc.T / (ms * 1e-3), 1), "ms_per_call": round(ms, 3),
                    "roofline": {"bound": "mfma", "achieved": round(tf, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                                 "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 5), "traffic": None,
                                 "alg_flops_per_call": flops, "kernel": lb.lola_kernel_path(lay.cfg, 0) + " prefill"}}
-        log(f"[prefill] {ms:.2f} ms per call, {prefill['tokens_per_s_per_layer'] / 1e6:.3f} M tokens/s/layer, {tf:.2f} TFLOP/s algorithmic")
-        del lay, a, out3
+            log(f"[prefill] {label}: {ms:.2f} ms per call, {res['tokens_per_s_per_layer'] / 1e6:.3f} M tokens/s/layer, "
+                f"{tf:.2f} TFLOP/s algorithmic")
+            return res
+
+        prefill = prefill_leg(3, "configs[2]: 8B-shape prefill B=4 T=4096 eta=64 lambda=128 C=64 bf16")
+        prefill_1b = prefill_leg(2, "configs[1]: 1B-shape prefill B=1 T=4096 head_dim=64 eta=64 lambda=64 C=64 bf16")
 
     # ---- CPU baseline: the oracle on a sample of the same decode workload ----
     cpu = None
@@ -256,7 +264,7 @@ def main():
         "config": {"workload": "configs[3]: 8B-shape decode, batch 64, 32 q / 8 kv heads, head_dim 128, feat_dim 128, "
                                f"eta 64, lambda 128, bf16 K/V + fp32 H/s, states prefilled with {sh.T} tokens, "
                                f"{L} layer-state copies cycled", "global_batch": sh.B, "prefill_tokens": sh.T, "layer_copies": L},
-        "roofline": roofline, "cpu_baseline": cpu, "prefill": prefill,
+        "roofline": roofline, "cpu_baseline": cpu, "prefill": prefill, "prefill_1b": prefill_1b,
     }
     print(json.dumps(line), flush=True)
 

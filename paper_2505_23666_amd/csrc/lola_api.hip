@@ -99,9 +99,10 @@ bool fast_decode_ok(const lola_config *c) {
            (c->sparse_budget == 128 || c->sparse_budget == 64) && c->n_q_heads / c->n_kv_heads == 4;
 }
 
-// The MFMA output kernel of the prefill covers the same head shape with chunk = window = 64.
+// The MFMA kernels of the prefill cover the Llama 8B and 1B head shapes (head_dim 128 / 64, 128 features) with
+// chunk = window = 64.
 bool fast_attend_ok(const lola_config *c) {
-    return c->dtype == LOLA_BF16 && c->head_dim == 128 && c->feat_dim == 128 && c->window == 64 && c->chunk == 64 &&
+    return c->dtype == LOLA_BF16 && (c->head_dim == 128 || c->head_dim == 64) && c->feat_dim == 128 && c->window == 64 && c->chunk == 64 &&
            (c->sparse_budget == 64 || c->sparse_budget == 128 || c->sparse_budget == 256) &&
            c->n_q_heads / c->n_kv_heads == 4;
 }
@@ -236,14 +237,17 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
                 // features of the pass's keys (chunk-parallel); then the serial evolution in three legs that hand the
                 // chunk position over in next_j: generic kernel until the first regular chunk, MFMA kernel over the
                 // regular chunks, generic kernel for what is left (a ragged last chunk)
-                hipLaunchKernelGGL(fast::phi_k_kernel, dim3((unsigned)(a.j1 - a.j0), (unsigned)ns), dim3(256), 0, stream, a);
+                const dim3 gp((unsigned)(a.j1 - a.j0), (unsigned)ns);
+                if (c->head_dim == 128) hipLaunchKernelGGL(fast::phi_k_kernel<128>, gp, dim3(256), 0, stream, a);
+                else hipLaunchKernelGGL(fast::phi_k_kernel<64>, gp, dim3(256), 0, stream, a);
                 LAUNCH_CHECK();
                 a.scan_mode = 1;
                 hipLaunchKernelGGL((generic::scan_kernel<T>), gs, block, lds_scan, stream, a);
                 LAUNCH_CHECK();
-                if (c->sparse_budget == 64) hipLaunchKernelGGL((fast::scan_fast_kernel<64>), gs, dim3(512), 0, stream, a);
-                else if (c->sparse_budget == 128) hipLaunchKernelGGL((fast::scan_fast_kernel<128>), gs, dim3(512), 0, stream, a);
-                else hipLaunchKernelGGL((fast::scan_fast_kernel<256>), gs, dim3(512), 0, stream, a);
+#define LOLA_SCAN(LAMV) do { if (c->head_dim == 128) hipLaunchKernelGGL((fast::scan_fast_kernel<LAMV, 128>), gs, dim3(512), 0, stream, a); \
+                             else hipLaunchKernelGGL((fast::scan_fast_kernel<LAMV, 64>), gs, dim3(256), 0, stream, a); } while (0)
+                if (c->sparse_budget == 64) LOLA_SCAN(64); else if (c->sparse_budget == 128) LOLA_SCAN(128); else LOLA_SCAN(256);
+#undef LOLA_SCAN
                 LAUNCH_CHECK();
                 a.scan_mode = 2;
                 hipLaunchKernelGGL((generic::scan_kernel<T>), gs, block, lds_scan, stream, a);
@@ -261,10 +265,12 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
             if constexpr (std::is_same<T, bf16_t>::value) {
                 if (fast_att) {
                     const bool f32o = c->out_dtype == LOLA_F32;
-#define LOLA_ATT(LAMV) do { if (f32o) hipLaunchKernelGGL((fast::attend_fast_kernel<LAMV, float>), ga, dim3(256), 0, stream, a); \
-                            else hipLaunchKernelGGL((fast::attend_fast_kernel<LAMV, bf16_t>), ga, dim3(256), 0, stream, a); } while (0)
+#define LOLA_ATT2(LAMV, DHV) do { if (f32o) hipLaunchKernelGGL((fast::attend_fast_kernel<LAMV, DHV, float>), ga, dim3(256), 0, stream, a); \
+                                  else hipLaunchKernelGGL((fast::attend_fast_kernel<LAMV, DHV, bf16_t>), ga, dim3(256), 0, stream, a); } while (0)
+#define LOLA_ATT(LAMV) do { if (c->head_dim == 128) LOLA_ATT2(LAMV, 128); else LOLA_ATT2(LAMV, 64); } while (0)
                     if (c->sparse_budget == 64) LOLA_ATT(64); else if (c->sparse_budget == 128) LOLA_ATT(128); else LOLA_ATT(256);
 #undef LOLA_ATT
+#undef LOLA_ATT2
                     LAUNCH_CHECK();
                     continue;
                 }

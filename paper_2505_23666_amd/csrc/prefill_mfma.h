@@ -27,9 +27,10 @@ namespace fast {
 __device__ __forceinline__ int perm_chunk(int x) { return ((x >> 5) << 2) | ((x >> 2) & 3); }
 __device__ __forceinline__ int perm_elem(int x) { return (((x >> 4) & 1) << 2) | (x & 3); }
 
-template <int LAM, typename TO>
+template <int LAM, int DH, typename TO>
 __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArgs<bf16_t> a) {
-    constexpr int DH = 128, M = 64, D = 128, C = 64, ETA = 64, G = 4;
+    constexpr int M = 64, D = 128, C = 64, ETA = 64, G = 4, KS = DH / 32, PR = DH / 8, NCT = DH / 16;
+    static_assert(DH == 64 || DH == 128, "head_dim");
     constexpr int P = LAM + ETA;                    // rows of the virtual prefix
     constexpr int NKEYS = LAM + ETA + C;            // key positions
     constexpr int NB = (NKEYS + 127) / 128;         // key blocks
@@ -59,22 +60,22 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
     // ---- loads: this wavefront's queries as MFMA B operand (column = query, k = input index); rows past the chunk's
     // end are read from row 0 (their results are never stored)
     const int qi = 16 * w + r16;
-    bf16x8 BQ[4];
+    bf16x8 BQ[KS];
 #pragma unroll
-    for (int ks = 0; ks < 4; ks++) BQ[ks] = ld_bf16x8(qh + (size_t)(qi < cl ? qi : 0) * DH + 32 * ks + 8 * g4);
+    for (int ks = 0; ks < KS; ks++) BQ[ks] = ld_bf16x8(qh + (size_t)(qi < cl ? qi : 0) * DH + 32 * ks + 8 * g4);
     // H^T snapshot -> LDS, 16-byte chunks XOR-swizzled by the row so that operand reads are conflict free
     if (tid < D / 4) reinterpret_cast<float4 *>(s_l)[tid] = reinterpret_cast<const float4 *>(ssnap)[tid];
     for (int x = tid; x < LAM; x += 256) G_l[x] = Gsnap[x];
 #pragma unroll
-    for (int p4 = 0; p4 < 4; p4++) {
+    for (int p4 = 0; p4 < DH / 32; p4++) {
         uint4 hv[4];
 #pragma unroll
         for (int it = 0; it < 4; it++) hv[it] = reinterpret_cast<const uint4 *>(Hsnap)[tid + 256 * (4 * p4 + it)];
 #pragma unroll
         for (int it = 0; it < 4; it++) {
-            // snapshot order: [part][row block of 32][row tile of 16][k-step][lane = 16 (piece % 4) + row % 16]
-            const int o = tid + 256 * (4 * p4 + it), part = o >> 11;
-            const int c = 32 * ((o >> 9) & 3) + 16 * ((o >> 8) & 1) + (o & 15), ch = 4 * ((o >> 6) & 3) + ((o >> 4) & 3);
+            // snapshot order: [part][row tile of 16][k-step][lane = 16 (piece % 4) + row % 16]
+            const int o = tid + 256 * (4 * p4 + it), part = o / (DH * 16), op = o % (DH * 16);
+            const int c = 16 * (op >> 8) + (o & 15), ch = 4 * ((o >> 6) & 3) + ((o >> 4) & 3);
             *reinterpret_cast<uint4 *>(&L[part * DH * D + c * D + ((ch ^ (c & 15)) << 3)]) = hv[it];
         }
     }
@@ -86,7 +87,7 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
         for (int mt = 0; mt < 4; mt++) {
             zt[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int ks = 0; ks < 4; ks++)
+            for (int ks = 0; ks < KS; ks++)
                 zt[mt] = mfma16(ld_bf16x8(Wq + (size_t)(16 * mt + r16) * DH + 32 * ks + 8 * g4), BQ[ks], zt[mt]);
         }
         phi_from_z(zt, a.dm.phi_kind, pp, pn);
@@ -104,13 +105,13 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
     }
     lden = grp_sum(lden);
     // ---- linear part: lin^T[c][q] = sum_f H^T[c][f] phi(q)[f]
-    f32x4 lin[8];
+    f32x4 lin[NCT];
     {
         bf16x8 Bh[4], Bl[4];
         split8(&pp[0], Bh[0], Bl[0]); split8(&pp[8], Bh[1], Bl[1]);
         split8(&pn[0], Bh[2], Bl[2]); split8(&pn[8], Bh[3], Bl[3]);
 #pragma unroll
-        for (int mt = 0; mt < 8; mt++) {
+        for (int mt = 0; mt < NCT; mt++) {
             f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acc2 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < 4; ks++) {
@@ -126,19 +127,19 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
     }
 
     // ---- softmax part over key blocks of 128 positions
-    uint16_t *Kl = L, *Vt = L + DH * 128;   // [key][input chunk ^ key%16] and [c][key chunk ^ swz(c)], 32 KB each
-    f32x4 out[8];
+    uint16_t *Kl = L, *Vt = L + DH * 128;   // [key][input piece ^ key % pieces] and [c][key chunk ^ swz(c)]
+    f32x4 out[NCT];
 #pragma unroll
-    for (int mt = 0; mt < 8; mt++) out[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int mt = 0; mt < NCT; mt++) out[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
     float mrun = 0.f, lsum = 0.f;   // running max (units of log2 e) and running sum of weights
     const int64_t tq = aj + qi;     // token index of this lane's query
 #pragma unroll 1
     for (int blk = 0; blk < NB; blk++) {
         // position -> source row (or none).  Thread handles 8 (key, 16-byte chunk) pairs of the block
         // (named scalars: an array held across the barrier would be sent through scratch memory).
-#define LOLA_REP8(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7)
-#define LOLA_KVLOAD(it) uint4 kreg##it = make_uint4(0, 0, 0, 0), vreg##it = make_uint4(0, 0, 0, 0); { \
-            const int o = tid + 256 * it, kk = o >> 4, ch = o & 15, pos = 128 * blk + kk; \
+#define LOLA_REP8(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7)   // items beyond 128 * PR / 256 compile to nothing
+#define LOLA_KVLOAD(it) uint4 kreg##it = make_uint4(0, 0, 0, 0), vreg##it = make_uint4(0, 0, 0, 0); if (it < PR / 2) { \
+            const int o = tid + 256 * it, kk = o / PR, ch = o % PR, pos = 128 * blk + kk; \
             int vr = -1; \
             if (pos < LAM) vr = G_l[pos]; \
             else if (pos < NKEYS) { vr = vrow_c - ETA + (pos - LAM); if (aj - ETA + (pos - LAM) < 0 || (pos - LAM - ETA) >= cl) vr = -1; } \
@@ -148,9 +149,9 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
                 kreg##it = reinterpret_cast<const uint4 *>(kr)[ch]; \
                 vreg##it = reinterpret_cast<const uint4 *>(vrp)[ch]; \
             } }
-#define LOLA_KVSTORE(it) { \
-            const int o = tid + 256 * it, kk = o >> 4, ch = o & 15; \
-            *reinterpret_cast<uint4 *>(&Kl[kk * DH + ((ch ^ (kk & 15)) << 3)]) = kreg##it; \
+#define LOLA_KVSTORE(it) if (it < PR / 2) { \
+            const int o = tid + 256 * it, kk = o / PR, ch = o % PR; \
+            *reinterpret_cast<uint4 *>(&Kl[kk * DH + ((ch ^ (kk & (PR - 1))) << 3)]) = kreg##it; \
             const uint32_t u[4] = {vreg##it.x, vreg##it.y, vreg##it.z, vreg##it.w}; \
             const int kchunk = perm_chunk(kk), kel = perm_elem(kk); \
             _Pragma("unroll") for (int x = 0; x < 8; x++) { \
@@ -171,8 +172,8 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
         for (int mt = 0; mt < 8; mt++) {
             f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int ks = 0; ks < 4; ks++)
-                acc = mfma16(as_bf16x8(*reinterpret_cast<const uint4 *>(&Kl[(16 * mt + r16) * DH + (((4 * ks + g4) ^ r16) << 3)])), BQ[ks], acc);
+            for (int ks = 0; ks < KS; ks++)
+                acc = mfma16(as_bf16x8(*reinterpret_cast<const uint4 *>(&Kl[(16 * mt + r16) * DH + (((4 * ks + g4) ^ (r16 & (PR - 1))) << 3)])), BQ[ks], acc);
 #pragma unroll
             for (int i = 0; i < 4; i++) {
                 const int pos = 128 * blk + 16 * mt + 4 * g4 + i;
@@ -190,7 +191,7 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
         mrun = bmax;
         lsum *= resc;
 #pragma unroll
-        for (int mt = 0; mt < 8; mt++) out[mt] *= resc;
+        for (int mt = 0; mt < NCT; mt++) out[mt] *= resc;
         // weights and out^T += V^T P^T, 32 keys per k-step (key tiles 2s, 2s+1)
 #pragma unroll
         for (int s = 0; s < 4; s++) {
@@ -200,7 +201,7 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
             bf16x8 Ph, Pl;
             split8(pw, Ph, Pl);
 #pragma unroll
-            for (int mt = 0; mt < 8; mt++) {
+            for (int mt = 0; mt < NCT; mt++) {
                 const int c = 16 * mt + r16;
                 const bf16x8 Av = as_bf16x8(*reinterpret_cast<const uint4 *>(&Vt[c * 128 + (((4 * s + g4) ^ ((c ^ (c >> 3)) & 15)) << 3)]));
                 out[mt] = mfma16(Av, Ph, out[mt]);
@@ -214,7 +215,7 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
         const float el = fexp2(-mrun);
         const float inv = 1.0f / fmaf(el, lden, lsum);
 #pragma unroll
-        for (int mt = 0; mt < 8; mt++) {
+        for (int mt = 0; mt < NCT; mt++) {
             TO *dst = oh + (size_t)qi * DH + 16 * mt + 4 * g4;
 #pragma unroll
             for (int i = 0; i < 4; i++) stf(dst, i, fmaf(el, lin[mt][i], out[mt][i]) * inv);
@@ -251,22 +252,23 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
 // phi of the keys of every chunk of a pass (Sec. 2.3 eq. feature_map), chunk-parallel: grid (chunk of the pass, stream),
 // one 16-key tile per wavefront.  The serial state evolution below then only reads these rows (bf16 high + low parts,
 // features in operand order) when the chunk's pairs leave the window one chunk later.
+template <int DH>
 __global__ __launch_bounds__(256) void phi_k_kernel(generic::PrefillArgs<bf16_t> a) {
-    constexpr int DH = 128, M = 64, D = 128, C = 64;
+    constexpr int M = 64, D = 128, C = 64, KS = DH / 32;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r16 = lane & 15, g4 = lane >> 4;
     const int jj = blockIdx.x, j = a.j0 + jj, si = blockIdx.y, h = si % a.dm.Hkv;
     const int row = 16 * w + r16, tok = j * C + row;
     const bf16_t *Wk = a.Wk + (size_t)h * M * DH;
     const bf16_t *kr = a.k + ((size_t)si * a.T_tokens + tok) * DH;
-    bf16x8 BK[4];
+    bf16x8 BK[KS];
 #pragma unroll
-    for (int ks = 0; ks < 4; ks++) BK[ks] = tok < a.T_tokens ? ld_bf16x8(kr + 32 * ks + 8 * g4) : zero_bf16x8();
+    for (int ks = 0; ks < KS; ks++) BK[ks] = tok < a.T_tokens ? ld_bf16x8(kr + 32 * ks + 8 * g4) : zero_bf16x8();
     f32x4 zt[4];
 #pragma unroll
     for (int mt = 0; mt < 4; mt++) {
         zt[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int ks = 0; ks < 4; ks++)
+        for (int ks = 0; ks < KS; ks++)
             zt[mt] = mfma16(ld_bf16x8(Wk + (size_t)(16 * mt + r16) * DH + 32 * ks + 8 * g4), BK[ks], zt[mt]);
     }
     float pp[16], pn[16];
@@ -286,9 +288,11 @@ __global__ __launch_bounds__(256) void phi_k_kernel(generic::PrefillArgs<bf16_t>
 // between the rows one wavefront writes at once (r2, r3, r5) and between the rows it reads at once (r0 .. r3).
 __device__ __forceinline__ int tswz(int r) { return ((((r >> 5) ^ r) & 1) << 2) | ((r >> 2) & 3); }
 
-template <int LAM>
-__global__ __launch_bounds__(512, 1) void scan_fast_kernel(generic::PrefillArgs<bf16_t> a) {
-    constexpr int DH = 128, M = 64, D = 128, C = 64, ETA = 64, NW = 8, NTH = 512;
+template <int LAM, int DH>
+__global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillArgs<bf16_t> a) {
+    // one wavefront per 16 rows of H^T: 8 wavefronts for head_dim 128, 4 for head_dim 64
+    constexpr int M = 64, D = 128, C = 64, ETA = 64, NW = DH / 16, NTH = 64 * NW, KS = DH / 32, PR = DH / 8;
+    static_assert(DH == 64 || DH == 128, "head_dim");
     constexpr int P = LAM + ETA, NE = LAM + C, NTILE = NE / 16, TB = LAM > 128 ? 10 : 12, RB = TB * 16;
     constexpr int TPW = (TB + NW - 1) / NW, NK = NE / 64, TC = LAM / 16;
     constexpr bool PERSIST = NTILE <= TB;   // one batch: the candidates' features all fit in LDS and the cache's part stays there
@@ -330,10 +334,13 @@ __global__ __launch_bounds__(512, 1) void scan_fast_kernel(generic::PrefillArgs<
     LOLA_SREP(LOLA_SDECL)
     bool started = false;
     bool phi_valid = false;     // PERSIST: rows [0, LAM) of PB hold phi of the cache slots, and PHn / vvn the rows requested ahead
-    uint4 PHn[4];               // this thread's pieces of phi of the pairs that leave the window in the next chunk
+    constexpr int PHN = C * 32 / NTH;   // 16-byte pieces of a chunk's features per thread
+    uint4 PHn[PHN];             // this thread's pieces of phi of the pairs that leave the window in the next chunk
     uint2 vvn[4];               // their values at this wavefront's columns
 #pragma unroll
-    for (int x = 0; x < 4; x++) { PHn[x] = make_uint4(0, 0, 0, 0); vvn[x] = make_uint2(0, 0); }
+    for (int x = 0; x < 4; x++) vvn[x] = make_uint2(0, 0);
+#pragma unroll
+    for (int x = 0; x < PHN; x++) PHn[x] = make_uint4(0, 0, 0, 0);
 
     for (; j < a.j1; j++) {
         const int cl = min(C, a.T_tokens - j * C);
@@ -408,31 +415,31 @@ __global__ __launch_bounds__(512, 1) void scan_fast_kernel(generic::PrefillArgs<
             }
             if (have_phi) {   // the rows requested one chunk ago take their place behind the cache's rows
 #pragma unroll
-                for (int it = 0; it < 4; it++) {
+                for (int it = 0; it < PHN; it++) {
                     const int o = tid + NTH * it, row = o >> 5, pt = (o >> 4) & 1, pc = o & 15;
                     *reinterpret_cast<uint4 *>(&PB[pt * RB * D + (LAM + row) * D + ((pc ^ (row & 15)) << 3)]) = PHn[it];
                 }
             } else {
                 // phi of the batch's tiles (first regular chunk of a pass, or a cache too large to stay in LDS):
-                // wavefront w takes tiles t0 + w, t0 + w + 8
-                bf16x8 AW[4][4];
+                // wavefront w takes tiles t0 + w, t0 + w + NW, ...
+                bf16x8 AW[4][KS];
 #pragma unroll
                 for (int mt = 0; mt < 4; mt++)
 #pragma unroll
-                    for (int ks = 0; ks < 4; ks++) AW[mt][ks] = ld_bf16x8(Wk + (size_t)(16 * mt + r16) * DH + 32 * ks + 8 * g4);
+                    for (int ks = 0; ks < KS; ks++) AW[mt][ks] = ld_bf16x8(Wk + (size_t)(16 * mt + r16) * DH + 32 * ks + 8 * g4);
 #pragma unroll 1
                 for (int t = t0 + w; t < t1; t += NW) {
                     const int e = 16 * t + r16;
                     const bf16_t *kr = krow(e);
-                    bf16x8 BK[4];
+                    bf16x8 BK[KS];
 #pragma unroll
-                    for (int ks = 0; ks < 4; ks++) BK[ks] = ld_bf16x8(kr + 32 * ks + 8 * g4);
+                    for (int ks = 0; ks < KS; ks++) BK[ks] = ld_bf16x8(kr + 32 * ks + 8 * g4);
                     f32x4 zt[4];
 #pragma unroll
                     for (int mt = 0; mt < 4; mt++) {
                         zt[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                        for (int ks = 0; ks < 4; ks++) zt[mt] = mfma16(AW[mt][ks], BK[ks], zt[mt]);
+                        for (int ks = 0; ks < KS; ks++) zt[mt] = mfma16(AW[mt][ks], BK[ks], zt[mt]);
                     }
                     float pp[16], pn[16];
                     phi_from_z(zt, a.dm.phi_kind, pp, pn);
@@ -455,7 +462,7 @@ __global__ __launch_bounds__(512, 1) void scan_fast_kernel(generic::PrefillArgs<
             if (PERSIST) {   // this chunk's own pairs leave the window in the next chunk
                 const uint4 *ph = reinterpret_cast<const uint4 *>(a.phiK + ((size_t)si * a.S + (j - a.j0)) * C * 2 * D);
 #pragma unroll
-                for (int it = 0; it < 4; it++) PHn[it] = ph[tid + NTH * it];
+                for (int it = 0; it < PHN; it++) PHn[it] = ph[tid + NTH * it];
 #pragma unroll
                 for (int u = 0; u < 4; u++)
                     vvn[u] = *reinterpret_cast<const uint2 *>(vc + (size_t)(j * C + 16 * u + r16) * DH + 16 * w + 4 * g4);
@@ -621,11 +628,13 @@ __global__ __launch_bounds__(512, 1) void scan_fast_kernel(generic::PrefillArgs<
         // these writes fall on all banks (two lanes per bank) and the 128-bit operand reads of the MFMAs below
         // on all eight chunks evenly.
         {
+            // phi^T: piece ch, part pt = w % 2 and column chunk w / 2 + (NW / 2) it of the folded pairs
+            constexpr int CPW = NW / 2, PIT = 8 / CPW;
             const int ch = tid & 15, pairpos = (tid >> 4) & 3, pt = w & 1;
-            uint4 pa[2], pb[2], va, vb;
+            uint4 pa[PIT], pb[PIT], va, vb;
 #pragma unroll
-            for (int it = 0; it < 2; it++) {
-                const int ep = 8 * ((w >> 1) + 4 * it) + 2 * pairpos;
+            for (int it = 0; it < PIT; it++) {
+                const int ep = 8 * ((w >> 1) + CPW * it) + 2 * pairpos;
                 const int ea = flist[ep], eb = flist[ep + 1];
                 if (PERSIST) {
                     pa[it] = *reinterpret_cast<const uint4 *>(&PB[pt * RB * D + ea * D + ((ch ^ (ea & 15)) << 3)]);
@@ -635,10 +644,12 @@ __global__ __launch_bounds__(512, 1) void scan_fast_kernel(generic::PrefillArgs<
                     pb[it] = *reinterpret_cast<const uint4 *>(phiE + (size_t)eb * 2 * D + pt * D + (ch << 3));
                 }
             }
+            // v^T: one item per thread: piece vch of the value rows of column pair vpair
+            const int vch = tid % PR, vpair = tid / PR;
             {
-                const int ep = 8 * w + 2 * pairpos;
-                va = reinterpret_cast<const uint4 *>(vrow(flist[ep]))[ch];
-                vb = reinterpret_cast<const uint4 *>(vrow(flist[ep + 1]))[ch];
+                const int ep = 2 * vpair;
+                va = reinterpret_cast<const uint4 *>(vrow(flist[ep]))[vch];
+                vb = reinterpret_cast<const uint4 *>(vrow(flist[ep + 1]))[vch];
             }
             // feature held by element x of piece ch (operand order): 32 (ch / 4) + 16 (x / 4) + 4 (ch % 4) + x % 4
 #pragma unroll
@@ -646,16 +657,16 @@ __global__ __launch_bounds__(512, 1) void scan_fast_kernel(generic::PrefillArgs<
                 const int f = 32 * (ch >> 2) + 16 * (x >> 2) + 4 * (ch & 3) + (x & 3);
                 const int bx = pt * D * C + f * C + ((((w >> 1) ^ tswz(f))) << 3) + 2 * pairpos;
 #pragma unroll
-                for (int it = 0; it < 2; it++) {
+                for (int it = 0; it < PIT; it++) {
                     const uint32_t ua = (&pa[it].x)[x >> 1], ub = (&pb[it].x)[x >> 1];
                     const uint32_t wv = (x & 1) ? ((ua >> 16) | (ub & 0xFFFF0000u)) : ((ua & 0xFFFFu) | (ub << 16));
-                    *reinterpret_cast<uint32_t *>(&PT[bx ^ (it << 5)]) = wv;
+                    *reinterpret_cast<uint32_t *>(&PT[bx ^ ((CPW * it) << 3)]) = wv;
                 }
             }
 #pragma unroll
             for (int x = 0; x < 8; x++) {
-                const int c = 8 * ch + x;
-                const int bx = c * C + (((w ^ tswz(c))) << 3) + 2 * pairpos;
+                const int c = 8 * vch + x;
+                const int bx = c * C + ((((vpair >> 2) ^ tswz(c))) << 3) + 2 * (vpair & 3);
                 const uint32_t ua = (&va.x)[x >> 1], ub = (&vb.x)[x >> 1];
                 const uint32_t wv = (x & 1) ? ((ua >> 16) | (ub & 0xFFFF0000u)) : ((ua & 0xFFFFu) | (ub << 16));
                 *reinterpret_cast<uint32_t *>(&VT[bx]) = wv;
@@ -671,10 +682,10 @@ __global__ __launch_bounds__(512, 1) void scan_fast_kernel(generic::PrefillArgs<
 #pragma unroll
             for (int it = 0; it < 4; it++) {
                 const int o = tid + NTH * it;
-                if (o < ne * 32) {
-                    const int x = o >> 5, rem = o & 31;
+                if (o < ne * 2 * PR) {
+                    const int x = o / (2 * PR), rem = o % (2 * PR);
                     const int e = ecand[x];
-                    cp[it] = reinterpret_cast<const uint4 *>((rem >> 4) ? vrow(e) : krow(e))[rem & 15];
+                    cp[it] = reinterpret_cast<const uint4 *>((rem >= PR) ? vrow(e) : krow(e))[rem % PR];
                 }
             }
             bf16x8 Bv[2];
@@ -689,37 +700,42 @@ __global__ __launch_bounds__(512, 1) void scan_fast_kernel(generic::PrefillArgs<
 #define LOLA_SFA(dst, mt) _Pragma("unroll") for (int x = 0; x < 4; x++) { const int f = 16 * (mt) + r16; \
                 dst[x] = as_bf16x8(*reinterpret_cast<const uint4 *>(&PT[(x >> 1) * D * C + f * C + (((4 * (x & 1) + g4) ^ tswz(f)) << 3)])); }
             LOLA_SFA(Ac, 0)
-            // s += sum of the folded features: feature tile w's operands times a vector of ones, by wavefront w
+            // s += sum of the folded features: a feature tile's operands times a vector of ones (tile mt by wavefront mt % NW)
             const bf16x8 ones = as_bf16x8(make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u));
-            f32x4 sacc = {0.f, 0.f, 0.f, 0.f};
+            f32x4 sacc[8 / NW];
+#pragma unroll
+            for (int x = 0; x < 8 / NW; x++) sacc[x] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #define LOLA_SFOLD2(ks, hf) { if (2 * ks + hf + 1 < 8) { LOLA_SFA(An, 2 * ks + hf + 1) } \
             _Pragma("unroll") for (int x = 0; x < 4; x++) hreg##ks##hf = mfma16(Ac[x], Bv[x & 1], hreg##ks##hf); \
-            if (2 * ks + hf == w) { _Pragma("unroll") for (int x = 0; x < 4; x++) sacc = mfma16(Ac[x], ones, sacc); } \
+            if (((2 * ks + hf) & (NW - 1)) == w) { _Pragma("unroll") for (int x = 0; x < 4; x++) sacc[(2 * ks + hf) / NW] = mfma16(Ac[x], ones, sacc[(2 * ks + hf) / NW]); } \
             __builtin_amdgcn_sched_barrier(0); \
             _Pragma("unroll") for (int x = 0; x < 4; x++) Ac[x] = An[x]; }
             LOLA_SREP(LOLA_SFOLD2)
 #undef LOLA_SFOLD2
 #undef LOLA_SFA
-            if (r16 == 0) {   // column 0 of the result tile: features 16w + 4 g4 + 0..3
-                float4 *sp = reinterpret_cast<float4 *>(&s_l[16 * w + 4 * g4]);
-                float4 sv = *sp;
-                sv.x += sacc[0]; sv.y += sacc[1]; sv.z += sacc[2]; sv.w += sacc[3];
-                *sp = sv;
+            if (r16 == 0) {   // column 0 of the result tiles: features 16 (w + NW x) + 4 g4 + 0..3
+#pragma unroll
+                for (int x = 0; x < 8 / NW; x++) {
+                    float4 *sp = reinterpret_cast<float4 *>(&s_l[16 * (w + NW * x) + 4 * g4]);
+                    float4 sv = *sp;
+                    sv.x += sacc[x][0]; sv.y += sacc[x][1]; sv.z += sacc[x][2]; sv.w += sacc[x][3];
+                    *sp = sv;
+                }
             }
             if (j == a.j1 - 1) LOLA_STAMP(10);
             // ---- 5. compaction, second half: entrants take the leavers' slots, in the state and (their features) in LDS
 #pragma unroll
             for (int it = 0; it < 4; it++) {
                 const int o = tid + NTH * it;
-                if (o < ne * 32) {
-                    const int x = o >> 5, rem = o & 31;
-                    bf16_t *dst = ((rem >> 4) ? sp_v : sp_k) + (size_t)eslot[x] * DH;
-                    reinterpret_cast<uint4 *>(dst)[rem & 15] = cp[it];
+                if (o < ne * 2 * PR) {
+                    const int x = o / (2 * PR), rem = o % (2 * PR);
+                    bf16_t *dst = ((rem >= PR) ? sp_v : sp_k) + (size_t)eslot[x] * DH;
+                    reinterpret_cast<uint4 *>(dst)[rem % PR] = cp[it];
                 }
             }
             if (PERSIST) {
 #pragma unroll
-                for (int it = 0; it < 4; it++) {
+                for (int it = 0; it < PHN; it++) {
                     const int o = tid + NTH * it;
                     if (o < ne * 32) {
                         const int x = o >> 5, rem = o & 31, pt = rem >> 4, ch = rem & 15;

@@ -156,6 +156,25 @@ def test_8b_shape_resume_ragged_multipass(lam, phi_kind):
         say("8b resume part", i, rep)
 
 
+@pytest.mark.parametrize("lam", [64, 128])
+def test_1b_shape_resume_ragged_multipass(lam):
+    """The MFMA prefill kernels at the 1B head shape (head_dim 64, 128 features) across call boundaries that are
+    not chunk-aligned, an update-only call and a multi-pass workspace; then generation steps (generic kernel)."""
+    sh = wl.scaled(2, T=64 * 12 + 21, lam=lam, n_decode=3)
+    Wq, Wk = wl.weights(sh)
+    q, k, v, _ = wl.sequence_inputs(sh)
+    cuts = [0, 64 * 4 + 5, 64 * 7 + 5, 64 * 9 + 33, sh.T]
+    layer, o = None, None
+    for i in range(4):
+        a, b = cuts[i], cuts[i + 1]
+        layer, o, rep = P.prefill_parity(sh, q[:, :, a:b], k[:, :, a:b], v[:, :, a:b], Wq, Wk, layer=layer, oracle=o,
+                                         with_outputs=(i != 2), workspace_limit=0 if i == 3 else None)
+        say("1b resume part", i, rep)
+    assert layer.lola_path[0] == "mfma"
+    rep2 = P.decode_parity(sh, layer, o, *steps(q, k, v, sh.T, sh.n_decode), Wq, Wk)
+    say("1b decode after prefill", rep2)
+
+
 def test_bf16_outputs():
     sh = wl.scaled(2, T=256)
     Wq, Wk = wl.weights(sh)
