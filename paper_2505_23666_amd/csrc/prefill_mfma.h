@@ -63,68 +63,9 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
     bf16x8 BQ[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) BQ[ks] = ld_bf16x8(qh + (size_t)(qi < cl ? qi : 0) * DH + 32 * ks + 8 * g4);
-    // H^T snapshot -> LDS, 16-byte chunks XOR-swizzled by the row so that operand reads are conflict free
     if (tid < D / 4) reinterpret_cast<float4 *>(s_l)[tid] = reinterpret_cast<const float4 *>(ssnap)[tid];
     for (int x = tid; x < LAM; x += 256) G_l[x] = Gsnap[x];
-#pragma unroll
-    for (int p4 = 0; p4 < DH / 32; p4++) {
-        uint4 hv[4];
-#pragma unroll
-        for (int it = 0; it < 4; it++) hv[it] = reinterpret_cast<const uint4 *>(Hsnap)[tid + 256 * (4 * p4 + it)];
-#pragma unroll
-        for (int it = 0; it < 4; it++) {
-            // snapshot order: [part][row tile of 16][k-step][lane = 16 (piece % 4) + row % 16]
-            const int o = tid + 256 * (4 * p4 + it), part = o / (DH * 16), op = o % (DH * 16);
-            const int c = 16 * (op >> 8) + (o & 15), ch = 4 * ((o >> 6) & 3) + ((o >> 4) & 3);
-            *reinterpret_cast<uint4 *>(&L[part * DH * D + c * D + ((ch ^ (c & 15)) << 3)]) = hv[it];
-        }
-    }
-    // ---- phi(q): z^T = W_q Q^T (A = W_q rows from global, B = queries)
-    float pp[16], pn[16];
-    {
-        f32x4 zt[4];
-#pragma unroll
-        for (int mt = 0; mt < 4; mt++) {
-            zt[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int ks = 0; ks < KS; ks++)
-                zt[mt] = mfma16(ld_bf16x8(Wq + (size_t)(16 * mt + r16) * DH + 32 * ks + 8 * g4), BQ[ks], zt[mt]);
-        }
-        phi_from_z(zt, a.dm.phi_kind, pp, pn);
-    }
     __syncthreads();
-    float lden = 0.f;   // phi(q)^T s
-#pragma unroll
-    for (int mt = 0; mt < 4; mt++) {
-        const float4 sp4 = *reinterpret_cast<const float4 *>(&s_l[16 * mt + 4 * g4]);
-        const float4 sn4 = *reinterpret_cast<const float4 *>(&s_l[M + 16 * mt + 4 * g4]);
-        lden = fmaf(pp[4 * mt], sp4.x, lden); lden = fmaf(pp[4 * mt + 1], sp4.y, lden);
-        lden = fmaf(pp[4 * mt + 2], sp4.z, lden); lden = fmaf(pp[4 * mt + 3], sp4.w, lden);
-        lden = fmaf(pn[4 * mt], sn4.x, lden); lden = fmaf(pn[4 * mt + 1], sn4.y, lden);
-        lden = fmaf(pn[4 * mt + 2], sn4.z, lden); lden = fmaf(pn[4 * mt + 3], sn4.w, lden);
-    }
-    lden = grp_sum(lden);
-    // ---- linear part: lin^T[c][q] = sum_f H^T[c][f] phi(q)[f]
-    f32x4 lin[NCT];
-    {
-        bf16x8 Bh[4], Bl[4];
-        split8(&pp[0], Bh[0], Bl[0]); split8(&pp[8], Bh[1], Bl[1]);
-        split8(&pn[0], Bh[2], Bl[2]); split8(&pn[8], Bh[3], Bl[3]);
-#pragma unroll
-        for (int mt = 0; mt < NCT; mt++) {
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acc2 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int ks = 0; ks < 4; ks++) {
-                const int addr = (16 * mt + r16) * D + (((4 * ks + g4) ^ r16) << 3);
-                const bf16x8 Ahi = as_bf16x8(*reinterpret_cast<const uint4 *>(&L[addr]));
-                const bf16x8 Alo = as_bf16x8(*reinterpret_cast<const uint4 *>(&L[DH * D + addr]));
-                acc = mfma16(Ahi, Bh[ks], acc);
-                acc2 = mfma16(Ahi, Bl[ks], acc2);
-                acc2 = mfma16(Alo, Bh[ks], acc2);
-            }
-            lin[mt] = acc + acc2;
-        }
-    }
 
     // ---- softmax part over key blocks of 128 positions
     uint16_t *Kl = L, *Vt = L + DH * 128;   // [key][input piece ^ key % pieces] and [c][key chunk ^ swz(c)]
@@ -210,15 +151,72 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
         }
     }
     lsum = grp_sum(lsum);
-    // ---- y = (out + exp(-m) lin) / (sum p + exp(-m) phi(q)^T s); lane holds columns c = 16 mt + 4 g4 + 0..3 of query qi
-    if (qi < cl) {
-        const float el = fexp2(-mrun);
-        const float inv = 1.0f / fmaf(el, lden, lsum);
+
+    // ---- linear part, after the softmax part so that its operands do not occupy registers during the key blocks:
+    // H^T snapshot -> LDS (16-byte pieces XOR-swizzled by the row so that operand reads are conflict free), phi(q),
+    // then per value tile lin^T[c][q] = sum_f H^T[c][f] phi(q)[f] and the output
+    //   y = (out + exp(-m) lin) / (sum p + exp(-m) phi(q)^T s);  the lane holds columns c = 16 mt + 4 g4 + 0..3 of query qi
+    __syncthreads();   // the last key block has been consumed
 #pragma unroll
-        for (int mt = 0; mt < NCT; mt++) {
+    for (int p4 = 0; p4 < DH / 32; p4++) {
+        uint4 hv[4];
+#pragma unroll
+        for (int it = 0; it < 4; it++) hv[it] = reinterpret_cast<const uint4 *>(Hsnap)[tid + 256 * (4 * p4 + it)];
+#pragma unroll
+        for (int it = 0; it < 4; it++) {
+            // snapshot order: [part][row tile of 16][k-step][lane = 16 (piece % 4) + row % 16]
+            const int o = tid + 256 * (4 * p4 + it), part = o / (DH * 16), op = o % (DH * 16);
+            const int c = 16 * (op >> 8) + (o & 15), ch = 4 * ((o >> 6) & 3) + ((o >> 4) & 3);
+            *reinterpret_cast<uint4 *>(&L[part * DH * D + c * D + ((ch ^ (c & 15)) << 3)]) = hv[it];
+        }
+    }
+    // phi(q): z^T = W_q Q^T (A = W_q rows from global, B = queries)
+    float pp[16], pn[16];
+    {
+        f32x4 zt[4];
+#pragma unroll
+        for (int mt = 0; mt < 4; mt++) {
+            zt[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ks++)
+                zt[mt] = mfma16(ld_bf16x8(Wq + (size_t)(16 * mt + r16) * DH + 32 * ks + 8 * g4), BQ[ks], zt[mt]);
+        }
+        phi_from_z(zt, a.dm.phi_kind, pp, pn);
+    }
+    float lden = 0.f;   // phi(q)^T s
+#pragma unroll
+    for (int mt = 0; mt < 4; mt++) {
+        const float4 sp4 = *reinterpret_cast<const float4 *>(&s_l[16 * mt + 4 * g4]);
+        const float4 sn4 = *reinterpret_cast<const float4 *>(&s_l[M + 16 * mt + 4 * g4]);
+        lden = fmaf(pp[4 * mt], sp4.x, lden); lden = fmaf(pp[4 * mt + 1], sp4.y, lden);
+        lden = fmaf(pp[4 * mt + 2], sp4.z, lden); lden = fmaf(pp[4 * mt + 3], sp4.w, lden);
+        lden = fmaf(pn[4 * mt], sn4.x, lden); lden = fmaf(pn[4 * mt + 1], sn4.y, lden);
+        lden = fmaf(pn[4 * mt + 2], sn4.z, lden); lden = fmaf(pn[4 * mt + 3], sn4.w, lden);
+    }
+    lden = grp_sum(lden);
+    bf16x8 Bh[4], Bl[4];
+    split8(&pp[0], Bh[0], Bl[0]); split8(&pp[8], Bh[1], Bl[1]);
+    split8(&pn[0], Bh[2], Bl[2]); split8(&pn[8], Bh[3], Bl[3]);
+    const float el = fexp2(-mrun);
+    const float inv = 1.0f / fmaf(el, lden, lsum);
+    __syncthreads();   // H^T is in LDS
+#pragma unroll
+    for (int mt = 0; mt < NCT; mt++) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acc2 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < 4; ks++) {
+            const int addr = (16 * mt + r16) * D + (((4 * ks + g4) ^ r16) << 3);
+            const bf16x8 Ahi = as_bf16x8(*reinterpret_cast<const uint4 *>(&L[addr]));
+            const bf16x8 Alo = as_bf16x8(*reinterpret_cast<const uint4 *>(&L[DH * D + addr]));
+            acc = mfma16(Ahi, Bh[ks], acc);
+            acc2 = mfma16(Ahi, Bl[ks], acc2);
+            acc2 = mfma16(Alo, Bh[ks], acc2);
+        }
+        const f32x4 lin = acc + acc2;
+        if (qi < cl) {
             TO *dst = oh + (size_t)qi * DH + 16 * mt + 4 * g4;
 #pragma unroll
-            for (int i = 0; i < 4; i++) stf(dst, i, fmaf(el, lin[mt][i], out[mt][i]) * inv);
+            for (int i = 0; i < 4; i++) stf(dst, i, fmaf(el, lin[i], out[mt][i]) * inv);
         }
     }
 }
