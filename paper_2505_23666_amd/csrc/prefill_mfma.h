@@ -76,34 +76,44 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
     const int64_t tq = aj + qi;     // token index of this lane's query
 #pragma unroll 1
     for (int blk = 0; blk < NB; blk++) {
-        // position -> source row (or none).  Thread handles 8 (key, 16-byte chunk) pairs of the block
+        // position -> source row (or none).  A thread handles PR / 4 items of the block, each one 16-byte piece of two
+        // neighbouring keys: the transposed values are then written as 32-bit words (two keys of one column)
         // (named scalars: an array held across the barrier would be sent through scratch memory).
-#define LOLA_REP8(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7)   // items beyond 128 * PR / 256 compile to nothing
-#define LOLA_KVLOAD(it) uint4 kreg##it = make_uint4(0, 0, 0, 0), vreg##it = make_uint4(0, 0, 0, 0); if (it < PR / 2) { \
-            const int o = tid + 256 * it, kk = o / PR, ch = o % PR, pos = 128 * blk + kk; \
-            int vr = -1; \
+#define LOLA_REP8(X) X(0) X(1) X(2) X(3)   // items beyond 64 * PR / 256 compile to nothing
+#define LOLA_KVROW(pos, vr) { vr = -1; \
             if (pos < LAM) vr = G_l[pos]; \
-            else if (pos < NKEYS) { vr = vrow_c - ETA + (pos - LAM); if (aj - ETA + (pos - LAM) < 0 || (pos - LAM - ETA) >= cl) vr = -1; } \
-            if (vr >= 0) { \
-                const bf16_t *kr = vr < P ? pK + (size_t)vr * DH : kc + (size_t)(vr - P) * DH; \
-                const bf16_t *vrp = vr < P ? pV + (size_t)vr * DH : vc + (size_t)(vr - P) * DH; \
-                kreg##it = reinterpret_cast<const uint4 *>(kr)[ch]; \
-                vreg##it = reinterpret_cast<const uint4 *>(vrp)[ch]; \
+            else if (pos < NKEYS) { vr = vrow_c - ETA + (pos - LAM); if (aj - ETA + (pos - LAM) < 0 || (pos - LAM - ETA) >= cl) vr = -1; } }
+#define LOLA_KVLOAD(it) uint4 kreg##it = make_uint4(0, 0, 0, 0), vreg##it = make_uint4(0, 0, 0, 0), \
+                              kreh##it = make_uint4(0, 0, 0, 0), vreh##it = make_uint4(0, 0, 0, 0); if (it < PR / 4) { \
+            const int o = tid + 256 * it, kk = 2 * (o / PR), ch = o % PR; \
+            int vr0, vr1; \
+            LOLA_KVROW((128 * blk + kk), vr0) LOLA_KVROW((128 * blk + kk + 1), vr1) \
+            if (vr0 >= 0) { \
+                kreg##it = reinterpret_cast<const uint4 *>(vr0 < P ? pK + (size_t)vr0 * DH : kc + (size_t)(vr0 - P) * DH)[ch]; \
+                vreg##it = reinterpret_cast<const uint4 *>(vr0 < P ? pV + (size_t)vr0 * DH : vc + (size_t)(vr0 - P) * DH)[ch]; \
+            } \
+            if (vr1 >= 0) { \
+                kreh##it = reinterpret_cast<const uint4 *>(vr1 < P ? pK + (size_t)vr1 * DH : kc + (size_t)(vr1 - P) * DH)[ch]; \
+                vreh##it = reinterpret_cast<const uint4 *>(vr1 < P ? pV + (size_t)vr1 * DH : vc + (size_t)(vr1 - P) * DH)[ch]; \
             } }
-#define LOLA_KVSTORE(it) if (it < PR / 2) { \
-            const int o = tid + 256 * it, kk = o / PR, ch = o % PR; \
+#define LOLA_KVSTORE(it) if (it < PR / 4) { \
+            const int o = tid + 256 * it, kk = 2 * (o / PR), ch = o % PR; \
             *reinterpret_cast<uint4 *>(&Kl[kk * DH + ((ch ^ (kk & (PR - 1))) << 3)]) = kreg##it; \
+            *reinterpret_cast<uint4 *>(&Kl[(kk + 1) * DH + ((ch ^ ((kk + 1) & (PR - 1))) << 3)]) = kreh##it; \
             const uint32_t u[4] = {vreg##it.x, vreg##it.y, vreg##it.z, vreg##it.w}; \
+            const uint32_t uh[4] = {vreh##it.x, vreh##it.y, vreh##it.z, vreh##it.w}; \
             const int kchunk = perm_chunk(kk), kel = perm_elem(kk); \
             _Pragma("unroll") for (int x = 0; x < 8; x++) { \
                 const int c = 8 * ch + x; \
-                Vt[c * 128 + ((kchunk ^ ((c ^ (c >> 3)) & 15)) << 3) + kel] = (uint16_t)((x & 1) ? (u[x >> 1] >> 16) : (u[x >> 1] & 0xFFFFu)); \
+                const uint32_t wv = (x & 1) ? ((u[x >> 1] >> 16) | (uh[x >> 1] & 0xFFFF0000u)) : ((u[x >> 1] & 0xFFFFu) | (uh[x >> 1] << 16)); \
+                *reinterpret_cast<uint32_t *>(&Vt[c * 128 + ((kchunk ^ ((c ^ (c >> 3)) & 15)) << 3) + kel]) = wv; \
             } }
         LOLA_REP8(LOLA_KVLOAD)
         __syncthreads();   // previous users of L (H^T, or the previous block) are done
         LOLA_REP8(LOLA_KVSTORE)
 #undef LOLA_KVLOAD
 #undef LOLA_KVSTORE
+#undef LOLA_KVROW
 #undef LOLA_REP8
         __syncthreads();
         // S^T = K Q^T for the 8 key tiles of the block; lane (column = query r16, group g4) holds keys 16 mt + 4 g4 + i
