@@ -68,6 +68,10 @@ def main():
     ap.add_argument("--layers", type=int, default=32, help="independent layer-state copies cycled by the decode loop")
     ap.add_argument("--prefill-tokens", type=int, default=32768, help="tokens prefilled per sequence before decoding")
     ap.add_argument("--prefill-reps", type=int, default=5)
+    ap.add_argument("--fold-defer", type=int, default=8, choices=(0, 8),
+                    help="deferred folds of the generation step (include/lola.h, lola_config.fold_defer); the other mode is "
+                         "timed as a side leg")
+    ap.add_argument("--skip-alt", action="store_true", help="skip the side leg that times the other fold mode")
     ap.add_argument("--skip-prefill", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
@@ -96,8 +100,8 @@ def main():
 
     # ---- state initialisation: update-only prefill of every sequence, 8 sequences at a time ----
     t0 = time.time()
-    layers = [lb.LolaLayer(sh.B, sh.Hq, sh.Hkv, sh.d, sh.D, sh.eta, sh.lam, sh.C, dtype="bf16", out_dtype="f32", device=dev)
-              for _ in range(L)]
+    layers = [lb.LolaLayer(sh.B, sh.Hq, sh.Hkv, sh.d, sh.D, sh.eta, sh.lam, sh.C, dtype="bf16", out_dtype="f32", device=dev,
+                           fold_defer=args.fold_defer) for _ in range(L)]
     n_tok = (K + W + L - 1) // L
     qd = np.empty((n_tok, sh.B, sh.Hq, sh.d), np.float32)
     kd = np.empty((n_tok, sh.B, sh.Hkv, sh.d), np.float32)
@@ -144,21 +148,23 @@ def main():
         l, t = i % L, i // L
         calls.append((C.byref(layers[l].cfg), C.byref(layers[l].st), vp_(dq[t]), vp_(dk[t]), vp_(dv[t]), vp_(dWq), vp_(dWk),
                       vp_(outs[l]), stream))
-    for i in range(W):
-        rc = fn(*calls[i])
-        assert rc == 0, rc
-    torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t_wall = time.perf_counter()
-    ev0.record()
-    for i in range(W, W + K):
-        rc = fn(*calls[i])
-        if rc != 0:
-            raise RuntimeError(f"lola_decode_step failed: {rc}")
-    ev1.record()
-    torch.cuda.synchronize()
-    t_wall = time.perf_counter() - t_wall
-    gpu_ms = ev0.elapsed_time(ev1)
+    def timed(cs, n_warm, n_timed):
+        for i in range(n_warm):
+            rc = fn(*cs[i])
+            assert rc == 0, rc
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        tw = time.perf_counter()
+        ev0.record()
+        for i in range(n_warm, n_warm + n_timed):
+            rc = fn(*cs[i])
+            if rc != 0:
+                raise RuntimeError(f"lola_decode_step failed: {rc}")
+        ev1.record()
+        torch.cuda.synchronize()
+        return time.perf_counter() - tw, ev0.elapsed_time(ev1)
+
+    t_wall, gpu_ms = timed(calls, W, K)
     ms_per_step = t_wall * 1e3 / K
     value = sh.B * K / t_wall
     per_stream, per_launch = decode_alg_bytes(sh, 4)
@@ -166,6 +172,25 @@ def main():
     achieved = per_launch / (launch_us * 1e-6) / 1e9
     log(f"[decode] {K} steps: wall {t_wall * 1e3:.1f} ms, gpu {gpu_ms:.1f} ms, {launch_us:.2f} us/launch, "
         f"{value / 1e6:.3f} M tokens/s/layer, {achieved:.0f} GB/s algorithmic")
+    # ---- side leg: the same steps in the other fold mode, on copies of the states as they stand now ----
+    decode_alt = None
+    if not args.skip_alt:
+        alt_R = 0 if args.fold_defer else 8
+        Ka = min(K, 256)
+        alt = [lb.LolaLayer(sh.B, sh.Hq, sh.Hkv, sh.d, sh.D, sh.eta, sh.lam, sh.C, dtype="bf16", out_dtype="f32", device=dev,
+                            fold_defer=alt_R) for _ in range(L)]
+        for l in range(L):
+            layers[l].flush()
+            for name in fields:
+                getattr(alt[l], name).copy_(getattr(layers[l], name))
+        acalls = [(C.byref(alt[i % L].cfg), C.byref(alt[i % L].st), vp_(dq[(i // L) % n_tok]), vp_(dk[(i // L) % n_tok]),
+                   vp_(dv[(i // L) % n_tok]), vp_(dWq), vp_(dWk), vp_(outs[i % L]), stream) for i in range(Ka + W)]
+        _, a_ms = timed(acalls, W, Ka)
+        decode_alt = {"fold_defer": alt_R, "steps": Ka, "launch_us": round(a_ms * 1e3 / Ka, 3),
+                      "tokens_per_s_per_layer": round(sh.B * Ka / (a_ms * 1e-3), 1)}
+        log(f"[decode, fold_defer={alt_R}] {Ka} steps: {decode_alt['launch_us']:.2f} us/launch, "
+            f"{decode_alt['tokens_per_s_per_layer'] / 1e6:.3f} M tokens/s/layer")
+        del alt, acalls
     if args.calib_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
@@ -263,8 +288,9 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "configs[3]: 8B-shape decode, batch 64, 32 q / 8 kv heads, head_dim 128, feat_dim 128, "
                                f"eta 64, lambda 128, bf16 K/V + fp32 H/s, states prefilled with {sh.T} tokens, "
-                               f"{L} layer-state copies cycled", "global_batch": sh.B, "prefill_tokens": sh.T, "layer_copies": L},
-        "roofline": roofline, "cpu_baseline": cpu, "prefill": prefill, "prefill_1b": prefill_1b,
+                               f"{L} layer-state copies cycled, fold_defer {args.fold_defer}",
+                   "global_batch": sh.B, "prefill_tokens": sh.T, "layer_copies": L, "fold_defer": args.fold_defer},
+        "roofline": roofline, "cpu_baseline": cpu, "decode_other_fold_mode": decode_alt, "prefill": prefill, "prefill_1b": prefill_1b,
     }
     print(json.dumps(line), flush=True)
 

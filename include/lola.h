@@ -55,6 +55,10 @@ typedef struct {
     int32_t out_dtype;     /* LOLA_F32 | LOLA_BF16: storage type of `out` */
     int32_t phi_kind;      /* LOLA_PHI_SOFTMAX | LOLA_PHI_EXP */
     float softmax_scale;   /* logit scale; <= 0 selects 1/sqrt(head_dim) (Sec. 2.1) */
+    int32_t fold_defer;    /* 0: every fold is applied to H and s in memory at once.
+                              R = 8: deferred folds (see lola_state.pend_*); accepted only where the fused
+                              generation-step kernel exists (bf16, head_dim 128, feat_dim 128, window 64,
+                              sparse_budget 64 or 128, 4 query heads per kv head), else LOLA_ERR_UNSUPPORTED */
 } lola_config;
 
 /* The memories of a layer.  H and s are always fp32 (Sec. 2.2, eq. recurrent_update). */
@@ -70,11 +74,24 @@ typedef struct {
     int32_t *sp_idx;   /* [B, Hkv, lambda]    token index held by each slot, -1 = empty */
     int32_t *sp_count; /* [B, Hkv] */
     int64_t *n_tokens; /* [B, Hkv]            tokens consumed so far (equal across kv heads of a sequence) */
+    /* Deferred folds (fold_defer = R > 0; NULL otherwise).  The sums of eq. recurrent_update are
+     * associative, so a generation step may keep its folded pair in a short list instead of
+     * rewriting H: the true state is
+     *     H_true = H + sum_{p < pend_count} pend_v[p] pend_phi[p]^T   (in the H^T layout above),
+     *     s_true = s + sum_{p < pend_count} pend_phi[p],
+     * and every entry point computes with H_true, s_true.  The generation step that finds R - 1
+     * pairs listed writes H_true, s_true (including its own fold) back and empties the list;
+     * lola_prefill and lola_state_flush do so on entry.  Read H or s directly only after
+     * lola_state_flush. */
+    float *pend_phi;     /* [B, Hkv, R, D]  phi(k) of the listed pairs, fp32 */
+    float *pend_v;       /* [B, Hkv, R, d]  their values, fp32 */
+    int32_t *pend_count; /* [B, Hkv]        pairs listed, 0 .. R-1 */
 } lola_state;
 
-/* Bytes of each state field in the order of the struct (host output, 9 entries); returns their
- * sum, or 0 if the configuration is invalid. */
-size_t lola_state_bytes(const lola_config *cfg, size_t field_bytes[9]);
+/* Bytes of each state field in the order of the struct (host output, 12 entries; the last three
+ * are 0 without deferred folds); returns their sum, or 0 if the configuration is invalid or
+ * unsupported. */
+size_t lola_state_bytes(const lola_config *cfg, size_t field_bytes[12]);
 
 /* Workspace of lola_prefill for T tokens: returns the size with which all chunks are processed in
  * one pass; *min_bytes (host, may be NULL) receives the smallest size accepted (the chunks are then
@@ -85,6 +102,10 @@ size_t lola_prefill_workspace_bytes(const lola_config *cfg, int32_t T, int32_t w
 /* Empty memories: H = 0, s = 0, window and sparse cache empty (appendix "Algorithm Pseudo-Code",
  * init).  Cached K, V rows are zeroed too so that a state is a deterministic function of its inputs. */
 lola_status lola_state_init(const lola_config *cfg, const lola_state *st, void *stream);
+
+/* Applies the listed pairs of every stream to H and s in memory and empties the lists (a no-op
+ * without deferred folds): afterwards H = H_true, s = s_true (Sec. 2.2, eq. recurrent_update). */
+lola_status lola_state_flush(const lola_config *cfg, const lola_state *st, void *stream);
 
 /*
  * Chunkwise prefill of T >= 0 tokens per sequence (Sec. 3 "Chunkwise Inference"; appendix
@@ -122,6 +143,8 @@ lola_status lola_prefill(const lola_config *cfg, const lola_state *st,
  * state); (3) the outputs of all query heads are computed with the updated memories, the window
  * including the new token.
  * q [B, Hq, d], k, v [B, Hkv, d], out [B, Hq, d] (out_dtype).
+ * With deferred folds the step's outputs, cache and window are the same; only where the folded
+ * pair is kept differs (see lola_state).
  */
 lola_status lola_decode_step(const lola_config *cfg, const lola_state *st,
                              const void *q, const void *k, const void *v,

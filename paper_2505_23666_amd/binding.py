@@ -16,19 +16,20 @@ LIB_PATH = os.path.join(_HERE, "liblola.so")
 
 LOLA_F32, LOLA_BF16 = 0, 1
 LOLA_PHI_SOFTMAX, LOLA_PHI_EXP = 0, 1
-EXPORTS = ("lola_state_bytes", "lola_prefill_workspace_bytes", "lola_state_init", "lola_prefill",
+EXPORTS = ("lola_state_bytes", "lola_prefill_workspace_bytes", "lola_state_init", "lola_state_flush", "lola_prefill",
            "lola_decode_step", "lola_status_str", "lola_kernel_path")
 
 
 class LolaConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "batch", "n_q_heads", "n_kv_heads", "head_dim", "feat_dim", "window", "sparse_budget", "chunk",
-        "dtype", "out_dtype", "phi_kind")] + [("softmax_scale", C.c_float)]
+        "dtype", "out_dtype", "phi_kind")] + [("softmax_scale", C.c_float), ("fold_defer", C.c_int32)]
 
 
 class LolaState(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in (
-        "H", "s", "win_k", "win_v", "sp_k", "sp_v", "sp_idx", "sp_count", "n_tokens")]
+        "H", "s", "win_k", "win_v", "sp_k", "sp_v", "sp_idx", "sp_count", "n_tokens",
+        "pend_phi", "pend_v", "pend_count")]
 
 
 class LolaError(RuntimeError):
@@ -53,6 +54,8 @@ def lib() -> C.CDLL:
         L.lola_prefill_workspace_bytes.argtypes = [cfgp, i32, i32, C.POINTER(sz)]
         L.lola_state_init.restype = C.c_int
         L.lola_state_init.argtypes = [cfgp, stp, vp]
+        L.lola_state_flush.restype = C.c_int
+        L.lola_state_flush.argtypes = [cfgp, stp, vp]
         L.lola_prefill.restype = C.c_int
         L.lola_prefill.argtypes = [cfgp, stp, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
         L.lola_decode_step.restype = C.c_int
@@ -79,7 +82,7 @@ def _stream():
 
 
 def lola_state_bytes(cfg: LolaConfig):
-    fb = (C.c_size_t * 9)()
+    fb = (C.c_size_t * 12)()
     tot = lib().lola_state_bytes(C.byref(cfg), fb)
     return int(tot), [int(x) for x in fb]
 
@@ -92,6 +95,10 @@ def lola_prefill_workspace_bytes(cfg: LolaConfig, T: int, with_outputs: bool = T
 
 def lola_state_init(cfg: LolaConfig, st: LolaState) -> None:
     _check(lib().lola_state_init(C.byref(cfg), C.byref(st), _stream()), "lola_state_init")
+
+
+def lola_state_flush(cfg: LolaConfig, st: LolaState) -> None:
+    _check(lib().lola_state_flush(C.byref(cfg), C.byref(st), _stream()), "lola_state_flush")
 
 
 def lola_prefill(cfg, st, q, k, v, Wq, Wk, T, out, sel_trace, workspace) -> None:
@@ -116,11 +123,12 @@ class LolaLayer:
     """Device buffers of one layer's memories plus the three calls, for tests and benchmarks."""
 
     def __init__(self, B, Hq, Hkv, d, D, eta, lam, C_, dtype="bf16", out_dtype="f32",
-                 phi_kind=LOLA_PHI_SOFTMAX, scale=0.0, device="cuda:0"):
+                 phi_kind=LOLA_PHI_SOFTMAX, scale=0.0, fold_defer=0, device="cuda:0"):
         self.device = torch.device(device)
         self.dt = LOLA_BF16 if dtype == "bf16" else LOLA_F32
         self.odt = LOLA_BF16 if out_dtype == "bf16" else LOLA_F32
-        self.cfg = LolaConfig(B, Hq, Hkv, d, D, eta, lam, C_, self.dt, self.odt, phi_kind, float(scale))
+        self.cfg = LolaConfig(B, Hq, Hkv, d, D, eta, lam, C_, self.dt, self.odt, phi_kind, float(scale), int(fold_defer))
+        self.fold_defer = R = int(fold_defer)
         self.B, self.Hq, self.Hkv, self.d, self.D, self.eta, self.lam, self.C = B, Hq, Hkv, d, D, eta, lam, C_
         tot, fb = lola_state_bytes(self.cfg)
         if tot == 0:
@@ -135,7 +143,11 @@ class LolaLayer:
         self.sp_idx = torch.empty((B, Hkv, lam), dtype=torch.int32, device=dev)
         self.sp_count = torch.empty((B, Hkv), dtype=torch.int32, device=dev)
         self.n_tokens = torch.empty((B, Hkv), dtype=torch.int64, device=dev)
-        fields = [self.H, self.s, self.win_k, self.win_v, self.sp_k, self.sp_v, self.sp_idx, self.sp_count, self.n_tokens]
+        self.pend_phi = torch.empty((B, Hkv, R, D), dtype=torch.float32, device=dev)
+        self.pend_v = torch.empty((B, Hkv, R, d), dtype=torch.float32, device=dev)
+        self.pend_count = torch.empty((B, Hkv) if R else (0,), dtype=torch.int32, device=dev)
+        fields = [self.H, self.s, self.win_k, self.win_v, self.sp_k, self.sp_v, self.sp_idx, self.sp_count, self.n_tokens,
+                  self.pend_phi, self.pend_v, self.pend_count]
         assert [t.numel() * t.element_size() for t in fields] == fb
         self.st = LolaState(*[t.data_ptr() if t.numel() else None for t in fields])
         self.workspace = None
@@ -150,6 +162,11 @@ class LolaLayer:
     def reset(self):
         with torch.cuda.device(self.device):
             lola_state_init(self.cfg, self.st)
+
+    def flush(self):
+        """Apply the listed (deferred) folds to H and s in memory."""
+        with torch.cuda.device(self.device):
+            lola_state_flush(self.cfg, self.st)
 
     def _ws(self, T, with_out, limit_bytes=None):
         full, mn = lola_prefill_workspace_bytes(self.cfg, T, with_out)

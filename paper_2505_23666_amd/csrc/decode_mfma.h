@@ -134,6 +134,9 @@ struct DecodeFastArgs {
     int Hq, Hkv;
     float scale;
     int phi_kind;
+    // deferred folds (R > 0): up to R - 1 folded pairs per stream wait here, [stream][R][D] / [stream][R][DH] fp32
+    float *pend_phi, *pend_v;
+    int32_t *pend_count;
 };
 
 // phi of 16 vectors from their projections held in the C layout of the projection GEMM: lane (column r16,
@@ -174,8 +177,16 @@ __device__ __forceinline__ void phi_from_z(const f32x4 zt[4], int phi_kind, floa
 //   PX    4 KB  the same for the "extra tile": row 0 the leaving key, rows 1..G the queries.
 //   the rest    small per-stream vectors.
 // H^T never goes through LDS: wavefront w owns its rows 32w .. 32w+31 (output columns of the recall GEMM).
-template <int LAM, int ETA, int G, typename TO>
+//
+// Deferred folds (R = 4): the state in memory lags behind by up to R - 1 folded pairs, which are kept as fp32 rows
+// (phi, v) beside it.  A step adds them to its register copy of H^T with fp32 MFMAs (16x16x4: the contraction index
+// is the pending pair) and to s, so everything downstream sees the true state; its own fold is appended to the
+// list, and only the step that would make the list full writes H and s back.  Same sums as folding at once
+// (Sec. 2.2, eq. recurrent_update), three of four write-backs of H saved.
+template <int LAM, int ETA, int G, int R, typename TO>
 __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> a) {
+    static_assert(R == 0 || R == 4 || R == 8, "pending pairs are the contraction index of 16x16x4 MFMAs");
+    constexpr int RG = R > 0 ? R / 4 : 1;
     constexpr int DH = 128, M = 64, D = 128;
     constexpr int NKT = LAM / 16;          // key tiles of the sparse cache
     constexpr int TPW = NKT / 4;           // key tiles whose phi a wavefront computes
@@ -242,6 +253,15 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     // per-stream vectors that the first barrier waits for, then the operands of the projections, then the window keys
     const uint4 q_ld = (tid >= 64 && tid < 64 + G * 16) ? reinterpret_cast<const uint4 *>(qg)[tid - 64] : make_uint4(0, 0, 0, 0);
     const float4 s_ld = tid < D / 4 ? reinterpret_cast<const float4 *>(sg)[tid] : make_float4(0.f, 0.f, 0.f, 0.f);
+    float *pphi = nullptr, *pval = nullptr;
+    int cnt = 0;
+    float4 sp_ld[R > 0 ? R : 1];
+    if (R > 0) {
+        pphi = a.pend_phi + (size_t)si * R * D; pval = a.pend_v + (size_t)si * R * DH;
+        cnt = a.pend_count[si];
+#pragma unroll
+        for (int p = 0; p < R; p++) sp_ld[p] = tid < D / 4 ? reinterpret_cast<const float4 *>(pphi + p * D)[tid] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
     const int idx_ld = tid < LAM ? sp_idx[tid] : 0;
     // W_k crosses the cache hierarchy once per workgroup: each wavefront fetches a quarter (16 projections, 4 KB,
     // whole lines) and the MFMA A operands are read back from LDS, where the feature tile is not in use yet
@@ -276,7 +296,15 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
         for (int ks = 0; ks < 4; ks++) BWin[ks] = ld_bf16x8(src + 32 * ks + 8 * g4);
     }
     LOLA_STAMP(9);
-    if (tid < D / 4) reinterpret_cast<float4 *>(s_l)[tid] = s_ld;
+    if (tid < D / 4) {
+        float4 sv = s_ld;
+        if (R > 0) {
+#pragma unroll
+            for (int p = 0; p < R; p++)
+                if (p < cnt) { sv.x += sp_ld[p].x; sv.y += sp_ld[p].y; sv.z += sp_ld[p].z; sv.w += sp_ld[p].w; }
+        }
+        reinterpret_cast<float4 *>(s_l)[tid] = sv;
+    }
     if (tid < LAM) idx_l[tid] = idx_ld;
     if (popped && tid < 32) {
         reinterpret_cast<uint4 *>(tid < 16 ? pkb : pvb)[tid & 15] = p_ld;
@@ -512,7 +540,33 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     if (steady) {
         // ---- stage 2: recall of all eligible pairs: P^T = H^T Phi^T; A = this wavefront's rows of H^T (bf16 high +
         // low parts made here), B = feature vectors from LDS
+        // operands of the pending pairs: A = phi_p (row = feature within a 16-block, k = p), B = v_p (column = value
+        // index); requested only now, after the feature map, whose registers they would otherwise compete for
+        float pa[RG][8], pb[RG][2];
+        if (R > 0) {
+            __builtin_amdgcn_sched_barrier(0);
+            int lp = lane;
+            asm volatile("" : "+v"(lp));
+            const int pr = lp & 15, pg = lp >> 4;
+#pragma unroll
+            for (int gr = 0; gr < RG; gr++) {
+                const int pp_ = 4 * gr + pg;
+                const bool live = pp_ < cnt;
+#pragma unroll
+                for (int x = 0; x < 8; x++) pa[gr][x] = live ? pphi[pp_ * D + 16 * x + pr] : 0.f;
+#pragma unroll
+                for (int ct = 0; ct < 2; ct++) pb[gr][ct] = live ? pval[pp_ * DH + 32 * w + 16 * ct + pr] : 0.f;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
         bf16x8 Ahi[2][4], Alo[2][4];
+        if (R > 0) {
+#define LOLA_HPEND(ct, ks, hf) { f32x4 c_ = {hreg##ct##ks##hf.x, hreg##ct##ks##hf.y, hreg##ct##ks##hf.z, hreg##ct##ks##hf.w}; \
+            _Pragma("unroll") for (int gr = 0; gr < RG; gr++) c_ = __builtin_amdgcn_mfma_f32_16x16x4f32(pa[gr][2 * ks + hf], pb[gr][ct], c_, 0, 0, 0); \
+            hreg##ct##ks##hf = make_float4(c_[0], c_[1], c_[2], c_[3]); }
+            LOLA_HREP(LOLA_HPEND)
+#undef LOLA_HPEND
+        }
 #define LOLA_HSPLIT(ct, ks, hf) { const float4 v = hreg##ct##ks##hf; \
             const __bf16 h0 = (__bf16)v.x, h1 = (__bf16)v.y, h2 = (__bf16)v.z, h3 = (__bf16)v.w; \
             Ahi[ct][ks][4 * hf] = h0; Ahi[ct][ks][4 * hf + 1] = h1; Ahi[ct][ks][4 * hf + 2] = h2; Ahi[ct][ks][4 * hf + 3] = h3; \
@@ -621,7 +675,11 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
             else if (tid < 32) reinterpret_cast<uint4 *>(sp_v + (size_t)drop * DH)[tid - 16] = reinterpret_cast<const uint4 *>(pvb)[tid - 16];
             else if (tid == 32) sp_idx[drop] = pidx;
         }
-        // fold: H^T += v_f phi_f^T on the fp32 registers, written back once; s += phi_f
+        // fold: H^T += v_f phi_f^T on the fp32 registers, written back once; s += phi_f.  With deferred folds only
+        // the step that finds the list one short of full does so (its registers include the listed pairs); the others
+        // append their pair to the list.
+        const bool write_back = R == 0 || cnt == R - 1;
+        if (write_back) {
 #define LOLA_HFOLD(ct, ks, hf) { const float vc = vf[32 * w + 16 * ct + r16]; \
             const float4 pf = *reinterpret_cast<const float4 *>(&phif[32 * ks + 16 * hf + 4 * g4]); \
             hreg##ct##ks##hf.x = fmaf(pf.x, vc, hreg##ct##ks##hf.x); hreg##ct##ks##hf.y = fmaf(pf.y, vc, hreg##ct##ks##hf.y); \
@@ -630,6 +688,12 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
         LOLA_HREP(LOLA_HFOLD)
 #undef LOLA_HFOLD
         if (tid < D) sg[tid] = s_l[tid] + phif[tid];
+        if (R > 0 && tid == 0) a.pend_count[si] = 0;
+        } else {
+            if (tid < D) pphi[cnt * D + tid] = phif[tid];
+            else if (tid < D + DH) pval[cnt * DH + tid - D] = vf[tid - D];
+            if (tid == 0) a.pend_count[si] = cnt + 1;
+        }
         // phi(q) . phi_f for the rank-1 correction of the linear read-out
         for (int r = w; r < G; r += 4) {
             float acc = 0.f;
@@ -666,6 +730,10 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
         uint32_t *dst = reinterpret_cast<uint32_t *>(Vl + key * VLS + 8 * c8);
         dst[0] = vst[it].x; dst[1] = vst[it].y; dst[2] = vst[it].z; dst[3] = vst[it].w;
     }
+    // the new pair, which takes the ring slot of the pair that left, is requested here and stored at the very end
+    // (a store that follows its own load waits for every load the wavefront has in flight: by then there is none)
+    uint4 new_ld = make_uint4(0, 0, 0, 0);
+    if (tid < 32) new_ld = reinterpret_cast<const uint4 *>(tid < 16 ? knew : vnew)[tid & 15];
     // softmax weights (one query per wavefront), m = max(0, max logit); written as bf16 high + low parts
     for (int r = w; r < G; r += 4) {
         float l[(KPAD + 63) / 64];
@@ -737,10 +805,8 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
             }
         }
     }
-    // the new pair takes the ring slot of the pair that left (read in stage 0).  Done last: a load-then-store waits
-    // for every load the wavefront has in flight.
-    if (tid < 16) reinterpret_cast<uint4 *>(win_k + (size_t)slot * DH)[tid] = reinterpret_cast<const uint4 *>(knew)[tid];
-    else if (tid < 32) reinterpret_cast<uint4 *>(win_v + (size_t)slot * DH)[tid - 16] = reinterpret_cast<const uint4 *>(vnew)[tid - 16];
+    // the new pair takes the ring slot of the pair that left (read in stage 0)
+    if (tid < 32) reinterpret_cast<uint4 *>(tid < 16 ? win_k + (size_t)slot * DH : win_v + (size_t)slot * DH)[tid & 15] = new_ld;
     if (tid == 0) a.st.n_tokens[si] = tok + 1;
     LOLA_STAMP(8);
 #ifdef LOLA_TIMING

@@ -29,6 +29,14 @@ inline size_t esize(int dtype) { return dtype == LOLA_BF16 ? 2 : 4; }
 
 constexpr size_t LDS_LIMIT = 64 * 1024 - 256;   // static workgroup limit minus the kernels' few static words
 
+constexpr int DEFER_R = 8;   // pairs a stream may list before the generation step writes its state back
+
+// The fused MFMA generation step covers the Llama-8B head shape with bf16 storage.
+bool fast_decode_ok(const lola_config *c) {
+    return c->dtype == LOLA_BF16 && c->head_dim == 128 && c->feat_dim == 128 && c->window == 64 &&
+           (c->sparse_budget == 128 || c->sparse_budget == 64) && c->n_q_heads / c->n_kv_heads == 4;
+}
+
 lola_status check_config(const lola_config *c) {
     if (!c) return LOLA_ERR_NULL;
     if (c->dtype != LOLA_F32 && c->dtype != LOLA_BF16) return LOLA_ERR_DTYPE;
@@ -41,6 +49,8 @@ lola_status check_config(const lola_config *c) {
     if (c->window < 0 || c->sparse_budget < 0 || c->chunk < 1) return LOLA_ERR_SHAPE;
     if (c->window > 4096 || c->sparse_budget > 4096 || c->chunk > 1024) return LOLA_ERR_SHAPE;
     if ((long long)c->batch * c->n_kv_heads > (1ll << 24)) return LOLA_ERR_SHAPE;
+    if (c->fold_defer != 0 && c->fold_defer != DEFER_R) return LOLA_ERR_SHAPE;
+    if (c->fold_defer != 0 && !fast_decode_ok(c)) return LOLA_ERR_UNSUPPORTED;
     return LOLA_OK;
 }
 
@@ -60,6 +70,41 @@ lola_status check_state(const lola_config *c, const lola_state *st) {
     if (c->sparse_budget > 0 && (!st->sp_k || !st->sp_v || !st->sp_idx)) return LOLA_ERR_NULL;
     const void *ps[] = {st->H, st->s, st->win_k, st->win_v, st->sp_k, st->sp_v, st->sp_idx, st->sp_count, st->n_tokens};
     for (const void *p : ps) if (p && misaligned(p)) return LOLA_ERR_ALIGN;
+    if (c->fold_defer) {
+        if (!st->pend_phi || !st->pend_v || !st->pend_count) return LOLA_ERR_NULL;
+        if (misaligned(st->pend_phi) || misaligned(st->pend_v) || misaligned(st->pend_count)) return LOLA_ERR_ALIGN;
+    }
+    return LOLA_OK;
+}
+
+// H += sum_p v_p phi_p^T, s += sum_p phi_p over the listed pairs of each stream; the list is emptied
+__global__ __launch_bounds__(256) void flush_pending_kernel(float *H, float *s, float *pend_phi, float *pend_v,
+                                                            int32_t *pend_count, int d, int D, int R) {
+    const int si = blockIdx.x;
+    const int cnt = pend_count[si];
+    if (cnt == 0) return;
+    const float *pphi = pend_phi + (size_t)si * R * D, *pv = pend_v + (size_t)si * R * d;
+    float *Hs = H + (size_t)si * d * D, *ss = s + (size_t)si * D;
+    for (int e = threadIdx.x; e < d * D; e += 256) {
+        const int c = e / D, f = e - c * D;
+        float acc = Hs[e];
+        for (int p = 0; p < cnt; p++) acc = fmaf(pv[p * d + c], pphi[p * D + f], acc);
+        Hs[e] = acc;
+    }
+    for (int f = threadIdx.x; f < D; f += 256) {
+        float acc = ss[f];
+        for (int p = 0; p < cnt; p++) acc += pphi[p * D + f];
+        ss[f] = acc;
+    }
+    __syncthreads();   // every thread has read the count
+    if (threadIdx.x == 0) pend_count[si] = 0;
+}
+
+lola_status flush_pending(const lola_config *c, const lola_state *st, hipStream_t stream) {
+    if (!c->fold_defer) return LOLA_OK;
+    hipLaunchKernelGGL(flush_pending_kernel, dim3(c->batch * c->n_kv_heads), dim3(256), 0, stream, st->H, st->s,
+                       st->pend_phi, st->pend_v, st->pend_count, c->head_dim, c->feat_dim, c->fold_defer);
+    if (hipGetLastError() != hipSuccess) return LOLA_ERR_HIP;
     return LOLA_OK;
 }
 
@@ -92,12 +137,6 @@ int attend_tile_queries(const Dims &dm) {
 }
 
 #define LAUNCH_CHECK() do { if (hipGetLastError() != hipSuccess) return LOLA_ERR_HIP; } while (0)
-
-// The fused MFMA generation step covers the Llama-8B head shape with bf16 storage.
-bool fast_decode_ok(const lola_config *c) {
-    return c->dtype == LOLA_BF16 && c->head_dim == 128 && c->feat_dim == 128 && c->window == 64 &&
-           (c->sparse_budget == 128 || c->sparse_budget == 64) && c->n_q_heads / c->n_kv_heads == 4;
-}
 
 // The MFMA kernels of the prefill cover the Llama 8B and 1B head shapes (head_dim 128 / 64, 128 features) with
 // chunk = window = 64.
@@ -143,7 +182,11 @@ lola_status launch_fast_decode(const lola_config *c, const lola_state *st, const
     a.Hq = c->n_q_heads; a.Hkv = c->n_kv_heads;
     a.scale = make_dims(c).scale;
     a.phi_kind = c->phi_kind;
-    hipLaunchKernelGGL((fast::decode_fast_kernel<LAM, 64, 4, TO>), dim3(c->batch * c->n_kv_heads), dim3(256), 0, stream, a);
+    a.pend_phi = st->pend_phi; a.pend_v = st->pend_v; a.pend_count = st->pend_count;
+    if (c->fold_defer)
+        hipLaunchKernelGGL((fast::decode_fast_kernel<LAM, 64, 4, DEFER_R, TO>), dim3(c->batch * c->n_kv_heads), dim3(256), 0, stream, a);
+    else
+        hipLaunchKernelGGL((fast::decode_fast_kernel<LAM, 64, 4, 0, TO>), dim3(c->batch * c->n_kv_heads), dim3(256), 0, stream, a);
     LAUNCH_CHECK();
     return LOLA_OK;
 }
@@ -289,14 +332,15 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
 
 extern "C" {
 
-size_t lola_state_bytes(const lola_config *c, size_t fb[9]) {
+size_t lola_state_bytes(const lola_config *c, size_t fb[12]) {
     if (check_config(c) != LOLA_OK) return 0;
     const size_t ns = (size_t)c->batch * c->n_kv_heads, es = esize(c->dtype);
-    const size_t d = c->head_dim, D = c->feat_dim, eta = c->window, lam = c->sparse_budget;
-    size_t f[9] = {ns * D * d * 4, ns * D * 4, ns * eta * d * es, ns * eta * d * es, ns * lam * d * es,
-                   ns * lam * d * es, ns * lam * 4, ns * 4, ns * 8};
+    const size_t d = c->head_dim, D = c->feat_dim, eta = c->window, lam = c->sparse_budget, R = c->fold_defer;
+    size_t f[12] = {ns * D * d * 4, ns * D * 4, ns * eta * d * es, ns * eta * d * es, ns * lam * d * es,
+                    ns * lam * d * es, ns * lam * 4, ns * 4, ns * 8,
+                    ns * R * D * 4, ns * R * d * 4, R ? ns * 4 : 0};
     size_t tot = 0;
-    for (int i = 0; i < 9; i++) { if (fb) fb[i] = f[i]; tot += f[i]; }
+    for (int i = 0; i < 12; i++) { if (fb) fb[i] = f[i]; tot += f[i]; }
     return tot;
 }
 
@@ -317,10 +361,12 @@ lola_status lola_state_init(const lola_config *c, const lola_state *st, void *st
     if (rc != LOLA_OK) return rc;
     rc = check_state(c, st);
     if (rc != LOLA_OK) return rc;
-    size_t fb[9];
+    size_t fb[12];
     lola_state_bytes(c, fb);
-    void *ptrs[9] = {st->H, st->s, st->win_k, st->win_v, st->sp_k, st->sp_v, st->sp_idx, st->sp_count, st->n_tokens};
-    for (int i = 0; i < 9; i++) {
+    void *ptrs[12] = {st->H, st->s, st->win_k, st->win_v, st->sp_k, st->sp_v, st->sp_idx, st->sp_count, st->n_tokens,
+                      c->fold_defer ? st->pend_phi : nullptr, c->fold_defer ? st->pend_v : nullptr,
+                      c->fold_defer ? st->pend_count : nullptr};
+    for (int i = 0; i < 12; i++) {
         if (!ptrs[i] || fb[i] == 0) continue;
         size_t n = fb[i] / 4;   // every field is a multiple of 4 bytes (head_dim is even)
         unsigned blocks = (unsigned)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
@@ -329,6 +375,14 @@ lola_status lola_state_init(const lola_config *c, const lola_state *st, void *st
         LAUNCH_CHECK();
     }
     return LOLA_OK;
+}
+
+lola_status lola_state_flush(const lola_config *c, const lola_state *st, void *stream) {
+    lola_status rc = check_config(c);
+    if (rc != LOLA_OK) return rc;
+    rc = check_state(c, st);
+    if (rc != LOLA_OK) return rc;
+    return flush_pending(c, st, (hipStream_t)stream);
 }
 
 lola_status lola_prefill(const lola_config *c, const lola_state *st, const void *q, const void *k, const void *v,
@@ -347,6 +401,8 @@ lola_status lola_prefill(const lola_config *c, const lola_state *st, const void 
     size_t need_min = 0;
     lola_prefill_workspace_bytes(c, T, q != nullptr, &need_min);
     if (!workspace || workspace_bytes < need_min) return LOLA_ERR_WORKSPACE;
+    rc = flush_pending(c, st, (hipStream_t)stream);   // the prefill kernels read H and s as they are in memory
+    if (rc != LOLA_OK) return rc;
     if (c->dtype == LOLA_F32)
         return run_prefill<float>(c, st, q, k, v, Wq, Wk, T, out, sel_trace, workspace, workspace_bytes, (hipStream_t)stream);
     return run_prefill<bf16_t>(c, st, q, k, v, Wq, Wk, T, out, sel_trace, workspace, workspace_bytes, (hipStream_t)stream);

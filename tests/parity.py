@@ -78,6 +78,18 @@ def gpu_state_np(layer: lb.LolaLayer, bsel=None, hsel=None) -> dict:
             t = t[:, list(hsel)]
         out[n] = (t.float() if t.dtype == torch.bfloat16 else t).cpu().numpy()
     out["H"] = np.ascontiguousarray(out["H"].transpose(0, 1, 3, 2))   # the library stores H^T [d, D]
+    if getattr(layer, "fold_defer", 0):
+        # deferred folds: the state is what memory holds plus the listed pairs (include/lola.h, lola_state.pend_*)
+        sel = lambda t: (t if bsel is None else t[list(bsel)])[:, slice(None) if hsel is None else list(hsel)]
+        phi = sel(layer.pend_phi).cpu().numpy().astype(np.float64)
+        val = sel(layer.pend_v).cpu().numpy().astype(np.float64)
+        cnt = sel(layer.pend_count).cpu().numpy()
+        assert cnt.min() >= 0 and cnt.max() < layer.fold_defer
+        live = (np.arange(layer.fold_defer)[None, None, :] < cnt[..., None]).astype(np.float64)
+        phi = phi * live[..., None]
+        out["H"] = out["H"].astype(np.float64) + np.einsum("bhpf,bhpc->bhfc", phi, val)
+        out["s"] = out["s"].astype(np.float64) + phi.sum(2)
+        out["pend_count"] = cnt
     return out
 
 
@@ -147,9 +159,13 @@ def prefill_parity(sh: wl.Shape, q, k, v, Wq, Wk, layer=None, oracle=None, with_
     return layer, oracle, rep
 
 
-def decode_parity(sh: wl.Shape, layer, oracle, qd, kd, vd, Wq, Wk, out_dtype="f32", bsel=None, hsel=None, check_every=1):
+def decode_parity(sh: wl.Shape, layer, oracle, qd, kd, vd, Wq, Wk, out_dtype="f32", bsel=None, hsel=None, check_every=1,
+                  shadow=None):
     """Generation steps; qd [n,B,Hq,d], kd, vd [n,B,Hkv,d] (host float32).  Every step's outputs and
-    selection are compared on the oracle's streams."""
+    selection are compared on the oracle's streams.  `shadow`: a second layer in the same state
+    (e.g. with deferred folds) that is fed the same steps; its outputs are held to the oracle in
+    the same way, its selections must equal the first layer's on every stream, its final state is
+    checked too."""
     tol = TOL[sh.dtype] + (2.0 ** -8 if out_dtype == "bf16" else 0.0)
     n = qd.shape[0]
     bs = list(bsel) if bsel is not None else list(range(kd.shape[1]))
@@ -167,6 +183,14 @@ def decode_parity(sh: wl.Shape, layer, oracle, qd, kd, vd, Wq, Wk, out_dtype="f3
         err = row_rel_err(out[bs][:, hq].float().cpu().numpy(), y_or).max()
         worst = max(worst, float(err))
         assert err <= tol, f"decode step {i}: output rel err {err:.3e} > {tol}"
+        if shadow is not None:
+            out2 = shadow.decode_step(dq[i], dk[i], dv[i], dWq, dWk)
+            err2 = row_rel_err(out2[bs][:, hq].float().cpu().numpy(), y_or).max()
+            worst = max(worst, float(err2))
+            assert err2 <= tol, f"decode step {i} (shadow layer): output rel err {err2:.3e} > {tol}"
+            assert torch.equal(shadow.sp_idx, layer.sp_idx), f"decode step {i}: the shadow layer selected differently"
+    if shadow is not None:
+        check_state(gpu_state_np(shadow, bs, hs), oracle, TOL[sh.dtype])
     st = oracle.stats()
     assert st["mismatch"] == 0, f"sparse-cache sets differ outside the tie band: {st}"
     eH, es = check_state(gpu_state_np(layer, bs, hs), oracle, TOL[sh.dtype])

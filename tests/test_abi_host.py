@@ -39,8 +39,13 @@ def test_state_bytes(L):
     tot, fb = lb.lola_state_bytes(cfg())
     ns = 4
     assert fb == [ns * 128 * 128 * 4, ns * 128 * 4, ns * 64 * 128 * 2, ns * 64 * 128 * 2, ns * 128 * 128 * 2,
-                  ns * 128 * 128 * 2, ns * 128 * 4, ns * 4, ns * 8]
+                  ns * 128 * 128 * 2, ns * 128 * 4, ns * 4, ns * 8, 0, 0, 0]
     assert tot == sum(fb)
+    # deferred folds: a list of 8 (phi, v) rows in fp32 and its length per stream
+    tot8, fb8 = lb.lola_state_bytes(cfg(fold_defer=8))
+    assert fb8[:9] == fb[:9] and fb8[9:] == [ns * 8 * 128 * 4, ns * 8 * 128 * 4, ns * 4] and tot8 == sum(fb8)
+    assert lb.lola_state_bytes(cfg(fold_defer=3))[0] == 0                 # not a supported list length
+    assert lb.lola_state_bytes(cfg(fold_defer=8, head_dim=64))[0] == 0    # no kernel with deferred folds for this shape
     assert lb.lola_state_bytes(cfg(head_dim=100))[0] == 0
     assert lb.lola_state_bytes(cfg(feat_dim=127))[0] == 0
     assert lb.lola_state_bytes(cfg(n_q_heads=7))[0] == 0
@@ -55,7 +60,7 @@ def test_workspace_bytes_monotone(L):
     upd, mnu = lb.lola_prefill_workspace_bytes(cfg(), 4096, False)
     upd2, _ = lb.lola_prefill_workspace_bytes(cfg(), 1 << 20, False)
     assert mnu < mn and mnu <= upd == upd2 < full
-    gen = cfg(head_dim=64)      # generic kernels: nothing per chunk
+    gen = cfg(window=32)        # generic kernels: nothing per chunk
     updg, mnug = lb.lola_prefill_workspace_bytes(gen, 4096, False)
     assert updg == mnug > 0
 
@@ -70,8 +75,8 @@ def test_arguments_rejected_before_launch(L):
     """Every call below must return an error from host-side validation (no GPU is present here)."""
     c = cfg()
     fake = 0x1000  # aligned, never dereferenced on the host
-    st = lb.LolaState(*([fake] * 9))
-    bad_st = lb.LolaState(*([fake] * 8 + [None]))
+    st = lb.LolaState(*([fake] * 9 + [None] * 3))
+    bad_st = lb.LolaState(*([fake] * 8 + [None] * 4))
     f = lambda *a: L.lola_decode_step(*a)
     vp = C.c_void_p
     assert f(C.byref(c), C.byref(bad_st), vp(fake), vp(fake), vp(fake), vp(fake), vp(fake), vp(fake), None) == -1
@@ -88,3 +93,9 @@ def test_arguments_rejected_before_launch(L):
     assert p(c, st, vp(fake), vp(fake), vp(fake), 64, vp(fake), 1024) == -6          # workspace too small
     assert p(c, st, None, None, None, 0, None, 0) == 0                                # T = 0: nothing is touched
     assert L.lola_state_init(C.byref(c), C.byref(bad_st), None) == -1
+    # deferred folds: the list pointers become required; shapes without the fused generation step are refused
+    c8 = cfg(fold_defer=8)
+    assert f(C.byref(c8), C.byref(st), vp(fake), vp(fake), vp(fake), vp(fake), vp(fake), vp(fake), None) == -1
+    assert L.lola_state_flush(C.byref(c8), C.byref(st), None) == -1
+    assert L.lola_state_flush(C.byref(cfg(fold_defer=8, sparse_budget=256)), C.byref(st), None) == -5
+    assert L.lola_state_flush(C.byref(cfg(fold_defer=5)), C.byref(st), None) == -2

@@ -107,6 +107,61 @@ def test_8b_shape_decode_from_cold_start(lam, phi_kind):
     assert rep["scored"] == 4 * 60
 
 
+@pytest.mark.parametrize("lam,phi_kind", [(128, 0), (64, 1)])
+def test_deferred_folds(lam, phi_kind):
+    """fold_defer = 8 on the fused generation kernel: the folded pair of a step is listed instead of
+    being applied to H in memory; memory + list must equal the oracle's state at every list length,
+    outputs every step, through cold start, a prefill call in between (which applies the list),
+    more steps, and an explicit flush."""
+    R = 8
+    sh = wl.Shape("defer8b", "bf16", 2, 8, 2, 128, 128, T=0, eta=64, lam=lam, C=64, seed=0)
+    n_pre = 64 * 2 + 17
+    blocks = [64 + lam + 5, 3, 8, 6]           # steady steps so far: 5, 8, 16, 22
+    n = sum(blocks) + n_pre + 11
+    q, k, v, Wq, Wk = rand_case(77 + lam, 2, 8, 2, 128, 128, n, "bf16", wscale=0.5 if phi_kind else 1.0)
+    kw = dict(phi_kind=phi_kind)
+    layer = P.make_layer(sh, fold_defer=R, **kw)
+    assert layer.lola_path[1] == "mfma"
+    o = P.make_oracle(sh, **kw)
+    t0, steady = 0, 0
+    for nb in blocks:
+        rep = P.decode_parity(sh, layer, o, *steps(q, k, v, t0, nb), Wq, Wk)   # ends with a state check (memory + list)
+        t0 += nb
+        steady = t0 - 64 - lam
+        cnt = layer.pend_count.cpu().numpy()
+        say("deferred folds", lam, phi_kind, "steps", t0, "listed", cnt.ravel().tolist(), rep)
+        assert (cnt == steady % R).all()
+    assert steady % R != 0
+    # a prefill call starts by applying the list; its own folds go to H directly
+    layer, o, rep = P.prefill_parity(sh, q[:, :, t0:t0 + n_pre], k[:, :, t0:t0 + n_pre], v[:, :, t0:t0 + n_pre], Wq, Wk,
+                                     layer=layer, oracle=o, layer_kw=kw)
+    t0 += n_pre
+    assert (layer.pend_count.cpu().numpy() == 0).all()
+    say("deferred folds: prefill in between", rep)
+    rep = P.decode_parity(sh, layer, o, *steps(q, k, v, t0, 11), Wq, Wk)
+    assert (layer.pend_count.cpu().numpy() == 11 % R).all()
+    # explicit flush: memory alone is the state
+    layer.flush()
+    torch.cuda.synchronize()
+    assert (layer.pend_count.cpu().numpy() == 0).all()
+    g = P.gpu_state_np(layer)
+    P.check_state(g, o, P.TOL["bf16"])
+    layer.flush()     # idempotent
+    torch.cuda.synchronize()
+    g2 = P.gpu_state_np(layer)
+    assert np.array_equal(g["H"], g2["H"]) and np.array_equal(g["s"], g2["s"])
+    say("deferred folds: after flush", rep)
+
+
+def test_deferred_folds_refused_elsewhere():
+    """Shapes without the fused generation kernel do not take fold_defer."""
+    from paper_2505_23666_amd import binding as lb
+    with pytest.raises(lb.LolaError):
+        lb.LolaLayer(1, 4, 1, 64, 128, 64, 64, 64, fold_defer=8)
+    with pytest.raises(lb.LolaError):
+        lb.LolaLayer(1, 4, 1, 128, 128, 64, 128, 64, fold_defer=4)
+
+
 def test_exp_feature_map():
     sh = wl.Shape("expphi", "f32", 1, 2, 1, 32, 16, T=64, eta=8, lam=6, C=8, seed=0)
     q, k, v, Wq, Wk = rand_case(8, 1, 2, 1, 32, 16, 70, "f32", wscale=0.5)
@@ -355,5 +410,9 @@ def test_config4_decode_batch64_full():
     say("config4 oracle prefill", st, f"{time.time() - t:.1f}s")
     assert st["mismatch"] == 0
     P.check_state(P.gpu_state_np(layer, bsel), o, P.TOL[sh.dtype])
-    rep = P.decode_parity(sh, layer, o, qd, kd, vd, Wq, Wk, bsel=bsel)
+    # a second layer in the same state runs the same steps with deferred folds (the mode the benchmark times)
+    shadow = P.make_layer(sh, fold_defer=8)
+    for name in ("H", "s", "win_k", "win_v", "sp_k", "sp_v", "sp_idx", "sp_count", "n_tokens"):
+        getattr(shadow, name).copy_(getattr(layer, name))
+    rep = P.decode_parity(sh, layer, o, qd, kd, vd, Wq, Wk, bsel=bsel, shadow=shadow)
     say(f"config4 decode x{n_steps} (sequences {bsel}, every step)", rep, f"{time.time() - t:.1f}s")
