@@ -454,6 +454,10 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
         }
     }
     LOLA_STAMP(12);
+    // operands of the listed pairs: A = phi_p (row = feature within a 16-block, k = p), B = v_p (column = value
+    // index).  They are requested after the first key tile's feature map: from there on enough registers are free,
+    // and the rest of the feature map covers their latency.
+    float pa[RG][8], pb[RG][2];
     if (steady) {
 #pragma unroll
         for (int t = 0; t < TPW; t++) {
@@ -483,6 +487,22 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
                 const int addr = row * D + (((4 * ks + g4) ^ r16) << 3);
                 *reinterpret_cast<uint4 *>(&PB[addr]) = __builtin_bit_cast(uint4, hi[ks]);
                 *reinterpret_cast<uint4 *>(&PB[LAM * D + addr]) = __builtin_bit_cast(uint4, lo[ks]);
+            }
+            if (R > 0 && t == 0) {
+                __builtin_amdgcn_sched_barrier(0);
+                int lp = lane;
+                asm volatile("" : "+v"(lp));
+                const int pr = lp & 15, pg = lp >> 4;
+#pragma unroll
+                for (int gr = 0; gr < RG; gr++) {
+                    const int pp_ = 4 * gr + pg;
+                    const bool live = pp_ < cnt;
+#pragma unroll
+                    for (int x = 0; x < 8; x++) pa[gr][x] = live ? pphi[pp_ * D + 16 * x + pr] : 0.f;
+#pragma unroll
+                    for (int ct = 0; ct < 2; ct++) pb[gr][ct] = live ? pval[pp_ * DH + 32 * w + 16 * ct + pr] : 0.f;
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
         if (w == 0) {
@@ -540,25 +560,6 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     if (steady) {
         // ---- stage 2: recall of all eligible pairs: P^T = H^T Phi^T; A = this wavefront's rows of H^T (bf16 high +
         // low parts made here), B = feature vectors from LDS
-        // operands of the pending pairs: A = phi_p (row = feature within a 16-block, k = p), B = v_p (column = value
-        // index); requested only now, after the feature map, whose registers they would otherwise compete for
-        float pa[RG][8], pb[RG][2];
-        if (R > 0) {
-            __builtin_amdgcn_sched_barrier(0);
-            int lp = lane;
-            asm volatile("" : "+v"(lp));
-            const int pr = lp & 15, pg = lp >> 4;
-#pragma unroll
-            for (int gr = 0; gr < RG; gr++) {
-                const int pp_ = 4 * gr + pg;
-                const bool live = pp_ < cnt;
-#pragma unroll
-                for (int x = 0; x < 8; x++) pa[gr][x] = live ? pphi[pp_ * D + 16 * x + pr] : 0.f;
-#pragma unroll
-                for (int ct = 0; ct < 2; ct++) pb[gr][ct] = live ? pval[pp_ * DH + 32 * w + 16 * ct + pr] : 0.f;
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
         bf16x8 Ahi[2][4], Alo[2][4];
         if (R > 0) {
 #define LOLA_HPEND(ct, ks, hf) { f32x4 c_ = {hreg##ct##ks##hf.x, hreg##ct##ks##hf.y, hreg##ct##ks##hf.z, hreg##ct##ks##hf.w}; \
