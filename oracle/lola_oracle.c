@@ -23,6 +23,9 @@
  *   orc_prefill        - chunkwise inference, Sec. 3 "Chunkwise Inference" (E_t for chunks) and
  *                        appendix update_chunk
  *   orc_cache_elems    - cache-size accounting, appendix "LoLA Cache vs. Transformers"
+ *   cfg.hide           - restricted-query ablation, appendix "Sparse Cache & Linear Attention
+ *                        Ablation": the memories are updated as usual, but the query does not read
+ *                        the hidden state (bit 0) and / or the sparse cache (bit 1)
  *
  * Readings taken where the paper is silent or ambiguous (each is also listed in the design notes):
  *   - scoring uses the state *before* the update of the same step (both pseudo-codes do);
@@ -56,6 +59,7 @@ enum { ORC_PHI_SOFTMAX = 0, ORC_PHI_EXP = 1 };
 typedef struct {
     int32_t B, Hq, Hkv, d, D, eta, lambda, C, phi_kind;
     double scale; /* logit scale; <= 0 means 1/sqrt(d) */
+    int32_t hide; /* bit 0: queries do not read (H, s); bit 1: queries do not read the sparse cache */
 } orc_config;
 
 typedef struct {
@@ -303,7 +307,8 @@ static double select_and_fold(const orc_config *c, stream_t *t, const float *Wk,
 /*
  * y = [phi(q)^T H + sum_i exp(scale q.k_i) v_i] / [phi(q)^T s + sum_i exp(scale q.k_i)]
  * over the sparse cache, the window, and the first n_extra rows of (xk, xv) (the causal part of
- * the current chunk during prefill; n_extra = 0 in decode).
+ * the current chunk during prefill; n_extra = 0 in decode).  With cfg.hide the hidden-state terms
+ * and / or the sparse-cache terms are left out of both sums.
  */
 static void attend(const orc_config *c, const stream_t *t, const float *Wq, const real *q,
                    const real *xk, const real *xv, int n_extra, double *out) {
@@ -312,14 +317,16 @@ static void attend(const orc_config *c, const stream_t *t, const float *Wq, cons
     real *num = (real *)calloc((size_t)d, sizeof(real));
     real den = 0;
     phi_map(c, Wq, q, phiq);
-    for (int f = 0; f < D; f++) {
-        real p = phiq[f];
-        const real *row = t->H + (size_t)f * d;
-        for (int j = 0; j < d; j++) num[j] += p * row[j];
-        den += p * t->s[f];
+    if (!(c->hide & 1)) {
+        for (int f = 0; f < D; f++) {
+            real p = phiq[f];
+            const real *row = t->H + (size_t)f * d;
+            for (int j = 0; j < d; j++) num[j] += p * row[j];
+            den += p * t->s[f];
+        }
     }
     const pair_list *lists[2] = { &t->sp, &t->win };
-    for (int l = 0; l < 2; l++) {
+    for (int l = (c->hide & 2) ? 1 : 0; l < 2; l++) {
         const pair_list *p = lists[l];
         for (int i = 0; i < p->n; i++) {
             real dot = 0;

@@ -16,11 +16,12 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "lola_oracle.c")
 
 PHI_SOFTMAX, PHI_EXP = 0, 1
+HIDE_STATE, HIDE_SPARSE = 1, 2   # restricted-query ablation: what the query does not read
 
 
 class _Cfg(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("B", "Hq", "Hkv", "d", "D", "eta", "lam", "C", "phi_kind")] + [
-        ("scale", C.c_double)
+        ("scale", C.c_double), ("hide", C.c_int32)
     ]
 
 
@@ -101,7 +102,7 @@ def phi(W, x, kind=PHI_SOFTMAX, real="f64") -> np.ndarray:
     """phi(x) for a single vector; W is [d, D/2]."""
     W = _f32(W)
     d, m = W.shape
-    cfg = _Cfg(1, 1, 1, d, 2 * m, 0, 0, 1, kind, 0.0)
+    cfg = _Cfg(1, 1, 1, d, 2 * m, 0, 0, 1, kind, 0.0, 0)
     x = np.ascontiguousarray(x, dtype=np.float64)
     out = np.empty(2 * m, dtype=np.float64)
     _lib(real).orc_phi(C.byref(cfg), _ptr(W), _ptr(x), _ptr(out))
@@ -111,11 +112,11 @@ def phi(W, x, kind=PHI_SOFTMAX, real="f64") -> np.ndarray:
 class Oracle:
     """State of one LoLA layer (all sequences and kv heads) plus the two update/attend calls."""
 
-    def __init__(self, B, Hq, Hkv, d, D, eta, lam, C_, phi_kind=PHI_SOFTMAX, scale=0.0, real="f64"):
+    def __init__(self, B, Hq, Hkv, d, D, eta, lam, C_, phi_kind=PHI_SOFTMAX, scale=0.0, real="f64", query_hide=0):
         self.L = _lib(real)
         self.B, self.Hq, self.Hkv, self.d, self.D = B, Hq, Hkv, d, D
         self.eta, self.lam, self.C, self.m = eta, lam, C_, D // 2
-        self.cfg = _Cfg(B, Hq, Hkv, d, D, eta, lam, C_, phi_kind, float(scale))
+        self.cfg = _Cfg(B, Hq, Hkv, d, D, eta, lam, C_, phi_kind, float(scale), int(query_hide))
         self.h = self.L.orc_state_new(C.byref(self.cfg))
         if not self.h:
             raise ValueError("invalid oracle configuration")

@@ -108,6 +108,79 @@ def test_full_window_is_causal_softmax_decode():
 
 
 # ---------------------------------------------------------------------------------------------
+# restricted-query ablation (appendix "Sparse Cache & Linear Attention Ablation"): the memories
+# are updated as usual, the query reads only some of them
+# ---------------------------------------------------------------------------------------------
+def brute_window_softmax(q, k, v, g, first_visible):
+    """softmax attention of query t over tokens first_visible[t] .. t (library softmax)."""
+    B, Hq, T, d = q.shape
+    out = np.zeros((B, Hq, T, d))
+    for b in range(B):
+        for h in range(Hq):
+            kk, vv = k[b, h // g].astype(np.float64), v[b, h // g].astype(np.float64)
+            for t in range(T):
+                lo = first_visible[t]
+                w = softmax(q[b, h, t].astype(np.float64) @ kk[lo:t + 1].T / np.sqrt(d))
+                out[b, h, t] = w @ vv[lo:t + 1]
+    return out
+
+
+@pytest.mark.parametrize("eta,lam,C", [(6, 4, 6), (5, 3, 8), (7, 0, 3), (4, 5, 1)])
+def test_hide_state_and_sparse_is_sliding_window_attention(eta, lam, C):
+    """With both hidden only the window (and the chunk's causal part) is read: decode sees the last
+    eta tokens, a prefill query sees from eta tokens before its chunk's start."""
+    B, Hq, Hkv, d, D, T = 1, 4, 2, 8, 6, 41
+    q, k, v, Wq, Wk = rand_inputs(41, B, Hq, Hkv, d, D, T)
+    o = orc.Oracle(B, Hq, Hkv, d, D, eta, lam, C, query_hide=orc.HIDE_STATE | orc.HIDE_SPARSE)
+    out = run_decode(o, q, k, v, Wq, Wk, 0, T)
+    ref = brute_window_softmax(q, k, v, Hq // Hkv, [max(0, t - eta + 1) for t in range(T)])
+    np.testing.assert_allclose(out, ref, rtol=1e-11, atol=1e-13)
+    o2 = orc.Oracle(B, Hq, Hkv, d, D, eta, lam, C, query_hide=3)
+    out2 = o2.prefill(q, k, v, Wq, Wk)
+    ref2 = brute_window_softmax(q, k, v, Hq // Hkv, [max(0, (t // C) * C - eta) for t in range(T)])
+    np.testing.assert_allclose(out2, ref2, rtol=1e-11, atol=1e-13)
+
+
+@pytest.mark.parametrize("hide", [1, 2, 3])
+def test_hidden_memories_are_still_updated(hide):
+    """Hiding changes what the query reads, never the memories."""
+    B, Hq, Hkv, d, D, T, eta, lam, C = 2, 4, 2, 8, 6, 50, 5, 4, 7
+    q, k, v, Wq, Wk = rand_inputs(42, B, Hq, Hkv, d, D, T + 9)
+    a = orc.Oracle(B, Hq, Hkv, d, D, eta, lam, C)
+    b = orc.Oracle(B, Hq, Hkv, d, D, eta, lam, C, query_hide=hide)
+    ya, yb = a.prefill(q[:, :, :T], k[:, :, :T], v[:, :, :T], Wq, Wk), b.prefill(q[:, :, :T], k[:, :, :T], v[:, :, :T], Wq, Wk)
+    ya2, yb2 = run_decode(a, q, k, v, Wq, Wk, T, 9), run_decode(b, q, k, v, Wq, Wk, T, 9)
+    assert np.array_equal(a.H, b.H) and np.array_equal(a.s, b.s)
+    assert np.array_equal(a.sparse_idx, b.sparse_idx) and np.array_equal(a.window_idx, b.window_idx)
+    assert not np.allclose(ya[:, :, eta + lam + 3:], yb[:, :, eta + lam + 3:]) and not np.allclose(ya2, yb2)
+
+
+@pytest.mark.parametrize("hide", [0, 1, 2])
+def test_hide_matches_sum_over_the_visible_memories(hide):
+    """Decode output rebuilt from the state the oracle reports after the step: the hidden state
+    through the library feature map, the listed sparse and window tokens through exp."""
+    B, Hq, Hkv, d, D, T, eta, lam, C = 1, 4, 2, 8, 6, 40, 5, 4, 4
+    g = Hq // Hkv
+    q, k, v, Wq, Wk = rand_inputs(43, B, Hq, Hkv, d, D, T)
+    o = orc.Oracle(B, Hq, Hkv, d, D, eta, lam, C, query_hide=hide)
+    for t in range(T):
+        y = o.decode_step(q[:, :, t], k[:, :, t], v[:, :, t], Wq, Wk)
+        H, s, sp, wi = o.H, o.s, o.sparse_idx, o.window_idx
+        for hq in range(Hq):
+            h = hq // g
+            qq = q[0, hq, t].astype(np.float64)
+            num, den = np.zeros(d), 0.0
+            if not hide & 1:
+                ph = np_phi(Wq[hq], qq[None])[0]
+                num, den = num + ph @ H[0, h], den + ph @ s[0, h]
+            toks = [int(i) for i in wi[0, h] if i >= 0] + ([] if hide & 2 else [int(i) for i in sp[0, h] if i >= 0])
+            for i in toks:
+                w = np.exp(qq @ k[0, h, i].astype(np.float64) / np.sqrt(d))
+                num, den = num + w * v[0, h, i].astype(np.float64), den + w
+            np.testing.assert_allclose(y[0, hq], num / den, rtol=1e-10, atol=1e-12)
+
+
+# ---------------------------------------------------------------------------------------------
 # pin 2: no window, no sparse cache -> normalised linear attention (Sec. 2.2 eq. lin_attn_forward)
 # ---------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("kind", [orc.PHI_SOFTMAX, orc.PHI_EXP])
