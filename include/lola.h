@@ -43,6 +43,9 @@ enum { LOLA_F32 = 0, LOLA_BF16 = 1 };
  * LOLA_PHI_EXP is the paper's form [exp(z), exp(-z)]; LOLA_PHI_SOFTMAX is the bounded form
  * [softmax(z), softmax(-z)] the benchmark configurations prescribe. */
 enum { LOLA_PHI_SOFTMAX = 0, LOLA_PHI_EXP = 1 };
+/* Restricted-query ablation (appendix "Sparse Cache & Linear Attention Ablation"): the memories are
+ * updated as usual, but the queries do not read the hidden state and / or the sparse cache. */
+enum { LOLA_HIDE_STATE = 1, LOLA_HIDE_SPARSE = 2 };
 
 typedef struct {
     int32_t batch, n_q_heads, n_kv_heads;
@@ -59,6 +62,8 @@ typedef struct {
                               R = 8: deferred folds (see lola_state.pend_*); accepted only where the fused
                               generation-step kernel exists (bf16, head_dim 128, feat_dim 128, window 64,
                               sparse_budget 64 or 128, 4 query heads per kv head), else LOLA_ERR_UNSUPPORTED */
+    int32_t query_hide;    /* 0, or LOLA_HIDE_STATE | LOLA_HIDE_SPARSE bits: terms left out of the numerator
+                              and the denominator of every output (lola_prefill and lola_decode_step) */
 } lola_config;
 
 /* The memories of a layer.  H and s are always fp32 (Sec. 2.2, eq. recurrent_update). */

@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(_HERE, "liblola.so")
 
 LOLA_F32, LOLA_BF16 = 0, 1
 LOLA_PHI_SOFTMAX, LOLA_PHI_EXP = 0, 1
+LOLA_HIDE_STATE, LOLA_HIDE_SPARSE = 1, 2
 EXPORTS = ("lola_state_bytes", "lola_prefill_workspace_bytes", "lola_state_init", "lola_state_flush", "lola_prefill",
            "lola_decode_step", "lola_status_str", "lola_kernel_path")
 
@@ -23,7 +24,7 @@ EXPORTS = ("lola_state_bytes", "lola_prefill_workspace_bytes", "lola_state_init"
 class LolaConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "batch", "n_q_heads", "n_kv_heads", "head_dim", "feat_dim", "window", "sparse_budget", "chunk",
-        "dtype", "out_dtype", "phi_kind")] + [("softmax_scale", C.c_float), ("fold_defer", C.c_int32)]
+        "dtype", "out_dtype", "phi_kind")] + [("softmax_scale", C.c_float), ("fold_defer", C.c_int32), ("query_hide", C.c_int32)]
 
 
 class LolaState(C.Structure):
@@ -123,11 +124,12 @@ class LolaLayer:
     """Device buffers of one layer's memories plus the three calls, for tests and benchmarks."""
 
     def __init__(self, B, Hq, Hkv, d, D, eta, lam, C_, dtype="bf16", out_dtype="f32",
-                 phi_kind=LOLA_PHI_SOFTMAX, scale=0.0, fold_defer=0, device="cuda:0"):
+                 phi_kind=LOLA_PHI_SOFTMAX, scale=0.0, fold_defer=0, query_hide=0, device="cuda:0"):
         self.device = torch.device(device)
         self.dt = LOLA_BF16 if dtype == "bf16" else LOLA_F32
         self.odt = LOLA_BF16 if out_dtype == "bf16" else LOLA_F32
-        self.cfg = LolaConfig(B, Hq, Hkv, d, D, eta, lam, C_, self.dt, self.odt, phi_kind, float(scale), int(fold_defer))
+        self.cfg = LolaConfig(B, Hq, Hkv, d, D, eta, lam, C_, self.dt, self.odt, phi_kind, float(scale), int(fold_defer),
+                              int(query_hide))
         self.fold_defer = R = int(fold_defer)
         self.B, self.Hq, self.Hkv, self.d, self.D, self.eta, self.lam, self.C = B, Hq, Hkv, d, D, eta, lam, C_
         tot, fb = lola_state_bytes(self.cfg)

@@ -134,6 +134,7 @@ struct DecodeFastArgs {
     int Hq, Hkv;
     float scale;
     int phi_kind;
+    int hide;   // restricted query: bit 0 the hidden state, bit 1 the sparse cache is not read
     // deferred folds (R > 0): up to R - 1 folded pairs per stream wait here, [stream][R][D] / [stream][R][DH] fp32
     float *pend_phi, *pend_v;
     int32_t *pend_count;
@@ -743,8 +744,8 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
         for (int x = 0; x < (KPAD + 63) / 64; x++) {
             const int key = lane + 64 * x;
             bool ok = false;
-            if (key < LAM) ok = key < spc && key != drop;
-            else if (key == KP) ok = popped && drop != LAM;
+            if (key < LAM) ok = key < spc && key != drop && !(a.hide & 2);
+            else if (key == KP) ok = popped && drop != LAM && !(a.hide & 2);   // it sits in the sparse cache now
             else if (key < NKEY) ok = (key - KW) < wn;
             l[x] = ok ? lg[r][key] : -INFINITY;
             mx = fmaxf(mx, l[x]);
@@ -796,7 +797,7 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
 #pragma unroll
                 for (int r = 0; r < G; r++) {
                     float num = acc[nt][r], den = psum_s[r];
-                    if (steady) {
+                    if (steady && !(a.hide & 1)) {
                         const float el = elin_s[r];
                         num = fmaf(el, fmaf(dotqf[r], vf[c], lin[r][c]), num);
                         den = fmaf(el, denq[r] + dotqf[r], den);

@@ -268,6 +268,7 @@ __global__ __launch_bounds__(NT) void decode_kernel(DecodeArgs<T> a) {
             float dot = 0.f;
             for (int j = 0; j < d; j++) dot = fmaf(xs[j], ldf(kr, j), dot);
             dot *= dm.scale;
+            if (i < spc && (dm.hide & 2)) dot = -INFINITY;   // restricted query: the sparse cache is not read
             pw[i] = dot;
             lmax = fmaxf(lmax, dot);
         }
@@ -282,7 +283,7 @@ __global__ __launch_bounds__(NT) void decode_kernel(DecodeArgs<T> a) {
         float lden = 0.f;
         for (int f = tid; f < D; f += NT) lden = fmaf(ph[f], s[f], lden);
         lden = block_sum(lden, red);
-        const float elin = expf(-lmax);
+        const float elin = (dm.hide & 1) ? 0.f : expf(-lmax);   // restricted query: the hidden state is not read
         const int c = tid % d, part = tid / d, nparts = NT / d;
         float num = 0.f;
         for (int i = part; i < nk; i += nparts) {
@@ -610,7 +611,7 @@ __global__ __launch_bounds__(NT) void attend_kernel(PrefillArgs<T> a) {
         for (int p = tid; p < nq * nk; p += NT) {
             int qi = p / nk, key = p - qi * nk;
             int vr; bool ok;
-            if (key < lam) { vr = G[key]; ok = vr >= 0; }
+            if (key < lam) { vr = G[key]; ok = vr >= 0 && !(dm.hide & 2); }
             else { int x = key - lam; vr = vrow0 + x; ok = (lo + x) <= (aj + i0 + qi); }
             float l = -INFINITY;
             if (ok) {
@@ -656,7 +657,7 @@ __global__ __launch_bounds__(NT) void attend_kernel(PrefillArgs<T> a) {
             float lin = 0.f;
             const float *pq = phq + qi * D;
             for (int f = 0; f < D; f++) lin = fmaf(pq[f], Hj[(size_t)c * D + f], lin);
-            const float elin = expf(-rmax[qi]);
+            const float elin = (dm.hide & 1) ? 0.f : expf(-rmax[qi]);
             stf(oh, (size_t)(i0 + qi) * d + c, fmaf(elin, lin, num) / (rsum[qi] + elin * rlin[qi]));
         }
         __syncthreads();

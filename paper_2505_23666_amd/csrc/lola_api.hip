@@ -49,6 +49,7 @@ lola_status check_config(const lola_config *c) {
     if (c->window < 0 || c->sparse_budget < 0 || c->chunk < 1) return LOLA_ERR_SHAPE;
     if (c->window > 4096 || c->sparse_budget > 4096 || c->chunk > 1024) return LOLA_ERR_SHAPE;
     if ((long long)c->batch * c->n_kv_heads > (1ll << 24)) return LOLA_ERR_SHAPE;
+    if (c->query_hide < 0 || c->query_hide > 3) return LOLA_ERR_SHAPE;
     if (c->fold_defer != 0 && c->fold_defer != DEFER_R) return LOLA_ERR_SHAPE;
     if (c->fold_defer != 0 && !fast_decode_ok(c)) return LOLA_ERR_UNSUPPORTED;
     return LOLA_OK;
@@ -61,6 +62,7 @@ Dims make_dims(const lola_config *c) {
     dm.eta = c->window; dm.lam = c->sparse_budget; dm.C = c->chunk;
     dm.phi_kind = c->phi_kind;
     dm.scale = c->softmax_scale > 0.f ? c->softmax_scale : 1.0f / sqrtf((float)c->head_dim);
+    dm.hide = c->query_hide;
     return dm;
 }
 
@@ -182,6 +184,7 @@ lola_status launch_fast_decode(const lola_config *c, const lola_state *st, const
     a.Hq = c->n_q_heads; a.Hkv = c->n_kv_heads;
     a.scale = make_dims(c).scale;
     a.phi_kind = c->phi_kind;
+    a.hide = c->query_hide;
     a.pend_phi = st->pend_phi; a.pend_v = st->pend_v; a.pend_count = st->pend_count;
     if (c->fold_defer)
         hipLaunchKernelGGL((fast::decode_fast_kernel<LAM, 64, 4, DEFER_R, TO>), dim3(c->batch * c->n_kv_heads), dim3(256), 0, stream, a);

@@ -16,6 +16,7 @@ struct Dims {
     int eta, lam, C;        // window, sparse budget, prefill chunk
     int phi_kind;           // 0 softmax kind, 1 exponential kind
     float scale;            // logit scale
+    int hide;               // bit 0: queries do not read (H, s); bit 1: queries do not read the sparse cache
 };
 
 // Device pointers of the memories (layout documented in include/lola.h).

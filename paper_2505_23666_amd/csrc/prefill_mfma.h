@@ -129,7 +129,7 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
             for (int i = 0; i < 4; i++) {
                 const int pos = 128 * blk + 16 * mt + 4 * g4 + i;
                 bool ok;
-                if (pos < LAM) ok = G_l[pos] >= 0;
+                if (pos < LAM) ok = G_l[pos] >= 0 && !(a.dm.hide & 2);
                 else if (pos < LAM + ETA) ok = aj - ETA + (pos - LAM) >= 0;
                 else ok = pos < NKEYS && (aj + (pos - LAM - ETA)) <= tq;
                 acc[i] = ok ? acc[i] * scale2 : -INFINITY;
@@ -207,7 +207,7 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
     bf16x8 Bh[4], Bl[4];
     split8(&pp[0], Bh[0], Bl[0]); split8(&pp[8], Bh[1], Bl[1]);
     split8(&pn[0], Bh[2], Bl[2]); split8(&pn[8], Bh[3], Bl[3]);
-    const float el = fexp2(-mrun);
+    const float el = (a.dm.hide & 1) ? 0.f : fexp2(-mrun);   // restricted query: no hidden-state terms
     const float inv = 1.0f / fmaf(el, lden, lsum);
     __syncthreads();   // H^T is in LDS
 #pragma unroll

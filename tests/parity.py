@@ -145,7 +145,8 @@ def prefill_parity(sh: wl.Shape, q, k, v, Wq, Wk, layer=None, oracle=None, with_
     if oracle is None:
         okw = dict(layer_kw or {})
         oracle = orc.Oracle(len(bs), len(hq), len(hs), sh.d, sh.D, sh.eta, sh.lam, sh.C,
-                            phi_kind=okw.get("phi_kind", 0), scale=okw.get("scale", 0.0))
+                            phi_kind=okw.get("phi_kind", 0), scale=okw.get("scale", 0.0),
+                            query_hide=okw.get("query_hide", 0))
     trace = trace.cpu().numpy()[np.ix_(bs, hs)] if sh.lam > 0 else None
     y_or = oracle.prefill(oq, ok_, ov, oWq if with_outputs else None, oWk, force_sel=trace, tie_eps=TIE_EPS)
     st = oracle.stats()

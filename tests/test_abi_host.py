@@ -99,3 +99,4 @@ def test_arguments_rejected_before_launch(L):
     assert L.lola_state_flush(C.byref(c8), C.byref(st), None) == -1
     assert L.lola_state_flush(C.byref(cfg(fold_defer=8, sparse_budget=256)), C.byref(st), None) == -5
     assert L.lola_state_flush(C.byref(cfg(fold_defer=5)), C.byref(st), None) == -2
+    assert f(C.byref(cfg(query_hide=4)), C.byref(st), vp(fake), vp(fake), vp(fake), vp(fake), vp(fake), vp(fake), None) == -2

@@ -162,6 +162,36 @@ def test_deferred_folds_refused_elsewhere():
         lb.LolaLayer(1, 4, 1, 128, 128, 64, 128, 64, fold_defer=4)
 
 
+@pytest.mark.parametrize("hide", [1, 2, 3])
+def test_restricted_query_generic_kernels(hide):
+    """Queries that do not read the hidden state (1), the sparse cache (2) or both (3); the
+    memories evolve as usual.  fp32, generic kernels, prefill with a ragged tail then decode."""
+    sh = wl.Shape("hide", "f32", 2, 4, 2, 32, 16, T=0, eta=8, lam=6, C=8, seed=0)
+    T = 8 * 9 + 5
+    q, k, v, Wq, Wk = rand_case(50 + hide, 2, 4, 2, 32, 16, T + 12, "f32")
+    kw = dict(query_hide=hide)
+    layer, o, rep = P.prefill_parity(sh, q[:, :, :T], k[:, :, :T], v[:, :, :T], Wq, Wk, layer_kw=kw)
+    rep2 = P.decode_parity(sh, layer, o, *steps(q, k, v, T, 12), Wq, Wk)
+    say("restricted query (generic)", hide, rep, rep2)
+    assert rep["scored"] > 0 and rep2["scored"] > 0
+
+
+@pytest.mark.parametrize("hide,defer", [(1, 0), (2, 8), (3, 0), (3, 8)])
+def test_restricted_query_mfma_kernels(hide, defer):
+    """The same on the MFMA prefill kernels and the fused generation step (8B head shape), with
+    and without deferred folds."""
+    sh = wl.scaled(3, B=1, T=64 * 6 + 10 + 20)
+    T = 64 * 6 + 10
+    Wq, Wk = wl.weights(sh)
+    q, k, v, _ = wl.sequence_inputs(sh)
+    kw = dict(query_hide=hide, fold_defer=defer)
+    layer, o, rep = P.prefill_parity(sh, q[:, :, :T], k[:, :, :T], v[:, :, :T], Wq, Wk, layer_kw=kw)
+    assert layer.lola_path == ("mfma", "mfma")
+    rep2 = P.decode_parity(sh, layer, o, *steps(q, k, v, T, 20), Wq, Wk)
+    say("restricted query (mfma)", hide, defer, rep, rep2)
+    assert rep2["scored"] - rep["scored"] == 8 * 20
+
+
 def test_exp_feature_map():
     sh = wl.Shape("expphi", "f32", 1, 2, 1, 32, 16, T=64, eta=8, lam=6, C=8, seed=0)
     q, k, v, Wq, Wk = rand_case(8, 1, 2, 1, 32, 16, 70, "f32", wscale=0.5)
