@@ -23,6 +23,12 @@
  *   orc_prefill        - chunkwise inference, Sec. 3 "Chunkwise Inference" (E_t for chunks) and
  *                        appendix update_chunk
  *   orc_cache_elems    - cache-size accounting, appendix "LoLA Cache vs. Transformers"
+ *   cfg.score_kind     - the alternative, query-dependent importance scores of Sec. 4 "scoring ablation"
+ *                        / appendix "scoring ablation": Score(k_i) = sum over the eta queries
+ *                        t = i .. i+eta-1 that see k_i in the sliding window (all query heads of the
+ *                        group) of (w - a)^2, |w - a|, a / w or w, with w = exp(scale q_t.k_i) and
+ *                        a = phi(q_t).phi(k_i); the score is final when the pair leaves the window
+ *                        and is kept with it in the sparse cache (query_term, accumulate_scores)
  *   cfg.hide           - restricted-query ablation, appendix "Sparse Cache & Linear Attention
  *                        Ablation": the memories are updated as usual, but the query does not read
  *                        the hidden state (bit 0) and / or the sparse cache (bit 1)
@@ -55,16 +61,19 @@
 typedef ORC_REAL real;
 
 enum { ORC_PHI_SOFTMAX = 0, ORC_PHI_EXP = 1 };
+enum { ORC_SCORE_SRE = 0, ORC_SCORE_WERR_SQ = 1, ORC_SCORE_WERR_ABS = 2, ORC_SCORE_OVEREST = 3, ORC_SCORE_ATTN = 4 };
 
 typedef struct {
     int32_t B, Hq, Hkv, d, D, eta, lambda, C, phi_kind;
     double scale; /* logit scale; <= 0 means 1/sqrt(d) */
     int32_t hide; /* bit 0: queries do not read (H, s); bit 1: queries do not read the sparse cache */
+    int32_t score_kind; /* ORC_SCORE_*: what ranks the eligible pairs */
 } orc_config;
 
 typedef struct {
     real *k, *v;   /* [cap][d] */
     int64_t *idx;  /* [cap] token index */
+    real *score;   /* [cap] query-dependent score gathered so far (unused with ORC_SCORE_SRE) */
     int n, cap;
 } pair_list;
 
@@ -91,29 +100,34 @@ static void pl_init(pair_list *p, int cap, int d) {
     p->k = (real *)calloc((size_t)p->cap * d, sizeof(real));
     p->v = (real *)calloc((size_t)p->cap * d, sizeof(real));
     p->idx = (int64_t *)calloc((size_t)p->cap, sizeof(int64_t));
+    p->score = (real *)calloc((size_t)p->cap, sizeof(real));
     p->n = 0;
 }
-static void pl_free(pair_list *p) { free(p->k); free(p->v); free(p->idx); }
+static void pl_free(pair_list *p) { free(p->k); free(p->v); free(p->idx); free(p->score); }
 static void pl_reserve(pair_list *p, int cap, int d) {
     if (cap <= p->cap) return;
     p->k = (real *)realloc(p->k, (size_t)cap * d * sizeof(real));
     p->v = (real *)realloc(p->v, (size_t)cap * d * sizeof(real));
     p->idx = (int64_t *)realloc(p->idx, (size_t)cap * sizeof(int64_t));
+    p->score = (real *)realloc(p->score, (size_t)cap * sizeof(real));
     p->cap = cap;
 }
-static void pl_push(pair_list *p, int d, const real *k, const real *v, int64_t idx) {
+static void pl_push_scored(pair_list *p, int d, const real *k, const real *v, int64_t idx, real score) {
     if (p->n == p->cap) pl_reserve(p, 2 * p->cap, d);
     memcpy(p->k + (size_t)p->n * d, k, d * sizeof(real));
     memcpy(p->v + (size_t)p->n * d, v, d * sizeof(real));
     p->idx[p->n] = idx;
+    p->score[p->n] = score;
     p->n++;
 }
+static void pl_push(pair_list *p, int d, const real *k, const real *v, int64_t idx) { pl_push_scored(p, d, k, v, idx, 0); }
 /* drop the first `cnt` entries */
 static void pl_drop_front(pair_list *p, int d, int cnt) {
     int rest = p->n - cnt;
     memmove(p->k, p->k + (size_t)cnt * d, (size_t)rest * d * sizeof(real));
     memmove(p->v, p->v + (size_t)cnt * d, (size_t)rest * d * sizeof(real));
     memmove(p->idx, p->idx + cnt, (size_t)rest * sizeof(int64_t));
+    memmove(p->score, p->score + cnt, (size_t)rest * sizeof(real));
     p->n = rest;
 }
 
@@ -236,7 +250,8 @@ static double select_and_fold(const orc_config *c, stream_t *t, const float *Wk,
     char *keep = (char *)calloc((size_t)n, 1);
     for (int e = 0; e < n; e++) {
         phi_map(c, Wk, t->sp.k + (size_t)e * d, phis + (size_t)e * D);
-        score[e] = sre(c, t, phis + (size_t)e * D, t->sp.v + (size_t)e * d);
+        score[e] = c->score_kind == ORC_SCORE_SRE ? sre(c, t, phis + (size_t)e * D, t->sp.v + (size_t)e * d)
+                                                  : t->sp.score[e];
         order[e] = e;
     }
     /* insertion sort by (score descending, token index ascending) */
@@ -272,7 +287,10 @@ static double select_and_fold(const orc_config *c, stream_t *t, const float *Wk,
                 if (keep[e] && !fkeep[e] && (double)score[e] > hi_dropped) hi_dropped = (double)score[e];
                 if (!keep[e] && fkeep[e] && (double)score[e] < lo_taken) lo_taken = (double)score[e];
             }
-            if (!unknown && n_forced == lam && hi_dropped - lo_taken <= tie_eps) {
+            /* the band is absolute for the self-recall error (values of order one) and relative for the
+               query-dependent scores, whose size depends on eta, the group size and the logits */
+            double band = c->score_kind == ORC_SCORE_SRE ? tie_eps : tie_eps * fmax(1.0, fabs(hi_dropped));
+            if (!unknown && n_forced == lam && hi_dropped - lo_taken <= band) {
                 memcpy(keep, fkeep, (size_t)n);
                 t->n_adopted++;
             } else {
@@ -295,6 +313,7 @@ static double select_and_fold(const orc_config *c, stream_t *t, const float *Wk,
                 memcpy(t->sp.k + (size_t)w * d, t->sp.k + (size_t)e * d, d * sizeof(real));
                 memcpy(t->sp.v + (size_t)w * d, t->sp.v + (size_t)e * d, d * sizeof(real));
                 t->sp.idx[w] = t->sp.idx[e];
+                t->sp.score[w] = t->sp.score[e];
             }
             w++;
         }
@@ -302,6 +321,45 @@ static double select_and_fold(const orc_config *c, stream_t *t, const float *Wk,
     t->sp.n = w;
     free(phis); free(score); free(order); free(keep);
     return margin;
+}
+
+/* One query's contribution to the score of one key (appendix "scoring ablation"). */
+static real query_term(const orc_config *c, const real *phiq, const real *q, const real *phik, const real *k) {
+    real dot = 0, a = 0;
+    for (int j = 0; j < c->d; j++) dot += q[j] * k[j];
+    for (int f = 0; f < c->D; f++) a += phiq[f] * phik[f];
+    real w = (real)exp((double)((real)c->scale * dot));
+    switch (c->score_kind) {
+        case ORC_SCORE_WERR_SQ: return (w - a) * (w - a);
+        case ORC_SCORE_WERR_ABS: return (real)fabs((double)(w - a));
+        case ORC_SCORE_OVEREST: return a / w;
+        default: return w; /* ORC_SCORE_ATTN */
+    }
+}
+
+/*
+ * Query q with token index tq adds its term to every pair it sees inside the sliding-window band
+ * tq-eta+1 .. tq: pairs of the window list and the first n_extra rows of the current chunk (token
+ * indices tok0 .. ; their sums are kept in xscore until the chunk joins the window).
+ */
+static void accumulate_scores(const orc_config *c, stream_t *t, const float *Wq, const float *Wk, const real *q,
+                              int64_t tq, const real *xk, int n_extra, int64_t tok0, real *xscore) {
+    if (c->score_kind == ORC_SCORE_SRE) return;
+    int d = c->d, D = c->D;
+    real *phiq = (real *)malloc((size_t)D * sizeof(real));
+    real *phik = (real *)malloc((size_t)D * sizeof(real));
+    phi_map(c, Wq, q, phiq);
+    for (int i = 0; i < t->win.n; i++) {
+        if (t->win.idx[i] < tq - c->eta + 1 || t->win.idx[i] > tq) continue;
+        phi_map(c, Wk, t->win.k + (size_t)i * d, phik);
+        t->win.score[i] += query_term(c, phiq, q, phik, t->win.k + (size_t)i * d);
+    }
+    for (int i = 0; i < n_extra; i++) {
+        if (tok0 + i < tq - c->eta + 1 || tok0 + i > tq) continue;
+        phi_map(c, Wk, xk + (size_t)i * d, phik);
+        xscore[i] += query_term(c, phiq, q, phik, xk + (size_t)i * d);
+    }
+    free(phiq); free(phik);
 }
 
 /*
@@ -375,7 +433,7 @@ int orc_decode_step(orc_state *S, const float *q, const float *k, const float *v
         double margin = -1.0;
         if (t->win.n > c->eta) {
             /* 2. E = G u {leaving pair}; keep top-lambda, fold the rest */
-            pl_push(&t->sp, d, t->win.k, t->win.v, t->win.idx[0]);
+            pl_push_scored(&t->sp, d, t->win.k, t->win.v, t->win.idx[0], t->win.score[0]);
             pl_drop_front(&t->win, d, 1);
             margin = select_and_fold(c, t, Wk_h, force_sel ? force_sel + (size_t)si * c->lambda : NULL, tie_eps);
         }
@@ -385,6 +443,7 @@ int orc_decode_step(orc_state *S, const float *q, const float *k, const float *v
             int hq = h * g + r;
             load_row(kr, q + ((size_t)b * c->Hq + hq) * d, d);
             attend(c, t, Wq + (size_t)hq * d * m, kr, NULL, NULL, 0, out + ((size_t)b * c->Hq + hq) * d);
+            accumulate_scores(c, t, Wq + (size_t)hq * d * m, Wk_h, kr, tok, NULL, 0, 0, NULL);
         }
         free(kr); free(vr);
     }
@@ -405,6 +464,7 @@ int orc_prefill(orc_state *S, const float *q, const float *k, const float *v,
                 const int32_t *force_sel, double tie_eps, int32_t *sel_log, double *margin_log) {
     if (!S || !k || !v || !Wk || T < 0) return -1;
     if ((q == NULL) != (out == NULL)) return -1;
+    if (!q && S->cfg.score_kind != ORC_SCORE_SRE && T > 0) return -1; /* these scores are sums over queries */
     if (q && !Wq) return -1;
     const orc_config *c = &S->cfg;
     int d = c->d, m = c->D / 2, g = c->Hq / c->Hkv, ns = c->B * c->Hkv, C = c->C, lam = c->lambda;
@@ -417,12 +477,14 @@ int orc_prefill(orc_state *S, const float *q, const float *k, const float *v,
         real *ck = (real *)malloc((size_t)C * d * sizeof(real));
         real *cv = (real *)malloc((size_t)C * d * sizeof(real));
         real *qr = (real *)malloc((size_t)d * sizeof(real));
+        real *cs = (real *)malloc((size_t)C * sizeof(real));
         for (int j = 0; j < n_chunks; j++) {
             int a = j * C, cl = (T - a < C) ? T - a : C;
             int64_t tok0 = S->n_tokens[b] + a;
             for (int i = 0; i < cl; i++) {
                 load_row(ck + (size_t)i * d, k + ((size_t)si * T + a + i) * d, d);
                 load_row(cv + (size_t)i * d, v + ((size_t)si * T + a + i) * d, d);
+                cs[i] = 0;
             }
             /* 1. outputs: entry state, entry sparse cache, entry window, own chunk causally */
             if (q) {
@@ -432,16 +494,17 @@ int orc_prefill(orc_state *S, const float *q, const float *k, const float *v,
                         size_t off = (((size_t)b * c->Hq + hq) * T + a + i) * d;
                         load_row(qr, q + off, d);
                         attend(c, t, Wq + (size_t)hq * d * m, qr, ck, cv, i + 1, out + off);
+                        accumulate_scores(c, t, Wq + (size_t)hq * d * m, Wk_h, qr, tok0 + i, ck, i + 1, tok0, cs);
                     }
                 }
             }
             /* 2. the chunk joins the window; what no longer fits is the evicted group */
-            for (int i = 0; i < cl; i++) pl_push(&t->win, d, ck + (size_t)i * d, cv + (size_t)i * d, tok0 + i);
+            for (int i = 0; i < cl; i++) pl_push_scored(&t->win, d, ck + (size_t)i * d, cv + (size_t)i * d, tok0 + i, cs[i]);
             int n_ev = t->win.n - c->eta;
             double margin = -1.0;
             if (n_ev > 0) {
                 for (int i = 0; i < n_ev; i++)
-                    pl_push(&t->sp, d, t->win.k + (size_t)i * d, t->win.v + (size_t)i * d, t->win.idx[i]);
+                    pl_push_scored(&t->sp, d, t->win.k + (size_t)i * d, t->win.v + (size_t)i * d, t->win.idx[i], t->win.score[i]);
                 pl_drop_front(&t->win, d, n_ev);
                 const int32_t *f = force_sel ? force_sel + ((size_t)si * n_chunks + j) * lam : NULL;
                 margin = select_and_fold(c, t, Wk_h, f, tie_eps);
@@ -459,7 +522,7 @@ int orc_prefill(orc_state *S, const float *q, const float *k, const float *v,
                 }
             }
         }
-        free(ck); free(cv); free(qr);
+        free(ck); free(cv); free(qr); free(cs);
     }
     for (int b = 0; b < c->B; b++) S->n_tokens[b] += T;
     return 0;
@@ -505,6 +568,12 @@ int orc_get_pairs(const orc_state *S, int stream, int which /*0 sparse, 1 window
         }
         if (idx) idx[i] = p->idx[i];
     }
+    return p->n;
+}
+/* query-dependent scores gathered so far by the sparse / window pairs of one stream, same order as orc_get_pairs */
+int orc_get_scores(const orc_state *S, int stream, int which, double *out) {
+    const pair_list *p = which ? &S->st[stream].win : &S->st[stream].sp;
+    for (int i = 0; i < p->n; i++) out[i] = (double)p->score[i];
     return p->n;
 }
 int64_t orc_get_folded(const orc_state *S, int stream, int64_t *out, int64_t cap) {

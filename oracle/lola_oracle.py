@@ -17,11 +17,13 @@ _SRC = os.path.join(_HERE, "lola_oracle.c")
 
 PHI_SOFTMAX, PHI_EXP = 0, 1
 HIDE_STATE, HIDE_SPARSE = 1, 2   # restricted-query ablation: what the query does not read
+# what ranks the eligible pairs: self-recall error, or one of the query-dependent sums of the scoring ablation
+SCORE_SRE, SCORE_WERR_SQ, SCORE_WERR_ABS, SCORE_OVEREST, SCORE_ATTN = 0, 1, 2, 3, 4
 
 
 class _Cfg(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("B", "Hq", "Hkv", "d", "D", "eta", "lam", "C", "phi_kind")] + [
-        ("scale", C.c_double), ("hide", C.c_int32)
+        ("scale", C.c_double), ("hide", C.c_int32), ("score_kind", C.c_int32)
     ]
 
 
@@ -59,6 +61,8 @@ def _lib(real: str) -> C.CDLL:
             getattr(L, n).argtypes = [vp, vp]
         L.orc_get_pairs.restype = C.c_int
         L.orc_get_pairs.argtypes = [vp, C.c_int, C.c_int, vp, vp, vp]
+        L.orc_get_scores.restype = C.c_int
+        L.orc_get_scores.argtypes = [vp, C.c_int, C.c_int, vp]
         L.orc_get_folded.restype = i64
         L.orc_get_folded.argtypes = [vp, C.c_int, vp, i64]
         L.orc_get_n_tokens.restype = i64
@@ -102,7 +106,7 @@ def phi(W, x, kind=PHI_SOFTMAX, real="f64") -> np.ndarray:
     """phi(x) for a single vector; W is [d, D/2]."""
     W = _f32(W)
     d, m = W.shape
-    cfg = _Cfg(1, 1, 1, d, 2 * m, 0, 0, 1, kind, 0.0, 0)
+    cfg = _Cfg(1, 1, 1, d, 2 * m, 0, 0, 1, kind, 0.0, 0, 0)
     x = np.ascontiguousarray(x, dtype=np.float64)
     out = np.empty(2 * m, dtype=np.float64)
     _lib(real).orc_phi(C.byref(cfg), _ptr(W), _ptr(x), _ptr(out))
@@ -112,11 +116,12 @@ def phi(W, x, kind=PHI_SOFTMAX, real="f64") -> np.ndarray:
 class Oracle:
     """State of one LoLA layer (all sequences and kv heads) plus the two update/attend calls."""
 
-    def __init__(self, B, Hq, Hkv, d, D, eta, lam, C_, phi_kind=PHI_SOFTMAX, scale=0.0, real="f64", query_hide=0):
+    def __init__(self, B, Hq, Hkv, d, D, eta, lam, C_, phi_kind=PHI_SOFTMAX, scale=0.0, real="f64", query_hide=0,
+                 score_kind=SCORE_SRE):
         self.L = _lib(real)
         self.B, self.Hq, self.Hkv, self.d, self.D = B, Hq, Hkv, d, D
         self.eta, self.lam, self.C, self.m = eta, lam, C_, D // 2
-        self.cfg = _Cfg(B, Hq, Hkv, d, D, eta, lam, C_, phi_kind, float(scale), int(query_hide))
+        self.cfg = _Cfg(B, Hq, Hkv, d, D, eta, lam, C_, phi_kind, float(scale), int(query_hide), int(score_kind))
         self.h = self.L.orc_state_new(C.byref(self.cfg))
         if not self.h:
             raise ValueError("invalid oracle configuration")
@@ -201,6 +206,12 @@ class Oracle:
         k = np.empty((cap, self.d)); v = np.empty((cap, self.d)); idx = np.empty(cap, dtype=np.int64)
         n = self.L.orc_get_pairs(self.h, stream, which, _ptr(k), _ptr(v), _ptr(idx))
         return k[:n].copy(), v[:n].copy(), idx[:n].copy()
+
+    def scores(self, stream, which):
+        """Query-dependent scores gathered so far by the pairs of `pairs(stream, which)`, same order."""
+        out = np.empty((self.lam if which == 0 else self.eta) + 1)
+        n = self.L.orc_get_scores(self.h, stream, which, _ptr(out))
+        return out[:n].copy()
 
     def folded(self, stream):
         n = self.L.orc_get_folded(self.h, stream, None, 0)

@@ -181,6 +181,71 @@ def test_hide_matches_sum_over_the_visible_memories(hide):
 
 
 # ---------------------------------------------------------------------------------------------
+# query-dependent scores of the scoring ablation (Sec. 4 / appendix "scoring ablation"): every
+# token's score written out from the definition, the cache must hold the lambda best tokens that
+# have left the window, everything else that left must have been folded
+# ---------------------------------------------------------------------------------------------
+def brute_query_scores(kind, q, k, Wq, Wk, g, eta, n_seen):
+    """Score(k_i) = sum_{t=i}^{i+eta-1} sum_{heads of the group} term(q_t, k_i), over queries t < n_seen."""
+    B, Hq, T, d = q.shape
+    Hkv = Hq // g
+    sc = np.zeros((B, Hkv, T))
+    for b in range(B):
+        for h in range(Hkv):
+            phk = np_phi(Wk[h], k[b, h])
+            for r in range(g):
+                hq = h * g + r
+                phq = np_phi(Wq[hq], q[b, hq])
+                w = np.exp(q[b, hq].astype(np.float64) @ k[b, h].astype(np.float64).T / np.sqrt(d))   # [t, i]
+                a = phq @ phk.T
+                term = {1: (w - a) ** 2, 2: np.abs(w - a), 3: a / w, 4: w}[kind]
+                for i in range(T):
+                    hi = min(i + eta, n_seen)
+                    if hi > i:
+                        sc[b, h, i] += term[i:hi, i].sum()
+    return sc
+
+
+@pytest.mark.parametrize("kind", [1, 2, 3, 4])
+@pytest.mark.parametrize("mode", ["decode", "prefill", "mixed"])
+def test_query_dependent_scores_from_the_definition(kind, mode):
+    B, Hq, Hkv, d, D, T, eta, lam, C = 1, 4, 2, 8, 6, 45, 5, 4, 7
+    g = Hq // Hkv
+    q, k, v, Wq, Wk = rand_inputs(60 + kind, B, Hq, Hkv, d, D, T)
+    o = orc.Oracle(B, Hq, Hkv, d, D, eta, lam, C, score_kind=kind)
+    if mode == "decode":
+        run_decode(o, q, k, v, Wq, Wk, 0, T)
+    elif mode == "prefill":
+        o.prefill(q, k, v, Wq, Wk)
+    else:   # chunk boundaries that do not line up with C, then generation steps, then a chunked call again
+        o.prefill(q[:, :, :17], k[:, :, :17], v[:, :, :17], Wq, Wk)
+        run_decode(o, q, k, v, Wq, Wk, 17, 9)
+        o.prefill(q[:, :, 26:], k[:, :, 26:], v[:, :, 26:], Wq, Wk)
+    sc = brute_query_scores(kind, q, k, Wq, Wk, g, eta, T)
+    left = T - eta                                     # tokens 0 .. left-1 have left the window, their scores are final
+    for h in range(Hkv):
+        order = sorted(range(left), key=lambda i: (-sc[0, h, i], i))
+        keep = sorted(order[:lam])
+        assert [int(x) for x in o.sparse_idx[0, h] if x >= 0] == keep
+        assert sorted(o.folded(h).tolist()) == sorted(order[lam:])
+        _, _, idx = o.pairs(h, 0)
+        np.testing.assert_allclose(o.scores(h, 0), sc[0, h, idx], rtol=1e-11)
+        _, _, widx = o.pairs(h, 1)                     # window pairs: partial sums over the queries seen so far
+        np.testing.assert_allclose(o.scores(h, 1), sc[0, h, widx], rtol=1e-11)
+        # the hidden state is the sum over the folded tokens (Sec. 2.2, eq. recurrent_update)
+        ph = np_phi(Wk[h], k[0, h])
+        fl = order[lam:]
+        np.testing.assert_allclose(o.H[0, h], ph[fl].T @ v[0, h, fl].astype(np.float64), rtol=1e-10, atol=1e-12)
+
+
+def test_query_dependent_scores_need_queries():
+    o = orc.Oracle(1, 2, 1, 8, 4, 3, 2, 4, score_kind=orc.SCORE_ATTN)
+    q, k, v, Wq, Wk = rand_inputs(70, 1, 2, 1, 8, 4, 8)
+    with pytest.raises(Exception):
+        o.prefill(None, k, v, None, Wk)
+
+
+# ---------------------------------------------------------------------------------------------
 # pin 2: no window, no sparse cache -> normalised linear attention (Sec. 2.2 eq. lin_attn_forward)
 # ---------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("kind", [orc.PHI_SOFTMAX, orc.PHI_EXP])
