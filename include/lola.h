@@ -46,6 +46,15 @@ enum { LOLA_PHI_SOFTMAX = 0, LOLA_PHI_EXP = 1 };
 /* Restricted-query ablation (appendix "Sparse Cache & Linear Attention Ablation"): the memories are
  * updated as usual, but the queries do not read the hidden state and / or the sparse cache. */
 enum { LOLA_HIDE_STATE = 1, LOLA_HIDE_SPARSE = 2 };
+/* What ranks the eligible pairs.  LOLA_SCORE_SRE is the method's self-recall error (Sec. 3, eq. score).
+ * The others are the query-dependent scores of the scoring ablation (Sec. 4, appendix "scoring
+ * ablation"): Score(k_i) = sum over the eta queries t = i .. i+eta-1 that see k_i in the sliding window,
+ * and over the query heads of its group, of
+ *     (w - a)^2 | |w - a| | a / w | w,    w = exp(scale q_t.k_i), a = phi(q_t).phi(k_i).
+ * A pair's sum is final when it leaves the window and stays with it in the sparse cache; the lambda
+ * largest stay (ties: lower token index), as with the self-recall error.  These kinds run on the
+ * shape-generic kernels and need queries: an update-only lola_prefill returns LOLA_ERR_UNSUPPORTED. */
+enum { LOLA_SCORE_SRE = 0, LOLA_SCORE_WERR_SQ = 1, LOLA_SCORE_WERR_ABS = 2, LOLA_SCORE_OVEREST = 3, LOLA_SCORE_ATTN = 4 };
 
 typedef struct {
     int32_t batch, n_q_heads, n_kv_heads;
@@ -64,6 +73,7 @@ typedef struct {
                               sparse_budget 64 or 128, 4 query heads per kv head), else LOLA_ERR_UNSUPPORTED */
     int32_t query_hide;    /* 0, or LOLA_HIDE_STATE | LOLA_HIDE_SPARSE bits: terms left out of the numerator
                               and the denominator of every output (lola_prefill and lola_decode_step) */
+    int32_t score_kind;    /* LOLA_SCORE_*; anything but LOLA_SCORE_SRE excludes fold_defer */
 } lola_config;
 
 /* The memories of a layer.  H and s are always fp32 (Sec. 2.2, eq. recurrent_update). */
@@ -91,12 +101,15 @@ typedef struct {
     float *pend_phi;     /* [B, Hkv, R, D]  phi(k) of the listed pairs, fp32 */
     float *pend_v;       /* [B, Hkv, R, d]  their values, fp32 */
     int32_t *pend_count; /* [B, Hkv]        pairs listed, 0 .. R-1 */
+    /* Query-dependent scores (score_kind != LOLA_SCORE_SRE; NULL otherwise). */
+    float *win_score;    /* [B, Hkv, eta]     sum gathered so far by the pair in each ring slot */
+    float *sp_score;     /* [B, Hkv, lambda]  final sum of the pair in each sparse slot */
 } lola_state;
 
-/* Bytes of each state field in the order of the struct (host output, 12 entries; the last three
- * are 0 without deferred folds); returns their sum, or 0 if the configuration is invalid or
+/* Bytes of each state field in the order of the struct (host output, 14 entries; fields of an
+ * option that is off are 0); returns their sum, or 0 if the configuration is invalid or
  * unsupported. */
-size_t lola_state_bytes(const lola_config *cfg, size_t field_bytes[12]);
+size_t lola_state_bytes(const lola_config *cfg, size_t field_bytes[14]);
 
 /* Workspace of lola_prefill for T tokens: returns the size with which all chunks are processed in
  * one pass; *min_bytes (host, may be NULL) receives the smallest size accepted (the chunks are then

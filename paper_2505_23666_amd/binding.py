@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "liblola.so")
 LOLA_F32, LOLA_BF16 = 0, 1
 LOLA_PHI_SOFTMAX, LOLA_PHI_EXP = 0, 1
 LOLA_HIDE_STATE, LOLA_HIDE_SPARSE = 1, 2
+LOLA_SCORE_SRE, LOLA_SCORE_WERR_SQ, LOLA_SCORE_WERR_ABS, LOLA_SCORE_OVEREST, LOLA_SCORE_ATTN = 0, 1, 2, 3, 4
 EXPORTS = ("lola_state_bytes", "lola_prefill_workspace_bytes", "lola_state_init", "lola_state_flush", "lola_prefill",
            "lola_decode_step", "lola_status_str", "lola_kernel_path")
 
@@ -24,13 +25,14 @@ EXPORTS = ("lola_state_bytes", "lola_prefill_workspace_bytes", "lola_state_init"
 class LolaConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "batch", "n_q_heads", "n_kv_heads", "head_dim", "feat_dim", "window", "sparse_budget", "chunk",
-        "dtype", "out_dtype", "phi_kind")] + [("softmax_scale", C.c_float), ("fold_defer", C.c_int32), ("query_hide", C.c_int32)]
+        "dtype", "out_dtype", "phi_kind")] + [("softmax_scale", C.c_float), ("fold_defer", C.c_int32), ("query_hide", C.c_int32),
+                                        ("score_kind", C.c_int32)]
 
 
 class LolaState(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in (
         "H", "s", "win_k", "win_v", "sp_k", "sp_v", "sp_idx", "sp_count", "n_tokens",
-        "pend_phi", "pend_v", "pend_count")]
+        "pend_phi", "pend_v", "pend_count", "win_score", "sp_score")]
 
 
 class LolaError(RuntimeError):
@@ -83,7 +85,7 @@ def _stream():
 
 
 def lola_state_bytes(cfg: LolaConfig):
-    fb = (C.c_size_t * 12)()
+    fb = (C.c_size_t * 14)()
     tot = lib().lola_state_bytes(C.byref(cfg), fb)
     return int(tot), [int(x) for x in fb]
 
@@ -124,12 +126,14 @@ class LolaLayer:
     """Device buffers of one layer's memories plus the three calls, for tests and benchmarks."""
 
     def __init__(self, B, Hq, Hkv, d, D, eta, lam, C_, dtype="bf16", out_dtype="f32",
-                 phi_kind=LOLA_PHI_SOFTMAX, scale=0.0, fold_defer=0, query_hide=0, device="cuda:0"):
+                 phi_kind=LOLA_PHI_SOFTMAX, scale=0.0, fold_defer=0, query_hide=0, score_kind=0,
+                 device="cuda:0"):
         self.device = torch.device(device)
         self.dt = LOLA_BF16 if dtype == "bf16" else LOLA_F32
         self.odt = LOLA_BF16 if out_dtype == "bf16" else LOLA_F32
         self.cfg = LolaConfig(B, Hq, Hkv, d, D, eta, lam, C_, self.dt, self.odt, phi_kind, float(scale), int(fold_defer),
-                              int(query_hide))
+                              int(query_hide), int(score_kind))
+        self.score_kind = int(score_kind)
         self.fold_defer = R = int(fold_defer)
         self.B, self.Hq, self.Hkv, self.d, self.D, self.eta, self.lam, self.C = B, Hq, Hkv, d, D, eta, lam, C_
         tot, fb = lola_state_bytes(self.cfg)
@@ -148,8 +152,11 @@ class LolaLayer:
         self.pend_phi = torch.empty((B, Hkv, R, D), dtype=torch.float32, device=dev)
         self.pend_v = torch.empty((B, Hkv, R, d), dtype=torch.float32, device=dev)
         self.pend_count = torch.empty((B, Hkv) if R else (0,), dtype=torch.int32, device=dev)
+        sk = 1 if self.score_kind else 0
+        self.win_score = torch.empty((B, Hkv, eta) if sk else (0,), dtype=torch.float32, device=dev)
+        self.sp_score = torch.empty((B, Hkv, lam) if sk else (0,), dtype=torch.float32, device=dev)
         fields = [self.H, self.s, self.win_k, self.win_v, self.sp_k, self.sp_v, self.sp_idx, self.sp_count, self.n_tokens,
-                  self.pend_phi, self.pend_v, self.pend_count]
+                  self.pend_phi, self.pend_v, self.pend_count, self.win_score, self.sp_score]
         assert [t.numel() * t.element_size() for t in fields] == fb
         self.st = LolaState(*[t.data_ptr() if t.numel() else None for t in fields])
         self.workspace = None

@@ -121,6 +121,16 @@ __device__ void score_rows(const Dims &dm, const float *H, const float *s, const
     __syncthreads();
 }
 
+// One query's contribution to a key's query-dependent score (Sec. 4 / appendix "scoring ablation"): w = exp(logit),
+// a = phi(q) . phi(k); kinds 1..4: (w - a)^2, |w - a|, a / w, w.
+__device__ __forceinline__ float query_term(int kind, float logit, float a) {
+    const float w = expf(logit);
+    if (kind == 1) return (w - a) * (w - a);
+    if (kind == 2) return fabsf(w - a);
+    if (kind == 3) return a / w;
+    return w;
+}
+
 // ---------------------------------------------------------------------------------------------
 // state init
 // ---------------------------------------------------------------------------------------------
@@ -158,7 +168,13 @@ __global__ __launch_bounds__(NT) void decode_kernel(DecodeArgs<T> a) {
     float *pv = pk + d;                // [d]
     float *pw = pv + d;                // [lam + eta] softmax weights
     float *red = pw + (lam + eta);     // [NW * 3]
+    // query-dependent scores only: sums of the window pairs, logits of one query, features of a tile of window keys
+    const int sk = dm.score_kind;
+    float *wsc = red + NW * 3 + 8;     // [eta]
+    float *wlg = wsc + eta;            // [eta]
+    float *ph2 = wlg + eta;            // [R][D]
     __shared__ int sh_drop;
+    __shared__ float sh_pscore;
 
     float *H = a.st.H + (size_t)si * D * d;
     float *s = a.st.s + (size_t)si * D;
@@ -173,6 +189,13 @@ __global__ __launch_bounds__(NT) void decode_kernel(DecodeArgs<T> a) {
     const int slot = eta > 0 ? (int)(tok % eta) : 0;
     const int32_t pidx = (int32_t)(tok - eta);
     int spc = a.st.sp_count[si];
+    float *win_score = sk ? a.st.win_score + (size_t)si * eta : nullptr;
+    float *sp_score = sk ? a.st.sp_score + (size_t)si * lam : nullptr;
+    if (sk) {
+        // the leaving pair's sum is final; the new pair starts at zero in the same ring slot
+        if (tid == 0) sh_pscore = (popped && eta > 0) ? win_score[slot] : 0.f;
+        for (int i = tid; i < eta; i += NT) wsc[i] = i == slot ? 0.f : win_score[i];
+    }
 
     // 1. the new pair enters the window (ring slot tok % eta); the pair it displaces leaves
     if (popped) {
@@ -196,12 +219,16 @@ __global__ __launch_bounds__(NT) void decode_kernel(DecodeArgs<T> a) {
                 stf(sp_k, (size_t)spc * d + i, pk[i]);
                 stf(sp_v, (size_t)spc * d + i, pv[i]);
             }
-            if (tid == 0) { sp_idx[spc] = pidx; a.st.sp_count[si] = spc + 1; }
+            if (tid == 0) { sp_idx[spc] = pidx; a.st.sp_count[si] = spc + 1; if (sk) sp_score[spc] = sh_pscore; }
             spc += 1;
         } else {
             int drop = 0;   // candidate index: < lam a sparse slot, == lam the leaving pair
             if (lam > 0) {
-                for (int t0 = 0; t0 <= lam; t0 += R) {
+                if (sk) {
+                    for (int e = tid; e <= lam; e += NT) score[e] = e < lam ? sp_score[e] : sh_pscore;
+                    __syncthreads();
+                }
+                for (int t0 = 0; t0 <= lam && !sk; t0 += R) {
                     int nr = min(R, lam + 1 - t0);
                     for (int p = tid; p < nr * d; p += NT) {
                         int r = p / d, i = p - r * d, e = t0 + r;
@@ -246,7 +273,7 @@ __global__ __launch_bounds__(NT) void decode_kernel(DecodeArgs<T> a) {
                     stf(sp_k, (size_t)drop * d + i, pk[i]);
                     stf(sp_v, (size_t)drop * d + i, pv[i]);
                 }
-                if (tid == 0) sp_idx[drop] = pidx;
+                if (tid == 0) { sp_idx[drop] = pidx; if (sk) sp_score[drop] = sh_pscore; }
             }
         }
     }
@@ -268,6 +295,7 @@ __global__ __launch_bounds__(NT) void decode_kernel(DecodeArgs<T> a) {
             float dot = 0.f;
             for (int j = 0; j < d; j++) dot = fmaf(xs[j], ldf(kr, j), dot);
             dot *= dm.scale;
+            if (i >= spc && sk) wlg[i - spc] = dot;
             if (i < spc && (dm.hide & 2)) dot = -INFINITY;   // restricted query: the sparse cache is not read
             pw[i] = dot;
             lmax = fmaxf(lmax, dot);
@@ -301,7 +329,25 @@ __global__ __launch_bounds__(NT) void decode_kernel(DecodeArgs<T> a) {
             stf(out, ((size_t)b * dm.Hq + hq) * d + tid, t / (psum + elin * lden));
         }
         __syncthreads();
+        if (sk) {
+            // this query's term for every pair in the window (ring slot order), a tile of R keys at a time; one
+            // wavefront per key sums phi(q) . phi(k)
+            for (int t0 = 0; t0 < wn; t0 += R) {
+                const int nr = min(R, wn - t0);
+                for (int p = tid; p < nr * d; p += NT) vs[p] = ldf(win_k, (size_t)t0 * d + p);
+                __syncthreads();
+                phi_rows(dm, Wk, vs, ph2, nr);
+                for (int rr = tid / WAVE; rr < nr; rr += NW) {
+                    float av = 0.f;
+                    for (int f = tid % WAVE; f < D; f += WAVE) av = fmaf(ph[f], ph2[rr * D + f], av);
+                    av = wave_sum(av);
+                    if (tid % WAVE == 0) wsc[t0 + rr] += query_term(sk, wlg[t0 + rr], av);
+                }
+                __syncthreads();
+            }
+        }
     }
+    if (sk) for (int i = tid; i < wn; i += NT) win_score[i] = wsc[i];
     if (tid == 0) a.st.n_tokens[si] = tok + 1;
 }
 
@@ -336,6 +382,8 @@ struct PrefillArgs {
     int scan_mode;            // scan_kernel: 0 all chunks of the pass; 1 stop at the first regular chunk (a full chunk with a full
                               // window behind it and a full cache: the MFMA kernel's case) and note it in next_j; 2 continue from next_j
     int32_t *next_j;          // [B*Hkv] hand-over of the chunk position between the kernels of a pass
+    float *tok_score;         // [B*Hkv][eta + T] query-dependent scores: entry window (virtual rows lam ..), then the call's tokens
+    int R2;                   // keys / queries per tile of band_score_kernel
 };
 
 template <typename T>
@@ -373,8 +421,80 @@ __global__ __launch_bounds__(NT) void finalize_kernel(PrefillArgs<T> a) {
         win_k[(size_t)slot * d + c] = k[(size_t)i * d + c];
         win_v[(size_t)slot * d + c] = v[(size_t)i * d + c];
     }
+    if (dm.score_kind) {
+        // the sums of the pairs that end in the window (some may have been there before the call) go back to their ring slots
+        float *win_score = a.st.win_score + (size_t)si * eta;
+        const float *ts = a.tok_score + (size_t)si * (eta + Tn);
+        const int64_t t_lo = max((int64_t)0, a0 + Tn - eta);
+        for (int64_t t = t_lo + tid; t < a0 + Tn; t += NT) win_score[t % eta] = ts[eta + (t - a0)];
+    }
     __syncthreads();
     if (tid == 0) a.st.n_tokens[si] = a0 + Tn;
+}
+
+// Query-dependent scores of a prefill call (Sec. 4 / appendix "scoring ablation"): row x of tok_score belongs to token
+// a0 - eta + x (x < eta: the entry window, x >= eta: the call's tokens) and receives what the pair had gathered before
+// the call plus the terms of the call's queries i (token a0 + i) with x - eta <= i <= x - 1, i.e. the queries that see
+// the key inside the sliding-window band, over all query heads of the group.  Chunk-parallel: grid (key tile, stream).
+// One wavefront owns a key and adds its terms in a fixed order (results do not depend on timing).
+template <typename T>
+__global__ __launch_bounds__(NT) void band_score_kernel(PrefillArgs<T> a) {
+    extern __shared__ float smem[];
+    const Dims &dm = a.dm;
+    const int tid = threadIdx.x, d = dm.d, D = dm.D, m = dm.m, eta = dm.eta, lam = dm.lam, R = a.R2;
+    const int si = blockIdx.y, b = si / dm.Hkv, h = si % dm.Hkv, x0 = blockIdx.x * R;
+    const int Tn = a.T_tokens, nrows = eta + Tn, P = lam + eta;
+    const int nk = min(R, nrows - x0);
+    float *ks = smem;               // [R][d]
+    float *phk = ks + R * d;        // [R][D]
+    float *qs = phk + R * D;        // [R][d]
+    float *phq = qs + R * d;        // [R][D]
+    float *acc = phq + R * D;       // [R]
+    const int64_t a0 = a.st.n_tokens[si];
+    const T *pK = a.prefK + (size_t)si * P * d;
+    const T *kc = a.k + (size_t)si * Tn * d;
+    const float *win_score = a.st.win_score + (size_t)si * eta;
+    for (int p = tid; p < nk * d; p += NT) {
+        const int r = p / d, c = p - r * d, x = x0 + r;
+        const bool valid = a0 - eta + x >= 0;
+        ks[p] = !valid ? 0.f : (x < eta ? ldf(pK, (size_t)(lam + x) * d + c) : ldf(kc, (size_t)(x - eta) * d + c));
+    }
+    for (int r = tid; r < nk; r += NT) {
+        const int x = x0 + r;
+        const int64_t t = a0 - eta + x;
+        acc[r] = (x < eta && t >= 0) ? win_score[t % eta] : 0.f;
+    }
+    __syncthreads();
+    phi_rows(dm, a.Wk + (size_t)h * d * m, ks, phk, nk);
+    const int i_lo = max(0, x0 - eta), i_hi = min(Tn - 1, x0 + nk - 2);   // queries that see some key of the tile
+    const int w = tid / WAVE, lane = tid % WAVE;
+    for (int r = 0; r < dm.g; r++) {
+        const int hq = h * dm.g + r;
+        const T *qh = a.q + ((size_t)b * dm.Hq + hq) * Tn * d;
+        for (int i0 = i_lo; i0 <= i_hi; i0 += R) {
+            const int nq = min(R, i_hi + 1 - i0);
+            for (int p = tid; p < nq * d; p += NT) qs[p] = ldf(qh, (size_t)i0 * d + p);
+            __syncthreads();
+            phi_rows(dm, a.Wq + (size_t)hq * d * m, qs, phq, nq);
+            for (int kr = w; kr < nk; kr += NW) {
+                const int x = x0 + kr;
+                if (a0 - eta + x < 0) continue;
+                float sum = 0.f;
+                for (int ql = 0; ql < nq; ql++) {
+                    const int i = i0 + ql;
+                    if (i < x - eta || i > x - 1) continue;
+                    float dot = 0.f, av = 0.f;
+                    for (int c = lane; c < d; c += WAVE) dot = fmaf(qs[ql * d + c], ks[kr * d + c], dot);
+                    for (int f = lane; f < D; f += WAVE) av = fmaf(phq[ql * D + f], phk[kr * D + f], av);
+                    dot = wave_sum(dot); av = wave_sum(av);
+                    sum += query_term(dm.score_kind, dot * dm.scale, av);
+                }
+                if (lane == 0) acc[kr] += sum;
+            }
+            __syncthreads();
+        }
+    }
+    for (int r = tid; r < nk; r += NT) a.tok_score[(size_t)si * nrows + x0 + r] = acc[r];
 }
 
 // One chunk of the sequential evolution of a stream's memories, all state in global memory (H^T, s, cache) except the
@@ -408,6 +528,9 @@ __device__ void scan_chunk(const PrefillArgs<T> &a, const int si, const int j, i
     const T *pK = a.prefK + (size_t)si * P * d, *pV = a.prefV + (size_t)si * P * d;
     const T *kc = a.k + (size_t)si * a.T_tokens * d, *vc = a.v + (size_t)si * a.T_tokens * d;
     const int64_t a0 = a.st.n_tokens[si];
+    const int sk = dm.score_kind;
+    float *sp_score = sk ? a.st.sp_score + (size_t)si * lam : nullptr;
+    const float *tsc = sk ? a.tok_score + (size_t)si * (eta + a.T_tokens) : nullptr;
 
     {
 
@@ -458,7 +581,10 @@ __device__ void scan_chunk(const PrefillArgs<T> &a, const int si, const int j, i
                 sp_k[(size_t)(spc + e) * d + i] = ksrc[i];
                 sp_v[(size_t)(spc + e) * d + i] = vsrc[i];
             }
-            for (int e = tid; e < n_ev; e += NT) { sp_idx[spc + e] = (int32_t)(lo + e); sp_row[spc + e] = vrow0 + e; }
+            for (int e = tid; e < n_ev; e += NT) {
+                sp_idx[spc + e] = (int32_t)(lo + e); sp_row[spc + e] = vrow0 + e;
+                if (sk) sp_score[spc + e] = tsc[vrow0 + e - lam];
+            }
             spc += n_ev;
             __syncthreads();
         } else if (n_ev > 0) {
@@ -479,8 +605,10 @@ __device__ void scan_chunk(const PrefillArgs<T> &a, const int si, const int j, i
                 __syncthreads();
                 phi_rows(dm, Wk, xs, ph, nr);
                 for (int p = tid; p < nr * D; p += NT) phiE[(size_t)t0 * D + p] = ph[p];
-                score_rows(dm, H, s, ph, vs, err, den, score + t0, nr);
+                if (!sk) score_rows(dm, H, s, ph, vs, err, den, score + t0, nr);
+                else __syncthreads();
             }
+            if (sk) for (int e = tid; e < nE; e += NT) score[e] = e < spc ? sp_score[e] : tsc[vrow0 + (e - spc) - lam];
             for (int e = tid; e < nE; e += NT) cidx[e] = e < spc ? sp_idx[e] : (int)(lo + (e - spc));
             __syncthreads();
             // rank by (score descending, token index ascending); the first lam stay
@@ -535,6 +663,7 @@ __device__ void scan_chunk(const PrefillArgs<T> &a, const int si, const int j, i
             for (int x = tid; x < ne; x += NT) {
                 sp_idx[eslot[x]] = cidx[ecand[x]];
                 sp_row[eslot[x]] = vrow0 + (ecand[x] - spc);
+                if (sk) sp_score[eslot[x]] = score[ecand[x]];
             }
             spc = lam;
             __syncthreads();

@@ -34,7 +34,8 @@ constexpr int DEFER_R = 8;   // pairs a stream may list before the generation st
 // The fused MFMA generation step covers the Llama-8B head shape with bf16 storage.
 bool fast_decode_ok(const lola_config *c) {
     return c->dtype == LOLA_BF16 && c->head_dim == 128 && c->feat_dim == 128 && c->window == 64 &&
-           (c->sparse_budget == 128 || c->sparse_budget == 64) && c->n_q_heads / c->n_kv_heads == 4;
+           (c->sparse_budget == 128 || c->sparse_budget == 64) && c->n_q_heads / c->n_kv_heads == 4 &&
+           c->score_kind == LOLA_SCORE_SRE;
 }
 
 lola_status check_config(const lola_config *c) {
@@ -50,6 +51,7 @@ lola_status check_config(const lola_config *c) {
     if (c->window > 4096 || c->sparse_budget > 4096 || c->chunk > 1024) return LOLA_ERR_SHAPE;
     if ((long long)c->batch * c->n_kv_heads > (1ll << 24)) return LOLA_ERR_SHAPE;
     if (c->query_hide < 0 || c->query_hide > 3) return LOLA_ERR_SHAPE;
+    if (c->score_kind < LOLA_SCORE_SRE || c->score_kind > LOLA_SCORE_ATTN) return LOLA_ERR_DTYPE;
     if (c->fold_defer != 0 && c->fold_defer != DEFER_R) return LOLA_ERR_SHAPE;
     if (c->fold_defer != 0 && !fast_decode_ok(c)) return LOLA_ERR_UNSUPPORTED;
     return LOLA_OK;
@@ -63,6 +65,7 @@ Dims make_dims(const lola_config *c) {
     dm.phi_kind = c->phi_kind;
     dm.scale = c->softmax_scale > 0.f ? c->softmax_scale : 1.0f / sqrtf((float)c->head_dim);
     dm.hide = c->query_hide;
+    dm.score_kind = c->score_kind;
     return dm;
 }
 
@@ -75,6 +78,10 @@ lola_status check_state(const lola_config *c, const lola_state *st) {
     if (c->fold_defer) {
         if (!st->pend_phi || !st->pend_v || !st->pend_count) return LOLA_ERR_NULL;
         if (misaligned(st->pend_phi) || misaligned(st->pend_v) || misaligned(st->pend_count)) return LOLA_ERR_ALIGN;
+    }
+    if (c->score_kind != LOLA_SCORE_SRE) {
+        if ((c->window > 0 && !st->win_score) || (c->sparse_budget > 0 && !st->sp_score)) return LOLA_ERR_NULL;
+        if (misaligned(st->win_score) || misaligned(st->sp_score)) return LOLA_ERR_ALIGN;
     }
     return LOLA_OK;
 }
@@ -116,12 +123,13 @@ State<T> make_state(const lola_state *st) {
     s.H = st->H; s.s = st->s;
     s.win_k = (T *)st->win_k; s.win_v = (T *)st->win_v; s.sp_k = (T *)st->sp_k; s.sp_v = (T *)st->sp_v;
     s.sp_idx = st->sp_idx; s.sp_count = st->sp_count; s.n_tokens = st->n_tokens;
+    s.win_score = st->win_score; s.sp_score = st->sp_score;
     return s;
 }
 
 // rows per scoring tile of the generic kernels: as many as fit next to `fixed_floats` in LDS
-int score_tile_rows(const Dims &dm, size_t fixed_floats) {
-    size_t per_row = (size_t)(3 * dm.d + dm.D + 1);
+int score_tile_rows(const Dims &dm, size_t fixed_floats, bool with_key_features = false) {
+    size_t per_row = (size_t)(3 * dm.d + dm.D + 1) + (with_key_features ? dm.D : 0);
     size_t avail = LDS_LIMIT / 4;
     int rmin = generic::NT / dm.d > 1 ? generic::NT / dm.d : 1;
     if (avail < fixed_floats + per_row * rmin) return 0;
@@ -129,7 +137,14 @@ int score_tile_rows(const Dims &dm, size_t fixed_floats) {
     if (r > 32) r = 32;
     return (int)r < rmin ? 0 : (int)r;
 }
-size_t decode_fixed_floats(const Dims &dm) { return (size_t)(dm.lam + 1) + 2 * dm.d + (dm.lam + dm.eta) + 3 * generic::NW + 8; }
+size_t decode_fixed_floats(const Dims &dm) {
+    return (size_t)(dm.lam + 1) + 2 * dm.d + (dm.lam + dm.eta) + 3 * generic::NW + 8 + (dm.score_kind ? 2 * dm.eta : 0);
+}
+// keys (= queries) per tile of the query-dependent score kernel of the prefill
+int band_tile_rows(const Dims &dm) {
+    size_t r = (LDS_LIMIT / 4) / (size_t)(2 * (dm.d + dm.D) + 1);
+    return (int)(r > 16 ? 16 : r);
+}
 size_t scan_fixed_floats(const Dims &dm) { return (size_t)4 * (dm.lam + dm.C) + 2 * dm.C + 8; }
 int attend_tile_queries(const Dims &dm) {
     size_t per_q = (size_t)dm.d + dm.D + (dm.lam + dm.eta + dm.C) + 3;
@@ -145,16 +160,16 @@ int attend_tile_queries(const Dims &dm) {
 bool fast_attend_ok(const lola_config *c) {
     return c->dtype == LOLA_BF16 && (c->head_dim == 128 || c->head_dim == 64) && c->feat_dim == 128 && c->window == 64 && c->chunk == 64 &&
            (c->sparse_budget == 64 || c->sparse_budget == 128 || c->sparse_budget == 256) &&
-           c->n_q_heads / c->n_kv_heads == 4;
+           c->n_q_heads / c->n_kv_heads == 4 && c->score_kind == LOLA_SCORE_SRE;
 }
 
 struct PrefillPlan {
-    size_t off_prefK, off_prefV, off_sp_row, off_phiE, off_next, off_snap;   // byte offsets
+    size_t off_prefK, off_prefV, off_sp_row, off_phiE, off_next, off_score, off_snap;   // byte offsets
     size_t snap_bytes_per_chunk;                                    // all streams, one chunk (snapshots + phi of its keys)
     size_t phik_bytes_per_chunk;
     size_t fixed_bytes;
 };
-PrefillPlan plan_prefill(const lola_config *c, int with_outputs) {
+PrefillPlan plan_prefill(const lola_config *c, int with_outputs, size_t Tn) {
     const size_t ns = (size_t)c->batch * c->n_kv_heads, es = esize(c->dtype);
     const size_t P = (size_t)c->sparse_budget + c->window, d = c->head_dim, D = c->feat_dim, lam = c->sparse_budget;
     PrefillPlan p;
@@ -164,6 +179,7 @@ PrefillPlan plan_prefill(const lola_config *c, int with_outputs) {
     p.off_sp_row = off; off += up(ns * lam * 4);
     p.off_phiE = off; off += up(ns * (lam + c->chunk) * D * 4);
     p.off_next = off; off += up(ns * 4);
+    p.off_score = off; if (c->score_kind != LOLA_SCORE_SRE) off += up(ns * ((size_t)c->window + Tn) * 4);
     p.off_snap = off;
     p.fixed_bytes = off;
     p.snap_bytes_per_chunk = with_outputs ? up(ns * D * d * 4) + up(ns * D * 4) + up(ns * (lam ? lam : 1) * 4) : 0;
@@ -213,9 +229,10 @@ lola_status run_decode(const lola_config *c, const lola_state *st, const void *q
     a.q = (const T *)q; a.k = (const T *)k; a.v = (const T *)v; a.Wq = (const T *)Wq; a.Wk = (const T *)Wk;
     a.out = out;
     const size_t fixed = decode_fixed_floats(a.dm);
-    a.R = score_tile_rows(a.dm, fixed);
+    const bool sk = a.dm.score_kind != 0;
+    a.R = score_tile_rows(a.dm, fixed, sk);
     if (a.R <= 0) return LOLA_ERR_UNSUPPORTED;
-    const size_t lds = 4 * (fixed + (size_t)a.R * (3 * a.dm.d + a.dm.D + 1));
+    const size_t lds = 4 * (fixed + (size_t)a.R * (3 * a.dm.d + a.dm.D + 1 + (sk ? a.dm.D : 0)));
     dim3 grid(a.dm.B * a.dm.Hkv), block(generic::NT);
     if (c->out_dtype == LOLA_F32) hipLaunchKernelGGL((generic::decode_kernel<T, float>), grid, block, lds, stream, a);
     else hipLaunchKernelGGL((generic::decode_kernel<T, bf16_t>), grid, block, lds, stream, a);
@@ -236,8 +253,10 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
     a.n_chunks = (Tn + a.dm.C - 1) / a.dm.C;
     a.want_out = q != nullptr;
     a.sel_trace = sel_trace;
-    const PrefillPlan p = plan_prefill(c, a.want_out);
+    const PrefillPlan p = plan_prefill(c, a.want_out, (size_t)Tn);
     char *ws = (char *)workspace;
+    a.tok_score = (float *)(ws + p.off_score);
+    a.R2 = band_tile_rows(a.dm);
     a.prefK = (T *)(ws + p.off_prefK); a.prefV = (T *)(ws + p.off_prefV);
     a.sp_row = (int32_t *)(ws + p.off_sp_row);
     a.phiE = (float *)(ws + p.off_phiE);
@@ -274,6 +293,13 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
 
     hipLaunchKernelGGL((generic::prefix_kernel<T>), gs, block, 0, stream, a);
     LAUNCH_CHECK();
+    if (a.dm.score_kind) {   // the query-dependent scores of every pair the call touches, before the state evolves
+        if (a.R2 <= 0) return LOLA_ERR_UNSUPPORTED;
+        const size_t lds_band = 4 * ((size_t)a.R2 * (2 * (d + D) + 1));
+        const dim3 gb((unsigned)(((size_t)a.dm.eta + Tn + a.R2 - 1) / a.R2), (unsigned)ns);
+        hipLaunchKernelGGL((generic::band_score_kernel<T>), gb, block, lds_band, stream, a);
+        LAUNCH_CHECK();
+    }
     for (int j0 = 0; j0 < a.n_chunks; j0 += S) {
         a.j0 = j0;
         a.j1 = j0 + S < a.n_chunks ? j0 + S : a.n_chunks;
@@ -335,21 +361,23 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
 
 extern "C" {
 
-size_t lola_state_bytes(const lola_config *c, size_t fb[12]) {
+size_t lola_state_bytes(const lola_config *c, size_t fb[14]) {
     if (check_config(c) != LOLA_OK) return 0;
     const size_t ns = (size_t)c->batch * c->n_kv_heads, es = esize(c->dtype);
     const size_t d = c->head_dim, D = c->feat_dim, eta = c->window, lam = c->sparse_budget, R = c->fold_defer;
-    size_t f[12] = {ns * D * d * 4, ns * D * 4, ns * eta * d * es, ns * eta * d * es, ns * lam * d * es,
+    const size_t sk = c->score_kind != LOLA_SCORE_SRE ? 1 : 0;
+    size_t f[14] = {ns * D * d * 4, ns * D * 4, ns * eta * d * es, ns * eta * d * es, ns * lam * d * es,
                     ns * lam * d * es, ns * lam * 4, ns * 4, ns * 8,
-                    ns * R * D * 4, ns * R * d * 4, R ? ns * 4 : 0};
+                    ns * R * D * 4, ns * R * d * 4, R ? ns * 4 : 0,
+                    sk * ns * eta * 4, sk * ns * lam * 4};
     size_t tot = 0;
-    for (int i = 0; i < 12; i++) { if (fb) fb[i] = f[i]; tot += f[i]; }
+    for (int i = 0; i < 14; i++) { if (fb) fb[i] = f[i]; tot += f[i]; }
     return tot;
 }
 
 size_t lola_prefill_workspace_bytes(const lola_config *c, int32_t T, int32_t with_outputs, size_t *min_bytes) {
     if (check_config(c) != LOLA_OK || T < 0) return 0;
-    const PrefillPlan p = plan_prefill(c, with_outputs);
+    const PrefillPlan p = plan_prefill(c, with_outputs, (size_t)T);
     size_t nch = ((size_t)T + c->chunk - 1) / c->chunk;
     if (nch < 1) nch = 1;
     if (min_bytes) *min_bytes = p.fixed_bytes + p.snap_bytes_per_chunk;
@@ -364,12 +392,13 @@ lola_status lola_state_init(const lola_config *c, const lola_state *st, void *st
     if (rc != LOLA_OK) return rc;
     rc = check_state(c, st);
     if (rc != LOLA_OK) return rc;
-    size_t fb[12];
+    size_t fb[14];
     lola_state_bytes(c, fb);
-    void *ptrs[12] = {st->H, st->s, st->win_k, st->win_v, st->sp_k, st->sp_v, st->sp_idx, st->sp_count, st->n_tokens,
+    const bool sk = c->score_kind != LOLA_SCORE_SRE;
+    void *ptrs[14] = {st->H, st->s, st->win_k, st->win_v, st->sp_k, st->sp_v, st->sp_idx, st->sp_count, st->n_tokens,
                       c->fold_defer ? st->pend_phi : nullptr, c->fold_defer ? st->pend_v : nullptr,
-                      c->fold_defer ? st->pend_count : nullptr};
-    for (int i = 0; i < 12; i++) {
+                      c->fold_defer ? st->pend_count : nullptr, sk ? st->win_score : nullptr, sk ? st->sp_score : nullptr};
+    for (int i = 0; i < 14; i++) {
         if (!ptrs[i] || fb[i] == 0) continue;
         size_t n = fb[i] / 4;   // every field is a multiple of 4 bytes (head_dim is even)
         unsigned blocks = (unsigned)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
@@ -399,6 +428,7 @@ lola_status lola_prefill(const lola_config *c, const lola_state *st, const void 
     if (T == 0) return LOLA_OK;   // nothing to read or write: the token pointers are not looked at
     if ((q == nullptr) != (out == nullptr)) return LOLA_ERR_NULL;
     if (!k || !v || !Wk || (q && !Wq)) return LOLA_ERR_NULL;
+    if (!q && c->score_kind != LOLA_SCORE_SRE) return LOLA_ERR_UNSUPPORTED;   // these scores are sums over queries
     const void *ps[] = {q, k, v, Wq, Wk, out, sel_trace, workspace};
     for (const void *p : ps) if (p && misaligned(p)) return LOLA_ERR_ALIGN;
     size_t need_min = 0;

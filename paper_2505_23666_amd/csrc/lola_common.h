@@ -17,6 +17,7 @@ struct Dims {
     int phi_kind;           // 0 softmax kind, 1 exponential kind
     float scale;            // logit scale
     int hide;               // bit 0: queries do not read (H, s); bit 1: queries do not read the sparse cache
+    int score_kind;         // 0 self-recall error; 1..4 the query-dependent scores of the scoring ablation
 };
 
 // Device pointers of the memories (layout documented in include/lola.h).
@@ -26,6 +27,7 @@ struct State {
     T *win_k, *win_v, *sp_k, *sp_v;
     int32_t *sp_idx, *sp_count;
     int64_t *n_tokens;
+    float *win_score, *sp_score;   // query-dependent scores only: per ring slot / per sparse slot
 };
 
 __device__ __forceinline__ float ldf(const float *p, size_t i) { return p[i]; }

@@ -39,11 +39,16 @@ def test_state_bytes(L):
     tot, fb = lb.lola_state_bytes(cfg())
     ns = 4
     assert fb == [ns * 128 * 128 * 4, ns * 128 * 4, ns * 64 * 128 * 2, ns * 64 * 128 * 2, ns * 128 * 128 * 2,
-                  ns * 128 * 128 * 2, ns * 128 * 4, ns * 4, ns * 8, 0, 0, 0]
+                  ns * 128 * 128 * 2, ns * 128 * 4, ns * 4, ns * 8, 0, 0, 0, 0, 0]
     assert tot == sum(fb)
     # deferred folds: a list of 8 (phi, v) rows in fp32 and its length per stream
     tot8, fb8 = lb.lola_state_bytes(cfg(fold_defer=8))
-    assert fb8[:9] == fb[:9] and fb8[9:] == [ns * 8 * 128 * 4, ns * 8 * 128 * 4, ns * 4] and tot8 == sum(fb8)
+    assert fb8[:9] == fb[:9] and fb8[9:] == [ns * 8 * 128 * 4, ns * 8 * 128 * 4, ns * 4, 0, 0] and tot8 == sum(fb8)
+    # query-dependent scores: one sum per ring slot and per sparse slot; they exclude deferred folds
+    tots, fbs = lb.lola_state_bytes(cfg(score_kind=lb.LOLA_SCORE_ATTN))
+    assert fbs[:12] == fb[:12] and fbs[12:] == [ns * 64 * 4, ns * 128 * 4] and tots == sum(fbs)
+    assert lb.lola_state_bytes(cfg(score_kind=2, fold_defer=8))[0] == 0
+    assert lb.lola_state_bytes(cfg(score_kind=5))[0] == 0
     assert lb.lola_state_bytes(cfg(fold_defer=3))[0] == 0                 # not a supported list length
     assert lb.lola_state_bytes(cfg(fold_defer=8, head_dim=64))[0] == 0    # no kernel with deferred folds for this shape
     assert lb.lola_state_bytes(cfg(head_dim=100))[0] == 0
@@ -75,8 +80,8 @@ def test_arguments_rejected_before_launch(L):
     """Every call below must return an error from host-side validation (no GPU is present here)."""
     c = cfg()
     fake = 0x1000  # aligned, never dereferenced on the host
-    st = lb.LolaState(*([fake] * 9 + [None] * 3))
-    bad_st = lb.LolaState(*([fake] * 8 + [None] * 4))
+    st = lb.LolaState(*([fake] * 9 + [None] * 5))
+    bad_st = lb.LolaState(*([fake] * 8 + [None] * 6))
     f = lambda *a: L.lola_decode_step(*a)
     vp = C.c_void_p
     assert f(C.byref(c), C.byref(bad_st), vp(fake), vp(fake), vp(fake), vp(fake), vp(fake), vp(fake), None) == -1
@@ -99,4 +104,9 @@ def test_arguments_rejected_before_launch(L):
     assert L.lola_state_flush(C.byref(c8), C.byref(st), None) == -1
     assert L.lola_state_flush(C.byref(cfg(fold_defer=8, sparse_budget=256)), C.byref(st), None) == -5
     assert L.lola_state_flush(C.byref(cfg(fold_defer=5)), C.byref(st), None) == -2
+    cs = cfg(score_kind=lb.LOLA_SCORE_WERR_SQ)
+    assert f(C.byref(cs), C.byref(st), vp(fake), vp(fake), vp(fake), vp(fake), vp(fake), vp(fake), None) == -1   # score fields missing
+    sts = lb.LolaState(*([fake] * 9 + [None] * 3 + [fake] * 2))
+    assert p(cs, sts, None, vp(fake), None, 64, vp(fake), 1 << 40) == -5    # update-only call: these scores need queries
+    assert lb.lola_kernel_path(cs, 0) == "generic" and lb.lola_kernel_path(cs, 1) == "generic"
     assert f(C.byref(cfg(query_hide=4)), C.byref(st), vp(fake), vp(fake), vp(fake), vp(fake), vp(fake), vp(fake), None) == -2

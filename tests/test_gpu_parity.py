@@ -192,6 +192,48 @@ def test_restricted_query_mfma_kernels(hide, defer):
     assert rep2["scored"] - rep["scored"] == 8 * 20
 
 
+@pytest.mark.parametrize("kind", [1, 2, 3, 4])
+def test_query_dependent_scores(kind):
+    """The importance scores of the scoring ablation instead of the self-recall error: sums over the
+    queries that see a key inside the sliding window, gathered by the generation step and by the
+    prefill (ragged calls that resume mid-chunk, several workspace passes), cache decided by them."""
+    sh = wl.Shape("qscore", "bf16", 2, 4, 2, 64, 32, T=0, eta=12, lam=9, C=16, seed=0)
+    q, k, v, Wq, Wk = rand_case(90 + kind, 2, 4, 2, 64, 32, 16 * 9 + 5 + 30, "bf16")
+    kw = dict(score_kind=kind)
+    cuts = [0, 7, 16 * 4 + 3, 16 * 9 + 5]
+    layer, o = None, None
+    for i in range(3):
+        a, b = cuts[i], cuts[i + 1]
+        layer, o, rep = P.prefill_parity(sh, q[:, :, a:b], k[:, :, a:b], v[:, :, a:b], Wq, Wk, layer=layer, oracle=o,
+                                         workspace_limit=0 if i == 2 else None, layer_kw=kw)
+        say("query-dependent scores, prefill part", kind, i, rep)
+    assert layer.lola_path == ("generic", "generic")
+    rep = P.decode_parity(sh, layer, o, *steps(q, k, v, cuts[3], 18), Wq, Wk)
+    a = cuts[3] + 18
+    layer, o, rep2 = P.prefill_parity(sh, q[:, :, a:a + 12], k[:, :, a:a + 12], v[:, :, a:a + 12], Wq, Wk, layer=layer, oracle=o,
+                                      layer_kw=kw)
+    say("query-dependent scores, decode + short prefill", kind, rep, rep2)
+    assert rep2["scored"] > 40
+
+
+def test_query_dependent_scores_fp32_cold_decode_and_8b_shape():
+    """fp32 storage from an empty state through warm-up; and the 8B head shape (generic kernels there)."""
+    sh = wl.Shape("qscore32", "f32", 1, 2, 1, 32, 16, T=0, eta=5, lam=4, C=4, seed=0)
+    q, k, v, Wq, Wk = rand_case(95, 1, 2, 1, 32, 16, 40, "f32")
+    kw = dict(score_kind=3)
+    layer, o = P.make_layer(sh, **kw), P.make_oracle(sh, **kw)
+    rep = P.decode_parity(sh, layer, o, *steps(q, k, v, 0, 40), Wq, Wk)
+    say("query-dependent scores, fp32 cold decode", rep)
+    sh = wl.scaled(3, B=1, T=64 * 4 + 9 + 6, lam=64)
+    Wq, Wk = wl.weights(sh)
+    q, k, v, _ = wl.sequence_inputs(sh)
+    kw = dict(score_kind=1)
+    T = 64 * 4 + 9
+    layer, o, rep = P.prefill_parity(sh, q[:, :, :T], k[:, :, :T], v[:, :, :T], Wq, Wk, layer_kw=kw)
+    rep2 = P.decode_parity(sh, layer, o, *steps(q, k, v, T, 6), Wq, Wk)
+    say("query-dependent scores, 8B head shape", rep, rep2)
+
+
 def test_exp_feature_map():
     sh = wl.Shape("expphi", "f32", 1, 2, 1, 32, 16, T=64, eta=8, lam=6, C=8, seed=0)
     q, k, v, Wq, Wk = rand_case(8, 1, 2, 1, 32, 16, 70, "f32", wscale=0.5)
