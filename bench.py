@@ -60,6 +60,67 @@ def prefill_alg_flops(sh):
     return per_chunk, per_chunk * (sh.T // C_) * sh.B * sh.Hkv
 
 
+def extras(torch, wl, lb, dev):
+    """Side measurements: one prefill call with outputs and a run of generation steps per mode, bf16, seeded N(0,1)
+    inputs; tokens/s per layer from HIP events.  Not the headline metric: context for the rows built beside it."""
+    def to_dev(x):
+        return torch.from_numpy(wl.bf16_bits(x).view(np.int16)).to(dev).view(torch.bfloat16)
+
+    def run(label, B, Hq, Hkv, d, D, eta, lam, Cc, T, n_dec, **kw):
+        g = wl.rng(11, 3)
+        mk = lambda *shape: to_dev(wl.store(g.standard_normal(shape, dtype=np.float32), "bf16"))
+        q, k, v = mk(B, Hq, T, d), mk(B, Hkv, T, d), mk(B, Hkv, T, d)
+        Wq = to_dev(wl.store((g.standard_normal((Hq, D // 2, d), dtype=np.float32) / np.sqrt(d)).astype(np.float32), "bf16"))
+        Wk = to_dev(wl.store((g.standard_normal((Hkv, D // 2, d), dtype=np.float32) / np.sqrt(d)).astype(np.float32), "bf16"))
+        qd, kd, vd = mk(n_dec, B, Hq, d), mk(n_dec, B, Hkv, d), mk(n_dec, B, Hkv, d)
+        lay = lb.LolaLayer(B, Hq, Hkv, d, D, eta, lam, Cc, dtype="bf16", out_dtype="f32", device=dev, **kw)
+        out = torch.empty((B, Hq, T, d), dtype=torch.float32, device=dev)
+        res = {"mode": label, "shape": f"B{B} Hq{Hq} Hkv{Hkv} d{d} D{D} eta{eta} lambda{lam} C{Cc}", "kernels": lay.lola_path}
+        times = []
+        for r in range(3):
+            lay.reset()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(); lay.prefill(q, k, v, Wq, Wk, out=out); e1.record()
+            torch.cuda.synchronize()
+            if r:
+                times.append(e0.elapsed_time(e1))
+        ms = float(np.mean(times))
+        res["prefill_tokens"] = B * T
+        res["prefill_ms"] = round(ms, 3)
+        res["prefill_tokens_per_s_per_layer"] = round(B * T / (ms * 1e-3), 1)
+        o1 = torch.empty((B, Hq, d), dtype=torch.float32, device=dev)
+        for i in range(4):
+            lay.decode_step(qd[i], kd[i], vd[i], Wq, Wk, out=o1)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(4, n_dec):
+            lay.decode_step(qd[i], kd[i], vd[i], Wq, Wk, out=o1)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / (n_dec - 4)
+        res["decode_us_per_step"] = round(us, 2)
+        res["decode_tokens_per_s_per_layer"] = round(B / (us * 1e-6), 1)
+        log(f"[extras] {label}: {res['shape']} {res['kernels']}: prefill {res['prefill_tokens_per_s_per_layer'] / 1e6:.3f} M tokens/s/layer "
+            f"({ms:.2f} ms), decode {us:.1f} us/step = {res['decode_tokens_per_s_per_layer'] / 1e6:.4f} M tokens/s/layer")
+        return res
+
+    rows = []
+    s8 = dict(B=4, Hq=32, Hkv=8, d=128, D=128, eta=64, lam=128, Cc=64, T=2048, n_dec=68)
+    rows.append(run("8B shape, self-recall error (reference point)", **s8))
+    rows.append(run("8B shape, queries do not read the sparse cache", **s8, query_hide=2))
+    rows.append(run("8B shape, queries do not read the hidden state", **s8, query_hide=1, fold_defer=8))
+    rows.append(run("8B shape, attention-weight score (kind 4)", **s8, score_kind=4))
+    rows.append(run("8B shape, squared weight-error score (kind 1)", **s8, score_kind=1))
+    long = dict(B=4, Hq=32, Hkv=8, d=128, D=256, Cc=64, T=2048, n_dec=36)
+    rows.append(run("long-context cache parameters eta=lambda=256, D=2d", eta=256, lam=256, **long))
+    rows.append(run("long-context cache parameters eta=lambda=512, D=2d", eta=512, lam=512, **long))
+    rows.append(run("long-context cache parameters eta=128, lambda=768, D=2d", eta=128, lam=768, **long))
+    rows.append(run("no sparse cache, window 192 (ablation: extended window)", B=4, Hq=32, Hkv=8, d=128, D=128, eta=192, lam=0, Cc=64, T=2048, n_dec=36))
+    return {"metric": "LoLA layer side modes, tokens/s/layer", "data": "synthetic", "dtype": "bf16", "rows": rows}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -72,6 +133,9 @@ def main():
                     help="deferred folds of the generation step (include/lola.h, lola_config.fold_defer); the other mode is "
                          "timed as a side leg")
     ap.add_argument("--skip-alt", action="store_true", help="skip the side leg that times the other fold mode")
+    ap.add_argument("--extras", action="store_true",
+                    help="instead of the benchmark proper, time the layer's other modes (restricted queries, query-dependent "
+                         "scores, the paper's long-context cache parameters) on small seeded workloads and print one JSON line")
     ap.add_argument("--skip-prefill", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
@@ -89,6 +153,9 @@ def main():
 
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.extras:
+        print(json.dumps(extras(torch, wl, lb, dev)), flush=True)
+        return
     sh = wl.scaled(4, T=args.prefill_tokens)
     K, W, L = args.steps, args.warmup, args.layers
 

@@ -58,6 +58,13 @@ __device__ __forceinline__ void split8(const float x[8], bf16x8 &hi, bf16x8 &lo)
         lo[2 * p] = l[0]; lo[2 * p + 1] = l[1];
     }
 }
+// LDS read with transposition inside each group of 16 lanes (gfx950): lane i of a group supplies the address of four
+// consecutive 16-bit values E[i][0..3]; lane j receives E[j / 4][j % 4], E[4 + j / 4][j % 4], E[8 + j / 4][j % 4],
+// E[12 + j / 4][j % 4] (verified on hardware).  The address must be 8-byte aligned.
+__device__ __forceinline__ bf16x4 tr_read(const uint16_t *p) {
+    typedef __bf16 v4 __attribute__((ext_vector_type(4)));
+    return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) v4 *)(p));
+}
 __device__ __forceinline__ float bf_lo(uint32_t u) { return __uint_as_float(u << 16); }
 __device__ __forceinline__ float bf_hi(uint32_t u) { return __uint_as_float(u & 0xFFFF0000u); }
 __device__ __forceinline__ float dot2bf(uint32_t a, uint32_t b, float c) {
@@ -197,7 +204,7 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     constexpr int NKEY = LAM + 1 + ETA;
     constexpr int NKS = (NKEY + 31) / 32;  // k-steps of the value read-out
     constexpr int KPAD = NKS * 32;
-    constexpr int VLS = 130;               // row stride (bf16) of the staged values
+    constexpr int VLS = 128;               // row stride (bf16) of the staged values (8-byte pieces XOR-swizzled by the row)
     constexpr int XR = 8;                  // rows reserved for the extra tile (1 + G used)
     static_assert(NKT % 4 == 0 && ETA % 16 == 0 && G >= 1 && G <= 4 && NKT <= 8 && NWT <= 4, "shape");
     constexpr int PB_ELEMS = (2 * LAM * D > KPAD * VLS + 2 * G * KPAD) ? 2 * LAM * D : ((KPAD * VLS + 2 * G * KPAD + 7) / 8) * 8;
@@ -729,8 +736,8 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
 #pragma unroll
     for (int it = 0; it < NVIT; it++) {
         const int o = tid + 256 * it, key = o >> 4, c8 = o & 15;
-        uint32_t *dst = reinterpret_cast<uint32_t *>(Vl + key * VLS + 8 * c8);
-        dst[0] = vst[it].x; dst[1] = vst[it].y; dst[2] = vst[it].z; dst[3] = vst[it].w;
+        // 8-byte piece p of row `key` sits at piece p ^ 4 (key % 8): the transposing reads below then touch every bank once
+        *reinterpret_cast<uint4 *>(Vl + key * VLS + 4 * ((2 * c8) ^ (4 * (key & 7)))) = vst[it];
     }
     // the new pair, which takes the ring slot of the pair that left, is requested here and stored at the very end
     // (a store that follows its own load waits for every load the wavefront has in flight: by then there is none)
@@ -775,17 +782,24 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
         f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
         for (int ks = 0; ks < NKS; ks++) {
+            // contraction slots of lane group g4: keys 32 ks + 4 g4 + 0..3, then 32 ks + 16 + 4 g4 + 0..3 (the order in which
+            // the transposing LDS read delivers the values; the weights follow it)
+            const int k0 = 32 * ks + 4 * g4;
             bf16x8 Aph = zero_bf16x8(), Apl = zero_bf16x8();
             if (r16 < G) {
-                Aph = as_bf16x8(*reinterpret_cast<const uint4 *>(&Ph[r16 * KPAD + 32 * ks + 8 * g4]));
-                Apl = as_bf16x8(*reinterpret_cast<const uint4 *>(&Pl[r16 * KPAD + 32 * ks + 8 * g4]));
+                const uint2 h0 = *reinterpret_cast<const uint2 *>(&Ph[r16 * KPAD + k0]), h1 = *reinterpret_cast<const uint2 *>(&Ph[r16 * KPAD + k0 + 16]);
+                const uint2 l0 = *reinterpret_cast<const uint2 *>(&Pl[r16 * KPAD + k0]), l1 = *reinterpret_cast<const uint2 *>(&Pl[r16 * KPAD + k0 + 16]);
+                Aph = as_bf16x8(make_uint4(h0.x, h0.y, h1.x, h1.y));
+                Apl = as_bf16x8(make_uint4(l0.x, l0.y, l1.x, l1.y));
             }
 #pragma unroll
             for (int nt = 0; nt < 2; nt++) {
-                const int c = 16 * (2 * w + nt) + r16;
-                bf16x8 Bv;
-#pragma unroll
-                for (int e = 0; e < 8; e++) Bv[e] = __builtin_bit_cast(__bf16, Vl[(32 * ks + 8 * g4 + e) * VLS + c]);
+                // a 16-lane group reads a 4 x 16 block of the row-major values (lane i: row i / 4, columns 4 (i % 4) ..) and
+                // receives it transposed: lane j holds column j of the four rows
+                const int row = k0 + (r16 >> 2), piece = 4 * (2 * w + nt) + (r16 & 3);
+                const bf16x4 t0 = tr_read(Vl + row * VLS + 4 * (piece ^ (4 * (row & 7))));
+                const bf16x4 t1 = tr_read(Vl + (row + 16) * VLS + 4 * (piece ^ (4 * (row & 7))));
+                const bf16x8 Bv = __builtin_shufflevector(t0, t1, 0, 1, 2, 3, 4, 5, 6, 7);
                 acc[nt] = mfma16(Aph, Bv, acc[nt]);
                 acc[nt] = mfma16(Apl, Bv, acc[nt]);
             }
