@@ -278,20 +278,21 @@ def main():
     # ---- prefill leg (configuration 3) ----
     prefill = None
     prefill_1b = None
+    prefill_64k = None
     if not args.skip_prefill:
         del layers[1:], calls
         torch.cuda.empty_cache()
 
-        def prefill_leg(cid, label):
+        def prefill_leg(cid, label, reps=None):
             """Times lola_prefill (with outputs) on one of the prefill configurations."""
             sc = wl.CONFIGS[cid]
             Wq_, Wk_ = wl.weights(sc)
-            q_, k_, v_, _ = wl.sequence_inputs(sc)
+            q_, k_, v_, extra_ = wl.sequence_inputs(sc)
             lay = lb.LolaLayer(sc.B, sc.Hq, sc.Hkv, sc.d, sc.D, sc.eta, sc.lam, sc.C, dtype="bf16", out_dtype="f32", device=dev)
             a_ = [to_dev(x) for x in (q_, k_, v_, Wq_.transpose(0, 2, 1), Wk_.transpose(0, 2, 1))]
             out_ = torch.empty((sc.B, sc.Hq, sc.T, sc.d), dtype=torch.float32, device=dev)
             times = []
-            for r in range(args.prefill_reps + 1):
+            for r in range((reps or args.prefill_reps) + 1):
                 lay.reset()
                 torch.cuda.synchronize()
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -311,10 +312,20 @@ def main():
                                 "alg_flops_per_call": flops, "kernel": lb.lola_kernel_path(lay.cfg, 0) + " prefill"}}
             log(f"[prefill] {label}: {ms:.2f} ms per call, {res['tokens_per_s_per_layer'] / 1e6:.3f} M tokens/s/layer, "
                 f"{tf:.2f} TFLOP/s algorithmic")
+            if extra_ and "planted_pos" in extra_:
+                # needle-style stand-in: how many of the planted positions the sparse cache holds at the end
+                torch.cuda.synchronize()
+                pos = set(int(p_) for p_ in extra_["planted_pos"])
+                idx = lay.sp_idx.cpu().numpy()
+                res["planted_positions_kept"] = round(float(np.mean(
+                    [len(pos & set(idx[b_, h_].tolist())) / len(pos) for b_ in range(sc.B) for h_ in range(sc.Hkv)])), 4)
+                log(f"[prefill] {label}: fraction of the {len(pos)} planted positions in the sparse cache at the end "
+                    f"{res['planted_positions_kept']:.3f} (mean over kv heads)")
             return res
 
         prefill = prefill_leg(3, "configs[2]: 8B-shape prefill B=4 T=4096 eta=64 lambda=128 C=64 bf16")
         prefill_1b = prefill_leg(2, "configs[1]: 1B-shape prefill B=1 T=4096 head_dim=64 eta=64 lambda=64 C=64 bf16")
+        prefill_64k = prefill_leg(5, "configs[4]: 8B-shape prefill B=1 T=65536 eta=64 lambda=256 C=64 bf16", reps=2)
 
     # ---- CPU baseline: the oracle on a sample of the same decode workload ----
     cpu = None
@@ -358,6 +369,7 @@ def main():
                                f"{L} layer-state copies cycled, fold_defer {args.fold_defer}",
                    "global_batch": sh.B, "prefill_tokens": sh.T, "layer_copies": L, "fold_defer": args.fold_defer},
         "roofline": roofline, "cpu_baseline": cpu, "decode_other_fold_mode": decode_alt, "prefill": prefill, "prefill_1b": prefill_1b,
+        "prefill_64k": prefill_64k,
     }
     print(json.dumps(line), flush=True)
 

@@ -342,6 +342,8 @@ __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillAr
     LOLA_SREP(LOLA_SDECL)
     bool started = false;
     bool phi_valid = false;     // PERSIST: rows [0, LAM) of PB hold phi of the cache slots, and PHn / vvn the rows requested ahead
+    bool rows_valid = false;    // !PERSIST: rows [0, LAM) of the global feature scratch hold phi of the cache slots (the previous
+                                // chunk of this launch left them there), and the feature kernel's rows of that chunk are the leaving pairs'
     constexpr int PHN = C * 32 / NTH;   // 16-byte pieces of a chunk's features per thread
     uint4 PHn[PHN];             // this thread's pieces of phi of the pairs that leave the window in the next chunk
     uint2 vvn[4];               // their values at this wavefront's columns
@@ -381,6 +383,11 @@ __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillAr
         };
         const bool have_phi = PERSIST && phi_valid;   // the cache's rows are in LDS and the leaving pairs' rows (from the
                                                       // parallel feature kernel) were requested one chunk ahead
+        // !PERSIST: where candidate e's features are once rows_valid holds (operand order, high part then low part)
+        const uint16_t *phk_prev = a.phiK + ((size_t)si * a.S + (size_t)(j - 1 - a.j0)) * C * 2 * D;
+        auto phirow = [&](int e) -> const uint16_t * {
+            return (rows_valid && e >= LAM) ? phk_prev + (size_t)(e - LAM) * 2 * D : phiE + (size_t)e * 2 * D;
+        };
 
         // ---- 1. operands of the recall GEMM from the fp32 registers (H^T, and s as one more row held by the lanes
         // of row 0); the snapshot for the output kernel is stored further down
@@ -427,14 +434,21 @@ __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillAr
                     const int o = tid + NTH * it, row = o >> 5, pt = (o >> 4) & 1, pc = o & 15;
                     *reinterpret_cast<uint4 *>(&PB[pt * RB * D + (LAM + row) * D + ((pc ^ (row & 15)) << 3)]) = PHn[it];
                 }
+            } else if (!PERSIST && rows_valid) {
+                // a cache too large to stay in LDS: the batch's rows are copied in from the global scratch (cache slots)
+                // and from the feature kernel's output (pairs leaving the window), 16-byte pieces, coalesced
+#pragma unroll 5
+                for (int it = 0; it < RB * 32 / NTH; it++) {
+                    const int o = tid + NTH * it, rl = o >> 5, rem = o & 31, pt = rem >> 4, pc = rem & 15;
+                    const int e = 16 * t0 + rl;
+                    if (e < 16 * t1) {
+                        const uint4 val = *reinterpret_cast<const uint4 *>(phirow(e) + rem * 8);
+                        *reinterpret_cast<uint4 *>(&PB[pt * RB * D + rl * D + ((pc ^ (rl & 15)) << 3)]) = val;
+                    }
+                }
             } else {
-                // phi of the batch's tiles (first regular chunk of a pass, or a cache too large to stay in LDS):
-                // wavefront w takes tiles t0 + w, t0 + w + NW, ...
-                bf16x8 AW[4][KS];
-#pragma unroll
-                for (int mt = 0; mt < 4; mt++)
-#pragma unroll
-                    for (int ks = 0; ks < KS; ks++) AW[mt][ks] = ld_bf16x8(Wk + (size_t)(16 * mt + r16) * DH + 32 * ks + 8 * g4);
+                // phi of the batch's tiles (first regular chunk of a launch): wavefront w takes tiles t0 + w, t0 + w + NW, ...
+                // (W_k is read where it is used: this path runs once per launch and must not raise the kernel's register need)
 #pragma unroll 1
                 for (int t = t0 + w; t < t1; t += NW) {
                     const int e = 16 * t + r16;
@@ -447,7 +461,8 @@ __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillAr
                     for (int mt = 0; mt < 4; mt++) {
                         zt[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                        for (int ks = 0; ks < KS; ks++) zt[mt] = mfma16(AW[mt][ks], BK[ks], zt[mt]);
+                        for (int ks = 0; ks < KS; ks++)
+                            zt[mt] = mfma16(ld_bf16x8(Wk + (size_t)(16 * mt + r16) * DH + 32 * ks + 8 * g4), BK[ks], zt[mt]);
                     }
                     float pp[16], pn[16];
                     phi_from_z(zt, a.dm.phi_kind, pp, pn);
@@ -648,8 +663,8 @@ __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillAr
                     pa[it] = *reinterpret_cast<const uint4 *>(&PB[pt * RB * D + ea * D + ((ch ^ (ea & 15)) << 3)]);
                     pb[it] = *reinterpret_cast<const uint4 *>(&PB[pt * RB * D + eb * D + ((ch ^ (eb & 15)) << 3)]);
                 } else {
-                    pa[it] = *reinterpret_cast<const uint4 *>(phiE + (size_t)ea * 2 * D + pt * D + (ch << 3));
-                    pb[it] = *reinterpret_cast<const uint4 *>(phiE + (size_t)eb * 2 * D + pt * D + (ch << 3));
+                    pa[it] = *reinterpret_cast<const uint4 *>(phirow(ea) + pt * D + (ch << 3));
+                    pb[it] = *reinterpret_cast<const uint4 *>(phirow(eb) + pt * D + (ch << 3));
                 }
             }
             // v^T: one item per thread: piece vch of the value rows of column pair vpair
@@ -752,6 +767,18 @@ __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillAr
                         *reinterpret_cast<uint4 *>(&PB[pt * RB * D + sl * D + ((ch ^ (sl & 15)) << 3)]) = val;
                     }
                 }
+            } else {
+                // the same in the global scratch: a slot's row follows its occupant (every read of the leavers' rows
+                // was completed before the barrier that precedes the fold)
+#pragma unroll
+                for (int it = 0; it < PHN; it++) {
+                    const int o = tid + NTH * it;
+                    if (o < ne * 32) {
+                        const int x = o >> 5, rem = o & 31;
+                        const uint4 val = *reinterpret_cast<const uint4 *>(phirow(ecand[x]) + rem * 8);
+                        *reinterpret_cast<uint4 *>(phiE + (size_t)eslot[x] * 2 * D + rem * 8) = val;
+                    }
+                }
             }
         }
         for (int x = tid; x < ne; x += NTH) {
@@ -760,6 +787,7 @@ __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillAr
             sp_row[sl] = vrow_c - ETA + (e - LAM);
         }
         phi_valid = PERSIST;
+        rows_valid = !PERSIST;
         if (j == a.j1 - 1) LOLA_STAMP(11);
         __syncthreads();   // (workgroup scope is enough: only this workgroup reads the stream's memories before the kernel ends)
         if (j == a.j1 - 1) LOLA_STAMP(12);
