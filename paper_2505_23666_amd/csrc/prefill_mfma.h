@@ -435,17 +435,23 @@ __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillAr
                     *reinterpret_cast<uint4 *>(&PB[pt * RB * D + (LAM + row) * D + ((pc ^ (row & 15)) << 3)]) = PHn[it];
                 }
             } else if (!PERSIST && rows_valid) {
-                // a cache too large to stay in LDS: the batch's rows are copied in from the global scratch (cache slots)
-                // and from the feature kernel's output (pairs leaving the window), 16-byte pieces, coalesced
-#pragma unroll 5
-                for (int it = 0; it < RB * 32 / NTH; it++) {
-                    const int o = tid + NTH * it, rl = o >> 5, rem = o & 31, pt = rem >> 4, pc = rem & 15;
-                    const int e = 16 * t0 + rl;
+                // a cache too large to stay in LDS: the batch's rows come in from the global scratch (cache slots) and
+                // from the feature kernel's output (pairs leaving the window) by direct global -> LDS loads: no registers,
+                // all of a wavefront's loads in flight at once.  One load instruction fills 1 KB of LDS, lane l its bytes
+                // 16 l ..: four rows of one part; a row's 16-byte pieces are XOR-swizzled, so lane l fetches the piece
+                // that belongs in its position.
+                constexpr int BPP = RB / 4;   // 1 KB blocks per part (high, low)
+#pragma unroll 1
+                for (int blk = w; blk < 2 * BPP; blk += NW) {
+                    const int pt = blk / BPP, rl0 = 4 * (blk % BPP);
+                    const int rl = rl0 + (lane >> 4), slot = lane & 15, e = 16 * t0 + rl;
                     if (e < 16 * t1) {
-                        const uint4 val = *reinterpret_cast<const uint4 *>(phirow(e) + rem * 8);
-                        *reinterpret_cast<uint4 *>(&PB[pt * RB * D + rl * D + ((pc ^ (rl & 15)) << 3)]) = val;
+                        const uint16_t *src = phirow(e) + pt * D + ((slot ^ (rl & 15)) << 3);
+                        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                                         (__attribute__((address_space(3))) void *)&PB[pt * RB * D + rl0 * D], 16, 0, 0);
                     }
                 }
+                __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wavefront's rows have landed (the barrier below publishes them)
             } else {
                 // phi of the batch's tiles (first regular chunk of a launch): wavefront w takes tiles t0 + w, t0 + w + NW, ...
                 // (W_k is read where it is used: this path runs once per launch and must not raise the kernel's register need)
