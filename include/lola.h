@@ -70,7 +70,7 @@ typedef struct {
     int32_t fold_defer;    /* 0: every fold is applied to H and s in memory at once.
                               R = 8: deferred folds (see lola_state.pend_*); accepted only where the fused
                               generation-step kernel exists (bf16, head_dim 128, feat_dim 128, window 64,
-                              sparse_budget 64 or 128, 4 query heads per kv head), else LOLA_ERR_UNSUPPORTED */
+                              sparse_budget 64 or 128, at most 4 query heads per kv head), else LOLA_ERR_UNSUPPORTED */
     int32_t query_hide;    /* 0, or LOLA_HIDE_STATE | LOLA_HIDE_SPARSE bits: terms left out of the numerator
                               and the denominator of every output (lola_prefill and lola_decode_step) */
     int32_t score_kind;    /* LOLA_SCORE_*; anything but LOLA_SCORE_SRE excludes fold_defer */

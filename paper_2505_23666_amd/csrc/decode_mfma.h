@@ -142,6 +142,7 @@ struct DecodeFastArgs {
     float scale;
     int phi_kind;
     int hide;   // restricted query: bit 0 the hidden state, bit 1 the sparse cache is not read
+    int g;      // query heads per kv head, 1 .. G (the kernel is compiled for G = 4 rows of queries; unused rows are zero)
     // deferred folds (R > 0): up to R - 1 folded pairs per stream wait here, [stream][R][D] / [stream][R][DH] fp32
     float *pend_phi, *pend_v;
     int32_t *pend_count;
@@ -191,7 +192,9 @@ __device__ __forceinline__ void phi_from_z(const f32x4 zt[4], int phi_kind, floa
 // is the pending pair) and to s, so everything downstream sees the true state; its own fold is appended to the
 // list, and only the step that would make the list full writes H and s back.  Same sums as folding at once
 // (Sec. 2.2, eq. recurrent_update), three of four write-backs of H saved.
-template <int LAM, int ETA, int G, int R, typename TO>
+// GDYN: the group size is read from the arguments (1 .. G) instead of being G; the benchmarked shape keeps the
+// compile-time form.
+template <int LAM, int ETA, int G, int R, bool GDYN, typename TO>
 __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> a) {
     static_assert(R == 0 || R == 4 || R == 8, "pending pairs are the contraction index of 16x16x4 MFMAs");
     constexpr int RG = R > 0 ? R / 4 : 1;
@@ -237,7 +240,8 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     int32_t *sp_idx = a.st.sp_idx + (size_t)si * LAM;
     const bf16_t *Wk = a.Wk + (size_t)h * M * DH;            // [M][DH], row j = w_j
     const bf16_t *knew = a.k + (size_t)si * DH, *vnew = a.v + (size_t)si * DH;
-    const bf16_t *qg = a.q + ((size_t)b * a.Hq + (size_t)h * G) * DH;   // G consecutive query rows
+    const int g = GDYN ? a.g : G;
+    const bf16_t *qg = a.q + ((size_t)b * a.Hq + (size_t)h * g) * DH;   // g consecutive query rows
 
     const int64_t tok = a.st.n_tokens[si];
     const int spc = a.st.sp_count[si];
@@ -259,7 +263,7 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
 #endif
     // ---- stage 0: loads are requested in the order in which they are consumed (they complete in order): the small
     // per-stream vectors that the first barrier waits for, then the operands of the projections, then the window keys
-    const uint4 q_ld = (tid >= 64 && tid < 64 + G * 16) ? reinterpret_cast<const uint4 *>(qg)[tid - 64] : make_uint4(0, 0, 0, 0);
+    const uint4 q_ld = (tid >= 64 && tid < 64 + g * 16) ? reinterpret_cast<const uint4 *>(qg)[tid - 64] : make_uint4(0, 0, 0, 0);
     const float4 s_ld = tid < D / 4 ? reinterpret_cast<const float4 *>(sg)[tid] : make_float4(0.f, 0.f, 0.f, 0.f);
     float *pphi = nullptr, *pval = nullptr;
     int cnt = 0;
@@ -280,7 +284,7 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     // the 8 inputs 8 (l % 16) .. of projection 4 it + l / 16 (each row's dot product is finished by a row reduction)
     uint4 wq[16];
     {
-        const bf16_t *Wq = a.Wq + ((size_t)h * G + (w < G ? w : 0)) * M * DH;
+        const bf16_t *Wq = a.Wq + ((size_t)h * g + (w < g ? w : 0)) * M * DH;
 #pragma unroll
         for (int it = 0; it < 16; it++) wq[it] = reinterpret_cast<const uint4 *>(Wq)[64 * it + lane];
     }
@@ -322,7 +326,7 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
             d[4] = bf_lo(p_ld.z); d[5] = bf_hi(p_ld.z); d[6] = bf_lo(p_ld.w); d[7] = bf_hi(p_ld.w);
         }
     }
-    if (tid >= 64 && tid < 64 + G * 16) reinterpret_cast<uint4 *>(qb)[tid - 64] = q_ld;
+    if (tid >= 64 && tid < 64 + g * 16) reinterpret_cast<uint4 *>(qb)[tid - 64] = q_ld;
     if (tid >= 128 && tid < 128 + 2 * XR * D / 8) reinterpret_cast<uint4 *>(PX)[tid - 128] = make_uint4(0, 0, 0, 0);
     // W_k staging: row j = projection, 16-byte piece p at position p ^ (j % 16) (the swizzle of the feature tile)
 #pragma unroll
@@ -344,7 +348,7 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     bf16x8 AQ[4];
 #pragma unroll
     for (int ks = 0; ks < 4; ks++)
-        AQ[ks] = r16 < G ? as_bf16x8(*reinterpret_cast<const uint4 *>(&qb[r16][16 * ks + 4 * g4])) : zero_bf16x8();
+        AQ[ks] = r16 < g ? as_bf16x8(*reinterpret_cast<const uint4 *>(&qb[r16][16 * ks + 4 * g4])) : zero_bf16x8();
 
     // ---- logits of this wavefront's cached-key tiles and window tile (Q K^T)
 #pragma unroll
@@ -373,7 +377,7 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     // ---- stage 1a: phi of this wavefront's query; stored as bf16 high + low parts in the operand layout of the
     // recall GEMM (row w + 1 of the extra tile).  Each 1 KB piece of W_q yields four projections: eight products per
     // lane, then a reduction over the 16 lanes of a row; lane (r16, g4) keeps projection j = 4 r16 + g4.
-    if (steady && w < G) {
+    if (steady && w < g) {
         const uint4 xq = reinterpret_cast<const uint4 *>(qb[w])[lane & 15];
         float z = 0.f;
 #pragma unroll
@@ -407,7 +411,7 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     }
     // logit of the leaving key (it is attended if it stays in the cache)
     if (popped) {
-        for (int r = w; r < G; r += 4) {
+        for (int r = w; r < g; r += 4) {
             float dot = wsum(dot2bf(qb[r][lane], reinterpret_cast<const uint32_t *>(pkb)[lane], 0.f));
             if (lane == 0) lg[r][KP] = dot * a.scale;
         }
@@ -639,7 +643,7 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
                     if (r16 == 0) {
 #pragma unroll
                         for (int i = 0; i < 4; i++) { const float e = fmaf(p[i], rd, -pvf[c0 + i]); e2 = fmaf(e, e, e2); }
-                    } else if (r16 <= G) {
+                    } else if (r16 <= g) {
 #pragma unroll
                         for (int i = 0; i < 4; i++) lin[r16 - 1][c0 + i] = p[i];
                     }
@@ -704,7 +708,7 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
             if (tid == 0) a.pend_count[si] = cnt + 1;
         }
         // phi(q) . phi_f for the rank-1 correction of the linear read-out
-        for (int r = w; r < G; r += 4) {
+        for (int r = w; r < g; r += 4) {
             float acc = 0.f;
 #pragma unroll
             for (int half = 0; half < 2; half++) {
@@ -744,7 +748,7 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     uint4 new_ld = make_uint4(0, 0, 0, 0);
     if (tid < 32) new_ld = reinterpret_cast<const uint4 *>(tid < 16 ? knew : vnew)[tid & 15];
     // softmax weights (one query per wavefront), m = max(0, max logit); written as bf16 high + low parts
-    for (int r = w; r < G; r += 4) {
+    for (int r = w; r < g; r += 4) {
         float l[(KPAD + 63) / 64];
         float mx = 0.f;
 #pragma unroll
@@ -786,7 +790,7 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
             // the transposing LDS read delivers the values; the weights follow it)
             const int k0 = 32 * ks + 4 * g4;
             bf16x8 Aph = zero_bf16x8(), Apl = zero_bf16x8();
-            if (r16 < G) {
+            if (r16 < g) {
                 const uint2 h0 = *reinterpret_cast<const uint2 *>(&Ph[r16 * KPAD + k0]), h1 = *reinterpret_cast<const uint2 *>(&Ph[r16 * KPAD + k0 + 16]);
                 const uint2 l0 = *reinterpret_cast<const uint2 *>(&Pl[r16 * KPAD + k0]), l1 = *reinterpret_cast<const uint2 *>(&Pl[r16 * KPAD + k0 + 16]);
                 Aph = as_bf16x8(make_uint4(h0.x, h0.y, h1.x, h1.y));
@@ -810,13 +814,14 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
                 const int c = 16 * (2 * w + nt) + r16;
 #pragma unroll
                 for (int r = 0; r < G; r++) {
+                    if (r >= g) break;
                     float num = acc[nt][r], den = psum_s[r];
                     if (steady && !(a.hide & 1)) {
                         const float el = elin_s[r];
                         num = fmaf(el, fmaf(dotqf[r], vf[c], lin[r][c]), num);
                         den = fmaf(el, denq[r] + dotqf[r], den);
                     }
-                    stf(a.out, ((size_t)b * a.Hq + (size_t)h * G + r) * DH + c, num / den);
+                    stf(a.out, ((size_t)b * a.Hq + (size_t)h * g + r) * DH + c, num / den);
                 }
             }
         }

@@ -34,7 +34,7 @@ constexpr int DEFER_R = 8;   // pairs a stream may list before the generation st
 // The fused MFMA generation step covers the Llama-8B head shape with bf16 storage.
 bool fast_decode_ok(const lola_config *c) {
     return c->dtype == LOLA_BF16 && c->head_dim == 128 && c->feat_dim == 128 && c->window == 64 &&
-           (c->sparse_budget == 128 || c->sparse_budget == 64) && c->n_q_heads / c->n_kv_heads == 4 &&
+           (c->sparse_budget == 128 || c->sparse_budget == 64) && c->n_q_heads / c->n_kv_heads <= 4 &&
            c->score_kind == LOLA_SCORE_SRE;
 }
 
@@ -160,7 +160,7 @@ int attend_tile_queries(const Dims &dm) {
 bool fast_attend_ok(const lola_config *c) {
     return c->dtype == LOLA_BF16 && (c->head_dim == 128 || c->head_dim == 64) && c->feat_dim == 128 && c->window == 64 && c->chunk == 64 &&
            (c->sparse_budget == 64 || c->sparse_budget == 128 || c->sparse_budget == 256) &&
-           c->n_q_heads / c->n_kv_heads == 4 && c->score_kind == LOLA_SCORE_SRE;
+           c->score_kind == LOLA_SCORE_SRE;
 }
 
 struct PrefillPlan {
@@ -201,11 +201,16 @@ lola_status launch_fast_decode(const lola_config *c, const lola_state *st, const
     a.scale = make_dims(c).scale;
     a.phi_kind = c->phi_kind;
     a.hide = c->query_hide;
+    a.g = c->n_q_heads / c->n_kv_heads;
     a.pend_phi = st->pend_phi; a.pend_v = st->pend_v; a.pend_count = st->pend_count;
-    if (c->fold_defer)
-        hipLaunchKernelGGL((fast::decode_fast_kernel<LAM, 64, 4, DEFER_R, TO>), dim3(c->batch * c->n_kv_heads), dim3(256), 0, stream, a);
-    else
-        hipLaunchKernelGGL((fast::decode_fast_kernel<LAM, 64, 4, 0, TO>), dim3(c->batch * c->n_kv_heads), dim3(256), 0, stream, a);
+    const dim3 grid(c->batch * c->n_kv_heads), block(256);
+    if (a.g == 4) {
+        if (c->fold_defer) hipLaunchKernelGGL((fast::decode_fast_kernel<LAM, 64, 4, DEFER_R, false, TO>), grid, block, 0, stream, a);
+        else hipLaunchKernelGGL((fast::decode_fast_kernel<LAM, 64, 4, 0, false, TO>), grid, block, 0, stream, a);
+    } else {
+        if (c->fold_defer) hipLaunchKernelGGL((fast::decode_fast_kernel<LAM, 64, 4, DEFER_R, true, TO>), grid, block, 0, stream, a);
+        else hipLaunchKernelGGL((fast::decode_fast_kernel<LAM, 64, 4, 0, true, TO>), grid, block, 0, stream, a);
+    }
     LAUNCH_CHECK();
     return LOLA_OK;
 }

@@ -29,7 +29,7 @@ __device__ __forceinline__ int perm_elem(int x) { return (((x >> 4) & 1) << 2) |
 
 template <int LAM, int DH, typename TO>
 __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArgs<bf16_t> a) {
-    constexpr int M = 64, D = 128, C = 64, ETA = 64, G = 4, KS = DH / 32, PR = DH / 8, NCT = DH / 16;
+    constexpr int M = 64, D = 128, C = 64, ETA = 64, KS = DH / 32, PR = DH / 8, NCT = DH / 16;
     static_assert(DH == 64 || DH == 128, "head_dim");
     constexpr int P = LAM + ETA;                    // rows of the virtual prefix
     constexpr int NKEYS = LAM + ETA + C;            // key positions
@@ -40,7 +40,7 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
 
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r16 = lane & 15, g4 = lane >> 4;
     const int jj = blockIdx.x, j = a.j0 + jj, hq = blockIdx.y, b = blockIdx.z;
-    const int h = hq / G, si = b * a.dm.Hkv + h;
+    const int h = hq / a.dm.g, si = b * a.dm.Hkv + h;
     const int64_t a0 = a.st.n_tokens[si];
     const int Tn = a.T_tokens;
     const int cl = min(C, Tn - j * C);              // queries in this chunk

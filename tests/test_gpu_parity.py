@@ -234,6 +234,19 @@ def test_query_dependent_scores_fp32_cold_decode_and_8b_shape():
     say("query-dependent scores, 8B head shape", rep, rep2)
 
 
+@pytest.mark.parametrize("g", [1, 2, 3])
+def test_mfma_kernels_with_other_group_sizes(g):
+    """Multi-head attention (one query head per kv head) and small groups on the MFMA kernels: the
+    generation step is built for up to four query rows per stream, the prefill kernels take any."""
+    sh = wl.Shape("group", "bf16", 1, 2 * g, 2, 128, 128, T=0, eta=64, lam=64, C=64, seed=0)
+    T = 64 * 4 + 21
+    q, k, v, Wq, Wk = rand_case(120 + g, 1, 2 * g, 2, 128, 128, T + 16, "bf16")
+    layer, o, rep = P.prefill_parity(sh, q[:, :, :T], k[:, :, :T], v[:, :, :T], Wq, Wk)
+    assert layer.lola_path == ("mfma", "mfma")
+    rep2 = P.decode_parity(sh, layer, o, *steps(q, k, v, T, 16), Wq, Wk)
+    say("group size", g, rep, rep2)
+
+
 def test_exp_feature_map():
     sh = wl.Shape("expphi", "f32", 1, 2, 1, 32, 16, T=64, eta=8, lam=6, C=8, seed=0)
     q, k, v, Wq, Wk = rand_case(8, 1, 2, 1, 32, 16, 70, "f32", wscale=0.5)
