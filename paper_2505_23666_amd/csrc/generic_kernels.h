@@ -386,23 +386,30 @@ struct PrefillArgs {
     int R2;                   // keys / queries per tile of band_score_kernel
 };
 
+// grid (stream, part): the parts of a stream share its rows evenly
 template <typename T>
 __global__ __launch_bounds__(NT) void prefix_kernel(PrefillArgs<T> a) {
     const Dims &dm = a.dm;
-    const int si = blockIdx.x, tid = threadIdx.x, d = dm.d, eta = dm.eta, lam = dm.lam, P = lam + eta;
+    const int si = blockIdx.x, d = dm.d, eta = dm.eta, lam = dm.lam, P = lam + eta;
+    const int tid = blockIdx.y * NT + threadIdx.x, nth = gridDim.y * NT;
     const int64_t a0 = a.st.n_tokens[si];
     T *pK = a.prefK + (size_t)si * P * d, *pV = a.prefV + (size_t)si * P * d;
     const T *sp_k = a.st.sp_k + (size_t)si * lam * d, *sp_v = a.st.sp_v + (size_t)si * lam * d;
     const T *win_k = a.st.win_k + (size_t)si * eta * d, *win_v = a.st.win_v + (size_t)si * eta * d;
-    for (int p = tid; p < lam * d; p += NT) { pK[p] = sp_k[p]; pV[p] = sp_v[p]; }
-    for (int s = tid; s < lam; s += NT) a.sp_row[(size_t)si * lam + s] = s;
+    // rows are copied as 16-byte pieces (a row is d * sizeof(T) bytes, a multiple of 16)
+    const int ppr = d * (int)sizeof(T) / 16;
+    const uint4 *sk4 = reinterpret_cast<const uint4 *>(sp_k), *sv4 = reinterpret_cast<const uint4 *>(sp_v);
+    uint4 *pK4 = reinterpret_cast<uint4 *>(pK), *pV4 = reinterpret_cast<uint4 *>(pV);
+    for (int p = tid; p < lam * ppr; p += nth) { pK4[p] = sk4[p]; pV4[p] = sv4[p]; }
+    for (int s = tid; s < lam; s += nth) a.sp_row[(size_t)si * lam + s] = s;
     const int nw = (int)min((int64_t)eta, a0);
-    for (int p = tid; p < nw * d; p += NT) {
-        int back = p / d + 1, i = p % d;          // token a0 - back
+    const uint4 *wk4 = reinterpret_cast<const uint4 *>(win_k), *wv4 = reinterpret_cast<const uint4 *>(win_v);
+    for (int p = tid; p < nw * ppr; p += nth) {
+        int back = p / ppr + 1, i = p % ppr;      // token a0 - back
         int slot = (int)((a0 - back) % eta);
         size_t row = (size_t)(P - back);
-        pK[row * d + i] = win_k[(size_t)slot * d + i];
-        pV[row * d + i] = win_v[(size_t)slot * d + i];
+        pK4[row * ppr + i] = wk4[(size_t)slot * ppr + i];
+        pV4[row * ppr + i] = wv4[(size_t)slot * ppr + i];
     }
 }
 
@@ -415,11 +422,14 @@ __global__ __launch_bounds__(NT) void finalize_kernel(PrefillArgs<T> a) {
     T *win_k = a.st.win_k + (size_t)si * eta * d, *win_v = a.st.win_v + (size_t)si * eta * d;
     const T *k = a.k + (size_t)si * Tn * d, *v = a.v + (size_t)si * Tn * d;
     const int first = max(0, Tn - eta);       // tokens of this call that end in the window
-    for (int p = tid; p < (Tn - first) * d; p += NT) {
-        int i = first + p / d, c = p % d;
+    const int ppr = d * (int)sizeof(T) / 16;  // 16-byte pieces per row
+    const uint4 *k4 = reinterpret_cast<const uint4 *>(k), *v4 = reinterpret_cast<const uint4 *>(v);
+    uint4 *wk4 = reinterpret_cast<uint4 *>(win_k), *wv4 = reinterpret_cast<uint4 *>(win_v);
+    for (int p = tid; p < (Tn - first) * ppr; p += NT) {
+        int i = first + p / ppr, c = p % ppr;
         int slot = (int)((a0 + i) % eta);
-        win_k[(size_t)slot * d + c] = k[(size_t)i * d + c];
-        win_v[(size_t)slot * d + c] = v[(size_t)i * d + c];
+        wk4[(size_t)slot * ppr + c] = k4[(size_t)i * ppr + c];
+        wv4[(size_t)slot * ppr + c] = v4[(size_t)i * ppr + c];
     }
     if (dm.score_kind) {
         // the sums of the pairs that end in the window (some may have been there before the call) go back to their ring slots

@@ -296,7 +296,12 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
     const size_t lds_att = 4 * ((size_t)a.QT * (d + D + (lam + a.dm.eta + a.dm.C) + 3));
     dim3 block(generic::NT), gs((unsigned)ns);
 
-    hipLaunchKernelGGL((generic::prefix_kernel<T>), gs, block, 0, stream, a);
+    {
+        // enough workgroups per stream to keep the copy of (lambda + eta) rows short when the streams are few
+        const size_t rows = (size_t)a.dm.lam + a.dm.eta;
+        const unsigned parts = (unsigned)(ns >= 512 ? 1 : (rows * d / (generic::NT * 16) > 16 ? 16 : (rows * d / (generic::NT * 16) < 1 ? 1 : rows * d / (generic::NT * 16))));
+        hipLaunchKernelGGL((generic::prefix_kernel<T>), dim3((unsigned)ns, parts), block, 0, stream, a);
+    }
     LAUNCH_CHECK();
     if (a.dm.score_kind) {   // the query-dependent scores of every pair the call touches, before the state evolves
         if (a.R2 <= 0) return LOLA_ERR_UNSUPPORTED;
@@ -326,9 +331,11 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
                 if (c->sparse_budget == 64) LOLA_SCAN(64); else if (c->sparse_budget == 128) LOLA_SCAN(128); else LOLA_SCAN(256);
 #undef LOLA_SCAN
                 LAUNCH_CHECK();
-                a.scan_mode = 2;
-                hipLaunchKernelGGL((generic::scan_kernel<T>), gs, block, lds_scan, stream, a);
-                LAUNCH_CHECK();
+                if (a.j1 == a.n_chunks && Tn % a.dm.C != 0) {   // only a ragged last chunk is left to the generic kernel
+                    a.scan_mode = 2;
+                    hipLaunchKernelGGL((generic::scan_kernel<T>), gs, block, lds_scan, stream, a);
+                    LAUNCH_CHECK();
+                }
                 a.scan_mode = 0;
                 scanned = true;
             }
