@@ -109,6 +109,10 @@ def extras(torch, wl, lb, dev):
     rows = []
     s8 = dict(B=4, Hq=32, Hkv=8, d=128, D=128, eta=64, lam=128, Cc=64, T=2048, n_dec=68)
     rows.append(run("8B shape, self-recall error (reference point)", **s8))
+    rows.append(run("1B shape (head_dim 64, lambda 64), deferred folds", B=16, Hq=32, Hkv=8, d=64, D=128, eta=64, lam=64, Cc=64, T=2048,
+                    n_dec=68, fold_defer=8))
+    rows.append(run("8B shape, batch 16, deferred folds", B=16, Hq=32, Hkv=8, d=128, D=128, eta=64, lam=128, Cc=64, T=2048, n_dec=68,
+                    fold_defer=8))
     rows.append(run("8B shape, queries do not read the sparse cache", **s8, query_hide=2))
     rows.append(run("8B shape, queries do not read the hidden state", **s8, query_hide=1, fold_defer=8))
     rows.append(run("8B shape, attention-weight score (kind 4)", **s8, score_kind=4))

@@ -194,11 +194,17 @@ __device__ __forceinline__ void phi_from_z(const f32x4 zt[4], int phi_kind, floa
 // (Sec. 2.2, eq. recurrent_update), three of four write-backs of H saved.
 // GDYN: the group size is read from the arguments (1 .. G) instead of being G; the benchmarked shape keeps the
 // compile-time form.
-template <int LAM, int ETA, int G, int R, bool GDYN, typename TO>
+// DH = head_dim: 128 (8B head shape) or 64 (1B head shape); with 64 a wavefront owns 16 rows of H^T instead of 32.
+template <int LAM, int ETA, int G, int R, bool GDYN, int DH, typename TO>
 __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> a) {
     static_assert(R == 0 || R == 4 || R == 8, "pending pairs are the contraction index of 16x16x4 MFMAs");
+    static_assert(DH == 128 || DH == 64, "head_dim");
     constexpr int RG = R > 0 ? R / 4 : 1;
-    constexpr int DH = 128, M = 64, D = 128;
+    constexpr int M = 64, D = 128;
+    constexpr int KS = DH / 32;            // k-steps of a contraction over the head dimension
+    constexpr int PR = DH / 8;             // 16-byte pieces of a key / value / query row
+    constexpr int CW = DH / 4;             // rows of H^T (= value columns) a wavefront owns
+    constexpr int NCT = CW / 16;           // its 16-row tiles
     constexpr int NKT = LAM / 16;          // key tiles of the sparse cache
     constexpr int TPW = NKT / 4;           // key tiles whose phi a wavefront computes
     constexpr int NWT = ETA / 16;          // window tiles
@@ -207,7 +213,7 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     constexpr int NKEY = LAM + 1 + ETA;
     constexpr int NKS = (NKEY + 31) / 32;  // k-steps of the value read-out
     constexpr int KPAD = NKS * 32;
-    constexpr int VLS = 128;               // row stride (bf16) of the staged values (8-byte pieces XOR-swizzled by the row)
+    constexpr int VLS = DH;                // row stride (bf16) of the staged values (8-byte pieces XOR-swizzled by the row)
     constexpr int XR = 8;                  // rows reserved for the extra tile (1 + G used)
     static_assert(NKT % 4 == 0 && ETA % 16 == 0 && G >= 1 && G <= 4 && NKT <= 8 && NWT <= 4, "shape");
     constexpr int PB_ELEMS = (2 * LAM * D > KPAD * VLS + 2 * G * KPAD) ? 2 * LAM * D : ((KPAD * VLS + 2 * G * KPAD + 7) / 8) * 8;
@@ -263,7 +269,7 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
 #endif
     // ---- stage 0: loads are requested in the order in which they are consumed (they complete in order): the small
     // per-stream vectors that the first barrier waits for, then the operands of the projections, then the window keys
-    const uint4 q_ld = (tid >= 64 && tid < 64 + g * 16) ? reinterpret_cast<const uint4 *>(qg)[tid - 64] : make_uint4(0, 0, 0, 0);
+    const uint4 q_ld = (tid >= 64 && tid < 64 + g * PR) ? reinterpret_cast<const uint4 *>(qg)[tid - 64] : make_uint4(0, 0, 0, 0);
     const float4 s_ld = tid < D / 4 ? reinterpret_cast<const float4 *>(sg)[tid] : make_float4(0.f, 0.f, 0.f, 0.f);
     float *pphi = nullptr, *pval = nullptr;
     int cnt = 0;
@@ -277,35 +283,36 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     const int idx_ld = tid < LAM ? sp_idx[tid] : 0;
     // W_k crosses the cache hierarchy once per workgroup: each wavefront fetches a quarter (16 projections, 4 KB,
     // whole lines) and the MFMA A operands are read back from LDS, where the feature tile is not in use yet
-    uint4 wk_ld[4];
+    uint4 wk_ld[KS];
 #pragma unroll
-    for (int it = 0; it < 4; it++) wk_ld[it] = reinterpret_cast<const uint4 *>(Wk)[256 * w + 64 * it + lane];
-    // W_q of this wavefront's query head, read as whole 1 KB pieces: piece `it` holds projections 4 it .. 4 it + 3, lane l
-    // the 8 inputs 8 (l % 16) .. of projection 4 it + l / 16 (each row's dot product is finished by a row reduction)
-    uint4 wq[16];
+    for (int it = 0; it < KS; it++) wk_ld[it] = reinterpret_cast<const uint4 *>(Wk)[16 * PR * w + 64 * it + lane];
+    // W_q of this wavefront's query head, read as whole 1 KB pieces: piece `it` holds 64 / PR projections, lane l the
+    // 8 inputs 8 (l % PR) .. of projection (64 / PR) it + l / PR (each row's dot product is finished by a reduction over
+    // PR neighbouring lanes)
+    uint4 wq[PR];
     {
         const bf16_t *Wq = a.Wq + ((size_t)h * g + (w < g ? w : 0)) * M * DH;
 #pragma unroll
-        for (int it = 0; it < 16; it++) wq[it] = reinterpret_cast<const uint4 *>(Wq)[64 * it + lane];
+        for (int it = 0; it < PR; it++) wq[it] = reinterpret_cast<const uint4 *>(Wq)[64 * it + lane];
     }
     // cached key rows of this wavefront's tiles, already in MFMA B-operand form (column = key, k = input index)
-    bf16x8 BK[TPW][4];
+    bf16x8 BK[TPW][KS];
 #pragma unroll
     for (int t = 0; t < TPW; t++)
 #pragma unroll
-        for (int ks = 0; ks < 4; ks++) BK[t][ks] = ld_bf16x8(sp_k + (size_t)(16 * (w + 4 * t) + r16) * DH + 32 * ks + 8 * g4);
+        for (int ks = 0; ks < KS; ks++) BK[t][ks] = ld_bf16x8(sp_k + (size_t)(16 * (w + 4 * t) + r16) * DH + 32 * ks + 8 * g4);
     // (everything requested so far is independent of the token counter, whose own load is still on its way; the
     // ring slot enters only from here on)
     uint4 p_ld = make_uint4(0, 0, 0, 0);
-    if (popped && tid < 32)   // 16 threads fetch the leaving key row, 16 the value row (16 bytes each)
-        p_ld = reinterpret_cast<const uint4 *>(tid < 16 ? win_k + (size_t)slot * DH : win_v + (size_t)slot * DH)[tid & 15];
+    if (popped && tid < 2 * PR)   // PR threads fetch the leaving key row, PR the value row (16 bytes each)
+        p_ld = reinterpret_cast<const uint4 *>(tid < PR ? win_k + (size_t)slot * DH : win_v + (size_t)slot * DH)[tid % PR];
     // window keys of this wavefront's tile; the ring slot of the new token is taken from the input
-    bf16x8 BWin[4];
+    bf16x8 BWin[KS];
     {
         const int row = 16 * (w < NWT ? w : 0) + r16;
         const bf16_t *src = row == slot ? knew : win_k + (size_t)row * DH;
 #pragma unroll
-        for (int ks = 0; ks < 4; ks++) BWin[ks] = ld_bf16x8(src + 32 * ks + 8 * g4);
+        for (int ks = 0; ks < KS; ks++) BWin[ks] = ld_bf16x8(src + 32 * ks + 8 * g4);
     }
     LOLA_STAMP(9);
     if (tid < D / 4) {
@@ -318,36 +325,36 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
         reinterpret_cast<float4 *>(s_l)[tid] = sv;
     }
     if (tid < LAM) idx_l[tid] = idx_ld;
-    if (popped && tid < 32) {
-        reinterpret_cast<uint4 *>(tid < 16 ? pkb : pvb)[tid & 15] = p_ld;
-        if (tid >= 16) {
-            float *d = pvf + 8 * (tid & 15);
+    if (popped && tid < 2 * PR) {
+        reinterpret_cast<uint4 *>(tid < PR ? pkb : pvb)[tid % PR] = p_ld;
+        if (tid >= PR) {
+            float *d = pvf + 8 * (tid - PR);
             d[0] = bf_lo(p_ld.x); d[1] = bf_hi(p_ld.x); d[2] = bf_lo(p_ld.y); d[3] = bf_hi(p_ld.y);
             d[4] = bf_lo(p_ld.z); d[5] = bf_hi(p_ld.z); d[6] = bf_lo(p_ld.w); d[7] = bf_hi(p_ld.w);
         }
     }
-    if (tid >= 64 && tid < 64 + g * 16) reinterpret_cast<uint4 *>(qb)[tid - 64] = q_ld;
+    if (tid >= 64 && tid < 64 + g * PR) reinterpret_cast<uint4 *>(qb)[tid - 64] = q_ld;
     if (tid >= 128 && tid < 128 + 2 * XR * D / 8) reinterpret_cast<uint4 *>(PX)[tid - 128] = make_uint4(0, 0, 0, 0);
-    // W_k staging: row j = projection, 16-byte piece p at position p ^ (j % 16) (the swizzle of the feature tile)
+    // W_k staging: row j = projection, 16-byte piece p at position p ^ (j % PR)
 #pragma unroll
-    for (int it = 0; it < 4; it++) {
-        const int j = 16 * w + 4 * it + (lane >> 4), pc = lane & 15;
-        *reinterpret_cast<uint4 *>(&PB[j * DH + ((pc ^ (j & 15)) << 3)]) = wk_ld[it];
+    for (int it = 0; it < KS; it++) {
+        const int j = 16 * w + (64 * it + lane) / PR, pc = lane % PR;
+        *reinterpret_cast<uint4 *>(&PB[j * DH + ((pc ^ (j & (PR - 1))) << 3)]) = wk_ld[it];
     }
     __syncthreads();
     LOLA_STAMP(1);
     // W_k as MFMA A operand (row = projection, k = input index): [projection tile][k-step]
-    bf16x8 AW[4][4];
+    bf16x8 AW[4][KS];
 #pragma unroll
     for (int mt = 0; mt < 4; mt++)
 #pragma unroll
-        for (int ks = 0; ks < 4; ks++)
-            AW[mt][ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(&PB[(16 * mt + r16) * DH + (((4 * ks + g4) ^ r16) << 3)]));
+        for (int ks = 0; ks < KS; ks++)
+            AW[mt][ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(&PB[(16 * mt + r16) * DH + (((4 * ks + g4) ^ (r16 & (PR - 1))) << 3)]));
     __syncthreads();   // every wavefront holds its operands: the staging area may become the feature tile
     // ---- query rows as MFMA A operand (rows >= G are zero)
-    bf16x8 AQ[4];
+    bf16x8 AQ[KS];
 #pragma unroll
-    for (int ks = 0; ks < 4; ks++)
+    for (int ks = 0; ks < KS; ks++)
         AQ[ks] = r16 < g ? as_bf16x8(*reinterpret_cast<const uint4 *>(&qb[r16][16 * ks + 4 * g4])) : zero_bf16x8();
 
     // ---- logits of this wavefront's cached-key tiles and window tile (Q K^T)
@@ -355,7 +362,7 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     for (int t = 0; t < TPW; t++) {
         f32x4 accL = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int ks = 0; ks < 4; ks++) accL = mfma16(AQ[ks], BK[t][ks], accL);
+        for (int ks = 0; ks < KS; ks++) accL = mfma16(AQ[ks], BK[t][ks], accL);
         if (g4 == 0) {
 #pragma unroll
             for (int i = 0; i < G; i++) lg[i][16 * (w + 4 * t) + r16] = accL[i] * a.scale;
@@ -366,7 +373,7 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
         const int row = 16 * w + r16;
         f32x4 accL = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int ks = 0; ks < 4; ks++) accL = mfma16(AQ[ks], BWin[ks], accL);
+        for (int ks = 0; ks < KS; ks++) accL = mfma16(AQ[ks], BWin[ks], accL);
         if (g4 == 0) {
 #pragma unroll
             for (int i = 0; i < G; i++) lg[i][KW + row] = accL[i] * a.scale;
@@ -378,16 +385,17 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     // recall GEMM (row w + 1 of the extra tile).  Each 1 KB piece of W_q yields four projections: eight products per
     // lane, then a reduction over the 16 lanes of a row; lane (r16, g4) keeps projection j = 4 r16 + g4.
     if (steady && w < g) {
-        const uint4 xq = reinterpret_cast<const uint4 *>(qb[w])[lane & 15];
+        const uint4 xq = reinterpret_cast<const uint4 *>(qb[w])[lane % PR];
         float z = 0.f;
 #pragma unroll
-        for (int it = 0; it < 16; it++) {
+        for (int it = 0; it < PR; it++) {
             float pz = dot2bf(wq[it].x, xq.x, 0.f); pz = dot2bf(wq[it].y, xq.y, pz);
             pz = dot2bf(wq[it].z, xq.z, pz); pz = dot2bf(wq[it].w, xq.w, pz);
-            pz += dpp_f<0xB1>(pz); pz += dpp_f<0x4E>(pz); pz += dpp_f<0x141>(pz); pz += dpp_f<0x140>(pz);
-            if (r16 == it) z = pz;
+            pz += dpp_f<0xB1>(pz); pz += dpp_f<0x4E>(pz); pz += dpp_f<0x141>(pz);
+            if (PR == 16) pz += dpp_f<0x140>(pz);
+            if (lane % PR == it) z = pz;
         }
-        const int j = 4 * r16 + g4;
+        const int j = (64 / PR) * (lane % PR) + lane / PR;   // the projection this lane keeps
         float pp, pn;
         if (a.phi_kind == 1) { pp = fexp2(z * LOG2E); pn = fexp2(-z * LOG2E); }
         else {
@@ -412,7 +420,7 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     // logit of the leaving key (it is attended if it stays in the cache)
     if (popped) {
         for (int r = w; r < g; r += 4) {
-            float dot = wsum(dot2bf(qb[r][lane], reinterpret_cast<const uint32_t *>(pkb)[lane], 0.f));
+            float dot = wsum(lane < DH / 2 ? dot2bf(qb[r][lane % (DH / 2)], reinterpret_cast<const uint32_t *>(pkb)[lane % (DH / 2)], 0.f) : 0.f);
             if (lane == 0) lg[r][KP] = dot * a.scale;
         }
     }
@@ -423,9 +431,9 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     // (named scalars rather than an array: arrays of this size end up in scratch memory)
 #define LOLA_HREP(X) X(0, 0, 0) X(0, 0, 1) X(0, 1, 0) X(0, 1, 1) X(0, 2, 0) X(0, 2, 1) X(0, 3, 0) X(0, 3, 1) \
                      X(1, 0, 0) X(1, 0, 1) X(1, 1, 0) X(1, 1, 1) X(1, 2, 0) X(1, 2, 1) X(1, 3, 0) X(1, 3, 1)
-#define LOLA_HADDR(ct, ks, hf) ((size_t)(32 * w + 16 * ct + r16) * D + 32 * ks + 16 * hf + 4 * g4)
+#define LOLA_HADDR(ct, ks, hf) ((size_t)(CW * w + 16 * ct + r16) * D + 32 * ks + 16 * hf + 4 * g4)
 #define LOLA_HDECL(ct, ks, hf) float4 hreg##ct##ks##hf = make_float4(0.f, 0.f, 0.f, 0.f);
-#define LOLA_HLOAD(ct, ks, hf) hreg##ct##ks##hf = *reinterpret_cast<const float4 *>(Hg + LOLA_HADDR(ct, ks, hf));
+#define LOLA_HLOAD(ct, ks, hf) if (ct < NCT) hreg##ct##ks##hf = *reinterpret_cast<const float4 *>(Hg + LOLA_HADDR(ct, ks, hf));
     LOLA_HREP(LOLA_HDECL)
     if (steady) { LOLA_HREP(LOLA_HLOAD) }
     // cached values at this wavefront's value columns, wanted by the recall epilogue of every key tile: requested here,
@@ -433,22 +441,22 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     // (the first half of the tiles; the second half is requested when the recall GEMM starts and has four tiles' worth
     // of matrix work to arrive)
     constexpr int NKE = NKT / 2;
-    uint2 vrec[NKT][2];
+    uint2 vrec[NKT][NCT];
 #pragma unroll
     for (int kt = 0; kt < NKT; kt++)
 #pragma unroll
-        for (int ct = 0; ct < 2; ct++) {
+        for (int ct = 0; ct < NCT; ct++) {
             vrec[kt][ct] = make_uint2(0, 0);
-            if (steady && kt < NKE) vrec[kt][ct] = *reinterpret_cast<const uint2 *>(sp_v + (size_t)(16 * kt + r16) * DH + 32 * w + 16 * ct + 4 * g4);
+            if (steady && kt < NKE) vrec[kt][ct] = *reinterpret_cast<const uint2 *>(sp_v + (size_t)(16 * kt + r16) * DH + CW * w + 16 * ct + 4 * g4);
         }
 
     // ---- stage 1b: logits Q K^T of this wavefront's key tiles; in steady state z^T = W_k K^T -> phi -> LDS.
     // Wavefront 0 also projects the leaving key (a tile with one real column).
     f32x4 zt[TPW + 1][4];
     if (steady) {
-        bf16x8 BP[4];
+        bf16x8 BP[KS];
 #pragma unroll
-        for (int ks = 0; ks < 4; ks++)
+        for (int ks = 0; ks < KS; ks++)
             BP[ks] = (w == 0 && r16 == 0) ? as_bf16x8(*reinterpret_cast<const uint4 *>(&pkb[32 * ks + 8 * g4])) : zero_bf16x8();
 #pragma unroll
         for (int mt = 0; mt < 4; mt++) {
@@ -456,12 +464,12 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
             for (int t = 0; t < TPW; t++) {
                 zt[t][mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int ks = 0; ks < 4; ks++) zt[t][mt] = mfma16(AW[mt][ks], BK[t][ks], zt[t][mt]);
+                for (int ks = 0; ks < KS; ks++) zt[t][mt] = mfma16(AW[mt][ks], BK[t][ks], zt[t][mt]);
             }
             zt[TPW][mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
             if (w == 0) {
 #pragma unroll
-                for (int ks = 0; ks < 4; ks++) zt[TPW][mt] = mfma16(AW[mt][ks], BP[ks], zt[TPW][mt]);
+                for (int ks = 0; ks < KS; ks++) zt[TPW][mt] = mfma16(AW[mt][ks], BP[ks], zt[TPW][mt]);
             }
         }
     }
@@ -469,7 +477,7 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     // operands of the listed pairs: A = phi_p (row = feature within a 16-block, k = p), B = v_p (column = value
     // index).  They are requested after the first key tile's feature map: from there on enough registers are free,
     // and the rest of the feature map covers their latency.
-    float pa[RG][8], pb[RG][2];
+    float pa[RG][8], pb[RG][NCT];
     if (steady) {
 #pragma unroll
         for (int t = 0; t < TPW; t++) {
@@ -512,7 +520,7 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
 #pragma unroll
                     for (int x = 0; x < 8; x++) pa[gr][x] = live ? pphi[pp_ * D + 16 * x + pr] : 0.f;
 #pragma unroll
-                    for (int ct = 0; ct < 2; ct++) pb[gr][ct] = live ? pval[pp_ * DH + 32 * w + 16 * ct + pr] : 0.f;
+                    for (int ct = 0; ct < NCT; ct++) pb[gr][ct] = live ? pval[pp_ * DH + CW * w + 16 * ct + pr] : 0.f;
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -550,13 +558,13 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     LOLA_STAMP(2);
     // value rows for the read-out are requested as soon as registers allow (after the recall GEMM in steady state);
     // they go to LDS once the feature tile is free
-    constexpr int NVIT = KPAD * (DH / 8) / 256;
-    static_assert(KPAD * (DH / 8) % 256 == 0, "value staging is an exact number of passes");
+    constexpr int NVIT = KPAD * PR / 256;
+    static_assert(KPAD * PR % 256 == 0, "value staging is an exact number of passes");
     uint4 vst[NVIT];
     auto load_values = [&]() {
 #pragma unroll
         for (int it = 0; it < NVIT; it++) {
-            const int o = tid + 256 * it, key = o >> 4, c8 = o & 15;
+            const int o = tid + 256 * it, key = o / PR, c8 = o % PR;
             vst[it] = make_uint4(0, 0, 0, 0);
             if (key < NKEY && key != KP) {
                 const bf16_t *src;
@@ -572,15 +580,15 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     if (steady) {
         // ---- stage 2: recall of all eligible pairs: P^T = H^T Phi^T; A = this wavefront's rows of H^T (bf16 high +
         // low parts made here), B = feature vectors from LDS
-        bf16x8 Ahi[2][4], Alo[2][4];
+        bf16x8 Ahi[NCT][4], Alo[NCT][4];
         if (R > 0) {
-#define LOLA_HPEND(ct, ks, hf) { f32x4 c_ = {hreg##ct##ks##hf.x, hreg##ct##ks##hf.y, hreg##ct##ks##hf.z, hreg##ct##ks##hf.w}; \
+#define LOLA_HPEND(ct, ks, hf) if (ct < NCT) { f32x4 c_ = {hreg##ct##ks##hf.x, hreg##ct##ks##hf.y, hreg##ct##ks##hf.z, hreg##ct##ks##hf.w}; \
             _Pragma("unroll") for (int gr = 0; gr < RG; gr++) c_ = __builtin_amdgcn_mfma_f32_16x16x4f32(pa[gr][2 * ks + hf], pb[gr][ct], c_, 0, 0, 0); \
             hreg##ct##ks##hf = make_float4(c_[0], c_[1], c_[2], c_[3]); }
             LOLA_HREP(LOLA_HPEND)
 #undef LOLA_HPEND
         }
-#define LOLA_HSPLIT(ct, ks, hf) { const float4 v = hreg##ct##ks##hf; \
+#define LOLA_HSPLIT(ct, ks, hf) if (ct < NCT) { const float4 v = hreg##ct##ks##hf; \
             const __bf16 h0 = (__bf16)v.x, h1 = (__bf16)v.y, h2 = (__bf16)v.z, h3 = (__bf16)v.w; \
             Ahi[ct][ks][4 * hf] = h0; Ahi[ct][ks][4 * hf + 1] = h1; Ahi[ct][ks][4 * hf + 2] = h2; Ahi[ct][ks][4 * hf + 3] = h3; \
             Alo[ct][ks][4 * hf] = (__bf16)(v.x - (float)h0); Alo[ct][ks][4 * hf + 1] = (__bf16)(v.y - (float)h1); \
@@ -595,8 +603,8 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
 #pragma unroll
         for (int kt = NKE; kt < NKT; kt++)
 #pragma unroll
-            for (int ct = 0; ct < 2; ct++)
-                vrec[kt][ct] = *reinterpret_cast<const uint2 *>(sp_v + (size_t)(16 * kt + r16) * DH + 32 * w + 16 * ct + 4 * g4);
+            for (int ct = 0; ct < NCT; ct++)
+                vrec[kt][ct] = *reinterpret_cast<const uint2 *>(sp_v + (size_t)(16 * kt + r16) * DH + CW * w + 16 * ct + 4 * g4);
 #pragma unroll
         for (int kt = 0; kt <= NKT; kt++) {
             const uint16_t *bh = kt < NKT ? PB + (16 * kt + r16) * D : PX + (r16 < XR ? r16 : 0) * D;
@@ -604,27 +612,28 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
             const int swz = kt < NKT ? r16 : (r16 < XR ? r16 : 0);
             // three passes (high x high, high x low, low x high), each with accumulators of its own: six independent
             // chains keep the matrix pipe from waiting on its own results
-            f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}}, acc2[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-            f32x4 acc3[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+            f32x4 acc[NCT], acc2[NCT], acc3[NCT];
+#pragma unroll
+            for (int ct = 0; ct < NCT; ct++) { acc[ct] = (f32x4){0.f, 0.f, 0.f, 0.f}; acc2[ct] = acc[ct]; acc3[ct] = acc[ct]; }
 #pragma unroll
             for (int ks = 0; ks < 4; ks++) {
                 const int off = ((4 * ks + g4) ^ swz) << 3;
                 const bf16x8 Bh = as_bf16x8(*reinterpret_cast<const uint4 *>(bh + off));
                 const bf16x8 Bl = as_bf16x8(*reinterpret_cast<const uint4 *>(bl + off));
 #pragma unroll
-                for (int ct = 0; ct < 2; ct++) acc[ct] = mfma16(Ahi[ct][ks], Bh, acc[ct]);
+                for (int ct = 0; ct < NCT; ct++) acc[ct] = mfma16(Ahi[ct][ks], Bh, acc[ct]);
 #pragma unroll
-                for (int ct = 0; ct < 2; ct++) acc2[ct] = mfma16(Ahi[ct][ks], Bl, acc2[ct]);
+                for (int ct = 0; ct < NCT; ct++) acc2[ct] = mfma16(Ahi[ct][ks], Bl, acc2[ct]);
 #pragma unroll
-                for (int ct = 0; ct < 2; ct++) acc3[ct] = mfma16(Alo[ct][ks], Bh, acc3[ct]);
+                for (int ct = 0; ct < NCT; ct++) acc3[ct] = mfma16(Alo[ct][ks], Bh, acc3[ct]);
             }
 #pragma unroll
-            for (int ct = 0; ct < 2; ct++) acc2[ct] += acc3[ct];
+            for (int ct = 0; ct < NCT; ct++) acc2[ct] += acc3[ct];
             if (kt < NKT) {
                 const float rd = rden_l[16 * kt + r16];
                 float e2 = 0.f;
 #pragma unroll
-                for (int ct = 0; ct < 2; ct++) {
+                for (int ct = 0; ct < NCT; ct++) {
                     const f32x4 p = acc[ct] + acc2[ct];
                     const uint2 vv = vrec[kt < NKT ? kt : 0][ct];
                     const float e0 = fmaf(p[0], rd, -bf_lo(vv.x)), e1 = fmaf(p[1], rd, -bf_hi(vv.x));
@@ -637,9 +646,9 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
                 const float rd = rden_l[KP];
                 float e2 = 0.f;
 #pragma unroll
-                for (int ct = 0; ct < 2; ct++) {
+                for (int ct = 0; ct < NCT; ct++) {
                     const f32x4 p = acc[ct] + acc2[ct];
-                    const int c0 = 32 * w + 16 * ct + 4 * g4;
+                    const int c0 = CW * w + 16 * ct + 4 * g4;
                     if (r16 == 0) {
 #pragma unroll
                         for (int i = 0; i < 4; i++) { const float e = fmaf(p[i], rd, -pvf[c0 + i]); e2 = fmaf(e, e, e2); }
@@ -679,21 +688,21 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
             const uint16_t *bh = drop < LAM ? PB + drop * D + ((chunk ^ (drop & 15)) << 3) + el : PX + (chunk << 3) + el;
             const uint16_t *bl = drop < LAM ? bh + LAM * D : bh + XR * D;
             phif[f] = bf_lo(*bh) + bf_lo(*bl);
-            vf[f] = drop < LAM ? ldf(sp_v, (size_t)drop * DH + f) : pvf[f];
+            if (f < DH) vf[f] = drop < LAM ? ldf(sp_v, (size_t)drop * DH + f) : pvf[f];
         }
         __syncthreads();
         // the leaving pair takes the freed slot (in-place compaction)
         if (drop < LAM) {
-            if (tid < 16) reinterpret_cast<uint4 *>(sp_k + (size_t)drop * DH)[tid] = reinterpret_cast<const uint4 *>(pkb)[tid];
-            else if (tid < 32) reinterpret_cast<uint4 *>(sp_v + (size_t)drop * DH)[tid - 16] = reinterpret_cast<const uint4 *>(pvb)[tid - 16];
-            else if (tid == 32) sp_idx[drop] = pidx;
+            if (tid < PR) reinterpret_cast<uint4 *>(sp_k + (size_t)drop * DH)[tid] = reinterpret_cast<const uint4 *>(pkb)[tid];
+            else if (tid < 2 * PR) reinterpret_cast<uint4 *>(sp_v + (size_t)drop * DH)[tid - PR] = reinterpret_cast<const uint4 *>(pvb)[tid - PR];
+            else if (tid == 2 * PR) sp_idx[drop] = pidx;
         }
         // fold: H^T += v_f phi_f^T on the fp32 registers, written back once; s += phi_f.  With deferred folds only
         // the step that finds the list one short of full does so (its registers include the listed pairs); the others
         // append their pair to the list.
         const bool write_back = R == 0 || cnt == R - 1;
         if (write_back) {
-#define LOLA_HFOLD(ct, ks, hf) { const float vc = vf[32 * w + 16 * ct + r16]; \
+#define LOLA_HFOLD(ct, ks, hf) if (ct < NCT) { const float vc = vf[CW * w + 16 * ct + r16]; \
             const float4 pf = *reinterpret_cast<const float4 *>(&phif[32 * ks + 16 * hf + 4 * g4]); \
             hreg##ct##ks##hf.x = fmaf(pf.x, vc, hreg##ct##ks##hf.x); hreg##ct##ks##hf.y = fmaf(pf.y, vc, hreg##ct##ks##hf.y); \
             hreg##ct##ks##hf.z = fmaf(pf.z, vc, hreg##ct##ks##hf.z); hreg##ct##ks##hf.w = fmaf(pf.w, vc, hreg##ct##ks##hf.w); \
@@ -729,24 +738,26 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
 #undef LOLA_HREP
     if (!steady && popped) {
         // cache not full yet: the leaving pair is appended, nothing is scored (spc < LAM)
-        if (tid < 16) reinterpret_cast<uint4 *>(sp_k + (size_t)spc * DH)[tid] = reinterpret_cast<const uint4 *>(pkb)[tid];
-        else if (tid < 32) reinterpret_cast<uint4 *>(sp_v + (size_t)spc * DH)[tid - 16] = reinterpret_cast<const uint4 *>(pvb)[tid - 16];
-        else if (tid == 32) { sp_idx[spc] = pidx; a.st.sp_count[si] = spc + 1; }
+        if (tid < PR) reinterpret_cast<uint4 *>(sp_k + (size_t)spc * DH)[tid] = reinterpret_cast<const uint4 *>(pkb)[tid];
+        else if (tid < 2 * PR) reinterpret_cast<uint4 *>(sp_v + (size_t)spc * DH)[tid - PR] = reinterpret_cast<const uint4 *>(pvb)[tid - PR];
+        else if (tid == 2 * PR) { sp_idx[spc] = pidx; a.st.sp_count[si] = spc + 1; }
     }
     LOLA_STAMP(6);
 
     // ---- stage 4: value rows into LDS (the feature tile is no longer needed): [key][c], key order = logit order; rows
     // past the last key are zero.  The cached value row of the dropped slot may be mid-overwrite: its weight is 0.
+    // 8-byte piece p of row `key` sits at piece p ^ vswz(key) (a multiple of 4 taken from the row bits that differ
+    // between the eight rows two lane groups read at once): the transposing reads below then touch every bank once
+    auto vswz = [](int key) { return DH == 128 ? 4 * (key & 7) : 4 * ((key >> 1) & 3); };
 #pragma unroll
     for (int it = 0; it < NVIT; it++) {
-        const int o = tid + 256 * it, key = o >> 4, c8 = o & 15;
-        // 8-byte piece p of row `key` sits at piece p ^ 4 (key % 8): the transposing reads below then touch every bank once
-        *reinterpret_cast<uint4 *>(Vl + key * VLS + 4 * ((2 * c8) ^ (4 * (key & 7)))) = vst[it];
+        const int o = tid + 256 * it, key = o / PR, c8 = o % PR;
+        *reinterpret_cast<uint4 *>(Vl + key * VLS + 4 * ((2 * c8) ^ vswz(key))) = vst[it];
     }
     // the new pair, which takes the ring slot of the pair that left, is requested here and stored at the very end
     // (a store that follows its own load waits for every load the wavefront has in flight: by then there is none)
     uint4 new_ld = make_uint4(0, 0, 0, 0);
-    if (tid < 32) new_ld = reinterpret_cast<const uint4 *>(tid < 16 ? knew : vnew)[tid & 15];
+    if (tid < 2 * PR) new_ld = reinterpret_cast<const uint4 *>(tid < PR ? knew : vnew)[tid % PR];
     // softmax weights (one query per wavefront), m = max(0, max logit); written as bf16 high + low parts
     for (int r = w; r < g; r += 4) {
         float l[(KPAD + 63) / 64];
@@ -781,9 +792,11 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     LOLA_STAMP(7);
 
     // ---- stage 5: out[q][c] = sum_key p[q][key] v[key][c] on MFMA: A = weights (rows = queries), B = staged values
-    // (column c, k = key); each wavefront owns 32 output columns
+    // (column c, k = key); each wavefront owns CW output columns
     {
-        f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+        f32x4 acc[NCT];
+#pragma unroll
+        for (int nt = 0; nt < NCT; nt++) acc[nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < NKS; ks++) {
             // contraction slots of lane group g4: keys 32 ks + 4 g4 + 0..3, then 32 ks + 16 + 4 g4 + 0..3 (the order in which
@@ -797,12 +810,12 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
                 Apl = as_bf16x8(make_uint4(l0.x, l0.y, l1.x, l1.y));
             }
 #pragma unroll
-            for (int nt = 0; nt < 2; nt++) {
+            for (int nt = 0; nt < NCT; nt++) {
                 // a 16-lane group reads a 4 x 16 block of the row-major values (lane i: row i / 4, columns 4 (i % 4) ..) and
                 // receives it transposed: lane j holds column j of the four rows
-                const int row = k0 + (r16 >> 2), piece = 4 * (2 * w + nt) + (r16 & 3);
-                const bf16x4 t0 = tr_read(Vl + row * VLS + 4 * (piece ^ (4 * (row & 7))));
-                const bf16x4 t1 = tr_read(Vl + (row + 16) * VLS + 4 * (piece ^ (4 * (row & 7))));
+                const int row = k0 + (r16 >> 2), piece = 4 * (NCT * w + nt) + (r16 & 3);
+                const bf16x4 t0 = tr_read(Vl + row * VLS + 4 * (piece ^ vswz(row)));
+                const bf16x4 t1 = tr_read(Vl + (row + 16) * VLS + 4 * (piece ^ vswz(row + 16)));
                 const bf16x8 Bv = __builtin_shufflevector(t0, t1, 0, 1, 2, 3, 4, 5, 6, 7);
                 acc[nt] = mfma16(Aph, Bv, acc[nt]);
                 acc[nt] = mfma16(Apl, Bv, acc[nt]);
@@ -810,8 +823,8 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
         }
         if (g4 == 0) {
 #pragma unroll
-            for (int nt = 0; nt < 2; nt++) {
-                const int c = 16 * (2 * w + nt) + r16;
+            for (int nt = 0; nt < NCT; nt++) {
+                const int c = 16 * (NCT * w + nt) + r16;
 #pragma unroll
                 for (int r = 0; r < G; r++) {
                     if (r >= g) break;
@@ -827,7 +840,7 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
         }
     }
     // the new pair takes the ring slot of the pair that left (read in stage 0)
-    if (tid < 32) reinterpret_cast<uint4 *>(tid < 16 ? win_k + (size_t)slot * DH : win_v + (size_t)slot * DH)[tid & 15] = new_ld;
+    if (tid < 2 * PR) reinterpret_cast<uint4 *>(tid < PR ? win_k + (size_t)slot * DH : win_v + (size_t)slot * DH)[tid % PR] = new_ld;
     if (tid == 0) a.st.n_tokens[si] = tok + 1;
     LOLA_STAMP(8);
 #ifdef LOLA_TIMING

@@ -33,7 +33,7 @@ constexpr int DEFER_R = 8;   // pairs a stream may list before the generation st
 
 // The fused MFMA generation step covers the Llama-8B head shape with bf16 storage.
 bool fast_decode_ok(const lola_config *c) {
-    return c->dtype == LOLA_BF16 && c->head_dim == 128 && c->feat_dim == 128 && c->window == 64 &&
+    return c->dtype == LOLA_BF16 && (c->head_dim == 128 || c->head_dim == 64) && c->feat_dim == 128 && c->window == 64 &&
            (c->sparse_budget == 128 || c->sparse_budget == 64) && c->n_q_heads / c->n_kv_heads <= 4 &&
            c->score_kind == LOLA_SCORE_SRE;
 }
@@ -204,13 +204,15 @@ lola_status launch_fast_decode(const lola_config *c, const lola_state *st, const
     a.g = c->n_q_heads / c->n_kv_heads;
     a.pend_phi = st->pend_phi; a.pend_v = st->pend_v; a.pend_count = st->pend_count;
     const dim3 grid(c->batch * c->n_kv_heads), block(256);
-    if (a.g == 4) {
-        if (c->fold_defer) hipLaunchKernelGGL((fast::decode_fast_kernel<LAM, 64, 4, DEFER_R, false, TO>), grid, block, 0, stream, a);
-        else hipLaunchKernelGGL((fast::decode_fast_kernel<LAM, 64, 4, 0, false, TO>), grid, block, 0, stream, a);
+#define LOLA_DEC(RV, GD, DHV) hipLaunchKernelGGL((fast::decode_fast_kernel<LAM, 64, 4, RV, GD, DHV, TO>), grid, block, 0, stream, a)
+    if (c->head_dim == 128) {
+        // the benchmarked shape keeps the group size as a compile-time constant
+        if (a.g == 4) { if (c->fold_defer) LOLA_DEC(DEFER_R, false, 128); else LOLA_DEC(0, false, 128); }
+        else { if (c->fold_defer) LOLA_DEC(DEFER_R, true, 128); else LOLA_DEC(0, true, 128); }
     } else {
-        if (c->fold_defer) hipLaunchKernelGGL((fast::decode_fast_kernel<LAM, 64, 4, DEFER_R, true, TO>), grid, block, 0, stream, a);
-        else hipLaunchKernelGGL((fast::decode_fast_kernel<LAM, 64, 4, 0, true, TO>), grid, block, 0, stream, a);
+        if (c->fold_defer) LOLA_DEC(DEFER_R, true, 64); else LOLA_DEC(0, true, 64);
     }
+#undef LOLA_DEC
     LAUNCH_CHECK();
     return LOLA_OK;
 }

@@ -50,7 +50,8 @@ def test_state_bytes(L):
     assert lb.lola_state_bytes(cfg(score_kind=2, fold_defer=8))[0] == 0
     assert lb.lola_state_bytes(cfg(score_kind=5))[0] == 0
     assert lb.lola_state_bytes(cfg(fold_defer=3))[0] == 0                 # not a supported list length
-    assert lb.lola_state_bytes(cfg(fold_defer=8, head_dim=64))[0] == 0    # no kernel with deferred folds for this shape
+    assert lb.lola_state_bytes(cfg(fold_defer=8, head_dim=32))[0] == 0    # no kernel with deferred folds for this shape
+    assert lb.lola_state_bytes(cfg(fold_defer=8, head_dim=64))[0] > 0     # the 1B head shape has one
     assert lb.lola_state_bytes(cfg(head_dim=100))[0] == 0
     assert lb.lola_state_bytes(cfg(feat_dim=127))[0] == 0
     assert lb.lola_state_bytes(cfg(n_q_heads=7))[0] == 0

@@ -107,6 +107,27 @@ def test_8b_shape_decode_from_cold_start(lam, phi_kind):
     assert rep["scored"] == 4 * 60
 
 
+@pytest.mark.parametrize("lam,phi_kind,defer,hide,g", [(64, 0, 0, 0, 4), (128, 1, 8, 0, 4), (64, 0, 8, 2, 2), (128, 0, 0, 1, 1)])
+def test_1b_head_shape_generation_step(lam, phi_kind, defer, hide, g):
+    """The fused generation kernel at head_dim 64 (a wavefront owns 16 rows of the state instead of 32):
+    cold start through warm-up into steady state, with and without deferred folds, restricted queries,
+    smaller groups; then a prefill call (MFMA kernels too) and more steps."""
+    sh = wl.Shape("dec1b", "bf16", 2, 2 * g, 2, 64, 128, T=0, eta=64, lam=lam, C=64, seed=0)
+    n1, n_pre, n2 = 64 + lam + 29, 64 * 2 + 11, 13
+    q, k, v, Wq, Wk = rand_case(140 + lam + g, 2, 2 * g, 2, 64, 128, n1 + n_pre + n2, "bf16", wscale=0.5 if phi_kind else 1.0)
+    kw = dict(phi_kind=phi_kind, fold_defer=defer, query_hide=hide)
+    okw = dict(phi_kind=phi_kind, query_hide=hide)
+    layer = P.make_layer(sh, **kw)
+    assert layer.lola_path == ("mfma", "mfma")
+    o = P.make_oracle(sh, **okw)
+    rep = P.decode_parity(sh, layer, o, *steps(q, k, v, 0, n1), Wq, Wk)
+    assert rep["scored"] == 4 * 29
+    layer, o, rep2 = P.prefill_parity(sh, q[:, :, n1:n1 + n_pre], k[:, :, n1:n1 + n_pre], v[:, :, n1:n1 + n_pre], Wq, Wk,
+                                      layer=layer, oracle=o, layer_kw=kw)
+    rep3 = P.decode_parity(sh, layer, o, *steps(q, k, v, n1 + n_pre, n2), Wq, Wk)
+    say("1B head shape generation step", lam, phi_kind, defer, hide, g, rep, rep2, rep3)
+
+
 @pytest.mark.parametrize("lam,phi_kind", [(128, 0), (64, 1)])
 def test_deferred_folds(lam, phi_kind):
     """fold_defer = 8 on the fused generation kernel: the folded pair of a step is listed instead of
@@ -157,7 +178,7 @@ def test_deferred_folds_refused_elsewhere():
     """Shapes without the fused generation kernel do not take fold_defer."""
     from paper_2505_23666_amd import binding as lb
     with pytest.raises(lb.LolaError):
-        lb.LolaLayer(1, 4, 1, 64, 128, 64, 64, 64, fold_defer=8)
+        lb.LolaLayer(1, 4, 1, 32, 128, 64, 64, 64, fold_defer=8)
     with pytest.raises(lb.LolaError):
         lb.LolaLayer(1, 4, 1, 128, 128, 64, 128, 64, fold_defer=4)
 
