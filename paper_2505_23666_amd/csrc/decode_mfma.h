@@ -301,19 +301,18 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     for (int t = 0; t < TPW; t++)
 #pragma unroll
         for (int ks = 0; ks < KS; ks++) BK[t][ks] = ld_bf16x8(sp_k + (size_t)(16 * (w + 4 * t) + r16) * DH + 32 * ks + 8 * g4);
-    // (everything requested so far is independent of the token counter, whose own load is still on its way; the
-    // ring slot enters only from here on)
-    uint4 p_ld = make_uint4(0, 0, 0, 0);
-    if (popped && tid < 2 * PR)   // PR threads fetch the leaving key row, PR the value row (16 bytes each)
-        p_ld = reinterpret_cast<const uint4 *>(tid < PR ? win_k + (size_t)slot * DH : win_v + (size_t)slot * DH)[tid % PR];
-    // window keys of this wavefront's tile; the ring slot of the new token is taken from the input
-    bf16x8 BWin[KS];
-    {
-        const int row = 16 * (w < NWT ? w : 0) + r16;
-        const bf16_t *src = row == slot ? knew : win_k + (size_t)row * DH;
+    // window keys of this wavefront's tile as they stand in memory, and the new key: the row in the new token's ring
+    // slot is the key of the pair that leaves; it is swapped for the new key once the token counter is known, so that
+    // nothing requested here waits for that counter (whose own load is still on its way)
+    bf16x8 BWin[KS], KN[KS];
 #pragma unroll
-        for (int ks = 0; ks < KS; ks++) BWin[ks] = ld_bf16x8(src + 32 * ks + 8 * g4);
+    for (int ks = 0; ks < KS; ks++) {
+        BWin[ks] = ld_bf16x8(win_k + (size_t)(16 * (w < NWT ? w : 0) + r16) * DH + 32 * ks + 8 * g4);
+        KN[ks] = ld_bf16x8(knew + 32 * ks + 8 * g4);
     }
+    // the value row of the leaving pair (PR threads, 16 bytes each) is wanted much later
+    uint4 p_ld = make_uint4(0, 0, 0, 0);
+    if (popped && tid < PR) p_ld = reinterpret_cast<const uint4 *>(win_v + (size_t)slot * DH)[tid];
     LOLA_STAMP(9);
     if (tid < D / 4) {
         float4 sv = s_ld;
@@ -325,12 +324,15 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
         reinterpret_cast<float4 *>(s_l)[tid] = sv;
     }
     if (tid < LAM) idx_l[tid] = idx_ld;
-    if (popped && tid < 2 * PR) {
-        reinterpret_cast<uint4 *>(tid < PR ? pkb : pvb)[tid % PR] = p_ld;
-        if (tid >= PR) {
-            float *d = pvf + 8 * (tid - PR);
-            d[0] = bf_lo(p_ld.x); d[1] = bf_hi(p_ld.x); d[2] = bf_lo(p_ld.y); d[3] = bf_hi(p_ld.y);
-            d[4] = bf_lo(p_ld.z); d[5] = bf_hi(p_ld.z); d[6] = bf_lo(p_ld.w); d[7] = bf_hi(p_ld.w);
+    {
+        // the lanes that hold the ring slot's row hand the leaving key over and take the new key
+        const bool mine = w < NWT && 16 * w + r16 == slot;
+        if (mine) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ks++) {
+                if (popped) *reinterpret_cast<uint4 *>(&pkb[32 * ks + 8 * g4]) = __builtin_bit_cast(uint4, BWin[ks]);
+                BWin[ks] = KN[ks];
+            }
         }
     }
     if (tid >= 64 && tid < 64 + g * PR) reinterpret_cast<uint4 *>(qb)[tid - 64] = q_ld;
@@ -555,6 +557,12 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
             }
         }
     }
+    if (popped && tid < PR) {   // (read by the recall epilogue and the fold, behind the next barrier)
+        reinterpret_cast<uint4 *>(pvb)[tid] = p_ld;
+        float *d = pvf + 8 * tid;
+        d[0] = bf_lo(p_ld.x); d[1] = bf_hi(p_ld.x); d[2] = bf_lo(p_ld.y); d[3] = bf_hi(p_ld.y);
+        d[4] = bf_lo(p_ld.z); d[5] = bf_hi(p_ld.z); d[6] = bf_lo(p_ld.w); d[7] = bf_hi(p_ld.w);
+    }
     LOLA_STAMP(2);
     // value rows for the read-out are requested as soon as registers allow (after the recall GEMM in steady state);
     // they go to LDS once the feature tile is free
@@ -729,8 +737,8 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
             if (lane == 0) dotqf[r] = acc;
         }
     } else {
+        __syncthreads();   // logits of all wavefronts and the leaving pair's value row are in LDS (the steady path has passed barriers of its own)
         load_values();
-        __syncthreads();   // logits of all wavefronts are in LDS (the steady path has passed barriers of its own)
     }
 #undef LOLA_HDECL
 #undef LOLA_HLOAD
