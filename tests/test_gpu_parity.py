@@ -422,6 +422,32 @@ def test_random_small_shapes():
         say("   ", rep2)
 
 
+def test_random_small_shapes_with_options():
+    """Sixteen more seeded random shapes with the options switched on at random: restricted queries and
+    the query-dependent scores, including windows and budgets of zero."""
+    g = wl.rng(777, 0)
+    for case in range(16):
+        dtype = "bf16" if case % 2 else "f32"
+        d = int(g.choice([32, 64])); D = int(g.choice([8, 16, 32, 64]))
+        Hkv = int(g.integers(1, 3)); grp = int(g.integers(1, 4)); Hq = Hkv * grp
+        B = int(g.integers(1, 3))
+        eta = int(g.integers(0, 14)); lam = int(g.integers(0, 14)); C_ = int(g.integers(1, 18))
+        T = int(g.integers(2, 70)); nd = int(g.integers(1, 6))
+        hide = int(g.integers(0, 4)); sk = int(g.integers(0, 5))
+        say("random shape with options", case, dict(dtype=dtype, B=B, Hq=Hq, Hkv=Hkv, d=d, D=D, eta=eta, lam=lam, C=C_, T=T, nd=nd,
+                                                   hide=hide, score_kind=sk))
+        sh = wl.Shape(f"rndo{case}", dtype, B, Hq, Hkv, d, D, T, eta, lam, C_, seed=0)
+        q, k, v, Wq, Wk = rand_case(6000 + case, B, Hq, Hkv, d, D, T + nd, dtype)
+        kw = dict(query_hide=hide, score_kind=sk)
+        cut = T // 2
+        layer, o = None, None
+        for a_, b_ in ((0, cut), (cut, T)):
+            layer, o, rep = P.prefill_parity(sh, q[:, :, a_:b_], k[:, :, a_:b_], v[:, :, a_:b_], Wq, Wk, layer=layer,
+                                             oracle=o, layer_kw=kw)
+        rep2 = P.decode_parity(sh, layer, o, *steps(q, k, v, T, nd), Wq, Wk)
+        say("   ", rep2)
+
+
 def test_generation_steps_replayed_from_a_hip_graph():
     """The library only enqueues kernels on the caller's stream (no allocation, no memset, no
     synchronisation), so a generation step can be captured into a HIP graph.  Every replay is
