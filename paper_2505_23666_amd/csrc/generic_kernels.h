@@ -37,6 +37,31 @@ __device__ __forceinline__ float block_max(float v, float *red) {
     return t;
 }
 
+// sum_i row[i] * x[i] in index order (same rounding as the element-wise loop), the row fetched 16 bytes at a time;
+// n is a multiple of 8 and the row is 16-byte aligned (head_dim is 32, 64, 128 or 256)
+__device__ __forceinline__ float dot_row(const bf16_t *row, const float *x, int n, float acc) {
+    const uint4 *r4 = reinterpret_cast<const uint4 *>(row);
+    for (int i = 0; i < n / 8; i++) {
+        const uint4 u = r4[i];
+        const uint32_t wds[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            acc = fmaf(__uint_as_float(wds[e] << 16), x[8 * i + 2 * e], acc);
+            acc = fmaf(__uint_as_float(wds[e] & 0xFFFF0000u), x[8 * i + 2 * e + 1], acc);
+        }
+    }
+    return acc;
+}
+__device__ __forceinline__ float dot_row(const float *row, const float *x, int n, float acc) {
+    const float4 *r4 = reinterpret_cast<const float4 *>(row);
+    for (int i = 0; i < n / 4; i++) {
+        const float4 u = r4[i];
+        acc = fmaf(u.x, x[4 * i], acc); acc = fmaf(u.y, x[4 * i + 1], acc);
+        acc = fmaf(u.z, x[4 * i + 2], acc); acc = fmaf(u.w, x[4 * i + 3], acc);
+    }
+    return acc;
+}
+
 // phi of R rows.  xs [R][d] (LDS, fp32 copies of the stored vectors), W [m][d] (global, row j = w_j), result
 // ph [R][D] (LDS).  Workgroup-wide; ends with a barrier.
 template <typename T>
@@ -45,9 +70,7 @@ __device__ void phi_rows(const Dims &dm, const T *W, const float *xs, float *ph,
     for (int p = tid; p < R * m; p += NT) {
         int r = p / m, j = p - r * m;
         const float *x = xs + r * d;
-        float z = 0.f;
-        for (int i = 0; i < d; i++) z = fmaf(ldf(W, (size_t)j * d + i), x[i], z);
-        ph[r * D + j] = z;
+        ph[r * D + j] = dot_row(W + (size_t)j * d, x, d, 0.f);
     }
     __syncthreads();
     const int w = tid / WAVE, lane = tid % WAVE;
@@ -101,15 +124,29 @@ __device__ void score_rows(const Dims &dm, const float *H, const float *s, const
         if (lane == 0) den[r] = a;
     }
     __syncthreads();
+    // thread (c, rg) takes rows rg, rg + nrg, ...; eight rows share one pass over row c of H^T, so that a value of H
+    // fetched from memory feeds eight multiply-adds (the features come from LDS, the same word for all c)
     const int c = tid % d, rg = tid / d, nrg = NT / d;
-    for (int r = rg; r < R; r += nrg) {
-        const float *p = ph + r * D;
-        float acc = 0.f;
-        for (int f = 0; f < D; f++) acc = fmaf(p[f], H[(size_t)c * D + f], acc);
-        float dn = den[r];
-        float pred = dn > 0.f ? acc / dn : 0.f;
-        float e = pred - vs[r * d + c];
-        err[r * d + c] = e * e;
+    for (int r0 = rg; r0 < R; r0 += 8 * nrg) {
+        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (int f = 0; f < D; f++) {
+            const float hv = H[(size_t)c * D + f];
+#pragma unroll
+            for (int i = 0; i < 8; i++) {
+                const int r = r0 + i * nrg;
+                if (r < R) acc[i] = fmaf(ph[r * D + f], hv, acc[i]);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+            const int r = r0 + i * nrg;
+            if (r < R) {
+                const float dn = den[r];
+                const float pred = dn > 0.f ? acc[i] / dn : 0.f;
+                const float e = pred - vs[r * d + c];
+                err[r * d + c] = e * e;
+            }
+        }
     }
     __syncthreads();
     for (int r = w; r < R; r += NW) {
@@ -292,8 +329,7 @@ __global__ __launch_bounds__(NT) void decode_kernel(DecodeArgs<T> a) {
         float lmax = 0.f;     // m = max(0, max logit): the linear terms carry weight exp(-m) <= 1
         for (int i = tid; i < nk; i += NT) {
             const T *kr = i < spc ? sp_k + (size_t)i * d : win_k + (size_t)(i - spc) * d;
-            float dot = 0.f;
-            for (int j = 0; j < d; j++) dot = fmaf(xs[j], ldf(kr, j), dot);
+            float dot = dot_row(kr, xs, d, 0.f);
             dot *= dm.scale;
             if (i >= spc && sk) wlg[i - spc] = dot;
             if (i < spc && (dm.hide & 2)) dot = -INFINITY;   // restricted query: the sparse cache is not read
@@ -756,9 +792,7 @@ __global__ __launch_bounds__(NT) void attend_kernel(PrefillArgs<T> a) {
             if (ok) {
                 const T *kr = vr < P ? pK + (size_t)vr * d : kc + (size_t)(vr - P) * d;
                 const float *qv = qs + qi * d;
-                float dot = 0.f;
-                for (int c = 0; c < d; c++) dot = fmaf(qv[c], ldf(kr, c), dot);
-                l = dot * dm.scale;
+                l = dot_row(kr, qv, d, 0.f) * dm.scale;
             }
             pw[qi * nkmax + key] = l;
         }
