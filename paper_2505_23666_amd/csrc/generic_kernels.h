@@ -129,12 +129,28 @@ __device__ void score_rows(const Dims &dm, const float *H, const float *s, const
     const int c = tid % d, rg = tid / d, nrg = NT / d;
     for (int r0 = rg; r0 < R; r0 += 8 * nrg) {
         float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        for (int f = 0; f < D; f++) {
-            const float hv = H[(size_t)c * D + f];
+        if ((D & 3) == 0) {   // four features per load of H and of the LDS rows (index order kept)
+            const float4 *H4 = reinterpret_cast<const float4 *>(H + (size_t)c * D);
+            for (int f4 = 0; f4 < D / 4; f4++) {
+                const float4 hv = H4[f4];
 #pragma unroll
-            for (int i = 0; i < 8; i++) {
-                const int r = r0 + i * nrg;
-                if (r < R) acc[i] = fmaf(ph[r * D + f], hv, acc[i]);
+                for (int i = 0; i < 8; i++) {
+                    const int r = r0 + i * nrg;
+                    if (r < R) {
+                        const float4 pv = *reinterpret_cast<const float4 *>(&ph[r * D + 4 * f4]);
+                        acc[i] = fmaf(pv.x, hv.x, acc[i]); acc[i] = fmaf(pv.y, hv.y, acc[i]);
+                        acc[i] = fmaf(pv.z, hv.z, acc[i]); acc[i] = fmaf(pv.w, hv.w, acc[i]);
+                    }
+                }
+            }
+        } else {
+            for (int f = 0; f < D; f++) {
+                const float hv = H[(size_t)c * D + f];
+#pragma unroll
+                for (int i = 0; i < 8; i++) {
+                    const int r = r0 + i * nrg;
+                    if (r < R) acc[i] = fmaf(ph[r * D + f], hv, acc[i]);
+                }
             }
         }
 #pragma unroll
@@ -191,7 +207,7 @@ struct DecodeArgs {
 
 template <typename T, typename TO>
 __global__ __launch_bounds__(NT) void decode_kernel(DecodeArgs<T> a) {
-    extern __shared__ float smem[];
+    extern __shared__ __attribute__((aligned(16))) float smem[];
     const Dims &dm = a.dm;
     const int tid = threadIdx.x, d = dm.d, D = dm.D, m = dm.m, eta = dm.eta, lam = dm.lam, R = a.R;
     const int si = blockIdx.x, b = si / dm.Hkv, h = si % dm.Hkv;
@@ -485,7 +501,7 @@ __global__ __launch_bounds__(NT) void finalize_kernel(PrefillArgs<T> a) {
 // One wavefront owns a key and adds its terms in a fixed order (results do not depend on timing).
 template <typename T>
 __global__ __launch_bounds__(NT) void band_score_kernel(PrefillArgs<T> a) {
-    extern __shared__ float smem[];
+    extern __shared__ __attribute__((aligned(16))) float smem[];
     const Dims &dm = a.dm;
     const int tid = threadIdx.x, d = dm.d, D = dm.D, m = dm.m, eta = dm.eta, lam = dm.lam, R = a.R2;
     const int si = blockIdx.y, b = si / dm.Hkv, h = si % dm.Hkv, x0 = blockIdx.x * R;
@@ -725,7 +741,7 @@ __device__ void scan_chunk(const PrefillArgs<T> &a, const int si, const int j, i
 // Sequential evolution of one stream's memories over the chunks [j0, j1).
 template <typename T>
 __global__ __launch_bounds__(NT) void scan_kernel(PrefillArgs<T> a) {
-    extern __shared__ float smem[];
+    extern __shared__ __attribute__((aligned(16))) float smem[];
     const int si = blockIdx.x;
     int spc = a.st.sp_count[si];
     int j = a.scan_mode == 2 ? a.next_j[si] : a.j0;
@@ -746,7 +762,7 @@ __global__ __launch_bounds__(NT) void scan_kernel(PrefillArgs<T> a) {
 // Outputs of one chunk of one query head from the snapshot taken at the chunk's entry.
 template <typename T, typename TO>
 __global__ __launch_bounds__(NT) void attend_kernel(PrefillArgs<T> a) {
-    extern __shared__ float smem[];
+    extern __shared__ __attribute__((aligned(16))) float smem[];
     const Dims &dm = a.dm;
     const int tid = threadIdx.x, d = dm.d, D = dm.D, m = dm.m, eta = dm.eta, lam = dm.lam, C = dm.C, QT = a.QT;
     const int P = lam + eta, nkmax = lam + eta + C;
