@@ -845,7 +845,15 @@ __global__ __launch_bounds__(NT) void attend_kernel(PrefillArgs<T> a) {
             }
             float lin = 0.f;
             const float *pq = phq + qi * D;
-            for (int f = 0; f < D; f++) lin = fmaf(pq[f], Hj[(size_t)c * D + f], lin);
+            if ((D & 3) == 0) {
+                const float4 *H4 = reinterpret_cast<const float4 *>(Hj + (size_t)c * D), *p4 = reinterpret_cast<const float4 *>(pq);
+                for (int f4 = 0; f4 < D / 4; f4++) {
+                    const float4 hv = H4[f4], pv = p4[f4];
+                    lin = fmaf(pv.x, hv.x, lin); lin = fmaf(pv.y, hv.y, lin); lin = fmaf(pv.z, hv.z, lin); lin = fmaf(pv.w, hv.w, lin);
+                }
+            } else {
+                for (int f = 0; f < D; f++) lin = fmaf(pq[f], Hj[(size_t)c * D + f], lin);
+            }
             const float elin = (dm.hide & 1) ? 0.f : expf(-rmax[qi]);
             stf(oh, (size_t)(i0 + qi) * d + c, fmaf(elin, lin, num) / (rsum[qi] + elin * rlin[qi]));
         }
