@@ -8,7 +8,9 @@
 // eligible set / top-lambda / fold Sec. 3 (E_t, G_t, S_t, H_t equations); output Sec. 3 (y_t
 // equation); chunk schedule Sec. 3 "Chunkwise Inference".
 #pragma once
+#include <type_traits>
 #include "lola_common.h"
+#include "decode_mfma.h"   // MFMA primitives (operand types, bf16 high/low split)
 
 namespace lola {
 namespace generic {
@@ -67,10 +69,43 @@ __device__ __forceinline__ float dot_row(const float *row, const float *x, int n
 template <typename T>
 __device__ void phi_rows(const Dims &dm, const T *W, const float *xs, float *ph, int R) {
     const int tid = threadIdx.x, d = dm.d, m = dm.m, D = dm.D;
-    for (int p = tid; p < R * m; p += NT) {
-        int r = p / m, j = p - r * m;
-        const float *x = xs + r * d;
-        ph[r * D + j] = dot_row(W + (size_t)j * d, x, d, 0.f);
+    if (std::is_same<T, bf16_t>::value && R >= 8 && (m & 15) == 0) {
+        // projections on MFMA (bf16 storage: the fp32 copies in LDS are exact bf16 values, products are exact, fp32
+        // accumulation): tile = 16 projections x 16 rows, A = rows of W from memory, B = the vectors from LDS
+        const int w = tid / WAVE, lane = tid % WAVE, r16 = lane & 15, g4 = lane >> 4;
+        const int njt = m / 16, ntile = ((R + 15) / 16) * njt;
+        for (int t = w; t < ntile; t += NW) {
+            const int rt = t / njt, jt = t - rt * njt, r = 16 * rt + r16;
+            fast::f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+            fast::bf16x8 A[8];   // head_dim <= 256: at most eight k-steps, all requested before the first is used
+#pragma unroll
+            for (int ks = 0; ks < 8; ks++)
+                A[ks] = ks < d / 32 ? fast::ld_bf16x8(reinterpret_cast<const bf16_t *>(W) + (size_t)(16 * jt + r16) * d + 32 * ks + 8 * g4)
+                                    : fast::zero_bf16x8();
+#pragma unroll
+            for (int ks = 0; ks < 8; ks++) {
+                if (ks < d / 32) {
+                    fast::bf16x8 B = fast::zero_bf16x8();
+                    if (r < R) {
+                        const float4 x0 = *reinterpret_cast<const float4 *>(&xs[r * d + 32 * ks + 8 * g4]);
+                        const float4 x1 = *reinterpret_cast<const float4 *>(&xs[r * d + 32 * ks + 8 * g4 + 4]);
+                        B[0] = (__bf16)x0.x; B[1] = (__bf16)x0.y; B[2] = (__bf16)x0.z; B[3] = (__bf16)x0.w;
+                        B[4] = (__bf16)x1.x; B[5] = (__bf16)x1.y; B[6] = (__bf16)x1.z; B[7] = (__bf16)x1.w;
+                    }
+                    acc = fast::mfma16(A[ks], B, acc);
+                }
+            }
+            if (r < R) {   // lane (column = row r of the batch, group g4) holds projections 16 jt + 4 g4 + 0..3
+#pragma unroll
+                for (int i = 0; i < 4; i++) ph[r * D + 16 * jt + 4 * g4 + i] = acc[i];
+            }
+        }
+    } else {
+        for (int p = tid; p < R * m; p += NT) {
+            int r = p / m, j = p - r * m;
+            const float *x = xs + r * d;
+            ph[r * D + j] = dot_row(W + (size_t)j * d, x, d, 0.f);
+        }
     }
     __syncthreads();
     const int w = tid / WAVE, lane = tid % WAVE;
@@ -113,6 +148,9 @@ __device__ void phi_rows(const Dims &dm, const T *W, const float *xs, float *ph,
 
 // Self-recall error of R pairs against (H, s), H stored transposed [d][D]: ph [R][D], vs [R][d] in LDS; err [R][d], den [R] LDS
 // scratch; score_out[r] = || ph_r^T H / ph_r^T s - v_r ||_2 (recall = 0 while ph_r^T s == 0).
+// MF (bf16 storage only): the recall contraction runs on MFMA with both fp32 operands split into bf16 high + low parts
+// (three passes, ~2^-17 relative), tile = 16 value columns x 16 rows.
+template <bool MF>
 __device__ void score_rows(const Dims &dm, const float *H, const float *s, const float *ph, const float *vs,
                            float *err, float *den, float *score_out, int R) {
     const int tid = threadIdx.x, d = dm.d, D = dm.D;
@@ -124,6 +162,70 @@ __device__ void score_rows(const Dims &dm, const float *H, const float *s, const
         if (lane == 0) den[r] = a;
     }
     __syncthreads();
+    if (MF && R >= 8 && (D & 31) == 0) {
+        const int r16 = lane & 15, g4 = lane >> 4;
+        const int nrt = (R + 15) / 16;
+        for (int ct = w; ct < d / 16; ct += NW) {
+            // A = this wavefront's 16 rows of H^T, eight k-steps at a time (all their loads in flight together, split once
+            // and used for both row tiles of the batch: a batch has at most 32 rows); B = the feature rows from LDS
+            fast::f32x4 acc[2][3];
+#pragma unroll
+            for (int rt = 0; rt < 2; rt++)
+#pragma unroll
+                for (int x = 0; x < 3; x++) acc[rt][x] = (fast::f32x4){0.f, 0.f, 0.f, 0.f};
+            for (int ks0 = 0; ks0 < D / 32; ks0 += 8) {
+                float4 h0[8], h1[8];
+#pragma unroll
+                for (int u = 0; u < 8; u++) {
+                    const int ks = ks0 + u < D / 32 ? ks0 + u : ks0;   // (a repeated load instead of a branch; its product is skipped below)
+                    const float *hp = H + (size_t)(16 * ct + r16) * D + 32 * ks + 8 * g4;
+                    h0[u] = *reinterpret_cast<const float4 *>(hp); h1[u] = *reinterpret_cast<const float4 *>(hp + 4);
+                }
+                fast::bf16x8 Ah[8], Al[8];
+#pragma unroll
+                for (int u = 0; u < 8; u++) {
+                    const float hv[8] = {h0[u].x, h0[u].y, h0[u].z, h0[u].w, h1[u].x, h1[u].y, h1[u].z, h1[u].w};
+                    fast::split8(hv, Ah[u], Al[u]);
+                }
+#pragma unroll
+                for (int rt = 0; rt < 2; rt++) {
+                    const int r = 16 * rt + r16;
+                    if (rt < nrt) {
+#pragma unroll
+                        for (int u = 0; u < 8; u++) {
+                            if (ks0 + u < D / 32) {
+                                fast::bf16x8 Bh = fast::zero_bf16x8(), Bl = fast::zero_bf16x8();
+                                if (r < R) {
+                                    const float4 p0 = *reinterpret_cast<const float4 *>(&ph[r * D + 32 * (ks0 + u) + 8 * g4]);
+                                    const float4 p1 = *reinterpret_cast<const float4 *>(&ph[r * D + 32 * (ks0 + u) + 8 * g4 + 4]);
+                                    const float pv[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+                                    fast::split8(pv, Bh, Bl);
+                                }
+                                acc[rt][0] = fast::mfma16(Ah[u], Bh, acc[rt][0]);
+                                acc[rt][1] = fast::mfma16(Ah[u], Bl, acc[rt][1]);
+                                acc[rt][2] = fast::mfma16(Al[u], Bh, acc[rt][2]);
+                            }
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int rt = 0; rt < 2; rt++) {
+                const int r = 16 * rt + r16;
+                if (rt < nrt && r < R) {   // lane (column = row r, group g4) holds value columns c = 16 ct + 4 g4 + 0..3
+                    const float dn = den[r];
+#pragma unroll
+                    for (int i = 0; i < 4; i++) {
+                        const int c = 16 * ct + 4 * g4 + i;
+                        const float p = acc[rt][0][i] + (acc[rt][1][i] + acc[rt][2][i]);
+                        const float pred = dn > 0.f ? p / dn : 0.f;
+                        const float e = pred - vs[r * d + c];
+                        err[r * d + c] = e * e;
+                    }
+                }
+            }
+        }
+    } else {
     // thread (c, rg) takes rows rg, rg + nrg, ...; eight rows share one pass over row c of H^T, so that a value of H
     // fetched from memory feeds eight multiply-adds (the features come from LDS, the same word for all c)
     const int c = tid % d, rg = tid / d, nrg = NT / d;
@@ -163,6 +265,7 @@ __device__ void score_rows(const Dims &dm, const float *H, const float *s, const
                 err[r * d + c] = e * e;
             }
         }
+    }
     }
     __syncthreads();
     for (int r = w; r < R; r += NW) {
@@ -290,7 +393,7 @@ __global__ __launch_bounds__(NT) void decode_kernel(DecodeArgs<T> a) {
                     }
                     __syncthreads();
                     phi_rows(dm, Wk, xs, ph, nr);
-                    score_rows(dm, H, s, ph, vs, err, den, score + t0, nr);
+                    score_rows<std::is_same<T, bf16_t>::value>(dm, H, s, ph, vs, err, den, score + t0, nr);
                 }
                 // the pair that goes: smallest score, ties -> the larger token index goes
                 if (tid < WAVE) {
@@ -667,7 +770,7 @@ __device__ void scan_chunk(const PrefillArgs<T> &a, const int si, const int j, i
                 __syncthreads();
                 phi_rows(dm, Wk, xs, ph, nr);
                 for (int p = tid; p < nr * D; p += NT) phiE[(size_t)t0 * D + p] = ph[p];
-                if (!sk) score_rows(dm, H, s, ph, vs, err, den, score + t0, nr);
+                if (!sk) score_rows<std::is_same<T, bf16_t>::value>(dm, H, s, ph, vs, err, den, score + t0, nr);
                 else __syncthreads();
             }
             if (sk) for (int e = tid; e < nE; e += NT) score[e] = e < spc ? sp_score[e] : tsc[vrow0 + (e - spc) - lam];
