@@ -111,3 +111,16 @@ def test_arguments_rejected_before_launch(L):
     assert p(cs, sts, None, vp(fake), None, 64, vp(fake), 1 << 40) == -5    # update-only call: these scores need queries
     assert lb.lola_kernel_path(cs, 0) == "generic" and lb.lola_kernel_path(cs, 1) == "generic"
     assert f(C.byref(cfg(query_hide=4)), C.byref(st), vp(fake), vp(fake), vp(fake), vp(fake), vp(fake), vp(fake), None) == -2
+
+
+def test_benchmark_work_counts_match_the_documented_figures():
+    """The algorithmic bytes / flops bench.py divides by are the ones the design notes derive from the
+    layer's definition (8B shape: 235 524 B per stream and step, 121.24 MB per launch at batch 64;
+    57.7 MFLOP per chunk and stream, 118.1 GFLOP per configuration-3 call)."""
+    import bench
+    import workloads as wl
+    per_stream, per_launch = bench.decode_alg_bytes(wl.CONFIGS[4], 4)
+    assert per_stream == 235524 and per_launch == 235524 * 512 + 40 * 128 * 64 * 2 == 121243648
+    per_chunk, per_call = bench.prefill_alg_flops(wl.CONFIGS[3])
+    assert per_chunk == 57671680 and per_call == per_chunk * 64 * 32
+    assert abs(per_call / 1e9 - 118.1) < 0.05
