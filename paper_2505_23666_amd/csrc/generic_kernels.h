@@ -739,12 +739,13 @@ __device__ void scan_chunk(const PrefillArgs<T> &a, const int si, const int j, i
         const int vrow0 = P + (int)(lo - a0);
         if (n_ev > 0 && spc + n_ev <= lam) {
             // warm-up: everything is cached, nothing scored
-            for (int p = tid; p < n_ev * d; p += NT) {
-                int e = p / d, i = p - e * d, vr = vrow0 + e;
+            const int ppr = d * (int)sizeof(T) / 16;   // rows are copied as 16-byte pieces
+            for (int p = tid; p < n_ev * ppr; p += NT) {
+                int e = p / ppr, i = p - e * ppr, vr = vrow0 + e;
                 const T *ksrc = vr < P ? pK + (size_t)vr * d : kc + (size_t)(vr - P) * d;
                 const T *vsrc = vr < P ? pV + (size_t)vr * d : vc + (size_t)(vr - P) * d;
-                sp_k[(size_t)(spc + e) * d + i] = ksrc[i];
-                sp_v[(size_t)(spc + e) * d + i] = vsrc[i];
+                reinterpret_cast<uint4 *>(sp_k + (size_t)(spc + e) * d)[i] = reinterpret_cast<const uint4 *>(ksrc)[i];
+                reinterpret_cast<uint4 *>(sp_v + (size_t)(spc + e) * d)[i] = reinterpret_cast<const uint4 *>(vsrc)[i];
             }
             for (int e = tid; e < n_ev; e += NT) {
                 sp_idx[spc + e] = (int32_t)(lo + e); sp_row[spc + e] = vrow0 + e;
@@ -817,13 +818,14 @@ __device__ void scan_chunk(const PrefillArgs<T> &a, const int si, const int j, i
             }
             __syncthreads();
             // compaction: entrants overwrite the slots that were freed
-            for (int p = tid; p < ne * d; p += NT) {
-                int x = p / d, i = p - x * d;
+            const int ppr = d * (int)sizeof(T) / 16;   // 16-byte pieces per row
+            for (int p = tid; p < ne * ppr; p += NT) {
+                int x = p / ppr, i = p - x * ppr;
                 int vr = vrow0 + (ecand[x] - spc), sl = eslot[x];
                 const T *ksrc = vr < P ? pK + (size_t)vr * d : kc + (size_t)(vr - P) * d;
                 const T *vsrc = vr < P ? pV + (size_t)vr * d : vc + (size_t)(vr - P) * d;
-                sp_k[(size_t)sl * d + i] = ksrc[i];
-                sp_v[(size_t)sl * d + i] = vsrc[i];
+                reinterpret_cast<uint4 *>(sp_k + (size_t)sl * d)[i] = reinterpret_cast<const uint4 *>(ksrc)[i];
+                reinterpret_cast<uint4 *>(sp_v + (size_t)sl * d)[i] = reinterpret_cast<const uint4 *>(vsrc)[i];
             }
             for (int x = tid; x < ne; x += NT) {
                 sp_idx[eslot[x]] = cidx[ecand[x]];
