@@ -4,8 +4,11 @@
  *
  * The library owns no memory and never synchronises: every pointer below is a DEVICE pointer
  * (unless marked host) to caller-owned, contiguous, row-major memory aligned to 16 bytes, and
- * every call only enqueues kernels on `stream` (a hipStream_t passed as void*; NULL is the
- * default stream).  Arguments are validated on the host before anything is launched; on error a
+ * every call only enqueues work that is ordered behind `stream` and that `stream` waits for (a
+ * hipStream_t passed as void*; NULL is the default stream): kernels on `stream` itself, and, in
+ * lola_prefill only, kernels on one second stream per device that the library creates on first
+ * use, forks from `stream` and joins back into it with events before the call returns (see
+ * lola_prefill).  Arguments are validated on the host before anything is launched; on error a
  * negative lola_status is returned and nothing has been enqueued.  Calls on distinct states are
  * independent; calls on one state must be ordered by the caller (same stream, or events).
  *
@@ -146,6 +149,13 @@ lola_status lola_state_flush(const lola_config *cfg, const lola_state *st, void 
  * workspace: see lola_prefill_workspace_bytes.  Contents are scratch; calls sharing a workspace
  *   must be ordered.
  * May be called repeatedly (the memories carry over) and be followed by lola_decode_step.
+ * Streams: with few streams of memories (B * Hkv <= 128) and enough output work, the MFMA kernels
+ *   cut a pass into up to 8 pieces and run the outputs of a piece on the library's second stream
+ *   beside the state evolution of the next piece; `stream` waits for that work before the call's
+ *   last kernel, so work the caller enqueues on `stream` afterwards sees every output.  While
+ *   `stream` is under graph capture, or if the second stream cannot be created, everything stays
+ *   on `stream`.  Results do not depend on which way a call ran.  Host threads may call
+ *   concurrently; the second stream is shared and guarded by a lock held while a call enqueues.
  * Token indices are int32: n_tokens + T must stay below 2^31.
  */
 lola_status lola_prefill(const lola_config *cfg, const lola_state *st,

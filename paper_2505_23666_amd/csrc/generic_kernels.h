@@ -521,7 +521,8 @@ struct PrefillArgs {
     const T *q, *k, *v, *Wq, *Wk;
     void *out;
     int T_tokens, n_chunks;   // of the whole call
-    int j0, j1;               // chunk range of this pass
+    int j0, j1;               // chunk range of this launch
+    int jb;                   // first chunk of the pass: per-chunk workspace regions are indexed by chunk - jb
     T *prefK, *prefV;         // [B*Hkv][P][d]
     int32_t *sp_row;          // [B*Hkv][lam] virtual row held by each sparse slot
     float *phiE;              // [B*Hkv][lam + C][D] features of the eligible set (scan scratch)
@@ -534,8 +535,9 @@ struct PrefillArgs {
     int QT;                   // queries per attend tile
     int snap_split;           // 1: H snapshots are written as bf16 high + low parts in MFMA operand order (D = d = 128)
     uint16_t *phiK;           // [B*Hkv][S][C][2][D] phi of the pass's keys, bf16 high + low parts (MFMA state-evolution kernel only)
-    int scan_mode;            // scan_kernel: 0 all chunks of the pass; 1 stop at the first regular chunk (a full chunk with a full
-                              // window behind it and a full cache: the MFMA kernel's case) and note it in next_j; 2 continue from next_j
+    int scan_mode;            // scan_kernel: 0 all chunks of the launch; bit 0: stop at the first regular chunk (a full chunk with
+                              // a full window behind it and a full cache: the MFMA kernel's case) and note it in next_j; bit 1:
+                              // start from next_j instead of j0
     int32_t *next_j;          // [B*Hkv] hand-over of the chunk position between the kernels of a pass
     float *tok_score;         // [B*Hkv][eta + T] query-dependent scores: entry window (virtual rows lam ..), then the call's tokens
     int R2;                   // keys / queries per tile of band_score_kernel
@@ -702,7 +704,7 @@ __device__ void scan_chunk(const PrefillArgs<T> &a, const int si, const int j, i
         const int cl = min(C, a.T_tokens - j * C);
         const int64_t aj = a0 + (int64_t)j * C;
         if (a.want_out) {   // snapshot of the memories the chunk's queries read
-            const size_t sj = (size_t)si * a.S + (j - a.j0);
+            const size_t sj = (size_t)si * a.S + (j - a.jb);
             float *sH = a.snapH + sj * D * d, *sS = a.snapS + sj * D;
             int32_t *sG = a.snapG + sj * lam;
             if (a.snap_split) {
@@ -849,10 +851,10 @@ __global__ __launch_bounds__(NT) void scan_kernel(PrefillArgs<T> a) {
     extern __shared__ __attribute__((aligned(16))) float smem[];
     const int si = blockIdx.x;
     int spc = a.st.sp_count[si];
-    int j = a.scan_mode == 2 ? a.next_j[si] : a.j0;
+    int j = (a.scan_mode & 2) ? a.next_j[si] : a.j0;
     const int64_t a0 = a.st.n_tokens[si];
     for (; j < a.j1; j++) {
-        if (a.scan_mode == 1) {
+        if (a.scan_mode & 1) {
             const int cl = min(a.dm.C, a.T_tokens - j * a.dm.C);
             if (cl == a.dm.C && a0 + (int64_t)j * a.dm.C >= a.dm.eta && spc == a.dm.lam) break;
         }
@@ -860,7 +862,7 @@ __global__ __launch_bounds__(NT) void scan_kernel(PrefillArgs<T> a) {
     }
     if (threadIdx.x == 0) {
         a.st.sp_count[si] = spc;
-        if (a.scan_mode == 1) a.next_j[si] = j;
+        if (a.scan_mode & 1) a.next_j[si] = j;
     }
 }
 
@@ -871,7 +873,7 @@ __global__ __launch_bounds__(NT) void attend_kernel(PrefillArgs<T> a) {
     const Dims &dm = a.dm;
     const int tid = threadIdx.x, d = dm.d, D = dm.D, m = dm.m, eta = dm.eta, lam = dm.lam, C = dm.C, QT = a.QT;
     const int P = lam + eta, nkmax = lam + eta + C;
-    const int jj = blockIdx.x, j = a.j0 + jj, hq = blockIdx.y, b = blockIdx.z;
+    const int j = a.j0 + blockIdx.x, jj = j - a.jb, hq = blockIdx.y, b = blockIdx.z;
     const int h = hq / dm.g, si = b * dm.Hkv + h;
     float *qs = smem;                 // [QT][d]
     float *phq = qs + QT * d;         // [QT][D]

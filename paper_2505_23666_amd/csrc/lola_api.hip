@@ -2,6 +2,7 @@
 // and kernel dispatch.  Nothing here allocates or synchronises.
 #include "../../include/lola.h"
 #include <type_traits>
+#include <mutex>
 #include "generic_kernels.h"
 #include "decode_mfma.h"
 #include "prefill_mfma.h"
@@ -247,6 +248,44 @@ lola_status run_decode(const lola_config *c, const lola_state *st, const void *q
     return LOLA_OK;
 }
 
+// Second stream of the prefill: one per device, created on first use at the default priority and kept until the process
+// ends.  Calls from several host threads share it; the events keep every call's work ordered behind its own stream.
+struct SideStream {
+    static constexpr int NEV = 8;   // pieces per pass at most
+    hipStream_t s;
+    hipEvent_t fork[NEV], join;
+};
+constexpr size_t OVERLAP_MAX_STREAMS = 128;   // beyond this many streams the serial evolution fills the chip by itself
+constexpr int OVERLAP_MIN_PIECE = 8;          // chunks per piece at least
+constexpr size_t OVERLAP_MIN_WORK = 4096;     // output workgroups (in units of 64 head columns) per piece at least: below
+                                              // this the restart of the evolution costs more than the overlap hides
+
+std::mutex side_init_mu;   // creation of the per-device entries
+std::mutex side_use_mu;    // held by a call from its first fork to its join: the events are shared
+
+SideStream *side_stream(hipStream_t caller) {
+    constexpr int MAX_DEV = 16;
+    static SideStream table[MAX_DEV];
+    static int state[MAX_DEV];   // 0 not tried, 1 ready, -1 unavailable
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(caller, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) {
+        (void)hipGetLastError();
+        return nullptr;          // under graph capture the call stays on the caller's stream
+    }
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEV) return nullptr;
+    std::lock_guard<std::mutex> lock(side_init_mu);
+    if (state[dev] == 0) {
+        SideStream &t = table[dev];
+        bool ok = hipStreamCreateWithFlags(&t.s, hipStreamNonBlocking) == hipSuccess;
+        for (int i = 0; ok && i < SideStream::NEV; i++) ok = hipEventCreateWithFlags(&t.fork[i], hipEventDisableTiming) == hipSuccess;
+        ok = ok && hipEventCreateWithFlags(&t.join, hipEventDisableTiming) == hipSuccess;
+        if (!ok) (void)hipGetLastError();
+        state[dev] = ok ? 1 : -1;
+    }
+    return state[dev] == 1 ? &table[dev] : nullptr;
+}
+
 template <typename T>
 lola_status run_prefill(const lola_config *c, const lola_state *st, const void *q, const void *k, const void *v,
                         const void *Wq, const void *Wk, int32_t Tn, void *out, int32_t *sel_trace,
@@ -313,54 +352,93 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
         LAUNCH_CHECK();
     }
     for (int j0 = 0; j0 < a.n_chunks; j0 += S) {
-        a.j0 = j0;
-        a.j1 = j0 + S < a.n_chunks ? j0 + S : a.n_chunks;
-        bool scanned = false;
+        const int jend = j0 + S < a.n_chunks ? j0 + S : a.n_chunks;
+        a.jb = a.j0 = j0;
+        a.j1 = jend;
         if constexpr (std::is_same<T, bf16_t>::value) {
             if (fast_attend_ok(c)) {   // same shape conditions as the output kernel
-                // features of the pass's keys (chunk-parallel); then the serial evolution in three legs that hand the
-                // chunk position over in next_j: generic kernel until the first regular chunk, MFMA kernel over the
-                // regular chunks, generic kernel for what is left (a ragged last chunk)
-                const dim3 gp((unsigned)(a.j1 - a.j0), (unsigned)ns);
+                // features of the pass's keys (chunk-parallel); then the serial evolution in legs that hand the chunk
+                // position over in next_j: generic kernel until the first regular chunk, MFMA kernel over the regular
+                // chunks, generic kernel for what is left (a ragged last chunk)
+                const dim3 gp((unsigned)(jend - j0), (unsigned)ns);
                 if (c->head_dim == 128) hipLaunchKernelGGL(fast::phi_k_kernel<128>, gp, dim3(256), 0, stream, a);
                 else hipLaunchKernelGGL(fast::phi_k_kernel<64>, gp, dim3(256), 0, stream, a);
                 LAUNCH_CHECK();
-                a.scan_mode = 1;
-                hipLaunchKernelGGL((generic::scan_kernel<T>), gs, block, lds_scan, stream, a);
-                LAUNCH_CHECK();
-#define LOLA_SCAN(LAMV) do { if (c->head_dim == 128) hipLaunchKernelGGL((fast::scan_fast_kernel<LAMV, 128>), gs, dim3(512), 0, stream, a); \
-                             else hipLaunchKernelGGL((fast::scan_fast_kernel<LAMV, 64>), gs, dim3(256), 0, stream, a); } while (0)
-                if (c->sparse_budget == 64) LOLA_SCAN(64); else if (c->sparse_budget == 128) LOLA_SCAN(128); else LOLA_SCAN(256);
-#undef LOLA_SCAN
-                LAUNCH_CHECK();
-                if (a.j1 == a.n_chunks && Tn % a.dm.C != 0) {   // only a ragged last chunk is left to the generic kernel
-                    a.scan_mode = 2;
-                    hipLaunchKernelGGL((generic::scan_kernel<T>), gs, block, lds_scan, stream, a);
-                    LAUNCH_CHECK();
+                // With few streams the serial evolution occupies few compute units, so the pass is cut into pieces and
+                // the outputs of a piece (chunk-parallel, from its snapshots) run on a second stream beside the
+                // evolution of the next piece.
+                int piece = jend - j0;
+                SideStream *side = nullptr;
+                int np = piece / OVERLAP_MIN_PIECE;
+                const size_t work = (size_t)piece * a.dm.Hq * a.dm.B * (size_t)(c->head_dim / 64);
+                if ((size_t)np > work / OVERLAP_MIN_WORK) np = (int)(work / OVERLAP_MIN_WORK);
+                if (np > SideStream::NEV) np = SideStream::NEV;
+                if (a.want_out && ns <= OVERLAP_MAX_STREAMS && np >= 2) side = side_stream(stream);
+                std::unique_lock<std::mutex> side_lock(side_use_mu, std::defer_lock);
+                if (side) {
+                    side_lock.lock();
+                    piece = (piece + np - 1) / np;
                 }
-                a.scan_mode = 0;
-                scanned = true;
-            }
-        }
-        if (!scanned) {
-            hipLaunchKernelGGL((generic::scan_kernel<T>), gs, block, lds_scan, stream, a);
-            LAUNCH_CHECK();
-        }
-        if (a.want_out) {
-            dim3 ga((unsigned)(a.j1 - a.j0), (unsigned)a.dm.Hq, (unsigned)a.dm.B);
-            if constexpr (std::is_same<T, bf16_t>::value) {
-                if (fast_att) {
-                    const bool f32o = c->out_dtype == LOLA_F32;
-#define LOLA_ATT2(LAMV, DHV) do { if (f32o) hipLaunchKernelGGL((fast::attend_fast_kernel<LAMV, DHV, float>), ga, dim3(256), 0, stream, a); \
-                                  else hipLaunchKernelGGL((fast::attend_fast_kernel<LAMV, DHV, bf16_t>), ga, dim3(256), 0, stream, a); } while (0)
+                const bool f32o = c->out_dtype == LOLA_F32;
+                auto attend = [&](hipStream_t so, int r0, int r1) {
+                    generic::PrefillArgs<T> ao = a;
+                    ao.j0 = r0; ao.j1 = r1; ao.scan_mode = 0;
+                    const dim3 ga((unsigned)(r1 - r0), (unsigned)a.dm.Hq, (unsigned)a.dm.B);
+#define LOLA_ATT2(LAMV, DHV) do { if (f32o) hipLaunchKernelGGL((fast::attend_fast_kernel<LAMV, DHV, float>), ga, dim3(256), 0, so, ao); \
+                                  else hipLaunchKernelGGL((fast::attend_fast_kernel<LAMV, DHV, bf16_t>), ga, dim3(256), 0, so, ao); } while (0)
 #define LOLA_ATT(LAMV) do { if (c->head_dim == 128) LOLA_ATT2(LAMV, 128); else LOLA_ATT2(LAMV, 64); } while (0)
                     if (c->sparse_budget == 64) LOLA_ATT(64); else if (c->sparse_budget == 128) LOLA_ATT(128); else LOLA_ATT(256);
 #undef LOLA_ATT
 #undef LOLA_ATT2
+                };
+                // outputs of the chunks [r0, r1) on the second stream, behind everything enqueued on `stream` so far
+                auto attend_aside = [&](int ev, int r0, int r1) -> bool {
+                    if (hipEventRecord(side->fork[ev], stream) != hipSuccess) return false;
+                    if (hipStreamWaitEvent(side->s, side->fork[ev], 0) != hipSuccess) return false;
+                    attend(side->s, r0, r1);
+                    return hipGetLastError() == hipSuccess;
+                };
+                int ip = 0, prev0 = j0;
+                for (int p0 = j0; p0 < jend; p0 += piece, ip++) {
+                    a.j0 = p0;
+                    a.j1 = p0 + piece < jend ? p0 + piece : jend;
+                    a.scan_mode = p0 == j0 ? 1 : 3;
+                    hipLaunchKernelGGL((generic::scan_kernel<T>), gs, block, lds_scan, stream, a);
                     LAUNCH_CHECK();
-                    continue;
+                    // The previous piece's outputs are released behind this short launch rather than right behind
+                    // their own evolution: the evolution kernel that follows is then resident before the output
+                    // workgroups arrive, instead of queueing for compute units behind them.
+                    if (side && ip > 0 && !attend_aside(ip - 1, prev0, p0)) return LOLA_ERR_HIP;
+#define LOLA_SCAN(LAMV) do { if (c->head_dim == 128) hipLaunchKernelGGL((fast::scan_fast_kernel<LAMV, 128>), gs, dim3(512), 0, stream, a); \
+                             else hipLaunchKernelGGL((fast::scan_fast_kernel<LAMV, 64>), gs, dim3(256), 0, stream, a); } while (0)
+                    if (c->sparse_budget == 64) LOLA_SCAN(64); else if (c->sparse_budget == 128) LOLA_SCAN(128); else LOLA_SCAN(256);
+#undef LOLA_SCAN
+                    LAUNCH_CHECK();
+                    if (a.j1 == a.n_chunks && Tn % a.dm.C != 0) {   // only a ragged last chunk is left to the generic kernel
+                        a.scan_mode = 2;
+                        hipLaunchKernelGGL((generic::scan_kernel<T>), gs, block, lds_scan, stream, a);
+                        LAUNCH_CHECK();
+                    }
+                    a.scan_mode = 0;
+                    if (a.want_out && !side) {
+                        attend(stream, a.j0, a.j1);
+                        LAUNCH_CHECK();
+                    }
+                    prev0 = p0;
                 }
+                if (side) {   // last piece; then the caller's stream continues (next pass, final write-back, the caller's
+                              // own work) behind all outputs
+                    if (!attend_aside(ip - 1, prev0, jend)) return LOLA_ERR_HIP;
+                    if (hipEventRecord(side->join, side->s) != hipSuccess) return LOLA_ERR_HIP;
+                    if (hipStreamWaitEvent(stream, side->join, 0) != hipSuccess) return LOLA_ERR_HIP;
+                }
+                continue;
             }
+        }
+        hipLaunchKernelGGL((generic::scan_kernel<T>), gs, block, lds_scan, stream, a);
+        LAUNCH_CHECK();
+        if (a.want_out) {
+            dim3 ga((unsigned)(a.j1 - a.j0), (unsigned)a.dm.Hq, (unsigned)a.dm.B);
             if (c->out_dtype == LOLA_F32) hipLaunchKernelGGL((generic::attend_kernel<T, float>), ga, block, lds_att, stream, a);
             else hipLaunchKernelGGL((generic::attend_kernel<T, bf16_t>), ga, block, lds_att, stream, a);
             LAUNCH_CHECK();

@@ -39,7 +39,7 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
     __shared__ int G_l[LAM > 0 ? LAM : 1];
 
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r16 = lane & 15, g4 = lane >> 4;
-    const int jj = blockIdx.x, j = a.j0 + jj, hq = blockIdx.y, b = blockIdx.z;
+    const int j = a.j0 + blockIdx.x, jj = j - a.jb, hq = blockIdx.y, b = blockIdx.z;
     const int h = hq / a.dm.g, si = b * a.dm.Hkv + h;
     const int64_t a0 = a.st.n_tokens[si];
     const int Tn = a.T_tokens;
@@ -264,7 +264,7 @@ template <int DH>
 __global__ __launch_bounds__(256) void phi_k_kernel(generic::PrefillArgs<bf16_t> a) {
     constexpr int M = 64, D = 128, C = 64, KS = DH / 32;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r16 = lane & 15, g4 = lane >> 4;
-    const int jj = blockIdx.x, j = a.j0 + jj, si = blockIdx.y, h = si % a.dm.Hkv;
+    const int j = a.j0 + blockIdx.x, jj = j - a.jb, si = blockIdx.y, h = si % a.dm.Hkv;
     const int row = 16 * w + r16, tok = j * C + row;
     const bf16_t *Wk = a.Wk + (size_t)h * M * DH;
     const bf16_t *kr = a.k + ((size_t)si * a.T_tokens + tok) * DH;
@@ -384,7 +384,7 @@ __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillAr
         const bool have_phi = PERSIST && phi_valid;   // the cache's rows are in LDS and the leaving pairs' rows (from the
                                                       // parallel feature kernel) were requested one chunk ahead
         // !PERSIST: where candidate e's features are once rows_valid holds (operand order, high part then low part)
-        const uint16_t *phk_prev = a.phiK + ((size_t)si * a.S + (size_t)(j - 1 - a.j0)) * C * 2 * D;
+        const uint16_t *phk_prev = a.phiK + ((size_t)si * a.S + (size_t)(j - 1 - a.jb)) * C * 2 * D;
         auto phirow = [&](int e) -> const uint16_t * {
             return (rows_valid && e >= LAM) ? phk_prev + (size_t)(e - LAM) * 2 * D : phiE + (size_t)e * 2 * D;
         };
@@ -489,7 +489,7 @@ __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillAr
                 }
             }
             if (PERSIST) {   // this chunk's own pairs leave the window in the next chunk
-                const uint4 *ph = reinterpret_cast<const uint4 *>(a.phiK + ((size_t)si * a.S + (j - a.j0)) * C * 2 * D);
+                const uint4 *ph = reinterpret_cast<const uint4 *>(a.phiK + ((size_t)si * a.S + (j - a.jb)) * C * 2 * D);
 #pragma unroll
                 for (int it = 0; it < PHN; it++) PHn[it] = ph[tid + NTH * it];
 #pragma unroll
@@ -497,7 +497,7 @@ __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillAr
                     vvn[u] = *reinterpret_cast<const uint2 *>(vc + (size_t)(j * C + 16 * u + r16) * DH + 16 * w + 4 * g4);
             }
             if (a.want_out && t0 == 0) {
-                const size_t sj = (size_t)si * a.S + (j - a.j0);
+                const size_t sj = (size_t)si * a.S + (j - a.jb);
                 uint16_t *s16 = reinterpret_cast<uint16_t *>(a.snapH) + sj * (2 * D * DH);
 #pragma unroll
                 for (int ks = 0; ks < 4; ks++) {

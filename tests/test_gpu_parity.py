@@ -317,6 +317,37 @@ def test_8b_shape_resume_ragged_multipass(lam, phi_kind):
         say("8b resume part", i, rep)
 
 
+def test_8b_shape_outputs_on_the_second_stream():
+    """A call large enough that the MFMA prefill cuts its pass into pieces and runs the outputs of a
+    piece on the library's second stream beside the evolution of the next one (batch 4, 33 chunks
+    with a ragged tail: two pieces); every output and all memories against the oracle; then a second
+    call on the same state, and work on the caller's stream right behind the call (a copy of the
+    outputs) must see all of them."""
+    sh = wl.scaled(3, T=64 * 32 + 37 + 64 * 33)
+    Wq, Wk = wl.weights(sh)
+    q, k, v, _ = wl.sequence_inputs(sh)
+    cut = 64 * 32 + 37
+    layer, o, rep = P.prefill_parity(sh, q[:, :, :cut], k[:, :, :cut], v[:, :, :cut], Wq, Wk)
+    say("two-stream call 1", rep)
+    layer, o, rep = P.prefill_parity(sh, q[:, :, cut:], k[:, :, cut:], v[:, :, cut:], Wq, Wk, layer=layer, oracle=o)
+    say("two-stream call 2", rep)
+    # the same tokens in one call: the copy enqueued right behind the call holds the finished outputs
+    one = P.make_layer(sh)
+    dq, dk, dv = P.to_dev(q[:, :, :cut], "bf16"), P.to_dev(k[:, :, :cut], "bf16"), P.to_dev(v[:, :, :cut], "bf16")
+    dWq, dWk = P.w_to_dev(Wq, "bf16"), P.w_to_dev(Wk, "bf16")
+    ref = one.prefill(dq, dk, dv, dWq, dWk).clone()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    for _ in range(3):
+        one.reset()
+        with torch.cuda.stream(side):
+            out = one.prefill(dq, dk, dv, dWq, dWk)
+            snap = out.clone()
+            out.zero_()
+        side.synchronize()
+        assert torch.equal(snap, ref)
+
+
 @pytest.mark.parametrize("lam", [64, 128])
 def test_1b_shape_resume_ragged_multipass(lam):
     """The MFMA prefill kernels at the 1B head shape (head_dim 64, 128 features) across call boundaries that are
