@@ -256,7 +256,8 @@ struct SideStream {
     hipEvent_t fork[NEV], join;
 };
 constexpr size_t OVERLAP_MAX_STREAMS = 128;   // beyond this many streams the serial evolution fills the chip by itself
-constexpr int OVERLAP_MIN_PIECE = 8;          // chunks per piece at least
+constexpr int OVERLAP_MIN_PIECE = 8;          // chunks per piece at least; more than the (256 + 64) / 64 chunks after which
+                                              // the sparse cache of the MFMA shapes is full
 constexpr size_t OVERLAP_MIN_WORK = 4096;     // output workgroups (in units of 64 head columns) per piece at least: below
                                               // this the restart of the evolution costs more than the overlap hides
 
@@ -391,9 +392,8 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
 #undef LOLA_ATT
 #undef LOLA_ATT2
                 };
-                // outputs of the chunks [r0, r1) on the second stream, behind everything enqueued on `stream` so far
+                // outputs of the chunks [r0, r1) on the second stream, behind what `stream` held when fork[ev] was recorded
                 auto attend_aside = [&](int ev, int r0, int r1) -> bool {
-                    if (hipEventRecord(side->fork[ev], stream) != hipSuccess) return false;
                     if (hipStreamWaitEvent(side->s, side->fork[ev], 0) != hipSuccess) return false;
                     attend(side->s, r0, r1);
                     return hipGetLastError() == hipSuccess;
@@ -402,18 +402,22 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
                 for (int p0 = j0; p0 < jend; p0 += piece, ip++) {
                     a.j0 = p0;
                     a.j1 = p0 + piece < jend ? p0 + piece : jend;
-                    a.scan_mode = p0 == j0 ? 1 : 3;
-                    hipLaunchKernelGGL((generic::scan_kernel<T>), gs, block, lds_scan, stream, a);
-                    LAUNCH_CHECK();
-                    // The previous piece's outputs are released behind this short launch rather than right behind
-                    // their own evolution: the evolution kernel that follows is then resident before the output
-                    // workgroups arrive, instead of queueing for compute units behind them.
-                    if (side && ip > 0 && !attend_aside(ip - 1, prev0, p0)) return LOLA_ERR_HIP;
+                    if (ip == 0) {
+                        a.scan_mode = 1;
+                        hipLaunchKernelGGL((generic::scan_kernel<T>), gs, block, lds_scan, stream, a);
+                        LAUNCH_CHECK();
+                    }
+                    // Later pieces start on regular chunks (a piece is longer than the (lambda + eta) / C chunks after
+                    // which the cache is full), so the MFMA kernel continues at once.  The previous piece's outputs are
+                    // enqueued after it: it should be resident before the output workgroups arrive, instead of queueing
+                    // for compute units behind them.
+                    if (side && ip > 0 && hipEventRecord(side->fork[ip - 1], stream) != hipSuccess) return LOLA_ERR_HIP;
 #define LOLA_SCAN(LAMV) do { if (c->head_dim == 128) hipLaunchKernelGGL((fast::scan_fast_kernel<LAMV, 128>), gs, dim3(512), 0, stream, a); \
                              else hipLaunchKernelGGL((fast::scan_fast_kernel<LAMV, 64>), gs, dim3(256), 0, stream, a); } while (0)
                     if (c->sparse_budget == 64) LOLA_SCAN(64); else if (c->sparse_budget == 128) LOLA_SCAN(128); else LOLA_SCAN(256);
 #undef LOLA_SCAN
                     LAUNCH_CHECK();
+                    if (side && ip > 0 && !attend_aside(ip - 1, prev0, p0)) return LOLA_ERR_HIP;
                     if (a.j1 == a.n_chunks && Tn % a.dm.C != 0) {   // only a ragged last chunk is left to the generic kernel
                         a.scan_mode = 2;
                         hipLaunchKernelGGL((generic::scan_kernel<T>), gs, block, lds_scan, stream, a);
@@ -428,6 +432,7 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
                 }
                 if (side) {   // last piece; then the caller's stream continues (next pass, final write-back, the caller's
                               // own work) behind all outputs
+                    if (hipEventRecord(side->fork[ip - 1], stream) != hipSuccess) return LOLA_ERR_HIP;
                     if (!attend_aside(ip - 1, prev0, jend)) return LOLA_ERR_HIP;
                     if (hipEventRecord(side->join, side->s) != hipSuccess) return LOLA_ERR_HIP;
                     if (hipStreamWaitEvent(stream, side->join, 0) != hipSuccess) return LOLA_ERR_HIP;
