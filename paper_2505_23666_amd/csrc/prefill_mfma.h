@@ -294,7 +294,7 @@ __global__ __launch_bounds__(256) void phi_k_kernel(generic::PrefillArgs<bf16_t>
 
 // Chunk swizzle of the transposed fold operands: three bits of the row index r, chosen among the bits that differ
 // between the rows one wavefront writes at once (r2, r3, r5) and between the rows it reads at once (r0 .. r3).
-__device__ __forceinline__ int tswz(int r) { return ((((r >> 5) ^ r) & 1) << 2) | ((r >> 2) & 3); }
+__device__ __forceinline__ int tswz(int r) { return ((((r >> 5) ^ (r >> 1)) & 1) << 2) | ((r >> 2) & 3); }
 
 template <int LAM, int DH>
 __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillArgs<bf16_t> a) {
@@ -488,7 +488,10 @@ __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillAr
                     }
                 }
             }
-            if (PERSIST) {   // this chunk's own pairs leave the window in the next chunk
+            // Requests that nothing in this chunk waits for - the rows wanted by the next chunk and the snapshot of
+            // H^T - are issued here by wavefront 0 only; the other wavefronts issue theirs while they wait for
+            // wavefront 0's selection, where the memory pipe is idle (all of them at this point cost 1.3 us per chunk).
+            if (PERSIST && w == 0) {   // this chunk's own pairs leave the window in the next chunk
                 const uint4 *ph = reinterpret_cast<const uint4 *>(a.phiK + ((size_t)si * a.S + (j - a.jb)) * C * 2 * D);
 #pragma unroll
                 for (int it = 0; it < PHN; it++) PHn[it] = ph[tid + NTH * it];
@@ -498,13 +501,15 @@ __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillAr
             }
             if (a.want_out && t0 == 0) {
                 const size_t sj = (size_t)si * a.S + (j - a.jb);
-                uint16_t *s16 = reinterpret_cast<uint16_t *>(a.snapH) + sj * (2 * D * DH);
+                if (w == 0) {
+                    uint16_t *s16 = reinterpret_cast<uint16_t *>(a.snapH) + sj * (2 * D * DH);
 #pragma unroll
-                for (int ks = 0; ks < 4; ks++) {
-                    // one contiguous 1 KB piece per store: [row tile w][k-step][lane]
-                    const int off = ((w * 4 + ks) * 64 + lane) << 3;
-                    *reinterpret_cast<uint4 *>(s16 + off) = __builtin_bit_cast(uint4, Ahi[ks]);
-                    *reinterpret_cast<uint4 *>(s16 + D * DH + off) = __builtin_bit_cast(uint4, Alo[ks]);
+                    for (int ks = 0; ks < 4; ks++) {
+                        // one contiguous 1 KB piece per store: [row tile w][k-step][lane]
+                        const int off = ((w * 4 + ks) * 64 + lane) << 3;
+                        *reinterpret_cast<uint4 *>(s16 + off) = __builtin_bit_cast(uint4, Ahi[ks]);
+                        *reinterpret_cast<uint4 *>(s16 + D * DH + off) = __builtin_bit_cast(uint4, Alo[ks]);
+                    }
                 }
                 if (tid < D / 4) reinterpret_cast<float4 *>(a.snapS + sj * D)[tid] = reinterpret_cast<const float4 *>(s_l)[tid];
                 for (int sl = tid; sl < LAM; sl += NTH) a.snapG[sj * LAM + sl] = sp_row[sl];
@@ -589,7 +594,27 @@ __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillAr
         // the threshold are folded too if that makes exactly 64; otherwise (exact ties across the cut) the same search
         // over their token indices picks the largest ones.  The lists follow from the fold predicate by ballots:
         // candidates to fold; entrants paired with the slots of the leavers.
-        if (w == 0) {
+        if (w != 0) {   // the requests wavefront 0 issued before the recall GEMM (H^T is still the chunk's entry state)
+            if (PERSIST) {
+                const uint4 *ph = reinterpret_cast<const uint4 *>(a.phiK + ((size_t)si * a.S + (j - a.jb)) * C * 2 * D);
+#pragma unroll
+                for (int it = 0; it < PHN; it++) PHn[it] = ph[tid + NTH * it];
+#pragma unroll
+                for (int u = 0; u < 4; u++)
+                    vvn[u] = *reinterpret_cast<const uint2 *>(vc + (size_t)(j * C + 16 * u + r16) * DH + 16 * w + 4 * g4);
+            }
+            if (a.want_out) {
+                uint16_t *s16 = reinterpret_cast<uint16_t *>(a.snapH) + ((size_t)si * a.S + (j - a.jb)) * (2 * D * DH);
+#define LOLA_SSNAP(ks) { float sv[8]; \
+                _Pragma("unroll") for (int x = 0; x < 4; x++) { sv[x] = hreg##ks##0[x]; sv[4 + x] = hreg##ks##1[x]; } \
+                bf16x8 hi8, lo8; split8(sv, hi8, lo8); \
+                const int off = ((w * 4 + ks) * 64 + lane) << 3; \
+                *reinterpret_cast<uint4 *>(s16 + off) = __builtin_bit_cast(uint4, hi8); \
+                *reinterpret_cast<uint4 *>(s16 + D * DH + off) = __builtin_bit_cast(uint4, lo8); }
+                LOLA_SSNAP(0) LOLA_SSNAP(1) LOLA_SSNAP(2) LOLA_SSNAP(3)
+#undef LOLA_SSNAP
+            }
+        } else {
             uint32_t sb[NK]; int ix[NK];
 #pragma unroll
             for (int x = 0; x < NK; x++) { sb[x] = skey[64 * x + lane]; ix[x] = cidx[64 * x + lane]; }
