@@ -348,6 +348,50 @@ def test_8b_shape_outputs_on_the_second_stream():
         assert torch.equal(snap, ref)
 
 
+def test_two_stream_prefill_from_two_host_threads():
+    """Two host threads, each with a layer and a stream of its own, call the prefill at the same time; both calls use
+    the library's one second stream and its events.  Each result must equal the one the same call gives alone."""
+    import threading
+    sh = wl.scaled(3, T=64 * 33 + 11)
+    Wq, Wk = wl.weights(sh)
+    dWq, dWk = P.w_to_dev(Wq, "bf16"), P.w_to_dev(Wk, "bf16")
+    cases = []
+    for seed in (11, 12):
+        q, k, v, _ = wl.sequence_inputs(wl.scaled(3, T=sh.T, seed=seed))
+        lay = P.make_layer(sh)
+        dq, dk, dv = P.to_dev(q, "bf16"), P.to_dev(k, "bf16"), P.to_dev(v, "bf16")
+        ref = lay.prefill(dq, dk, dv, dWq, dWk).clone()
+        torch.cuda.synchronize()
+        ref_state = [t.clone() for t in (lay.H, lay.s, lay.sp_idx, lay.win_k)]
+        cases.append((lay, dq, dk, dv, ref, ref_state))
+    outs, errs = [None, None], []
+
+    def run(i):
+        try:
+            lay, dq, dk, dv, _, _ = cases[i]
+            st = torch.cuda.Stream()
+            for _ in range(4):
+                lay.reset()
+                with torch.cuda.stream(st):
+                    outs[i] = lay.prefill(dq, dk, dv, dWq, dWk)
+                st.synchronize()
+        except Exception as e:   # surfaced in the main thread
+            errs.append(e)
+
+    torch.cuda.synchronize()
+    th = [threading.Thread(target=run, args=(i,)) for i in range(2)]
+    for t in th:
+        t.start()
+    for t in th:
+        t.join()
+    assert not errs, errs
+    torch.cuda.synchronize()
+    for i, (lay, _, _, _, ref, ref_state) in enumerate(cases):
+        assert torch.equal(outs[i], ref)
+        for got, want in zip((lay.H, lay.s, lay.sp_idx, lay.win_k), ref_state):
+            assert torch.equal(got, want)
+
+
 @pytest.mark.parametrize("lam", [64, 128])
 def test_1b_shape_resume_ragged_multipass(lam):
     """The MFMA prefill kernels at the 1B head shape (head_dim 64, 128 features) across call boundaries that are
