@@ -360,6 +360,9 @@ __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillAr
             LOLA_SREP(LOLA_SLOAD)
             if (tid0 < D) s_l[tid0] = sg[tid0];
             started = true;
+            // The state is waited for here, once: left to the first use, the wait would stand in the loop body behind the
+            // chunk's own requests (the counter is in order) and hold every chunk until half of those had arrived.
+            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
             __syncthreads();
         }
         if (j == a.j1 - 1) LOLA_STAMP(0);
@@ -411,6 +414,10 @@ __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillAr
             if (r16 != 0) { Ash[ks] = zero_bf16x8(); Asl[ks] = zero_bf16x8(); }
         }
         for (int e = tid; e < NE; e += NTH) cidx[e] = e < LAM ? sp_idx[e] : (int)(aj - ETA + (e - LAM));
+        // the snapshot's row list is requested ahead of the chunk's other loads (the wait counter is in order: requested
+        // where it is stored, its wait would cover all of them)
+        static_assert(LAM <= NTH, "one slot per thread");
+        const int sprow_ld = (a.want_out && tid < LAM) ? sp_row[tid] : 0;
 
         if (j == a.j1 - 1) LOLA_STAMP(1);
         // ---- 2. phi of the candidates and their recall error, in batches of TB tiles.  Global loads of a batch are
@@ -512,7 +519,7 @@ __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillAr
                     }
                 }
                 if (tid < D / 4) reinterpret_cast<float4 *>(a.snapS + sj * D)[tid] = reinterpret_cast<const float4 *>(s_l)[tid];
-                for (int sl = tid; sl < LAM; sl += NTH) a.snapG[sj * LAM + sl] = sp_row[sl];
+                if (tid < LAM) a.snapG[sj * LAM + tid] = sprow_ld;
             }
             if (j == a.j1 - 1 && t0 == 0) LOLA_STAMP(2);
             __syncthreads();
