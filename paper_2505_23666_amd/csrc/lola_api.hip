@@ -255,6 +255,10 @@ struct SideStream {
     hipStream_t s;
     hipEvent_t fork[NEV], join;
 };
+#ifndef LOLA_SCAN_RT128
+#define LOLA_SCAN_RT128 1
+#endif
+constexpr int SCAN_RT128 = LOLA_SCAN_RT128;   // row tiles of H^T per wavefront in the MFMA scan at head_dim 128
 constexpr size_t OVERLAP_MAX_STREAMS = 128;   // beyond this many streams the serial evolution fills the chip by itself
 constexpr int OVERLAP_MIN_PIECE = 8;          // chunks per piece at least; more than the (256 + 64) / 64 chunks after which
                                               // the sparse cache of the MFMA shapes is full
@@ -412,8 +416,8 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
                     // enqueued after it: it should be resident before the output workgroups arrive, instead of queueing
                     // for compute units behind them.
                     if (side && ip > 0 && hipEventRecord(side->fork[ip - 1], stream) != hipSuccess) return LOLA_ERR_HIP;
-#define LOLA_SCAN(LAMV) do { if (c->head_dim == 128) hipLaunchKernelGGL((fast::scan_fast_kernel<LAMV, 128>), gs, dim3(512), 0, stream, a); \
-                             else hipLaunchKernelGGL((fast::scan_fast_kernel<LAMV, 64>), gs, dim3(256), 0, stream, a); } while (0)
+#define LOLA_SCAN(LAMV) do { if (c->head_dim == 128) hipLaunchKernelGGL((fast::scan_fast_kernel<LAMV, 128, SCAN_RT128>), gs, dim3(512 / SCAN_RT128), 0, stream, a); \
+                             else hipLaunchKernelGGL((fast::scan_fast_kernel<LAMV, 64, 1>), gs, dim3(256), 0, stream, a); } while (0)
                     if (c->sparse_budget == 64) LOLA_SCAN(64); else if (c->sparse_budget == 128) LOLA_SCAN(128); else LOLA_SCAN(256);
 #undef LOLA_SCAN
                     LAUNCH_CHECK();

@@ -306,10 +306,13 @@ __device__ __forceinline__ unsigned long long below_mask(uint32_t v, uint32_t tr
     return m;
 }
 
-template <int LAM, int DH>
-__global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillArgs<bf16_t> a) {
-    // one wavefront per 16 rows of H^T: 8 wavefronts for head_dim 128, 4 for head_dim 64
-    constexpr int M = 64, D = 128, C = 64, ETA = 64, NW = DH / 16, NTH = 64 * NW, KS = DH / 32, PR = DH / 8;
+template <int LAM, int DH, int RT>
+__global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::PrefillArgs<bf16_t> a) {
+    // one wavefront per RT tiles of 16 rows of H^T (row tile RT w + rt).  With two tiles per wavefront (head_dim 128:
+    // four wavefronts) every feature operand read from LDS serves two row tiles, which halves the LDS traffic of the
+    // recall GEMM and of the fold, and one wavefront per SIMD has the whole register file (nothing spills).
+    constexpr int M = 64, D = 128, C = 64, ETA = 64, NW = DH / (16 * RT), NTH = 64 * NW, KS = DH / 32, PR = DH / 8;
+    static_assert(RT == 1 || RT == 2, "row tiles per wavefront");
     static_assert(DH == 64 || DH == 128, "head_dim");
     constexpr int P = LAM + ETA, NE = LAM + C, NTILE = NE / 16, TB = LAM > 128 ? 10 : 12, RB = TB * 16;
     constexpr int TPW = (TB + NW - 1) / NW, NK = NE / 64, TC = LAM / 16;
@@ -329,7 +332,11 @@ __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillAr
     __shared__ int flist[C], ecand[C], eslot[C];
     // per wavefront: |P|^2, P.v, |v|^2 over its 16 value columns; lives in the transposed tile, which is idle until the selection is done
     float (*part)[NW][NE] = reinterpret_cast<float (*)[NW][NE]>(PT);
-    static_assert(3 * NW * NE * 4 <= 2 * D * C * 2, "the partial sums fit the transposed tile");
+#ifndef LOLA_PIPE_ALL
+#define LOLA_PIPE_ALL 0
+#endif
+    constexpr bool PIPE = NW == 4 || (LOLA_PIPE_ALL && 4 * NW * NE * 4 <= 2 * D * C * 2);   // the recall loop is software-pipelined (a fourth, spare row of sums)
+    static_assert((PIPE ? 4 : 3) * NW * NE * 4 <= 2 * D * C * 2, "the partial sums fit the transposed tile");
 
     const int tid0 = threadIdx.x, w0 = tid0 >> 6;
     const int si = blockIdx.x, h = si % a.dm.Hkv;
@@ -346,12 +353,13 @@ __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillAr
     const int spc = a.st.sp_count[si];
     int j = a.next_j[si];
 
-    // H^T row 16w + r16, features 32ks + 16hf + 4g4 + 0..3
-#define LOLA_SREP(X) X(0, 0) X(0, 1) X(1, 0) X(1, 1) X(2, 0) X(2, 1) X(3, 0) X(3, 1)
-#define LOLA_SADDR(ks, hf) ((size_t)(16 * w0 + (tid0 & 15)) * D + 32 * ks + 16 * hf + 4 * ((tid0 & 63) >> 4))
-#define LOLA_SDECL(ks, hf) f32x4 hreg##ks##hf = {0.f, 0.f, 0.f, 0.f};
-#define LOLA_SLOAD(ks, hf) hreg##ks##hf = *reinterpret_cast<const f32x4 *>(Hg + LOLA_SADDR(ks, hf));
-#define LOLA_SSTORE(ks, hf) *reinterpret_cast<f32x4 *>(Hg + LOLA_SADDR(ks, hf)) = hreg##ks##hf;
+    // H^T row 16 (RT w + rt) + r16, features 32ks + 16hf + 4g4 + 0..3 (the names of row tile 1 stay unused when RT = 1)
+#define LOLA_SREP1(X, rt) X(rt, 0, 0) X(rt, 0, 1) X(rt, 1, 0) X(rt, 1, 1) X(rt, 2, 0) X(rt, 2, 1) X(rt, 3, 0) X(rt, 3, 1)
+#define LOLA_SREP(X) LOLA_SREP1(X, 0) LOLA_SREP1(X, 1)
+#define LOLA_SADDR(rt, ks, hf) ((size_t)(16 * (RT * w0 + rt) + (tid0 & 15)) * D + 32 * ks + 16 * hf + 4 * ((tid0 & 63) >> 4))
+#define LOLA_SDECL(rt, ks, hf) f32x4 hreg##rt##ks##hf = {0.f, 0.f, 0.f, 0.f};
+#define LOLA_SLOAD(rt, ks, hf) if (rt < RT) hreg##rt##ks##hf = *reinterpret_cast<const f32x4 *>(Hg + LOLA_SADDR(rt, ks, hf));
+#define LOLA_SSTORE(rt, ks, hf) if (rt < RT) *reinterpret_cast<f32x4 *>(Hg + LOLA_SADDR(rt, ks, hf)) = hreg##rt##ks##hf;
     LOLA_SREP(LOLA_SDECL)
     bool started = false;
     if (tid0 == 0) thr_s = 0;   // published by the barrier that follows the loading of the state
@@ -360,9 +368,11 @@ __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillAr
                                 // chunk of this launch left them there), and the feature kernel's rows of that chunk are the leaving pairs'
     constexpr int PHN = C * 32 / NTH;   // 16-byte pieces of a chunk's features per thread
     uint4 PHn[PHN];             // this thread's pieces of phi of the pairs that leave the window in the next chunk
-    uint2 vvn[4];               // their values at this wavefront's columns
+    uint2 vvn[4][RT];           // their values at this wavefront's columns
 #pragma unroll
-    for (int x = 0; x < 4; x++) vvn[x] = make_uint2(0, 0);
+    for (int x = 0; x < 4; x++)
+#pragma unroll
+        for (int rt = 0; rt < RT; rt++) vvn[x][rt] = make_uint2(0, 0);
 #pragma unroll
     for (int x = 0; x < PHN; x++) PHn[x] = make_uint4(0, 0, 0, 0);
 
@@ -408,12 +418,12 @@ __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillAr
 
         // ---- 1. operands of the recall GEMM from the fp32 registers (H^T, and s as one more row held by the lanes
         // of row 0); the snapshot for the output kernel is stored further down
-        bf16x8 Ahi[4], Alo[4], Ash[4], Asl[4];
-#define LOLA_SSPLIT(ks, hf) { const f32x4 v = hreg##ks##hf; \
+        bf16x8 Ahi[RT][4], Alo[RT][4], Ash[4], Asl[4];
+#define LOLA_SSPLIT(rt, ks, hf) if (rt < RT) { const f32x4 v = hreg##rt##ks##hf; \
             const __bf16 h0 = (__bf16)v[0], h1 = (__bf16)v[1], h2 = (__bf16)v[2], h3 = (__bf16)v[3]; \
-            Ahi[ks][4 * hf] = h0; Ahi[ks][4 * hf + 1] = h1; Ahi[ks][4 * hf + 2] = h2; Ahi[ks][4 * hf + 3] = h3; \
-            Alo[ks][4 * hf] = (__bf16)(v[0] - (float)h0); Alo[ks][4 * hf + 1] = (__bf16)(v[1] - (float)h1); \
-            Alo[ks][4 * hf + 2] = (__bf16)(v[2] - (float)h2); Alo[ks][4 * hf + 3] = (__bf16)(v[3] - (float)h3); }
+            Ahi[rt % RT][ks][4 * hf] = h0; Ahi[rt % RT][ks][4 * hf + 1] = h1; Ahi[rt % RT][ks][4 * hf + 2] = h2; Ahi[rt % RT][ks][4 * hf + 3] = h3; \
+            Alo[rt % RT][ks][4 * hf] = (__bf16)(v[0] - (float)h0); Alo[rt % RT][ks][4 * hf + 1] = (__bf16)(v[1] - (float)h1); \
+            Alo[rt % RT][ks][4 * hf + 2] = (__bf16)(v[2] - (float)h2); Alo[rt % RT][ks][4 * hf + 3] = (__bf16)(v[3] - (float)h3); }
         LOLA_SREP(LOLA_SSPLIT)
 #undef LOLA_SSPLIT
 #pragma unroll
@@ -440,13 +450,16 @@ __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillAr
 #pragma unroll 1
         for (int t0 = 0; t0 < NTILE; t0 += TB) {
             const int t1 = min(NTILE, t0 + TB);
-            uint2 vv[TB];
+            uint2 vv[TB][RT];
 #pragma unroll
             for (int u = 0; u < TB; u++) {
-                if (PERSIST && u >= TC && have_phi) {
-                    vv[u] = vvn[u >= TC ? u - TC : 0];
-                } else if (t0 + u < t1) {
-                    vv[u] = *reinterpret_cast<const uint2 *>(vrow(16 * (t0 + u) + r16) + 16 * w + 4 * g4);
+#pragma unroll
+                for (int rt = 0; rt < RT; rt++) {
+                    if (PERSIST && u >= TC && have_phi) {
+                        vv[u][rt] = vvn[u >= TC ? u - TC : 0][rt];
+                    } else if (t0 + u < t1) {
+                        vv[u][rt] = *reinterpret_cast<const uint2 *>(vrow(16 * (t0 + u) + r16) + 16 * (RT * w + rt) + 4 * g4);
+                    }
                 }
             }
             if (have_phi) {   // the rows requested one chunk ago take their place behind the cache's rows
@@ -518,19 +531,23 @@ __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillAr
                 for (int it = 0; it < PHN; it++) PHn[it] = ph[tid + NTH * it];
 #pragma unroll
                 for (int u = 0; u < 4; u++)
-                    vvn[u] = *reinterpret_cast<const uint2 *>(vc + (size_t)(j * C + 16 * u + r16) * DH + 16 * w + 4 * g4);
+#pragma unroll
+                    for (int rt = 0; rt < RT; rt++)
+                        vvn[u][rt] = *reinterpret_cast<const uint2 *>(vc + (size_t)(j * C + 16 * u + r16) * DH + 16 * (RT * w + rt) + 4 * g4);
             }
             if (a.want_out && t0 == 0) {
                 const size_t sj = (size_t)si * a.S + (j - a.jb);
                 if (w == 0) {
                     uint16_t *s16 = reinterpret_cast<uint16_t *>(a.snapH) + sj * (2 * D * DH);
 #pragma unroll
-                    for (int ks = 0; ks < 4; ks++) {
-                        // one contiguous 1 KB piece per store: [row tile w][k-step][lane]
-                        const int off = ((w * 4 + ks) * 64 + lane) << 3;
-                        *reinterpret_cast<uint4 *>(s16 + off) = __builtin_bit_cast(uint4, Ahi[ks]);
-                        *reinterpret_cast<uint4 *>(s16 + D * DH + off) = __builtin_bit_cast(uint4, Alo[ks]);
-                    }
+                    for (int rt = 0; rt < RT; rt++)
+#pragma unroll
+                        for (int ks = 0; ks < 4; ks++) {
+                            // one contiguous 1 KB piece per store: [row tile][k-step][lane]
+                            const int off = (((RT * w + rt) * 4 + ks) * 64 + lane) << 3;
+                            *reinterpret_cast<uint4 *>(s16 + off) = __builtin_bit_cast(uint4, Ahi[rt][ks]);
+                            *reinterpret_cast<uint4 *>(s16 + D * DH + off) = __builtin_bit_cast(uint4, Alo[rt][ks]);
+                        }
                 }
                 if (tid < D / 4) reinterpret_cast<float4 *>(a.snapS + sj * D)[tid] = reinterpret_cast<const float4 *>(s_l)[tid];
                 if (tid < LAM) a.snapG[sj * LAM + tid] = sprow_ld;
@@ -550,6 +567,71 @@ __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillAr
                 Bc[ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(&PB[addr]));
                 Bc[4 + ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(&PB[RB * D + addr]));
             }
+            if constexpr (PIPE) {
+                // One wavefront per SIMD: the error terms of tile u - 1 (vector instructions) are issued between the
+                // matrix instructions of tile u, in one branch-free block per tile (the three sums leave through one
+                // store: lane group g4 stores sum g4, group 3 into a spare row); the denominators' matrix
+                // instructions follow in a block of their own.
+                f32x4 pp[RT];
+#pragma unroll
+                for (int rt = 0; rt < RT; rt++) pp[rt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int u = 0; u <= TB; u++) {
+                    const bool cur = u < TB && t0 + u < t1, prev = u > 0 && t0 + u - 1 < t1;
+                    f32x4 acc[RT];   // the three products of a k-step go into one accumulator: the large one first
+#pragma unroll
+                    for (int rt = 0; rt < RT; rt++) acc[rt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+                    if (cur) {
+                        if (u + 1 < TB && t0 + u + 1 < t1) {
+#pragma unroll
+                            for (int ks = 0; ks < 4; ks++) {
+                                const int addr = (16 * (u + 1) + r16) * D + (((4 * ks + g4) ^ r16) << 3);
+                                Bn[ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(&PB[addr]));
+                                Bn[4 + ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(&PB[RB * D + addr]));
+                            }
+                        }
+#pragma unroll
+                        for (int pass = 0; pass < 3; pass++)
+#pragma unroll
+                            for (int ks = 0; ks < 4; ks++)
+#pragma unroll
+                                for (int rt = 0; rt < RT; rt++)
+                                    acc[rt] = mfma16(pass == 2 ? Alo[rt][ks] : Ahi[rt][ks], Bc[pass == 1 ? 4 + ks : ks], acc[rt]);
+                    }
+                    if (prev) {
+                        float sa = 0.f, sb = 0.f, sc = 0.f;
+#pragma unroll
+                        for (int rt = 0; rt < RT; rt++) {
+                            const f32x4 p = pp[rt];
+                            const uint2 vvu = vv[u > 0 ? u - 1 : 0][rt];
+                            const float v0 = bf_lo(vvu.x), v1 = bf_hi(vvu.x), v2 = bf_lo(vvu.y), v3 = bf_hi(vvu.y);
+                            sa = fmaf(p[0], p[0], sa); sa = fmaf(p[1], p[1], sa); sa = fmaf(p[2], p[2], sa); sa = fmaf(p[3], p[3], sa);
+                            sb = fmaf(p[0], v0, sb); sb = fmaf(p[1], v1, sb); sb = fmaf(p[2], v2, sb); sb = fmaf(p[3], v3, sb);
+                            sc = fmaf(v0, v0, sc); sc = fmaf(v1, v1, sc); sc = fmaf(v2, v2, sc); sc = fmaf(v3, v3, sc);
+                        }
+                        sa = grp_sum(sa); sb = grp_sum(sb); sc = grp_sum(sc);
+                        part[g4][w][16 * (t0 + u - 1) + r16] = g4 == 0 ? sa : (g4 == 1 ? sb : sc);
+                    }
+                    if (cur) {
+#pragma unroll
+                        for (int rt = 0; rt < RT; rt++) pp[rt] = acc[rt];
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (cur && ((t0 + u) & (NW - 1)) == w) {
+                        f32x4 ds = {0.f, 0.f, 0.f, 0.f}, ds2 = {0.f, 0.f, 0.f, 0.f}, ds3 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                        for (int ks = 0; ks < 4; ks++) {
+                            ds = mfma16(Ash[ks], Bc[ks], ds);
+                            ds2 = mfma16(Ash[ks], Bc[4 + ks], ds2);
+                            ds3 = mfma16(Asl[ks], Bc[ks], ds3);
+                        }
+                        if (g4 == 0) dn_l[16 * (t0 + u) + r16] = ds[0] + (ds2[0] + ds3[0]);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int x = 0; x < 8; x++) Bc[x] = Bn[x];
+                }
+            } else {
 #pragma unroll
             for (int u = 0; u < TB; u++) {
                 if (t0 + u < t1) {
@@ -562,13 +644,16 @@ __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillAr
                             Bn[4 + ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(&PB[RB * D + addr]));
                         }
                     }
-                    f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acc2 = {0.f, 0.f, 0.f, 0.f}, acc3 = {0.f, 0.f, 0.f, 0.f};
+                    f32x4 acc[RT];   // the three products of a k-step go into one accumulator: the large one first
 #pragma unroll
-                    for (int ks = 0; ks < 4; ks++) {
-                        acc = mfma16(Ahi[ks], Bc[ks], acc);
-                        acc2 = mfma16(Ahi[ks], Bc[4 + ks], acc2);
-                        acc3 = mfma16(Alo[ks], Bc[ks], acc3);
-                    }
+                    for (int rt = 0; rt < RT; rt++) acc[rt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int pass = 0; pass < 3; pass++)
+#pragma unroll
+                        for (int ks = 0; ks < 4; ks++)
+#pragma unroll
+                            for (int rt = 0; rt < RT; rt++)
+                                acc[rt] = mfma16(pass == 2 ? Alo[rt][ks] : Ahi[rt][ks], Bc[pass == 1 ? 4 + ks : ks], acc[rt]);
                     if (((t0 + u) & (NW - 1)) == w) {
                         f32x4 ds = {0.f, 0.f, 0.f, 0.f}, ds2 = {0.f, 0.f, 0.f, 0.f}, ds3 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -579,18 +664,22 @@ __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillAr
                         }
                         if (g4 == 0) dn_l[e] = ds[0] + (ds2[0] + ds3[0]);
                     }
-                    const f32x4 p = acc + (acc2 + acc3);
-                    const float v0 = bf_lo(vv[u].x), v1 = bf_hi(vv[u].x), v2 = bf_lo(vv[u].y), v3 = bf_hi(vv[u].y);
-                    float sa = p[0] * p[0], sb = p[0] * v0, sc = v0 * v0;
-                    sa = fmaf(p[1], p[1], sa); sa = fmaf(p[2], p[2], sa); sa = fmaf(p[3], p[3], sa);
-                    sb = fmaf(p[1], v1, sb); sb = fmaf(p[2], v2, sb); sb = fmaf(p[3], v3, sb);
-                    sc = fmaf(v1, v1, sc); sc = fmaf(v2, v2, sc); sc = fmaf(v3, v3, sc);
+                    float sa = 0.f, sb = 0.f, sc = 0.f;
+#pragma unroll
+                    for (int rt = 0; rt < RT; rt++) {
+                        const f32x4 p = acc[rt];
+                        const float v0 = bf_lo(vv[u][rt].x), v1 = bf_hi(vv[u][rt].x), v2 = bf_lo(vv[u][rt].y), v3 = bf_hi(vv[u][rt].y);
+                        sa = fmaf(p[0], p[0], sa); sa = fmaf(p[1], p[1], sa); sa = fmaf(p[2], p[2], sa); sa = fmaf(p[3], p[3], sa);
+                        sb = fmaf(p[0], v0, sb); sb = fmaf(p[1], v1, sb); sb = fmaf(p[2], v2, sb); sb = fmaf(p[3], v3, sb);
+                        sc = fmaf(v0, v0, sc); sc = fmaf(v1, v1, sc); sc = fmaf(v2, v2, sc); sc = fmaf(v3, v3, sc);
+                    }
                     sa = grp_sum(sa); sb = grp_sum(sb); sc = grp_sum(sc);
                     if (g4 == 0) { part[0][w][e] = sa; part[1][w][e] = sb; part[2][w][e] = sc; }
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                     for (int x = 0; x < 8; x++) Bc[x] = Bn[x];
                 }
+            }
             }
             if (j == a.j1 - 1 && t0 == 0) LOLA_STAMP(4);
             __syncthreads();
@@ -622,17 +711,20 @@ __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillAr
                 for (int it = 0; it < PHN; it++) PHn[it] = ph[tid + NTH * it];
 #pragma unroll
                 for (int u = 0; u < 4; u++)
-                    vvn[u] = *reinterpret_cast<const uint2 *>(vc + (size_t)(j * C + 16 * u + r16) * DH + 16 * w + 4 * g4);
+#pragma unroll
+                    for (int rt = 0; rt < RT; rt++)
+                        vvn[u][rt] = *reinterpret_cast<const uint2 *>(vc + (size_t)(j * C + 16 * u + r16) * DH + 16 * (RT * w + rt) + 4 * g4);
             }
             if (a.want_out) {
                 uint16_t *s16 = reinterpret_cast<uint16_t *>(a.snapH) + ((size_t)si * a.S + (j - a.jb)) * (2 * D * DH);
-#define LOLA_SSNAP(ks) { float sv[8]; \
-                _Pragma("unroll") for (int x = 0; x < 4; x++) { sv[x] = hreg##ks##0[x]; sv[4 + x] = hreg##ks##1[x]; } \
+#define LOLA_SSNAP(rt, ks) if (rt < RT) { float sv[8]; \
+                _Pragma("unroll") for (int x = 0; x < 4; x++) { sv[x] = hreg##rt##ks##0[x]; sv[4 + x] = hreg##rt##ks##1[x]; } \
                 bf16x8 hi8, lo8; split8(sv, hi8, lo8); \
-                const int off = ((w * 4 + ks) * 64 + lane) << 3; \
+                const int off = (((RT * w + rt) * 4 + ks) * 64 + lane) << 3; \
                 *reinterpret_cast<uint4 *>(s16 + off) = __builtin_bit_cast(uint4, hi8); \
                 *reinterpret_cast<uint4 *>(s16 + D * DH + off) = __builtin_bit_cast(uint4, lo8); }
-                LOLA_SSNAP(0) LOLA_SSNAP(1) LOLA_SSNAP(2) LOLA_SSNAP(3)
+                LOLA_SSNAP(0, 0) LOLA_SSNAP(0, 1) LOLA_SSNAP(0, 2) LOLA_SSNAP(0, 3)
+                LOLA_SSNAP(1, 0) LOLA_SSNAP(1, 1) LOLA_SSNAP(1, 2) LOLA_SSNAP(1, 3)
 #undef LOLA_SSNAP
             }
         } else {
@@ -723,7 +815,8 @@ __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillAr
             // phi^T: piece ch, part pt = w % 2 and column chunk w / 2 + (NW / 2) it of the folded pairs
             constexpr int CPW = NW / 2, PIT = 8 / CPW;
             const int ch = tid & 15, pairpos = (tid >> 4) & 3, pt = w & 1;
-            uint4 pa[PIT], pb[PIT], va, vb;
+            constexpr int VIT = 32 * PR / NTH;   // column pairs of v^T per thread
+            uint4 pa[PIT], pb[PIT], va[VIT], vb[VIT];
 #pragma unroll
             for (int it = 0; it < PIT; it++) {
                 const int ep = 8 * ((w >> 1) + CPW * it) + 2 * pairpos;
@@ -736,12 +829,13 @@ __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillAr
                     pb[it] = *reinterpret_cast<const uint4 *>(phirow(eb) + pt * D + (ch << 3));
                 }
             }
-            // v^T: one item per thread: piece vch of the value rows of column pair vpair
-            const int vch = tid % PR, vpair = tid / PR;
-            {
-                const int ep = 2 * vpair;
-                va = reinterpret_cast<const uint4 *>(vrow(flist[ep]))[vch];
-                vb = reinterpret_cast<const uint4 *>(vrow(flist[ep + 1]))[vch];
+            // v^T: VIT items per thread: piece vch of the value rows of column pair vpair0 + (NTH / PR) vit
+            const int vch = tid % PR, vpair0 = tid / PR;
+#pragma unroll
+            for (int vit = 0; vit < VIT; vit++) {
+                const int ep = 2 * (vpair0 + (NTH / PR) * vit);
+                va[vit] = reinterpret_cast<const uint4 *>(vrow(flist[ep]))[vch];
+                vb[vit] = reinterpret_cast<const uint4 *>(vrow(flist[ep + 1]))[vch];
             }
             // feature held by element x of piece ch (operand order): 32 (ch / 4) + 16 (x / 4) + 4 (ch % 4) + x % 4
 #pragma unroll
@@ -756,12 +850,16 @@ __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillAr
                 }
             }
 #pragma unroll
-            for (int x = 0; x < 8; x++) {
-                const int c = 8 * vch + x;
-                const int bx = c * C + ((((vpair >> 2) ^ tswz(c))) << 3) + 2 * (vpair & 3);
-                const uint32_t ua = (&va.x)[x >> 1], ub = (&vb.x)[x >> 1];
-                const uint32_t wv = (x & 1) ? ((ua >> 16) | (ub & 0xFFFF0000u)) : ((ua & 0xFFFFu) | (ub << 16));
-                *reinterpret_cast<uint32_t *>(&VT[bx]) = wv;
+            for (int vit = 0; vit < VIT; vit++) {
+                const int vpair = vpair0 + (NTH / PR) * vit;
+#pragma unroll
+                for (int x = 0; x < 8; x++) {
+                    const int c = 8 * vch + x;
+                    const int bx = c * C + ((((vpair >> 2) ^ tswz(c))) << 3) + 2 * (vpair & 3);
+                    const uint32_t ua = (&va[vit].x)[x >> 1], ub = (&vb[vit].x)[x >> 1];
+                    const uint32_t wv = (x & 1) ? ((ua >> 16) | (ub & 0xFFFF0000u)) : ((ua & 0xFFFFu) | (ub << 16));
+                    *reinterpret_cast<uint32_t *>(&VT[bx]) = wv;
+                }
             }
         }
         if (j == a.j1 - 1) LOLA_STAMP(8);
@@ -770,9 +868,10 @@ __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillAr
         {
             // compaction, first half: the entrants' rows are requested now and stored after the fold (all reads of
             // the leavers' rows were completed before the barrier above)
-            uint4 cp[4];
+            constexpr int CIT = C * 2 * PR / NTH;   // 16-byte pieces of up to 64 entrants' rows per thread
+            uint4 cp[CIT];
 #pragma unroll
-            for (int it = 0; it < 4; it++) {
+            for (int it = 0; it < CIT; it++) {
                 const int o = tid + NTH * it;
                 if (o < ne * 2 * PR) {
                     const int x = o / (2 * PR), rem = o % (2 * PR);
@@ -780,12 +879,14 @@ __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillAr
                     cp[it] = reinterpret_cast<const uint4 *>((rem >= PR) ? vrow(e) : krow(e))[rem % PR];
                 }
             }
-            bf16x8 Bv[2];
+            bf16x8 Bv[RT][2];
 #pragma unroll
-            for (int k2 = 0; k2 < 2; k2++) {
-                const int c = 16 * w + r16;
-                Bv[k2] = as_bf16x8(*reinterpret_cast<const uint4 *>(&VT[c * C + (((4 * k2 + g4) ^ tswz(c)) << 3)]));
-            }
+            for (int rt = 0; rt < RT; rt++)
+#pragma unroll
+                for (int k2 = 0; k2 < 2; k2++) {
+                    const int c = 16 * (RT * w + rt) + r16;
+                    Bv[rt][k2] = as_bf16x8(*reinterpret_cast<const uint4 *>(&VT[c * C + (((4 * k2 + g4) ^ tswz(c)) << 3)]));
+                }
             // per feature tile (16 features): four A operands (high / low part x two k-steps); the operands of the next
             // tile are read from LDS before this tile's MFMAs are issued
             bf16x8 Ac[4], An[4];
@@ -798,11 +899,12 @@ __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillAr
 #pragma unroll
             for (int x = 0; x < 8 / NW; x++) sacc[x] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #define LOLA_SFOLD2(ks, hf) { if (2 * ks + hf + 1 < 8) { LOLA_SFA(An, 2 * ks + hf + 1) } \
-            _Pragma("unroll") for (int x = 0; x < 4; x++) hreg##ks##hf = mfma16(Ac[x], Bv[x & 1], hreg##ks##hf); \
+            _Pragma("unroll") for (int x = 0; x < 4; x++) { hreg0##ks##hf = mfma16(Ac[x], Bv[0][x & 1], hreg0##ks##hf); \
+                                                            if (RT > 1) hreg1##ks##hf = mfma16(Ac[x], Bv[RT - 1][x & 1], hreg1##ks##hf); } \
             if (((2 * ks + hf) & (NW - 1)) == w) { _Pragma("unroll") for (int x = 0; x < 4; x++) sacc[(2 * ks + hf) / NW] = mfma16(Ac[x], ones, sacc[(2 * ks + hf) / NW]); } \
             __builtin_amdgcn_sched_barrier(0); \
             _Pragma("unroll") for (int x = 0; x < 4; x++) Ac[x] = An[x]; }
-            LOLA_SREP(LOLA_SFOLD2)
+            LOLA_SFOLD2(0, 0) LOLA_SFOLD2(0, 1) LOLA_SFOLD2(1, 0) LOLA_SFOLD2(1, 1) LOLA_SFOLD2(2, 0) LOLA_SFOLD2(2, 1) LOLA_SFOLD2(3, 0) LOLA_SFOLD2(3, 1)
 #undef LOLA_SFOLD2
 #undef LOLA_SFA
             if (r16 == 0) {   // column 0 of the result tiles: features 16 (w + NW x) + 4 g4 + 0..3
@@ -817,7 +919,7 @@ __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillAr
             if (j == a.j1 - 1) LOLA_STAMP(10);
             // ---- 5. compaction, second half: entrants take the leavers' slots, in the state and (their features) in LDS
 #pragma unroll
-            for (int it = 0; it < 4; it++) {
+            for (int it = 0; it < CIT; it++) {
                 const int o = tid + NTH * it;
                 if (o < ne * 2 * PR) {
                     const int x = o / (2 * PR), rem = o % (2 * PR);
@@ -871,6 +973,7 @@ __global__ __launch_bounds__(DH * 4, 1) void scan_fast_kernel(generic::PrefillAr
     }
     if (tid0 == 0) a.next_j[si] = j;
 #undef LOLA_SREP
+#undef LOLA_SREP1
 #undef LOLA_SADDR
 #undef LOLA_SDECL
 #undef LOLA_SLOAD
