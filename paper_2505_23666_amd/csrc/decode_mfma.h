@@ -81,6 +81,17 @@ __device__ __forceinline__ void swap32(float v, float &r0, float &r1) {
 }
 // reductions over the four lanes that share l % 16
 __device__ __forceinline__ float grp_sum(float v) { float x, y; swap16(v, x, y); v = x + y; swap32(v, x, y); return x + y; }
+// Three sums at once over the four lanes that share l % 16: lane group l / 16 = 0, 1, 2 receives the sum of a, b, c
+// (group 3 receives 0).  The row swap exchanges the odd rows of its first operand with the even rows of its second, so
+// one swap pairs partial sums of two different quantities: three swaps and three additions instead of six and six.
+__device__ __forceinline__ float grp_sum3(float a, float b, float c) {
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+    const float x = __uint_as_float(r[0]) + __uint_as_float(r[1]);   // rows: a0+a1, b0+b1, a2+a3, b2+b3
+    const auto q = __builtin_amdgcn_permlane16_swap(__float_as_uint(c), 0u, false, false);
+    const float y = __uint_as_float(q[0]) + __uint_as_float(q[1]);   // rows: c0+c1, 0, c2+c3, 0
+    const auto t = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(y), false, false);
+    return __uint_as_float(t[0]) + __uint_as_float(t[1]);            // rows: sum a, sum b, sum c, 0
+}
 __device__ __forceinline__ float grp_max(float v) { float x, y; swap16(v, x, y); v = fmaxf(x, y); swap32(v, x, y); return fmaxf(x, y); }
 __device__ __forceinline__ float grp_min(float v) { float x, y; swap16(v, x, y); v = fminf(x, y); swap32(v, x, y); return fminf(x, y); }
 // reductions over the whole wavefront: four data-parallel-primitive steps inside each row of 16 lanes (swap

@@ -609,8 +609,7 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
                             sb = fmaf(p[0], v0, sb); sb = fmaf(p[1], v1, sb); sb = fmaf(p[2], v2, sb); sb = fmaf(p[3], v3, sb);
                             sc = fmaf(v0, v0, sc); sc = fmaf(v1, v1, sc); sc = fmaf(v2, v2, sc); sc = fmaf(v3, v3, sc);
                         }
-                        sa = grp_sum(sa); sb = grp_sum(sb); sc = grp_sum(sc);
-                        part[g4][w][16 * (t0 + u - 1) + r16] = g4 == 0 ? sa : (g4 == 1 ? sb : sc);
+                        part[g4][w][16 * (t0 + u - 1) + r16] = grp_sum3(sa, sb, sc);
                     }
                     if (cur) {
 #pragma unroll
@@ -673,8 +672,8 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
                         sb = fmaf(p[0], v0, sb); sb = fmaf(p[1], v1, sb); sb = fmaf(p[2], v2, sb); sb = fmaf(p[3], v3, sb);
                         sc = fmaf(v0, v0, sc); sc = fmaf(v1, v1, sc); sc = fmaf(v2, v2, sc); sc = fmaf(v3, v3, sc);
                     }
-                    sa = grp_sum(sa); sb = grp_sum(sb); sc = grp_sum(sc);
-                    if (g4 == 0) { part[0][w][e] = sa; part[1][w][e] = sb; part[2][w][e] = sc; }
+                    const float s3 = grp_sum3(sa, sb, sc);   // lane group g4 holds sum g4
+                    if (g4 < 3) part[g4][w][e] = s3;
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                     for (int x = 0; x < 8; x++) Bc[x] = Bn[x];
