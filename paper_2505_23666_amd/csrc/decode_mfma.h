@@ -629,31 +629,31 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
             const uint16_t *bh = kt < NKT ? PB + (16 * kt + r16) * D : PX + (r16 < XR ? r16 : 0) * D;
             const uint16_t *bl = kt < NKT ? bh + LAM * D : bh + XR * D;
             const int swz = kt < NKT ? r16 : (r16 < XR ? r16 : 0);
-            // three passes (high x high, high x low, low x high), each with accumulators of its own: six independent
-            // chains keep the matrix pipe from waiting on its own results
-            f32x4 acc[NCT], acc2[NCT], acc3[NCT];
+            // three passes (high x high, high x low, low x high) into one accumulator per row tile, the large products
+            // first; the row tiles alternate, so a matrix instruction never waits on the one before it
+            f32x4 acc[NCT];
 #pragma unroll
-            for (int ct = 0; ct < NCT; ct++) { acc[ct] = (f32x4){0.f, 0.f, 0.f, 0.f}; acc2[ct] = acc[ct]; acc3[ct] = acc[ct]; }
+            for (int ct = 0; ct < NCT; ct++) acc[ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            bf16x8 Bh[4], Bl[4];
 #pragma unroll
             for (int ks = 0; ks < 4; ks++) {
                 const int off = ((4 * ks + g4) ^ swz) << 3;
-                const bf16x8 Bh = as_bf16x8(*reinterpret_cast<const uint4 *>(bh + off));
-                const bf16x8 Bl = as_bf16x8(*reinterpret_cast<const uint4 *>(bl + off));
-#pragma unroll
-                for (int ct = 0; ct < NCT; ct++) acc[ct] = mfma16(Ahi[ct][ks], Bh, acc[ct]);
-#pragma unroll
-                for (int ct = 0; ct < NCT; ct++) acc2[ct] = mfma16(Ahi[ct][ks], Bl, acc2[ct]);
-#pragma unroll
-                for (int ct = 0; ct < NCT; ct++) acc3[ct] = mfma16(Alo[ct][ks], Bh, acc3[ct]);
+                Bh[ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(bh + off));
+                Bl[ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(bl + off));
             }
 #pragma unroll
-            for (int ct = 0; ct < NCT; ct++) acc2[ct] += acc3[ct];
+            for (int pass = 0; pass < 3; pass++)
+#pragma unroll
+                for (int ks = 0; ks < 4; ks++)
+#pragma unroll
+                    for (int ct = 0; ct < NCT; ct++)
+                        acc[ct] = mfma16(pass == 2 ? Alo[ct][ks] : Ahi[ct][ks], pass == 1 ? Bl[ks] : Bh[ks], acc[ct]);
             if (kt < NKT) {
                 const float rd = rden_l[16 * kt + r16];
                 float e2 = 0.f;
 #pragma unroll
                 for (int ct = 0; ct < NCT; ct++) {
-                    const f32x4 p = acc[ct] + acc2[ct];
+                    const f32x4 p = acc[ct];
                     const uint2 vv = vrec[kt < NKT ? kt : 0][ct];
                     const float e0 = fmaf(p[0], rd, -bf_lo(vv.x)), e1 = fmaf(p[1], rd, -bf_hi(vv.x));
                     const float e2_ = fmaf(p[2], rd, -bf_lo(vv.y)), e3 = fmaf(p[3], rd, -bf_hi(vv.y));
@@ -666,7 +666,7 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
                 float e2 = 0.f;
 #pragma unroll
                 for (int ct = 0; ct < NCT; ct++) {
-                    const f32x4 p = acc[ct] + acc2[ct];
+                    const f32x4 p = acc[ct];
                     const int c0 = CW * w + 16 * ct + 4 * g4;
                     if (r16 == 0) {
 #pragma unroll
