@@ -362,6 +362,7 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
 #define LOLA_SSTORE(rt, ks, hf) if (rt < RT) *reinterpret_cast<f32x4 *>(Hg + LOLA_SADDR(rt, ks, hf)) = hreg##rt##ks##hf;
     LOLA_SREP(LOLA_SDECL)
     bool started = false;
+    bool idx_valid = false;     // rows [0, LAM) of cidx hold the cache slots' token indices
     if (tid0 == 0) thr_s = 0;   // published by the barrier that follows the loading of the state
     bool phi_valid = false;     // PERSIST: rows [0, LAM) of PB hold phi of the cache slots, and PHn / vvn the rows requested ahead
     bool rows_valid = false;    // !PERSIST: rows [0, LAM) of the global feature scratch hold phi of the cache slots (the previous
@@ -437,7 +438,11 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
             split8(sv, Ash[ks], Asl[ks]);
             if (r16 != 0) { Ash[ks] = zero_bf16x8(); Asl[ks] = zero_bf16x8(); }
         }
-        for (int e = tid; e < NE; e += NTH) cidx[e] = e < LAM ? sp_idx[e] : (int)(aj - ETA + (e - LAM));
+        // token indices of the candidates: the cache slots' stay in LDS from chunk to chunk (an entrant's index follows
+        // it into its slot), so only a launch's first chunk reads them from memory
+        if (!idx_valid)
+            for (int e = tid; e < LAM; e += NTH) cidx[e] = sp_idx[e];
+        for (int e = LAM + tid; e < NE; e += NTH) cidx[e] = (int)(aj - ETA + (e - LAM));
         // the snapshot's row list is requested ahead of the chunk's other loads (the wait counter is in order: requested
         // where it is stored, its wait would cover all of them)
         static_assert(LAM <= NTH, "one slot per thread");
@@ -953,9 +958,12 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
         }
         for (int x = tid; x < ne; x += NTH) {
             const int e = ecand[x], sl = eslot[x];
-            sp_idx[sl] = cidx[e];
+            const int ti = cidx[e];
+            sp_idx[sl] = ti;
+            cidx[sl] = ti;
             sp_row[sl] = vrow_c - ETA + (e - LAM);
         }
+        idx_valid = true;
         phi_valid = PERSIST;
         rows_valid = !PERSIST;
         if (j == a.j1 - 1) LOLA_STAMP(11);
