@@ -527,33 +527,8 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
                     }
                 }
             }
-            // Requests that nothing in this chunk waits for - the rows wanted by the next chunk and the snapshot of
-            // H^T - are issued here by wavefront 0 only; the other wavefronts issue theirs while they wait for
-            // wavefront 0's selection, where the memory pipe is idle (all of them at this point cost 1.3 us per chunk).
-            if (PERSIST && w == 0) {   // this chunk's own pairs leave the window in the next chunk
-                const uint4 *ph = reinterpret_cast<const uint4 *>(a.phiK + ((size_t)si * a.S + (j - a.jb)) * C * 2 * D);
-#pragma unroll
-                for (int it = 0; it < PHN; it++) PHn[it] = ph[tid + NTH * it];
-#pragma unroll
-                for (int u = 0; u < 4; u++)
-#pragma unroll
-                    for (int rt = 0; rt < RT; rt++)
-                        vvn[u][rt] = *reinterpret_cast<const uint2 *>(vc + (size_t)(j * C + 16 * u + r16) * DH + 16 * (RT * w + rt) + 4 * g4);
-            }
             if (a.want_out && t0 == 0) {
                 const size_t sj = (size_t)si * a.S + (j - a.jb);
-                if (w == 0) {
-                    uint16_t *s16 = reinterpret_cast<uint16_t *>(a.snapH) + sj * (2 * D * DH);
-#pragma unroll
-                    for (int rt = 0; rt < RT; rt++)
-#pragma unroll
-                        for (int ks = 0; ks < 4; ks++) {
-                            // one contiguous 1 KB piece per store: [row tile][k-step][lane]
-                            const int off = (((RT * w + rt) * 4 + ks) * 64 + lane) << 3;
-                            *reinterpret_cast<uint4 *>(s16 + off) = __builtin_bit_cast(uint4, Ahi[rt][ks]);
-                            *reinterpret_cast<uint4 *>(s16 + D * DH + off) = __builtin_bit_cast(uint4, Alo[rt][ks]);
-                        }
-                }
                 if (tid < D / 4) reinterpret_cast<float4 *>(a.snapS + sj * D)[tid] = reinterpret_cast<const float4 *>(s_l)[tid];
                 if (tid < LAM) a.snapG[sj * LAM + tid] = sprow_ld;
             }
@@ -684,6 +659,34 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
                     for (int x = 0; x < 8; x++) Bc[x] = Bn[x];
                 }
             }
+            }
+            // Requests that nothing in this chunk waits for - the rows wanted by the next chunk and the snapshot of
+            // H^T - are issued where a wavefront would otherwise idle: by wavefront 0 here, behind its share of the
+            // recall GEMM (it waits for the other wavefront of its SIMD anyway), by the others while wavefront 0 runs the
+            // selection.  Issued by all wavefronts ahead of the recall GEMM they cost 1.3 us per chunk.
+            if (w == 0 && t0 + TB >= NTILE) {
+                if (PERSIST) {   // this chunk's own pairs leave the window in the next chunk
+                    const uint4 *ph = reinterpret_cast<const uint4 *>(a.phiK + ((size_t)si * a.S + (j - a.jb)) * C * 2 * D);
+#pragma unroll
+                    for (int it = 0; it < PHN; it++) PHn[it] = ph[tid + NTH * it];
+#pragma unroll
+                    for (int u = 0; u < 4; u++)
+#pragma unroll
+                        for (int rt = 0; rt < RT; rt++)
+                            vvn[u][rt] = *reinterpret_cast<const uint2 *>(vc + (size_t)(j * C + 16 * u + r16) * DH + 16 * (RT * w + rt) + 4 * g4);
+                }
+                if (a.want_out) {
+                    uint16_t *s16 = reinterpret_cast<uint16_t *>(a.snapH) + ((size_t)si * a.S + (j - a.jb)) * (2 * D * DH);
+#pragma unroll
+                    for (int rt = 0; rt < RT; rt++)
+#pragma unroll
+                        for (int ks = 0; ks < 4; ks++) {
+                            // one contiguous 1 KB piece per store: [row tile][k-step][lane]
+                            const int off = (((RT * w + rt) * 4 + ks) * 64 + lane) << 3;
+                            *reinterpret_cast<uint4 *>(s16 + off) = __builtin_bit_cast(uint4, Ahi[rt][ks]);
+                            *reinterpret_cast<uint4 *>(s16 + D * DH + off) = __builtin_bit_cast(uint4, Alo[rt][ks]);
+                        }
+                }
             }
             if (j == a.j1 - 1 && t0 == 0) LOLA_STAMP(4);
             __syncthreads();
