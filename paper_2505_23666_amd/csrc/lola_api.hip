@@ -380,9 +380,19 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
                 if (np > SideStream::NEV) np = SideStream::NEV;
                 if (a.want_out && ns <= OVERLAP_MAX_STREAMS && np >= 2) side = side_stream(stream);
                 std::unique_lock<std::mutex> side_lock(side_use_mu, std::defer_lock);
+                // piece boundaries: equal pieces, except that the last one is half as long - its outputs are the only
+                // ones that nothing hides
+                int bnd[SideStream::NEV + 1];
+                bnd[0] = j0; bnd[1] = jend;
+                int npieces = 1;
                 if (side) {
                     side_lock.lock();
-                    piece = (piece + np - 1) / np;
+                    npieces = np;
+                    int last = piece / (2 * np - 1);
+                    if (last < OVERLAP_MIN_PIECE) last = OVERLAP_MIN_PIECE;
+                    const int rest = piece - last;
+                    for (int i = 1; i < np; i++) bnd[i] = j0 + (int)((long long)rest * i / (np - 1));
+                    bnd[np] = jend;
                 }
                 const bool f32o = c->out_dtype == LOLA_F32;
                 auto attend = [&](hipStream_t so, int r0, int r1) {
@@ -403,9 +413,10 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
                     return hipGetLastError() == hipSuccess;
                 };
                 int ip = 0, prev0 = j0;
-                for (int p0 = j0; p0 < jend; p0 += piece, ip++) {
+                for (; ip < npieces; ip++) {
+                    const int p0 = bnd[ip];
                     a.j0 = p0;
-                    a.j1 = p0 + piece < jend ? p0 + piece : jend;
+                    a.j1 = bnd[ip + 1];
                     if (ip == 0) {
                         a.scan_mode = 1;
                         hipLaunchKernelGGL((generic::scan_kernel<T>), gs, block, lds_scan, stream, a);

@@ -315,7 +315,7 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
     static_assert(RT == 1 || RT == 2, "row tiles per wavefront");
     static_assert(DH == 64 || DH == 128, "head_dim");
     constexpr int P = LAM + ETA, NE = LAM + C, NTILE = NE / 16, TB = LAM > 128 ? 10 : 12, RB = TB * 16;
-    constexpr int TPW = (TB + NW - 1) / NW, NK = NE / 64, TC = LAM / 16;
+    constexpr int NK = NE / 64, TC = LAM / 16;
     constexpr bool PERSIST = NTILE <= TB;   // one batch: the candidates' features all fit in LDS and the cache's part stays there
     static_assert(NE % 64 == 0, "candidates are selected 64 per register");
     __shared__ __attribute__((aligned(16))) uint16_t PB[2 * RB * D];    // phi of (a batch of) candidates: high parts, low parts
