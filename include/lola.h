@@ -150,7 +150,7 @@ lola_status lola_state_flush(const lola_config *cfg, const lola_state *st, void 
  *   must be ordered.
  * May be called repeatedly (the memories carry over) and be followed by lola_decode_step.
  * Streams: with few streams of memories (B * Hkv <= 128) and enough output work, the MFMA kernels
- *   cut a pass into up to 8 pieces (the last one half as long as the others) and run the outputs of a piece on the library's second stream
+ *   cut a pass into up to 8 pieces (each half as long as the one before) and run the outputs of a piece on the library's second stream
  *   beside the state evolution of the next piece; `stream` waits for that work before the call's
  *   last kernel, so work the caller enqueues on `stream` afterwards sees every output.  While
  *   `stream` is under graph capture, or if the second stream cannot be created, everything stays

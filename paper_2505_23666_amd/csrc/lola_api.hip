@@ -259,6 +259,7 @@ struct SideStream {
 #define LOLA_SCAN_RT128 1
 #endif
 constexpr int SCAN_RT128 = LOLA_SCAN_RT128;   // row tiles of H^T per wavefront in the MFMA scan at head_dim 128
+constexpr int CHIP_CUS = 256;                 // compute units of the MI355X
 constexpr size_t OVERLAP_MAX_STREAMS = 128;   // beyond this many streams the serial evolution fills the chip by itself
 constexpr int OVERLAP_MIN_PIECE = 8;          // chunks per piece at least; more than the (256 + 64) / 64 chunks after which
                                               // the sparse cache of the MFMA shapes is full
@@ -380,19 +381,24 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
                 if (np > SideStream::NEV) np = SideStream::NEV;
                 if (a.want_out && ns <= OVERLAP_MAX_STREAMS && np >= 2) side = side_stream(stream);
                 std::unique_lock<std::mutex> side_lock(side_use_mu, std::defer_lock);
-                // piece boundaries: equal pieces, except that the last one is half as long - its outputs are the only
-                // ones that nothing hides
+                // Piece boundaries: each piece half as long as the one before it, so that the outputs of a piece
+                // (which take about half as long per chunk as the evolution) are hidden behind the evolution of the
+                // next; the last piece, whose outputs nothing hides, is at least one round of output workgroups on the
+                // chip (two per compute unit).
                 int bnd[SideStream::NEV + 1];
                 bnd[0] = j0; bnd[1] = jend;
                 int npieces = 1;
                 if (side) {
                     side_lock.lock();
+                    const int per_chunk = a.dm.Hq * a.dm.B;   // output workgroups per chunk
+                    int last = (2 * CHIP_CUS + per_chunk - 1) / per_chunk;
+                    if (last < 2) last = 2;
+                    while (np > 2 && piece / ((1 << np) - 1) < last) np--;
+                    int unit = piece / ((1 << np) - 1);
+                    if (unit < 1) unit = 1;
                     npieces = np;
-                    int last = piece / (2 * np - 1);
-                    if (last < OVERLAP_MIN_PIECE) last = OVERLAP_MIN_PIECE;
-                    const int rest = piece - last;
-                    for (int i = 1; i < np; i++) bnd[i] = j0 + (int)((long long)rest * i / (np - 1));
                     bnd[np] = jend;
+                    for (int i = np - 1; i >= 1; i--) bnd[i] = bnd[i + 1] - (unit << (np - 1 - i));   // the first piece takes the rest
                 }
                 const bool f32o = c->out_dtype == LOLA_F32;
                 auto attend = [&](hipStream_t so, int r0, int r1) {
