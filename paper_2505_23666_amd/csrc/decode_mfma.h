@@ -65,6 +65,8 @@ __device__ __forceinline__ bf16x4 tr_read(const uint16_t *p) {
     typedef __bf16 v4 __attribute__((ext_vector_type(4)));
     return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) v4 *)(p));
 }
+// reciprocal to one unit in the last place (the hardware instruction); an IEEE division costs ten instructions
+__device__ __forceinline__ float frcp(float x) { return __builtin_amdgcn_rcpf(x); }
 __device__ __forceinline__ float bf_lo(uint32_t u) { return __uint_as_float(u << 16); }
 __device__ __forceinline__ float bf_hi(uint32_t u) { return __uint_as_float(u & 0xFFFF0000u); }
 __device__ __forceinline__ float dot2bf(uint32_t a, uint32_t b, float c) {
@@ -181,7 +183,7 @@ __device__ __forceinline__ void phi_from_z(const f32x4 zt[4], int phi_kind, floa
         sp += pp[x]; sn += pn[x];
     }
     sp = grp_sum(sp); sn = grp_sum(sn);
-    const float ip = 1.0f / sp, in_ = 1.0f / sn;
+    const float ip = frcp(sp), in_ = frcp(sn);
 #pragma unroll
     for (int x = 0; x < 16; x++) { pp[x] *= ip; pn[x] *= in_; }
 }
@@ -414,7 +416,7 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
         else {
             const float zmax = wmax(z), zmin = wmin(z);
             const float ep = fexp2((z - zmax) * LOG2E), en = fexp2((zmin - z) * LOG2E);
-            pp = ep / wsum(ep); pn = en / wsum(en);
+            pp = ep * frcp(wsum(ep)); pn = en * frcp(wsum(en));
         }
         const float dn = wsum(fmaf(pp, s_l[j], pn * s_l[M + j]));
         if (lane == 0) denq[w] = dn;
@@ -514,7 +516,7 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
             bf16x8 hi[4], lo[4];
             split8(&pp[0], hi[0], lo[0]); split8(&pp[8], hi[1], lo[1]);
             split8(&pn[0], hi[2], lo[2]); split8(&pn[8], hi[3], lo[3]);
-            if (g4 == 0) rden_l[row] = dn > 0.f ? 1.0f / dn : 0.f;
+            if (g4 == 0) rden_l[row] = dn > 0.f ? frcp(dn) : 0.f;
 #pragma unroll
             for (int ks = 0; ks < 4; ks++) {
                 const int addr = row * D + (((4 * ks + g4) ^ r16) << 3);
@@ -553,10 +555,10 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
             else {
                 const float zmax = wmax(z), zmin = wmin(z);
                 const float ep = fexp2((z - zmax) * LOG2E), en = fexp2((zmin - z) * LOG2E);
-                pp = ep / wsum(ep); pn = en / wsum(en);
+                pp = ep * frcp(wsum(ep)); pn = en * frcp(wsum(en));
             }
             const float dn = wsum(fmaf(pp, s_l[lane], pn * s_l[M + lane]));
-            if (lane == 0) rden_l[KP] = dn > 0.f ? 1.0f / dn : 0.f;
+            if (lane == 0) rden_l[KP] = dn > 0.f ? frcp(dn) : 0.f;
 #pragma unroll
             for (int half = 0; half < 2; half++) {
                 const int f = half * M + lane;
@@ -853,7 +855,7 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
                         num = fmaf(el, fmaf(dotqf[r], vf[c], lin[r][c]), num);
                         den = fmaf(el, denq[r] + dotqf[r], den);
                     }
-                    stf(a.out, ((size_t)b * a.Hq + (size_t)h * g + r) * DH + c, num / den);
+                    stf(a.out, ((size_t)b * a.Hq + (size_t)h * g + r) * DH + c, num * frcp(den));
                 }
             }
         }

@@ -208,7 +208,7 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
     split8(&pp[0], Bh[0], Bl[0]); split8(&pp[8], Bh[1], Bl[1]);
     split8(&pn[0], Bh[2], Bl[2]); split8(&pn[8], Bh[3], Bl[3]);
     const float el = (a.dm.hide & 1) ? 0.f : fexp2(-mrun);   // restricted query: no hidden-state terms
-    const float inv = 1.0f / fmaf(el, lden, lsum);
+    const float inv = frcp(fmaf(el, lden, lsum));
     __syncthreads();   // H^T is in LDS
 #pragma unroll
     for (int mt = 0; mt < NCT; mt++) {
