@@ -158,11 +158,13 @@ int attend_tile_queries(const Dims &dm) {
 
 // The MFMA kernels of the prefill cover the Llama 8B and 1B head shapes (head_dim 128 / 64, 128 features) with
 // chunk = window = 64.
-bool fast_attend_ok(const lola_config *c) {
+// shapes of the MFMA prefill kernels; the output kernel serves every score kind (its inputs are the snapshots, whoever
+// took them), the state-evolution kernel ranks by self-recall error only
+bool fast_output_ok(const lola_config *c) {
     return c->dtype == LOLA_BF16 && (c->head_dim == 128 || c->head_dim == 64) && c->feat_dim == 128 && c->window == 64 && c->chunk == 64 &&
-           (c->sparse_budget == 64 || c->sparse_budget == 128 || c->sparse_budget == 256) &&
-           c->score_kind == LOLA_SCORE_SRE;
+           (c->sparse_budget == 64 || c->sparse_budget == 128 || c->sparse_budget == 256);
 }
+bool fast_attend_ok(const lola_config *c) { return fast_output_ok(c) && c->score_kind == LOLA_SCORE_SRE; }
 
 struct PrefillPlan {
     size_t off_prefK, off_prefV, off_sp_row, off_phiE, off_next, off_score, off_snap;   // byte offsets
@@ -292,6 +294,20 @@ SideStream *side_stream(hipStream_t caller) {
     return state[dev] == 1 ? &table[dev] : nullptr;
 }
 
+// outputs of the chunks [r0, r1) by the MFMA output kernel
+void launch_output_kernel(const lola_config *c, const generic::PrefillArgs<bf16_t> &a, int r0, int r1, hipStream_t so) {
+    generic::PrefillArgs<bf16_t> ao = a;
+    ao.j0 = r0; ao.j1 = r1; ao.scan_mode = 0;
+    const dim3 ga((unsigned)(r1 - r0), (unsigned)a.dm.Hq, (unsigned)a.dm.B);
+    const bool f32o = c->out_dtype == LOLA_F32;
+#define LOLA_ATT2(LAMV, DHV) do { if (f32o) hipLaunchKernelGGL((fast::attend_fast_kernel<LAMV, DHV, float>), ga, dim3(256), 0, so, ao); \
+                                  else hipLaunchKernelGGL((fast::attend_fast_kernel<LAMV, DHV, bf16_t>), ga, dim3(256), 0, so, ao); } while (0)
+#define LOLA_ATT(LAMV) do { if (c->head_dim == 128) LOLA_ATT2(LAMV, 128); else LOLA_ATT2(LAMV, 64); } while (0)
+    if (c->sparse_budget == 64) LOLA_ATT(64); else if (c->sparse_budget == 128) LOLA_ATT(128); else LOLA_ATT(256);
+#undef LOLA_ATT
+#undef LOLA_ATT2
+}
+
 template <typename T>
 lola_status run_prefill(const lola_config *c, const lola_state *st, const void *q, const void *k, const void *v,
                         const void *Wq, const void *Wk, int32_t Tn, void *out, int32_t *sel_trace,
@@ -336,7 +352,7 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
     const size_t scan_fixed = scan_fixed_floats(a.dm);
     a.R = score_tile_rows(a.dm, scan_fixed);
     a.QT = attend_tile_queries(a.dm);
-    const bool fast_att = a.want_out && fast_attend_ok(c);
+    const bool fast_att = a.want_out && fast_output_ok(c);
     a.snap_split = fast_att ? 1 : 0;
     if (a.R <= 0 || (a.want_out && a.QT <= 0)) return LOLA_ERR_UNSUPPORTED;
     const size_t lds_scan = 4 * (scan_fixed + (size_t)a.R * (3 * d + D + 1));
@@ -400,18 +416,7 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
                     bnd[np] = jend;
                     for (int i = np - 1; i >= 1; i--) bnd[i] = bnd[i + 1] - (unit << (np - 1 - i));   // the first piece takes the rest
                 }
-                const bool f32o = c->out_dtype == LOLA_F32;
-                auto attend = [&](hipStream_t so, int r0, int r1) {
-                    generic::PrefillArgs<T> ao = a;
-                    ao.j0 = r0; ao.j1 = r1; ao.scan_mode = 0;
-                    const dim3 ga((unsigned)(r1 - r0), (unsigned)a.dm.Hq, (unsigned)a.dm.B);
-#define LOLA_ATT2(LAMV, DHV) do { if (f32o) hipLaunchKernelGGL((fast::attend_fast_kernel<LAMV, DHV, float>), ga, dim3(256), 0, so, ao); \
-                                  else hipLaunchKernelGGL((fast::attend_fast_kernel<LAMV, DHV, bf16_t>), ga, dim3(256), 0, so, ao); } while (0)
-#define LOLA_ATT(LAMV) do { if (c->head_dim == 128) LOLA_ATT2(LAMV, 128); else LOLA_ATT2(LAMV, 64); } while (0)
-                    if (c->sparse_budget == 64) LOLA_ATT(64); else if (c->sparse_budget == 128) LOLA_ATT(128); else LOLA_ATT(256);
-#undef LOLA_ATT
-#undef LOLA_ATT2
-                };
+                auto attend = [&](hipStream_t so, int r0, int r1) { launch_output_kernel(c, a, r0, r1, so); };
                 // outputs of the chunks [r0, r1) on the second stream, behind what `stream` held when fork[ev] was recorded
                 auto attend_aside = [&](int ev, int r0, int r1) -> bool {
                     if (hipStreamWaitEvent(side->s, side->fork[ev], 0) != hipSuccess) return false;
@@ -464,9 +469,18 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
         hipLaunchKernelGGL((generic::scan_kernel<T>), gs, block, lds_scan, stream, a);
         LAUNCH_CHECK();
         if (a.want_out) {
-            dim3 ga((unsigned)(a.j1 - a.j0), (unsigned)a.dm.Hq, (unsigned)a.dm.B);
-            if (c->out_dtype == LOLA_F32) hipLaunchKernelGGL((generic::attend_kernel<T, float>), ga, block, lds_att, stream, a);
-            else hipLaunchKernelGGL((generic::attend_kernel<T, bf16_t>), ga, block, lds_att, stream, a);
+            bool done = false;
+            if constexpr (std::is_same<T, bf16_t>::value) {
+                if (fast_att) {   // the generic evolution took the snapshots in the MFMA output kernel's layout
+                    launch_output_kernel(c, a, a.j0, a.j1, stream);
+                    done = true;
+                }
+            }
+            if (!done) {
+                dim3 ga((unsigned)(a.j1 - a.j0), (unsigned)a.dm.Hq, (unsigned)a.dm.B);
+                if (c->out_dtype == LOLA_F32) hipLaunchKernelGGL((generic::attend_kernel<T, float>), ga, block, lds_att, stream, a);
+                else hipLaunchKernelGGL((generic::attend_kernel<T, bf16_t>), ga, block, lds_att, stream, a);
+            }
             LAUNCH_CHECK();
         }
     }
