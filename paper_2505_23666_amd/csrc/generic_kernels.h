@@ -800,7 +800,64 @@ __device__ void scan_chunk(const PrefillArgs<T> &a, const int si, const int j, i
             }
             __syncthreads();
             const int nf = sh_nf, ne = sh_ne;
-            // fold: H += sum phi(k) v^T, s += sum phi(k) over the pairs that do not stay
+            // fold: H += sum phi(k) v^T, s += sum phi(k) over the pairs that do not stay.  R pairs at a time are staged in
+            // LDS (features and values as fp32) and every thread accumulates blocks of 4 value columns x 16 features in
+            // registers: 5 LDS reads of 16 bytes per 64 multiply-adds, where the plain loop below reads global memory
+            // twice per multiply-add (0.9 ms per chunk at the 8B shape).
+            if (d % 4 == 0 && D % 16 == 0) {
+                const int nbf = D / 16, nblk = (d / 4) * nbf;
+                for (int t0 = 0; t0 < nf; t0 += R) {
+                    const int nr = min(R, nf - t0);
+                    for (int p = tid; p < nr * (D / 4); p += NT) {
+                        const int r = p / (D / 4), i = p - r * (D / 4);
+                        reinterpret_cast<float4 *>(ph + r * D)[i] = reinterpret_cast<const float4 *>(phiE + (size_t)flist[t0 + r] * D)[i];
+                    }
+                    for (int p = tid; p < nr * d; p += NT) {
+                        const int r = p / d, c = p - r * d, e = flist[t0 + r];
+                        float val;
+                        if (e < spc) val = ldf(sp_v, (size_t)e * d + c);
+                        else { const int vr = vrow0 + (e - spc); val = vr < P ? ldf(pV, (size_t)vr * d + c) : ldf(vc, (size_t)(vr - P) * d + c); }
+                        vs[p] = val;
+                    }
+                    __syncthreads();
+                    for (int b = tid; b < nblk; b += NT) {
+                        const int c0 = 4 * (b / nbf), f0 = 16 * (b % nbf);
+                        float acc[4][16];
+#pragma unroll
+                        for (int i = 0; i < 4; i++)
+#pragma unroll
+                            for (int x = 0; x < 16; x++) acc[i][x] = 0.f;
+                        for (int r = 0; r < nr; r++) {
+                            const float4 v4 = *reinterpret_cast<const float4 *>(vs + r * d + c0);
+                            const float vv[4] = {v4.x, v4.y, v4.z, v4.w};
+#pragma unroll
+                            for (int q4 = 0; q4 < 4; q4++) {
+                                const float4 p4 = *reinterpret_cast<const float4 *>(ph + r * D + f0 + 4 * q4);
+#pragma unroll
+                                for (int i = 0; i < 4; i++) {
+                                    acc[i][4 * q4] = fmaf(p4.x, vv[i], acc[i][4 * q4]); acc[i][4 * q4 + 1] = fmaf(p4.y, vv[i], acc[i][4 * q4 + 1]);
+                                    acc[i][4 * q4 + 2] = fmaf(p4.z, vv[i], acc[i][4 * q4 + 2]); acc[i][4 * q4 + 3] = fmaf(p4.w, vv[i], acc[i][4 * q4 + 3]);
+                                }
+                            }
+                        }
+#pragma unroll
+                        for (int i = 0; i < 4; i++)
+#pragma unroll
+                            for (int q4 = 0; q4 < 4; q4++) {
+                                float4 *hp = reinterpret_cast<float4 *>(H + (size_t)(c0 + i) * D + f0 + 4 * q4);
+                                float4 hv = *hp;
+                                hv.x += acc[i][4 * q4]; hv.y += acc[i][4 * q4 + 1]; hv.z += acc[i][4 * q4 + 2]; hv.w += acc[i][4 * q4 + 3];
+                                *hp = hv;
+                            }
+                    }
+                    for (int f = tid; f < D; f += NT) {
+                        float acc = 0.f;
+                        for (int r = 0; r < nr; r++) acc += ph[r * D + f];
+                        s[f] += acc;
+                    }
+                    __syncthreads();
+                }
+            } else {
             for (int idx = tid; idx < D * d; idx += NT) {
                 int c = idx / D, f = idx - c * D;
                 float acc = 0.f;
@@ -817,6 +874,7 @@ __device__ void scan_chunk(const PrefillArgs<T> &a, const int si, const int j, i
                 float acc = 0.f;
                 for (int x = 0; x < nf; x++) acc += phiE[(size_t)flist[x] * D + f];
                 s[f] += acc;
+            }
             }
             __syncthreads();
             // compaction: entrants overwrite the slots that were freed
