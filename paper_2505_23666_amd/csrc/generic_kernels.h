@@ -64,6 +64,42 @@ __device__ __forceinline__ float dot_row(const float *row, const float *x, int n
     return acc;
 }
 
+// acc[q] = sum_i row[i] * xs[q][i] for q < nq <= 16, each in index order (the rounding of dot_row); the row crosses the
+// memory system once for all nq vectors (xs in LDS, row stride n)
+__device__ __forceinline__ void dot_row_many(const bf16_t *row, const float *xs, int n, int nq, float (&acc)[16]) {
+    const uint4 *r4 = reinterpret_cast<const uint4 *>(row);
+    for (int i = 0; i < n / 8; i++) {
+        const uint4 u = r4[i];
+        const float kf[8] = {__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xFFFF0000u), __uint_as_float(u.y << 16), __uint_as_float(u.y & 0xFFFF0000u),
+                             __uint_as_float(u.z << 16), __uint_as_float(u.z & 0xFFFF0000u), __uint_as_float(u.w << 16), __uint_as_float(u.w & 0xFFFF0000u)};
+#pragma unroll
+        for (int q = 0; q < 16; q++) {
+            if (q < nq) {
+                const float4 x0 = *reinterpret_cast<const float4 *>(xs + q * n + 8 * i), x1 = *reinterpret_cast<const float4 *>(xs + q * n + 8 * i + 4);
+                float t = acc[q];
+                t = fmaf(kf[0], x0.x, t); t = fmaf(kf[1], x0.y, t); t = fmaf(kf[2], x0.z, t); t = fmaf(kf[3], x0.w, t);
+                t = fmaf(kf[4], x1.x, t); t = fmaf(kf[5], x1.y, t); t = fmaf(kf[6], x1.z, t); t = fmaf(kf[7], x1.w, t);
+                acc[q] = t;
+            }
+        }
+    }
+}
+__device__ __forceinline__ void dot_row_many(const float *row, const float *xs, int n, int nq, float (&acc)[16]) {
+    const float4 *r4 = reinterpret_cast<const float4 *>(row);
+    for (int i = 0; i < n / 4; i++) {
+        const float4 u = r4[i];
+#pragma unroll
+        for (int q = 0; q < 16; q++) {
+            if (q < nq) {
+                const float4 x0 = *reinterpret_cast<const float4 *>(xs + q * n + 4 * i);
+                float t = acc[q];
+                t = fmaf(u.x, x0.x, t); t = fmaf(u.y, x0.y, t); t = fmaf(u.z, x0.z, t); t = fmaf(u.w, x0.w, t);
+                acc[q] = t;
+            }
+        }
+    }
+}
+
 // phi of R rows.  xs [R][d] (LDS, fp32 copies of the stored vectors), W [m][d] (global, row j = w_j), result
 // ph [R][D] (LDS).  Workgroup-wide; ends with a barrier.
 template <typename T>
@@ -964,18 +1000,25 @@ __global__ __launch_bounds__(NT) void attend_kernel(PrefillArgs<T> a) {
         __syncthreads();
         phi_rows(dm, Wq, qs, phq, nq);
         // logits; a key is visible to query i iff it is cached, in the entry window, or a chunk token <= i
-        for (int p = tid; p < nq * nk; p += NT) {
-            int qi = p / nk, key = p - qi * nk;
-            int vr; bool ok;
-            if (key < lam) { vr = G[key]; ok = vr >= 0 && !(dm.hide & 2); }
-            else { int x = key - lam; vr = vrow0 + x; ok = (lo + x) <= (aj + i0 + qi); }
-            float l = -INFINITY;
-            if (ok) {
+        // (one thread per key: its row is read once for all queries of the tile)
+        for (int key = tid; key < nk; key += NT) {
+            int vr; bool row_ok = true;
+            if (key < lam) { vr = G[key]; row_ok = vr >= 0 && !(dm.hide & 2); }
+            else vr = vrow0 + (key - lam);
+            float lq[16];
+#pragma unroll
+            for (int qi = 0; qi < 16; qi++) lq[qi] = 0.f;
+            if (row_ok) {
                 const T *kr = vr < P ? pK + (size_t)vr * d : kc + (size_t)(vr - P) * d;
-                const float *qv = qs + qi * d;
-                l = dot_row(kr, qv, d, 0.f) * dm.scale;
+                dot_row_many(kr, qs, d, nq, lq);
             }
-            pw[qi * nkmax + key] = l;
+#pragma unroll
+            for (int qi = 0; qi < 16; qi++) {
+                if (qi < nq) {
+                    const bool ok = key < lam ? row_ok : (lo + (key - lam)) <= (aj + i0 + qi);
+                    pw[qi * nkmax + key] = ok ? lq[qi] * dm.scale : -INFINITY;
+                }
+            }
         }
         __syncthreads();
         for (int qi = w; qi < nq; qi += NW) {
@@ -996,31 +1039,51 @@ __global__ __launch_bounds__(NT) void attend_kernel(PrefillArgs<T> a) {
             if (lane == 0) { rmax[qi] = mx; rsum[qi] = sum; rlin[qi] = lin; }
         }
         __syncthreads();
+        // one thread per value column (and per group of queries): a value row and a row of H^T are read once for all
+        // the thread's queries of the tile, the sums of each query run in key / feature order
         const int c = tid % d, part = tid / d, nparts = NT / d;
-        for (int qi = part; qi < nq; qi += nparts) {
-            const float *row = pw + qi * nkmax;
-            float num = 0.f;
-            for (int key = 0; key < nk; key++) {
-                float p = row[key];
-                if (p != 0.f) {
-                    int vr = key < lam ? G[key] : vrow0 + (key - lam);
-                    float val = vr < P ? ldf(pV, (size_t)vr * d + c) : ldf(vc, (size_t)(vr - P) * d + c);
-                    num = fmaf(p, val, num);
+        float num[16], lin[16];
+#pragma unroll
+        for (int x = 0; x < 16; x++) { num[x] = 0.f; lin[x] = 0.f; }
+        for (int key = 0; key < nk; key++) {
+            const int vr = key < lam ? G[key] : vrow0 + (key - lam);
+            if (vr < 0) continue;   // empty slot: weight 0 for every query
+            const float val = vr < P ? ldf(pV, (size_t)vr * d + c) : ldf(vc, (size_t)(vr - P) * d + c);
+#pragma unroll
+            for (int x = 0; x < 16; x++) {
+                const int qi = part + x * nparts;
+                if (qi < nq) num[x] = fmaf(pw[qi * nkmax + key], val, num[x]);
+            }
+        }
+        if ((D & 3) == 0) {
+            const float4 *H4 = reinterpret_cast<const float4 *>(Hj + (size_t)c * D);
+            for (int f4 = 0; f4 < D / 4; f4++) {
+                const float4 hv = H4[f4];
+#pragma unroll
+                for (int x = 0; x < 16; x++) {
+                    const int qi = part + x * nparts;
+                    if (qi < nq) {
+                        const float4 pv = reinterpret_cast<const float4 *>(phq + qi * D)[f4];
+                        float t = lin[x];
+                        t = fmaf(pv.x, hv.x, t); t = fmaf(pv.y, hv.y, t); t = fmaf(pv.z, hv.z, t); t = fmaf(pv.w, hv.w, t);
+                        lin[x] = t;
+                    }
                 }
             }
-            float lin = 0.f;
-            const float *pq = phq + qi * D;
-            if ((D & 3) == 0) {
-                const float4 *H4 = reinterpret_cast<const float4 *>(Hj + (size_t)c * D), *p4 = reinterpret_cast<const float4 *>(pq);
-                for (int f4 = 0; f4 < D / 4; f4++) {
-                    const float4 hv = H4[f4], pv = p4[f4];
-                    lin = fmaf(pv.x, hv.x, lin); lin = fmaf(pv.y, hv.y, lin); lin = fmaf(pv.z, hv.z, lin); lin = fmaf(pv.w, hv.w, lin);
-                }
-            } else {
-                for (int f = 0; f < D; f++) lin = fmaf(pq[f], Hj[(size_t)c * D + f], lin);
+        } else {
+#pragma unroll
+            for (int x = 0; x < 16; x++) {
+                const int qi = part + x * nparts;
+                if (qi < nq) { float t = 0.f; for (int f = 0; f < D; f++) t = fmaf(phq[qi * D + f], Hj[(size_t)c * D + f], t); lin[x] = t; }
             }
-            const float elin = (dm.hide & 1) ? 0.f : expf(-rmax[qi]);
-            stf(oh, (size_t)(i0 + qi) * d + c, fmaf(elin, lin, num) / (rsum[qi] + elin * rlin[qi]));
+        }
+#pragma unroll
+        for (int x = 0; x < 16; x++) {
+            const int qi = part + x * nparts;
+            if (qi < nq) {
+                const float elin = (dm.hide & 1) ? 0.f : expf(-rmax[qi]);
+                stf(oh, (size_t)(i0 + qi) * d + c, fmaf(elin, lin[x], num[x]) / (rsum[qi] + elin * rlin[qi]));
+            }
         }
         __syncthreads();
     }
