@@ -263,8 +263,9 @@ struct SideStream {
 constexpr int SCAN_RT128 = LOLA_SCAN_RT128;   // row tiles of H^T per wavefront in the MFMA scan at head_dim 128
 constexpr int CHIP_CUS = 256;                 // compute units of the MI355X
 constexpr size_t OVERLAP_MAX_STREAMS = 128;   // beyond this many streams the serial evolution fills the chip by itself
-constexpr int OVERLAP_MIN_PIECE = 8;          // chunks per piece at least; more than the (256 + 64) / 64 chunks after which
-                                              // the sparse cache of the MFMA shapes is full
+constexpr int OVERLAP_MIN_PIECE = 8;          // chunks per piece on average at least.  The first piece, at least half of the
+                                              // pass and so at least 8 chunks, is longer than the (256 + 64) / 64 chunks
+                                              // after which the sparse cache of the MFMA shapes is full
 constexpr size_t OVERLAP_MIN_WORK = 4096;     // output workgroups (in units of 64 head columns) per piece at least: below
                                               // this the restart of the evolution costs more than the overlap hides
 
@@ -433,8 +434,8 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
                         hipLaunchKernelGGL((generic::scan_kernel<T>), gs, block, lds_scan, stream, a);
                         LAUNCH_CHECK();
                     }
-                    // Later pieces start on regular chunks (a piece is longer than the (lambda + eta) / C chunks after
-                    // which the cache is full), so the MFMA kernel continues at once.  The previous piece's outputs are
+                    // Later pieces start on regular chunks (the first piece is longer than the (lambda + eta) / C chunks
+                    // after which the cache is full), so the MFMA kernel continues at once.  The previous piece's outputs are
                     // enqueued after it: it should be resident before the output workgroups arrive, instead of queueing
                     // for compute units behind them.
                     if (side && ip > 0 && hipEventRecord(side->fork[ip - 1], stream) != hipSuccess) return LOLA_ERR_HIP;
