@@ -64,6 +64,18 @@ __device__ __forceinline__ float dot_row(const float *row, const float *x, int n
     return acc;
 }
 
+// one 16-byte piece of a stored row as fp32 into LDS (dst is the row's fp32 copy; 8 bf16 or 4 fp32 values per piece)
+__device__ __forceinline__ void piece_to_f32(const bf16_t *row, int piece, float *dst) {
+    const uint4 u = reinterpret_cast<const uint4 *>(row)[piece];
+    reinterpret_cast<float4 *>(dst)[2 * piece] = make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xFFFF0000u),
+                                                              __uint_as_float(u.y << 16), __uint_as_float(u.y & 0xFFFF0000u));
+    reinterpret_cast<float4 *>(dst)[2 * piece + 1] = make_float4(__uint_as_float(u.z << 16), __uint_as_float(u.z & 0xFFFF0000u),
+                                                                  __uint_as_float(u.w << 16), __uint_as_float(u.w & 0xFFFF0000u));
+}
+__device__ __forceinline__ void piece_to_f32(const float *row, int piece, float *dst) {
+    reinterpret_cast<float4 *>(dst)[piece] = reinterpret_cast<const float4 *>(row)[piece];
+}
+
 // acc[q] = sum_i row[i] * xs[q][i] for q < nq <= 16, each in index order (the rounding of dot_row); the row crosses the
 // memory system once for all nq vectors (xs in LDS, row stride n)
 __device__ __forceinline__ void dot_row_many(const bf16_t *row, const float *xs, int n, int nq, float (&acc)[16]) {
@@ -795,16 +807,18 @@ __device__ void scan_chunk(const PrefillArgs<T> &a, const int si, const int j, i
             const int nE = spc + n_ev;
             for (int t0 = 0; t0 < nE; t0 += R) {
                 int nr = min(R, nE - t0);
-                for (int p = tid; p < nr * d; p += NT) {
-                    int r = p / d, i = p - r * d, e = t0 + r;
-                    if (e < spc) {
-                        xs[p] = ldf(sp_k, (size_t)e * d + i);
-                        vs[p] = ldf(sp_v, (size_t)e * d + i);
-                    } else {
-                        int vr = vrow0 + (e - spc);
-                        xs[p] = vr < P ? ldf(pK, (size_t)vr * d + i) : ldf(kc, (size_t)(vr - P) * d + i);
-                        vs[p] = vr < P ? ldf(pV, (size_t)vr * d + i) : ldf(vc, (size_t)(vr - P) * d + i);
+                const int ppr = d * (int)sizeof(T) / 16;   // 16-byte pieces per stored row
+                for (int p = tid; p < nr * ppr; p += NT) {
+                    const int r = p / ppr, i = p - r * ppr, e = t0 + r;
+                    const T *ksrc, *vsrc;
+                    if (e < spc) { ksrc = sp_k + (size_t)e * d; vsrc = sp_v + (size_t)e * d; }
+                    else {
+                        const int vr = vrow0 + (e - spc);
+                        ksrc = vr < P ? pK + (size_t)vr * d : kc + (size_t)(vr - P) * d;
+                        vsrc = vr < P ? pV + (size_t)vr * d : vc + (size_t)(vr - P) * d;
                     }
+                    piece_to_f32(ksrc, i, xs + r * d);
+                    piece_to_f32(vsrc, i, vs + r * d);
                 }
                 __syncthreads();
                 phi_rows(dm, Wk, xs, ph, nr);
@@ -825,14 +839,32 @@ __device__ void scan_chunk(const PrefillArgs<T> &a, const int si, const int j, i
                 keep[e] = rank < lam;
             }
             __syncthreads();
-            if (tid == 0) {
+            if (tid < WAVE) {
+                // one wavefront builds the lists, 64 candidates per step, positions from ballots (candidate order kept):
+                // the pairs to fold, the entrants, and the slots they take: those of leaving cache entries first, then
+                // the never-used tail
+                const unsigned long long below = (1ull << tid) - 1ull;
                 int nf = 0, ne = 0, nfree = 0;
-                for (int e = 0; e < nE; e++) if (!keep[e]) flist[nf++] = e;
-                // free slots: those of leaving cache entries, then the never-used tail
-                for (int e = spc; e < nE; e++) if (keep[e]) ecand[ne++] = e;
-                for (int e = 0; e < spc && nfree < ne; e++) if (!keep[e]) eslot[nfree++] = e;
-                for (int sl = spc; sl < lam && nfree < ne; sl++) eslot[nfree++] = sl;
-                sh_nf = nf; sh_ne = ne;
+                for (int e0 = 0; e0 < nE; e0 += WAVE) {
+                    const int e = e0 + tid;
+                    const bool in = e < nE, kp = in && keep[e];
+                    const bool fo = in && !kp, en = kp && e >= spc;
+                    const unsigned long long mf = __ballot(fo), me = __ballot(en);
+                    if (fo) flist[nf + __popcll(mf & below)] = e;
+                    if (en) ecand[ne + __popcll(me & below)] = e;
+                    nf += __popcll(mf); ne += __popcll(me);
+                }
+                for (int e0 = 0; e0 < spc; e0 += WAVE) {
+                    const int e = e0 + tid;
+                    const bool lv = e < spc && !keep[e];
+                    const unsigned long long ml = __ballot(lv);
+                    const int pos = nfree + __popcll(ml & below);
+                    if (lv && pos < ne) eslot[pos] = e;
+                    nfree += __popcll(ml);
+                }
+                if (nfree > ne) nfree = ne;
+                for (int sl = spc + tid; sl < lam && nfree + (sl - spc) < ne; sl += WAVE) eslot[nfree + (sl - spc)] = sl;
+                if (tid == 0) { sh_nf = nf; sh_ne = ne; }
             }
             __syncthreads();
             const int nf = sh_nf, ne = sh_ne;
@@ -848,12 +880,13 @@ __device__ void scan_chunk(const PrefillArgs<T> &a, const int si, const int j, i
                         const int r = p / (D / 4), i = p - r * (D / 4);
                         reinterpret_cast<float4 *>(ph + r * D)[i] = reinterpret_cast<const float4 *>(phiE + (size_t)flist[t0 + r] * D)[i];
                     }
-                    for (int p = tid; p < nr * d; p += NT) {
-                        const int r = p / d, c = p - r * d, e = flist[t0 + r];
-                        float val;
-                        if (e < spc) val = ldf(sp_v, (size_t)e * d + c);
-                        else { const int vr = vrow0 + (e - spc); val = vr < P ? ldf(pV, (size_t)vr * d + c) : ldf(vc, (size_t)(vr - P) * d + c); }
-                        vs[p] = val;
+                    const int ppr = d * (int)sizeof(T) / 16;
+                    for (int p = tid; p < nr * ppr; p += NT) {
+                        const int r = p / ppr, i = p - r * ppr, e = flist[t0 + r];
+                        const T *vsrc;
+                        if (e < spc) vsrc = sp_v + (size_t)e * d;
+                        else { const int vr = vrow0 + (e - spc); vsrc = vr < P ? pV + (size_t)vr * d : vc + (size_t)(vr - P) * d; }
+                        piece_to_f32(vsrc, i, vs + r * d);
                     }
                     __syncthreads();
                     for (int b = tid; b < nblk; b += NT) {
