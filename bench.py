@@ -296,7 +296,8 @@ def main():
             sc = wl.CONFIGS[cid]
             Wq_, Wk_ = wl.weights(sc)
             q_, k_, v_, extra_ = wl.sequence_inputs(sc)
-            lay = lb.LolaLayer(sc.B, sc.Hq, sc.Hkv, sc.d, sc.D, sc.eta, sc.lam, sc.C, dtype="bf16", out_dtype="f32", device=dev)
+            lay = lb.LolaLayer(sc.B, sc.Hq, sc.Hkv, sc.d, sc.D, sc.eta, sc.lam, sc.C, dtype="bf16", out_dtype="f32", device=dev,
+                               prefill_overlap=1)
             a_ = [to_dev(x) for x in (q_, k_, v_, Wq_.transpose(0, 2, 1), Wk_.transpose(0, 2, 1))]
             out_ = torch.empty((sc.B, sc.Hq, sc.T, sc.d), dtype=torch.float32, device=dev)
             times = []

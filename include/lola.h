@@ -4,13 +4,19 @@
  *
  * The library owns no memory and never synchronises: every pointer below is a DEVICE pointer
  * (unless marked host) to caller-owned, contiguous, row-major memory aligned to 16 bytes, and
- * every call only enqueues work that is ordered behind `stream` and that `stream` waits for (a
- * hipStream_t passed as void*; NULL is the default stream): kernels on `stream` itself, and, in
- * lola_prefill only, kernels on one second stream per device that the library creates on first
- * use, forks from `stream` and joins back into it with events before the call returns (see
- * lola_prefill).  Arguments are validated on the host before anything is launched; on error a
- * negative lola_status is returned and nothing has been enqueued.  Calls on distinct states are
- * independent; calls on one state must be ordered by the caller (same stream, or events).
+ * every call only enqueues kernels on `stream` (a hipStream_t passed as void*; NULL is the default
+ * stream).  The one exception is opt-in: with lola_config.prefill_overlap = 1, lola_prefill may also
+ * use one second stream per device that the library creates on first use, forks from `stream` and
+ * joins back into it with events before the call returns, on every path (see lola_prefill;
+ * lola_release_streams destroys it).  With prefill_overlap = 0 the library holds no state at all.
+ * Errors: arguments, shapes, alignment, workspace size and whether a kernel exists for the
+ * configuration are all checked on the host before anything is launched, so every status other
+ * than LOLA_OK and LOLA_ERR_HIP means that nothing was enqueued and the memories are untouched.
+ * LOLA_ERR_HIP means that hipGetLastError reported an error after one of the call's launches:
+ * earlier launches of the call stay enqueued and the memories are then undefined.  An error that
+ * the caller's own earlier HIP calls left pending is reported (and cleared) the same way.
+ * Calls on distinct states are independent; calls on one state must be ordered by the caller
+ * (same stream, or events).
  *
  * Notation (paper, Sec. 2-3): B batch, Hq query heads, Hkv key/value heads (Hq % Hkv == 0, query
  * head h reads kv head h / (Hq/Hkv)), d = head_dim = d_k = d_v, D = feat_dim (phi: R^d -> R^D,
@@ -77,6 +83,8 @@ typedef struct {
     int32_t query_hide;    /* 0, or LOLA_HIDE_STATE | LOLA_HIDE_SPARSE bits: terms left out of the numerator
                               and the denominator of every output (lola_prefill and lola_decode_step) */
     int32_t score_kind;    /* LOLA_SCORE_*; anything but LOLA_SCORE_SRE excludes fold_defer */
+    int32_t prefill_overlap; /* 0: lola_prefill enqueues on `stream` only.  1: it may run the outputs of a piece of the
+                              call on the library's second stream beside the state evolution of the next piece */
 } lola_config;
 
 /* The memories of a layer.  H and s are always fp32 (Sec. 2.2, eq. recurrent_update). */
@@ -149,8 +157,8 @@ lola_status lola_state_flush(const lola_config *cfg, const lola_state *st, void 
  * workspace: see lola_prefill_workspace_bytes.  Contents are scratch; calls sharing a workspace
  *   must be ordered.
  * May be called repeatedly (the memories carry over) and be followed by lola_decode_step.
- * Streams: with few streams of memories (B * Hkv <= 128) and enough output work, the MFMA kernels
- *   cut a pass into up to 8 pieces (each half as long as the one before) and run the outputs of a piece on the library's second stream
+ * Streams: with prefill_overlap = 1, few streams of memories (B * Hkv <= 128) and enough output work, the MFMA
+ *   kernels cut a pass into up to 8 pieces (each half as long as the one before) and run the outputs of a piece on the library's second stream
  *   beside the state evolution of the next piece; `stream` waits for that work before the call's
  *   last kernel, so work the caller enqueues on `stream` afterwards sees every output.  While
  *   `stream` is under graph capture, or if the second stream cannot be created, everything stays
@@ -177,6 +185,11 @@ lola_status lola_prefill(const lola_config *cfg, const lola_state *st,
 lola_status lola_decode_step(const lola_config *cfg, const lola_state *st,
                              const void *q, const void *k, const void *v,
                              const void *Wq, const void *Wk, void *out, void *stream);
+
+/* Destroys the second streams and events that lola_prefill calls with prefill_overlap = 1 created (all
+ * devices); a later such call creates them again.  The caller makes sure that no lola_prefill call is
+ * running on another host thread.  Synchronises with the second streams only.  A no-op if none exists. */
+void lola_release_streams(void);
 
 /* Human-readable name of a status code (host string, never NULL). */
 const char *lola_status_str(lola_status s);

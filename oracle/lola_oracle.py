@@ -13,7 +13,12 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "lola_oracle.c")
+# The checks of the oracle itself (a sanitizer build, planted mistakes) run the pin suite against
+# another build of it: LOLA_ORACLE_SRC names the C file, LOLA_ORACLE_LIBDIR the folder that takes the
+# libraries, LOLA_ORACLE_CFLAGS extra compiler flags.  Unset, the oracle proper is built in place.
+_SRC = os.environ.get("LOLA_ORACLE_SRC") or os.path.join(_HERE, "lola_oracle.c")
+_LIBDIR = os.environ.get("LOLA_ORACLE_LIBDIR") or _HERE
+_EXTRA_CFLAGS = os.environ.get("LOLA_ORACLE_CFLAGS", "").split()
 
 PHI_SOFTMAX, PHI_EXP = 0, 1
 HIDE_STATE, HIDE_SPARSE = 1, 2   # restricted-query ablation: what the query does not read
@@ -28,7 +33,7 @@ class _Cfg(C.Structure):
 
 
 def _lib_path(real: str) -> str:
-    return os.path.join(_HERE, f"liblola_oracle_{real}.so")
+    return os.path.join(_LIBDIR, f"liblola_oracle_{real}.so")
 
 
 def build(force: bool = False) -> None:
@@ -38,7 +43,7 @@ def build(force: bool = False) -> None:
         if not force and os.path.exists(out) and os.path.getmtime(out) >= os.path.getmtime(_SRC):
             continue
         cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", f"-DORC_REAL={ctype}",
-               "-Wall", "-Wextra", "-o", out, _SRC, "-lm"]
+               "-Wall", "-Wextra", *_EXTRA_CFLAGS, "-o", out, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
 
 

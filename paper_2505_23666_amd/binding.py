@@ -19,14 +19,14 @@ LOLA_PHI_SOFTMAX, LOLA_PHI_EXP = 0, 1
 LOLA_HIDE_STATE, LOLA_HIDE_SPARSE = 1, 2
 LOLA_SCORE_SRE, LOLA_SCORE_WERR_SQ, LOLA_SCORE_WERR_ABS, LOLA_SCORE_OVEREST, LOLA_SCORE_ATTN = 0, 1, 2, 3, 4
 EXPORTS = ("lola_state_bytes", "lola_prefill_workspace_bytes", "lola_state_init", "lola_state_flush", "lola_prefill",
-           "lola_decode_step", "lola_status_str", "lola_kernel_path")
+           "lola_decode_step", "lola_status_str", "lola_kernel_path", "lola_release_streams")
 
 
 class LolaConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "batch", "n_q_heads", "n_kv_heads", "head_dim", "feat_dim", "window", "sparse_budget", "chunk",
         "dtype", "out_dtype", "phi_kind")] + [("softmax_scale", C.c_float), ("fold_defer", C.c_int32), ("query_hide", C.c_int32),
-                                        ("score_kind", C.c_int32)]
+                                        ("score_kind", C.c_int32), ("prefill_overlap", C.c_int32)]
 
 
 class LolaState(C.Structure):
@@ -67,6 +67,8 @@ def lib() -> C.CDLL:
         L.lola_status_str.argtypes = [C.c_int]
         L.lola_kernel_path.restype = C.c_char_p
         L.lola_kernel_path.argtypes = [cfgp, i32]
+        L.lola_release_streams.restype = None
+        L.lola_release_streams.argtypes = []
         _lib = L
     return _lib
 
@@ -115,6 +117,10 @@ def lola_decode_step(cfg, st, q, k, v, Wq, Wk, out) -> None:
                                   _ptr(out), _stream()), "lola_decode_step")
 
 
+def lola_release_streams() -> None:
+    lib().lola_release_streams()
+
+
 def lola_kernel_path(cfg: LolaConfig, which: int) -> str:
     return lib().lola_kernel_path(C.byref(cfg), which).decode()
 
@@ -127,12 +133,12 @@ class LolaLayer:
 
     def __init__(self, B, Hq, Hkv, d, D, eta, lam, C_, dtype="bf16", out_dtype="f32",
                  phi_kind=LOLA_PHI_SOFTMAX, scale=0.0, fold_defer=0, query_hide=0, score_kind=0,
-                 device="cuda:0"):
+                 prefill_overlap=0, device="cuda:0"):
         self.device = torch.device(device)
         self.dt = LOLA_BF16 if dtype == "bf16" else LOLA_F32
         self.odt = LOLA_BF16 if out_dtype == "bf16" else LOLA_F32
         self.cfg = LolaConfig(B, Hq, Hkv, d, D, eta, lam, C_, self.dt, self.odt, phi_kind, float(scale), int(fold_defer),
-                              int(query_hide), int(score_kind))
+                              int(query_hide), int(score_kind), int(prefill_overlap))
         self.score_kind = int(score_kind)
         self.fold_defer = R = int(fold_defer)
         self.B, self.Hq, self.Hkv, self.d, self.D, self.eta, self.lam, self.C = B, Hq, Hkv, d, D, eta, lam, C_
@@ -197,9 +203,9 @@ class LolaLayer:
         if trace:
             nch = (T + self.C - 1) // self.C
             tr = torch.empty((self.B, self.Hkv, nch, self.lam), dtype=torch.int32, device=self.device)
-        ws = self._ws(T, q is not None, workspace_limit)
+        trp = tr if (tr is not None and tr.numel()) else None
         with torch.cuda.device(self.device):
-            lola_prefill(self.cfg, self.st, q, k, v, Wq, Wk, T, out, tr if (tr is not None and tr.numel()) else None, ws)
+            lola_prefill(self.cfg, self.st, q, k, v, Wq, Wk, T, out, trp, self._ws(T, q is not None, workspace_limit))
         return (out, tr) if trace else out
 
     def decode_step(self, q, k, v, Wq, Wk, out=None):

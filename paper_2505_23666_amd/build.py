@@ -12,7 +12,10 @@ SOURCES = [os.path.join(HERE, "csrc", "lola_api.hip")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-    # packed-fp32 instructions are kept off on the test machines
+    # packed-fp32 instructions are kept off on the test machines.  The switch is an AMDGPU target feature: the device
+    # pass honours it (the same source compiled with `-S --cuda-device-only` shows v_pk_fma_f32 / v_pk_mul_f32 without
+    # it and none with it); the x86 host pass of the same command does not know it and says so once per
+    # translation step, which build_library() filters out of the compiler's output.
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
 ]
@@ -23,7 +26,12 @@ def build_library(verbose: bool = False) -> str:
     cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-o", LIB, *SOURCES]
     if verbose:
         print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
+    r = subprocess.run(cmd, stderr=subprocess.PIPE, text=True)
+    for line in r.stderr.splitlines():
+        if "'-packed-fp32-ops' is not a recognized feature for this target" not in line:
+            print(line, file=sys.stderr)
+    if r.returncode != 0:
+        raise subprocess.CalledProcessError(r.returncode, cmd)
     return LIB
 
 

@@ -138,13 +138,6 @@ __device__ __forceinline__ float wmin(float v) { return -wmax(-v); }
 __device__ __forceinline__ float fexp2(float x) { return __builtin_amdgcn_exp2f(x); }
 constexpr float LOG2E = 1.4426950408889634f;
 
-#ifdef LOLA_TIMING
-extern __device__ long long lola_timing[];
-extern __device__ long long lola_stagger_ticks;
-#define LOLA_STAMP(k) do { if (threadIdx.x == 0) lola_timing[blockIdx.x * 16 + (k)] = wall_clock64(); } while (0)
-#else
-#define LOLA_STAMP(k) do { } while (0)
-#endif
 
 template <typename TO>
 struct DecodeFastArgs {
@@ -270,16 +263,6 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     const int pidx = (int)(tok - ETA);
     const int wn = (int)min((int64_t)ETA, tok + 1);   // window pairs after the push
 
-#ifdef LOLA_TIMING
-    if (lola_stagger_ticks > 0 && blockIdx.x >= gridDim.x / 2) {
-        const long long t0 = wall_clock64();
-        while (wall_clock64() - t0 < lola_stagger_ticks) __builtin_amdgcn_s_sleep(8);
-    }
-#endif
-    LOLA_STAMP(0);
-#ifdef LOLA_TIMING
-    if (threadIdx.x == 0) lola_timing[blockIdx.x * 16 + 13] = clock64();
-#endif
     // ---- stage 0: loads are requested in the order in which they are consumed (they complete in order): the small
     // per-stream vectors that the first barrier waits for, then the operands of the projections, then the window keys
     const uint4 q_ld = (tid >= 64 && tid < 64 + g * PR) ? reinterpret_cast<const uint4 *>(qg)[tid - 64] : make_uint4(0, 0, 0, 0);
@@ -326,7 +309,6 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     // the value row of the leaving pair (PR threads, 16 bytes each) is wanted much later
     uint4 p_ld = make_uint4(0, 0, 0, 0);
     if (popped && tid < PR) p_ld = reinterpret_cast<const uint4 *>(win_v + (size_t)slot * DH)[tid];
-    LOLA_STAMP(9);
     if (tid < D / 4) {
         float4 sv = s_ld;
         if (R > 0) {
@@ -357,7 +339,6 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
         *reinterpret_cast<uint4 *>(&PB[j * DH + ((pc ^ (j & (PR - 1))) << 3)]) = wk_ld[it];
     }
     __syncthreads();
-    LOLA_STAMP(1);
     // W_k as MFMA A operand (row = projection, k = input index): [projection tile][k-step]
     bf16x8 AW[4][KS];
 #pragma unroll
@@ -395,7 +376,6 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
         }
     }
 
-    LOLA_STAMP(10);
     // ---- stage 1a: phi of this wavefront's query; stored as bf16 high + low parts in the operand layout of the
     // recall GEMM (row w + 1 of the extra tile).  Each 1 KB piece of W_q yields four projections: eight products per
     // lane, then a reduction over the 16 lanes of a row; lane (r16, g4) keeps projection j = 4 r16 + g4.
@@ -440,7 +420,6 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
         }
     }
 
-    LOLA_STAMP(11);
     // ---- H^T rows of this wavefront are requested now and stay in registers until the fold writes them back:
     // lane (r16, g4) holds, for column tile ct and k-step ks, H^T[32w + 16ct + r16][32ks + 16 half + 4 g4 + 0..3]
     // (named scalars rather than an array: arrays of this size end up in scratch memory)
@@ -488,7 +467,6 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
             }
         }
     }
-    LOLA_STAMP(12);
     // operands of the listed pairs: A = phi_p (row = feature within a 16-block, k = p), B = v_p (column = value
     // index).  They are requested after the first key tile's feature map: from there on enough registers are free,
     // and the rest of the feature map covers their latency.
@@ -576,7 +554,6 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
         d[0] = bf_lo(p_ld.x); d[1] = bf_hi(p_ld.x); d[2] = bf_lo(p_ld.y); d[3] = bf_hi(p_ld.y);
         d[4] = bf_lo(p_ld.z); d[5] = bf_hi(p_ld.z); d[6] = bf_lo(p_ld.w); d[7] = bf_hi(p_ld.w);
     }
-    LOLA_STAMP(2);
     // value rows for the read-out are requested as soon as registers allow (after the recall GEMM in steady state);
     // they go to LDS once the feature tile is free
     constexpr int NVIT = KPAD * PR / 256;
@@ -617,7 +594,6 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
         LOLA_HREP(LOLA_HSPLIT)
 #undef LOLA_HSPLIT
         __syncthreads();   // feature vectors and denominators of all eligible pairs are in LDS
-        LOLA_STAMP(3);
         // Key tiles 0..NKT-1 are the cache slots; tile NKT is the extra tile (column 0: the leaving key, columns 1..G:
         // the queries, whose "recall" numerators are the linear read-out).  C layout: lane (column r16, group g4)
         // holds rows c = 32w + 16ct + 4 g4 + i.
@@ -682,7 +658,6 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
                 if (lane == 0) part[w][KP] = e2;
             }
         }
-        LOLA_STAMP(4);
         __syncthreads();
         load_values();
         // ---- stage 3: the pair that leaves the cache: smallest error, ties -> larger token index
@@ -701,7 +676,6 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
             const unsigned long long owner = __ballot(kb == kmin);
             drop = __builtin_amdgcn_readlane(be, (int)__builtin_ctzll(owner));
         }
-        LOLA_STAMP(5);
         // phi and v of the folded pair (phi from its bf16 high + low parts)
         if (tid < D) {
             const int f = tid;
@@ -763,7 +737,6 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
         else if (tid < 2 * PR) reinterpret_cast<uint4 *>(sp_v + (size_t)spc * DH)[tid - PR] = reinterpret_cast<const uint4 *>(pvb)[tid - PR];
         else if (tid == 2 * PR) { sp_idx[spc] = pidx; a.st.sp_count[si] = spc + 1; }
     }
-    LOLA_STAMP(6);
 
     // ---- stage 4: value rows into LDS (the feature tile is no longer needed): [key][c], key order = logit order; rows
     // past the last key are zero.  The cached value row of the dropped slot may be mid-overwrite: its weight is 0.
@@ -810,7 +783,6 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
         if (lane == 0) { psum_s[r] = sum; elin_s[r] = fexp2(-mx * LOG2E); }
     }
     __syncthreads();
-    LOLA_STAMP(7);
 
     // ---- stage 5: out[q][c] = sum_key p[q][key] v[key][c] on MFMA: A = weights (rows = queries), B = staged values
     // (column c, k = key); each wavefront owns CW output columns
@@ -863,10 +835,6 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     // the new pair takes the ring slot of the pair that left (read in stage 0)
     if (tid < 2 * PR) reinterpret_cast<uint4 *>(tid < PR ? win_k + (size_t)slot * DH : win_v + (size_t)slot * DH)[tid % PR] = new_ld;
     if (tid == 0) a.st.n_tokens[si] = tok + 1;
-    LOLA_STAMP(8);
-#ifdef LOLA_TIMING
-    if (threadIdx.x == 0) lola_timing[blockIdx.x * 16 + 14] = clock64();
-#endif
 }
 
 }  // namespace fast

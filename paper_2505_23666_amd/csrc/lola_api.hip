@@ -9,18 +9,6 @@
 
 using namespace lola;
 
-#ifdef LOLA_TIMING
-// development build only: per-workgroup phase time stamps of the fused decode kernel
-__device__ long long lola::fast::lola_timing[4096 * 16];
-__device__ long long lola::fast::lola_stagger_ticks = 0;
-extern "C" int lola_debug_set_stagger(long long ticks) {
-    return (int)hipMemcpyToSymbol(HIP_SYMBOL(lola::fast::lola_stagger_ticks), &ticks, sizeof(ticks));
-}
-extern "C" int lola_debug_read_timing(long long *host, size_t n) {
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(lola::fast::lola_timing), n * sizeof(long long));
-}
-#endif
-
 namespace {
 
 constexpr size_t ALIGN = 256;
@@ -50,7 +38,9 @@ lola_status check_config(const lola_config *c) {
     if (c->feat_dim < 2 || c->feat_dim > 512 || (c->feat_dim & 1)) return LOLA_ERR_SHAPE;
     if (c->window < 0 || c->sparse_budget < 0 || c->chunk < 1) return LOLA_ERR_SHAPE;
     if (c->window > 4096 || c->sparse_budget > 4096 || c->chunk > 1024) return LOLA_ERR_SHAPE;
-    if ((long long)c->batch * c->n_kv_heads > (1ll << 24)) return LOLA_ERR_SHAPE;
+    // streams, query heads and sequences index the y and z dimensions of some launch grids (limit 65535)
+    if ((long long)c->batch * c->n_kv_heads > 65535 || c->n_q_heads > 65535) return LOLA_ERR_SHAPE;
+    if (c->prefill_overlap != 0 && c->prefill_overlap != 1) return LOLA_ERR_SHAPE;
     if (c->query_hide < 0 || c->query_hide > 3) return LOLA_ERR_SHAPE;
     if (c->score_kind < LOLA_SCORE_SRE || c->score_kind > LOLA_SCORE_ATTN) return LOLA_ERR_DTYPE;
     if (c->fold_defer != 0 && c->fold_defer != DEFER_R) return LOLA_ERR_SHAPE;
@@ -155,6 +145,20 @@ int attend_tile_queries(const Dims &dm) {
 }
 
 #define LAUNCH_CHECK() do { if (hipGetLastError() != hipSuccess) return LOLA_ERR_HIP; } while (0)
+
+// Whether the shape-generic prefill kernels can tile this configuration into LDS; asked before anything is enqueued.
+lola_status prefill_feasible(const lola_config *c, bool want_out) {
+    const Dims dm = make_dims(c);
+    if (score_tile_rows(dm, scan_fixed_floats(dm)) <= 0) return LOLA_ERR_UNSUPPORTED;
+    if (want_out && attend_tile_queries(dm) <= 0) return LOLA_ERR_UNSUPPORTED;
+    if (dm.score_kind && band_tile_rows(dm) <= 0) return LOLA_ERR_UNSUPPORTED;
+    return LOLA_OK;
+}
+lola_status decode_feasible(const lola_config *c) {
+    if (c->dtype == LOLA_BF16 && fast_decode_ok(c)) return LOLA_OK;
+    const Dims dm = make_dims(c);
+    return score_tile_rows(dm, decode_fixed_floats(dm), dm.score_kind != 0) > 0 ? LOLA_OK : LOLA_ERR_UNSUPPORTED;
+}
 
 // The MFMA kernels of the prefill cover the Llama 8B and 1B head shapes (head_dim 128 / 64, 128 features) with
 // chunk = window = 64.
@@ -272,10 +276,32 @@ constexpr size_t OVERLAP_MIN_WORK = 4096;     // output workgroups (in units of 
 std::mutex side_init_mu;   // creation of the per-device entries
 std::mutex side_use_mu;    // held by a call from its first fork to its join: the events are shared
 
+constexpr int MAX_DEV = 16;
+SideStream side_table[MAX_DEV];
+int side_state[MAX_DEV];   // 0 not created, 1 ready, -1 unavailable
+
+// destroys every second stream and its events (the next call that wants one creates it again)
+void release_side_streams() {
+    std::lock_guard<std::mutex> lock(side_init_mu);
+    int cur = -1;
+    const bool have_cur = hipGetDevice(&cur) == hipSuccess;
+    for (int dev = 0; dev < MAX_DEV; dev++) {
+        if (side_state[dev] == 1 && hipSetDevice(dev) == hipSuccess) {
+            SideStream &t = side_table[dev];
+            (void)hipStreamSynchronize(t.s);
+            for (int i = 0; i < SideStream::NEV; i++) (void)hipEventDestroy(t.fork[i]);
+            (void)hipEventDestroy(t.join);
+            (void)hipStreamDestroy(t.s);
+        }
+        side_state[dev] = 0;
+    }
+    if (have_cur) (void)hipSetDevice(cur);
+    (void)hipGetLastError();
+}
+
 SideStream *side_stream(hipStream_t caller) {
-    constexpr int MAX_DEV = 16;
-    static SideStream table[MAX_DEV];
-    static int state[MAX_DEV];   // 0 not tried, 1 ready, -1 unavailable
+    SideStream *table = side_table;
+    int *state = side_state;
     hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
     if (hipStreamIsCapturing(caller, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) {
         (void)hipGetLastError();
@@ -396,8 +422,23 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
                 const size_t work = (size_t)piece * a.dm.Hq * a.dm.B * (size_t)(c->head_dim / 64);
                 if ((size_t)np > work / OVERLAP_MIN_WORK) np = (int)(work / OVERLAP_MIN_WORK);
                 if (np > SideStream::NEV) np = SideStream::NEV;
-                if (a.want_out && ns <= OVERLAP_MAX_STREAMS && np >= 2) side = side_stream(stream);
+                if (c->prefill_overlap && a.want_out && ns <= OVERLAP_MAX_STREAMS && np >= 2) side = side_stream(stream);
                 std::unique_lock<std::mutex> side_lock(side_use_mu, std::defer_lock);
+                // Whatever happens after the first fork, the caller's stream waits for the second stream before this
+                // call returns (an error path included): declared after the lock, so it runs while the lock is held.
+                struct Joiner {
+                    SideStream *side = nullptr; hipStream_t stream = nullptr; bool forked = false;
+                    bool join() {
+                        if (!forked) return true;
+                        forked = false;
+                        const bool ok = hipEventRecord(side->join, side->s) == hipSuccess &&
+                                        hipStreamWaitEvent(stream, side->join, 0) == hipSuccess;
+                        if (!ok) (void)hipGetLastError();
+                        return ok;
+                    }
+                    ~Joiner() { (void)join(); }
+                } joiner;
+                joiner.side = side; joiner.stream = stream;
                 // Piece boundaries: each piece half as long as the one before it, so that the outputs of a piece
                 // (which take about half as long per chunk as the evolution) are hidden behind the evolution of the
                 // next; the last piece, whose outputs nothing hides, is at least one round of output workgroups on the
@@ -421,6 +462,7 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
                 // outputs of the chunks [r0, r1) on the second stream, behind what `stream` held when fork[ev] was recorded
                 auto attend_aside = [&](int ev, int r0, int r1) -> bool {
                     if (hipStreamWaitEvent(side->s, side->fork[ev], 0) != hipSuccess) return false;
+                    joiner.forked = true;
                     attend(side->s, r0, r1);
                     return hipGetLastError() == hipSuccess;
                 };
@@ -461,8 +503,7 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
                               // own work) behind all outputs
                     if (hipEventRecord(side->fork[ip - 1], stream) != hipSuccess) return LOLA_ERR_HIP;
                     if (!attend_aside(ip - 1, prev0, jend)) return LOLA_ERR_HIP;
-                    if (hipEventRecord(side->join, side->s) != hipSuccess) return LOLA_ERR_HIP;
-                    if (hipStreamWaitEvent(stream, side->join, 0) != hipSuccess) return LOLA_ERR_HIP;
+                    if (!joiner.join()) return LOLA_ERR_HIP;
                 }
                 continue;
             }
@@ -567,6 +608,8 @@ lola_status lola_prefill(const lola_config *c, const lola_state *st, const void 
     size_t need_min = 0;
     lola_prefill_workspace_bytes(c, T, q != nullptr, &need_min);
     if (!workspace || workspace_bytes < need_min) return LOLA_ERR_WORKSPACE;
+    rc = prefill_feasible(c, q != nullptr);
+    if (rc != LOLA_OK) return rc;
     rc = flush_pending(c, st, (hipStream_t)stream);   // the prefill kernels read H and s as they are in memory
     if (rc != LOLA_OK) return rc;
     if (c->dtype == LOLA_F32)
@@ -583,9 +626,16 @@ lola_status lola_decode_step(const lola_config *c, const lola_state *st, const v
     if (!q || !k || !v || !Wq || !Wk || !out) return LOLA_ERR_NULL;
     const void *ps[] = {q, k, v, Wq, Wk, out};
     for (const void *p : ps) if (misaligned(p)) return LOLA_ERR_ALIGN;
+    rc = decode_feasible(c);
+    if (rc != LOLA_OK) return rc;
     if (c->dtype == LOLA_F32) return run_decode<float>(c, st, q, k, v, Wq, Wk, out, (hipStream_t)stream);
     if (fast_decode_ok(c)) return run_fast_decode(c, st, q, k, v, Wq, Wk, out, (hipStream_t)stream);
     return run_decode<bf16_t>(c, st, q, k, v, Wq, Wk, out, (hipStream_t)stream);
+}
+
+void lola_release_streams(void) {
+    std::lock_guard<std::mutex> use(side_use_mu);
+    release_side_streams();
 }
 
 const char *lola_status_str(lola_status s) {

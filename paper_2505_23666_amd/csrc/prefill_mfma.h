@@ -390,7 +390,6 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
             __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
             __syncthreads();
         }
-        if (j == a.j1 - 1) LOLA_STAMP(0);
         // The lane coordinates are made opaque once per chunk: everything derived from them (LDS and global
         // addresses of every phase) is then recomputed inside the loop instead of being hoisted out of it as
         // hundreds of loop-invariant registers, which the register file cannot hold next to H^T.
@@ -448,7 +447,6 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
         static_assert(LAM <= NTH, "one slot per thread");
         const int sprow_ld = (a.want_out && tid < LAM) ? sp_row[tid] : 0;
 
-        if (j == a.j1 - 1) LOLA_STAMP(1);
         // ---- 2. phi of the candidates and their recall error, in batches of TB tiles.  Global loads of a batch are
         // requested up front: the candidates' values for the recall epilogue, then the rows wanted by the next chunk; the
         // snapshot stores follow, so that they drain while the recall GEMM runs out of LDS and registers.
@@ -532,9 +530,7 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
                 if (tid < D / 4) reinterpret_cast<float4 *>(a.snapS + sj * D)[tid] = reinterpret_cast<const float4 *>(s_l)[tid];
                 if (tid < LAM) a.snapG[sj * LAM + tid] = sprow_ld;
             }
-            if (j == a.j1 - 1 && t0 == 0) LOLA_STAMP(2);
             __syncthreads();
-            if (j == a.j1 - 1 && t0 == 0) LOLA_STAMP(3);
             // recall GEMM for the batch: A = this wavefront's 16 rows of H^T, B = phi from LDS; lane (candidate r16,
             // group g4) holds rows c = 16w + 4 g4 + i and pairs them with the candidate's values at those columns.
             // Tile t's denominators come from wavefront t % 8 (A = s in row 0, zeros below).  Operands of the next
@@ -688,11 +684,9 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
                         }
                 }
             }
-            if (j == a.j1 - 1 && t0 == 0) LOLA_STAMP(4);
             __syncthreads();
         }
 
-        if (j == a.j1 - 1) LOLA_STAMP(5);
         // ---- 3. selection: the 64 candidates with the smallest squared error are folded (order: score descending,
         // token index ascending, the first LAM stay).  The squared error is |P|^2 / (phi.s)^2 - 2 P.v / (phi.s) + |v|^2
         // (recall = 0 while phi.s = 0, i.e. nothing folded yet); the bit pattern of a float >= 0 orders like an integer.
@@ -705,7 +699,6 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
             skey[e] = __float_as_uint(sq) & 0x7FFFFFFFu;
         }
         __syncthreads();
-        if (j == a.j1 - 1) LOLA_STAMP(6);
         // One wavefront holds all scores (NK per lane) and finds the 64th smallest by building it bit by bit: a trial
         // value is kept when fewer than 64 scores lie below it (votes counted on the scalar unit).  Scores equal to
         // the threshold are folded too if that makes exactly 64; otherwise (exact ties across the cut) the same search
@@ -810,7 +803,6 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
         __syncthreads();
         // exactly 64 are folded, so entrants and leavers pair up
         const int ne = ne_s;
-        if (j == a.j1 - 1) LOLA_STAMP(7);
 
         // ---- 4. fold: operands of the folded pairs transposed into LDS, then H[f][c] += sum_e phi_e[f] v_e[c].
         // Each thread takes two folded pairs (e', e'+1) and one 16-byte piece of their rows and writes eight 32-bit
@@ -869,9 +861,7 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
                 }
             }
         }
-        if (j == a.j1 - 1) LOLA_STAMP(8);
         __syncthreads();
-        if (j == a.j1 - 1) LOLA_STAMP(9);
         {
             // compaction, first half: the entrants' rows are requested now and stored after the fold (all reads of
             // the leavers' rows were completed before the barrier above)
@@ -923,7 +913,6 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
                     *sp = sv;
                 }
             }
-            if (j == a.j1 - 1) LOLA_STAMP(10);
             // ---- 5. compaction, second half: entrants take the leavers' slots, in the state and (their features) in LDS
 #pragma unroll
             for (int it = 0; it < CIT; it++) {
@@ -969,9 +958,7 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
         idx_valid = true;
         phi_valid = PERSIST;
         rows_valid = !PERSIST;
-        if (j == a.j1 - 1) LOLA_STAMP(11);
         __syncthreads();   // (workgroup scope is enough: only this workgroup reads the stream's memories before the kernel ends)
-        if (j == a.j1 - 1) LOLA_STAMP(12);
         if (a.sel_trace) {
             int32_t *tr = a.sel_trace + ((size_t)si * a.n_chunks + j) * LAM;
             for (int sl = tid; sl < LAM; sl += NTH) tr[sl] = sp_idx[sl];

@@ -16,3 +16,14 @@ def pytest_configure(config):
 def _oracle_built():
     from oracle import lola_oracle
     lola_oracle.build()
+
+
+def pytest_terminal_summary(terminalreporter):
+    """After a GPU run: the largest error each compared quantity reached, beside its bounds."""
+    parity = sys.modules.get("parity")
+    if parity is None or not getattr(parity, "WORST", None):
+        return
+    terminalreporter.write_line("largest relative errors against the oracle in this session "
+                                "(contract bf16 2e-3 / f32 1e-5; regression bounds bf16 1e-4 / f32 5e-6):")
+    for (dtype, what), err in sorted(parity.WORST.items()):
+        terminalreporter.write_line(f"  {dtype:5s} {what:28s} {err:.3e}")

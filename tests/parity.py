@@ -18,6 +18,15 @@ from oracle import lola_oracle as orc
 from paper_2505_23666_amd import binding as lb
 
 TOL = {"bf16": 2e-3, "f32": 1e-5}
+# Regression bounds, asserted beside the contractual tolerances above: about twenty times what the
+# kernels deliver (bf16 storage: fp32 accumulation and bf16 high + low operand parts, observed <= 6e-6;
+# fp32 storage: observed <= 1.5e-6), so that a change which costs a digit fails although it would
+# still meet the contract.
+REGRESS = {"bf16": 1e-4, "f32": 5e-6}
+# One rounding of an output to bf16 (8 significant bits, round to nearest even) moves it by at most
+# 2^-8 of its magnitude, hence by at most 2^-8 of the row's largest magnitude in the row-wise measure.
+BF16_OUT = 2.0 ** -8
+WORST = {}   # largest error seen per (storage type, quantity) in this test session, printed at its end
 TIE_EPS = 1e-4
 SCORE_TOL = 1e-4   # query-dependent scores: fp32 sums of up to eta * g positive terms against fp64
 DEV = "cuda:0"
@@ -107,11 +116,26 @@ def subset_inputs(sh: wl.Shape, q, k, v, Wq, Wk, bsel=None, hsel=None):
     return qq, np.ascontiguousarray(k[ik]), np.ascontiguousarray(v[ik]), np.ascontiguousarray(Wq[hq]), np.ascontiguousarray(Wk[hs]), bs, hs, hq
 
 
+def note(dtype: str, what: str, err: float):
+    key = (dtype, what)
+    WORST[key] = max(WORST.get(key, 0.0), float(err))
+
+
+def bounds(dtype: str, out_dtype: str = "f32"):
+    """(contractual tolerance, regression bound) of a compared quantity"""
+    extra = BF16_OUT if out_dtype == "bf16" else 0.0
+    return TOL[dtype] + extra, REGRESS[dtype] + extra
+
+
 def check_state(g: dict, o: orc.Oracle, tol: float):
     """H, s, sparse index sets, cached K/V rows by token index, window rows, counters."""
     eH, es = stream_rel_err(g["H"], o.H), stream_rel_err(g["s"], o.s)
+    dtype = "f32" if tol <= TOL["f32"] else "bf16"
+    note(dtype, "H", eH.max()); note(dtype, "s", es.max())
     assert eH.max() <= tol, f"H rel err {eH.max():.3e}"
     assert es.max() <= tol, f"s rel err {es.max():.3e}"
+    assert eH.max() <= REGRESS[dtype], f"H rel err {eH.max():.3e} meets the contract but not the regression bound {REGRESS[dtype]}"
+    assert es.max() <= REGRESS[dtype], f"s rel err {es.max():.3e} meets the contract but not the regression bound {REGRESS[dtype]}"
     np.testing.assert_array_equal(sorted_sets(g["sp_idx"]), o.sparse_idx)
     cnt = g["sp_count"]
     np.testing.assert_array_equal(cnt, (o.sparse_idx >= 0).sum(-1))
@@ -144,7 +168,7 @@ def prefill_parity(sh: wl.Shape, q, k, v, Wq, Wk, layer=None, oracle=None, with_
                    out_dtype="f32", bsel=None, hsel=None, layer_kw=None):
     """One prefill call on both sides (the oracle possibly on a subset of the streams);
     returns (layer, oracle, report)."""
-    tol = TOL[sh.dtype] + (2.0 ** -8 if out_dtype == "bf16" else 0.0)
+    tol, reg = bounds(sh.dtype, out_dtype)
     layer = layer or make_layer(sh, out_dtype=out_dtype, B=k.shape[0], **(layer_kw or {}))
     dq = to_dev(q, sh.dtype) if with_outputs else None
     dk, dv = to_dev(k, sh.dtype), to_dev(v, sh.dtype)
@@ -165,7 +189,9 @@ def prefill_parity(sh: wl.Shape, q, k, v, Wq, Wk, layer=None, oracle=None, with_
     if with_outputs:
         err = row_rel_err(out[bs][:, hq].float().cpu().numpy(), y_or)
         rep["max_out_err"] = float(err.max())
+        note(sh.dtype, "prefill out" + (" (bf16 out)" if out_dtype == "bf16" else ""), err.max())
         assert err.max() <= tol, f"output rel err {err.max():.3e} > {tol}"
+        assert err.max() <= reg, f"output rel err {err.max():.3e} meets the contract but not the regression bound {reg}"
     rep["H_err"], rep["s_err"] = check_state(gpu_state_np(layer, bs, hs), oracle, TOL[sh.dtype])
     return layer, oracle, rep
 
@@ -177,7 +203,7 @@ def decode_parity(sh: wl.Shape, layer, oracle, qd, kd, vd, Wq, Wk, out_dtype="f3
     (e.g. with deferred folds) that is fed the same steps; its outputs are held to the oracle in
     the same way, its selections must equal the first layer's on every stream, its final state is
     checked too."""
-    tol = TOL[sh.dtype] + (2.0 ** -8 if out_dtype == "bf16" else 0.0)
+    tol, reg = bounds(sh.dtype, out_dtype)
     n = qd.shape[0]
     bs = list(bsel) if bsel is not None else list(range(kd.shape[1]))
     hs = list(hsel) if hsel is not None else list(range(sh.Hkv))
@@ -194,15 +220,18 @@ def decode_parity(sh: wl.Shape, layer, oracle, qd, kd, vd, Wq, Wk, out_dtype="f3
         err = row_rel_err(out[bs][:, hq].float().cpu().numpy(), y_or).max()
         worst = max(worst, float(err))
         assert err <= tol, f"decode step {i}: output rel err {err:.3e} > {tol}"
+        assert err <= reg, f"decode step {i}: output rel err {err:.3e} meets the contract but not the regression bound {reg}"
         if shadow is not None:
             out2 = shadow.decode_step(dq[i], dk[i], dv[i], dWq, dWk)
             err2 = row_rel_err(out2[bs][:, hq].float().cpu().numpy(), y_or).max()
             worst = max(worst, float(err2))
             assert err2 <= tol, f"decode step {i} (shadow layer): output rel err {err2:.3e} > {tol}"
+            assert err2 <= reg, f"decode step {i} (shadow layer): output rel err {err2:.3e} > regression bound {reg}"
             assert torch.equal(shadow.sp_idx, layer.sp_idx), f"decode step {i}: the shadow layer selected differently"
     if shadow is not None:
         check_state(gpu_state_np(shadow, bs, hs), oracle, TOL[sh.dtype])
     st = oracle.stats()
     assert st["mismatch"] == 0, f"sparse-cache sets differ outside the tie band: {st}"
     eH, es = check_state(gpu_state_np(layer, bs, hs), oracle, TOL[sh.dtype])
+    note(sh.dtype, "decode out" + (" (bf16 out)" if out_dtype == "bf16" else ""), worst)
     return {"max_out_err": worst, "H_err": eH, "s_err": es, **st}

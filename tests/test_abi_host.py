@@ -113,6 +113,32 @@ def test_arguments_rejected_before_launch(L):
     assert f(C.byref(cfg(query_hide=4)), C.byref(st), vp(fake), vp(fake), vp(fake), vp(fake), vp(fake), vp(fake), None) == -2
 
 
+def test_unsupported_tilings_are_refused_before_anything_is_enqueued(L):
+    """A configuration that passes the range checks but that no kernel can tile into LDS must come back as
+    LOLA_ERR_UNSUPPORTED from the host-side checks.  No GPU is present here, so anything that reached a
+    launch (the flush of deferred folds, the first prefill kernel) would come back as LOLA_ERR_HIP instead."""
+    vp = C.c_void_p
+    fake = 0x1000
+    st = lb.LolaState(*([fake] * 9 + [None] * 5))
+    big = cfg(dtype=lb.LOLA_F32, head_dim=256, feat_dim=512, window=4096, sparse_budget=4096, chunk=1024)
+    assert lb.lola_state_bytes(big)[0] > 0                      # a valid configuration
+    full, mn = lb.lola_prefill_workspace_bytes(big, 1024, True)
+    assert mn > 0
+    rc = L.lola_prefill(C.byref(big), C.byref(st), vp(fake), vp(fake), vp(fake), vp(fake), vp(fake), 1024, vp(fake), None,
+                        vp(fake), 1 << 50, None)
+    assert rc == -5
+    # the generation step of this shape fits (it would be launched); with a query-dependent score it does not
+    bigs = cfg(dtype=lb.LOLA_F32, head_dim=256, feat_dim=512, window=4096, sparse_budget=4096, chunk=1024, score_kind=1)
+    sts = lb.LolaState(*([fake] * 9 + [None] * 3 + [fake] * 2))
+    rc = L.lola_decode_step(C.byref(bigs), C.byref(sts), vp(fake), vp(fake), vp(fake), vp(fake), vp(fake), vp(fake), None)
+    assert rc == -5
+    # streams, query heads and sequences must fit the launch grids' y / z limits
+    assert lb.lola_state_bytes(cfg(batch=40000, n_q_heads=2, n_kv_heads=2))[0] == 0
+    assert lb.lola_state_bytes(cfg(batch=1, n_q_heads=131072, n_kv_heads=2))[0] == 0
+    assert lb.lola_state_bytes(cfg(prefill_overlap=2))[0] == 0
+    L.lola_release_streams()    # nothing was created: a no-op
+
+
 def test_benchmark_work_counts_match_the_documented_figures():
     """The algorithmic bytes / flops bench.py divides by are the ones the design notes derive from the
     layer's definition (8B shape: 235 524 B per stream and step, 121.24 MB per launch at batch 64;

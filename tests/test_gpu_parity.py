@@ -327,15 +327,17 @@ def test_8b_shape_outputs_on_the_second_stream():
     Wq, Wk = wl.weights(sh)
     q, k, v, _ = wl.sequence_inputs(sh)
     cut = 64 * 32 + 37
-    layer, o, rep = P.prefill_parity(sh, q[:, :, :cut], k[:, :, :cut], v[:, :, :cut], Wq, Wk)
+    kw = dict(prefill_overlap=1)
+    layer, o, rep = P.prefill_parity(sh, q[:, :, :cut], k[:, :, :cut], v[:, :, :cut], Wq, Wk, layer_kw=kw)
     say("two-stream call 1", rep)
-    layer, o, rep = P.prefill_parity(sh, q[:, :, cut:], k[:, :, cut:], v[:, :, cut:], Wq, Wk, layer=layer, oracle=o)
+    layer, o, rep = P.prefill_parity(sh, q[:, :, cut:], k[:, :, cut:], v[:, :, cut:], Wq, Wk, layer=layer, oracle=o, layer_kw=kw)
     say("two-stream call 2", rep)
-    # the same tokens in one call: the copy enqueued right behind the call holds the finished outputs
-    one = P.make_layer(sh)
+    # the same tokens in one call: the copy enqueued right behind the call holds the finished outputs, and they are
+    # bit for bit those of a call that stays on one stream (prefill_overlap = 0)
     dq, dk, dv = P.to_dev(q[:, :, :cut], "bf16"), P.to_dev(k[:, :, :cut], "bf16"), P.to_dev(v[:, :, :cut], "bf16")
     dWq, dWk = P.w_to_dev(Wq, "bf16"), P.w_to_dev(Wk, "bf16")
-    ref = one.prefill(dq, dk, dv, dWq, dWk).clone()
+    ref = P.make_layer(sh).prefill(dq, dk, dv, dWq, dWk).clone()
+    one = P.make_layer(sh, **kw)
     torch.cuda.synchronize()
     side = torch.cuda.Stream()
     for _ in range(3):
@@ -346,6 +348,13 @@ def test_8b_shape_outputs_on_the_second_stream():
             out.zero_()
         side.synchronize()
         assert torch.equal(snap, ref)
+    # the library's second stream can be destroyed and comes back on the next call that wants it
+    from paper_2505_23666_amd import binding as lb
+    lb.lola_release_streams()
+    one.reset()
+    assert torch.equal(one.prefill(dq, dk, dv, dWq, dWk), ref)
+    torch.cuda.synchronize()
+    lb.lola_release_streams()
 
 
 def test_two_stream_prefill_from_two_host_threads():
@@ -358,7 +367,7 @@ def test_two_stream_prefill_from_two_host_threads():
     cases = []
     for seed in (11, 12):
         q, k, v, _ = wl.sequence_inputs(wl.scaled(3, T=sh.T, seed=seed))
-        lay = P.make_layer(sh)
+        lay = P.make_layer(sh, prefill_overlap=1)
         dq, dk, dv = P.to_dev(q, "bf16"), P.to_dev(k, "bf16"), P.to_dev(v, "bf16")
         ref = lay.prefill(dq, dk, dv, dWq, dWk).clone()
         torch.cuda.synchronize()
@@ -616,7 +625,7 @@ def test_config2_1b_prefill_full():
     Wq, Wk = wl.weights(sh)
     q, k, v, _ = wl.sequence_inputs(sh)
     t = time.time()
-    _, _, rep = P.prefill_parity(sh, q, k, v, Wq, Wk)
+    _, _, rep = P.prefill_parity(sh, q, k, v, Wq, Wk, layer_kw=dict(prefill_overlap=1))
     say("config2 full (all 8 streams, all 4096 x 32 output rows)", rep, f"{time.time() - t:.1f}s")
     assert rep["scored"] == 8 * (4096 // 64 - 2)
 
@@ -626,7 +635,7 @@ def test_config3_8b_prefill_full():
     Wq, Wk = wl.weights(sh)
     q, k, v, _ = wl.sequence_inputs(sh)
     t = time.time()
-    _, _, rep = P.prefill_parity(sh, q, k, v, Wq, Wk)
+    _, _, rep = P.prefill_parity(sh, q, k, v, Wq, Wk, layer_kw=dict(prefill_overlap=1))
     say("config3 full (all 32 streams, all outputs)", rep, f"{time.time() - t:.1f}s")
 
 
@@ -636,7 +645,7 @@ def test_config5_recall_64k_full():
     Wq, Wk = wl.weights(sh)
     q, k, v, ex = wl.sequence_inputs(sh)
     t = time.time()
-    layer, o, rep = P.prefill_parity(sh, q, k, v, Wq, Wk, hsel=[0, 3, 7])
+    layer, o, rep = P.prefill_parity(sh, q, k, v, Wq, Wk, hsel=[0, 3, 7], layer_kw=dict(prefill_overlap=1))
     pos = set(int(p) for p in ex["planted_pos"])
     g_frac = np.mean([len(pos & set(layer.sp_idx[0, h].cpu().numpy().tolist())) / len(pos) for h in range(sh.Hkv)])
     o_frac = np.mean([len(pos & set(o.sparse_idx[0, h].tolist())) / len(pos) for h in range(3)])
@@ -647,7 +656,7 @@ def test_config4_decode_batch64_full():
     """Batch 64, each sequence prefilled with 32768 tokens (update-only call), then generation
     steps.  The oracle follows sequences 0, 21, 42, 63 end to end (prefill + every step)."""
     sh = wl.CONFIGS[4]
-    n_steps = int(os.environ.get("LOLA_TEST_DECODE_STEPS", "256"))
+    n_steps = int(os.environ.get("LOLA_TEST_DECODE_STEPS", "1024"))
     bsel = [0, 21, 42, 63]
     Wq, Wk = wl.weights(sh)
     layer = P.make_layer(sh)

@@ -542,3 +542,33 @@ def test_forced_selection_only_inside_tie_band(gap, adopt):
         assert o.sparse_idx[0, 0, 0] == 1 and st["adopted"] == 1 and st["mismatch"] == 0
     else:
         assert o.sparse_idx[0, 0, 0] == 2 and st["adopted"] == 0 and st["mismatch"] == 1
+
+
+@pytest.mark.parametrize("delta,adopt", [(5e-5, True), (1e-3, False)])
+def test_forced_selection_band_is_relative_for_query_dependent_scores(delta, adopt):
+    # Attention-weight score (appendix "scoring ablation"), eta = lambda = 1, one query head, scale 1:
+    # a key is seen in the window by the query of its own position only, so Score(k_i) = exp(q_i . k_i).
+    # Tokens 1 and 2 score e^6 and e^(6 + delta): about 403 apart by 403 * delta.  delta = 5e-5 gives a
+    # difference of 0.02: far outside an absolute band of 1e-4, inside the relative band 1e-4 * 403.
+    d = 2
+    W = np.zeros((1, d, 1), np.float32)
+    qx = np.array([0.0, 6.0, 6.0 + delta, 0.0], np.float32)
+    q = np.zeros((1, 1, 4, d), np.float32); q[0, 0, :, 0] = qx
+    k = np.zeros((1, 1, 4, d), np.float32); k[0, 0, :, 0] = 1.0
+    v = np.arange(8, dtype=np.float32).reshape(1, 1, 4, d)
+    o = orc.Oracle(1, 1, 1, d, 2, eta=1, lam=1, C_=1, scale=1.0, score_kind=orc.SCORE_ATTN)
+    for t in range(2):
+        o.decode_step(q[:, :, t], k[:, :, t], v[:, :, t], W, W)
+    assert o.sparse_idx[0, 0, 0] == 0                       # token 0 left the window into an empty cache
+    o.decode_step(q[:, :, 2], k[:, :, 2], v[:, :, 2], W, W)   # token 1 leaves: e^6 beats e^0
+    assert o.sparse_idx[0, 0, 0] == 1 and list(o.folded(0)) == [0]
+    # token 2 leaves: the oracle would keep it (larger score); another implementation kept token 1
+    force = np.array([[[1]]], np.int32)
+    o.decode_step(q[:, :, 3], k[:, :, 3], v[:, :, 3], W, W, force_sel=force, tie_eps=1e-4)
+    st = o.stats()
+    gap = float(np.exp(np.float64(qx[2])) - np.exp(6.0))
+    assert gap > 1e-4                                        # an absolute band would refuse both cases
+    if adopt:
+        assert o.sparse_idx[0, 0, 0] == 1 and st["adopted"] == 1 and st["mismatch"] == 0
+    else:
+        assert o.sparse_idx[0, 0, 0] == 2 and st["adopted"] == 0 and st["mismatch"] == 1
