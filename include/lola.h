@@ -44,7 +44,8 @@ typedef enum {
     LOLA_ERR_ALIGN = -4,       /* a pointer is not 16-byte aligned */
     LOLA_ERR_UNSUPPORTED = -5, /* valid request this build has no kernel for */
     LOLA_ERR_WORKSPACE = -6,   /* workspace missing or smaller than the stated minimum */
-    LOLA_ERR_HIP = -7          /* a HIP launch reported an error */
+    LOLA_ERR_HIP = -7,         /* a HIP launch reported an error */
+    LOLA_ERR_TOO_LARGE = -8    /* lola_prefill_noalloc: the call needs more scratch than the library holds */
 } lola_status;
 
 enum { LOLA_F32 = 0, LOLA_BF16 = 1 };
@@ -170,6 +171,26 @@ lola_status lola_prefill(const lola_config *cfg, const lola_state *st,
                          const void *q, const void *k, const void *v,
                          const void *Wq, const void *Wk, int32_t T, void *out,
                          int32_t *sel_trace, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * lola_prefill for callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, same results and same checks as lola_prefill, without the workspace: the
+ * scratch is an array of lola_noalloc_scratch_bytes() = 64 MiB in the library's own device data, one copy per GPU,
+ * held until the process ends.  The call allocates nothing, frees nothing, creates no stream or event (it stays on
+ * `stream`, whatever prefill_overlap says) and never synchronises; the array's device address is looked up on the
+ * first call on each device.  A call whose smallest workspace (lola_prefill_workspace_bytes, *min_bytes) exceeds the
+ * array returns LOLA_ERR_TOO_LARGE with nothing enqueued; a call that fits but is large is processed in several
+ * passes over its chunks, as lola_prefill does with a small workspace.  The scratch need not be cleared between
+ * calls (every pass writes what it reads).  All calls on one GPU share the array: the caller orders them (one
+ * stream, or events); calls that overlap on one GPU race.
+ */
+lola_status lola_prefill_noalloc(const lola_config *cfg, const lola_state *st,
+                                 const void *q, const void *k, const void *v,
+                                 const void *Wq, const void *Wk, int32_t T, void *out,
+                                 int32_t *sel_trace, void *stream);
+
+/* Size of the static scratch of lola_prefill_noalloc (host value, the same on every device). */
+size_t lola_noalloc_scratch_bytes(void);
 
 /*
  * One generation step for every sequence (Sec. 3, E_t / G_t / S_t / y_t equations; appendix

@@ -19,7 +19,8 @@ LOLA_PHI_SOFTMAX, LOLA_PHI_EXP = 0, 1
 LOLA_HIDE_STATE, LOLA_HIDE_SPARSE = 1, 2
 LOLA_SCORE_SRE, LOLA_SCORE_WERR_SQ, LOLA_SCORE_WERR_ABS, LOLA_SCORE_OVEREST, LOLA_SCORE_ATTN = 0, 1, 2, 3, 4
 EXPORTS = ("lola_state_bytes", "lola_prefill_workspace_bytes", "lola_state_init", "lola_state_flush", "lola_prefill",
-           "lola_decode_step", "lola_status_str", "lola_kernel_path", "lola_release_streams")
+           "lola_decode_step", "lola_status_str", "lola_kernel_path", "lola_release_streams", "lola_prefill_noalloc",
+           "lola_noalloc_scratch_bytes")
 
 
 class LolaConfig(C.Structure):
@@ -67,6 +68,10 @@ def lib() -> C.CDLL:
         L.lola_status_str.argtypes = [C.c_int]
         L.lola_kernel_path.restype = C.c_char_p
         L.lola_kernel_path.argtypes = [cfgp, i32]
+        L.lola_prefill_noalloc.restype = C.c_int
+        L.lola_prefill_noalloc.argtypes = [cfgp, stp, vp, vp, vp, vp, vp, i32, vp, vp, vp]
+        L.lola_noalloc_scratch_bytes.restype = sz
+        L.lola_noalloc_scratch_bytes.argtypes = []
         L.lola_release_streams.restype = None
         L.lola_release_streams.argtypes = []
         _lib = L
@@ -110,6 +115,11 @@ def lola_prefill(cfg, st, q, k, v, Wq, Wk, T, out, sel_trace, workspace) -> None
     nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().lola_prefill(C.byref(cfg), C.byref(st), _ptr(q), _ptr(k), _ptr(v), _ptr(Wq), _ptr(Wk), int(T),
                               _ptr(out), _ptr(sel_trace), _ptr(workspace), nbytes, _stream()), "lola_prefill")
+
+
+def lola_prefill_noalloc(cfg, st, q, k, v, Wq, Wk, T, out, sel_trace) -> None:
+    _check(lib().lola_prefill_noalloc(C.byref(cfg), C.byref(st), _ptr(q), _ptr(k), _ptr(v), _ptr(Wq), _ptr(Wk), int(T),
+                                      _ptr(out), _ptr(sel_trace), _stream()), "lola_prefill_noalloc")
 
 
 def lola_decode_step(cfg, st, q, k, v, Wq, Wk, out) -> None:
@@ -190,9 +200,10 @@ class LolaLayer:
             self.workspace = torch.empty(want, dtype=torch.uint8, device=self.device)
         return self.workspace[:want] if limit_bytes is not None else self.workspace
 
-    def prefill(self, q, k, v, Wq, Wk, out=None, trace=False, workspace_limit=None):
+    def prefill(self, q, k, v, Wq, Wk, out=None, trace=False, workspace_limit=None, noalloc=False):
         """q [B,Hq,T,d] or None; k, v [B,Hkv,T,d].  Returns out (or None), plus the selection
-        trace [B,Hkv,n_chunks,lam] when trace=True."""
+        trace [B,Hkv,n_chunks,lam] when trace=True.  noalloc=True calls lola_prefill_noalloc (`out` must be given:
+        this wrapper then allocates nothing either, unless a trace is asked for)."""
         T = k.shape[2]
         assert k.shape == (self.B, self.Hkv, T, self.d) and v.shape == k.shape and k.is_contiguous() and v.is_contiguous()
         if q is not None:
@@ -205,7 +216,10 @@ class LolaLayer:
             tr = torch.empty((self.B, self.Hkv, nch, self.lam), dtype=torch.int32, device=self.device)
         trp = tr if (tr is not None and tr.numel()) else None
         with torch.cuda.device(self.device):
-            lola_prefill(self.cfg, self.st, q, k, v, Wq, Wk, T, out, trp, self._ws(T, q is not None, workspace_limit))
+            if noalloc:
+                lola_prefill_noalloc(self.cfg, self.st, q, k, v, Wq, Wk, T, out, trp)
+            else:
+                lola_prefill(self.cfg, self.st, q, k, v, Wq, Wk, T, out, trp, self._ws(T, q is not None, workspace_limit))
         return (out, tr) if trace else out
 
     def decode_step(self, q, k, v, Wq, Wk, out=None):

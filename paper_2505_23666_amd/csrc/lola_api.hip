@@ -9,6 +9,12 @@
 
 using namespace lola;
 
+// Scratch of lola_prefill_noalloc: one copy per GPU, held from the moment the library's code is loaded there until
+// the process ends.  In host code this name is only a handle for hipGetSymbolAddress; the device address is looked up
+// once per device (noalloc_scratch below) and that pointer is what kernels receive.
+#define LOLA_NOALLOC_SCRATCH_BYTES (64u << 20)
+static __device__ __align__(256) unsigned char scratch[LOLA_NOALLOC_SCRATCH_BYTES];
+
 namespace {
 
 constexpr size_t ALIGN = 256;
@@ -338,7 +344,7 @@ void launch_output_kernel(const lola_config *c, const generic::PrefillArgs<bf16_
 template <typename T>
 lola_status run_prefill(const lola_config *c, const lola_state *st, const void *q, const void *k, const void *v,
                         const void *Wq, const void *Wk, int32_t Tn, void *out, int32_t *sel_trace,
-                        void *workspace, size_t workspace_bytes, hipStream_t stream) {
+                        void *workspace, size_t workspace_bytes, hipStream_t stream, bool allow_side_stream = true) {
     generic::PrefillArgs<T> a;
     a.dm = make_dims(c);
     a.st = make_state<T>(st);
@@ -422,7 +428,7 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
                 const size_t work = (size_t)piece * a.dm.Hq * a.dm.B * (size_t)(c->head_dim / 64);
                 if ((size_t)np > work / OVERLAP_MIN_WORK) np = (int)(work / OVERLAP_MIN_WORK);
                 if (np > SideStream::NEV) np = SideStream::NEV;
-                if (c->prefill_overlap && a.want_out && ns <= OVERLAP_MAX_STREAMS && np >= 2) side = side_stream(stream);
+                if (allow_side_stream && c->prefill_overlap && a.want_out && ns <= OVERLAP_MAX_STREAMS && np >= 2) side = side_stream(stream);
                 std::unique_lock<std::mutex> side_lock(side_use_mu, std::defer_lock);
                 // Whatever happens after the first fork, the caller's stream waits for the second stream before this
                 // call returns (an error path included): declared after the lock, so it runs while the lock is held.
@@ -591,9 +597,30 @@ lola_status lola_state_flush(const lola_config *c, const lola_state *st, void *s
     return flush_pending(c, st, (hipStream_t)stream);
 }
 
-lola_status lola_prefill(const lola_config *c, const lola_state *st, const void *q, const void *k, const void *v,
-                         const void *Wq, const void *Wk, int32_t T, void *out, int32_t *sel_trace,
-                         void *workspace, size_t workspace_bytes, void *stream) {
+}  // extern "C"
+
+namespace {
+
+// device address of this GPU's copy of `scratch`, looked up on the first call on each device
+std::mutex noalloc_mu;
+void *noalloc_ptr[MAX_DEV];
+lola_status noalloc_scratch(void **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEV) { (void)hipGetLastError(); return LOLA_ERR_HIP; }
+    std::lock_guard<std::mutex> lock(noalloc_mu);
+    if (!noalloc_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) { (void)hipGetLastError(); return LOLA_ERR_HIP; }
+        noalloc_ptr[dev] = p;
+    }
+    *out = noalloc_ptr[dev];
+    return LOLA_OK;
+}
+
+// the two prefill entry points differ in where the workspace comes from and in whether the second stream may be used
+lola_status prefill_entry(const lola_config *c, const lola_state *st, const void *q, const void *k, const void *v,
+                          const void *Wq, const void *Wk, int32_t T, void *out, int32_t *sel_trace,
+                          void *workspace, size_t workspace_bytes, void *stream, bool noalloc) {
     lola_status rc = check_config(c);
     if (rc != LOLA_OK) return rc;
     rc = check_state(c, st);
@@ -603,19 +630,45 @@ lola_status lola_prefill(const lola_config *c, const lola_state *st, const void 
     if ((q == nullptr) != (out == nullptr)) return LOLA_ERR_NULL;
     if (!k || !v || !Wk || (q && !Wq)) return LOLA_ERR_NULL;
     if (!q && c->score_kind != LOLA_SCORE_SRE) return LOLA_ERR_UNSUPPORTED;   // these scores are sums over queries
-    const void *ps[] = {q, k, v, Wq, Wk, out, sel_trace, workspace};
+    const void *ps[] = {q, k, v, Wq, Wk, out, sel_trace, noalloc ? nullptr : workspace};
     for (const void *p : ps) if (p && misaligned(p)) return LOLA_ERR_ALIGN;
     size_t need_min = 0;
     lola_prefill_workspace_bytes(c, T, q != nullptr, &need_min);
-    if (!workspace || workspace_bytes < need_min) return LOLA_ERR_WORKSPACE;
-    rc = prefill_feasible(c, q != nullptr);
-    if (rc != LOLA_OK) return rc;
+    if (noalloc) {
+        if (need_min > LOLA_NOALLOC_SCRATCH_BYTES) return LOLA_ERR_TOO_LARGE;
+        rc = prefill_feasible(c, q != nullptr);
+        if (rc != LOLA_OK) return rc;
+        rc = noalloc_scratch(&workspace);
+        if (rc != LOLA_OK) return rc;
+        workspace_bytes = LOLA_NOALLOC_SCRATCH_BYTES;
+    } else {
+        if (!workspace || workspace_bytes < need_min) return LOLA_ERR_WORKSPACE;
+        rc = prefill_feasible(c, q != nullptr);
+        if (rc != LOLA_OK) return rc;
+    }
     rc = flush_pending(c, st, (hipStream_t)stream);   // the prefill kernels read H and s as they are in memory
     if (rc != LOLA_OK) return rc;
     if (c->dtype == LOLA_F32)
-        return run_prefill<float>(c, st, q, k, v, Wq, Wk, T, out, sel_trace, workspace, workspace_bytes, (hipStream_t)stream);
-    return run_prefill<bf16_t>(c, st, q, k, v, Wq, Wk, T, out, sel_trace, workspace, workspace_bytes, (hipStream_t)stream);
+        return run_prefill<float>(c, st, q, k, v, Wq, Wk, T, out, sel_trace, workspace, workspace_bytes, (hipStream_t)stream, !noalloc);
+    return run_prefill<bf16_t>(c, st, q, k, v, Wq, Wk, T, out, sel_trace, workspace, workspace_bytes, (hipStream_t)stream, !noalloc);
 }
+
+}  // namespace
+
+extern "C" {
+
+lola_status lola_prefill(const lola_config *c, const lola_state *st, const void *q, const void *k, const void *v,
+                         const void *Wq, const void *Wk, int32_t T, void *out, int32_t *sel_trace,
+                         void *workspace, size_t workspace_bytes, void *stream) {
+    return prefill_entry(c, st, q, k, v, Wq, Wk, T, out, sel_trace, workspace, workspace_bytes, stream, false);
+}
+
+lola_status lola_prefill_noalloc(const lola_config *c, const lola_state *st, const void *q, const void *k, const void *v,
+                                 const void *Wq, const void *Wk, int32_t T, void *out, int32_t *sel_trace, void *stream) {
+    return prefill_entry(c, st, q, k, v, Wq, Wk, T, out, sel_trace, nullptr, 0, stream, true);
+}
+
+size_t lola_noalloc_scratch_bytes(void) { return LOLA_NOALLOC_SCRATCH_BYTES; }
 
 lola_status lola_decode_step(const lola_config *c, const lola_state *st, const void *q, const void *k, const void *v,
                              const void *Wq, const void *Wk, void *out, void *stream) {
@@ -648,6 +701,7 @@ const char *lola_status_str(lola_status s) {
         case LOLA_ERR_UNSUPPORTED: return "no kernel for this configuration";
         case LOLA_ERR_WORKSPACE: return "workspace missing or too small";
         case LOLA_ERR_HIP: return "HIP launch failed";
+        case LOLA_ERR_TOO_LARGE: return "request exceeds the static scratch of the entry point that allocates nothing";
     }
     return "unknown status";
 }
