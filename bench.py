@@ -52,6 +52,18 @@ def decode_alg_bytes(sh, out_bytes):
     return per_stream, per_stream * sh.B * sh.Hkv + weights
 
 
+def decode_deferred_bytes(sh, out_bytes, R=8):
+    """Bytes per launch of the step as timed with deferred folds (fold_defer = R): H and s are written on one step in R,
+    the list of folded pairs (phi and v in fp32) is read every step (R / 2 + 1/2 pairs on average) and one pair is
+    appended; everything else as in decode_alg_bytes."""
+    per_stream, _ = decode_alg_bytes(sh, out_bytes)
+    d, D = sh.d, sh.D
+    pair = (D + d) * 4
+    per_stream += -(D * d * 4 + D * 4) + (D * d * 4 + D * 4) // R + pair * (R + 1) // 2 + pair
+    weights = (sh.Hq + sh.Hkv) * d * sh.m * 2
+    return per_stream, per_stream * sh.B * sh.Hkv + weights
+
+
 def prefill_alg_flops(sh):
     """Multiply-adds x 2 of one chunk of one stream in steady state, from the equations."""
     g, C_, d, D, m, lam, eta = sh.g, sh.C, sh.d, sh.D, sh.m, sh.lam, sh.eta
@@ -177,7 +189,10 @@ def main():
     t0 = time.time()
     layers = [lb.LolaLayer(sh.B, sh.Hq, sh.Hkv, sh.d, sh.D, sh.eta, sh.lam, sh.C, dtype="bf16", out_dtype="f32", device=dev,
                            fold_defer=args.fold_defer) for _ in range(L)]
-    n_tok = (K + W + L - 1) // L
+    # layer copy l takes l % 8 untimed steps first, so that the copies' lists of deferred folds have every length and
+    # one launch in eight of ANY timed window writes H back (all copies in step would hide the write-backs between windows)
+    stagger = 8 if args.fold_defer else 1
+    n_tok = (K + W + L - 1) // L + stagger
     qd = np.empty((n_tok, sh.B, sh.Hq, sh.d), np.float32)
     kd = np.empty((n_tok, sh.B, sh.Hkv, sh.d), np.float32)
     vd = np.empty((n_tok, sh.B, sh.Hkv, sh.d), np.float32)
@@ -218,11 +233,17 @@ def main():
     fn = lb.lib().lola_decode_step
     stream = C.c_void_p(torch.cuda.current_stream().cuda_stream)
     vp_ = lambda t: C.c_void_p(t.data_ptr())
-    calls = []
-    for i in range(K + W):
-        l, t = i % L, i // L
-        calls.append((C.byref(layers[l].cfg), C.byref(layers[l].st), vp_(dq[t]), vp_(dk[t]), vp_(dv[t]), vp_(dWq), vp_(dWk),
-                      vp_(outs[l]), stream))
+    mk_call = lambda l, t: (C.byref(layers[l].cfg), C.byref(layers[l].st), vp_(dq[t]), vp_(dk[t]), vp_(dv[t]), vp_(dWq), vp_(dWk),
+                            vp_(outs[l]), stream)
+    for l in range(L):
+        for t in range(l % stagger):
+            rc = fn(*mk_call(l, t))
+            assert rc == 0, rc
+    torch.cuda.synchronize()
+    if args.fold_defer:
+        listed = sorted(set(int(layers[l].pend_count[0, 0]) for l in range(L)))
+        log(f"[setup] lists of deferred folds at the start of the decode loop hold {listed} pairs over the {L} layer copies")
+    calls = [mk_call(i % L, (i % L) % stagger + i // L) for i in range(K + W)]
     def timed(cs, n_warm, n_timed):
         for i in range(n_warm):
             rc = fn(*cs[i])
@@ -272,16 +293,31 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    traffic = None
-    tfile = os.path.join(ROOT, "profiles", "decode_8b_b64_hbm_traffic.md")
-    if os.path.exists(tfile):
-        for line in open(tfile):
-            if line.startswith("traffic_bytes_per_launch:"):
-                traffic = float(line.split(":")[1])
+    def stored(fname, key):
+        """A figure kept in a committed rocprofv3 summary (counter runs are separate from this run)."""
+        path = os.path.join(ROOT, "profiles", fname)
+        if os.path.exists(path):
+            for line in open(path):
+                if line.startswith(key + ":"):
+                    return float(line.split(":")[1])
+        return None
+
+    traffic = stored("decode_8b_b64_hbm_traffic.md", "traffic_bytes_per_launch")
+    _, per_launch_timed = decode_deferred_bytes(sh, 4) if args.fold_defer else (per_stream, per_launch)
+    moved = per_launch_timed / (launch_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "traffic_source": "profiles/decode_8b_b64_hbm_traffic.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this "
+                                  "command, calibrated against a device copy; not a reading of this run)",
                 "kernel": lb.lola_kernel_path(layers[0].cfg, 1) + " decode", "launch_us": round(launch_us, 3),
-                "alg_bytes_per_launch": per_launch}
+                "alg_bytes_per_launch": per_launch,
+                "note": "achieved/frac divide the bytes of the method as written (H rewritten every step) by the measured launch time; "
+                        "the timed mode (fold_defer) moves fewer bytes: see timed_mode",
+                "timed_mode": {"fold_defer": args.fold_defer, "model_bytes_per_launch": per_launch_timed,
+                               "achieved": round(moved, 1), "frac": round(moved / HBM_PEAK_GBS, 4),
+                               "measured_traffic_frac": None if traffic is None else
+                               round(traffic / (launch_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)},
+                "target": {"frac": 0.60, "launch_us": round(per_launch / (0.6 * HBM_PEAK_GBS * 1e9) * 1e6, 2), "met": bool(achieved / HBM_PEAK_GBS >= 0.6)}}
 
     # ---- prefill leg (configuration 3) ----
     prefill = None
@@ -291,8 +327,9 @@ def main():
         del layers[1:], calls
         torch.cuda.empty_cache()
 
-        def prefill_leg(cid, label, reps=None):
-            """Times lola_prefill (with outputs) on one of the prefill configurations."""
+        def prefill_leg(cid, label, reps=None, cpu_sample=None):
+            """Times lola_prefill (with outputs) on one of the prefill configurations.  cpu_sample = (sequences, kv heads,
+            tokens): the part of the same workload the oracle is timed on."""
             sc = wl.CONFIGS[cid]
             Wq_, Wk_ = wl.weights(sc)
             q_, k_, v_, extra_ = wl.sequence_inputs(sc)
@@ -314,11 +351,38 @@ def main():
             ms = float(np.mean(times))
             _, flops = prefill_alg_flops(sc)
             tf = flops / (ms * 1e-3) / 1e12
+            # What bounds the call is the chunk recurrence: one workgroup (one compute unit) per stream evolves the memories
+            # chunk by chunk.  Beside the nominal fraction of the chip's MFMA peak: the fraction of the peak of the compute
+            # units the recurrence can occupy, and the time per chunk of the serial chain.
+            ns_, nch_ = sc.B * sc.Hkv, sc.T // sc.C
+            cus = min(256, ns_)
             res = {"workload": label,
                    "tokens_per_s_per_layer": round(sc.B * sc.T / (ms * 1e-3), 1), "ms_per_call": round(ms, 3),
                    "roofline": {"bound": "mfma", "achieved": round(tf, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                                "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 5), "traffic": None,
-                                "alg_flops_per_call": flops, "kernel": lb.lola_kernel_path(lay.cfg, 0) + " prefill"}}
+                                "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 5),
+                                "traffic": stored("prefill_8b_mfma_kernel_stats.md", f"traffic_bytes_per_call_cfg{cid}"),
+                                "traffic_source": "profiles/prefill_8b_mfma_kernel_stats.md (stored rocprofv3 --pmc figure, if any)",
+                                "alg_flops_per_call": flops, "alg_bytes_per_call": sc.B * sc.Hq * sc.T * sc.d * (2 + 4) + 2 * sc.B * sc.Hkv * sc.T * sc.d * 2,
+                                "kernel": lb.lola_kernel_path(lay.cfg, 0) + " prefill",
+                                "streams": ns_, "serial_chunks": nch_, "us_per_chunk_of_the_serial_chain": round(ms * 1e3 / nch_, 2),
+                                "frac_of_occupied_cus": round(tf / (MFMA_BF16_PEAK_TFLOPS * cus / 256), 5)}}
+            if cpu_sample is not None and not args.skip_cpu:
+                from oracle import lola_oracle as orc
+                bs, hs, Ts = cpu_sample
+                hq = [h_ * sc.g + r_ for h_ in hs for r_ in range(sc.g)]
+                o_ = orc.Oracle(len(bs), len(hq), len(hs), sc.d, sc.D, sc.eta, sc.lam, sc.C)
+                cut = lambda a, heads: np.ascontiguousarray(a[np.ix_(bs, heads)][:, :, :Ts])
+                t1 = time.perf_counter()
+                o_.prefill(cut(q_, hq), cut(k_, hs), cut(v_, hs), np.ascontiguousarray(Wq_[hq]), np.ascontiguousarray(Wk_[hs]))
+                dt = time.perf_counter() - t1
+                # tokens/s/layer of the whole layer (all kv heads): the sample's heads are this fraction of a layer
+                frac_layer = len(hs) / sc.Hkv
+                res["cpu_baseline"] = {"value": round(len(bs) * Ts * frac_layer / dt, 2), "unit": "tokens/s/layer",
+                                       "cores": orc.num_threads(), "kind": "oracle",
+                                       "sample": f"prefill with outputs of sequences {list(bs)}, kv heads {list(hs)}, first {Ts} of "
+                                                 f"{sc.T} tokens; {dt:.1f}s"}
+                log(f"[cpu] oracle on {label}: {res['cpu_baseline']['value']} tokens/s/layer on {res['cpu_baseline']['cores']} threads "
+                    f"({res['cpu_baseline']['sample']})")
             log(f"[prefill] {label}: {ms:.2f} ms per call, {res['tokens_per_s_per_layer'] / 1e6:.3f} M tokens/s/layer, "
                 f"{tf:.2f} TFLOP/s algorithmic")
             if extra_ and "planted_pos" in extra_:
@@ -332,9 +396,12 @@ def main():
                     f"{res['planted_positions_kept']:.3f} (mean over kv heads)")
             return res
 
-        prefill = prefill_leg(3, "configs[2]: 8B-shape prefill B=4 T=4096 eta=64 lambda=128 C=64 bf16")
-        prefill_1b = prefill_leg(2, "configs[1]: 1B-shape prefill B=1 T=4096 head_dim=64 eta=64 lambda=64 C=64 bf16")
-        prefill_64k = prefill_leg(5, "configs[4]: 8B-shape prefill B=1 T=65536 eta=64 lambda=256 C=64 bf16", reps=2)
+        prefill = prefill_leg(3, "configs[2]: 8B-shape prefill B=4 T=4096 eta=64 lambda=128 C=64 bf16",
+                              cpu_sample=([0, 1, 2, 3], list(range(8)), 4096))
+        prefill_1b = prefill_leg(2, "configs[1]: 1B-shape prefill B=1 T=4096 head_dim=64 eta=64 lambda=64 C=64 bf16",
+                                 cpu_sample=([0], list(range(8)), 4096))
+        prefill_64k = prefill_leg(5, "configs[4]: 8B-shape prefill B=1 T=65536 eta=64 lambda=256 C=64 bf16", reps=2,
+                                  cpu_sample=([0], [0, 3, 7], 65536))
 
     # ---- CPU baseline: the oracle on a sample of the same decode workload ----
     cpu = None

@@ -106,13 +106,13 @@ typedef struct {
      * rewriting H: the true state is
      *     H_true = H + sum_{p < pend_count} pend_v[p] pend_phi[p]^T   (in the H^T layout above),
      *     s_true = s + sum_{p < pend_count} pend_phi[p],
-     * and every entry point computes with H_true, s_true.  The generation step that finds R - 1
-     * pairs listed writes H_true, s_true (including its own fold) back and empties the list;
-     * lola_prefill and lola_state_flush do so on entry.  Read H or s directly only after
-     * lola_state_flush. */
+     * and every entry point computes with H_true, s_true.  The generation step that finds R pairs
+     * listed writes H_true, s_true back (without its own fold) and starts a new list with its own
+     * pair; lola_prefill and lola_state_flush write back and empty the list on entry.  Read H or s
+     * directly only after lola_state_flush. */
     float *pend_phi;     /* [B, Hkv, R, D]  phi(k) of the listed pairs, fp32 */
     float *pend_v;       /* [B, Hkv, R, d]  their values, fp32 */
-    int32_t *pend_count; /* [B, Hkv]        pairs listed, 0 .. R-1 */
+    int32_t *pend_count; /* [B, Hkv]        pairs listed, 0 .. R */
     /* Query-dependent scores (score_kind != LOLA_SCORE_SRE; NULL otherwise). */
     float *win_score;    /* [B, Hkv, eta]     sum gathered so far by the pair in each ring slot */
     float *sp_score;     /* [B, Hkv, lambda]  final sum of the pair in each sparse slot */

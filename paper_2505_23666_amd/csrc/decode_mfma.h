@@ -193,11 +193,12 @@ __device__ __forceinline__ void phi_from_z(const f32x4 zt[4], int phi_kind, floa
 //   the rest    small per-stream vectors.
 // H^T never goes through LDS: wavefront w owns its rows 32w .. 32w+31 (output columns of the recall GEMM).
 //
-// Deferred folds (R = 4): the state in memory lags behind by up to R - 1 folded pairs, which are kept as fp32 rows
+// Deferred folds (R = 8): the state in memory lags behind by up to R folded pairs, which are kept as fp32 rows
 // (phi, v) beside it.  A step adds them to its register copy of H^T with fp32 MFMAs (16x16x4: the contraction index
 // is the pending pair) and to s, so everything downstream sees the true state; its own fold is appended to the
-// list, and only the step that would make the list full writes H and s back.  Same sums as folding at once
-// (Sec. 2.2, eq. recurrent_update), three of four write-backs of H saved.
+// list.  The step that finds the list full writes H and s (with the R listed pairs, without its own) back and
+// starts a new list with its own pair.  Same sums as folding at once (Sec. 2.2, eq. recurrent_update), seven of
+// eight write-backs of H saved.
 // GDYN: the group size is read from the arguments (1 .. G) instead of being G; the benchmarked shape keeps the
 // compile-time form.
 // DH = head_dim: 128 (8B head shape) or 64 (1B head shape); with 64 a wavefront owns 16 rows of H^T instead of 32.
@@ -692,24 +693,30 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
             else if (tid < 2 * PR) reinterpret_cast<uint4 *>(sp_v + (size_t)drop * DH)[tid - PR] = reinterpret_cast<const uint4 *>(pvb)[tid - PR];
             else if (tid == 2 * PR) sp_idx[drop] = pidx;
         }
-        // fold: H^T += v_f phi_f^T on the fp32 registers, written back once; s += phi_f.  With deferred folds only
-        // the step that finds the list one short of full does so (its registers include the listed pairs); the others
-        // append their pair to the list.
-        const bool write_back = R == 0 || cnt == R - 1;
-        if (write_back) {
+        // fold: without deferred folds H^T += v_f phi_f^T on the fp32 registers, written back at once; s += phi_f.
+        // With deferred folds the pair is appended to the list; the step that finds the list full first writes its
+        // registers (H^T plus the listed pairs) and s back and then starts a new list with its own pair.
+        if (R == 0) {
 #define LOLA_HFOLD(ct, ks, hf) if (ct < NCT) { const float vc = vf[CW * w + 16 * ct + r16]; \
             const float4 pf = *reinterpret_cast<const float4 *>(&phif[32 * ks + 16 * hf + 4 * g4]); \
             hreg##ct##ks##hf.x = fmaf(pf.x, vc, hreg##ct##ks##hf.x); hreg##ct##ks##hf.y = fmaf(pf.y, vc, hreg##ct##ks##hf.y); \
             hreg##ct##ks##hf.z = fmaf(pf.z, vc, hreg##ct##ks##hf.z); hreg##ct##ks##hf.w = fmaf(pf.w, vc, hreg##ct##ks##hf.w); \
             *reinterpret_cast<float4 *>(Hg + LOLA_HADDR(ct, ks, hf)) = hreg##ct##ks##hf; }
-        LOLA_HREP(LOLA_HFOLD)
+            LOLA_HREP(LOLA_HFOLD)
 #undef LOLA_HFOLD
-        if (tid < D) sg[tid] = s_l[tid] + phif[tid];
-        if (R > 0 && tid == 0) a.pend_count[si] = 0;
+            if (tid < D) sg[tid] = s_l[tid] + phif[tid];
         } else {
-            if (tid < D) pphi[cnt * D + tid] = phif[tid];
-            else if (tid < D + DH) pval[cnt * DH + tid - D] = vf[tid - D];
-            if (tid == 0) a.pend_count[si] = cnt + 1;
+            const bool full = cnt == R;
+            if (full) {
+#define LOLA_HSTORE(ct, ks, hf) if (ct < NCT) *reinterpret_cast<float4 *>(Hg + LOLA_HADDR(ct, ks, hf)) = hreg##ct##ks##hf;
+                LOLA_HREP(LOLA_HSTORE)
+#undef LOLA_HSTORE
+                if (tid < D) sg[tid] = s_l[tid];
+            }
+            const int p_at = full ? 0 : cnt;
+            if (tid < D) pphi[p_at * D + tid] = phif[tid];
+            else if (tid < D + DH) pval[p_at * DH + tid - D] = vf[tid - D];
+            if (tid == 0) a.pend_count[si] = p_at + 1;
         }
         // phi(q) . phi_f for the rank-1 correction of the linear read-out
         for (int r = w; r < g; r += 4) {

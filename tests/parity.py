@@ -96,7 +96,7 @@ def gpu_state_np(layer: lb.LolaLayer, bsel=None, hsel=None) -> dict:
         phi = sel(layer.pend_phi).cpu().numpy().astype(np.float64)
         val = sel(layer.pend_v).cpu().numpy().astype(np.float64)
         cnt = sel(layer.pend_count).cpu().numpy()
-        assert cnt.min() >= 0 and cnt.max() < layer.fold_defer
+        assert cnt.min() >= 0 and cnt.max() <= layer.fold_defer
         live = (np.arange(layer.fold_defer)[None, None, :] < cnt[..., None]).astype(np.float64)
         phi = phi * live[..., None]
         out["H"] = out["H"].astype(np.float64) + np.einsum("bhpf,bhpc->bhfc", phi, val)

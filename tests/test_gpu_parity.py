@@ -135,6 +135,8 @@ def test_deferred_folds(lam, phi_kind):
     outputs every step, through cold start, a prefill call in between (which applies the list),
     more steps, and an explicit flush."""
     R = 8
+    listed = lambda n: n if n <= R else 1 + (n - 1) % R    # pairs listed after n steady steps: the step that finds R listed
+                                                           # writes them back and starts a new list with its own pair
     sh = wl.Shape("defer8b", "bf16", 2, 8, 2, 128, 128, T=0, eta=64, lam=lam, C=64, seed=0)
     n_pre = 64 * 2 + 17
     blocks = [64 + lam + 5, 3, 8, 6]           # steady steps so far: 5, 8, 16, 22
@@ -151,8 +153,7 @@ def test_deferred_folds(lam, phi_kind):
         steady = t0 - 64 - lam
         cnt = layer.pend_count.cpu().numpy()
         say("deferred folds", lam, phi_kind, "steps", t0, "listed", cnt.ravel().tolist(), rep)
-        assert (cnt == steady % R).all()
-    assert steady % R != 0
+        assert (cnt == listed(steady)).all()
     # a prefill call starts by applying the list; its own folds go to H directly
     layer, o, rep = P.prefill_parity(sh, q[:, :, t0:t0 + n_pre], k[:, :, t0:t0 + n_pre], v[:, :, t0:t0 + n_pre], Wq, Wk,
                                      layer=layer, oracle=o, layer_kw=kw)
@@ -160,7 +161,7 @@ def test_deferred_folds(lam, phi_kind):
     assert (layer.pend_count.cpu().numpy() == 0).all()
     say("deferred folds: prefill in between", rep)
     rep = P.decode_parity(sh, layer, o, *steps(q, k, v, t0, 11), Wq, Wk)
-    assert (layer.pend_count.cpu().numpy() == 11 % R).all()
+    assert (layer.pend_count.cpu().numpy() == listed(11)).all()
     # explicit flush: memory alone is the state
     layer.flush()
     torch.cuda.synchronize()
