@@ -467,15 +467,21 @@ def test_maximum_sizes_generic_family():
     say("max dims", rep, rep2)
 
 
-def test_paper_scale_cache_parameters():
-    """Cache parameters of the paper's long-context runs (window = sparse budget = 256, feature dimension 2 d): the
-    generic kernels, every output, state element and selection against the oracle."""
-    sh = wl.Shape("paperscale", "bf16", 1, 4, 1, 128, 256, T=64 * 14 + 9, eta=256, lam=256, C=64, seed=0)
-    q, k, v, Wq, Wk = rand_case(211, 1, 4, 1, 128, 256, sh.T + 3, "bf16")
-    layer, o, rep = P.prefill_parity(sh, q[:, :, :sh.T], k[:, :, :sh.T], v[:, :, :sh.T], Wq, Wk)
-    rep2 = P.decode_parity(sh, layer, o, *steps(q, k, v, sh.T, 3), Wq, Wk)
-    say("paper-scale cache", rep, rep2)
-    assert rep["scored"] > 0
+@pytest.mark.parametrize("eta,lam,chunk", [(256, 256, 64), (512, 512, 64), (128, 768, 64), (512, 1024, 128)],
+                         ids=["eta256_lam256", "eta512_lam512", "eta128_lam768", "eta512_lam1024"])
+def test_paper_scale_cache_parameters(eta, lam, chunk):
+    """Cache parameters of the paper's long-context runs (Sec. 4: the S-NIAH table's window = sparse budget = 256 and
+    512, the RULER setting window 128 / budget 768, the LongBench setting window 512 / budget 1024; feature dimension
+    2 d = 256, head_dim 128): a prefill with a ragged tail that runs well past the point where the cache is full,
+    then generation steps; every output, state element and selection against the oracle."""
+    n_full = (eta + lam) // chunk + 5              # chunks until the cache is full, then five scored selections
+    T = chunk * n_full + 9
+    sh = wl.Shape("paperscale", "bf16", 1, 4, 1, 128, 256, T=T, eta=eta, lam=lam, C=chunk, seed=0)
+    q, k, v, Wq, Wk = rand_case(211 + eta + lam, 1, 4, 1, 128, 256, T + 3, "bf16")
+    layer, o, rep = P.prefill_parity(sh, q[:, :, :T], k[:, :, :T], v[:, :, :T], Wq, Wk)
+    rep2 = P.decode_parity(sh, layer, o, *steps(q, k, v, T, 3), Wq, Wk)
+    say("paper-scale cache", eta, lam, chunk, layer.lola_path, rep, rep2)
+    assert rep["scored"] >= 5 and rep2["scored"] - rep["scored"] == 3
 
 
 def test_random_small_shapes():
