@@ -133,6 +133,8 @@ def extras(torch, wl, lb, dev):
     rows.append(run("long-context cache parameters eta=lambda=256, D=2d", eta=256, lam=256, **long))
     rows.append(run("long-context cache parameters eta=lambda=512, D=2d", eta=512, lam=512, **long))
     rows.append(run("long-context cache parameters eta=128, lambda=768, D=2d", eta=128, lam=768, **long))
+    rows.append(run("no sparse cache (sliding window + linear attention base model), window 64", B=4, Hq=32, Hkv=8, d=128, D=128, eta=64,
+                    lam=0, Cc=64, T=2048, n_dec=36))
     rows.append(run("no sparse cache, window 192 (ablation: extended window)", B=4, Hq=32, Hkv=8, d=128, D=128, eta=192, lam=0, Cc=64, T=2048, n_dec=36))
     # the shape of the paper's isolated layer-latency table (Sec. 5 "Efficiency Analysis": batch 2, 32 heads without grouping,
     # head_dim 128, T = 4096, eta = 64, lambda = 128) except for the feature dimension (128 here, 2 d there)

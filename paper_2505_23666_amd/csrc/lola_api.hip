@@ -172,7 +172,7 @@ lola_status decode_feasible(const lola_config *c) {
 // took them), the state-evolution kernel ranks by self-recall error only
 bool fast_output_ok(const lola_config *c) {
     return c->dtype == LOLA_BF16 && (c->head_dim == 128 || c->head_dim == 64) && c->feat_dim == 128 && c->window == 64 && c->chunk == 64 &&
-           (c->sparse_budget == 64 || c->sparse_budget == 128 || c->sparse_budget == 256);
+           (c->sparse_budget == 0 || c->sparse_budget == 64 || c->sparse_budget == 128 || c->sparse_budget == 256);
 }
 bool fast_attend_ok(const lola_config *c) { return fast_output_ok(c) && c->score_kind == LOLA_SCORE_SRE; }
 
@@ -336,7 +336,8 @@ void launch_output_kernel(const lola_config *c, const generic::PrefillArgs<bf16_
 #define LOLA_ATT2(LAMV, DHV) do { if (f32o) hipLaunchKernelGGL((fast::attend_fast_kernel<LAMV, DHV, float>), ga, dim3(256), 0, so, ao); \
                                   else hipLaunchKernelGGL((fast::attend_fast_kernel<LAMV, DHV, bf16_t>), ga, dim3(256), 0, so, ao); } while (0)
 #define LOLA_ATT(LAMV) do { if (c->head_dim == 128) LOLA_ATT2(LAMV, 128); else LOLA_ATT2(LAMV, 64); } while (0)
-    if (c->sparse_budget == 64) LOLA_ATT(64); else if (c->sparse_budget == 128) LOLA_ATT(128); else LOLA_ATT(256);
+    if (c->sparse_budget == 0) LOLA_ATT(0); else if (c->sparse_budget == 64) LOLA_ATT(64);
+    else if (c->sparse_budget == 128) LOLA_ATT(128); else LOLA_ATT(256);
 #undef LOLA_ATT
 #undef LOLA_ATT2
 }
@@ -411,6 +412,37 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
         a.jb = a.j0 = j0;
         a.j1 = jend;
         if constexpr (std::is_same<T, bf16_t>::value) {
+            if (fast_attend_ok(c) && c->sparse_budget == 0) {
+                // No sparse cache: nothing is scored, every pair that leaves the window is folded, and the recurrence splits
+                // over the value columns of H.  Features of the pass's keys (chunk-parallel); the generic kernel until the
+                // first regular chunk (a full chunk with a full window behind it); the row-split kernel over the full
+                // chunks; the generic kernel again for a ragged last chunk; the outputs from the snapshots.
+                const dim3 gp((unsigned)(jend - j0), (unsigned)ns);
+                if (c->head_dim == 128) hipLaunchKernelGGL(fast::phi_k_kernel<128>, gp, dim3(256), 0, stream, a);
+                else hipLaunchKernelGGL(fast::phi_k_kernel<64>, gp, dim3(256), 0, stream, a);
+                LAUNCH_CHECK();
+                a.scan_mode = 1;
+                hipLaunchKernelGGL((generic::scan_kernel<T>), gs, block, lds_scan, stream, a);
+                LAUNCH_CHECK();
+                const dim3 gn((unsigned)(c->head_dim / 16), (unsigned)ns);
+                if (c->head_dim == 128) hipLaunchKernelGGL(fast::scan_nocache_kernel<128>, gn, dim3(64), 0, stream, a);
+                else hipLaunchKernelGGL(fast::scan_nocache_kernel<64>, gn, dim3(64), 0, stream, a);
+                LAUNCH_CHECK();
+                const int full_end = jend < Tn / a.dm.C ? jend : Tn / a.dm.C;
+                hipLaunchKernelGGL(fast::advance_next_j_kernel, dim3((unsigned)((ns + 255) / 256)), dim3(256), 0, stream, a.next_j, (int)ns, full_end);
+                LAUNCH_CHECK();
+                if (jend == a.n_chunks && Tn % a.dm.C != 0) {
+                    a.scan_mode = 2;
+                    hipLaunchKernelGGL((generic::scan_kernel<T>), gs, block, lds_scan, stream, a);
+                    LAUNCH_CHECK();
+                }
+                a.scan_mode = 0;
+                if (a.want_out) {
+                    launch_output_kernel(c, a, j0, jend, stream);
+                    LAUNCH_CHECK();
+                }
+                continue;
+            }
             if (fast_attend_ok(c)) {   // same shape conditions as the output kernel
                 // features of the pass's keys (chunk-parallel); then the serial evolution in legs that hand the chunk
                 // position over in next_j: generic kernel until the first regular chunk, MFMA kernel over the regular

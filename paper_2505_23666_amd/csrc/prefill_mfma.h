@@ -977,5 +977,165 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
 #undef LOLA_SSTORE
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// State evolution of the prefill WITHOUT a sparse cache (sparse budget 0: the sliding-window + linear-attention
+// base model, paper appendix "Efficiency Analysis", the lambda = 0 case).  Nothing is scored, so every pair that
+// leaves the window is folded (Sec. 2.2 eq. recurrent_update): H at the entry of chunk j is a prefix sum over the
+// groups that left before it.  Without the selection nothing couples the value columns of H, so the recurrence is
+// split over them: grid (16-row tile of H^T, stream), ONE wavefront per workgroup (no barriers at all); head_dim / 16
+// times as many workgroups as streams evolve the state.  Per regular chunk (a full chunk with a full window behind it):
+//   1. snapshot of this tile's rows of H^T as bf16 high + low parts in the output kernel's operand order (and of s,
+//      by the workgroup of tile 0);
+//   2. H[f][c] += sum_t phi_t[f] v_t[c] over the 64 pairs that leave: both MFMA operands come out of row-major LDS
+//      tiles through the transposing LDS read (contraction index = the pair); the pairs' features are the chunk-parallel
+//      feature kernel's (copied into LDS by direct global -> LDS loads, one chunk ahead), their values this tile's
+//      16 columns of the rows.  s += sum_t phi_t rides along as a column of ones (tile 0 only).
+// Chunks whose leaving group was not covered by the feature kernel (the first chunk of a pass: the group lies in the
+// previous pass or in the window the call found) get their features computed here.
+// Feature order: the feature kernel stores a row in operand order (position p holds feature 32 (p/32) + 16 ((p%8)/4)
+// + 4 ((p/8)%4) + p%4); the accumulators are kept in plain feature order (lane (column c, group g) holds features
+// 16 mt + 4 g + i of tile mt), which makes the lane's registers exactly the snapshot's pieces; row 16 mt + r of the A
+// operand is therefore read from position 32 (mt/2) + 8 (r/4) + 4 (mt%2) + r%4.
+template <int DH>
+__global__ __launch_bounds__(64) void scan_nocache_kernel(generic::PrefillArgs<bf16_t> a) {
+    constexpr int M = 64, D = 128, C = 64, ETA = 64, KS = DH / 32, P = ETA, NMT = D / 16;
+    static_assert(DH == 64 || DH == 128, "head_dim");
+    __shared__ __attribute__((aligned(16))) uint16_t PHs[2][C * 2 * D];   // phi of a leaving group [pair][part][position], two buffers
+    __shared__ __attribute__((aligned(16))) uint16_t VS[2][2 * C * 8];    // their values at this tile's columns [half of 8][pair][8]
+    const int lane = threadIdx.x, r16 = lane & 15, g4 = lane >> 4;
+    const int ct = blockIdx.x, si = blockIdx.y, h = si % a.dm.Hkv;
+    float *Hg = a.st.H + (size_t)si * D * DH, *sg = a.st.s + (size_t)si * D;
+    const bf16_t *Wk = a.Wk + (size_t)h * M * DH;
+    const bf16_t *pK = a.prefK + (size_t)si * P * DH, *pV = a.prefV + (size_t)si * P * DH;
+    const bf16_t *kc = a.k + (size_t)si * a.T_tokens * DH, *vc = a.v + (size_t)si * a.T_tokens * DH;
+    const int j_first = a.next_j[si];
+    const int j_end = min(a.j1, a.T_tokens / C);      // the full chunks of this launch; regular once the first one is
+    if (j_first >= j_end) return;
+    const bool tile0 = ct == 0;
+
+    // this tile's rows of H^T: acc[mt][i] = H^T[16 ct + r16][16 mt + 4 g4 + i]; s likewise in column 0's lanes
+    f32x4 acc[NMT], sacc[NMT];
+#pragma unroll
+    for (int mt = 0; mt < NMT; mt++) {
+        acc[mt] = *reinterpret_cast<const f32x4 *>(Hg + (size_t)(16 * ct + r16) * D + 16 * mt + 4 * g4);
+        sacc[mt] = tile0 ? *reinterpret_cast<const f32x4 *>(sg + 16 * mt + 4 * g4) : (f32x4){0.f, 0.f, 0.f, 0.f};
+    }
+    const uint32_t one2 = 0x3F803F80u;   // two bf16 ones
+    const bf16x8 Bones = as_bf16x8(make_uint4(one2, one2, one2, one2));
+
+    // rows of the group that leaves after chunk j: virtual rows j C + e, e < 64 (rows below P are the window the call found)
+    auto krow = [&](int j, int e) { const int vr = j * C + e; return vr < P ? pK + (size_t)vr * DH : kc + (size_t)(vr - P) * DH; };
+    auto vrow = [&](int j, int e) { const int vr = j * C + e; return vr < P ? pV + (size_t)vr * DH : vc + (size_t)(vr - P) * DH; };
+    // requests for chunk j's leaving group into buffer `buf`
+    auto fetch = [&](int j, int buf) {
+        // values: 32 bytes per pair (this tile's 16 columns), lane = pair, one instruction per half
+#pragma unroll
+        for (int x = 0; x < 2; x++)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(vrow(j, lane) + 16 * ct + 8 * x),
+                                             (__attribute__((address_space(3))) void *)&VS[buf][x * C * 8], 16, 0, 0);
+        if (j - 1 >= a.jb) {
+            // the feature kernel's rows of chunk j - 1: 32 KB, copied as they are
+            const uint16_t *src = a.phiK + ((size_t)si * a.S + (j - 1 - a.jb)) * C * 2 * D;
+#pragma unroll 8
+            for (int i = 0; i < C * 2 * D / 512; i++)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + (i * 64 + lane) * 8),
+                                                 (__attribute__((address_space(3))) void *)&PHs[buf][i * 512], 16, 0, 0);
+        } else {
+            // not covered by the feature kernel: phi of the 64 keys here (Sec. 2.3 eq. feature_map), four tiles of 16
+#pragma unroll 1
+            for (int t4 = 0; t4 < 4; t4++) {
+                const int row = 16 * t4 + r16;
+                const bf16_t *kr = krow(j, row);
+                bf16x8 BK[KS];
+#pragma unroll
+                for (int ks = 0; ks < KS; ks++) BK[ks] = ld_bf16x8(kr + 32 * ks + 8 * g4);
+                f32x4 zt[4];
+#pragma unroll
+                for (int mt = 0; mt < 4; mt++) {
+                    zt[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int ks = 0; ks < KS; ks++)
+                        zt[mt] = mfma16(ld_bf16x8(Wk + (size_t)(16 * mt + r16) * DH + 32 * ks + 8 * g4), BK[ks], zt[mt]);
+                }
+                float pp[16], pn[16];
+                phi_from_z(zt, a.dm.phi_kind, pp, pn);
+                bf16x8 hi[4], lo[4];
+                split8(&pp[0], hi[0], lo[0]); split8(&pp[8], hi[1], lo[1]);
+                split8(&pn[0], hi[2], lo[2]); split8(&pn[8], hi[3], lo[3]);
+                uint16_t *dst = &PHs[buf][row * 2 * D];
+#pragma unroll
+                for (int ks = 0; ks < 4; ks++) {
+                    *reinterpret_cast<uint4 *>(dst + ((4 * ks + g4) << 3)) = __builtin_bit_cast(uint4, hi[ks]);
+                    *reinterpret_cast<uint4 *>(dst + D + ((4 * ks + g4) << 3)) = __builtin_bit_cast(uint4, lo[ks]);
+                }
+            }
+        }
+    };
+
+    fetch(j_first, j_first & 1);
+    for (int j = j_first; j < j_end; j++) {
+        const int buf = j & 1;
+        // ---- 1. snapshot of the state at the chunk's entry
+        if (a.want_out) {
+            const size_t sj = (size_t)si * a.S + (j - a.jb);
+            uint4 *Hs = reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(a.snapH) + sj * (2 * DH * D));
+#pragma unroll
+            for (int ks = 0; ks < 4; ks++) {
+                const float x8[8] = {acc[2 * ks][0], acc[2 * ks][1], acc[2 * ks][2], acc[2 * ks][3],
+                                     acc[2 * ks + 1][0], acc[2 * ks + 1][1], acc[2 * ks + 1][2], acc[2 * ks + 1][3]};
+                bf16x8 hi, lo;
+                split8(x8, hi, lo);
+                Hs[ct * 256 + ks * 64 + lane] = __builtin_bit_cast(uint4, hi);                 // [part][row tile][k-step][lane]
+                Hs[DH * 16 + ct * 256 + ks * 64 + lane] = __builtin_bit_cast(uint4, lo);
+            }
+            if (tile0 && r16 == 0) {
+#pragma unroll
+                for (int mt = 0; mt < NMT; mt++) *reinterpret_cast<f32x4 *>(a.snapS + sj * D + 16 * mt + 4 * g4) = sacc[mt];
+            }
+        }
+        // ---- the leaving group's rows have landed (direct loads have no register to wait on); then the next group is
+        // requested into the other buffer, whose last reads were the previous chunk's
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+        asm volatile("" ::: "memory");
+        if (j + 1 < j_end) fetch(j + 1, buf ^ 1);
+        // ---- 2. fold.  Contraction slots of lane group g4 in k-step kst: pairs 32 kst + 4 g4 + 0..3, then + 16 (the
+        // order in which the transposing read delivers them, the same for both operands)
+#pragma unroll
+        for (int kst = 0; kst < 2; kst++) {
+            const int t0 = 32 * kst + 4 * g4 + (r16 >> 2);
+            // B: values, column c = 16 ct + r16; lane i of a group points at pair t0's 4 columns 4 (i % 4) ..
+            const uint16_t *vb = &VS[buf][((r16 & 3) >> 1) * C * 8 + 4 * (r16 & 1)];
+            const bf16x4 b0 = tr_read(vb + t0 * 8), b1 = tr_read(vb + (t0 + 16) * 8);
+            const bf16x8 Bv = __builtin_shufflevector(b0, b1, 0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+            for (int mt = 0; mt < NMT; mt++) {
+                // A: phi^T, row f = 16 mt + r of the tile from position 32 (mt / 2) + 8 (r / 4) + 4 (mt % 2) + r % 4
+                const int pos = 32 * (mt >> 1) + 8 * (r16 & 3) + 4 * (mt & 1);
+#pragma unroll
+                for (int part = 0; part < 2; part++) {
+                    const uint16_t *pa = &PHs[buf][part * D + pos];
+                    const bf16x4 a0 = tr_read(pa + t0 * 2 * D), a1 = tr_read(pa + (t0 + 16) * 2 * D);
+                    const bf16x8 Av = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
+                    acc[mt] = mfma16(Av, Bv, acc[mt]);
+                    if (tile0) sacc[mt] = mfma16(Av, Bones, sacc[mt]);
+                }
+            }
+        }
+    }
+    // ---- the state after the last full chunk goes back to memory
+#pragma unroll
+    for (int mt = 0; mt < NMT; mt++) {
+        *reinterpret_cast<f32x4 *>(Hg + (size_t)(16 * ct + r16) * D + 16 * mt + 4 * g4) = acc[mt];
+        if (tile0 && r16 == 0) *reinterpret_cast<f32x4 *>(sg + 16 * mt + 4 * g4) = sacc[mt];
+    }
+}
+
+// after scan_nocache_kernel: the chunk position of every stream moves behind the full chunks of the launch
+__global__ void advance_next_j_kernel(int32_t *next_j, int ns, int j_end) {
+    const int si = blockIdx.x * blockDim.x + threadIdx.x;
+    if (si < ns && next_j[si] < j_end) next_j[si] = j_end;
+}
+
 }  // namespace fast
 }  // namespace lola

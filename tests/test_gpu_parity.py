@@ -484,6 +484,30 @@ def test_paper_scale_cache_parameters(eta, lam, chunk):
     assert rep["scored"] >= 5 and rep2["scored"] - rep["scored"] == 3
 
 
+@pytest.mark.parametrize("d,g,phi_kind", [(128, 4, 0), (64, 4, 0), (128, 2, 1)])
+def test_no_sparse_cache_on_the_mfma_prefill_kernels(d, g, phi_kind):
+    """Sparse budget 0 (the sliding-window + linear-attention base model, appendix "Efficiency Analysis") at the MFMA
+    shapes: the state evolution runs split over the value columns of H (scan_nocache_kernel).  Three calls on one
+    state: from empty memories with a ragged tail, a resumed call that starts mid-chunk (generic kernels take the
+    irregular chunks) and a long one processed in several workspace passes; then generation steps (generic kernel)."""
+    sh = wl.Shape("nocache", "bf16", 2, 2 * g, 2, d, 128, T=0, eta=64, lam=0, C=64, seed=0)
+    cuts = [0, 64 * 5 + 23, 64 * 5 + 23 + 64 * 3, 64 * 5 + 23 + 64 * 3 + 64 * 11 + 7]
+    nd = 5
+    q, k, v, Wq, Wk = rand_case(300 + d + g, 2, 2 * g, 2, d, 128, cuts[-1] + nd, "bf16", wscale=0.5 if phi_kind else 1.0)
+    kw = dict(phi_kind=phi_kind)
+    layer, o = None, None
+    for i in range(3):
+        a, b = cuts[i], cuts[i + 1]
+        layer, o, rep = P.prefill_parity(sh, q[:, :, a:b], k[:, :, a:b], v[:, :, a:b], Wq, Wk, layer=layer, oracle=o, layer_kw=kw,
+                                         workspace_limit=0 if i == 2 else None)
+        assert layer.lola_path[0] == "mfma"
+        say("no sparse cache, call", i, rep)
+    # an update-only call, then generation steps
+    a = cuts[3]
+    rep2 = P.decode_parity(sh, layer, o, *steps(q, k, v, a, nd), Wq, Wk)
+    say("no sparse cache, generation steps", rep2)
+
+
 def test_random_small_shapes():
     """Twenty seeded random shapes (both storage types, both feature maps, odd chunk / window / budget
     combinations, ragged lengths, GQA groups 1..4): prefill in two calls, then generation steps."""
