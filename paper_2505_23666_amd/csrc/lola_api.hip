@@ -424,7 +424,7 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
                 a.scan_mode = 1;
                 hipLaunchKernelGGL((generic::scan_kernel<T>), gs, block, lds_scan, stream, a);
                 LAUNCH_CHECK();
-                const dim3 gn((unsigned)(c->head_dim / 16), (unsigned)ns);
+                const dim3 gn((unsigned)(c->head_dim / 16 + 1), (unsigned)ns);   // row tiles of H^T, then s
                 if (c->head_dim == 128) hipLaunchKernelGGL(fast::scan_nocache_kernel<128>, gn, dim3(64), 0, stream, a);
                 else hipLaunchKernelGGL(fast::scan_nocache_kernel<64>, gn, dim3(64), 0, stream, a);
                 LAUNCH_CHECK();

@@ -990,7 +990,8 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
 //   2. H[f][c] += sum_t phi_t[f] v_t[c] over the 64 pairs that leave: both MFMA operands come out of row-major LDS
 //      tiles through the transposing LDS read (contraction index = the pair); the pairs' features are the chunk-parallel
 //      feature kernel's (copied into LDS by direct global -> LDS loads, one chunk ahead), their values this tile's
-//      16 columns of the rows.  s += sum_t phi_t rides along as a column of ones (tile 0 only).
+//      16 columns of the rows.  s += sum_t phi_t is the same product with a column of ones in place of the values: one
+//      more workgroup per stream (block index head_dim / 16) evolves s that way.
 // Chunks whose leaving group was not covered by the feature kernel (the first chunk of a pass: the group lies in the
 // previous pass or in the window the call found) get their features computed here.
 // Feature order: the feature kernel stores a row in operand order (position p holds feature 32 (p/32) + 16 ((p%8)/4)
@@ -1005,6 +1006,9 @@ __global__ __launch_bounds__(64) void scan_nocache_kernel(generic::PrefillArgs<b
     __shared__ __attribute__((aligned(16))) uint16_t VS[2][2 * C * 8];    // their values at this tile's columns [half of 8][pair][8]
     const int lane = threadIdx.x, r16 = lane & 15, g4 = lane >> 4;
     const int ct = blockIdx.x, si = blockIdx.y, h = si % a.dm.Hkv;
+    // The workgroup past the last row tile evolves s instead of rows of H^T: its "values" are a column of ones, everything
+    // else is the same code (the role is decided outside the MFMA loops).
+    const bool s_role = ct == DH / 16;
     float *Hg = a.st.H + (size_t)si * D * DH, *sg = a.st.s + (size_t)si * D;
     const bf16_t *Wk = a.Wk + (size_t)h * M * DH;
     const bf16_t *pK = a.prefK + (size_t)si * P * DH, *pV = a.prefV + (size_t)si * P * DH;
@@ -1012,15 +1016,12 @@ __global__ __launch_bounds__(64) void scan_nocache_kernel(generic::PrefillArgs<b
     const int j_first = a.next_j[si];
     const int j_end = min(a.j1, a.T_tokens / C);      // the full chunks of this launch; regular once the first one is
     if (j_first >= j_end) return;
-    const bool tile0 = ct == 0;
 
-    // this tile's rows of H^T: acc[mt][i] = H^T[16 ct + r16][16 mt + 4 g4 + i]; s likewise in column 0's lanes
-    f32x4 acc[NMT], sacc[NMT];
+    // this tile's rows of H^T: acc[mt][i] = H^T[16 ct + r16][16 mt + 4 g4 + i]  (s role: s[16 mt + 4 g4 + i] in every column)
+    float *row_mem = s_role ? sg : Hg + (size_t)(16 * ct + r16) * D;
+    f32x4 acc[NMT];
 #pragma unroll
-    for (int mt = 0; mt < NMT; mt++) {
-        acc[mt] = *reinterpret_cast<const f32x4 *>(Hg + (size_t)(16 * ct + r16) * D + 16 * mt + 4 * g4);
-        sacc[mt] = tile0 ? *reinterpret_cast<const f32x4 *>(sg + 16 * mt + 4 * g4) : (f32x4){0.f, 0.f, 0.f, 0.f};
-    }
+    for (int mt = 0; mt < NMT; mt++) acc[mt] = *reinterpret_cast<const f32x4 *>(row_mem + 16 * mt + 4 * g4);
     const uint32_t one2 = 0x3F803F80u;   // two bf16 ones
     const bf16x8 Bones = as_bf16x8(make_uint4(one2, one2, one2, one2));
 
@@ -1030,17 +1031,24 @@ __global__ __launch_bounds__(64) void scan_nocache_kernel(generic::PrefillArgs<b
     // requests for chunk j's leaving group into buffer `buf`
     auto fetch = [&](int j, int buf) {
         // values: 32 bytes per pair (this tile's 16 columns), lane = pair, one instruction per half
+        if (!s_role) {
 #pragma unroll
-        for (int x = 0; x < 2; x++)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(vrow(j, lane) + 16 * ct + 8 * x),
-                                             (__attribute__((address_space(3))) void *)&VS[buf][x * C * 8], 16, 0, 0);
+            for (int x = 0; x < 2; x++)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(vrow(j, lane) + 16 * ct + 8 * x),
+                                                 (__attribute__((address_space(3))) void *)&VS[buf][x * C * 8], 16, 0, 0);
+        }
         if (j - 1 >= a.jb) {
-            // the feature kernel's rows of chunk j - 1: 32 KB, copied as they are
+            // the feature kernel's rows of chunk j - 1: 32 KB.  An instruction fills 1 KB = two rows; lane l fills part
+            // (l / 16) % 2 of row 2 i + l / 32 at 16-byte position l % 16, which holds the row's piece (l % 16) ^ (row % 16):
+            // sixteen rows read at once then hit different banks
             const uint16_t *src = a.phiK + ((size_t)si * a.S + (j - 1 - a.jb)) * C * 2 * D;
 #pragma unroll 8
-            for (int i = 0; i < C * 2 * D / 512; i++)
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + (i * 64 + lane) * 8),
+            for (int i = 0; i < C * 2 * D / 512; i++) {
+                const int row = 2 * i + (lane >> 5);
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)
+                                                     (src + row * 2 * D + ((lane >> 4) & 1) * D + (((lane & 15) ^ (row & 15)) << 3)),
                                                  (__attribute__((address_space(3))) void *)&PHs[buf][i * 512], 16, 0, 0);
+            }
         } else {
             // not covered by the feature kernel: phi of the 64 keys here (Sec. 2.3 eq. feature_map), four tiles of 16
 #pragma unroll 1
@@ -1066,8 +1074,8 @@ __global__ __launch_bounds__(64) void scan_nocache_kernel(generic::PrefillArgs<b
                 uint16_t *dst = &PHs[buf][row * 2 * D];
 #pragma unroll
                 for (int ks = 0; ks < 4; ks++) {
-                    *reinterpret_cast<uint4 *>(dst + ((4 * ks + g4) << 3)) = __builtin_bit_cast(uint4, hi[ks]);
-                    *reinterpret_cast<uint4 *>(dst + D + ((4 * ks + g4) << 3)) = __builtin_bit_cast(uint4, lo[ks]);
+                    *reinterpret_cast<uint4 *>(dst + (((4 * ks + g4) ^ (row & 15)) << 3)) = __builtin_bit_cast(uint4, hi[ks]);
+                    *reinterpret_cast<uint4 *>(dst + D + (((4 * ks + g4) ^ (row & 15)) << 3)) = __builtin_bit_cast(uint4, lo[ks]);
                 }
             }
         }
@@ -1076,22 +1084,25 @@ __global__ __launch_bounds__(64) void scan_nocache_kernel(generic::PrefillArgs<b
     fetch(j_first, j_first & 1);
     for (int j = j_first; j < j_end; j++) {
         const int buf = j & 1;
-        // ---- 1. snapshot of the state at the chunk's entry
+        // ---- 1. snapshot of the state at the chunk's entry (stores; the loads they follow complete first)
         if (a.want_out) {
             const size_t sj = (size_t)si * a.S + (j - a.jb);
-            uint4 *Hs = reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(a.snapH) + sj * (2 * DH * D));
+            if (s_role) {
+                if (r16 == 0) {
 #pragma unroll
-            for (int ks = 0; ks < 4; ks++) {
-                const float x8[8] = {acc[2 * ks][0], acc[2 * ks][1], acc[2 * ks][2], acc[2 * ks][3],
-                                     acc[2 * ks + 1][0], acc[2 * ks + 1][1], acc[2 * ks + 1][2], acc[2 * ks + 1][3]};
-                bf16x8 hi, lo;
-                split8(x8, hi, lo);
-                Hs[ct * 256 + ks * 64 + lane] = __builtin_bit_cast(uint4, hi);                 // [part][row tile][k-step][lane]
-                Hs[DH * 16 + ct * 256 + ks * 64 + lane] = __builtin_bit_cast(uint4, lo);
-            }
-            if (tile0 && r16 == 0) {
+                    for (int mt = 0; mt < NMT; mt++) *reinterpret_cast<f32x4 *>(a.snapS + sj * D + 16 * mt + 4 * g4) = acc[mt];
+                }
+            } else {
+                uint4 *Hs = reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(a.snapH) + sj * (2 * DH * D));
 #pragma unroll
-                for (int mt = 0; mt < NMT; mt++) *reinterpret_cast<f32x4 *>(a.snapS + sj * D + 16 * mt + 4 * g4) = sacc[mt];
+                for (int ks = 0; ks < 4; ks++) {
+                    const float x8[8] = {acc[2 * ks][0], acc[2 * ks][1], acc[2 * ks][2], acc[2 * ks][3],
+                                         acc[2 * ks + 1][0], acc[2 * ks + 1][1], acc[2 * ks + 1][2], acc[2 * ks + 1][3]};
+                    bf16x8 hi, lo;
+                    split8(x8, hi, lo);
+                    Hs[ct * 256 + ks * 64 + lane] = __builtin_bit_cast(uint4, hi);                 // [part][row tile][k-step][lane]
+                    Hs[DH * 16 + ct * 256 + ks * 64 + lane] = __builtin_bit_cast(uint4, lo);
+                }
             }
         }
         // ---- the leaving group's rows have landed (direct loads have no register to wait on); then the next group is
@@ -1103,31 +1114,33 @@ __global__ __launch_bounds__(64) void scan_nocache_kernel(generic::PrefillArgs<b
         // order in which the transposing read delivers them, the same for both operands)
 #pragma unroll
         for (int kst = 0; kst < 2; kst++) {
-            const int t0 = 32 * kst + 4 * g4 + (r16 >> 2);
+            const int t0 = 32 * kst + 4 * g4 + (r16 >> 2), t15 = t0 & 15;
             // B: values, column c = 16 ct + r16; lane i of a group points at pair t0's 4 columns 4 (i % 4) ..
-            const uint16_t *vb = &VS[buf][((r16 & 3) >> 1) * C * 8 + 4 * (r16 & 1)];
-            const bf16x4 b0 = tr_read(vb + t0 * 8), b1 = tr_read(vb + (t0 + 16) * 8);
-            const bf16x8 Bv = __builtin_shufflevector(b0, b1, 0, 1, 2, 3, 4, 5, 6, 7);
+            bf16x8 Bv = Bones;
+            if (!s_role) {
+                const uint16_t *vb = &VS[buf][((r16 & 3) >> 1) * C * 8 + 4 * (r16 & 1)];
+                const bf16x4 b0 = tr_read(vb + t0 * 8), b1 = tr_read(vb + (t0 + 16) * 8);
+                Bv = __builtin_shufflevector(b0, b1, 0, 1, 2, 3, 4, 5, 6, 7);
+            }
 #pragma unroll
             for (int mt = 0; mt < NMT; mt++) {
-                // A: phi^T, row f = 16 mt + r of the tile from position 32 (mt / 2) + 8 (r / 4) + 4 (mt % 2) + r % 4
-                const int pos = 32 * (mt >> 1) + 8 * (r16 & 3) + 4 * (mt & 1);
+                // A: phi^T, row f = 16 mt + r of the tile from position 32 (mt / 2) + 8 (r / 4) + 4 (mt % 2) + r % 4, i.e.
+                // 16-byte piece 4 (mt / 2) + r / 4 of the row (stored at that piece ^ pair % 16), its half mt % 2
+                const int off = (((4 * (mt >> 1) + (r16 & 3)) ^ t15) << 3) + 4 * (mt & 1);
 #pragma unroll
                 for (int part = 0; part < 2; part++) {
-                    const uint16_t *pa = &PHs[buf][part * D + pos];
+                    const uint16_t *pa = &PHs[buf][part * D + off];
                     const bf16x4 a0 = tr_read(pa + t0 * 2 * D), a1 = tr_read(pa + (t0 + 16) * 2 * D);
                     const bf16x8 Av = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
                     acc[mt] = mfma16(Av, Bv, acc[mt]);
-                    if (tile0) sacc[mt] = mfma16(Av, Bones, sacc[mt]);
                 }
             }
         }
     }
     // ---- the state after the last full chunk goes back to memory
+    if (!s_role || r16 == 0) {
 #pragma unroll
-    for (int mt = 0; mt < NMT; mt++) {
-        *reinterpret_cast<f32x4 *>(Hg + (size_t)(16 * ct + r16) * D + 16 * mt + 4 * g4) = acc[mt];
-        if (tile0 && r16 == 0) *reinterpret_cast<f32x4 *>(sg + 16 * mt + 4 * g4) = sacc[mt];
+        for (int mt = 0; mt < NMT; mt++) *reinterpret_cast<f32x4 *>(row_mem + 16 * mt + 4 * g4) = acc[mt];
     }
 }
 
