@@ -215,8 +215,9 @@ void lola_release_streams(void);
 /* Human-readable name of a status code (host string, never NULL). */
 const char *lola_status_str(lola_status s);
 
-/* Name of the kernel family the given call would use ("generic", "mfma"); host string.
- * which: 0 = lola_prefill, 1 = lola_decode_step. */
+/* Name of the kernel family the given call would use; host string.  "mfma": every kernel of the call is an
+ * MFMA kernel; "mixed" (lola_prefill only): the state evolution runs on the shape-generic kernel, the outputs on an
+ * MFMA kernel; "generic": shape-generic kernels.  which: 0 = lola_prefill, 1 = lola_decode_step. */
 const char *lola_kernel_path(const lola_config *cfg, int32_t which);
 
 #ifdef __cplusplus

@@ -581,7 +581,7 @@ struct PrefillArgs {
     int32_t *sel_trace;       // [B*Hkv][n_chunks][lam] or NULL
     int R;                    // rows per scoring tile
     int QT;                   // queries per attend tile
-    int snap_split;           // 1: H snapshots are written as bf16 high + low parts in MFMA operand order (D = d = 128)
+    int snap_split;           // 1: H snapshots are written as bf16 high + low parts in MFMA operand order (D a multiple of 32)
     uint16_t *phiK;           // [B*Hkv][S][C][2][D] phi of the pass's keys, bf16 high + low parts (MFMA state-evolution kernel only)
     int scan_mode;            // scan_kernel: 0 all chunks of the launch; bit 0: stop at the first regular chunk (a full chunk with
                               // a full window behind it and a full cache: the MFMA kernel's case) and note it in next_j; bit 1:
@@ -757,11 +757,12 @@ __device__ void scan_chunk(const PrefillArgs<T> &a, const int si, const int j, i
             int32_t *sG = a.snapG + sj * lam;
             if (a.snap_split) {
                 // feature f sits in 16-byte piece (f/32)*4 + (f/4)%4, element 4*((f/16)%2) + f%4 of its row; pieces are
-                // ordered [part][row block of 32][row tile of 16][piece / 4][16 (piece % 4) + row % 16] (the order in
+                // ordered [part][row tile of 16][k-step = piece / 4][16 (piece % 4) + row % 16] (the order in
                 // which the MFMA kernels hold them, one contiguous 1 KB per wavefront store)
                 uint16_t *s16 = reinterpret_cast<uint16_t *>(sH);
+                const int ppr = D / 8, ksd = D / 32;            // 16-byte pieces per row, k-steps of 32 features
                 for (int pi = tid; pi < D * d / 8; pi += NT) {   // one 16-byte piece (8 features of one row) per step
-                    const int c = pi >> 4, piece = pi & 15;
+                    const int c = pi / ppr, piece = pi % ppr;
                     const float *src = H + (size_t)c * D + 32 * (piece >> 2) + 4 * (piece & 3);
                     const float4 lo4 = *reinterpret_cast<const float4 *>(src), hi4 = *reinterpret_cast<const float4 *>(src + 16);
                     const float x[8] = {lo4.x, lo4.y, lo4.z, lo4.w, hi4.x, hi4.y, hi4.z, hi4.w};
@@ -773,7 +774,7 @@ __device__ void scan_chunk(const PrefillArgs<T> &a, const int si, const int j, i
                         ph[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
                         pl[e] = (uint32_t)f32_to_bf16_bits(r0) | ((uint32_t)f32_to_bf16_bits(r1) << 16);
                     }
-                    const int pos = (((((c >> 5) * 2 + ((c >> 4) & 1)) * 4 + (piece >> 2)) * 64) + 16 * (piece & 3) + (c & 15)) << 3;
+                    const int pos = ((((c >> 4) * ksd + (piece >> 2)) * 64) + 16 * (piece & 3) + (c & 15)) << 3;
                     *reinterpret_cast<uint4 *>(s16 + pos) = make_uint4(ph[0], ph[1], ph[2], ph[3]);
                     *reinterpret_cast<uint4 *>(s16 + D * d + pos) = make_uint4(pl[0], pl[1], pl[2], pl[3]);
                 }

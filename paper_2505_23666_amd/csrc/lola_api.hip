@@ -175,6 +175,11 @@ bool fast_output_ok(const lola_config *c) {
            (c->sparse_budget == 0 || c->sparse_budget == 64 || c->sparse_budget == 128 || c->sparse_budget == 256);
 }
 bool fast_attend_ok(const lola_config *c) { return fast_output_ok(c) && c->score_kind == LOLA_SCORE_SRE; }
+// shapes of the MFMA output kernel with run-time window and sparse budget (any score kind: its inputs are the snapshots)
+bool wide_output_ok(const lola_config *c) {
+    return c->dtype == LOLA_BF16 && (c->head_dim == 128 || c->head_dim == 64) && (c->feat_dim == 128 || c->feat_dim == 256) &&
+           c->chunk == 64 && c->sparse_budget <= 1024;
+}
 
 struct PrefillPlan {
     size_t off_prefK, off_prefV, off_sp_row, off_phiE, off_next, off_score, off_snap;   // byte offsets
@@ -387,7 +392,8 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
     a.R = score_tile_rows(a.dm, scan_fixed);
     a.QT = attend_tile_queries(a.dm);
     const bool fast_att = a.want_out && fast_output_ok(c);
-    a.snap_split = fast_att ? 1 : 0;
+    const bool wide_att = a.want_out && !fast_att && wide_output_ok(c);
+    a.snap_split = (fast_att || wide_att) ? 1 : 0;
     if (a.R <= 0 || (a.want_out && a.QT <= 0)) return LOLA_ERR_UNSUPPORTED;
     const size_t lds_scan = 4 * (scan_fixed + (size_t)a.R * (3 * d + D + 1));
     const size_t lds_att = 4 * ((size_t)a.QT * (d + D + (lam + a.dm.eta + a.dm.C) + 3));
@@ -553,6 +559,18 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
             if constexpr (std::is_same<T, bf16_t>::value) {
                 if (fast_att) {   // the generic evolution took the snapshots in the MFMA output kernel's layout
                     launch_output_kernel(c, a, a.j0, a.j1, stream);
+                    done = true;
+                }
+            }
+            if constexpr (std::is_same<T, bf16_t>::value) {
+                if (!done && wide_att) {   // any window / budget, 128 or 256 features: the run-time form of the MFMA output kernel
+                    const dim3 gw((unsigned)(a.j1 - a.j0), (unsigned)a.dm.Hq, (unsigned)a.dm.B);
+                    const bool f32o = c->out_dtype == LOLA_F32;
+#define LOLA_WIDE(DHV, DFV) do { if (f32o) hipLaunchKernelGGL((fast::attend_wide_kernel<DHV, DFV, float>), gw, dim3(256), 0, stream, a); \
+                                 else hipLaunchKernelGGL((fast::attend_wide_kernel<DHV, DFV, bf16_t>), gw, dim3(256), 0, stream, a); } while (0)
+                    if (c->head_dim == 128) { if (c->feat_dim == 256) LOLA_WIDE(128, 256); else LOLA_WIDE(128, 128); }
+                    else { if (c->feat_dim == 256) LOLA_WIDE(64, 256); else LOLA_WIDE(64, 128); }
+#undef LOLA_WIDE
                     done = true;
                 }
             }
@@ -742,6 +760,7 @@ const char *lola_kernel_path(const lola_config *c, int32_t which) {
     if (check_config(c) != LOLA_OK) return "invalid";
     if (which == 1 && fast_decode_ok(c)) return "mfma";
     if (which == 0 && fast_attend_ok(c)) return "mfma";
+    if (which == 0 && (fast_output_ok(c) || wide_output_ok(c))) return "mixed";
     return "generic";
 }
 

@@ -232,6 +232,249 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
 }
 
 
+// phi of 16 vectors from their NT tiles of projections in the C layout of the projection GEMM (lane (column r16, group
+// g4) holds z[16 mt + 4 g4 + i] in zt[mt][i]): the lane's 4 NT positive-half and 4 NT negative-half features, index
+// 4 mt + i (Sec. 2.3 eq. feature_map; the softmax kind normalises each half over all 16 NT projections).
+template <int NT>
+__device__ __forceinline__ void phi_from_z_tiles(const f32x4 (&zt)[NT], int phi_kind, float (&pp)[4 * NT], float (&pn)[4 * NT]) {
+    if (phi_kind == 1) {
+#pragma unroll
+        for (int x = 0; x < 4 * NT; x++) { const float zs = zt[x >> 2][x & 3] * LOG2E; pp[x] = fexp2(zs); pn[x] = fexp2(-zs); }
+        return;
+    }
+    float zmax = zt[0][0], zmin = zt[0][0];
+#pragma unroll
+    for (int x = 1; x < 4 * NT; x++) { zmax = fmaxf(zmax, zt[x >> 2][x & 3]); zmin = fminf(zmin, zt[x >> 2][x & 3]); }
+    zmax = grp_max(zmax); zmin = grp_min(zmin);
+    const float cp = -zmax * LOG2E, cn = zmin * LOG2E;
+    float sp = 0.f, sn = 0.f;
+#pragma unroll
+    for (int x = 0; x < 4 * NT; x++) {
+        const float zz = zt[x >> 2][x & 3];
+        pp[x] = fexp2(fmaf(zz, LOG2E, cp)); pn[x] = fexp2(fmaf(zz, -LOG2E, cn));
+        sp += pp[x]; sn += pn[x];
+    }
+    sp = grp_sum(sp); sn = grp_sum(sn);
+    const float ip = frcp(sp), in_ = frcp(sn);
+#pragma unroll
+    for (int x = 0; x < 4 * NT; x++) { pp[x] *= ip; pn[x] *= in_; }
+}
+
+// The output kernel for any window and sparse budget (read from the arguments) and for 128 or 256 features: the
+// paper's own models use twice the head dimension as feature dimension and windows / budgets of 128 .. 1024 in the
+// long-context runs (Sec. 4).  Same computation and layouts as attend_fast_kernel (chunks of 64 queries, key blocks of
+// 128 positions: cache slots, window, the chunk itself), with run-time trip counts; the H^T snapshot passes through LDS
+// 128 features at a time.  The snapshot's pieces are ordered [part][row tile of 16][k-step of 32 features][lane].
+template <int DH, int DF, typename TO>
+__global__ __launch_bounds__(256, 2) void attend_wide_kernel(generic::PrefillArgs<bf16_t> a) {
+    constexpr int M = DF / 2, C = 64, KS = DH / 32, PR = DH / 8, NCT = DH / 16, NZT = M / 16, KSD = DF / 32, NFH = DF / 128;
+    constexpr int MAXLAM = 1024;
+    static_assert((DH == 64 || DH == 128) && (DF == 128 || DF == 256), "shape");
+    __shared__ __attribute__((aligned(16))) uint16_t L[2 * DH * 128];   // 64 KB: K block + V^T block, then half of H^T (high/low parts)
+    __shared__ __attribute__((aligned(16))) float s_l[DF];
+    __shared__ int G_l[MAXLAM];
+
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r16 = lane & 15, g4 = lane >> 4;
+    const int LAM = a.dm.lam, ETA = a.dm.eta;
+    const int P = LAM + ETA, NKEYS = LAM + ETA + C, NB = (NKEYS + 127) / 128;
+    const int j = a.j0 + blockIdx.x, jj = j - a.jb, hq = blockIdx.y, b = blockIdx.z;
+    const int h = hq / a.dm.g, si = b * a.dm.Hkv + h;
+    const int64_t a0 = a.st.n_tokens[si];
+    const int Tn = a.T_tokens;
+    const int cl = min(C, Tn - j * C);              // queries in this chunk
+    const int64_t aj = a0 + (int64_t)j * C;         // token index of the chunk's first query
+    const size_t sj = (size_t)si * a.S + jj;
+    const uint16_t *Hsnap = reinterpret_cast<const uint16_t *>(a.snapH) + sj * (2 * DH * DF);
+    const float *ssnap = a.snapS + sj * DF;
+    const int32_t *Gsnap = a.snapG + sj * LAM;
+    const bf16_t *pK = a.prefK + (size_t)si * P * DH, *pV = a.prefV + (size_t)si * P * DH;
+    const bf16_t *kc = a.k + (size_t)si * Tn * DH, *vc = a.v + (size_t)si * Tn * DH;
+    const bf16_t *qh = a.q + (((size_t)b * a.dm.Hq + hq) * Tn + (size_t)j * C) * DH;
+    TO *oh = (TO *)a.out + (((size_t)b * a.dm.Hq + hq) * Tn + (size_t)j * C) * DH;
+    const bf16_t *Wq = a.Wq + (size_t)hq * M * DH;   // [M][DH]
+    const int vrow_c = P + j * C;                     // virtual row of the chunk's first token
+    const float scale2 = a.dm.scale * LOG2E;          // logits are kept in units of log2(e)
+
+    const int qi = 16 * w + r16;
+    bf16x8 BQ[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) BQ[ks] = ld_bf16x8(qh + (size_t)(qi < cl ? qi : 0) * DH + 32 * ks + 8 * g4);
+    for (int x = tid; x < DF / 4; x += 256) reinterpret_cast<float4 *>(s_l)[x] = reinterpret_cast<const float4 *>(ssnap)[x];
+    for (int x = tid; x < LAM; x += 256) G_l[x] = Gsnap[x];
+    __syncthreads();
+
+    // position -> source row of the key / value (or -1)
+    auto kv_row = [&](int pos) -> int {
+        if (pos < LAM) return G_l[pos];
+        if (pos >= NKEYS) return -1;
+        const int wpos = pos - LAM;                       // 0 .. ETA + C - 1: window, then the chunk
+        if (aj - ETA + wpos < 0 || wpos - ETA >= cl) return -1;
+        return vrow_c - ETA + wpos;
+    };
+
+    // ---- softmax part over key blocks of 128 positions
+    uint16_t *Kl = L, *Vt = L + DH * 128;   // [key][input piece ^ key % pieces] and [c][key chunk ^ swz(c)]
+    f32x4 out[NCT];
+#pragma unroll
+    for (int mt = 0; mt < NCT; mt++) out[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    float mrun = 0.f, lsum = 0.f;   // running max (units of log2 e) and running sum of weights
+    const int64_t tq = aj + qi;     // token index of this lane's query
+#pragma unroll 1
+    for (int blk = 0; blk < NB; blk++) {
+        // a thread stages PR / 4 items of the block, each one 16-byte piece of two neighbouring keys: the transposed values
+        // are then written as 32-bit words (two keys of one column)
+        constexpr int NIT = PR / 4;
+        uint4 kreg[NIT], kreh[NIT], vreg[NIT], vreh[NIT];
+#pragma unroll
+        for (int it = 0; it < NIT; it++) {
+            const int o = tid + 256 * it, kk = 2 * (o / PR), ch = o % PR;
+            const int vr0 = kv_row(128 * blk + kk), vr1 = kv_row(128 * blk + kk + 1);
+            kreg[it] = kreh[it] = vreg[it] = vreh[it] = make_uint4(0, 0, 0, 0);
+            if (vr0 >= 0) {
+                kreg[it] = reinterpret_cast<const uint4 *>(vr0 < P ? pK + (size_t)vr0 * DH : kc + (size_t)(vr0 - P) * DH)[ch];
+                vreg[it] = reinterpret_cast<const uint4 *>(vr0 < P ? pV + (size_t)vr0 * DH : vc + (size_t)(vr0 - P) * DH)[ch];
+            }
+            if (vr1 >= 0) {
+                kreh[it] = reinterpret_cast<const uint4 *>(vr1 < P ? pK + (size_t)vr1 * DH : kc + (size_t)(vr1 - P) * DH)[ch];
+                vreh[it] = reinterpret_cast<const uint4 *>(vr1 < P ? pV + (size_t)vr1 * DH : vc + (size_t)(vr1 - P) * DH)[ch];
+            }
+        }
+        __syncthreads();   // previous users of L (the previous block) are done
+#pragma unroll
+        for (int it = 0; it < NIT; it++) {
+            const int o = tid + 256 * it, kk = 2 * (o / PR), ch = o % PR;
+            *reinterpret_cast<uint4 *>(&Kl[kk * DH + ((ch ^ (kk & (PR - 1))) << 3)]) = kreg[it];
+            *reinterpret_cast<uint4 *>(&Kl[(kk + 1) * DH + ((ch ^ ((kk + 1) & (PR - 1))) << 3)]) = kreh[it];
+            const uint32_t u[4] = {vreg[it].x, vreg[it].y, vreg[it].z, vreg[it].w};
+            const uint32_t uh[4] = {vreh[it].x, vreh[it].y, vreh[it].z, vreh[it].w};
+            const int kchunk = perm_chunk(kk), kel = perm_elem(kk);
+#pragma unroll
+            for (int x = 0; x < 8; x++) {
+                const int c = 8 * ch + x;
+                const uint32_t wv = (x & 1) ? ((u[x >> 1] >> 16) | (uh[x >> 1] & 0xFFFF0000u)) : ((u[x >> 1] & 0xFFFFu) | (uh[x >> 1] << 16));
+                *reinterpret_cast<uint32_t *>(&Vt[c * 128 + ((kchunk ^ ((c ^ (c >> 3)) & 15)) << 3) + kel]) = wv;
+            }
+        }
+        __syncthreads();
+        // S^T = K Q^T for the 8 key tiles of the block; lane (column = query r16, group g4) holds keys 16 mt + 4 g4 + i
+        f32x4 sc[8];
+        float bmax = mrun;
+#pragma unroll
+        for (int mt = 0; mt < 8; mt++) {
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ks++)
+                acc = mfma16(as_bf16x8(*reinterpret_cast<const uint4 *>(&Kl[(16 * mt + r16) * DH + (((4 * ks + g4) ^ (r16 & (PR - 1))) << 3)])), BQ[ks], acc);
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                const int pos = 128 * blk + 16 * mt + 4 * g4 + i;
+                bool ok;
+                if (pos < LAM) ok = G_l[pos] >= 0 && !(a.dm.hide & 2);
+                else if (pos < LAM + ETA) ok = aj - ETA + (pos - LAM) >= 0;
+                else ok = pos < NKEYS && (aj + (pos - LAM - ETA)) <= tq;
+                acc[i] = ok ? acc[i] * scale2 : -INFINITY;
+                bmax = fmaxf(bmax, acc[i]);
+            }
+            sc[mt] = acc;
+        }
+        bmax = grp_max(bmax);
+        const float resc = fexp2(mrun - bmax);
+        mrun = bmax;
+        lsum *= resc;
+#pragma unroll
+        for (int mt = 0; mt < NCT; mt++) out[mt] *= resc;
+#pragma unroll
+        for (int s = 0; s < 4; s++) {
+            float pw[8];
+#pragma unroll
+            for (int e = 0; e < 8; e++) { pw[e] = fexp2(sc[2 * s + (e >> 2)][e & 3] - mrun); lsum += pw[e]; }
+            bf16x8 Ph, Pl;
+            split8(pw, Ph, Pl);
+#pragma unroll
+            for (int mt = 0; mt < NCT; mt++) {
+                const int c = 16 * mt + r16;
+                const bf16x8 Av = as_bf16x8(*reinterpret_cast<const uint4 *>(&Vt[c * 128 + (((4 * s + g4) ^ ((c ^ (c >> 3)) & 15)) << 3)]));
+                out[mt] = mfma16(Av, Ph, out[mt]);
+                out[mt] = mfma16(Av, Pl, out[mt]);
+            }
+        }
+    }
+    lsum = grp_sum(lsum);
+
+    // ---- linear part: phi(q), phi(q)^T s, then lin^T = H^T phi(q)^T with the snapshot staged 128 features at a time
+    float pp[4 * NZT], pn[4 * NZT];
+    {
+        f32x4 zt[NZT];
+#pragma unroll
+        for (int mt = 0; mt < NZT; mt++) {
+            zt[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ks++)
+                zt[mt] = mfma16(ld_bf16x8(Wq + (size_t)(16 * mt + r16) * DH + 32 * ks + 8 * g4), BQ[ks], zt[mt]);
+        }
+        phi_from_z_tiles<NZT>(zt, a.dm.phi_kind, pp, pn);
+    }
+    float lden = 0.f;   // phi(q)^T s
+#pragma unroll
+    for (int mt = 0; mt < NZT; mt++) {
+        const float4 sp4 = *reinterpret_cast<const float4 *>(&s_l[16 * mt + 4 * g4]);
+        const float4 sn4 = *reinterpret_cast<const float4 *>(&s_l[M + 16 * mt + 4 * g4]);
+        lden = fmaf(pp[4 * mt], sp4.x, lden); lden = fmaf(pp[4 * mt + 1], sp4.y, lden);
+        lden = fmaf(pp[4 * mt + 2], sp4.z, lden); lden = fmaf(pp[4 * mt + 3], sp4.w, lden);
+        lden = fmaf(pn[4 * mt], sn4.x, lden); lden = fmaf(pn[4 * mt + 1], sn4.y, lden);
+        lden = fmaf(pn[4 * mt + 2], sn4.z, lden); lden = fmaf(pn[4 * mt + 3], sn4.w, lden);
+    }
+    lden = grp_sum(lden);
+    // B operands of the read-out: k-step ks covers features 32 ks ..: the first KSD / 2 k-steps the positive half
+    bf16x8 Bh[KSD], Bl[KSD];
+#pragma unroll
+    for (int ks = 0; ks < KSD / 2; ks++) {
+        split8(&pp[8 * ks], Bh[ks], Bl[ks]);
+        split8(&pn[8 * ks], Bh[KSD / 2 + ks], Bl[KSD / 2 + ks]);
+    }
+    const float el = (a.dm.hide & 1) ? 0.f : fexp2(-mrun);   // restricted query: no hidden-state terms
+    const float inv = frcp(fmaf(el, lden, lsum));
+    f32x4 lin[NCT], lin2[NCT];
+#pragma unroll
+    for (int mt = 0; mt < NCT; mt++) { lin[mt] = (f32x4){0.f, 0.f, 0.f, 0.f}; lin2[mt] = (f32x4){0.f, 0.f, 0.f, 0.f}; }
+#pragma unroll 1
+    for (int fh = 0; fh < NFH; fh++) {
+        __syncthreads();   // the last key block (or the previous half) has been consumed
+        // snapshot order: [part][row tile of 16][k-step][lane = 16 (piece % 4) + row % 16]; this half: k-steps 4 fh .. 4 fh + 3
+        for (int o = tid; o < 2 * DH * 16; o += 256) {
+            const int part = o / (DH * 16), op = o % (DH * 16);
+            const int ct = op >> 8, ksl = (op >> 6) & 3, ln = op & 63;
+            const uint4 hv = reinterpret_cast<const uint4 *>(Hsnap)[(size_t)part * (DH * DF / 8) + (ct * KSD + 4 * fh + ksl) * 64 + ln];
+            const int c = 16 * ct + (ln & 15), ch = 4 * ksl + (ln >> 4);
+            *reinterpret_cast<uint4 *>(&L[part * DH * 128 + c * 128 + ((ch ^ (c & 15)) << 3)]) = hv;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int mt = 0; mt < NCT; mt++) {
+#pragma unroll
+            for (int ks = 0; ks < 4; ks++) {
+                const int addr = (16 * mt + r16) * 128 + (((4 * ks + g4) ^ r16) << 3);
+                const bf16x8 Ahi = as_bf16x8(*reinterpret_cast<const uint4 *>(&L[addr]));
+                const bf16x8 Alo = as_bf16x8(*reinterpret_cast<const uint4 *>(&L[DH * 128 + addr]));
+                const bf16x8 bh = fh == 0 ? Bh[ks] : Bh[(KSD > 4 ? 4 : 0) + ks], bl = fh == 0 ? Bl[ks] : Bl[(KSD > 4 ? 4 : 0) + ks];
+                lin[mt] = mfma16(Ahi, bh, lin[mt]);
+                lin2[mt] = mfma16(Ahi, bl, lin2[mt]);
+                lin2[mt] = mfma16(Alo, bh, lin2[mt]);
+            }
+        }
+    }
+    if (qi < cl) {
+#pragma unroll
+        for (int mt = 0; mt < NCT; mt++) {
+            const f32x4 ln4 = lin[mt] + lin2[mt];
+            TO *dst = oh + (size_t)qi * DH + 16 * mt + 4 * g4;
+#pragma unroll
+            for (int i = 0; i < 4; i++) stf(dst, i, fmaf(el, ln4[i], out[mt][i]) * inv);
+        }
+    }
+}
+
+
 // ---------------------------------------------------------------------------------------------
 // Sequential state evolution of the prefill (paper Sec. 3 "Chunkwise Inference": after each chunk the
 // oldest chunk leaves the window; it and the sparse cache are scored by self-recall error, the top
