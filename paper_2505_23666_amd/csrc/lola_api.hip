@@ -181,6 +181,13 @@ bool wide_output_ok(const lola_config *c) {
            c->chunk == 64 && c->sparse_budget <= 1024;
 }
 
+// shapes of the MFMA state-evolution kernel with run-time window and sparse budget (multiples of 64; it ranks by
+// self-recall error only); the shapes of the specialised kernels above keep those
+bool wide_scan_ok(const lola_config *c) {
+    return wide_output_ok(c) && !fast_output_ok(c) && c->score_kind == LOLA_SCORE_SRE && c->sparse_budget >= 64 &&
+           c->sparse_budget % 64 == 0 && c->window >= 64 && c->window % 64 == 0;
+}
+
 struct PrefillPlan {
     size_t off_prefK, off_prefV, off_sp_row, off_phiE, off_next, off_score, off_snap;   // byte offsets
     size_t snap_bytes_per_chunk;                                    // all streams, one chunk (snapshots + phi of its keys)
@@ -201,7 +208,7 @@ PrefillPlan plan_prefill(const lola_config *c, int with_outputs, size_t Tn) {
     p.off_snap = off;
     p.fixed_bytes = off;
     p.snap_bytes_per_chunk = with_outputs ? up(ns * D * d * 4) + up(ns * D * 4) + up(ns * (lam ? lam : 1) * 4) : 0;
-    p.phik_bytes_per_chunk = fast_attend_ok(c) ? up(ns * (size_t)c->chunk * D * 4) : 0;   // phi of the chunk's keys, two bf16 parts
+    p.phik_bytes_per_chunk = (fast_attend_ok(c) || wide_scan_ok(c)) ? up(ns * (size_t)c->chunk * D * 4) : 0;   // phi of the chunk's keys, two bf16 parts
     p.snap_bytes_per_chunk += p.phik_bytes_per_chunk;
     return p;
 }
@@ -445,6 +452,39 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
                 a.scan_mode = 0;
                 if (a.want_out) {
                     launch_output_kernel(c, a, j0, jend, stream);
+                    LAUNCH_CHECK();
+                }
+                continue;
+            }
+            if (wide_scan_ok(c)) {
+                // Any window / budget in multiples of 64, 128 or 256 features: the generic kernel until the first regular
+                // chunk (a full chunk with a full window behind it and a full cache); phi of the rows the MFMA kernel
+                // reads (the pairs leaving the window in each chunk of the pass, and the cache slots as they are now); the
+                // MFMA kernel over the regular chunks; the generic kernel again for a ragged last chunk; the outputs.
+                a.scan_mode = 1;
+                hipLaunchKernelGGL((generic::scan_kernel<T>), gs, block, lds_scan, stream, a);
+                LAUNCH_CHECK();
+                const dim3 gp((unsigned)(jend - j0) + (unsigned)(c->sparse_budget / 64), (unsigned)ns);
+#define LOLA_WSCAN(DHV, DFV) do { hipLaunchKernelGGL((fast::phi_wide_kernel<DHV, DFV>), gp, dim3(256), 0, stream, a); \
+                                  hipLaunchKernelGGL((fast::scan_wide_kernel<DHV, DFV>), gs, dim3(DHV * 4), 0, stream, a); } while (0)
+                if (c->head_dim == 128) { if (c->feat_dim == 256) LOLA_WSCAN(128, 256); else LOLA_WSCAN(128, 128); }
+                else { if (c->feat_dim == 256) LOLA_WSCAN(64, 256); else LOLA_WSCAN(64, 128); }
+#undef LOLA_WSCAN
+                LAUNCH_CHECK();
+                if (jend == a.n_chunks && Tn % a.dm.C != 0) {
+                    a.scan_mode = 2;
+                    hipLaunchKernelGGL((generic::scan_kernel<T>), gs, block, lds_scan, stream, a);
+                    LAUNCH_CHECK();
+                }
+                a.scan_mode = 0;
+                if (a.want_out) {
+                    const dim3 gw((unsigned)(jend - j0), (unsigned)a.dm.Hq, (unsigned)a.dm.B);
+                    const bool f32o = c->out_dtype == LOLA_F32;
+#define LOLA_WIDE(DHV, DFV) do { if (f32o) hipLaunchKernelGGL((fast::attend_wide_kernel<DHV, DFV, float>), gw, dim3(256), 0, stream, a); \
+                                 else hipLaunchKernelGGL((fast::attend_wide_kernel<DHV, DFV, bf16_t>), gw, dim3(256), 0, stream, a); } while (0)
+                    if (c->head_dim == 128) { if (c->feat_dim == 256) LOLA_WIDE(128, 256); else LOLA_WIDE(128, 128); }
+                    else { if (c->feat_dim == 256) LOLA_WIDE(64, 256); else LOLA_WIDE(64, 128); }
+#undef LOLA_WIDE
                     LAUNCH_CHECK();
                 }
                 continue;
@@ -759,7 +799,7 @@ const char *lola_status_str(lola_status s) {
 const char *lola_kernel_path(const lola_config *c, int32_t which) {
     if (check_config(c) != LOLA_OK) return "invalid";
     if (which == 1 && fast_decode_ok(c)) return "mfma";
-    if (which == 0 && fast_attend_ok(c)) return "mfma";
+    if (which == 0 && (fast_attend_ok(c) || wide_scan_ok(c))) return "mfma";
     if (which == 0 && (fast_output_ok(c) || wide_output_ok(c))) return "mixed";
     return "generic";
 }

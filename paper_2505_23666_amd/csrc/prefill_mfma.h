@@ -1220,6 +1220,458 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
 #undef LOLA_SSTORE
 }
 
+// ---------------------------------------------------------------------------------------------
+// State evolution of the prefill for any window and sparse budget (multiples of 64, read from the arguments) and 128 or
+// 256 features: the paper's own models use twice the head dimension as feature dimension and windows / budgets of
+// 128 .. 1024 in the long-context runs (Sec. 4).  Same five steps per regular chunk as scan_fast_kernel (snapshot,
+// self-recall error of the lambda + 64 candidates, selection of the 64 to fold, fold, compaction; Sec. 3.1 - 3.2), laid
+// out for a candidate set that does not fit LDS:
+//   * phi of every row is computed chunk-parallel beforehand (phi_wide_kernel): the pairs that leave the window in chunk
+//     j (phiK[j - jb]) and the cache slots as the launch finds them (phiE[slot], kept current by the compaction);
+//   * one wavefront per 16 rows of H^T (fp32 accumulators, split into bf16 high + low parts once per chunk);
+//   * the candidates' features and values stream through LDS in batches of RB rows, double-buffered, by direct
+//     global -> LDS loads issued one batch ahead; each wavefront runs the recall GEMM of the batch against its rows of
+//     H^T and leaves |P|^2, P.v, |v|^2 over its 16 value columns per candidate, summed over the wavefronts one batch
+//     later; phi(k).s is a plain dot product per row of the batch;
+//   * the fold reads both MFMA operands out of row-major LDS tiles (the 64 folded rows gathered by direct loads)
+//     through the transposing LDS read, the contraction index being the pair.
+template <int DH, int DF>
+__global__ __launch_bounds__(256) void phi_wide_kernel(generic::PrefillArgs<bf16_t> a) {
+    constexpr int M = DF / 2, C = 64, KS = DH / 32, NZT = M / 16, FR = 2 * DF;
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r16 = lane & 15, g4 = lane >> 4;
+    const int si = blockIdx.y, h = si % a.dm.Hkv, LAM = a.dm.lam, P = LAM + a.dm.eta;
+    const int nch = a.j1 - a.j0, row = 16 * w + r16;
+    const bf16_t *Wk = a.Wk + (size_t)h * M * DH;
+    const bf16_t *kr;
+    uint16_t *dst;
+    bool valid = true;
+    if ((int)blockIdx.x < nch) {
+        // the pairs that leave the window while chunk j joins it: virtual rows lam + j C + 0..63 (rows below P: the cache
+        // and window the call found)
+        const int j = a.j0 + (int)blockIdx.x, vr = LAM + j * C + row;
+        valid = vr - P < a.T_tokens;
+        kr = vr < P ? a.prefK + ((size_t)si * P + vr) * DH : a.k + ((size_t)si * a.T_tokens + (valid ? vr - P : 0)) * DH;
+        dst = a.phiK + (((size_t)si * a.S + (j - a.jb)) * C + row) * FR;
+    } else {
+        const int slot = 64 * ((int)blockIdx.x - nch) + row;   // the grid covers lam / 64 such blocks
+        kr = a.st.sp_k + ((size_t)si * LAM + slot) * DH;
+        dst = reinterpret_cast<uint16_t *>(a.phiE + (size_t)si * (LAM + C) * DF) + (size_t)slot * FR;
+    }
+    bf16x8 BK[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) BK[ks] = valid ? ld_bf16x8(kr + 32 * ks + 8 * g4) : zero_bf16x8();
+    f32x4 zt[NZT];
+#pragma unroll
+    for (int mt = 0; mt < NZT; mt++) {
+        zt[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ks++)
+            zt[mt] = mfma16(ld_bf16x8(Wk + (size_t)(16 * mt + r16) * DH + 32 * ks + 8 * g4), BK[ks], zt[mt]);
+    }
+    float pp[4 * NZT], pn[4 * NZT];
+    phi_from_z_tiles<NZT>(zt, a.dm.phi_kind, pp, pn);
+    // operand order: 16-byte piece 4 ks + g4 of a part holds features 32 ks + 16 (x / 4) + 4 g4 + x % 4, x < 8: the
+    // lane's values of projection tiles 2 ks and 2 ks + 1; the negative half follows the positive half
+#pragma unroll
+    for (int ks = 0; ks < M / 32; ks++) {
+        bf16x8 hi, lo;
+        split8(&pp[8 * ks], hi, lo);
+        *reinterpret_cast<uint4 *>(dst + ((4 * ks + g4) << 3)) = __builtin_bit_cast(uint4, hi);
+        *reinterpret_cast<uint4 *>(dst + DF + ((4 * ks + g4) << 3)) = __builtin_bit_cast(uint4, lo);
+        split8(&pn[8 * ks], hi, lo);
+        *reinterpret_cast<uint4 *>(dst + ((4 * (M / 32 + ks) + g4) << 3)) = __builtin_bit_cast(uint4, hi);
+        *reinterpret_cast<uint4 *>(dst + DF + ((4 * (M / 32 + ks) + g4) << 3)) = __builtin_bit_cast(uint4, lo);
+    }
+}
+
+template <int DH, int DF>
+__global__ __launch_bounds__(DH * 4) void scan_wide_kernel(generic::PrefillArgs<bf16_t> a) {
+    constexpr int C = 64, NW = DH / 16, NTH = 64 * NW, KF = DF / 32, NMT = DF / 16, PR = DH / 8, FR = 2 * DF, PP = DF / 8;
+    constexpr int RB = 8192 / DF, TB = RB / 16;            // candidates per batch: 32 KB of features
+    constexpr int NEMAX = 1024 + C, NKMAX = NEMAX / 64;
+    constexpr int BUF = RB * FR + RB * DH;                 // 16-bit elements of one batch buffer: features, then values
+    constexpr int FOLD = C * FR + C * DH;                  // the folded pairs' features and values
+    constexpr int POOL = 2 * BUF > FOLD ? 2 * BUF : FOLD;
+    static_assert((DH == 64 || DH == 128) && (DF == 128 || DF == 256), "shape");
+    __shared__ __attribute__((aligned(16))) uint16_t pool[POOL];
+    __shared__ __attribute__((aligned(16))) float s_l[DF];
+    __shared__ float dn_l[NEMAX];              // phi(k).s
+    __shared__ float tot[3][NEMAX];            // |P|^2, P.v, |v|^2 over all value columns
+    __shared__ uint32_t skey[NEMAX];           // bit patterns of the squared errors
+    __shared__ int cidx[NEMAX];                // token index of each candidate
+    __shared__ float part[2][3][NW][RB];       // per wavefront: the three sums over its 16 columns, for the batch in flight
+    __shared__ int flist[C], ecand[C], eslot[C];
+    __shared__ int ne_s;
+
+    const int tid0 = threadIdx.x, w0 = tid0 >> 6;
+    const int si = blockIdx.x;
+    const int LAM = a.dm.lam, ETA = a.dm.eta, P = LAM + ETA, NE = LAM + C, NBATCH = NE / RB, nk = NE / 64;
+    float *Hg = a.st.H + (size_t)si * DF * DH;
+    float *sg = a.st.s + (size_t)si * DF;
+    bf16_t *sp_k = a.st.sp_k + (size_t)si * LAM * DH, *sp_v = a.st.sp_v + (size_t)si * LAM * DH;
+    int32_t *sp_idx = a.st.sp_idx + (size_t)si * LAM;
+    int32_t *sp_row = a.sp_row + (size_t)si * LAM;
+    uint16_t *phiE = reinterpret_cast<uint16_t *>(a.phiE + (size_t)si * (LAM + C) * DF);   // [slot][part][DF] bf16, operand order
+    const bf16_t *pK = a.prefK + (size_t)si * P * DH, *pV = a.prefV + (size_t)si * P * DH;
+    const bf16_t *kc = a.k + (size_t)si * a.T_tokens * DH, *vc = a.v + (size_t)si * a.T_tokens * DH;
+    const int64_t a0 = a.st.n_tokens[si];
+    const int spc = a.st.sp_count[si];
+    int j = a.next_j[si];
+
+    // H^T row 16 w + r16, features 16 mt + 4 g4 + 0..3
+    f32x4 hacc[NMT];
+#pragma unroll
+    for (int mt = 0; mt < NMT; mt++) hacc[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    bool started = false;
+
+    for (; j < a.j1; j++) {
+        const int cl = min(C, a.T_tokens - j * C);
+        const int64_t aj = a0 + (int64_t)j * C;
+        if (!(cl == C && aj >= ETA && spc == LAM)) break;   // not a regular chunk: the generic kernel takes over
+        if (!started) {
+            const float *hrow = Hg + (size_t)(16 * w0 + (tid0 & 15)) * DF + 4 * ((tid0 & 63) >> 4);
+#pragma unroll
+            for (int mt = 0; mt < NMT; mt++) hacc[mt] = *reinterpret_cast<const f32x4 *>(hrow + 16 * mt);
+            for (int x = tid0; x < DF; x += NTH) s_l[x] = sg[x];
+            for (int e = tid0; e < LAM; e += NTH) cidx[e] = sp_idx[e];
+            started = true;
+            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+            __syncthreads();
+        }
+        // the lane coordinates are made opaque once per chunk, so that the addresses derived from them are recomputed in
+        // the loop instead of being kept as loop-invariant registers next to H^T
+        int tl_ = threadIdx.x;
+        asm volatile("" : "+v"(tl_));
+        const int tid = tl_, lane = tid & 63, r16 = lane & 15, g4 = lane >> 4, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+        const int vrow_l = LAM + j * C;   // virtual row of the first pair that leaves the window in this chunk
+        const uint16_t *phk = a.phiK + ((size_t)si * a.S + (size_t)(j - a.jb)) * C * FR;
+        auto krow = [&](int e) -> const bf16_t * {
+            if (e < LAM) return sp_k + (size_t)e * DH;
+            const int vr = vrow_l + (e - LAM);
+            return vr < P ? pK + (size_t)vr * DH : kc + (size_t)(vr - P) * DH;
+        };
+        auto vrow = [&](int e) -> const bf16_t * {
+            if (e < LAM) return sp_v + (size_t)e * DH;
+            const int vr = vrow_l + (e - LAM);
+            return vr < P ? pV + (size_t)vr * DH : vc + (size_t)(vr - P) * DH;
+        };
+        auto phirow = [&](int e) -> const uint16_t * { return e < LAM ? phiE + (size_t)e * FR : phk + (size_t)(e - LAM) * FR; };
+
+        // ---- 1. operands of the recall GEMM from the fp32 registers; they are the snapshot's pieces as well
+        bf16x8 Ahi[KF], Alo[KF];
+#pragma unroll
+        for (int ks = 0; ks < KF; ks++) {
+            const float x8[8] = {hacc[2 * ks][0], hacc[2 * ks][1], hacc[2 * ks][2], hacc[2 * ks][3],
+                                 hacc[2 * ks + 1][0], hacc[2 * ks + 1][1], hacc[2 * ks + 1][2], hacc[2 * ks + 1][3]};
+            split8(x8, Ahi[ks], Alo[ks]);
+        }
+        if (tid < C) cidx[LAM + tid] = (int)(aj - ETA + tid);
+
+        // requests of batch b into buffer buf: 1 KB per instruction, lane l fills bytes 16 l ..; a row's 16-byte pieces are
+        // XOR-swizzled with the row number, so a lane fetches the piece that belongs in its position
+        auto issue = [&](int b, int buf) {
+            uint16_t *PBb = pool + buf * BUF, *VBb = PBb + RB * FR;
+            const int e0 = b * RB;
+#pragma unroll
+            for (int it = 0; it < RB * FR / 512 / NW; it++) {
+                const int i = w + NW * it, g = 512 * i + 8 * lane, row = g / FR, pt = (g % FR) / DF, slot = (g % DF) >> 3;
+                const uint16_t *src = phirow(e0 + row) + pt * DF + ((slot ^ (row & 15)) << 3);
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                                 (__attribute__((address_space(3))) void *)(PBb + 512 * i), 16, 0, 0);
+            }
+#pragma unroll
+            for (int it = 0; it < (RB * DH / 512 + NW - 1) / NW; it++) {
+                const int i = w + NW * it;
+                if (i < RB * DH / 512) {
+                    const int g = 512 * i + 8 * lane, row = g / DH, slot = (g % DH) >> 3;
+                    const bf16_t *src = vrow(e0 + row) + ((slot ^ (row & (PR - 1))) << 3);
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                                     (__attribute__((address_space(3))) void *)(VBb + 512 * i), 16, 0, 0);
+                }
+            }
+        };
+        issue(0, 0);
+        if (a.want_out) {
+            const size_t sj = (size_t)si * a.S + (j - a.jb);
+            uint16_t *s16 = reinterpret_cast<uint16_t *>(a.snapH) + sj * (2 * DF * DH);
+#pragma unroll
+            for (int ks = 0; ks < KF; ks++) {
+                // one contiguous 1 KB piece per store: [part][row tile][k-step][lane]
+                const int off = ((w * KF + ks) * 64 + lane) << 3;
+                *reinterpret_cast<uint4 *>(s16 + off) = __builtin_bit_cast(uint4, Ahi[ks]);
+                *reinterpret_cast<uint4 *>(s16 + DF * DH + off) = __builtin_bit_cast(uint4, Alo[ks]);
+            }
+            for (int x = tid; x < DF / 4; x += NTH) reinterpret_cast<float4 *>(a.snapS + sj * DF)[x] = reinterpret_cast<const float4 *>(s_l)[x];
+            for (int sl = tid; sl < LAM; sl += NTH) a.snapG[sj * LAM + sl] = sp_row[sl];
+        }
+
+        // ---- 2. recall error of the candidates, batch by batch
+#pragma unroll 1
+        for (int b = 0; b < NBATCH; b++) {
+            const int buf = b & 1;
+            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wavefront's share of batch b has landed
+            __syncthreads();                      // ... and everybody's; the other buffer's readers (batch b - 1) are done
+            if (b + 1 < NBATCH) issue(b + 1, buf ^ 1);
+            const uint16_t *PBb = pool + buf * BUF, *VBb = PBb + RB * FR;
+            if (b > 0 && tid < 3 * RB) {          // batch b - 1: the wavefronts' sums over their columns, added in a fixed order
+                const int k = tid / RB, r = tid % RB;
+                float sum = 0.f;
+#pragma unroll
+                for (int x = 0; x < NW; x++) sum += part[buf ^ 1][k][x][r];
+                tot[k][(b - 1) * RB + r] = sum;
+            }
+            {   // phi(k).s of the batch's rows: TPR neighbouring lanes share a row
+                constexpr int TPR = NTH / RB, NPC = PP / TPR;
+                const int r = tid / TPR, sub = tid % TPR;
+                float dsum = 0.f;
+#pragma unroll
+                for (int x = 0; x < NPC; x++) {
+                    const int pc = sub + TPR * x, addr = r * FR + ((pc ^ (r & 15)) << 3);
+                    const uint4 hi = *reinterpret_cast<const uint4 *>(&PBb[addr]), lo = *reinterpret_cast<const uint4 *>(&PBb[addr + DF]);
+                    const float4 s0 = *reinterpret_cast<const float4 *>(&s_l[32 * (pc >> 2) + 4 * (pc & 3)]);
+                    const float4 s1 = *reinterpret_cast<const float4 *>(&s_l[32 * (pc >> 2) + 16 + 4 * (pc & 3)]);
+                    dsum = fmaf(bf_lo(hi.x) + bf_lo(lo.x), s0.x, dsum); dsum = fmaf(bf_hi(hi.x) + bf_hi(lo.x), s0.y, dsum);
+                    dsum = fmaf(bf_lo(hi.y) + bf_lo(lo.y), s0.z, dsum); dsum = fmaf(bf_hi(hi.y) + bf_hi(lo.y), s0.w, dsum);
+                    dsum = fmaf(bf_lo(hi.z) + bf_lo(lo.z), s1.x, dsum); dsum = fmaf(bf_hi(hi.z) + bf_hi(lo.z), s1.y, dsum);
+                    dsum = fmaf(bf_lo(hi.w) + bf_lo(lo.w), s1.z, dsum); dsum = fmaf(bf_hi(hi.w) + bf_hi(lo.w), s1.w, dsum);
+                }
+                dsum += dpp_f<0xB1>(dsum); dsum += dpp_f<0x4E>(dsum);
+                if (TPR >= 8) dsum += dpp_f<0x141>(dsum);
+                if (TPR >= 16) dsum += dpp_f<0x140>(dsum);
+                if (sub == 0) dn_l[b * RB + r] = dsum;
+            }
+            // recall GEMM: A = this wavefront's 16 rows of H^T, B = phi of 16 candidates from LDS; lane (candidate r16,
+            // group g4) holds the recall at columns 16 w + 4 g4 + i and pairs it with the candidate's values there
+#pragma unroll
+            for (int u = 0; u < TB; u++) {
+                const uint16_t *rowp = PBb + (16 * u + r16) * FR;
+                bf16x8 Bh[KF], Bl[KF];
+#pragma unroll
+                for (int ks = 0; ks < KF; ks++) {
+                    const int addr = ((4 * ks + g4) ^ r16) << 3;
+                    Bh[ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(rowp + addr));
+                    Bl[ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(rowp + DF + addr));
+                }
+                f32x4 acc = {0.f, 0.f, 0.f, 0.f};   // the three products of a k-step go into one accumulator: the large one first
+#pragma unroll
+                for (int ks = 0; ks < KF; ks++) acc = mfma16(Ahi[ks], Bh[ks], acc);
+#pragma unroll
+                for (int ks = 0; ks < KF; ks++) acc = mfma16(Ahi[ks], Bl[ks], acc);
+#pragma unroll
+                for (int ks = 0; ks < KF; ks++) acc = mfma16(Alo[ks], Bh[ks], acc);
+                const uint2 vv = *reinterpret_cast<const uint2 *>(&VBb[(16 * u + r16) * DH + (((2 * w + (g4 >> 1)) ^ (r16 & (PR - 1))) << 3) + 4 * (g4 & 1)]);
+                const float v0 = bf_lo(vv.x), v1 = bf_hi(vv.x), v2 = bf_lo(vv.y), v3 = bf_hi(vv.y);
+                float sa = 0.f, sb = 0.f, sc = 0.f;
+                sa = fmaf(acc[0], acc[0], sa); sa = fmaf(acc[1], acc[1], sa); sa = fmaf(acc[2], acc[2], sa); sa = fmaf(acc[3], acc[3], sa);
+                sb = fmaf(acc[0], v0, sb); sb = fmaf(acc[1], v1, sb); sb = fmaf(acc[2], v2, sb); sb = fmaf(acc[3], v3, sb);
+                sc = fmaf(v0, v0, sc); sc = fmaf(v1, v1, sc); sc = fmaf(v2, v2, sc); sc = fmaf(v3, v3, sc);
+                const float s3 = grp_sum3(sa, sb, sc);   // lane group g4 holds sum g4
+                if (g4 < 3) part[buf][g4][w][16 * u + r16] = s3;
+            }
+        }
+        __syncthreads();
+        if (tid < 3 * RB) {
+            const int k = tid / RB, r = tid % RB;
+            float sum = 0.f;
+#pragma unroll
+            for (int x = 0; x < NW; x++) sum += part[(NBATCH - 1) & 1][k][x][r];
+            tot[k][(NBATCH - 1) * RB + r] = sum;
+        }
+        __syncthreads();
+
+        // ---- 3. selection: the 64 candidates with the smallest squared error are folded (order: score descending,
+        // token index ascending, the first lambda stay).  The squared error is |P|^2 / (phi.s)^2 - 2 P.v / (phi.s) + |v|^2
+        // (recall = 0 while phi.s = 0); the bit pattern of a float >= 0 orders like an integer.
+        for (int e = tid; e < NE; e += NTH) {
+            const float dn = dn_l[e], rd = dn > 0.f ? __builtin_amdgcn_rcpf(dn) : 0.f;
+            const float sq = fmaxf(fmaf(rd * rd, tot[0][e], fmaf(-2.0f * rd, tot[1][e], tot[2][e])), 0.f);
+            skey[e] = __float_as_uint(sq) & 0x7FFFFFFFu;
+        }
+        __syncthreads();
+        if (w == 0) {
+            // One wavefront holds all scores (up to 17 per lane) and builds the 64th smallest bit by bit: a trial value is
+            // kept while fewer than 64 scores lie below it.  Scores equal to the threshold are folded too if that makes
+            // exactly 64; otherwise (exact ties across the cut) the same search over their token indices picks the
+            // largest ones.  The lists follow from the fold predicate by ballots (candidate order kept).
+            uint32_t sb[NKMAX]; int ix[NKMAX];
+#pragma unroll
+            for (int x = 0; x < NKMAX; x++) {
+                sb[x] = 0xFFFFFFFFu; ix[x] = 0;
+                if (x < nk) { sb[x] = skey[64 * x + lane]; ix[x] = cidx[64 * x + lane]; }
+            }
+            uint32_t thr = 0, cut = 0;   // cut != 0: exactly 64 scores lie below it
+#pragma unroll 1
+            for (int bit = 30; bit >= 0 && cut == 0; bit--) {
+                const uint32_t trial = thr | (1u << bit);
+                int c = 0;
+#pragma unroll
+                for (int x = 0; x < NKMAX; x++) if (x < nk) c += __popcll(__ballot(sb[x] < trial));
+                if (c == C) cut = trial;
+                if (c < C) thr = trial;
+            }
+            int n_lt = 0, n_eq = 0;
+            if (cut != 0) { thr = cut; n_lt = C; }
+            else {
+#pragma unroll
+                for (int x = 0; x < NKMAX; x++)
+                    if (x < nk) { n_lt += __popcll(__ballot(sb[x] < thr)); n_eq += __popcll(__ballot(sb[x] == thr)); }
+            }
+            const int need = C - n_lt;      // ties at the threshold to fold: 0 after an early stop, else 1 <= need <= n_eq
+            uint32_t imin = need == 0 ? 0xFFFFFFFFu : 0u;   // ties are folded from token index imin upwards
+            if (need != 0 && n_eq != need) {
+#pragma unroll 1
+                for (int bit = 30; bit >= 0; bit--) {
+                    const uint32_t trial = imin | (1u << bit);
+                    int c = 0;
+#pragma unroll
+                    for (int x = 0; x < NKMAX; x++) if (x < nk) c += __popcll(__ballot(sb[x] == thr && (uint32_t)ix[x] >= trial));
+                    if (c >= need) imin = trial;
+                }
+            }
+            int nf = 0, nen = 0, nlv = 0;
+            const unsigned long long below = (1ull << lane) - 1ull;
+#pragma unroll
+            for (int x = 0; x < NKMAX; x++) {
+                if (x < nk) {
+                    const int e = 64 * x + lane;
+                    const bool fo = sb[x] < thr || (sb[x] == thr && (uint32_t)ix[x] >= imin);
+                    const bool en = !fo && e >= LAM, lv = fo && e < LAM;
+                    const unsigned long long mf = __ballot(fo), me = __ballot(en), ml = __ballot(lv);
+                    if (fo) flist[nf + __popcll(mf & below)] = e;
+                    if (en) ecand[nen + __popcll(me & below)] = e;
+                    if (lv) eslot[nlv + __popcll(ml & below)] = e;
+                    nf += __popcll(mf); nen += __popcll(me); nlv += __popcll(ml);
+                }
+            }
+            if (lane == 0) ne_s = nen;
+        }
+        __syncthreads();
+        const int ne = ne_s;   // exactly 64 are folded, so entrants and leavers pair up
+
+        // ---- 4. fold: H[f][c] += sum_e phi_e[f] v_e[c], s[f] += sum_e phi_e[f] over the 64 folded pairs, whose rows are
+        // gathered into LDS ([pair][part][position] and [pair][column], 16-byte pieces XOR-swizzled with the pair number)
+        uint16_t *FP = pool, *FV = pool + C * FR;
+#pragma unroll
+        for (int it = 0; it < C * FR / 512 / NW; it++) {
+            const int i = w + NW * it, g = 512 * i + 8 * lane, row = g / FR, pt = (g % FR) / DF, slot = (g % DF) >> 3;
+            const uint16_t *src = phirow(flist[row]) + pt * DF + ((slot ^ (row & 15)) << 3);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                             (__attribute__((address_space(3))) void *)(FP + 512 * i), 16, 0, 0);
+        }
+#pragma unroll
+        for (int it = 0; it < C * DH / 512 / NW; it++) {
+            const int i = w + NW * it, g = 512 * i + 8 * lane, row = g / DH, slot = (g % DH) >> 3;
+            const bf16_t *src = vrow(flist[row]) + ((slot ^ (row & (PR - 1))) << 3);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                             (__attribute__((address_space(3))) void *)(FV + 512 * i), 16, 0, 0);
+        }
+        // compaction, first half: the entrants' rows (keys, values, features) are requested now and stored after the fold
+        constexpr int CIT = C * 2 * PR / NTH, PIT = C * (FR / 8) / NTH;
+        uint4 cp[CIT], fe[PIT];
+#pragma unroll
+        for (int it = 0; it < CIT; it++) {
+            const int o = tid + NTH * it;
+            cp[it] = make_uint4(0, 0, 0, 0);
+            if (o < ne * 2 * PR) {
+                const int x = o / (2 * PR), rem = o % (2 * PR), e = ecand[x];
+                cp[it] = reinterpret_cast<const uint4 *>((rem >= PR) ? vrow(e) : krow(e))[rem % PR];
+            }
+        }
+#pragma unroll
+        for (int it = 0; it < PIT; it++) {
+            const int o = tid + NTH * it;
+            fe[it] = make_uint4(0, 0, 0, 0);
+            if (o < ne * (FR / 8)) fe[it] = reinterpret_cast<const uint4 *>(phirow(ecand[o / (FR / 8)]))[o % (FR / 8)];
+        }
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+        __syncthreads();
+        // contraction slots of lane group g4 in k-step kst: pairs 32 kst + 4 g4 + 0..3, then + 16 (the order in which the
+        // transposing read delivers them, the same for both operands)
+#pragma unroll
+        for (int kst = 0; kst < 2; kst++) {
+            const int t0 = 32 * kst + 4 * g4 + (r16 >> 2), t15 = t0 & 15;
+            // B: values, column 16 w + r16: lane i of a group points at pair t0's four columns 16 w + 4 (i % 4) ..
+            const uint16_t *vb = FV + t0 * DH + (((2 * w + ((r16 & 3) >> 1)) ^ (t0 & (PR - 1))) << 3) + 4 * (r16 & 1);
+            const bf16x4 b0 = tr_read(vb), b1 = tr_read(vb + 16 * DH);
+            const bf16x8 Bv = __builtin_shufflevector(b0, b1, 0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+            for (int mt = 0; mt < NMT; mt++) {
+                // A: phi^T, row f = 16 mt + r of the tile from position 32 (mt / 2) + 8 (r / 4) + 4 (mt % 2) + r % 4, i.e.
+                // 16-byte piece 4 (mt / 2) + r / 4 of the row (stored at that piece ^ pair % 16), its half mt % 2
+                const int off = (((4 * (mt >> 1) + (r16 & 3)) ^ t15) << 3) + 4 * (mt & 1);
+#pragma unroll
+                for (int pt = 0; pt < 2; pt++) {
+                    const uint16_t *pa = FP + pt * DF + off;
+                    const bf16x4 a0v = tr_read(pa + t0 * FR), a1v = tr_read(pa + (t0 + 16) * FR);
+                    const bf16x8 Av = __builtin_shufflevector(a0v, a1v, 0, 1, 2, 3, 4, 5, 6, 7);
+                    hacc[mt] = mfma16(Av, Bv, hacc[mt]);
+                }
+            }
+        }
+        {   // s: the same product with a column of ones in place of the values, feature tiles w, w + NW, ... by wavefront w
+            const uint32_t one2 = 0x3F803F80u;
+            const bf16x8 Bones = as_bf16x8(make_uint4(one2, one2, one2, one2));
+#pragma unroll
+            for (int x = 0; x < NMT / NW; x++) {
+                const int mt = w + NW * x;
+                f32x4 sacc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int kst = 0; kst < 2; kst++) {
+                    const int t0 = 32 * kst + 4 * g4 + (r16 >> 2), t15 = t0 & 15;
+                    const int off = (((4 * (mt >> 1) + (r16 & 3)) ^ t15) << 3) + 4 * (mt & 1);
+#pragma unroll
+                    for (int pt = 0; pt < 2; pt++) {
+                        const uint16_t *pa = FP + pt * DF + off;
+                        const bf16x4 a0v = tr_read(pa + t0 * FR), a1v = tr_read(pa + (t0 + 16) * FR);
+                        const bf16x8 Av = __builtin_shufflevector(a0v, a1v, 0, 1, 2, 3, 4, 5, 6, 7);
+                        sacc = mfma16(Av, Bones, sacc);
+                    }
+                }
+                if (r16 == 0) {   // column 0 of the result tile: features 16 mt + 4 g4 + 0..3
+                    float4 *sp = reinterpret_cast<float4 *>(&s_l[16 * mt + 4 * g4]);
+                    float4 sv = *sp;
+                    sv.x += sacc[0]; sv.y += sacc[1]; sv.z += sacc[2]; sv.w += sacc[3];
+                    *sp = sv;
+                }
+            }
+        }
+        // ---- 5. compaction, second half: entrants take the leavers' slots (rows of the state, features, indices)
+#pragma unroll
+        for (int it = 0; it < CIT; it++) {
+            const int o = tid + NTH * it;
+            if (o < ne * 2 * PR) {
+                const int x = o / (2 * PR), rem = o % (2 * PR);
+                bf16_t *dst = ((rem >= PR) ? sp_v : sp_k) + (size_t)eslot[x] * DH;
+                reinterpret_cast<uint4 *>(dst)[rem % PR] = cp[it];
+            }
+        }
+#pragma unroll
+        for (int it = 0; it < PIT; it++) {
+            const int o = tid + NTH * it;
+            if (o < ne * (FR / 8)) reinterpret_cast<uint4 *>(phiE + (size_t)eslot[o / (FR / 8)] * FR)[o % (FR / 8)] = fe[it];
+        }
+        for (int x = tid; x < ne; x += NTH) {
+            const int e = ecand[x], sl = eslot[x];
+            const int ti = cidx[e];
+            sp_idx[sl] = ti;
+            cidx[sl] = ti;
+            sp_row[sl] = vrow_l + (e - LAM);
+        }
+        __syncthreads();   // (workgroup scope is enough: only this workgroup reads the stream's memories before the kernel ends)
+        if (a.sel_trace) {
+            int32_t *tr = a.sel_trace + ((size_t)si * a.n_chunks + j) * LAM;
+            for (int sl = tid; sl < LAM; sl += NTH) tr[sl] = cidx[sl];
+        }
+    }
+    if (started) {
+        float *hrow = Hg + (size_t)(16 * w0 + (tid0 & 15)) * DF + 4 * ((tid0 & 63) >> 4);
+#pragma unroll
+        for (int mt = 0; mt < NMT; mt++) *reinterpret_cast<f32x4 *>(hrow + 16 * mt) = hacc[mt];
+        for (int x = tid0; x < DF; x += NTH) sg[x] = s_l[x];
+    }
+    if (tid0 == 0) a.next_j[si] = j;
+}
+
 
 // ---------------------------------------------------------------------------------------------
 // State evolution of the prefill WITHOUT a sparse cache (sparse budget 0: the sliding-window + linear-attention

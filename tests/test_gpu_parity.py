@@ -481,8 +481,34 @@ def test_paper_scale_cache_parameters(eta, lam, chunk):
     layer, o, rep = P.prefill_parity(sh, q[:, :, :T], k[:, :, :T], v[:, :, :T], Wq, Wk)
     rep2 = P.decode_parity(sh, layer, o, *steps(q, k, v, T, 3), Wq, Wk)
     say("paper-scale cache", eta, lam, chunk, layer.lola_path, rep, rep2)
-    assert layer.lola_path[0] == ("mixed" if chunk == 64 else "generic")   # chunk 64: outputs from the MFMA output kernel
+    assert layer.lola_path[0] == ("mfma" if chunk == 64 else "generic")   # chunk 64: the run-time-parameter MFMA kernels
     assert rep["scored"] >= 5 and rep2["scored"] - rep["scored"] == 3
+
+
+@pytest.mark.parametrize("d,D,eta,lam,phi_kind", [(128, 256, 128, 192, 0), (128, 128, 128, 64, 1), (64, 128, 192, 320, 0),
+                                                  (64, 256, 64, 128, 1), (128, 128, 64, 512, 0)])
+def test_run_time_window_and_budget_on_the_mfma_prefill_kernels(d, D, eta, lam, phi_kind):
+    """The MFMA state-evolution and output kernels with run-time window and sparse budget (multiples of 64) at every
+    head / feature dimension they are built for, both feature maps.  Three calls on one state: from empty memories with
+    a ragged tail, a resumed call that starts mid-chunk (the generic kernel takes the irregular chunks) and one
+    processed in several workspace passes; the selection of every chunk is compared; then generation steps."""
+    sh = wl.Shape("wide", "bf16", 2, 4, 2, d, D, T=0, eta=eta, lam=lam, C=64, seed=0)
+    n_fill = (eta + lam) // 64
+    cuts = [0, 64 * (n_fill + 3) + 23]
+    cuts.append(cuts[-1] + 64 * 3)
+    cuts.append(cuts[-1] + 64 * 6 + 7)
+    nd = 3
+    q, k, v, Wq, Wk = rand_case(700 + d + D + eta + lam, 2, 4, 2, d, D, cuts[-1] + nd, "bf16", wscale=0.5 if phi_kind else 1.0)
+    kw = dict(phi_kind=phi_kind)
+    layer, o = None, None
+    for i in range(3):
+        a, b = cuts[i], cuts[i + 1]
+        layer, o, rep = P.prefill_parity(sh, q[:, :, a:b], k[:, :, a:b], v[:, :, a:b], Wq, Wk, layer=layer, oracle=o, layer_kw=kw,
+                                         workspace_limit=0 if i == 2 else None)
+        assert layer.lola_path[0] == "mfma"
+        say("run-time window / budget, call", i, rep)
+    rep2 = P.decode_parity(sh, layer, o, *steps(q, k, v, cuts[3], nd), Wq, Wk)
+    say("run-time window / budget, generation steps", rep2)
 
 
 @pytest.mark.parametrize("d,g,phi_kind", [(128, 4, 0), (64, 4, 0), (128, 2, 1)])
