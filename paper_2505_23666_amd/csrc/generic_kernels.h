@@ -354,6 +354,8 @@ struct DecodeArgs {
     const T *q, *k, *v, *Wq, *Wk;
     void *out;
     int R;          // rows scored per tile
+    const float *ext_score;   // [B*Hkv][lam + 1] self-recall errors of the candidates computed beforehand (steady-state streams), or NULL
+    int no_out;               // 1: the memories are updated only (another kernel computes the outputs)
 };
 
 template <typename T, typename TO>
@@ -431,8 +433,11 @@ __global__ __launch_bounds__(NT) void decode_kernel(DecodeArgs<T> a) {
                 if (sk) {
                     for (int e = tid; e <= lam; e += NT) score[e] = e < lam ? sp_score[e] : sh_pscore;
                     __syncthreads();
+                } else if (a.ext_score) {
+                    for (int e = tid; e <= lam; e += NT) score[e] = a.ext_score[(size_t)si * (lam + 1) + e];
+                    __syncthreads();
                 }
-                for (int t0 = 0; t0 <= lam && !sk; t0 += R) {
+                for (int t0 = 0; t0 <= lam && !sk && !a.ext_score; t0 += R) {
                     int nr = min(R, lam + 1 - t0);
                     for (int p = tid; p < nr * d; p += NT) {
                         int r = p / d, i = p - r * d, e = t0 + r;
@@ -487,7 +492,7 @@ __global__ __launch_bounds__(NT) void decode_kernel(DecodeArgs<T> a) {
     const int wn = (int)min((int64_t)eta, tok + 1);
     const int nk = spc + wn;
     TO *out = (TO *)a.out;
-    for (int r = 0; r < dm.g; r++) {
+    for (int r = 0; r < dm.g && !a.no_out; r++) {
         const int hq = h * dm.g + r;
         const T *qrow = a.q + ((size_t)b * dm.Hq + hq) * d;
         for (int i = tid; i < d; i += NT) xs[i] = ldf(qrow, i);

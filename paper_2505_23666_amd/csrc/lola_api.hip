@@ -33,6 +33,15 @@ bool fast_decode_ok(const lola_config *c) {
            c->score_kind == LOLA_SCORE_SRE;
 }
 
+// Shapes at which the generation step scores its candidates in a kernel of its own (several workgroups per stream, MFMA)
+// ahead of the shape-generic step kernel; needs the state's step_scores field.
+bool wide_decode_ok(const lola_config *c) {
+    return c->dtype == LOLA_BF16 && (c->head_dim == 128 || c->head_dim == 64) && (c->feat_dim == 128 || c->feat_dim == 256) &&
+           c->sparse_budget >= 64 && c->sparse_budget % 64 == 0 && c->sparse_budget <= 4096 && c->window >= 1 &&
+           c->score_kind == LOLA_SCORE_SRE && !fast_decode_ok(c) && c->n_q_heads / c->n_kv_heads <= 4 &&
+           c->sparse_budget + c->window <= fast::STEP_OUT_NKMAX;
+}
+
 lola_status check_config(const lola_config *c) {
     if (!c) return LOLA_ERR_NULL;
     if (c->dtype != LOLA_F32 && c->dtype != LOLA_BF16) return LOLA_ERR_DTYPE;
@@ -80,6 +89,7 @@ lola_status check_state(const lola_config *c, const lola_state *st) {
         if ((c->window > 0 && !st->win_score) || (c->sparse_budget > 0 && !st->sp_score)) return LOLA_ERR_NULL;
         if (misaligned(st->win_score) || misaligned(st->sp_score)) return LOLA_ERR_ALIGN;
     }
+    if (st->step_scores && misaligned(st->step_scores)) return LOLA_ERR_ALIGN;
     return LOLA_OK;
 }
 
@@ -266,9 +276,53 @@ lola_status run_decode(const lola_config *c, const lola_state *st, const void *q
     if (a.R <= 0) return LOLA_ERR_UNSUPPORTED;
     const size_t lds = 4 * (fixed + (size_t)a.R * (3 * a.dm.d + a.dm.D + 1 + (sk ? a.dm.D : 0)));
     dim3 grid(a.dm.B * a.dm.Hkv), block(generic::NT);
+    a.ext_score = nullptr;
+    a.no_out = 0;
+    bool wide_out = false;
+    if constexpr (std::is_same<T, bf16_t>::value) {
+        if (wide_decode_ok(c) && st->step_scores) {
+            // the candidates' self-recall errors from a kernel of their own: 64 candidates per workgroup, the leaving pair
+            // in one more; streams that are not in steady state (window or cache still filling) are left to the step kernel
+            fast::ScoreWideArgs sa;
+            sa.st = a.st; sa.Wk = a.Wk; sa.scores = st->step_scores;
+            sa.Hkv = a.dm.Hkv; sa.lam = a.dm.lam; sa.eta = a.dm.eta; sa.phi_kind = a.dm.phi_kind;
+            const dim3 gsc((unsigned)(a.dm.lam / 64 + 1), (unsigned)(a.dm.B * a.dm.Hkv));
+            if (c->head_dim == 128) {
+                if (c->feat_dim == 256) hipLaunchKernelGGL((fast::score_wide_kernel<128, 256>), gsc, dim3(256), 0, stream, sa);
+                else hipLaunchKernelGGL((fast::score_wide_kernel<128, 128>), gsc, dim3(256), 0, stream, sa);
+            } else {
+                if (c->feat_dim == 256) hipLaunchKernelGGL((fast::score_wide_kernel<64, 256>), gsc, dim3(256), 0, stream, sa);
+                else hipLaunchKernelGGL((fast::score_wide_kernel<64, 128>), gsc, dim3(256), 0, stream, sa);
+            }
+            LAUNCH_CHECK();
+            a.ext_score = st->step_scores;
+            a.no_out = 1;
+            wide_out = true;
+        }
+    }
     if (c->out_dtype == LOLA_F32) hipLaunchKernelGGL((generic::decode_kernel<T, float>), grid, block, lds, stream, a);
     else hipLaunchKernelGGL((generic::decode_kernel<T, bf16_t>), grid, block, lds, stream, a);
     LAUNCH_CHECK();
+    if constexpr (std::is_same<T, bf16_t>::value) {
+        if (wide_out) {   // the outputs from the updated memories (streams in any state)
+            auto launch = [&](auto *o) {
+                using TO = std::remove_pointer_t<decltype(o)>;
+                fast::StepOutArgs<TO> oa;
+                oa.st = a.st; oa.q = a.q; oa.Wq = a.Wq; oa.out = (TO *)out;
+                oa.Hq = a.dm.Hq; oa.Hkv = a.dm.Hkv; oa.g = a.dm.g; oa.lam = a.dm.lam; oa.eta = a.dm.eta;
+                oa.phi_kind = a.dm.phi_kind; oa.hide = a.dm.hide; oa.scale = a.dm.scale;
+                if (c->head_dim == 128) {
+                    if (c->feat_dim == 256) hipLaunchKernelGGL((fast::step_out_wide_kernel<128, 256, TO>), grid, dim3(256), 0, stream, oa);
+                    else hipLaunchKernelGGL((fast::step_out_wide_kernel<128, 128, TO>), grid, dim3(256), 0, stream, oa);
+                } else {
+                    if (c->feat_dim == 256) hipLaunchKernelGGL((fast::step_out_wide_kernel<64, 256, TO>), grid, dim3(256), 0, stream, oa);
+                    else hipLaunchKernelGGL((fast::step_out_wide_kernel<64, 128, TO>), grid, dim3(256), 0, stream, oa);
+                }
+            };
+            if (c->out_dtype == LOLA_F32) launch((float *)nullptr); else launch((bf16_t *)nullptr);
+            LAUNCH_CHECK();
+        }
+    }
     return LOLA_OK;
 }
 
@@ -631,17 +685,17 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
 
 extern "C" {
 
-size_t lola_state_bytes(const lola_config *c, size_t fb[14]) {
+size_t lola_state_bytes(const lola_config *c, size_t fb[15]) {
     if (check_config(c) != LOLA_OK) return 0;
     const size_t ns = (size_t)c->batch * c->n_kv_heads, es = esize(c->dtype);
     const size_t d = c->head_dim, D = c->feat_dim, eta = c->window, lam = c->sparse_budget, R = c->fold_defer;
     const size_t sk = c->score_kind != LOLA_SCORE_SRE ? 1 : 0;
-    size_t f[14] = {ns * D * d * 4, ns * D * 4, ns * eta * d * es, ns * eta * d * es, ns * lam * d * es,
+    size_t f[15] = {ns * D * d * 4, ns * D * 4, ns * eta * d * es, ns * eta * d * es, ns * lam * d * es,
                     ns * lam * d * es, ns * lam * 4, ns * 4, ns * 8,
                     ns * R * D * 4, ns * R * d * 4, R ? ns * 4 : 0,
-                    sk * ns * eta * 4, sk * ns * lam * 4};
+                    sk * ns * eta * 4, sk * ns * lam * 4, wide_decode_ok(c) ? ns * (lam + 1) * 4 : 0};
     size_t tot = 0;
-    for (int i = 0; i < 14; i++) { if (fb) fb[i] = f[i]; tot += f[i]; }
+    for (int i = 0; i < 15; i++) { if (fb) fb[i] = f[i]; tot += f[i]; }
     return tot;
 }
 
@@ -662,13 +716,14 @@ lola_status lola_state_init(const lola_config *c, const lola_state *st, void *st
     if (rc != LOLA_OK) return rc;
     rc = check_state(c, st);
     if (rc != LOLA_OK) return rc;
-    size_t fb[14];
+    size_t fb[15];
     lola_state_bytes(c, fb);
     const bool sk = c->score_kind != LOLA_SCORE_SRE;
-    void *ptrs[14] = {st->H, st->s, st->win_k, st->win_v, st->sp_k, st->sp_v, st->sp_idx, st->sp_count, st->n_tokens,
+    void *ptrs[15] = {st->H, st->s, st->win_k, st->win_v, st->sp_k, st->sp_v, st->sp_idx, st->sp_count, st->n_tokens,
                       c->fold_defer ? st->pend_phi : nullptr, c->fold_defer ? st->pend_v : nullptr,
-                      c->fold_defer ? st->pend_count : nullptr, sk ? st->win_score : nullptr, sk ? st->sp_score : nullptr};
-    for (int i = 0; i < 14; i++) {
+                      c->fold_defer ? st->pend_count : nullptr, sk ? st->win_score : nullptr, sk ? st->sp_score : nullptr,
+                      st->step_scores};
+    for (int i = 0; i < 15; i++) {
         if (!ptrs[i] || fb[i] == 0) continue;
         size_t n = fb[i] / 4;   // every field is a multiple of 4 bytes (head_dim is even)
         unsigned blocks = (unsigned)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
@@ -799,6 +854,7 @@ const char *lola_status_str(lola_status s) {
 const char *lola_kernel_path(const lola_config *c, int32_t which) {
     if (check_config(c) != LOLA_OK) return "invalid";
     if (which == 1 && fast_decode_ok(c)) return "mfma";
+    if (which == 1 && wide_decode_ok(c)) return "mixed";   // scoring on MFMA (with the state's step_scores), the rest shape-generic
     if (which == 0 && (fast_attend_ok(c) || wide_scan_ok(c))) return "mfma";
     if (which == 0 && (fast_output_ok(c) || wide_output_ok(c))) return "mixed";
     return "generic";

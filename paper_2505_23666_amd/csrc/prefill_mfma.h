@@ -1287,11 +1287,14 @@ __global__ __launch_bounds__(256) void phi_wide_kernel(generic::PrefillArgs<bf16
 template <int DH, int DF>
 __global__ __launch_bounds__(DH * 4) void scan_wide_kernel(generic::PrefillArgs<bf16_t> a) {
     constexpr int C = 64, NW = DH / 16, NTH = 64 * NW, KF = DF / 32, NMT = DF / 16, PR = DH / 8, FR = 2 * DF, PP = DF / 8;
-    constexpr int RB = 8192 / DF, TB = RB / 16;            // candidates per batch: 32 KB of features
+    constexpr int RB = 32, TB = RB / 16;                   // candidates per batch
+    constexpr int NBUF = DF == 256 ? 3 : 4;                // batch buffers in LDS: requests run NBUF - 1 batches ahead
+    constexpr int LPB = RB * FR / 512 / NW + 1;            // direct loads per wavefront and batch: features, then values
+    static_assert(RB * DH / 512 == NW, "one instruction per wavefront covers the values of a batch");
     constexpr int NEMAX = 1024 + C, NKMAX = NEMAX / 64;
     constexpr int BUF = RB * FR + RB * DH;                 // 16-bit elements of one batch buffer: features, then values
     constexpr int FOLD = C * FR + C * DH;                  // the folded pairs' features and values
-    constexpr int POOL = 2 * BUF > FOLD ? 2 * BUF : FOLD;
+    constexpr int POOL = NBUF * BUF > FOLD ? NBUF * BUF : FOLD;
     static_assert((DH == 64 || DH == 128) && (DF == 128 || DF == 256), "shape");
     __shared__ __attribute__((aligned(16))) uint16_t pool[POOL];
     __shared__ __attribute__((aligned(16))) float s_l[DF];
@@ -1357,6 +1360,12 @@ __global__ __launch_bounds__(DH * 4) void scan_wide_kernel(generic::PrefillArgs<
         };
         auto phirow = [&](int e) -> const uint16_t * { return e < LAM ? phiE + (size_t)e * FR : phk + (size_t)(e - LAM) * FR; };
 
+        // the snapshot's row list is read before anything else is requested or stored (the memory counter is in order)
+        constexpr int NSP = 1024 / NTH;
+        int sprow_ld[NSP];
+#pragma unroll
+        for (int x = 0; x < NSP; x++) sprow_ld[x] = (a.want_out && tid + NTH * x < LAM) ? sp_row[tid + NTH * x] : 0;
+
         // ---- 1. operands of the recall GEMM from the fp32 registers; they are the snapshot's pieces as well
         bf16x8 Ahi[KF], Alo[KF];
 #pragma unroll
@@ -1379,18 +1388,15 @@ __global__ __launch_bounds__(DH * 4) void scan_wide_kernel(generic::PrefillArgs<
                 __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
                                                  (__attribute__((address_space(3))) void *)(PBb + 512 * i), 16, 0, 0);
             }
-#pragma unroll
-            for (int it = 0; it < (RB * DH / 512 + NW - 1) / NW; it++) {
-                const int i = w + NW * it;
-                if (i < RB * DH / 512) {
-                    const int g = 512 * i + 8 * lane, row = g / DH, slot = (g % DH) >> 3;
-                    const bf16_t *src = vrow(e0 + row) + ((slot ^ (row & (PR - 1))) << 3);
-                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                                     (__attribute__((address_space(3))) void *)(VBb + 512 * i), 16, 0, 0);
-                }
+            {
+                const int g = 512 * w + 8 * lane, row = g / DH, slot = (g % DH) >> 3;
+                const bf16_t *src = vrow(e0 + row) + ((slot ^ (row & (PR - 1))) << 3);
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                                 (__attribute__((address_space(3))) void *)(VBb + 512 * w), 16, 0, 0);
             }
         };
-        issue(0, 0);
+        // (the snapshot's stores are issued ahead of the requests: the waits below count on the requests being the youngest
+        // entries of the in-order memory counter)
         if (a.want_out) {
             const size_t sj = (size_t)si * a.S + (j - a.jb);
             uint16_t *s16 = reinterpret_cast<uint16_t *>(a.snapH) + sj * (2 * DF * DH);
@@ -1402,22 +1408,31 @@ __global__ __launch_bounds__(DH * 4) void scan_wide_kernel(generic::PrefillArgs<
                 *reinterpret_cast<uint4 *>(s16 + DF * DH + off) = __builtin_bit_cast(uint4, Alo[ks]);
             }
             for (int x = tid; x < DF / 4; x += NTH) reinterpret_cast<float4 *>(a.snapS + sj * DF)[x] = reinterpret_cast<const float4 *>(s_l)[x];
-            for (int sl = tid; sl < LAM; sl += NTH) a.snapG[sj * LAM + sl] = sp_row[sl];
+#pragma unroll
+            for (int x = 0; x < NSP; x++)
+                if (tid + NTH * x < LAM) a.snapG[sj * LAM + tid + NTH * x] = sprow_ld[x];
         }
+#pragma unroll
+        for (int b = 0; b < NBUF - 1; b++) issue(b, b);   // lambda + 64 >= 128 candidates: at least four batches
 
         // ---- 2. recall error of the candidates, batch by batch
+        int buf = 0;
 #pragma unroll 1
         for (int b = 0; b < NBATCH; b++) {
-            const int buf = b & 1;
-            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wavefront's share of batch b has landed
-            __syncthreads();                      // ... and everybody's; the other buffer's readers (batch b - 1) are done
-            if (b + 1 < NBATCH) issue(b + 1, buf ^ 1);
+            // this wavefront's share of batch b has landed: all but the requests of the batches behind it
+            const int ahead = min(NBUF - 2, NBATCH - 1 - b);
+            if (ahead >= 2) __builtin_amdgcn_s_waitcnt(0x0F70 | ((2 * LPB) & 15) | (((2 * LPB) >> 4) << 14));
+            else if (ahead == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | (LPB & 15) | ((LPB >> 4) << 14));
+            else __builtin_amdgcn_s_waitcnt(0x0F70);
+            __syncthreads();                      // ... and everybody's; the readers of batch b - 1's buffer are done
+            if (b + NBUF - 1 < NBATCH) issue(b + NBUF - 1, buf == 0 ? NBUF - 1 : buf - 1);
             const uint16_t *PBb = pool + buf * BUF, *VBb = PBb + RB * FR;
+            const int pb = b & 1;
             if (b > 0 && tid < 3 * RB) {          // batch b - 1: the wavefronts' sums over their columns, added in a fixed order
                 const int k = tid / RB, r = tid % RB;
                 float sum = 0.f;
 #pragma unroll
-                for (int x = 0; x < NW; x++) sum += part[buf ^ 1][k][x][r];
+                for (int x = 0; x < NW; x++) sum += part[pb ^ 1][k][x][r];
                 tot[k][(b - 1) * RB + r] = sum;
             }
             {   // phi(k).s of the batch's rows: TPR neighbouring lanes share a row
@@ -1466,8 +1481,9 @@ __global__ __launch_bounds__(DH * 4) void scan_wide_kernel(generic::PrefillArgs<
                 sb = fmaf(acc[0], v0, sb); sb = fmaf(acc[1], v1, sb); sb = fmaf(acc[2], v2, sb); sb = fmaf(acc[3], v3, sb);
                 sc = fmaf(v0, v0, sc); sc = fmaf(v1, v1, sc); sc = fmaf(v2, v2, sc); sc = fmaf(v3, v3, sc);
                 const float s3 = grp_sum3(sa, sb, sc);   // lane group g4 holds sum g4
-                if (g4 < 3) part[buf][g4][w][16 * u + r16] = s3;
+                if (g4 < 3) part[pb][g4][w][16 * u + r16] = s3;
             }
+            buf = buf == NBUF - 1 ? 0 : buf + 1;
         }
         __syncthreads();
         if (tid < 3 * RB) {
@@ -1670,6 +1686,326 @@ __global__ __launch_bounds__(DH * 4) void scan_wide_kernel(generic::PrefillArgs<
         for (int x = tid0; x < DF; x += NTH) sg[x] = s_l[x];
     }
     if (tid0 == 0) a.next_j[si] = j;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Self-recall errors of the lambda + 1 candidates of a generation step (Sec. 3.2, eq. sre: the sparse cache and the
+// pair that leaves the window, scored with the state before the step's fold) as a kernel of its own, for sparse budgets
+// in multiples of 64 and 128 or 256 features: grid (lambda / 64 + 1, stream), one wavefront per 16 candidates, the
+// last block's wavefront 0 the leaving pair.  No LDS and no barriers: a wavefront computes phi of its keys
+// (Sec. 2.3 eq. feature_map) on MFMA, keeps it as the B operand of the recall GEMM (bf16 high + low parts) and walks
+// over the 16-row tiles of H^T, read from memory and split on the way (the streams' H^T stay in L2 between the
+// blocks that read them).  Streams outside the steady state (window or cache still filling) are skipped.
+struct ScoreWideArgs {
+    State<bf16_t> st;
+    const bf16_t *Wk;
+    float *scores;        // [stream][lam + 1]
+    int Hkv, lam, eta, phi_kind;
+};
+
+template <int DH, int DF>
+__global__ __launch_bounds__(256) void score_wide_kernel(ScoreWideArgs a) {
+    constexpr int M = DF / 2, KS = DH / 32, NZT = M / 16, KF = DF / 32, NCT = DH / 16;
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r16 = lane & 15, g4 = lane >> 4;
+    const int si = blockIdx.y, h = si % a.Hkv, LAM = a.lam, ETA = a.eta;
+    const int64_t tok = a.st.n_tokens[si];
+    if (!(tok >= (int64_t)ETA && a.st.sp_count[si] == LAM)) return;
+    const bool tail = (int)blockIdx.x == LAM / 64;   // the leaving pair: every column of wavefront 0's tile holds it
+    if (tail && w != 0) return;
+    const int e = tail ? LAM : 64 * (int)blockIdx.x + 16 * w + r16;
+    const int slot = (int)(tok % ETA);
+    const bf16_t *kr = tail ? a.st.win_k + ((size_t)si * ETA + slot) * DH : a.st.sp_k + ((size_t)si * LAM + e) * DH;
+    const bf16_t *vr = tail ? a.st.win_v + ((size_t)si * ETA + slot) * DH : a.st.sp_v + ((size_t)si * LAM + e) * DH;
+    const bf16_t *Wk = a.Wk + (size_t)h * M * DH;
+    const float *Hg = a.st.H + (size_t)si * DF * DH, *sg = a.st.s + (size_t)si * DF;
+
+    bf16x8 BK[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) BK[ks] = ld_bf16x8(kr + 32 * ks + 8 * g4);
+    f32x4 zt[NZT];
+#pragma unroll
+    for (int mt = 0; mt < NZT; mt++) {
+        zt[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ks++)
+            zt[mt] = mfma16(ld_bf16x8(Wk + (size_t)(16 * mt + r16) * DH + 32 * ks + 8 * g4), BK[ks], zt[mt]);
+    }
+    float pp[4 * NZT], pn[4 * NZT];
+    phi_from_z_tiles<NZT>(zt, a.phi_kind, pp, pn);
+    // phi(k).s: the lane holds features 16 mt + 4 g4 + i of both halves
+    float dn = 0.f;
+#pragma unroll
+    for (int mt = 0; mt < NZT; mt++) {
+        const float4 sp4 = *reinterpret_cast<const float4 *>(sg + 16 * mt + 4 * g4);
+        const float4 sn4 = *reinterpret_cast<const float4 *>(sg + M + 16 * mt + 4 * g4);
+        dn = fmaf(pp[4 * mt], sp4.x, dn); dn = fmaf(pp[4 * mt + 1], sp4.y, dn);
+        dn = fmaf(pp[4 * mt + 2], sp4.z, dn); dn = fmaf(pp[4 * mt + 3], sp4.w, dn);
+        dn = fmaf(pn[4 * mt], sn4.x, dn); dn = fmaf(pn[4 * mt + 1], sn4.y, dn);
+        dn = fmaf(pn[4 * mt + 2], sn4.z, dn); dn = fmaf(pn[4 * mt + 3], sn4.w, dn);
+    }
+    dn = grp_sum(dn);
+    const float rd = dn > 0.f ? 1.0f / dn : 0.f;   // recall = 0 while nothing was folded
+    // B operands: k-step ks of the contraction over the features holds 32 ks + 16 (x / 4) + 4 g4 + x % 4, x < 8
+    bf16x8 Bh[KF], Bl[KF];
+#pragma unroll
+    for (int ks = 0; ks < KF / 2; ks++) {
+        split8(&pp[8 * ks], Bh[ks], Bl[ks]);
+        split8(&pn[8 * ks], Bh[KF / 2 + ks], Bl[KF / 2 + ks]);
+    }
+    float esum = 0.f;
+#pragma unroll 2
+    for (int ct = 0; ct < NCT; ct++) {
+        const float *hrow = Hg + (size_t)(16 * ct + r16) * DF + 4 * g4;
+        const uint2 vv = *reinterpret_cast<const uint2 *>(vr + 16 * ct + 4 * g4);
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acc2 = {0.f, 0.f, 0.f, 0.f}, acc3 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KF; ks++) {
+            const float4 h0 = *reinterpret_cast<const float4 *>(hrow + 32 * ks), h1 = *reinterpret_cast<const float4 *>(hrow + 32 * ks + 16);
+            const float x8[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
+            bf16x8 Ah, Al;
+            split8(x8, Ah, Al);
+            acc = mfma16(Ah, Bh[ks], acc);
+            acc2 = mfma16(Ah, Bl[ks], acc2);
+            acc3 = mfma16(Al, Bh[ks], acc3);
+        }
+        // lane (candidate r16, group g4): phi(k)^T H at value columns 16 ct + 4 g4 + i
+        const float v4[4] = {bf_lo(vv.x), bf_hi(vv.x), bf_lo(vv.y), bf_hi(vv.y)};
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            const float err = (acc[i] + (acc2[i] + acc3[i])) * rd - v4[i];
+            esum = fmaf(err, err, esum);
+        }
+    }
+    esum = grp_sum(esum);
+    if (g4 == 0 && (!tail || r16 == 0)) a.scores[(size_t)si * (LAM + 1) + e] = sqrtf(esum);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Outputs of a generation step from the memories as the step's update left them (Sec. 3.1 eq. lola_output with the
+// shared normaliser: softmax part over the sparse cache and the window, linear part phi(q)^T H, phi(q)^T s), for any
+// window and sparse budget with at most NKMAX keys, 128 or 256 features and up to four query heads per kv head.  One
+// workgroup per stream, four wavefronts:
+//   1. logits Q K^T on MFMA (A = the group's queries, B = 16 keys straight from memory), tiles dealt round-robin;
+//   2. phi of query w by wavefront w (projection on MFMA with the query in every column);
+//   3. m = max(0, max logit) and the weights e^(l - m) per query, left in LDS as bf16 high + low parts;
+//   4. weights x values on MFMA: each wavefront stages blocks of 32 value rows in its own LDS tile (direct loads, two
+//      tiles in flight) and reads them as B operand through the transposing LDS read;
+//   5. phi(q)^T H on MFMA with H^T read from memory and split into bf16 high + low parts on the way;
+//   6. y = (sum w v + e^(-m) phi(q)^T H) / (sum w + e^(-m) phi(q)^T s).
+template <typename TO>
+struct StepOutArgs {
+    State<bf16_t> st;
+    const bf16_t *q, *Wq;
+    TO *out;
+    int Hq, Hkv, g, lam, eta, phi_kind, hide;
+    float scale;
+};
+
+constexpr int STEP_OUT_NKMAX = 3072;
+
+template <int DH, int DF, typename TO>
+__global__ __launch_bounds__(256) void step_out_wide_kernel(StepOutArgs<TO> a) {
+    constexpr int M = DF / 2, KS = DH / 32, NZT = M / 16, KF = DF / 32, NCT = DH / 16, PR = DH / 8, G = 4, NKMAX = STEP_OUT_NKMAX;
+    __shared__ __attribute__((aligned(16))) float lg[G][NKMAX];              // logits; then per 4 keys: 4 high parts, 4 low parts
+    __shared__ __attribute__((aligned(16))) uint16_t VS[4][2][32 * DH];      // per wavefront: two blocks of 32 value rows
+    __shared__ __attribute__((aligned(16))) uint16_t PQ[G][2][DF];           // phi(q), operand order, high / low parts
+    __shared__ __attribute__((aligned(16))) float outp[4][G][DH];            // per wavefront: its keys' share of sum w v
+    __shared__ __attribute__((aligned(16))) float lin_l[G][DH];
+    __shared__ float m_l[G], psum_l[G], denq_l[G];
+
+    const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, r16 = lane & 15, g4 = lane >> 4;
+    const int si = blockIdx.x, b = si / a.Hkv, h = si - b * a.Hkv, g = a.g, LAM = a.lam, ETA = a.eta;
+    const int64_t tok = a.st.n_tokens[si];                    // tokens consumed, this step's included
+    const int spc = a.st.sp_count[si];
+    const int wn = (int)min((int64_t)ETA, tok), nk = spc + wn, KPAD = (nk + 31) & ~31;
+    const bf16_t *sp_k = a.st.sp_k + (size_t)si * LAM * DH, *sp_v = a.st.sp_v + (size_t)si * LAM * DH;
+    const bf16_t *win_k = a.st.win_k + (size_t)si * ETA * DH, *win_v = a.st.win_v + (size_t)si * ETA * DH;
+    const float *Hg = a.st.H + (size_t)si * DF * DH, *sg = a.st.s + (size_t)si * DF;
+    const bf16_t *qg = a.q + ((size_t)b * a.Hq + (size_t)h * g) * DH;   // g consecutive query rows
+
+    if (tid < G) { m_l[tid] = 0.f; psum_l[tid] = 0.f; denq_l[tid] = 0.f; }
+    for (int x = tid; x < G * 2 * DF / 8; x += 256) reinterpret_cast<uint4 *>(PQ)[x] = make_uint4(0, 0, 0, 0);
+    __syncthreads();
+
+    // ---- 1. logits
+    {
+        bf16x8 AQ[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ks++) AQ[ks] = r16 < g ? ld_bf16x8(qg + (size_t)r16 * DH + 32 * ks + 8 * g4) : zero_bf16x8();
+        for (int t = w; t < KPAD / 16; t += 4) {
+            const int key = 16 * t + r16;
+            const bool valid = key < nk;
+            const bf16_t *kr = key < spc ? sp_k + (size_t)key * DH : win_k + (size_t)(valid ? key - spc : 0) * DH;
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ks++) acc = mfma16(AQ[ks], ld_bf16x8(kr + 32 * ks + 8 * g4), acc);
+            if (g4 == 0) {   // rows 0..3 of the tile: the queries
+                const bool hidden = !valid || ((a.hide & 2) && key < spc);   // restricted query: the sparse cache is not read
+#pragma unroll
+                for (int i = 0; i < G; i++) lg[i][key] = hidden ? -INFINITY : acc[i] * a.scale;
+            }
+        }
+    }
+    // ---- 2. phi of query w (Sec. 2.3 eq. feature_map) and phi(q).s
+    if (w < g) {
+        const bf16_t *Wq = a.Wq + ((size_t)h * g + w) * M * DH;
+        bf16x8 BQ[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ks++) BQ[ks] = ld_bf16x8(qg + (size_t)w * DH + 32 * ks + 8 * g4);
+        f32x4 zt[NZT];
+#pragma unroll
+        for (int mt = 0; mt < NZT; mt++) {
+            zt[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ks++)
+                zt[mt] = mfma16(ld_bf16x8(Wq + (size_t)(16 * mt + r16) * DH + 32 * ks + 8 * g4), BQ[ks], zt[mt]);
+        }
+        float pp[4 * NZT], pn[4 * NZT];
+        phi_from_z_tiles<NZT>(zt, a.phi_kind, pp, pn);
+        float dn = 0.f;
+#pragma unroll
+        for (int mt = 0; mt < NZT; mt++) {
+            const float4 sp4 = *reinterpret_cast<const float4 *>(sg + 16 * mt + 4 * g4);
+            const float4 sn4 = *reinterpret_cast<const float4 *>(sg + M + 16 * mt + 4 * g4);
+            dn = fmaf(pp[4 * mt], sp4.x, dn); dn = fmaf(pp[4 * mt + 1], sp4.y, dn);
+            dn = fmaf(pp[4 * mt + 2], sp4.z, dn); dn = fmaf(pp[4 * mt + 3], sp4.w, dn);
+            dn = fmaf(pn[4 * mt], sn4.x, dn); dn = fmaf(pn[4 * mt + 1], sn4.y, dn);
+            dn = fmaf(pn[4 * mt + 2], sn4.z, dn); dn = fmaf(pn[4 * mt + 3], sn4.w, dn);
+        }
+        dn = grp_sum(dn);
+        if (lane == 0) denq_l[w] = dn;
+        if (r16 == 0) {   // every column holds the same query: column 0 stores
+#pragma unroll
+            for (int ks = 0; ks < KF / 2; ks++) {
+                bf16x8 hi, lo;
+                split8(&pp[8 * ks], hi, lo);
+                *reinterpret_cast<uint4 *>(&PQ[w][0][(4 * ks + g4) << 3]) = __builtin_bit_cast(uint4, hi);
+                *reinterpret_cast<uint4 *>(&PQ[w][1][(4 * ks + g4) << 3]) = __builtin_bit_cast(uint4, lo);
+                split8(&pn[8 * ks], hi, lo);
+                *reinterpret_cast<uint4 *>(&PQ[w][0][(4 * (KF / 2 + ks) + g4) << 3]) = __builtin_bit_cast(uint4, hi);
+                *reinterpret_cast<uint4 *>(&PQ[w][1][(4 * (KF / 2 + ks) + g4) << 3]) = __builtin_bit_cast(uint4, lo);
+            }
+        }
+    }
+    __syncthreads();
+    // ---- 3. weights of query w: m = max(0, max logit) (the linear terms carry weight e^(-m) <= 1)
+    if (w < g) {
+        float mx = 0.f;
+        for (int x = lane; x < KPAD / 4; x += 64) {
+            const float4 l4 = reinterpret_cast<const float4 *>(lg[w])[x];
+            mx = fmaxf(mx, fmaxf(fmaxf(l4.x, l4.y), fmaxf(l4.z, l4.w)));
+        }
+        mx = wmax(mx);
+        float ps = 0.f;
+        for (int x = lane; x < KPAD / 4; x += 64) {
+            const float4 l4 = reinterpret_cast<const float4 *>(lg[w])[x];
+            const float p[4] = {fexp2((l4.x - mx) * LOG2E), fexp2((l4.y - mx) * LOG2E), fexp2((l4.z - mx) * LOG2E), fexp2((l4.w - mx) * LOG2E)};
+            uint32_t hi[2], lo[2];
+#pragma unroll
+            for (int y = 0; y < 2; y++) {
+                const uint16_t h0 = f32_to_bf16_bits(p[2 * y]), h1 = f32_to_bf16_bits(p[2 * y + 1]);
+                const float r0 = p[2 * y] - __uint_as_float((uint32_t)h0 << 16), r1 = p[2 * y + 1] - __uint_as_float((uint32_t)h1 << 16);
+                hi[y] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+                lo[y] = (uint32_t)f32_to_bf16_bits(r0) | ((uint32_t)f32_to_bf16_bits(r1) << 16);
+                // (the sum runs over the weights as the MFMAs will see them)
+                ps += (__uint_as_float((uint32_t)h0 << 16) + __uint_as_float((uint32_t)f32_to_bf16_bits(r0) << 16)) +
+                      (__uint_as_float((uint32_t)h1 << 16) + __uint_as_float((uint32_t)f32_to_bf16_bits(r1) << 16));
+            }
+            reinterpret_cast<uint4 *>(lg[w])[x] = make_uint4(hi[0], hi[1], lo[0], lo[1]);
+        }
+        ps = wsum(ps);
+        if (lane == 0) { m_l[w] = mx; psum_l[w] = ps; }
+    }
+    __syncthreads();
+    // ---- 4. sum w v: key blocks of 32 dealt round-robin; A = weights (rows = queries), B = values through the
+    // transposing read (contraction slots of lane group g4: keys 4 g4 + 0..3, then + 16)
+    {
+        f32x4 acc[NCT];
+#pragma unroll
+        for (int ct = 0; ct < NCT; ct++) acc[ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        auto stage = [&](int kb, int buf) {
+            // 1 KB per instruction = 2048 / DH rows; lane l fills bytes 16 l ..: the row's piece (l % PR) ^ (row % PR)
+#pragma unroll
+            for (int i = 0; i < 32 * DH / 512; i++) {
+                const int row = (512 * i + 8 * lane) / DH, slot = lane % PR;
+                int key = 32 * kb + row;
+                if (key >= nk) key = 0;   // weight 0: any readable row will do
+                const bf16_t *vr = key < spc ? sp_v + (size_t)key * DH : win_v + (size_t)(key - spc) * DH;
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(vr + ((slot ^ (row & (PR - 1))) << 3)),
+                                                 (__attribute__((address_space(3))) void *)(&VS[w][buf][512 * i]), 16, 0, 0);
+            }
+        };
+        const int nblk = KPAD / 32;
+        if (w < nblk) stage(w, 0);
+        int buf = 0;
+#pragma unroll 1
+        for (int kb = w; kb < nblk; kb += 4) {
+            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the block has landed (only this wavefront reads it)
+            asm volatile("" ::: "memory");
+            if (kb + 4 < nblk) stage(kb + 4, buf ^ 1);
+            bf16x8 Ahi = zero_bf16x8(), Alo = zero_bf16x8();
+            if (r16 < g) {
+                const uint4 u0 = reinterpret_cast<const uint4 *>(lg[r16])[8 * kb + g4], u1 = reinterpret_cast<const uint4 *>(lg[r16])[8 * kb + 4 + g4];
+                Ahi = as_bf16x8(make_uint4(u0.x, u0.y, u1.x, u1.y));
+                Alo = as_bf16x8(make_uint4(u0.z, u0.w, u1.z, u1.w));
+            }
+            const int t0 = 4 * g4 + (r16 >> 2);
+            const uint16_t *vb = &VS[w][buf][t0 * DH + 4 * (r16 & 1)];
+#pragma unroll
+            for (int ct = 0; ct < NCT; ct++) {
+                const int pc = ((2 * ct + ((r16 & 3) >> 1)) ^ (t0 & (PR - 1))) << 3;
+                const bf16x4 b0 = tr_read(vb + pc), b1 = tr_read(vb + 16 * DH + pc);
+                const bf16x8 Bv = __builtin_shufflevector(b0, b1, 0, 1, 2, 3, 4, 5, 6, 7);
+                acc[ct] = mfma16(Ahi, Bv, acc[ct]);
+                acc[ct] = mfma16(Alo, Bv, acc[ct]);
+            }
+            buf ^= 1;
+        }
+        if (g4 == 0) {   // lane (column r16 of tile ct): rows 0..3 = the queries
+#pragma unroll
+            for (int ct = 0; ct < NCT; ct++)
+#pragma unroll
+                for (int i = 0; i < G; i++) outp[w][i][16 * ct + r16] = acc[ct][i];
+        }
+    }
+    // ---- 5. phi(q)^T H: column tiles w, w + 4, ...; A = phi(q) (rows = queries), B = 16 rows of H^T
+    {
+        bf16x8 Ahi[KF], Alo[KF];
+#pragma unroll
+        for (int ks = 0; ks < KF; ks++) {
+            Ahi[ks] = r16 < G ? as_bf16x8(*reinterpret_cast<const uint4 *>(&PQ[r16][0][(4 * ks + g4) << 3])) : zero_bf16x8();
+            Alo[ks] = r16 < G ? as_bf16x8(*reinterpret_cast<const uint4 *>(&PQ[r16][1][(4 * ks + g4) << 3])) : zero_bf16x8();
+        }
+#pragma unroll
+        for (int x = 0; x < NCT / 4; x++) {
+            const int ct = w + 4 * x;
+            const float *hrow = Hg + (size_t)(16 * ct + r16) * DF + 4 * g4;
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acc2 = {0.f, 0.f, 0.f, 0.f}, acc3 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KF; ks++) {
+                const float4 h0 = *reinterpret_cast<const float4 *>(hrow + 32 * ks), h1 = *reinterpret_cast<const float4 *>(hrow + 32 * ks + 16);
+                const float x8[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
+                bf16x8 Bh, Bl;
+                split8(x8, Bh, Bl);
+                acc = mfma16(Ahi[ks], Bh, acc);
+                acc2 = mfma16(Ahi[ks], Bl, acc2);
+                acc3 = mfma16(Alo[ks], Bh, acc3);
+            }
+            if (g4 == 0) {
+#pragma unroll
+                for (int i = 0; i < G; i++) lin_l[i][16 * ct + r16] = acc[i] + (acc2[i] + acc3[i]);
+            }
+        }
+    }
+    __syncthreads();
+    // ---- 6. outputs
+    for (int o = tid; o < g * DH; o += 256) {
+        const int qi = o / DH, c = o - qi * DH;
+        const float elin = (a.hide & 1) ? 0.f : fexp2(-m_l[qi] * LOG2E);   // restricted query: the hidden state is not read
+        const float num = (outp[0][qi][c] + outp[1][qi][c]) + (outp[2][qi][c] + outp[3][qi][c]) + elin * lin_l[qi][c];
+        const float val = num / (psum_l[qi] + elin * denq_l[qi]);
+        stf(a.out, ((size_t)b * a.Hq + (size_t)h * g + qi) * DH + c, val);
+    }
 }
 
 
