@@ -33,13 +33,17 @@ bool fast_decode_ok(const lola_config *c) {
            c->score_kind == LOLA_SCORE_SRE;
 }
 
-// Shapes at which the generation step scores its candidates in a kernel of its own (several workgroups per stream, MFMA)
-// ahead of the shape-generic step kernel; needs the state's step_scores field.
-bool wide_decode_ok(const lola_config *c) {
+// Shapes at which the outputs of the generation step come from the MFMA output kernel (any window and sparse budget up
+// to its key limit, 128 or 256 features), the shape-generic kernel keeping the update of the memories ...
+bool wide_step_out_ok(const lola_config *c) {
     return c->dtype == LOLA_BF16 && (c->head_dim == 128 || c->head_dim == 64) && (c->feat_dim == 128 || c->feat_dim == 256) &&
-           c->sparse_budget >= 64 && c->sparse_budget % 64 == 0 && c->sparse_budget <= 4096 && c->window >= 1 &&
-           c->score_kind == LOLA_SCORE_SRE && !fast_decode_ok(c) && c->n_q_heads / c->n_kv_heads <= 4 &&
+           c->window >= 1 && c->score_kind == LOLA_SCORE_SRE && !fast_decode_ok(c) && c->n_q_heads / c->n_kv_heads <= 4 &&
            c->sparse_budget + c->window <= fast::STEP_OUT_NKMAX;
+}
+// ... and at which the candidates are scored by a kernel of their own ahead of it (several workgroups per stream, MFMA;
+// sparse budgets in multiples of 64); needs the state's step_scores field.
+bool wide_decode_ok(const lola_config *c) {
+    return wide_step_out_ok(c) && c->sparse_budget >= 64 && c->sparse_budget % 64 == 0;
 }
 
 lola_status check_config(const lola_config *c) {
@@ -296,6 +300,8 @@ lola_status run_decode(const lola_config *c, const lola_state *st, const void *q
             }
             LAUNCH_CHECK();
             a.ext_score = st->step_scores;
+        }
+        if (wide_step_out_ok(c)) {
             a.no_out = 1;
             wide_out = true;
         }
@@ -854,7 +860,7 @@ const char *lola_status_str(lola_status s) {
 const char *lola_kernel_path(const lola_config *c, int32_t which) {
     if (check_config(c) != LOLA_OK) return "invalid";
     if (which == 1 && fast_decode_ok(c)) return "mfma";
-    if (which == 1 && wide_decode_ok(c)) return "mixed";   // scoring on MFMA (with the state's step_scores), the rest shape-generic
+    if (which == 1 && wide_step_out_ok(c)) return "mixed";   // outputs (and, with the state's step_scores, the scoring) on MFMA
     if (which == 0 && (fast_attend_ok(c) || wide_scan_ok(c))) return "mfma";
     if (which == 0 && (fast_output_ok(c) || wide_output_ok(c))) return "mixed";
     return "generic";
