@@ -72,13 +72,15 @@ def prefill_alg_flops(sh):
     return per_chunk, per_chunk * (sh.T // C_) * sh.B * sh.Hkv
 
 
-def extras(torch, wl, lb, dev):
+def extras(torch, wl, lb, dev, only=None):
     """Side measurements: one prefill call with outputs and a run of generation steps per mode, bf16, seeded N(0,1)
     inputs; tokens/s per layer from HIP events.  Not the headline metric: context for the rows built beside it."""
     def to_dev(x):
         return torch.from_numpy(wl.bf16_bits(x).view(np.int16)).to(dev).view(torch.bfloat16)
 
     def run(label, B, Hq, Hkv, d, D, eta, lam, Cc, T, n_dec, **kw):
+        if only and only not in label:
+            return None
         g = wl.rng(11, 3)
         mk = lambda *shape: to_dev(wl.store(g.standard_normal(shape, dtype=np.float32), "bf16"))
         q, k, v = mk(B, Hq, T, d), mk(B, Hkv, T, d), mk(B, Hkv, T, d)
@@ -133,6 +135,8 @@ def extras(torch, wl, lb, dev):
     rows.append(run("long-context cache parameters eta=lambda=256, D=2d", eta=256, lam=256, **long))
     rows.append(run("long-context cache parameters eta=lambda=512, D=2d", eta=512, lam=512, **long))
     rows.append(run("long-context cache parameters eta=128, lambda=768, D=2d", eta=128, lam=768, **long))
+    rows.append(run("long-context cache parameters eta=512, lambda=1024, D=2d", eta=512, lam=1024, **long))
+    rows.append(run("long-context cache parameters eta=lambda=256, D=2d, batch 32", eta=256, lam=256, **dict(long, B=32, T=1024)))
     rows.append(run("no sparse cache (sliding window + linear attention base model), window 64", B=4, Hq=32, Hkv=8, d=128, D=128, eta=64,
                     lam=0, Cc=64, T=2048, n_dec=36))
     rows.append(run("no sparse cache, window 192 (ablation: extended window)", B=4, Hq=32, Hkv=8, d=128, D=128, eta=192, lam=0, Cc=64, T=2048, n_dec=36))
@@ -140,7 +144,7 @@ def extras(torch, wl, lb, dev):
     # head_dim 128, T = 4096, eta = 64, lambda = 128) except for the feature dimension (128 here, 2 d there)
     rows.append(run("layer-latency table shape: batch 2, 32 heads (no grouping), T 4096", B=2, Hq=32, Hkv=32, d=128, D=128, eta=64, lam=128,
                     Cc=64, T=4096, n_dec=36, fold_defer=8))
-    return {"metric": "LoLA layer side modes, tokens/s/layer", "data": "synthetic", "dtype": "bf16", "rows": rows}
+    return {"metric": "LoLA layer side modes, tokens/s/layer", "data": "synthetic", "dtype": "bf16", "rows": [r for r in rows if r]}
 
 
 def main():
@@ -158,6 +162,7 @@ def main():
     ap.add_argument("--extras", action="store_true",
                     help="instead of the benchmark proper, time the layer's other modes (restricted queries, query-dependent "
                          "scores, the paper's long-context cache parameters) on small seeded workloads and print one JSON line")
+    ap.add_argument("--extras-only", default=None, help="with --extras: run only the rows whose label contains this text")
     ap.add_argument("--skip-prefill", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
@@ -176,7 +181,7 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     if args.extras:
-        print(json.dumps(extras(torch, wl, lb, dev)), flush=True)
+        print(json.dumps(extras(torch, wl, lb, dev, args.extras_only)), flush=True)
         return
     sh = wl.scaled(4, T=args.prefill_tokens)
     K, W, L = args.steps, args.warmup, args.layers
