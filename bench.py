@@ -136,7 +136,7 @@ def extras(torch, wl, lb, dev, only=None):
     rows.append(run("long-context cache parameters eta=lambda=512, D=2d", eta=512, lam=512, **long))
     rows.append(run("long-context cache parameters eta=128, lambda=768, D=2d", eta=128, lam=768, **long))
     rows.append(run("long-context cache parameters eta=512, lambda=1024, D=2d", eta=512, lam=1024, **long))
-    rows.append(run("long-context cache parameters eta=lambda=256, D=2d, batch 32", eta=256, lam=256, **dict(long, B=32, T=1024)))
+    rows.append(run("batch 32 at the long-context cache parameters eta = lambda = 256, D = 2d", eta=256, lam=256, **dict(long, B=32, T=1024)))
     rows.append(run("no sparse cache (sliding window + linear attention base model), window 64", B=4, Hq=32, Hkv=8, d=128, D=128, eta=64,
                     lam=0, Cc=64, T=2048, n_dec=36))
     rows.append(run("no sparse cache, window 192 (ablation: extended window)", B=4, Hq=32, Hkv=8, d=128, D=128, eta=192, lam=0, Cc=64, T=2048, n_dec=36))
