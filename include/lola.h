@@ -116,18 +116,12 @@ typedef struct {
     /* Query-dependent scores (score_kind != LOLA_SCORE_SRE; NULL otherwise). */
     float *win_score;    /* [B, Hkv, eta]     sum gathered so far by the pair in each ring slot */
     float *sp_score;     /* [B, Hkv, lambda]  final sum of the pair in each sparse slot */
-    /* Scratch of the generation step (optional, may be NULL): the self-recall errors (Sec. 3.2, eq. sre) of the
-     * lambda + 1 candidates of a step, written by a scoring kernel of its own that spreads a stream's candidates over
-     * several workgroups.  Used with bf16 storage, head_dim 64 or 128, feat_dim 128 or 256, a sparse budget that is a
-     * multiple of 64 and LOLA_SCORE_SRE where the fused step does not apply; without it those shapes run the
-     * shape-generic kernel.  Contents between calls are meaningless. */
-    float *step_scores;  /* [B, Hkv, lambda + 1] */
 } lola_state;
 
-/* Bytes of each state field in the order of the struct (host output, 15 entries; fields of an
+/* Bytes of each state field in the order of the struct (host output, 14 entries; fields of an
  * option that is off are 0); returns their sum, or 0 if the configuration is invalid or
  * unsupported. */
-size_t lola_state_bytes(const lola_config *cfg, size_t field_bytes[15]);
+size_t lola_state_bytes(const lola_config *cfg, size_t field_bytes[14]);
 
 /* Workspace of lola_prefill for T tokens: returns the size with which all chunks are processed in
  * one pass; *min_bytes (host, may be NULL) receives the smallest size accepted (the chunks are then

@@ -33,7 +33,7 @@ class LolaConfig(C.Structure):
 class LolaState(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in (
         "H", "s", "win_k", "win_v", "sp_k", "sp_v", "sp_idx", "sp_count", "n_tokens",
-        "pend_phi", "pend_v", "pend_count", "win_score", "sp_score", "step_scores")]
+        "pend_phi", "pend_v", "pend_count", "win_score", "sp_score")]
 
 
 class LolaError(RuntimeError):
@@ -92,7 +92,7 @@ def _stream():
 
 
 def lola_state_bytes(cfg: LolaConfig):
-    fb = (C.c_size_t * 15)()
+    fb = (C.c_size_t * 14)()
     tot = lib().lola_state_bytes(C.byref(cfg), fb)
     return int(tot), [int(x) for x in fb]
 
@@ -171,9 +171,8 @@ class LolaLayer:
         sk = 1 if self.score_kind else 0
         self.win_score = torch.empty((B, Hkv, eta) if sk else (0,), dtype=torch.float32, device=dev)
         self.sp_score = torch.empty((B, Hkv, lam) if sk else (0,), dtype=torch.float32, device=dev)
-        self.step_scores = torch.empty((fb[14] // 4,), dtype=torch.float32, device=dev)   # 0 where no kernel uses it
         fields = [self.H, self.s, self.win_k, self.win_v, self.sp_k, self.sp_v, self.sp_idx, self.sp_count, self.n_tokens,
-                  self.pend_phi, self.pend_v, self.pend_count, self.win_score, self.sp_score, self.step_scores]
+                  self.pend_phi, self.pend_v, self.pend_count, self.win_score, self.sp_score]
         assert [t.numel() * t.element_size() for t in fields] == fb
         self.st = LolaState(*[t.data_ptr() if t.numel() else None for t in fields])
         self.workspace = None

@@ -354,8 +354,8 @@ struct DecodeArgs {
     const T *q, *k, *v, *Wq, *Wk;
     void *out;
     int R;          // rows scored per tile
-    const float *ext_score;   // [B*Hkv][lam + 1] self-recall errors of the candidates computed beforehand (steady-state streams), or NULL
     int no_out;               // 1: the memories are updated only (another kernel computes the outputs)
+    int skip_steady;          // 1: streams in steady state (window and cache full) were updated by another kernel already
 };
 
 template <typename T, typename TO>
@@ -395,6 +395,7 @@ __global__ __launch_bounds__(NT) void decode_kernel(DecodeArgs<T> a) {
     const int slot = eta > 0 ? (int)(tok % eta) : 0;
     const int32_t pidx = (int32_t)(tok - eta);
     int spc = a.st.sp_count[si];
+    if (a.skip_steady && popped && lam > 0 && spc == lam) return;   // (a stream stays in steady state once it is there)
     float *win_score = sk ? a.st.win_score + (size_t)si * eta : nullptr;
     float *sp_score = sk ? a.st.sp_score + (size_t)si * lam : nullptr;
     if (sk) {
@@ -433,11 +434,8 @@ __global__ __launch_bounds__(NT) void decode_kernel(DecodeArgs<T> a) {
                 if (sk) {
                     for (int e = tid; e <= lam; e += NT) score[e] = e < lam ? sp_score[e] : sh_pscore;
                     __syncthreads();
-                } else if (a.ext_score) {
-                    for (int e = tid; e <= lam; e += NT) score[e] = a.ext_score[(size_t)si * (lam + 1) + e];
-                    __syncthreads();
                 }
-                for (int t0 = 0; t0 <= lam && !sk && !a.ext_score; t0 += R) {
+                for (int t0 = 0; t0 <= lam && !sk; t0 += R) {
                     int nr = min(R, lam + 1 - t0);
                     for (int p = tid; p < nr * d; p += NT) {
                         int r = p / d, i = p - r * d, e = t0 + r;

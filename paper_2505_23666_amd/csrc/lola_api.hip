@@ -40,10 +40,10 @@ bool wide_step_out_ok(const lola_config *c) {
            c->window >= 1 && c->score_kind == LOLA_SCORE_SRE && !fast_decode_ok(c) && c->n_q_heads / c->n_kv_heads <= 4 &&
            c->sparse_budget + c->window <= fast::STEP_OUT_NKMAX;
 }
-// ... and at which the candidates are scored by a kernel of their own ahead of it (several workgroups per stream, MFMA;
-// sparse budgets in multiples of 64); needs the state's step_scores field.
+// ... and at which the streams in steady state are updated by the MFMA update kernel ahead of it (sparse budgets in
+// multiples of 64).
 bool wide_decode_ok(const lola_config *c) {
-    return wide_step_out_ok(c) && c->sparse_budget >= 64 && c->sparse_budget % 64 == 0;
+    return wide_step_out_ok(c) && c->sparse_budget >= 64 && c->sparse_budget % 64 == 0 && c->sparse_budget <= fast::STEP_UPDATE_LAMMAX;
 }
 
 lola_status check_config(const lola_config *c) {
@@ -93,7 +93,6 @@ lola_status check_state(const lola_config *c, const lola_state *st) {
         if ((c->window > 0 && !st->win_score) || (c->sparse_budget > 0 && !st->sp_score)) return LOLA_ERR_NULL;
         if (misaligned(st->win_score) || misaligned(st->sp_score)) return LOLA_ERR_ALIGN;
     }
-    if (st->step_scores && misaligned(st->step_scores)) return LOLA_ERR_ALIGN;
     return LOLA_OK;
 }
 
@@ -280,26 +279,25 @@ lola_status run_decode(const lola_config *c, const lola_state *st, const void *q
     if (a.R <= 0) return LOLA_ERR_UNSUPPORTED;
     const size_t lds = 4 * (fixed + (size_t)a.R * (3 * a.dm.d + a.dm.D + 1 + (sk ? a.dm.D : 0)));
     dim3 grid(a.dm.B * a.dm.Hkv), block(generic::NT);
-    a.ext_score = nullptr;
     a.no_out = 0;
+    a.skip_steady = 0;
     bool wide_out = false;
     if constexpr (std::is_same<T, bf16_t>::value) {
-        if (wide_decode_ok(c) && st->step_scores) {
-            // the candidates' self-recall errors from a kernel of their own: 64 candidates per workgroup, the leaving pair
-            // in one more; streams that are not in steady state (window or cache still filling) are left to the step kernel
-            fast::ScoreWideArgs sa;
-            sa.st = a.st; sa.Wk = a.Wk; sa.scores = st->step_scores;
-            sa.Hkv = a.dm.Hkv; sa.lam = a.dm.lam; sa.eta = a.dm.eta; sa.phi_kind = a.dm.phi_kind;
-            const dim3 gsc((unsigned)(a.dm.lam / 64 + 1), (unsigned)(a.dm.B * a.dm.Hkv));
+        if (wide_decode_ok(c)) {
+            // streams in steady state (window and cache full: scoring, arg-min, fold, slot replacement) by the MFMA update
+            // kernel; the others (still filling) are left to the step kernel, which skips the steady ones
+            fast::StepUpdateArgs ua;
+            ua.st = a.st; ua.k = a.k; ua.v = a.v; ua.Wk = a.Wk;
+            ua.Hkv = a.dm.Hkv; ua.lam = a.dm.lam; ua.eta = a.dm.eta; ua.phi_kind = a.dm.phi_kind;
             if (c->head_dim == 128) {
-                if (c->feat_dim == 256) hipLaunchKernelGGL((fast::score_wide_kernel<128, 256>), gsc, dim3(256), 0, stream, sa);
-                else hipLaunchKernelGGL((fast::score_wide_kernel<128, 128>), gsc, dim3(256), 0, stream, sa);
+                if (c->feat_dim == 256) hipLaunchKernelGGL((fast::step_update_wide_kernel<128, 256>), grid, dim3(512), 0, stream, ua);
+                else hipLaunchKernelGGL((fast::step_update_wide_kernel<128, 128>), grid, dim3(512), 0, stream, ua);
             } else {
-                if (c->feat_dim == 256) hipLaunchKernelGGL((fast::score_wide_kernel<64, 256>), gsc, dim3(256), 0, stream, sa);
-                else hipLaunchKernelGGL((fast::score_wide_kernel<64, 128>), gsc, dim3(256), 0, stream, sa);
+                if (c->feat_dim == 256) hipLaunchKernelGGL((fast::step_update_wide_kernel<64, 256>), grid, dim3(512), 0, stream, ua);
+                else hipLaunchKernelGGL((fast::step_update_wide_kernel<64, 128>), grid, dim3(512), 0, stream, ua);
             }
             LAUNCH_CHECK();
-            a.ext_score = st->step_scores;
+            a.skip_steady = 1;
         }
         if (wide_step_out_ok(c)) {
             a.no_out = 1;
@@ -691,17 +689,17 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
 
 extern "C" {
 
-size_t lola_state_bytes(const lola_config *c, size_t fb[15]) {
+size_t lola_state_bytes(const lola_config *c, size_t fb[14]) {
     if (check_config(c) != LOLA_OK) return 0;
     const size_t ns = (size_t)c->batch * c->n_kv_heads, es = esize(c->dtype);
     const size_t d = c->head_dim, D = c->feat_dim, eta = c->window, lam = c->sparse_budget, R = c->fold_defer;
     const size_t sk = c->score_kind != LOLA_SCORE_SRE ? 1 : 0;
-    size_t f[15] = {ns * D * d * 4, ns * D * 4, ns * eta * d * es, ns * eta * d * es, ns * lam * d * es,
+    size_t f[14] = {ns * D * d * 4, ns * D * 4, ns * eta * d * es, ns * eta * d * es, ns * lam * d * es,
                     ns * lam * d * es, ns * lam * 4, ns * 4, ns * 8,
                     ns * R * D * 4, ns * R * d * 4, R ? ns * 4 : 0,
-                    sk * ns * eta * 4, sk * ns * lam * 4, wide_decode_ok(c) ? ns * (lam + 1) * 4 : 0};
+                    sk * ns * eta * 4, sk * ns * lam * 4};
     size_t tot = 0;
-    for (int i = 0; i < 15; i++) { if (fb) fb[i] = f[i]; tot += f[i]; }
+    for (int i = 0; i < 14; i++) { if (fb) fb[i] = f[i]; tot += f[i]; }
     return tot;
 }
 
@@ -722,14 +720,13 @@ lola_status lola_state_init(const lola_config *c, const lola_state *st, void *st
     if (rc != LOLA_OK) return rc;
     rc = check_state(c, st);
     if (rc != LOLA_OK) return rc;
-    size_t fb[15];
+    size_t fb[14];
     lola_state_bytes(c, fb);
     const bool sk = c->score_kind != LOLA_SCORE_SRE;
-    void *ptrs[15] = {st->H, st->s, st->win_k, st->win_v, st->sp_k, st->sp_v, st->sp_idx, st->sp_count, st->n_tokens,
+    void *ptrs[14] = {st->H, st->s, st->win_k, st->win_v, st->sp_k, st->sp_v, st->sp_idx, st->sp_count, st->n_tokens,
                       c->fold_defer ? st->pend_phi : nullptr, c->fold_defer ? st->pend_v : nullptr,
-                      c->fold_defer ? st->pend_count : nullptr, sk ? st->win_score : nullptr, sk ? st->sp_score : nullptr,
-                      st->step_scores};
-    for (int i = 0; i < 15; i++) {
+                      c->fold_defer ? st->pend_count : nullptr, sk ? st->win_score : nullptr, sk ? st->sp_score : nullptr};
+    for (int i = 0; i < 14; i++) {
         if (!ptrs[i] || fb[i] == 0) continue;
         size_t n = fb[i] / 4;   // every field is a multiple of 4 bytes (head_dim is even)
         unsigned blocks = (unsigned)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
@@ -860,7 +857,8 @@ const char *lola_status_str(lola_status s) {
 const char *lola_kernel_path(const lola_config *c, int32_t which) {
     if (check_config(c) != LOLA_OK) return "invalid";
     if (which == 1 && fast_decode_ok(c)) return "mfma";
-    if (which == 1 && wide_step_out_ok(c)) return "mixed";   // outputs (and, with the state's step_scores, the scoring) on MFMA
+    if (which == 1 && wide_decode_ok(c)) return "mfma";      // update of steady-state streams and outputs on MFMA
+    if (which == 1 && wide_step_out_ok(c)) return "mixed";   // outputs on MFMA, update shape-generic
     if (which == 0 && (fast_attend_ok(c) || wide_scan_ok(c))) return "mfma";
     if (which == 0 && (fast_output_ok(c) || wide_output_ok(c))) return "mixed";
     return "generic";

@@ -1689,98 +1689,6 @@ __global__ __launch_bounds__(DH * 4) void scan_wide_kernel(generic::PrefillArgs<
 }
 
 // ---------------------------------------------------------------------------------------------
-// Self-recall errors of the lambda + 1 candidates of a generation step (Sec. 3.2, eq. sre: the sparse cache and the
-// pair that leaves the window, scored with the state before the step's fold) as a kernel of its own, for sparse budgets
-// in multiples of 64 and 128 or 256 features: grid (lambda / 64 + 1, stream), one wavefront per 16 candidates, the
-// last block's wavefront 0 the leaving pair.  No LDS and no barriers: a wavefront computes phi of its keys
-// (Sec. 2.3 eq. feature_map) on MFMA, keeps it as the B operand of the recall GEMM (bf16 high + low parts) and walks
-// over the 16-row tiles of H^T, read from memory and split on the way (the streams' H^T stay in L2 between the
-// blocks that read them).  Streams outside the steady state (window or cache still filling) are skipped.
-struct ScoreWideArgs {
-    State<bf16_t> st;
-    const bf16_t *Wk;
-    float *scores;        // [stream][lam + 1]
-    int Hkv, lam, eta, phi_kind;
-};
-
-template <int DH, int DF>
-__global__ __launch_bounds__(256) void score_wide_kernel(ScoreWideArgs a) {
-    constexpr int M = DF / 2, KS = DH / 32, NZT = M / 16, KF = DF / 32, NCT = DH / 16;
-    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r16 = lane & 15, g4 = lane >> 4;
-    const int si = blockIdx.y, h = si % a.Hkv, LAM = a.lam, ETA = a.eta;
-    const int64_t tok = a.st.n_tokens[si];
-    if (!(tok >= (int64_t)ETA && a.st.sp_count[si] == LAM)) return;
-    const bool tail = (int)blockIdx.x == LAM / 64;   // the leaving pair: every column of wavefront 0's tile holds it
-    if (tail && w != 0) return;
-    const int e = tail ? LAM : 64 * (int)blockIdx.x + 16 * w + r16;
-    const int slot = (int)(tok % ETA);
-    const bf16_t *kr = tail ? a.st.win_k + ((size_t)si * ETA + slot) * DH : a.st.sp_k + ((size_t)si * LAM + e) * DH;
-    const bf16_t *vr = tail ? a.st.win_v + ((size_t)si * ETA + slot) * DH : a.st.sp_v + ((size_t)si * LAM + e) * DH;
-    const bf16_t *Wk = a.Wk + (size_t)h * M * DH;
-    const float *Hg = a.st.H + (size_t)si * DF * DH, *sg = a.st.s + (size_t)si * DF;
-
-    bf16x8 BK[KS];
-#pragma unroll
-    for (int ks = 0; ks < KS; ks++) BK[ks] = ld_bf16x8(kr + 32 * ks + 8 * g4);
-    f32x4 zt[NZT];
-#pragma unroll
-    for (int mt = 0; mt < NZT; mt++) {
-        zt[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < KS; ks++)
-            zt[mt] = mfma16(ld_bf16x8(Wk + (size_t)(16 * mt + r16) * DH + 32 * ks + 8 * g4), BK[ks], zt[mt]);
-    }
-    float pp[4 * NZT], pn[4 * NZT];
-    phi_from_z_tiles<NZT>(zt, a.phi_kind, pp, pn);
-    // phi(k).s: the lane holds features 16 mt + 4 g4 + i of both halves
-    float dn = 0.f;
-#pragma unroll
-    for (int mt = 0; mt < NZT; mt++) {
-        const float4 sp4 = *reinterpret_cast<const float4 *>(sg + 16 * mt + 4 * g4);
-        const float4 sn4 = *reinterpret_cast<const float4 *>(sg + M + 16 * mt + 4 * g4);
-        dn = fmaf(pp[4 * mt], sp4.x, dn); dn = fmaf(pp[4 * mt + 1], sp4.y, dn);
-        dn = fmaf(pp[4 * mt + 2], sp4.z, dn); dn = fmaf(pp[4 * mt + 3], sp4.w, dn);
-        dn = fmaf(pn[4 * mt], sn4.x, dn); dn = fmaf(pn[4 * mt + 1], sn4.y, dn);
-        dn = fmaf(pn[4 * mt + 2], sn4.z, dn); dn = fmaf(pn[4 * mt + 3], sn4.w, dn);
-    }
-    dn = grp_sum(dn);
-    const float rd = dn > 0.f ? 1.0f / dn : 0.f;   // recall = 0 while nothing was folded
-    // B operands: k-step ks of the contraction over the features holds 32 ks + 16 (x / 4) + 4 g4 + x % 4, x < 8
-    bf16x8 Bh[KF], Bl[KF];
-#pragma unroll
-    for (int ks = 0; ks < KF / 2; ks++) {
-        split8(&pp[8 * ks], Bh[ks], Bl[ks]);
-        split8(&pn[8 * ks], Bh[KF / 2 + ks], Bl[KF / 2 + ks]);
-    }
-    float esum = 0.f;
-#pragma unroll 2
-    for (int ct = 0; ct < NCT; ct++) {
-        const float *hrow = Hg + (size_t)(16 * ct + r16) * DF + 4 * g4;
-        const uint2 vv = *reinterpret_cast<const uint2 *>(vr + 16 * ct + 4 * g4);
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acc2 = {0.f, 0.f, 0.f, 0.f}, acc3 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < KF; ks++) {
-            const float4 h0 = *reinterpret_cast<const float4 *>(hrow + 32 * ks), h1 = *reinterpret_cast<const float4 *>(hrow + 32 * ks + 16);
-            const float x8[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
-            bf16x8 Ah, Al;
-            split8(x8, Ah, Al);
-            acc = mfma16(Ah, Bh[ks], acc);
-            acc2 = mfma16(Ah, Bl[ks], acc2);
-            acc3 = mfma16(Al, Bh[ks], acc3);
-        }
-        // lane (candidate r16, group g4): phi(k)^T H at value columns 16 ct + 4 g4 + i
-        const float v4[4] = {bf_lo(vv.x), bf_hi(vv.x), bf_lo(vv.y), bf_hi(vv.y)};
-#pragma unroll
-        for (int i = 0; i < 4; i++) {
-            const float err = (acc[i] + (acc2[i] + acc3[i])) * rd - v4[i];
-            esum = fmaf(err, err, esum);
-        }
-    }
-    esum = grp_sum(esum);
-    if (g4 == 0 && (!tail || r16 == 0)) a.scores[(size_t)si * (LAM + 1) + e] = sqrtf(esum);
-}
-
-// ---------------------------------------------------------------------------------------------
 // Outputs of a generation step from the memories as the step's update left them (Sec. 3.1 eq. lola_output with the
 // shared normaliser: softmax part over the sparse cache and the window, linear part phi(q)^T H, phi(q)^T s), for any
 // window and sparse budget with at most NKMAX keys, 128 or 256 features and up to four query heads per kv head.  One
@@ -2006,6 +1914,253 @@ __global__ __launch_bounds__(256) void step_out_wide_kernel(StepOutArgs<TO> a) {
         const float val = num / (psum_l[qi] + elin * denq_l[qi]);
         stf(a.out, ((size_t)b * a.Hq + (size_t)h * g + qi) * DH + c, val);
     }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Update of the memories in a generation step in steady state (window and cache full; Sec. 3.1 "Method Overview" and
+// Sec. 3.2 eq. sre: the new pair enters the window, the pair it displaces and the lambda cached pairs are scored with the
+// state as it stands, the one with the smallest self-recall error is folded into H and s, the others stay cached), for
+// sparse budgets in multiples of 64 and 128 or 256 features.  One workgroup of eight wavefronts per stream:
+//   1. H^T is read once: every thread keeps its 16-byte-piece pairs as fp32 (they are rewritten by the fold) and leaves
+//      them in LDS split into bf16 high + low parts, in the A-operand order of the recall GEMM;
+//   2. the cache's tiles of 16 candidates are dealt to the wavefronts round-robin: phi of the keys on MFMA (Sec. 2.3
+//      eq. feature_map), kept as B operand, recall against all of H^T from LDS, || recall - v || per candidate to LDS;
+//      the leaving pair, which would be a tile (and a round) of its own, is scored from the fp32 registers instead:
+//      wavefront 7 computes its phi first, and after the tiles every thread multiplies its pieces of H^T with it;
+//   3. wavefront 0: arg-min (ties: the larger token index goes), phi of the folded pair as fp32;
+//   4. rank-1 fold on the registers, H^T and s written back; the leaving pair takes the folded pair's slot unless it is
+//      the one folded; the new pair takes the ring slot; the token counter advances.
+// Streams that are not in steady state are left untouched (the shape-generic step kernel takes them).
+struct StepUpdateArgs {
+    State<bf16_t> st;
+    const bf16_t *k, *v, *Wk;
+    int Hkv, lam, eta, phi_kind;
+};
+
+constexpr int STEP_UPDATE_LAMMAX = 2048;
+
+template <int DH, int DF>
+__global__ __launch_bounds__(512) void step_update_wide_kernel(StepUpdateArgs a) {
+    constexpr int M = DF / 2, KS = DH / 32, NZT = M / 16, KF = DF / 32, NCT = DH / 16, NP = NCT * KF / 8, PR = DH / 8;
+    constexpr int LAMMAX = STEP_UPDATE_LAMMAX;
+    __shared__ __attribute__((aligned(16))) uint4 HA[NCT * KF * 2 * 64];     // [row tile][k-step][part][lane]
+    __shared__ __attribute__((aligned(16))) float s_l[DF];
+    __shared__ __attribute__((aligned(16))) float phif[DF];                  // phi of the folded pair
+    __shared__ __attribute__((aligned(16))) float vf[DH];                    // its value
+    __shared__ __attribute__((aligned(16))) uint16_t pkb[DH], pvb[DH];       // the pair that leaves the window
+    __shared__ float score[LAMMAX + 1];
+    __shared__ int idx_l[LAMMAX + 1];
+    __shared__ int drop_s;
+    __shared__ __attribute__((aligned(16))) float phip[DF];   // phi of the leaving pair
+    __shared__ float partp[KF][DH];                           // its recall, partial sums over 32 features each
+    __shared__ float rdp_s, errp[2];
+
+    const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, r16 = lane & 15, g4 = lane >> 4;
+    const int si = blockIdx.x, h = si % a.Hkv, LAM = a.lam, ETA = a.eta;
+    const int64_t tok = a.st.n_tokens[si];
+    if (!(tok >= (int64_t)ETA && a.st.sp_count[si] == LAM)) return;
+    const int slot = (int)(tok % ETA), pidx = (int)(tok - ETA);
+    float *Hg = a.st.H + (size_t)si * DF * DH, *sg = a.st.s + (size_t)si * DF;
+    bf16_t *sp_k = a.st.sp_k + (size_t)si * LAM * DH, *sp_v = a.st.sp_v + (size_t)si * LAM * DH;
+    bf16_t *win_k = a.st.win_k + ((size_t)si * ETA + slot) * DH, *win_v = a.st.win_v + ((size_t)si * ETA + slot) * DH;
+    int32_t *sp_idx = a.st.sp_idx + (size_t)si * LAM;
+    const bf16_t *Wk = a.Wk + (size_t)h * M * DH;
+
+    // ---- 1. the state; the leaving pair; the slots' token indices
+    float4 hreg[NP][2];
+#pragma unroll
+    for (int i = 0; i < NP; i++) {
+        const int idx = w + 8 * i, ct = idx / KF, ks = idx % KF;
+        const float *hp = Hg + (size_t)(16 * ct + r16) * DF + 32 * ks + 4 * g4;
+        hreg[i][0] = *reinterpret_cast<const float4 *>(hp);
+        hreg[i][1] = *reinterpret_cast<const float4 *>(hp + 16);
+    }
+    if (tid < PR) reinterpret_cast<uint4 *>(pkb)[tid] = reinterpret_cast<const uint4 *>(win_k)[tid];
+    else if (tid < 2 * PR) reinterpret_cast<uint4 *>(pvb)[tid - PR] = reinterpret_cast<const uint4 *>(win_v)[tid - PR];
+    for (int x = tid; x < DF; x += 512) s_l[x] = sg[x];
+    for (int e = tid; e < LAM; e += 512) idx_l[e] = sp_idx[e];
+    if (tid == 0) idx_l[LAM] = pidx;
+#pragma unroll
+    for (int i = 0; i < NP; i++) {
+        const float x8[8] = {hreg[i][0].x, hreg[i][0].y, hreg[i][0].z, hreg[i][0].w, hreg[i][1].x, hreg[i][1].y, hreg[i][1].z, hreg[i][1].w};
+        bf16x8 hi, lo;
+        split8(x8, hi, lo);
+        HA[((w + 8 * i) * 2 + 0) * 64 + lane] = __builtin_bit_cast(uint4, hi);
+        HA[((w + 8 * i) * 2 + 1) * 64 + lane] = __builtin_bit_cast(uint4, lo);
+    }
+    __syncthreads();
+
+    // phi of the 16 keys a tile's lanes point at (lane (column r16, group g4) reads 16 bytes of its key per k-step):
+    // the lane's features 16 mt + 4 g4 + i of both halves
+    auto phi_tile = [&](const bf16_t *kr, float (&pp)[4 * NZT], float (&pn)[4 * NZT]) {
+        bf16x8 BK[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ks++) BK[ks] = ld_bf16x8(kr + 32 * ks + 8 * g4);
+        f32x4 zt[NZT];
+#pragma unroll
+        for (int mt = 0; mt < NZT; mt++) {
+            zt[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ks++)
+                zt[mt] = mfma16(ld_bf16x8(Wk + (size_t)(16 * mt + r16) * DH + 32 * ks + 8 * g4), BK[ks], zt[mt]);
+        }
+        phi_from_z_tiles<NZT>(zt, a.phi_kind, pp, pn);
+    };
+
+    // ---- 2. self-recall errors
+    if (w == 7) {   // the leaving pair's features (every column of the tile holds the same key: column 0 stores)
+        float pp[4 * NZT], pn[4 * NZT];
+        phi_tile(reinterpret_cast<const bf16_t *>(pkb), pp, pn);
+        float dn = 0.f;
+#pragma unroll
+        for (int mt = 0; mt < NZT; mt++) {
+            const float4 sp4 = *reinterpret_cast<const float4 *>(&s_l[16 * mt + 4 * g4]);
+            const float4 sn4 = *reinterpret_cast<const float4 *>(&s_l[M + 16 * mt + 4 * g4]);
+            dn = fmaf(pp[4 * mt], sp4.x, dn); dn = fmaf(pp[4 * mt + 1], sp4.y, dn);
+            dn = fmaf(pp[4 * mt + 2], sp4.z, dn); dn = fmaf(pp[4 * mt + 3], sp4.w, dn);
+            dn = fmaf(pn[4 * mt], sn4.x, dn); dn = fmaf(pn[4 * mt + 1], sn4.y, dn);
+            dn = fmaf(pn[4 * mt + 2], sn4.z, dn); dn = fmaf(pn[4 * mt + 3], sn4.w, dn);
+        }
+        dn = grp_sum(dn);
+        if (lane == 0) rdp_s = dn > 0.f ? 1.0f / dn : 0.f;
+        if (r16 == 0) {
+#pragma unroll
+            for (int mt = 0; mt < NZT; mt++) {
+                *reinterpret_cast<float4 *>(&phip[16 * mt + 4 * g4]) = make_float4(pp[4 * mt], pp[4 * mt + 1], pp[4 * mt + 2], pp[4 * mt + 3]);
+                *reinterpret_cast<float4 *>(&phip[M + 16 * mt + 4 * g4]) = make_float4(pn[4 * mt], pn[4 * mt + 1], pn[4 * mt + 2], pn[4 * mt + 3]);
+            }
+        }
+    }
+    const int ntile = LAM / 16;
+#pragma unroll 1
+    for (int t = w; t < ntile; t += 8) {
+        const bool tail = false;
+        const int e = 16 * t + r16;
+        const bf16_t *kr = sp_k + (size_t)e * DH;
+        const bf16_t *vr = sp_v + (size_t)e * DH;
+        float pp[4 * NZT], pn[4 * NZT];
+        phi_tile(kr, pp, pn);
+        float dn = 0.f;
+#pragma unroll
+        for (int mt = 0; mt < NZT; mt++) {
+            const float4 sp4 = *reinterpret_cast<const float4 *>(&s_l[16 * mt + 4 * g4]);
+            const float4 sn4 = *reinterpret_cast<const float4 *>(&s_l[M + 16 * mt + 4 * g4]);
+            dn = fmaf(pp[4 * mt], sp4.x, dn); dn = fmaf(pp[4 * mt + 1], sp4.y, dn);
+            dn = fmaf(pp[4 * mt + 2], sp4.z, dn); dn = fmaf(pp[4 * mt + 3], sp4.w, dn);
+            dn = fmaf(pn[4 * mt], sn4.x, dn); dn = fmaf(pn[4 * mt + 1], sn4.y, dn);
+            dn = fmaf(pn[4 * mt + 2], sn4.z, dn); dn = fmaf(pn[4 * mt + 3], sn4.w, dn);
+        }
+        dn = grp_sum(dn);
+        const float rd = dn > 0.f ? 1.0f / dn : 0.f;   // recall = 0 while nothing was folded
+        bf16x8 Bh[KF], Bl[KF];
+#pragma unroll
+        for (int ks = 0; ks < KF / 2; ks++) {
+            split8(&pp[8 * ks], Bh[ks], Bl[ks]);
+            split8(&pn[8 * ks], Bh[KF / 2 + ks], Bl[KF / 2 + ks]);
+        }
+        float esum = 0.f;
+#pragma unroll 2
+        for (int ct = 0; ct < NCT; ct++) {
+            const uint2 vv = *reinterpret_cast<const uint2 *>(vr + 16 * ct + 4 * g4);
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acc2 = {0.f, 0.f, 0.f, 0.f}, acc3 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KF; ks++) {
+                const bf16x8 Ah = as_bf16x8(HA[((ct * KF + ks) * 2 + 0) * 64 + lane]), Al = as_bf16x8(HA[((ct * KF + ks) * 2 + 1) * 64 + lane]);
+                acc = mfma16(Ah, Bh[ks], acc);
+                acc2 = mfma16(Ah, Bl[ks], acc2);
+                acc3 = mfma16(Al, Bh[ks], acc3);
+            }
+            const float v4[4] = {bf_lo(vv.x), bf_hi(vv.x), bf_lo(vv.y), bf_hi(vv.y)};
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                const float err = (acc[i] + (acc2[i] + acc3[i])) * rd - v4[i];
+                esum = fmaf(err, err, esum);
+            }
+        }
+        esum = grp_sum(esum);
+        if (g4 == 0 && (!tail || r16 == 0)) score[e] = sqrtf(esum);
+    }
+    __syncthreads();
+    // the leaving pair: this thread's pieces of H^T (row 16 ct + r16, features 32 ks + 4 g4 .. and + 16) times phi
+#pragma unroll
+    for (int i = 0; i < NP; i++) {
+        const int idx = w + 8 * i, ct = idx / KF, ks = idx % KF;
+        const float4 p0 = *reinterpret_cast<const float4 *>(&phip[32 * ks + 4 * g4]), p1 = *reinterpret_cast<const float4 *>(&phip[32 * ks + 16 + 4 * g4]);
+        float d0 = hreg[i][0].x * p0.x;
+        d0 = fmaf(hreg[i][0].y, p0.y, d0); d0 = fmaf(hreg[i][0].z, p0.z, d0); d0 = fmaf(hreg[i][0].w, p0.w, d0);
+        d0 = fmaf(hreg[i][1].x, p1.x, d0); d0 = fmaf(hreg[i][1].y, p1.y, d0); d0 = fmaf(hreg[i][1].z, p1.z, d0); d0 = fmaf(hreg[i][1].w, p1.w, d0);
+        d0 = grp_sum(d0);
+        if (g4 == 0) partp[ks][16 * ct + r16] = d0;
+    }
+    __syncthreads();
+    if (tid < 128) {   // (two wavefronts; head_dim 64 leaves the upper half idle)
+        float err = 0.f;
+        if (tid < DH) {
+            float rec = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < KF; ks++) rec += partp[ks][tid];
+            err = rec * rdp_s - __uint_as_float((uint32_t)pvb[tid] << 16);
+        }
+        err = wsum(err * err);
+        if (lane == 0) errp[w] = err;
+    }
+    __syncthreads();
+    if (tid == 0) score[LAM] = sqrtf(errp[0] + errp[1]);
+    __syncthreads();
+
+    // ---- 3. the pair that goes: smallest score, ties -> the larger token index; its features and value as fp32
+    if (w == 0) {
+        float bs = INFINITY; int bi = -1, be = 0;
+        for (int e = lane; e <= LAM; e += 64) {
+            const float sc = score[e]; const int ix = idx_l[e];
+            if (sc < bs || (sc == bs && ix > bi)) { bs = sc; bi = ix; be = e; }
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const float os = __shfl_xor(bs, o, 64); const int oi = __shfl_xor(bi, o, 64), oe = __shfl_xor(be, o, 64);
+            if (os < bs || (os == bs && oi > bi)) { bs = os; bi = oi; be = oe; }
+        }
+        const int drop = __builtin_amdgcn_readfirstlane(be);
+        const bf16_t *kr = drop < LAM ? sp_k + (size_t)drop * DH : reinterpret_cast<const bf16_t *>(pkb);
+        const bf16_t *vr = drop < LAM ? sp_v + (size_t)drop * DH : reinterpret_cast<const bf16_t *>(pvb);
+        float pp[4 * NZT], pn[4 * NZT];
+        phi_tile(kr, pp, pn);   // every column holds the same key: column 0 stores
+        if (r16 == 0) {
+#pragma unroll
+            for (int mt = 0; mt < NZT; mt++) {
+                *reinterpret_cast<float4 *>(&phif[16 * mt + 4 * g4]) = make_float4(pp[4 * mt], pp[4 * mt + 1], pp[4 * mt + 2], pp[4 * mt + 3]);
+                *reinterpret_cast<float4 *>(&phif[M + 16 * mt + 4 * g4]) = make_float4(pn[4 * mt], pn[4 * mt + 1], pn[4 * mt + 2], pn[4 * mt + 3]);
+            }
+        }
+        for (int c = lane; c < DH; c += 64) vf[c] = ldf(vr, c);
+        if (lane == 0) drop_s = drop;
+    }
+    __syncthreads();
+
+    // ---- 4. fold, write-back, slot replacement, ring slot
+    const int drop = drop_s;
+#pragma unroll
+    for (int i = 0; i < NP; i++) {
+        const int idx = w + 8 * i, ct = idx / KF, ks = idx % KF;
+        const float vc = vf[16 * ct + r16];
+        const float4 p0 = *reinterpret_cast<const float4 *>(&phif[32 * ks + 4 * g4]), p1 = *reinterpret_cast<const float4 *>(&phif[32 * ks + 16 + 4 * g4]);
+        float4 h0 = hreg[i][0], h1 = hreg[i][1];
+        h0.x = fmaf(p0.x, vc, h0.x); h0.y = fmaf(p0.y, vc, h0.y); h0.z = fmaf(p0.z, vc, h0.z); h0.w = fmaf(p0.w, vc, h0.w);
+        h1.x = fmaf(p1.x, vc, h1.x); h1.y = fmaf(p1.y, vc, h1.y); h1.z = fmaf(p1.z, vc, h1.z); h1.w = fmaf(p1.w, vc, h1.w);
+        float *hp = Hg + (size_t)(16 * ct + r16) * DF + 32 * ks + 4 * g4;
+        *reinterpret_cast<float4 *>(hp) = h0;
+        *reinterpret_cast<float4 *>(hp + 16) = h1;
+    }
+    for (int x = tid; x < DF; x += 512) sg[x] = s_l[x] + phif[x];
+    if (drop < LAM) {   // the leaving pair takes the freed slot
+        if (tid < PR) reinterpret_cast<uint4 *>(sp_k + (size_t)drop * DH)[tid] = reinterpret_cast<const uint4 *>(pkb)[tid];
+        else if (tid < 2 * PR) reinterpret_cast<uint4 *>(sp_v + (size_t)drop * DH)[tid - PR] = reinterpret_cast<const uint4 *>(pvb)[tid - PR];
+        if (tid == 64) sp_idx[drop] = pidx;
+    }
+    const bf16_t *knew = a.k + (size_t)si * DH, *vnew = a.v + (size_t)si * DH;
+    if (tid >= 128 && tid < 128 + PR) reinterpret_cast<uint4 *>(win_k)[tid - 128] = reinterpret_cast<const uint4 *>(knew)[tid - 128];
+    else if (tid >= 192 && tid < 192 + PR) reinterpret_cast<uint4 *>(win_v)[tid - 192] = reinterpret_cast<const uint4 *>(vnew)[tid - 192];
+    if (tid == 0) a.st.n_tokens[si] = tok + 1;
 }
 
 
