@@ -402,7 +402,7 @@ def test_two_stream_prefill_from_two_host_threads():
             assert torch.equal(got, want)
 
 
-@pytest.mark.parametrize("lam", [64, 128])
+@pytest.mark.parametrize("lam", [64, 128, 256])
 def test_1b_shape_resume_ragged_multipass(lam):
     """The MFMA prefill kernels at the 1B head shape (head_dim 64, 128 features) across call boundaries that are
     not chunk-aligned, an update-only call and a multi-pass workspace; then generation steps (generic kernel)."""

@@ -268,7 +268,7 @@ def test_empty_caches_is_linear_attention(kind):
 
 # ---------------------------------------------------------------------------------------------
 # pin 3: lambda = 0 -> sliding window + linear attention base model, closed form
-# (efficiency appendix: "When lambda=0 ... recovering the SWA+LA base model")
+# (appendix "Efficiency Analysis", the lambda = 0 case)
 # ---------------------------------------------------------------------------------------------
 def swa_la_reference(q, k, v, Wq, Wk, eta, first_visible, g):
     """first_visible(t) = index of the oldest token query t reads by softmax; older ones are folded."""
