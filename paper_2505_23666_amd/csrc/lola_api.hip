@@ -197,7 +197,9 @@ bool wide_output_ok(const lola_config *c) {
 // shapes of the MFMA state-evolution kernel with run-time window and sparse budget (multiples of 64; it ranks by
 // self-recall error only); the shapes of the specialised kernels above keep those
 bool wide_scan_ok(const lola_config *c) {
-    return wide_output_ok(c) && !fast_output_ok(c) && c->score_kind == LOLA_SCORE_SRE && c->sparse_budget >= 64 &&
+    // (the compile-time shapes keep their own state-evolution kernel for the self-recall error; with the
+    // query-dependent scores, which are given to the selection instead of being computed by it, they come here too)
+    return wide_output_ok(c) && (!fast_output_ok(c) || c->score_kind != LOLA_SCORE_SRE) && c->sparse_budget >= 64 &&
            c->sparse_budget % 64 == 0 && c->window >= 64 && c->window % 64 == 0;
 }
 
@@ -524,7 +526,8 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
                 LAUNCH_CHECK();
                 const dim3 gp((unsigned)(jend - j0) + (unsigned)(c->sparse_budget / 64), (unsigned)ns);
 #define LOLA_WSCAN(DHV, DFV) do { hipLaunchKernelGGL((fast::phi_wide_kernel<DHV, DFV>), gp, dim3(256), 0, stream, a); \
-                                  hipLaunchKernelGGL((fast::scan_wide_kernel<DHV, DFV>), gs, dim3(DHV * 4), 0, stream, a); } while (0)
+                                  if (a.dm.score_kind) hipLaunchKernelGGL((fast::scan_wide_kernel<DHV, DFV, true>), gs, dim3(DHV * 4), 0, stream, a); \
+                                  else hipLaunchKernelGGL((fast::scan_wide_kernel<DHV, DFV, false>), gs, dim3(DHV * 4), 0, stream, a); } while (0)
                 if (c->head_dim == 128) { if (c->feat_dim == 256) LOLA_WSCAN(128, 256); else LOLA_WSCAN(128, 128); }
                 else { if (c->feat_dim == 256) LOLA_WSCAN(64, 256); else LOLA_WSCAN(64, 128); }
 #undef LOLA_WSCAN
@@ -535,7 +538,10 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
                     LAUNCH_CHECK();
                 }
                 a.scan_mode = 0;
-                if (a.want_out) {
+                if (a.want_out && fast_output_ok(c)) {   // (a compile-time shape with query-dependent scores)
+                    launch_output_kernel(c, a, j0, jend, stream);
+                    LAUNCH_CHECK();
+                } else if (a.want_out) {
                     const dim3 gw((unsigned)(jend - j0), (unsigned)a.dm.Hq, (unsigned)a.dm.B);
                     const bool f32o = c->out_dtype == LOLA_F32;
 #define LOLA_WIDE(DHV, DFV) do { if (f32o) hipLaunchKernelGGL((fast::attend_wide_kernel<DHV, DFV, float>), gw, dim3(256), 0, stream, a); \

@@ -1284,7 +1284,10 @@ __global__ __launch_bounds__(256) void phi_wide_kernel(generic::PrefillArgs<bf16
     }
 }
 
-template <int DH, int DF>
+// SCORED: the candidates' scores are given (the query-dependent scores of Sec. 4 / appendix "scoring ablation", summed
+// beforehand per token: tok_score for the pairs that leave the window, sp_score for the cache slots) instead of being
+// self-recall errors; step 2 is skipped, an entrant's score follows it into its slot, everything else is the same.
+template <int DH, int DF, bool SCORED>
 __global__ __launch_bounds__(DH * 4) void scan_wide_kernel(generic::PrefillArgs<bf16_t> a) {
     constexpr int C = 64, NW = DH / 16, NTH = 64 * NW, KF = DF / 32, NMT = DF / 16, PR = DH / 8, FR = 2 * DF, PP = DF / 8;
     constexpr int RB = 32, TB = RB / 16;                   // candidates per batch
@@ -1412,6 +1415,7 @@ __global__ __launch_bounds__(DH * 4) void scan_wide_kernel(generic::PrefillArgs<
             for (int x = 0; x < NSP; x++)
                 if (tid + NTH * x < LAM) a.snapG[sj * LAM + tid + NTH * x] = sprow_ld[x];
         }
+        if (!SCORED) {
 #pragma unroll
         for (int b = 0; b < NBUF - 1; b++) issue(b, b);   // lambda + 64 >= 128 candidates: at least four batches
 
@@ -1494,14 +1498,27 @@ __global__ __launch_bounds__(DH * 4) void scan_wide_kernel(generic::PrefillArgs<
             tot[k][(NBATCH - 1) * RB + r] = sum;
         }
         __syncthreads();
+        }
 
         // ---- 3. selection: the 64 candidates with the smallest squared error are folded (order: score descending,
         // token index ascending, the first lambda stay).  The squared error is |P|^2 / (phi.s)^2 - 2 P.v / (phi.s) + |v|^2
         // (recall = 0 while phi.s = 0); the bit pattern of a float >= 0 orders like an integer.
+        if (SCORED) {
+            // given scores (sums of non-negative terms): the cache slots' from the state, the leaving pairs' from the
+            // per-token sums of the call (row j C + x of the stream's block: token a0 - eta + j C + x)
+            const float *sps = a.st.sp_score + (size_t)si * LAM;
+            const float *tsc = a.tok_score + (size_t)si * (ETA + a.T_tokens) + (size_t)j * C;
+            for (int e = tid; e < NE; e += NTH) {
+                const float sc = e < LAM ? sps[e] : tsc[e - LAM];
+                tot[0][e] = sc;
+                skey[e] = __float_as_uint(sc) & 0x7FFFFFFFu;
+            }
+        } else {
         for (int e = tid; e < NE; e += NTH) {
             const float dn = dn_l[e], rd = dn > 0.f ? __builtin_amdgcn_rcpf(dn) : 0.f;
             const float sq = fmaxf(fmaf(rd * rd, tot[0][e], fmaf(-2.0f * rd, tot[1][e], tot[2][e])), 0.f);
             skey[e] = __float_as_uint(sq) & 0x7FFFFFFFu;
+        }
         }
         __syncthreads();
         if (w == 0) {
@@ -1672,6 +1689,7 @@ __global__ __launch_bounds__(DH * 4) void scan_wide_kernel(generic::PrefillArgs<
             sp_idx[sl] = ti;
             cidx[sl] = ti;
             sp_row[sl] = vrow_l + (e - LAM);
+            if (SCORED) a.st.sp_score[(size_t)si * LAM + sl] = tot[0][e];
         }
         __syncthreads();   // (workgroup scope is enough: only this workgroup reads the stream's memories before the kernel ends)
         if (a.sel_trace) {

@@ -256,6 +256,30 @@ def test_query_dependent_scores_fp32_cold_decode_and_8b_shape():
     say("query-dependent scores, 8B head shape", rep, rep2)
 
 
+@pytest.mark.parametrize("kind,d,D,eta,lam", [(1, 128, 128, 64, 128), (2, 64, 128, 64, 64), (3, 128, 256, 128, 64), (4, 128, 128, 192, 256)])
+def test_query_dependent_scores_on_the_mfma_prefill_kernels(kind, d, D, eta, lam):
+    """The four query-dependent scores (Sec. 4 / appendix "scoring ablation") where the selection, fold and outputs of
+    the prefill run on the MFMA kernels (the sums are given to the selection): three calls on one state (ragged tail,
+    resumed mid-chunk, several workspace passes), every selection, output, state element and per-slot sum against the
+    oracle; then generation steps."""
+    sh = wl.Shape("qscore_mfma", "bf16", 2, 4, 2, d, D, T=0, eta=eta, lam=lam, C=64, seed=0)
+    n_fill = (eta + lam) // 64
+    cuts = [0, 64 * (n_fill + 3) + 23]
+    cuts.append(cuts[-1] + 64 * 3)
+    cuts.append(cuts[-1] + 64 * 5 + 7)
+    nd = 4
+    q, k, v, Wq, Wk = rand_case(900 + kind + d + D, 2, 4, 2, d, D, cuts[-1] + nd, "bf16")
+    kw = dict(score_kind=kind)
+    layer, o = None, None
+    for i in range(3):
+        a, b = cuts[i], cuts[i + 1]
+        layer, o, rep = P.prefill_parity(sh, q[:, :, a:b], k[:, :, a:b], v[:, :, a:b], Wq, Wk, layer=layer, oracle=o, layer_kw=kw,
+                                         workspace_limit=0 if i == 2 else None)
+        say("query-dependent scores on the MFMA prefill kernels, call", kind, i, layer.lola_path, rep)
+    rep2 = P.decode_parity(sh, layer, o, *steps(q, k, v, cuts[3], nd), Wq, Wk)
+    say("query-dependent scores on the MFMA prefill kernels, generation steps", rep2)
+
+
 @pytest.mark.parametrize("g", [1, 2, 3])
 def test_mfma_kernels_with_other_group_sizes(g):
     """Multi-head attention (one query head per kv head) and small groups on the MFMA kernels: the
