@@ -37,13 +37,14 @@ bool fast_decode_ok(const lola_config *c) {
 // to its key limit, 128 or 256 features), the shape-generic kernel keeping the update of the memories ...
 bool wide_step_out_ok(const lola_config *c) {
     return c->dtype == LOLA_BF16 && (c->head_dim == 128 || c->head_dim == 64) && (c->feat_dim == 128 || c->feat_dim == 256) &&
-           c->window >= 1 && c->score_kind == LOLA_SCORE_SRE && !fast_decode_ok(c) && c->n_q_heads / c->n_kv_heads <= 4 &&
+           c->window >= 1 && !fast_decode_ok(c) && c->n_q_heads / c->n_kv_heads <= 4 &&
            c->sparse_budget + c->window <= fast::STEP_OUT_NKMAX;
 }
 // ... and at which the streams in steady state are updated by the MFMA update kernel ahead of it (sparse budgets in
 // multiples of 64).
 bool wide_decode_ok(const lola_config *c) {
-    return wide_step_out_ok(c) && c->sparse_budget >= 64 && c->sparse_budget % 64 == 0 && c->sparse_budget <= fast::STEP_UPDATE_LAMMAX;
+    return wide_step_out_ok(c) && c->score_kind == LOLA_SCORE_SRE && c->sparse_budget >= 64 && c->sparse_budget % 64 == 0 &&
+           c->sparse_budget <= fast::STEP_UPDATE_LAMMAX;
 }
 
 lola_status check_config(const lola_config *c) {
@@ -199,7 +200,8 @@ bool wide_output_ok(const lola_config *c) {
 bool wide_scan_ok(const lola_config *c) {
     // (the compile-time shapes keep their own state-evolution kernel for the self-recall error; with the
     // query-dependent scores, which are given to the selection instead of being computed by it, they come here too)
-    return wide_output_ok(c) && (!fast_output_ok(c) || c->score_kind != LOLA_SCORE_SRE) && c->sparse_budget >= 64 &&
+    // (sparse budget 0: no selection, every leaving pair is folded; at window 64 the row-split kernel is faster)
+    return wide_output_ok(c) && (!fast_output_ok(c) || (c->score_kind != LOLA_SCORE_SRE && c->sparse_budget > 0)) &&
            c->sparse_budget % 64 == 0 && c->window >= 64 && c->window % 64 == 0;
 }
 
@@ -314,7 +316,7 @@ lola_status run_decode(const lola_config *c, const lola_state *st, const void *q
             auto launch = [&](auto *o) {
                 using TO = std::remove_pointer_t<decltype(o)>;
                 fast::StepOutArgs<TO> oa;
-                oa.st = a.st; oa.q = a.q; oa.Wq = a.Wq; oa.out = (TO *)out;
+                oa.st = a.st; oa.q = a.q; oa.Wq = a.Wq; oa.Wk = a.Wk; oa.out = (TO *)out; oa.score_kind = a.dm.score_kind;
                 oa.Hq = a.dm.Hq; oa.Hkv = a.dm.Hkv; oa.g = a.dm.g; oa.lam = a.dm.lam; oa.eta = a.dm.eta;
                 oa.phi_kind = a.dm.phi_kind; oa.hide = a.dm.hide; oa.scale = a.dm.scale;
                 if (c->head_dim == 128) {
@@ -473,7 +475,22 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
         hipLaunchKernelGGL((generic::prefix_kernel<T>), dim3((unsigned)ns, parts), block, 0, stream, a);
     }
     LAUNCH_CHECK();
-    if (a.dm.score_kind) {   // the query-dependent scores of every pair the call touches, before the state evolves
+    bool band_done = false;
+    if constexpr (std::is_same<T, bf16_t>::value) {
+        if (a.dm.score_kind && wide_scan_ok(c)) {   // the MFMA form of the same sums
+            const dim3 gb((unsigned)(((size_t)a.dm.eta + Tn + 63) / 64), (unsigned)ns);
+            if (c->head_dim == 128) {
+                if (c->feat_dim == 256) hipLaunchKernelGGL((fast::band_score_wide_kernel<128, 256>), gb, dim3(256), 0, stream, a);
+                else hipLaunchKernelGGL((fast::band_score_wide_kernel<128, 128>), gb, dim3(256), 0, stream, a);
+            } else {
+                if (c->feat_dim == 256) hipLaunchKernelGGL((fast::band_score_wide_kernel<64, 256>), gb, dim3(256), 0, stream, a);
+                else hipLaunchKernelGGL((fast::band_score_wide_kernel<64, 128>), gb, dim3(256), 0, stream, a);
+            }
+            LAUNCH_CHECK();
+            band_done = true;
+        }
+    }
+    if (a.dm.score_kind && !band_done) {   // the query-dependent scores of every pair the call touches, before the state evolves
         if (a.R2 <= 0) return LOLA_ERR_UNSUPPORTED;
         const size_t lds_band = 4 * ((size_t)a.R2 * (2 * (d + D) + 1));
         const dim3 gb((unsigned)(((size_t)a.dm.eta + Tn + a.R2 - 1) / a.R2), (unsigned)ns);

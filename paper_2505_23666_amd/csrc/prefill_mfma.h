@@ -1415,7 +1415,7 @@ __global__ __launch_bounds__(DH * 4) void scan_wide_kernel(generic::PrefillArgs<
             for (int x = 0; x < NSP; x++)
                 if (tid + NTH * x < LAM) a.snapG[sj * LAM + tid + NTH * x] = sprow_ld[x];
         }
-        if (!SCORED) {
+        if (!SCORED && LAM > 0) {
 #pragma unroll
         for (int b = 0; b < NBUF - 1; b++) issue(b, b);   // lambda + 64 >= 128 candidates: at least four batches
 
@@ -1503,7 +1503,11 @@ __global__ __launch_bounds__(DH * 4) void scan_wide_kernel(generic::PrefillArgs<
         // ---- 3. selection: the 64 candidates with the smallest squared error are folded (order: score descending,
         // token index ascending, the first lambda stay).  The squared error is |P|^2 / (phi.s)^2 - 2 P.v / (phi.s) + |v|^2
         // (recall = 0 while phi.s = 0); the bit pattern of a float >= 0 orders like an integer.
-        if (SCORED) {
+        if (LAM == 0) {
+            // no sparse cache: nothing to select, every pair that leaves is folded
+            if (tid < C) flist[tid] = tid;
+            if (tid == 0) ne_s = 0;
+        } else if (SCORED) {
             // given scores (sums of non-negative terms): the cache slots' from the state, the leaving pairs' from the
             // per-token sums of the call (row j C + x of the stream's block: token a0 - eta + j C + x)
             const float *sps = a.st.sp_score + (size_t)si * LAM;
@@ -1521,7 +1525,7 @@ __global__ __launch_bounds__(DH * 4) void scan_wide_kernel(generic::PrefillArgs<
         }
         }
         __syncthreads();
-        if (w == 0) {
+        if (w == 0 && LAM > 0) {
             // One wavefront holds all scores (up to 17 per lane) and builds the 64th smallest bit by bit: a trial value is
             // kept while fewer than 64 scores lie below it.  Scores equal to the threshold are folded too if that makes
             // exactly 64; otherwise (exact ties across the cut) the same search over their token indices picks the
@@ -1718,12 +1722,15 @@ __global__ __launch_bounds__(DH * 4) void scan_wide_kernel(generic::PrefillArgs<
 //      tiles in flight) and reads them as B operand through the transposing LDS read;
 //   5. phi(q)^T H on MFMA with H^T read from memory and split into bf16 high + low parts on the way;
 //   6. y = (sum w v + e^(-m) phi(q)^T H) / (sum w + e^(-m) phi(q)^T s).
+// With a query-dependent score (Sec. 4 / appendix "scoring ablation") the step's queries also add their terms to the
+// sums of the pairs in the window (between 2 and 3: phi of the window keys on MFMA, phi(q) phi(k)^T against the
+// queries' features in LDS, the logits still in LDS as fp32), as the shape-generic step does.
 template <typename TO>
 struct StepOutArgs {
     State<bf16_t> st;
-    const bf16_t *q, *Wq;
+    const bf16_t *q, *Wq, *Wk;
     TO *out;
-    int Hq, Hkv, g, lam, eta, phi_kind, hide;
+    int Hq, Hkv, g, lam, eta, phi_kind, hide, score_kind;
     float scale;
 };
 
@@ -1814,6 +1821,51 @@ __global__ __launch_bounds__(256) void step_out_wide_kernel(StepOutArgs<TO> a) {
         }
     }
     __syncthreads();
+    if (a.score_kind) {
+        const bf16_t *Wk = a.Wk + (size_t)h * M * DH;
+        float *wsc = a.st.win_score + (size_t)si * ETA;
+        bf16x8 Ahi[KF], Alo[KF];
+#pragma unroll
+        for (int ks = 0; ks < KF; ks++) {
+            Ahi[ks] = r16 < G ? as_bf16x8(*reinterpret_cast<const uint4 *>(&PQ[r16][0][(4 * ks + g4) << 3])) : zero_bf16x8();
+            Alo[ks] = r16 < G ? as_bf16x8(*reinterpret_cast<const uint4 *>(&PQ[r16][1][(4 * ks + g4) << 3])) : zero_bf16x8();
+        }
+        for (int t = w; t < (wn + 15) / 16; t += 4) {
+            const int kk = 16 * t + r16;       // ring slot
+            const bool valid = kk < wn;
+            const bf16_t *kr = win_k + (size_t)(valid ? kk : 0) * DH;
+            bf16x8 BK[KS];
+#pragma unroll
+            for (int ks = 0; ks < KS; ks++) BK[ks] = ld_bf16x8(kr + 32 * ks + 8 * g4);
+            f32x4 zt[NZT];
+#pragma unroll
+            for (int mt = 0; mt < NZT; mt++) {
+                zt[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < KS; ks++)
+                    zt[mt] = mfma16(ld_bf16x8(Wk + (size_t)(16 * mt + r16) * DH + 32 * ks + 8 * g4), BK[ks], zt[mt]);
+            }
+            float pp[4 * NZT], pn[4 * NZT];
+            phi_from_z_tiles<NZT>(zt, a.phi_kind, pp, pn);
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acc2 = {0.f, 0.f, 0.f, 0.f}, acc3 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KF; ks++) {
+                bf16x8 Bh, Bl;
+                split8(ks < KF / 2 ? &pp[8 * ks] : &pn[8 * (ks - KF / 2)], Bh, Bl);
+                acc = mfma16(Ahi[ks], Bh, acc);
+                acc2 = mfma16(Ahi[ks], Bl, acc2);
+                acc3 = mfma16(Alo[ks], Bh, acc3);
+            }
+            if (g4 == 0 && valid) {   // rows 0..3 of the tile: the queries; column: this lane's key
+                float add = 0.f;
+#pragma unroll
+                for (int i = 0; i < G; i++)
+                    if (i < g) add += generic::query_term(a.score_kind, lg[i][spc + kk], acc[i] + (acc2[i] + acc3[i]));
+                wsc[kk] += add;
+            }
+        }
+        __syncthreads();   // the logits are overwritten next
+    }
     // ---- 3. weights of query w: m = max(0, max logit) (the linear terms carry weight e^(-m) <= 1)
     if (w < g) {
         float mx = 0.f;
@@ -2179,6 +2231,122 @@ __global__ __launch_bounds__(512) void step_update_wide_kernel(StepUpdateArgs a)
     if (tid >= 128 && tid < 128 + PR) reinterpret_cast<uint4 *>(win_k)[tid - 128] = reinterpret_cast<const uint4 *>(knew)[tid - 128];
     else if (tid >= 192 && tid < 192 + PR) reinterpret_cast<uint4 *>(win_v)[tid - 192] = reinterpret_cast<const uint4 *>(vnew)[tid - 192];
     if (tid == 0) a.st.n_tokens[si] = tok + 1;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Query-dependent scores of a prefill call on MFMA (Sec. 4 / appendix "scoring ablation"; same sums as
+// generic::band_score_kernel): row x of tok_score belongs to token a0 - eta + x (x < eta: the window the call found,
+// then the call's tokens) and receives what the pair had gathered before the call plus, over all query heads of the
+// group, the terms of the call's queries i with x - eta <= i <= x - 1 (the queries that see the key inside the sliding
+// window).  Grid (tile of 64 keys, stream), one wavefront per 16 keys: phi of its keys stays in registers as the B
+// operand (bf16 high + low parts); the (query head, tile of 16 queries) pairs of the band are taken four at a time:
+// wavefront w computes phi of the queries of pair w into LDS, then every wavefront forms Q K^T and phi(Q) phi(K)^T of
+// all four against its keys and adds the terms inside the band.
+template <int DH, int DF>
+__global__ __launch_bounds__(256) void band_score_wide_kernel(generic::PrefillArgs<bf16_t> a) {
+    constexpr int M = DF / 2, KS = DH / 32, NZT = M / 16, KF = DF / 32;
+    __shared__ __attribute__((aligned(16))) uint16_t PQ[4][2][16 * DF];   // phi of four query tiles, high / low parts, operand order
+    const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, r16 = lane & 15, g4 = lane >> 4;
+    const int si = blockIdx.y, b = si / a.dm.Hkv, h = si % a.dm.Hkv, g = a.dm.g;
+    const int ETA = a.dm.eta, LAM = a.dm.lam, P = LAM + ETA, Tn = a.T_tokens, nrows = ETA + Tn, kind = a.dm.score_kind;
+    const int64_t a0 = a.st.n_tokens[si];
+    const int x0 = 64 * (int)blockIdx.x, x = x0 + 16 * w + r16;
+    const bool kvalid = x < nrows && a0 - ETA + x >= 0;
+    const int xr = x < nrows ? x : nrows - 1;   // (rows past the end read the last row; their sums are not stored)
+    const bf16_t *kr = xr < ETA ? a.prefK + ((size_t)si * P + LAM + xr) * DH : a.k + ((size_t)si * Tn + (xr - ETA)) * DH;
+    const bf16_t *Wk = a.Wk + (size_t)h * M * DH;
+
+    bf16x8 BK[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) BK[ks] = ld_bf16x8(kr + 32 * ks + 8 * g4);
+    bf16x8 Bh[KF], Bl[KF];
+    {
+        f32x4 zt[NZT];
+#pragma unroll
+        for (int mt = 0; mt < NZT; mt++) {
+            zt[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ks++)
+                zt[mt] = mfma16(ld_bf16x8(Wk + (size_t)(16 * mt + r16) * DH + 32 * ks + 8 * g4), BK[ks], zt[mt]);
+        }
+        float pp[4 * NZT], pn[4 * NZT];
+        phi_from_z_tiles<NZT>(zt, a.dm.phi_kind, pp, pn);
+#pragma unroll
+        for (int ks = 0; ks < KF / 2; ks++) {
+            split8(&pp[8 * ks], Bh[ks], Bl[ks]);
+            split8(&pn[8 * ks], Bh[KF / 2 + ks], Bl[KF / 2 + ks]);
+        }
+    }
+    // queries that see some key of the tile
+    const int i_lo = max(0, x0 - ETA), i_hi = min(Tn - 1, x0 + 62);
+    const int nqt = i_hi >= i_lo ? (i_hi - i_lo) / 16 + 1 : 0, np = g * nqt;
+    float sum = 0.f;
+#pragma unroll 1
+    for (int p0 = 0; p0 < np; p0 += 4) {
+        if (p0 + w < np) {   // phi of the 16 queries of pair p0 + w (lane (column = query r16, group g4))
+            const int r = (p0 + w) / nqt, qt = (p0 + w) - r * nqt, hq = h * g + r;
+            const int iq = min(i_lo + 16 * qt + r16, i_hi);
+            const bf16_t *qr = a.q + (((size_t)b * a.dm.Hq + hq) * Tn + iq) * DH;
+            const bf16_t *Wq = a.Wq + (size_t)hq * M * DH;
+            bf16x8 BQ[KS];
+#pragma unroll
+            for (int ks = 0; ks < KS; ks++) BQ[ks] = ld_bf16x8(qr + 32 * ks + 8 * g4);
+            f32x4 zt[NZT];
+#pragma unroll
+            for (int mt = 0; mt < NZT; mt++) {
+                zt[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < KS; ks++)
+                    zt[mt] = mfma16(ld_bf16x8(Wq + (size_t)(16 * mt + r16) * DH + 32 * ks + 8 * g4), BQ[ks], zt[mt]);
+            }
+            float pp[4 * NZT], pn[4 * NZT];
+            phi_from_z_tiles<NZT>(zt, a.dm.phi_kind, pp, pn);
+#pragma unroll
+            for (int ks = 0; ks < KF / 2; ks++) {
+                bf16x8 hi, lo;
+                split8(&pp[8 * ks], hi, lo);
+                *reinterpret_cast<uint4 *>(&PQ[w][0][r16 * DF + (((4 * ks + g4) ^ r16) << 3)]) = __builtin_bit_cast(uint4, hi);
+                *reinterpret_cast<uint4 *>(&PQ[w][1][r16 * DF + (((4 * ks + g4) ^ r16) << 3)]) = __builtin_bit_cast(uint4, lo);
+                split8(&pn[8 * ks], hi, lo);
+                *reinterpret_cast<uint4 *>(&PQ[w][0][r16 * DF + (((4 * (KF / 2 + ks) + g4) ^ r16) << 3)]) = __builtin_bit_cast(uint4, hi);
+                *reinterpret_cast<uint4 *>(&PQ[w][1][r16 * DF + (((4 * (KF / 2 + ks) + g4) ^ r16) << 3)]) = __builtin_bit_cast(uint4, lo);
+            }
+        }
+        __syncthreads();
+#pragma unroll 1
+        for (int u = 0; u < 4; u++) {
+            if (p0 + u >= np) break;
+            const int r = (p0 + u) / nqt, qt = (p0 + u) - r * nqt, hq = h * g + r;
+            const int iqa = min(i_lo + 16 * qt + r16, i_hi);   // A operand: row = query r16 of the tile
+            const bf16_t *qr = a.q + (((size_t)b * a.dm.Hq + hq) * Tn + iqa) * DH;
+            f32x4 S = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ks++) S = mfma16(ld_bf16x8(qr + 32 * ks + 8 * g4), BK[ks], S);
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acc2 = {0.f, 0.f, 0.f, 0.f}, acc3 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KF; ks++) {
+                const int addr = r16 * DF + (((4 * ks + g4) ^ r16) << 3);
+                const bf16x8 Ah = as_bf16x8(*reinterpret_cast<const uint4 *>(&PQ[u][0][addr])), Al = as_bf16x8(*reinterpret_cast<const uint4 *>(&PQ[u][1][addr]));
+                acc = mfma16(Ah, Bh[ks], acc);
+                acc2 = mfma16(Ah, Bl[ks], acc2);
+                acc3 = mfma16(Al, Bh[ks], acc3);
+            }
+            // lane (key r16 of this wavefront's tile, group g4): queries i_lo + 16 qt + 4 g4 + i
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                const int iq = i_lo + 16 * qt + 4 * g4 + i;
+                if (kvalid && iq <= i_hi && iq >= x - ETA && iq <= x - 1)
+                    sum += generic::query_term(kind, S[i] * a.dm.scale, acc[i] + (acc2[i] + acc3[i]));
+            }
+        }
+        __syncthreads();
+    }
+    sum = grp_sum(sum);
+    if (g4 == 0 && x < nrows) {
+        const int64_t t = a0 - ETA + x;
+        const float prior = (x < ETA && t >= 0) ? a.st.win_score[(size_t)si * ETA + (int)(t % ETA)] : 0.f;
+        a.tok_score[(size_t)si * nrows + x] = kvalid ? prior + sum : 0.f;
+    }
 }
 
 

@@ -511,7 +511,7 @@ def test_paper_scale_cache_parameters(eta, lam, chunk):
 
 
 @pytest.mark.parametrize("d,D,eta,lam,phi_kind", [(128, 256, 128, 192, 0), (128, 128, 128, 64, 1), (64, 128, 192, 320, 0),
-                                                  (64, 256, 64, 128, 1), (128, 128, 64, 512, 0)])
+                                                  (64, 256, 64, 128, 1), (128, 128, 64, 512, 0), (128, 128, 192, 0, 0), (64, 256, 128, 0, 1)])
 def test_run_time_window_and_budget_on_the_mfma_prefill_kernels(d, D, eta, lam, phi_kind):
     """The MFMA state-evolution and output kernels with run-time window and sparse budget (multiples of 64) at every
     head / feature dimension they are built for, both feature maps.  Three calls on one state: from empty memories with
