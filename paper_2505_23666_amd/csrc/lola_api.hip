@@ -43,8 +43,7 @@ bool wide_step_out_ok(const lola_config *c) {
 // ... and at which the streams in steady state are updated by the MFMA update kernel ahead of it (sparse budgets in
 // multiples of 64).
 bool wide_decode_ok(const lola_config *c) {
-    return wide_step_out_ok(c) && c->score_kind == LOLA_SCORE_SRE && c->sparse_budget >= 64 && c->sparse_budget % 64 == 0 &&
-           c->sparse_budget <= fast::STEP_UPDATE_LAMMAX;
+    return wide_step_out_ok(c) && c->sparse_budget >= 64 && c->sparse_budget % 64 == 0 && c->sparse_budget <= fast::STEP_UPDATE_LAMMAX;
 }
 
 lola_status check_config(const lola_config *c) {
@@ -293,13 +292,11 @@ lola_status run_decode(const lola_config *c, const lola_state *st, const void *q
             fast::StepUpdateArgs ua;
             ua.st = a.st; ua.k = a.k; ua.v = a.v; ua.Wk = a.Wk;
             ua.Hkv = a.dm.Hkv; ua.lam = a.dm.lam; ua.eta = a.dm.eta; ua.phi_kind = a.dm.phi_kind;
-            if (c->head_dim == 128) {
-                if (c->feat_dim == 256) hipLaunchKernelGGL((fast::step_update_wide_kernel<128, 256>), grid, dim3(512), 0, stream, ua);
-                else hipLaunchKernelGGL((fast::step_update_wide_kernel<128, 128>), grid, dim3(512), 0, stream, ua);
-            } else {
-                if (c->feat_dim == 256) hipLaunchKernelGGL((fast::step_update_wide_kernel<64, 256>), grid, dim3(512), 0, stream, ua);
-                else hipLaunchKernelGGL((fast::step_update_wide_kernel<64, 128>), grid, dim3(512), 0, stream, ua);
-            }
+#define LOLA_UPD(DHV, DFV) do { if (a.dm.score_kind) hipLaunchKernelGGL((fast::step_update_wide_kernel<DHV, DFV, true>), grid, dim3(512), 0, stream, ua); \
+                                else hipLaunchKernelGGL((fast::step_update_wide_kernel<DHV, DFV, false>), grid, dim3(512), 0, stream, ua); } while (0)
+            if (c->head_dim == 128) { if (c->feat_dim == 256) LOLA_UPD(128, 256); else LOLA_UPD(128, 128); }
+            else { if (c->feat_dim == 256) LOLA_UPD(64, 256); else LOLA_UPD(64, 128); }
+#undef LOLA_UPD
             LAUNCH_CHECK();
             a.skip_steady = 1;
         }

@@ -2009,7 +2009,10 @@ struct StepUpdateArgs {
 
 constexpr int STEP_UPDATE_LAMMAX = 2048;
 
-template <int DH, int DF>
+// SCORED: the candidates' scores are the query-dependent sums kept in the state (Sec. 4 / appendix "scoring ablation":
+// sp_score per cache slot, the leaving pair's finished sum in its ring slot) instead of self-recall errors: step 2 is
+// skipped, the leaving pair's sum follows it into the cache, the new pair's sum starts at zero.
+template <int DH, int DF, bool SCORED>
 __global__ __launch_bounds__(512) void step_update_wide_kernel(StepUpdateArgs a) {
     constexpr int M = DF / 2, KS = DH / 32, NZT = M / 16, KF = DF / 32, NCT = DH / 16, NP = NCT * KF / 8, PR = DH / 8;
     constexpr int LAMMAX = STEP_UPDATE_LAMMAX;
@@ -2050,6 +2053,13 @@ __global__ __launch_bounds__(512) void step_update_wide_kernel(StepUpdateArgs a)
     for (int x = tid; x < DF; x += 512) s_l[x] = sg[x];
     for (int e = tid; e < LAM; e += 512) idx_l[e] = sp_idx[e];
     if (tid == 0) idx_l[LAM] = pidx;
+    float *wsc = nullptr, *sps = nullptr;
+    if (SCORED) {
+        wsc = a.st.win_score + (size_t)si * ETA + slot; sps = a.st.sp_score + (size_t)si * LAM;
+        for (int e = tid; e < LAM; e += 512) score[e] = sps[e];
+        if (tid == 0) score[LAM] = wsc[0];
+    }
+    if (!SCORED) {
 #pragma unroll
     for (int i = 0; i < NP; i++) {
         const float x8[8] = {hreg[i][0].x, hreg[i][0].y, hreg[i][0].z, hreg[i][0].w, hreg[i][1].x, hreg[i][1].y, hreg[i][1].z, hreg[i][1].w};
@@ -2057,6 +2067,7 @@ __global__ __launch_bounds__(512) void step_update_wide_kernel(StepUpdateArgs a)
         split8(x8, hi, lo);
         HA[((w + 8 * i) * 2 + 0) * 64 + lane] = __builtin_bit_cast(uint4, hi);
         HA[((w + 8 * i) * 2 + 1) * 64 + lane] = __builtin_bit_cast(uint4, lo);
+    }
     }
     __syncthreads();
 
@@ -2078,6 +2089,7 @@ __global__ __launch_bounds__(512) void step_update_wide_kernel(StepUpdateArgs a)
     };
 
     // ---- 2. self-recall errors
+    if (!SCORED) {
     if (w == 7) {   // the leaving pair's features (every column of the tile holds the same key: column 0 stores)
         float pp[4 * NZT], pn[4 * NZT];
         phi_tile(reinterpret_cast<const bf16_t *>(pkb), pp, pn);
@@ -2177,6 +2189,7 @@ __global__ __launch_bounds__(512) void step_update_wide_kernel(StepUpdateArgs a)
     __syncthreads();
     if (tid == 0) score[LAM] = sqrtf(errp[0] + errp[1]);
     __syncthreads();
+    }
 
     // ---- 3. the pair that goes: smallest score, ties -> the larger token index; its features and value as fp32
     if (w == 0) {
@@ -2226,7 +2239,9 @@ __global__ __launch_bounds__(512) void step_update_wide_kernel(StepUpdateArgs a)
         if (tid < PR) reinterpret_cast<uint4 *>(sp_k + (size_t)drop * DH)[tid] = reinterpret_cast<const uint4 *>(pkb)[tid];
         else if (tid < 2 * PR) reinterpret_cast<uint4 *>(sp_v + (size_t)drop * DH)[tid - PR] = reinterpret_cast<const uint4 *>(pvb)[tid - PR];
         if (tid == 64) sp_idx[drop] = pidx;
+        if (SCORED && tid == 65) sps[drop] = score[LAM];
     }
+    if (SCORED && tid == 66) wsc[0] = 0.f;
     const bf16_t *knew = a.k + (size_t)si * DH, *vnew = a.v + (size_t)si * DH;
     if (tid >= 128 && tid < 128 + PR) reinterpret_cast<uint4 *>(win_k)[tid - 128] = reinterpret_cast<const uint4 *>(knew)[tid - 128];
     else if (tid >= 192 && tid < 192 + PR) reinterpret_cast<uint4 *>(win_v)[tid - 192] = reinterpret_cast<const uint4 *>(vnew)[tid - 192];

@@ -109,7 +109,7 @@ def test_arguments_rejected_before_launch(L):
     assert f(C.byref(cs), C.byref(st), vp(fake), vp(fake), vp(fake), vp(fake), vp(fake), vp(fake), None) == -1   # score fields missing
     sts = lb.LolaState(*([fake] * 9 + [None] * 3 + [fake] * 2))
     assert p(cs, sts, None, vp(fake), None, 64, vp(fake), 1 << 40) == -5    # update-only call: these scores need queries
-    assert lb.lola_kernel_path(cs, 0) == "mfma" and lb.lola_kernel_path(cs, 1) == "mixed"   # step: update generic, outputs on MFMA
+    assert lb.lola_kernel_path(cs, 0) == "mfma" and lb.lola_kernel_path(cs, 1) == "mfma"    # the run-time-parameter kernels
     assert lb.lola_kernel_path(cfg(feat_dim=256, window=256, sparse_budget=256), 0) == "mfma"    # run-time window / budget kernels
     assert lb.lola_kernel_path(cfg(feat_dim=256, window=256, sparse_budget=200), 0) == "mixed"   # budget not a multiple of 64
     assert lb.lola_kernel_path(cfg(feat_dim=256, window=256, sparse_budget=256, chunk=128), 0) == "generic"
