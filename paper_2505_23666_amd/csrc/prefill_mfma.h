@@ -1,4 +1,11 @@
-// Chunk-parallel output kernel of the prefill for the 8B head shape (bf16 storage) on gfx950.
+// MFMA kernels of the prefill (and, further down, of the generation step at the shapes the fused kernel of
+// decode_mfma.h does not cover) for gfx950, bf16 storage.  In file order: attend_fast_kernel / attend_wide_kernel
+// (chunk-parallel outputs, compile-time / run-time window and budget), phi_k_kernel, scan_fast_kernel (state evolution,
+// compile-time shapes), phi_wide_kernel, scan_wide_kernel (run-time shapes; also with given scores and without a
+// cache), step_out_wide_kernel, step_update_wide_kernel (generation step), band_score_wide_kernel (query-dependent
+// scores of a call), scan_nocache_kernel (no sparse cache, window 64).
+//
+// The chunk-parallel output kernel for the 8B head shape:
 //
 // One workgroup (four wavefronts) per (sequence, query head, chunk); every wavefront owns 16 of the
 // chunk's 64 queries.  All GEMMs are computed transposed (queries are MFMA columns), so that
@@ -1229,12 +1236,17 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
 //   * phi of every row is computed chunk-parallel beforehand (phi_wide_kernel): the pairs that leave the window in chunk
 //     j (phiK[j - jb]) and the cache slots as the launch finds them (phiE[slot], kept current by the compaction);
 //   * one wavefront per 16 rows of H^T (fp32 accumulators, split into bf16 high + low parts once per chunk);
-//   * the candidates' features and values stream through LDS in batches of RB rows, double-buffered, by direct
-//     global -> LDS loads issued one batch ahead; each wavefront runs the recall GEMM of the batch against its rows of
-//     H^T and leaves |P|^2, P.v, |v|^2 over its 16 value columns per candidate, summed over the wavefronts one batch
-//     later; phi(k).s is a plain dot product per row of the batch;
+//   * the candidates' features and values stream through LDS in batches of RB rows (NBUF buffers) by direct
+//     global -> LDS loads issued NBUF - 1 batches ahead; each wavefront runs the recall GEMM of the batch against its
+//     rows of H^T and leaves |P|^2, P.v, |v|^2 over its 16 value columns per candidate, summed over the wavefronts one
+//     batch later; phi(k).s is a plain dot product per row of the batch;
 //   * the fold reads both MFMA operands out of row-major LDS tiles (the 64 folded rows gathered by direct loads)
 //     through the transposing LDS read, the contraction index being the pair.
+// A sparse budget of 0 switches scoring and selection off (every leaving pair is folded).
+//
+// phi_wide_kernel: phi of the rows the evolution kernel reads (Sec. 2.3 eq. feature_map), 64 rows per workgroup, bf16
+// high + low parts in operand order: blocks [0, j1 - j0) the pairs that leave the window in chunk j0 + block (virtual
+// rows lam + j C + 0..63) -> phiK[j - jb]; the lam / 64 blocks behind them the cache slots -> phiE[slot].
 template <int DH, int DF>
 __global__ __launch_bounds__(256) void phi_wide_kernel(generic::PrefillArgs<bf16_t> a) {
     constexpr int M = DF / 2, C = 64, KS = DH / 32, NZT = M / 16, FR = 2 * DF;
