@@ -654,6 +654,41 @@ def test_generation_steps_replayed_from_a_hip_graph():
         say("graph replays match eager steps, fold_defer", defer)
 
 
+def test_three_launch_generation_step_replayed_from_a_hip_graph():
+    """The generation step at a run-time-parameter shape (update kernel, shape-generic kernel for streams still filling,
+    output kernel) captured into a HIP graph from an empty state: the replays take the streams through window filling,
+    cache filling and steady state, each checked against an eager layer fed the same tokens."""
+    sh = wl.Shape("graphwide", "bf16", 2, 4, 2, 128, 256, T=0, eta=64, lam=64, C=64, seed=0)
+    n = 64 + 64 + 20
+    q, k, v, Wq, Wk = rand_case(1234, 2, 4, 2, 128, 256, n, "bf16")
+    dWq, dWk = P.w_to_dev(Wq, sh.dtype), P.w_to_dev(Wk, sh.dtype)
+    dq, dk, dv = (P.to_dev(x, sh.dtype) for x in steps(q, k, v, 0, n))
+    eager, graphed = P.make_layer(sh), P.make_layer(sh)
+    assert eager.lola_path[1] == "mfma"
+    sq, sk_, sv = torch.empty_like(dq[0]), torch.empty_like(dk[0]), torch.empty_like(dv[0])
+    out_g = torch.empty((sh.B, sh.Hq, sh.d), dtype=torch.float32, device=P.DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):       # warm-up outside capture, on the capture stream
+        sq.copy_(dq[0]); sk_.copy_(dk[0]); sv.copy_(dv[0])
+        graphed.decode_step(sq, sk_, sv, dWq, dWk, out=out_g)
+    torch.cuda.current_stream().wait_stream(side)
+    ref = eager.decode_step(dq[0], dk[0], dv[0], dWq, dWk)
+    torch.cuda.synchronize()
+    assert torch.equal(ref, out_g)
+    gr = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(gr):
+        graphed.decode_step(sq, sk_, sv, dWq, dWk, out=out_g)
+    for i in range(1, n):
+        sq.copy_(dq[i]); sk_.copy_(dk[i]); sv.copy_(dv[i])
+        gr.replay()
+        ref = eager.decode_step(dq[i], dk[i], dv[i], dWq, dWk)
+        torch.cuda.synchronize()
+        assert torch.equal(ref, out_g), f"replay {i} differs from the eager step"
+    for name in ("H", "s", "sp_idx", "sp_k", "win_k", "n_tokens"):
+        assert torch.equal(getattr(eager, name), getattr(graphed, name)), name
+
+
 def test_prefill_replayed_from_a_hip_graph():
     """A prefill call large enough for the two-stream path, captured into a HIP graph: under capture the library keeps
     everything on the caller's stream.  Every replay (each continues the sequence with the same tokens) is checked
