@@ -1302,10 +1302,11 @@ __global__ __launch_bounds__(256) void phi_wide_kernel(generic::PrefillArgs<bf16
 template <int DH, int DF, bool SCORED>
 __global__ __launch_bounds__(DH * 4) void scan_wide_kernel(generic::PrefillArgs<bf16_t> a) {
     constexpr int C = 64, NW = DH / 16, NTH = 64 * NW, KF = DF / 32, NMT = DF / 16, PR = DH / 8, FR = 2 * DF, PP = DF / 8;
-    constexpr int RB = 32, TB = RB / 16;                   // candidates per batch
-    constexpr int NBUF = DF == 256 ? 3 : 4;                // batch buffers in LDS: requests run NBUF - 1 batches ahead
-    constexpr int LPB = RB * FR / 512 / NW + 1;            // direct loads per wavefront and batch: features, then values
-    static_assert(RB * DH / 512 == NW, "one instruction per wavefront covers the values of a batch");
+    constexpr int RB = DF == 256 ? 32 : 64, TB = RB / 16;  // candidates per batch (32 KB of features)
+    constexpr int NBUF = DF == 256 ? 3 : 2;                // batch buffers in LDS: requests run NBUF - 1 batches ahead
+    constexpr int VPB = RB * DH / 512 / NW;                // direct loads per wavefront and batch: values ...
+    constexpr int LPB = RB * FR / 512 / NW + VPB;          // ... and features + values
+    static_assert(VPB >= 1 && VPB * NW * 512 == RB * DH, "the wavefronts share the values of a batch evenly");
     constexpr int NEMAX = 1024 + C, NKMAX = NEMAX / 64;
     constexpr int BUF = RB * FR + RB * DH;                 // 16-bit elements of one batch buffer: features, then values
     constexpr int FOLD = C * FR + C * DH;                  // the folded pairs' features and values
@@ -1403,11 +1404,12 @@ __global__ __launch_bounds__(DH * 4) void scan_wide_kernel(generic::PrefillArgs<
                 __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
                                                  (__attribute__((address_space(3))) void *)(PBb + 512 * i), 16, 0, 0);
             }
-            {
-                const int g = 512 * w + 8 * lane, row = g / DH, slot = (g % DH) >> 3;
+#pragma unroll
+            for (int it = 0; it < VPB; it++) {
+                const int i = w + NW * it, g = 512 * i + 8 * lane, row = g / DH, slot = (g % DH) >> 3;
                 const bf16_t *src = vrow(e0 + row) + ((slot ^ (row & (PR - 1))) << 3);
                 __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                                 (__attribute__((address_space(3))) void *)(VBb + 512 * w), 16, 0, 0);
+                                                 (__attribute__((address_space(3))) void *)(VBb + 512 * i), 16, 0, 0);
             }
         };
         // (the snapshot's stores are issued ahead of the requests: the waits below count on the requests being the youngest
@@ -1429,7 +1431,7 @@ __global__ __launch_bounds__(DH * 4) void scan_wide_kernel(generic::PrefillArgs<
         }
         if (!SCORED && LAM > 0) {
 #pragma unroll
-        for (int b = 0; b < NBUF - 1; b++) issue(b, b);   // lambda + 64 >= 128 candidates: at least four batches
+        for (int b = 0; b < NBUF - 1; b++) issue(b, b);   // (lambda + 64 >= 128 candidates: at least NBUF batches)
 
         // ---- 2. recall error of the candidates, batch by batch
         int buf = 0;
@@ -1437,8 +1439,8 @@ __global__ __launch_bounds__(DH * 4) void scan_wide_kernel(generic::PrefillArgs<
         for (int b = 0; b < NBATCH; b++) {
             // this wavefront's share of batch b has landed: all but the requests of the batches behind it
             const int ahead = min(NBUF - 2, NBATCH - 1 - b);
-            if (ahead >= 2) __builtin_amdgcn_s_waitcnt(0x0F70 | ((2 * LPB) & 15) | (((2 * LPB) >> 4) << 14));
-            else if (ahead == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | (LPB & 15) | ((LPB >> 4) << 14));
+            if (NBUF >= 4 && ahead >= 2) __builtin_amdgcn_s_waitcnt(0x0F70 | ((2 * LPB) & 15) | (((2 * LPB) >> 4) << 14));
+            else if (NBUF >= 3 && ahead == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | (LPB & 15) | ((LPB >> 4) << 14));
             else __builtin_amdgcn_s_waitcnt(0x0F70);
             __syncthreads();                      // ... and everybody's; the readers of batch b - 1's buffer are done
             if (b + NBUF - 1 < NBATCH) issue(b + NBUF - 1, buf == 0 ? NBUF - 1 : buf - 1);
