@@ -131,7 +131,7 @@ def extras(torch, wl, lb, dev, only=None):
     rows.append(run("8B shape, queries do not read the hidden state", **s8, query_hide=1, fold_defer=8))
     rows.append(run("8B shape, attention-weight score (kind 4)", **s8, score_kind=4))
     rows.append(run("8B shape, squared weight-error score (kind 1)", **s8, score_kind=1))
-    long = dict(B=4, Hq=32, Hkv=8, d=128, D=256, Cc=64, T=2048, n_dec=36)
+    long = dict(B=4, Hq=32, Hkv=8, d=128, D=256, Cc=64, T=2048, n_dec=36, prefill_overlap=1)
     rows.append(run("long-context cache parameters eta=lambda=256, D=2d", eta=256, lam=256, **long))
     rows.append(run("long-context cache parameters eta=lambda=512, D=2d", eta=512, lam=512, **long))
     rows.append(run("long-context cache parameters eta=128, lambda=768, D=2d", eta=128, lam=768, **long))

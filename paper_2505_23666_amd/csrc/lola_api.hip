@@ -398,12 +398,21 @@ SideStream *side_stream(hipStream_t caller) {
     return state[dev] == 1 ? &table[dev] : nullptr;
 }
 
-// outputs of the chunks [r0, r1) by the MFMA output kernel
+// outputs of the chunks [r0, r1) by the MFMA output kernels: the compile-time form where the shape has one, else the
+// form with run-time window and sparse budget
 void launch_output_kernel(const lola_config *c, const generic::PrefillArgs<bf16_t> &a, int r0, int r1, hipStream_t so) {
     generic::PrefillArgs<bf16_t> ao = a;
     ao.j0 = r0; ao.j1 = r1; ao.scan_mode = 0;
     const dim3 ga((unsigned)(r1 - r0), (unsigned)a.dm.Hq, (unsigned)a.dm.B);
     const bool f32o = c->out_dtype == LOLA_F32;
+    if (!fast_output_ok(c)) {
+#define LOLA_WIDE(DHV, DFV) do { if (f32o) hipLaunchKernelGGL((fast::attend_wide_kernel<DHV, DFV, float>), ga, dim3(256), 0, so, ao); \
+                                 else hipLaunchKernelGGL((fast::attend_wide_kernel<DHV, DFV, bf16_t>), ga, dim3(256), 0, so, ao); } while (0)
+        if (c->head_dim == 128) { if (c->feat_dim == 256) LOLA_WIDE(128, 256); else LOLA_WIDE(128, 128); }
+        else { if (c->feat_dim == 256) LOLA_WIDE(64, 256); else LOLA_WIDE(64, 128); }
+#undef LOLA_WIDE
+        return;
+    }
 #define LOLA_ATT2(LAMV, DHV) do { if (f32o) hipLaunchKernelGGL((fast::attend_fast_kernel<LAMV, DHV, float>), ga, dim3(256), 0, so, ao); \
                                   else hipLaunchKernelGGL((fast::attend_fast_kernel<LAMV, DHV, bf16_t>), ga, dim3(256), 0, so, ao); } while (0)
 #define LOLA_ATT(LAMV) do { if (c->head_dim == 128) LOLA_ATT2(LAMV, 128); else LOLA_ATT2(LAMV, 64); } while (0)
@@ -530,51 +539,20 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
                 }
                 continue;
             }
-            if (wide_scan_ok(c)) {
-                // Any window / budget in multiples of 64, 128 or 256 features: the generic kernel until the first regular
-                // chunk (a full chunk with a full window behind it and a full cache); phi of the rows the MFMA kernel
-                // reads (the pairs leaving the window in each chunk of the pass, and the cache slots as they are now); the
-                // MFMA kernel over the regular chunks; the generic kernel again for a ragged last chunk; the outputs.
-                a.scan_mode = 1;
-                hipLaunchKernelGGL((generic::scan_kernel<T>), gs, block, lds_scan, stream, a);
-                LAUNCH_CHECK();
-                const dim3 gp((unsigned)(jend - j0) + (unsigned)(c->sparse_budget / 64), (unsigned)ns);
-#define LOLA_WSCAN(DHV, DFV) do { hipLaunchKernelGGL((fast::phi_wide_kernel<DHV, DFV>), gp, dim3(256), 0, stream, a); \
-                                  if (a.dm.score_kind) hipLaunchKernelGGL((fast::scan_wide_kernel<DHV, DFV, true>), gs, dim3(DHV * 4), 0, stream, a); \
-                                  else hipLaunchKernelGGL((fast::scan_wide_kernel<DHV, DFV, false>), gs, dim3(DHV * 4), 0, stream, a); } while (0)
-                if (c->head_dim == 128) { if (c->feat_dim == 256) LOLA_WSCAN(128, 256); else LOLA_WSCAN(128, 128); }
-                else { if (c->feat_dim == 256) LOLA_WSCAN(64, 256); else LOLA_WSCAN(64, 128); }
-#undef LOLA_WSCAN
-                LAUNCH_CHECK();
-                if (jend == a.n_chunks && Tn % a.dm.C != 0) {
-                    a.scan_mode = 2;
-                    hipLaunchKernelGGL((generic::scan_kernel<T>), gs, block, lds_scan, stream, a);
+            const bool wide = wide_scan_ok(c);   // (run-time window / budget kernels; else the compile-time shapes)
+            if (wide || fast_attend_ok(c)) {
+                // The serial evolution in legs that hand the chunk position over in next_j: generic kernel until the first
+                // regular chunk (a full chunk with a full window behind it and a full cache), MFMA kernel over the regular
+                // chunks, generic kernel for what is left (a ragged last chunk); phi of the keys chunk-parallel
+                // beforehand: at the compile-time shapes of every key of the pass, at the run-time shapes (per piece,
+                // behind the generic leg) of the pairs that leave the window in each chunk and of the cache slots as
+                // they stand.
+                if (!wide) {
+                    const dim3 gp((unsigned)(jend - j0), (unsigned)ns);
+                    if (c->head_dim == 128) hipLaunchKernelGGL(fast::phi_k_kernel<128>, gp, dim3(256), 0, stream, a);
+                    else hipLaunchKernelGGL(fast::phi_k_kernel<64>, gp, dim3(256), 0, stream, a);
                     LAUNCH_CHECK();
                 }
-                a.scan_mode = 0;
-                if (a.want_out && fast_output_ok(c)) {   // (a compile-time shape with query-dependent scores)
-                    launch_output_kernel(c, a, j0, jend, stream);
-                    LAUNCH_CHECK();
-                } else if (a.want_out) {
-                    const dim3 gw((unsigned)(jend - j0), (unsigned)a.dm.Hq, (unsigned)a.dm.B);
-                    const bool f32o = c->out_dtype == LOLA_F32;
-#define LOLA_WIDE(DHV, DFV) do { if (f32o) hipLaunchKernelGGL((fast::attend_wide_kernel<DHV, DFV, float>), gw, dim3(256), 0, stream, a); \
-                                 else hipLaunchKernelGGL((fast::attend_wide_kernel<DHV, DFV, bf16_t>), gw, dim3(256), 0, stream, a); } while (0)
-                    if (c->head_dim == 128) { if (c->feat_dim == 256) LOLA_WIDE(128, 256); else LOLA_WIDE(128, 128); }
-                    else { if (c->feat_dim == 256) LOLA_WIDE(64, 256); else LOLA_WIDE(64, 128); }
-#undef LOLA_WIDE
-                    LAUNCH_CHECK();
-                }
-                continue;
-            }
-            if (fast_attend_ok(c)) {   // same shape conditions as the output kernel
-                // features of the pass's keys (chunk-parallel); then the serial evolution in legs that hand the chunk
-                // position over in next_j: generic kernel until the first regular chunk, MFMA kernel over the regular
-                // chunks, generic kernel for what is left (a ragged last chunk)
-                const dim3 gp((unsigned)(jend - j0), (unsigned)ns);
-                if (c->head_dim == 128) hipLaunchKernelGGL(fast::phi_k_kernel<128>, gp, dim3(256), 0, stream, a);
-                else hipLaunchKernelGGL(fast::phi_k_kernel<64>, gp, dim3(256), 0, stream, a);
-                LAUNCH_CHECK();
                 // With few streams the serial evolution occupies few compute units, so the pass is cut into pieces and
                 // the outputs of a piece (chunk-parallel, from its snapshots) run on a second stream beside the
                 // evolution of the next piece.
@@ -633,20 +611,35 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
                     const int p0 = bnd[ip];
                     a.j0 = p0;
                     a.j1 = bnd[ip + 1];
-                    if (ip == 0) {
+                    // At the compile-time shapes later pieces start on regular chunks (the first piece is longer than the
+                    // (lambda + eta) / C chunks after which the cache is full); with a long window and a large budget a
+                    // piece may still begin while they fill, so the run-time shapes run the generic leg in every piece (it
+                    // returns at once on a regular chunk).
+                    if (ip == 0 || wide) {
                         a.scan_mode = 1;
                         hipLaunchKernelGGL((generic::scan_kernel<T>), gs, block, lds_scan, stream, a);
                         LAUNCH_CHECK();
                     }
-                    // Later pieces start on regular chunks (the first piece is longer than the (lambda + eta) / C chunks
-                    // after which the cache is full), so the MFMA kernel continues at once.  The previous piece's outputs are
-                    // enqueued after it: it should be resident before the output workgroups arrive, instead of queueing
-                    // for compute units behind them.
+                    // The previous piece's outputs may start once the evolution kernel of this piece is next in line (the
+                    // event) and are enqueued after its launch: the evolution's workgroups, which need a compute unit's whole
+                    // register file, should be resident before the output workgroups arrive, instead of queueing for
+                    // compute units behind them.
+                    if (wide) {
+                        const dim3 gp((unsigned)(a.j1 - a.j0) + (unsigned)(c->sparse_budget / 64), (unsigned)ns);
+#define LOLA_WSCAN(DHV, DFV) do { hipLaunchKernelGGL((fast::phi_wide_kernel<DHV, DFV>), gp, dim3(256), 0, stream, a); \
+                                  if (side && ip > 0 && hipEventRecord(side->fork[ip - 1], stream) != hipSuccess) return LOLA_ERR_HIP; \
+                                  if (a.dm.score_kind) hipLaunchKernelGGL((fast::scan_wide_kernel<DHV, DFV, true>), gs, dim3(DHV * 4), 0, stream, a); \
+                                  else hipLaunchKernelGGL((fast::scan_wide_kernel<DHV, DFV, false>), gs, dim3(DHV * 4), 0, stream, a); } while (0)
+                        if (c->head_dim == 128) { if (c->feat_dim == 256) LOLA_WSCAN(128, 256); else LOLA_WSCAN(128, 128); }
+                        else { if (c->feat_dim == 256) LOLA_WSCAN(64, 256); else LOLA_WSCAN(64, 128); }
+#undef LOLA_WSCAN
+                    } else {
                     if (side && ip > 0 && hipEventRecord(side->fork[ip - 1], stream) != hipSuccess) return LOLA_ERR_HIP;
 #define LOLA_SCAN(LAMV) do { if (c->head_dim == 128) hipLaunchKernelGGL((fast::scan_fast_kernel<LAMV, 128, SCAN_RT128>), gs, dim3(512 / SCAN_RT128), 0, stream, a); \
                              else hipLaunchKernelGGL((fast::scan_fast_kernel<LAMV, 64, 1>), gs, dim3(256), 0, stream, a); } while (0)
                     if (c->sparse_budget == 64) LOLA_SCAN(64); else if (c->sparse_budget == 128) LOLA_SCAN(128); else LOLA_SCAN(256);
 #undef LOLA_SCAN
+                    }
                     LAUNCH_CHECK();
                     if (side && ip > 0 && !attend_aside(ip - 1, prev0, p0)) return LOLA_ERR_HIP;
                     if (a.j1 == a.n_chunks && Tn % a.dm.C != 0) {   // only a ragged last chunk is left to the generic kernel
@@ -682,13 +675,7 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
             }
             if constexpr (std::is_same<T, bf16_t>::value) {
                 if (!done && wide_att) {   // any window / budget, 128 or 256 features: the run-time form of the MFMA output kernel
-                    const dim3 gw((unsigned)(a.j1 - a.j0), (unsigned)a.dm.Hq, (unsigned)a.dm.B);
-                    const bool f32o = c->out_dtype == LOLA_F32;
-#define LOLA_WIDE(DHV, DFV) do { if (f32o) hipLaunchKernelGGL((fast::attend_wide_kernel<DHV, DFV, float>), gw, dim3(256), 0, stream, a); \
-                                 else hipLaunchKernelGGL((fast::attend_wide_kernel<DHV, DFV, bf16_t>), gw, dim3(256), 0, stream, a); } while (0)
-                    if (c->head_dim == 128) { if (c->feat_dim == 256) LOLA_WIDE(128, 256); else LOLA_WIDE(128, 128); }
-                    else { if (c->feat_dim == 256) LOLA_WIDE(64, 256); else LOLA_WIDE(64, 128); }
-#undef LOLA_WIDE
+                    launch_output_kernel(c, a, a.j0, a.j1, stream);
                     done = true;
                 }
             }

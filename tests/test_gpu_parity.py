@@ -342,6 +342,29 @@ def test_8b_shape_resume_ragged_multipass(lam, phi_kind):
         say("8b resume part", i, rep)
 
 
+def test_run_time_window_kernels_outputs_on_the_second_stream():
+    """The same at a run-time-parameter shape (window 128, budget 192, 256 features, batch 4): the pass is cut into pieces,
+    each piece runs the shape-generic leg (window and cache are still filling when the second piece would start at a larger
+    budget), the feature kernel and the MFMA evolution, the outputs of a piece on the second stream; against the oracle,
+    and bit for bit against a call that stays on one stream."""
+    sh = wl.Shape("wide2s", "bf16", 4, 32, 8, 128, 256, T=64 * 40 + 21, eta=128, lam=192, C=64, seed=0)
+    q, k, v, Wq, Wk = rand_case(4321, 4, 32, 8, 128, 256, sh.T, "bf16")
+    kw = dict(prefill_overlap=1)
+    layer, o, rep = P.prefill_parity(sh, q, k, v, Wq, Wk, layer_kw=kw)
+    say("two-stream call, run-time window / budget", layer.lola_path, rep)
+    dq, dk, dv = P.to_dev(q, "bf16"), P.to_dev(k, "bf16"), P.to_dev(v, "bf16")
+    dWq, dWk = P.w_to_dev(Wq, "bf16"), P.w_to_dev(Wk, "bf16")
+    ref_layer = P.make_layer(sh)
+    ref = ref_layer.prefill(dq, dk, dv, dWq, dWk).clone()
+    one = P.make_layer(sh, **kw)
+    out = one.prefill(dq, dk, dv, dWq, dWk)
+    torch.cuda.synchronize()
+    assert torch.equal(out, ref)
+    for name in ("H", "s", "sp_idx", "sp_k", "win_k", "n_tokens"):
+        assert torch.equal(getattr(one, name), getattr(ref_layer, name)), name
+    P.lb.lola_release_streams()
+
+
 def test_8b_shape_outputs_on_the_second_stream():
     """A call large enough that the MFMA prefill cuts its pass into pieces and runs the outputs of a
     piece on the library's second stream beside the evolution of the next one (batch 4, 33 chunks
