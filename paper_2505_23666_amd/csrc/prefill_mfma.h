@@ -546,6 +546,14 @@ __global__ __launch_bounds__(256) void phi_k_kernel(generic::PrefillArgs<bf16_t>
 // between the rows one wavefront writes at once (r2, r3, r5) and between the rows it reads at once (r0 .. r3).
 __device__ __forceinline__ int tswz(int r) { return ((((r >> 5) ^ (r >> 1)) & 1) << 2) | ((r >> 2) & 3); }
 
+// Piece swizzles of row-major LDS tiles that the transposing read consumes.  A 16-lane group of that read touches four
+// consecutive rows (pairs) x four consecutive 16-byte pieces (features) or two pieces x two halves (values); rows are a
+// multiple of 256 bytes apart, so the piece index is XOR-ed with row bits moved to where the group's pieces do not
+// differ: the two low row bits go to piece bits 2-3 (features: 16 distinct pieces per group; the swapped bit pairs also
+// keep the 16 rows of a plain operand read on 16 different pieces), or to piece bits 1-2 (values).
+__device__ __forceinline__ int fswz(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
+template <int PR> __device__ __forceinline__ int vswz2(int row) { return (row & (PR / 2 - 1)) << 1; }
+
 // Lanes whose value lies below a wavefront-uniform trial value, as a mask in scalar registers.  Written as an
 // instruction of its own so that the compares of one search step are issued back to back into masks of their own and
 // counted afterwards: compiled from a ballot, each compare writes the one condition register and its count waits for
@@ -1600,19 +1608,19 @@ __global__ __launch_bounds__(DH * 4) void scan_wide_kernel(generic::PrefillArgs<
         const int ne = ne_s;   // exactly 64 are folded, so entrants and leavers pair up
 
         // ---- 4. fold: H[f][c] += sum_e phi_e[f] v_e[c], s[f] += sum_e phi_e[f] over the 64 folded pairs, whose rows are
-        // gathered into LDS ([pair][part][position] and [pair][column], 16-byte pieces XOR-swizzled with the pair number)
+        // gathered into LDS ([pair][part][position] and [pair][column], 16-byte pieces XOR-swizzled with bits of the pair number: fswz, vswz2)
         uint16_t *FP = pool, *FV = pool + C * FR;
 #pragma unroll
         for (int it = 0; it < C * FR / 512 / NW; it++) {
             const int i = w + NW * it, g = 512 * i + 8 * lane, row = g / FR, pt = (g % FR) / DF, slot = (g % DF) >> 3;
-            const uint16_t *src = phirow(flist[row]) + pt * DF + ((slot ^ (row & 15)) << 3);
+            const uint16_t *src = phirow(flist[row]) + pt * DF + ((slot ^ fswz(row)) << 3);
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
                                              (__attribute__((address_space(3))) void *)(FP + 512 * i), 16, 0, 0);
         }
 #pragma unroll
         for (int it = 0; it < C * DH / 512 / NW; it++) {
             const int i = w + NW * it, g = 512 * i + 8 * lane, row = g / DH, slot = (g % DH) >> 3;
-            const bf16_t *src = vrow(flist[row]) + ((slot ^ (row & (PR - 1))) << 3);
+            const bf16_t *src = vrow(flist[row]) + ((slot ^ vswz2<PR>(row)) << 3);
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
                                              (__attribute__((address_space(3))) void *)(FV + 512 * i), 16, 0, 0);
         }
@@ -1640,15 +1648,15 @@ __global__ __launch_bounds__(DH * 4) void scan_wide_kernel(generic::PrefillArgs<
         // transposing read delivers them, the same for both operands)
 #pragma unroll
         for (int kst = 0; kst < 2; kst++) {
-            const int t0 = 32 * kst + 4 * g4 + (r16 >> 2), t15 = t0 & 15;
+            const int t0 = 32 * kst + 4 * g4 + (r16 >> 2), t15 = fswz(t0);
             // B: values, column 16 w + r16: lane i of a group points at pair t0's four columns 16 w + 4 (i % 4) ..
-            const uint16_t *vb = FV + t0 * DH + (((2 * w + ((r16 & 3) >> 1)) ^ (t0 & (PR - 1))) << 3) + 4 * (r16 & 1);
+            const uint16_t *vb = FV + t0 * DH + (((2 * w + ((r16 & 3) >> 1)) ^ vswz2<PR>(t0)) << 3) + 4 * (r16 & 1);
             const bf16x4 b0 = tr_read(vb), b1 = tr_read(vb + 16 * DH);
             const bf16x8 Bv = __builtin_shufflevector(b0, b1, 0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
             for (int mt = 0; mt < NMT; mt++) {
                 // A: phi^T, row f = 16 mt + r of the tile from position 32 (mt / 2) + 8 (r / 4) + 4 (mt % 2) + r % 4, i.e.
-                // 16-byte piece 4 (mt / 2) + r / 4 of the row (stored at that piece ^ pair % 16), its half mt % 2
+                // 16-byte piece 4 (mt / 2) + r / 4 of the row (stored at that piece ^ fswz(pair)), its half mt % 2
                 const int off = (((4 * (mt >> 1) + (r16 & 3)) ^ t15) << 3) + 4 * (mt & 1);
 #pragma unroll
                 for (int pt = 0; pt < 2; pt++) {
@@ -1668,7 +1676,7 @@ __global__ __launch_bounds__(DH * 4) void scan_wide_kernel(generic::PrefillArgs<
                 f32x4 sacc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int kst = 0; kst < 2; kst++) {
-                    const int t0 = 32 * kst + 4 * g4 + (r16 >> 2), t15 = t0 & 15;
+                    const int t0 = 32 * kst + 4 * g4 + (r16 >> 2), t15 = fswz(t0);
                     const int off = (((4 * (mt >> 1) + (r16 & 3)) ^ t15) << 3) + 4 * (mt & 1);
 #pragma unroll
                     for (int pt = 0; pt < 2; pt++) {
@@ -1916,14 +1924,14 @@ __global__ __launch_bounds__(256) void step_out_wide_kernel(StepOutArgs<TO> a) {
 #pragma unroll
         for (int ct = 0; ct < NCT; ct++) acc[ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
         auto stage = [&](int kb, int buf) {
-            // 1 KB per instruction = 2048 / DH rows; lane l fills bytes 16 l ..: the row's piece (l % PR) ^ (row % PR)
+            // 1 KB per instruction = 2048 / DH rows; lane l fills bytes 16 l ..: the row's piece (l % PR) ^ vswz2(row)
 #pragma unroll
             for (int i = 0; i < 32 * DH / 512; i++) {
                 const int row = (512 * i + 8 * lane) / DH, slot = lane % PR;
                 int key = 32 * kb + row;
                 if (key >= nk) key = 0;   // weight 0: any readable row will do
                 const bf16_t *vr = key < spc ? sp_v + (size_t)key * DH : win_v + (size_t)(key - spc) * DH;
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(vr + ((slot ^ (row & (PR - 1))) << 3)),
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(vr + ((slot ^ vswz2<PR>(row)) << 3)),
                                                  (__attribute__((address_space(3))) void *)(&VS[w][buf][512 * i]), 16, 0, 0);
             }
         };
@@ -1945,7 +1953,7 @@ __global__ __launch_bounds__(256) void step_out_wide_kernel(StepOutArgs<TO> a) {
             const uint16_t *vb = &VS[w][buf][t0 * DH + 4 * (r16 & 1)];
 #pragma unroll
             for (int ct = 0; ct < NCT; ct++) {
-                const int pc = ((2 * ct + ((r16 & 3) >> 1)) ^ (t0 & (PR - 1))) << 3;
+                const int pc = ((2 * ct + ((r16 & 3) >> 1)) ^ vswz2<PR>(t0)) << 3;
                 const bf16x4 b0 = tr_read(vb + pc), b1 = tr_read(vb + 16 * DH + pc);
                 const bf16x8 Bv = __builtin_shufflevector(b0, b1, 0, 1, 2, 3, 4, 5, 6, 7);
                 acc[ct] = mfma16(Ahi, Bv, acc[ct]);
@@ -2440,14 +2448,14 @@ __global__ __launch_bounds__(64) void scan_nocache_kernel(generic::PrefillArgs<b
         }
         if (j - 1 >= a.jb) {
             // the feature kernel's rows of chunk j - 1: 32 KB.  An instruction fills 1 KB = two rows; lane l fills part
-            // (l / 16) % 2 of row 2 i + l / 32 at 16-byte position l % 16, which holds the row's piece (l % 16) ^ (row % 16):
+            // (l / 16) % 2 of row 2 i + l / 32 at 16-byte position l % 16, which holds the row's piece (l % 16) ^ fswz(row):
             // sixteen rows read at once then hit different banks
             const uint16_t *src = a.phiK + ((size_t)si * a.S + (j - 1 - a.jb)) * C * 2 * D;
 #pragma unroll 8
             for (int i = 0; i < C * 2 * D / 512; i++) {
                 const int row = 2 * i + (lane >> 5);
                 __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)
-                                                     (src + row * 2 * D + ((lane >> 4) & 1) * D + (((lane & 15) ^ (row & 15)) << 3)),
+                                                     (src + row * 2 * D + ((lane >> 4) & 1) * D + (((lane & 15) ^ fswz(row)) << 3)),
                                                  (__attribute__((address_space(3))) void *)&PHs[buf][i * 512], 16, 0, 0);
             }
         } else {
@@ -2475,8 +2483,8 @@ __global__ __launch_bounds__(64) void scan_nocache_kernel(generic::PrefillArgs<b
                 uint16_t *dst = &PHs[buf][row * 2 * D];
 #pragma unroll
                 for (int ks = 0; ks < 4; ks++) {
-                    *reinterpret_cast<uint4 *>(dst + (((4 * ks + g4) ^ (row & 15)) << 3)) = __builtin_bit_cast(uint4, hi[ks]);
-                    *reinterpret_cast<uint4 *>(dst + D + (((4 * ks + g4) ^ (row & 15)) << 3)) = __builtin_bit_cast(uint4, lo[ks]);
+                    *reinterpret_cast<uint4 *>(dst + (((4 * ks + g4) ^ fswz(row)) << 3)) = __builtin_bit_cast(uint4, hi[ks]);
+                    *reinterpret_cast<uint4 *>(dst + D + (((4 * ks + g4) ^ fswz(row)) << 3)) = __builtin_bit_cast(uint4, lo[ks]);
                 }
             }
         }
@@ -2515,7 +2523,7 @@ __global__ __launch_bounds__(64) void scan_nocache_kernel(generic::PrefillArgs<b
         // order in which the transposing read delivers them, the same for both operands)
 #pragma unroll
         for (int kst = 0; kst < 2; kst++) {
-            const int t0 = 32 * kst + 4 * g4 + (r16 >> 2), t15 = t0 & 15;
+            const int t0 = 32 * kst + 4 * g4 + (r16 >> 2), t15 = fswz(t0);
             // B: values, column c = 16 ct + r16; lane i of a group points at pair t0's 4 columns 4 (i % 4) ..
             bf16x8 Bv = Bones;
             if (!s_role) {
@@ -2526,7 +2534,7 @@ __global__ __launch_bounds__(64) void scan_nocache_kernel(generic::PrefillArgs<b
 #pragma unroll
             for (int mt = 0; mt < NMT; mt++) {
                 // A: phi^T, row f = 16 mt + r of the tile from position 32 (mt / 2) + 8 (r / 4) + 4 (mt % 2) + r % 4, i.e.
-                // 16-byte piece 4 (mt / 2) + r / 4 of the row (stored at that piece ^ pair % 16), its half mt % 2
+                // 16-byte piece 4 (mt / 2) + r / 4 of the row (stored at that piece ^ fswz(pair)), its half mt % 2
                 const int off = (((4 * (mt >> 1) + (r16 & 3)) ^ t15) << 3) + 4 * (mt & 1);
 #pragma unroll
                 for (int part = 0; part < 2; part++) {
