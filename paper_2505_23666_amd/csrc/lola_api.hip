@@ -37,8 +37,8 @@ bool fast_decode_ok(const lola_config *c) {
 // to its key limit, 128 or 256 features), the shape-generic kernel keeping the update of the memories ...
 bool wide_step_out_ok(const lola_config *c) {
     return c->dtype == LOLA_BF16 && (c->head_dim == 128 || c->head_dim == 64) && (c->feat_dim == 128 || c->feat_dim == 256) &&
-           c->window >= 1 && !fast_decode_ok(c) && c->n_q_heads / c->n_kv_heads <= 4 &&
-           c->sparse_budget + c->window <= fast::STEP_OUT_NKMAX;
+           c->window >= 1 && !fast_decode_ok(c) && c->n_q_heads / c->n_kv_heads <= 8 &&
+           c->sparse_budget + c->window <= (c->n_q_heads / c->n_kv_heads <= 4 ? fast::STEP_OUT_NKMAX : fast::STEP_OUT_NKMAX / 2);
 }
 // ... and at which the streams in steady state are updated by the MFMA update kernel ahead of it (sparse budgets in
 // multiples of 64).
@@ -316,13 +316,11 @@ lola_status run_decode(const lola_config *c, const lola_state *st, const void *q
                 oa.st = a.st; oa.q = a.q; oa.Wq = a.Wq; oa.Wk = a.Wk; oa.out = (TO *)out; oa.score_kind = a.dm.score_kind;
                 oa.Hq = a.dm.Hq; oa.Hkv = a.dm.Hkv; oa.g = a.dm.g; oa.lam = a.dm.lam; oa.eta = a.dm.eta;
                 oa.phi_kind = a.dm.phi_kind; oa.hide = a.dm.hide; oa.scale = a.dm.scale;
-                if (c->head_dim == 128) {
-                    if (c->feat_dim == 256) hipLaunchKernelGGL((fast::step_out_wide_kernel<128, 256, TO>), grid, dim3(256), 0, stream, oa);
-                    else hipLaunchKernelGGL((fast::step_out_wide_kernel<128, 128, TO>), grid, dim3(256), 0, stream, oa);
-                } else {
-                    if (c->feat_dim == 256) hipLaunchKernelGGL((fast::step_out_wide_kernel<64, 256, TO>), grid, dim3(256), 0, stream, oa);
-                    else hipLaunchKernelGGL((fast::step_out_wide_kernel<64, 128, TO>), grid, dim3(256), 0, stream, oa);
-                }
+#define LOLA_OUT(DHV, DFV) do { if (oa.g <= 4) hipLaunchKernelGGL((fast::step_out_wide_kernel<DHV, DFV, TO, 4>), grid, dim3(256), 0, stream, oa); \
+                                else hipLaunchKernelGGL((fast::step_out_wide_kernel<DHV, DFV, TO, 8>), grid, dim3(256), 0, stream, oa); } while (0)
+                if (c->head_dim == 128) { if (c->feat_dim == 256) LOLA_OUT(128, 256); else LOLA_OUT(128, 128); }
+                else { if (c->feat_dim == 256) LOLA_OUT(64, 256); else LOLA_OUT(64, 128); }
+#undef LOLA_OUT
             };
             if (c->out_dtype == LOLA_F32) launch((float *)nullptr); else launch((bf16_t *)nullptr);
             LAUNCH_CHECK();

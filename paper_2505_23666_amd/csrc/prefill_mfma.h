@@ -1735,7 +1735,7 @@ __global__ __launch_bounds__(DH * 4) void scan_wide_kernel(generic::PrefillArgs<
 // ---------------------------------------------------------------------------------------------
 // Outputs of a generation step from the memories as the step's update left them (Sec. 3.1 eq. lola_output with the
 // shared normaliser: softmax part over the sparse cache and the window, linear part phi(q)^T H, phi(q)^T s), for any
-// window and sparse budget with at most NKMAX keys, 128 or 256 features and up to four query heads per kv head.  One
+// window and sparse budget with at most NKMAX keys, 128 or 256 features and up to eight query heads per kv head.  One
 // workgroup per stream, four wavefronts:
 //   1. logits Q K^T on MFMA (A = the group's queries, B = 16 keys straight from memory), tiles dealt round-robin;
 //   2. phi of query w by wavefront w (projection on MFMA with the query in every column);
@@ -1758,9 +1758,13 @@ struct StepOutArgs {
 
 constexpr int STEP_OUT_NKMAX = 3072;
 
-template <int DH, int DF, typename TO>
+// G = 4 or 8: query rows the kernel is built for (query heads per kv head <= G); the logits of all of them stay in
+// LDS, so the key limit is STEP_OUT_NKMAX * 4 / G.  Lane (column, group g4) of an MFMA result holds rows 4 g4 + i: the
+// queries sit in the lane groups g4 < G / 4.
+template <int DH, int DF, typename TO, int G>
 __global__ __launch_bounds__(256) void step_out_wide_kernel(StepOutArgs<TO> a) {
-    constexpr int M = DF / 2, KS = DH / 32, NZT = M / 16, KF = DF / 32, NCT = DH / 16, PR = DH / 8, G = 4, NKMAX = STEP_OUT_NKMAX;
+    constexpr int M = DF / 2, KS = DH / 32, NZT = M / 16, KF = DF / 32, NCT = DH / 16, PR = DH / 8, NKMAX = STEP_OUT_NKMAX * 4 / G;
+    static_assert(G == 4 || G == 8, "query rows");
     __shared__ __attribute__((aligned(16))) float lg[G][NKMAX];              // logits; then per 4 keys: 4 high parts, 4 low parts
     __shared__ __attribute__((aligned(16))) uint16_t VS[4][2][32 * DH];      // per wavefront: two blocks of 32 value rows
     __shared__ __attribute__((aligned(16))) uint16_t PQ[G][2][DF];           // phi(q), operand order, high / low parts
@@ -1794,19 +1798,20 @@ __global__ __launch_bounds__(256) void step_out_wide_kernel(StepOutArgs<TO> a) {
             f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < KS; ks++) acc = mfma16(AQ[ks], ld_bf16x8(kr + 32 * ks + 8 * g4), acc);
-            if (g4 == 0) {   // rows 0..3 of the tile: the queries
+            if (g4 < G / 4) {   // rows 4 g4 + i of the tile: the queries
                 const bool hidden = !valid || ((a.hide & 2) && key < spc);   // restricted query: the sparse cache is not read
 #pragma unroll
-                for (int i = 0; i < G; i++) lg[i][key] = hidden ? -INFINITY : acc[i] * a.scale;
+                for (int i = 0; i < 4; i++) lg[4 * g4 + i][key] = hidden ? -INFINITY : acc[i] * a.scale;
             }
         }
     }
-    // ---- 2. phi of query w (Sec. 2.3 eq. feature_map) and phi(q).s
-    if (w < g) {
-        const bf16_t *Wq = a.Wq + ((size_t)h * g + w) * M * DH;
+    // ---- 2. phi of queries w, w + 4, ... (Sec. 2.3 eq. feature_map) and phi(q).s
+#pragma unroll 1
+    for (int qi = w; qi < g; qi += 4) {
+        const bf16_t *Wq = a.Wq + ((size_t)h * g + qi) * M * DH;
         bf16x8 BQ[KS];
 #pragma unroll
-        for (int ks = 0; ks < KS; ks++) BQ[ks] = ld_bf16x8(qg + (size_t)w * DH + 32 * ks + 8 * g4);
+        for (int ks = 0; ks < KS; ks++) BQ[ks] = ld_bf16x8(qg + (size_t)qi * DH + 32 * ks + 8 * g4);
         f32x4 zt[NZT];
 #pragma unroll
         for (int mt = 0; mt < NZT; mt++) {
@@ -1828,17 +1833,17 @@ __global__ __launch_bounds__(256) void step_out_wide_kernel(StepOutArgs<TO> a) {
             dn = fmaf(pn[4 * mt + 2], sn4.z, dn); dn = fmaf(pn[4 * mt + 3], sn4.w, dn);
         }
         dn = grp_sum(dn);
-        if (lane == 0) denq_l[w] = dn;
+        if (lane == 0) denq_l[qi] = dn;
         if (r16 == 0) {   // every column holds the same query: column 0 stores
 #pragma unroll
             for (int ks = 0; ks < KF / 2; ks++) {
                 bf16x8 hi, lo;
                 split8(&pp[8 * ks], hi, lo);
-                *reinterpret_cast<uint4 *>(&PQ[w][0][(4 * ks + g4) << 3]) = __builtin_bit_cast(uint4, hi);
-                *reinterpret_cast<uint4 *>(&PQ[w][1][(4 * ks + g4) << 3]) = __builtin_bit_cast(uint4, lo);
+                *reinterpret_cast<uint4 *>(&PQ[qi][0][(4 * ks + g4) << 3]) = __builtin_bit_cast(uint4, hi);
+                *reinterpret_cast<uint4 *>(&PQ[qi][1][(4 * ks + g4) << 3]) = __builtin_bit_cast(uint4, lo);
                 split8(&pn[8 * ks], hi, lo);
-                *reinterpret_cast<uint4 *>(&PQ[w][0][(4 * (KF / 2 + ks) + g4) << 3]) = __builtin_bit_cast(uint4, hi);
-                *reinterpret_cast<uint4 *>(&PQ[w][1][(4 * (KF / 2 + ks) + g4) << 3]) = __builtin_bit_cast(uint4, lo);
+                *reinterpret_cast<uint4 *>(&PQ[qi][0][(4 * (KF / 2 + ks) + g4) << 3]) = __builtin_bit_cast(uint4, hi);
+                *reinterpret_cast<uint4 *>(&PQ[qi][1][(4 * (KF / 2 + ks) + g4) << 3]) = __builtin_bit_cast(uint4, lo);
             }
         }
     }
@@ -1878,27 +1883,29 @@ __global__ __launch_bounds__(256) void step_out_wide_kernel(StepOutArgs<TO> a) {
                 acc2 = mfma16(Ahi[ks], Bl, acc2);
                 acc3 = mfma16(Alo[ks], Bh, acc3);
             }
-            if (g4 == 0 && valid) {   // rows 0..3 of the tile: the queries; column: this lane's key
+            {   // rows 4 g4 + i of the tile: the queries; column: this lane's key
                 float add = 0.f;
 #pragma unroll
-                for (int i = 0; i < G; i++)
-                    if (i < g) add += generic::query_term(a.score_kind, lg[i][spc + kk], acc[i] + (acc2[i] + acc3[i]));
-                wsc[kk] += add;
+                for (int i = 0; i < 4; i++)
+                    if (valid && 4 * g4 + i < g) add += generic::query_term(a.score_kind, lg[4 * g4 + i][spc + kk], acc[i] + (acc2[i] + acc3[i]));
+                add = grp_sum(add);
+                if (g4 == 0 && valid) wsc[kk] += add;
             }
         }
         __syncthreads();   // the logits are overwritten next
     }
-    // ---- 3. weights of query w: m = max(0, max logit) (the linear terms carry weight e^(-m) <= 1)
-    if (w < g) {
+    // ---- 3. weights of queries w, w + 4, ...: m = max(0, max logit) (the linear terms carry weight e^(-m) <= 1)
+#pragma unroll 1
+    for (int qi = w; qi < g; qi += 4) {
         float mx = 0.f;
         for (int x = lane; x < KPAD / 4; x += 64) {
-            const float4 l4 = reinterpret_cast<const float4 *>(lg[w])[x];
+            const float4 l4 = reinterpret_cast<const float4 *>(lg[qi])[x];
             mx = fmaxf(mx, fmaxf(fmaxf(l4.x, l4.y), fmaxf(l4.z, l4.w)));
         }
         mx = wmax(mx);
         float ps = 0.f;
         for (int x = lane; x < KPAD / 4; x += 64) {
-            const float4 l4 = reinterpret_cast<const float4 *>(lg[w])[x];
+            const float4 l4 = reinterpret_cast<const float4 *>(lg[qi])[x];
             const float p[4] = {fexp2((l4.x - mx) * LOG2E), fexp2((l4.y - mx) * LOG2E), fexp2((l4.z - mx) * LOG2E), fexp2((l4.w - mx) * LOG2E)};
             uint32_t hi[2], lo[2];
 #pragma unroll
@@ -1911,10 +1918,10 @@ __global__ __launch_bounds__(256) void step_out_wide_kernel(StepOutArgs<TO> a) {
                 ps += (__uint_as_float((uint32_t)h0 << 16) + __uint_as_float((uint32_t)f32_to_bf16_bits(r0) << 16)) +
                       (__uint_as_float((uint32_t)h1 << 16) + __uint_as_float((uint32_t)f32_to_bf16_bits(r1) << 16));
             }
-            reinterpret_cast<uint4 *>(lg[w])[x] = make_uint4(hi[0], hi[1], lo[0], lo[1]);
+            reinterpret_cast<uint4 *>(lg[qi])[x] = make_uint4(hi[0], hi[1], lo[0], lo[1]);
         }
         ps = wsum(ps);
-        if (lane == 0) { m_l[w] = mx; psum_l[w] = ps; }
+        if (lane == 0) { m_l[qi] = mx; psum_l[qi] = ps; }
     }
     __syncthreads();
     // ---- 4. sum w v: key blocks of 32 dealt round-robin; A = weights (rows = queries), B = values through the
@@ -1961,11 +1968,11 @@ __global__ __launch_bounds__(256) void step_out_wide_kernel(StepOutArgs<TO> a) {
             }
             buf ^= 1;
         }
-        if (g4 == 0) {   // lane (column r16 of tile ct): rows 0..3 = the queries
+        if (g4 < G / 4) {   // lane (column r16 of tile ct): rows 4 g4 + i = the queries
 #pragma unroll
             for (int ct = 0; ct < NCT; ct++)
 #pragma unroll
-                for (int i = 0; i < G; i++) outp[w][i][16 * ct + r16] = acc[ct][i];
+                for (int i = 0; i < 4; i++) outp[w][4 * g4 + i][16 * ct + r16] = acc[ct][i];
         }
     }
     // ---- 5. phi(q)^T H: column tiles w, w + 4, ...; A = phi(q) (rows = queries), B = 16 rows of H^T
@@ -1991,9 +1998,9 @@ __global__ __launch_bounds__(256) void step_out_wide_kernel(StepOutArgs<TO> a) {
                 acc2 = mfma16(Ahi[ks], Bl, acc2);
                 acc3 = mfma16(Alo[ks], Bh, acc3);
             }
-            if (g4 == 0) {
+            if (g4 < G / 4) {
 #pragma unroll
-                for (int i = 0; i < G; i++) lin_l[i][16 * ct + r16] = acc[i] + (acc2[i] + acc3[i]);
+                for (int i = 0; i < 4; i++) lin_l[4 * g4 + i][16 * ct + r16] = acc[i] + (acc2[i] + acc3[i]);
             }
         }
     }

@@ -708,6 +708,24 @@ def test_generation_steps_replayed_from_a_hip_graph():
         say("graph replays match eager steps, fold_defer", defer)
 
 
+@pytest.mark.parametrize("g,d,D,eta,lam,sk", [(8, 128, 128, 64, 128, 0), (6, 64, 256, 128, 64, 0), (8, 128, 128, 64, 64, 2), (5, 64, 128, 64, 0, 0)])
+def test_generation_step_with_more_than_four_query_heads_per_kv_head(g, d, D, eta, lam, sk):
+    """Groups of 5 to 8 query heads per kv head (the fused generation step takes at most 4): update and output kernels with
+    run-time window and budget, the output kernel in its 8-row form.  Cold start through window filling, cache filling and
+    steady state, a prefill call in between, more steps."""
+    sh = wl.Shape("g8", "bf16", 2, 2 * g, 2, d, D, T=0, eta=eta, lam=lam, C=64, seed=0)
+    n1, n_pre, n2 = eta + lam + 21, 64 * 2 + 11, 9
+    q, k, v, Wq, Wk = rand_case(1500 + g + d, 2, 2 * g, 2, d, D, n1 + n_pre + n2, "bf16")
+    kw = dict(score_kind=sk)
+    layer, o = P.make_layer(sh, **kw), P.make_oracle(sh, **kw)
+    assert layer.lola_path[1] == ("mfma" if lam else "mixed")
+    rep = P.decode_parity(sh, layer, o, *steps(q, k, v, 0, n1), Wq, Wk)
+    layer, o, rep2 = P.prefill_parity(sh, q[:, :, n1:n1 + n_pre], k[:, :, n1:n1 + n_pre], v[:, :, n1:n1 + n_pre], Wq, Wk,
+                                      layer=layer, oracle=o, layer_kw=kw)
+    rep3 = P.decode_parity(sh, layer, o, *steps(q, k, v, n1 + n_pre, n2), Wq, Wk)
+    say("generation step, group size", g, d, D, eta, lam, sk, rep, rep2, rep3)
+
+
 def test_three_launch_generation_step_replayed_from_a_hip_graph():
     """The generation step at a run-time-parameter shape (update kernel, shape-generic kernel for streams still filling,
     output kernel) captured into a HIP graph from an empty state: the replays take the streams through window filling,
