@@ -114,6 +114,19 @@ def test_arguments_rejected_before_launch(L):
     assert lb.lola_kernel_path(cfg(feat_dim=256, window=256, sparse_budget=200), 0) == "mixed"   # budget not a multiple of 64
     assert lb.lola_kernel_path(cfg(feat_dim=256, window=256, sparse_budget=256, chunk=128), 0) == "generic"
     assert lb.lola_kernel_path(cfg(sparse_budget=0), 0) == "mfma"
+    # which kernel family serves what (prefill, generation step)
+    path = lambda **kw: (lb.lola_kernel_path(cfg(**kw), 0), lb.lola_kernel_path(cfg(**kw), 1))
+    assert path() == ("mfma", "mfma")                                            # the 8B shape: compile-time kernels
+    assert path(sparse_budget=256) == ("mfma", "mfma")                           # fused step only for budgets 64 / 128: run-time step kernels
+    assert path(sparse_budget=0) == ("mfma", "mixed")                            # no cache: row-split evolution; step: generic update, MFMA outputs
+    assert path(sparse_budget=0, window=192) == ("mfma", "mixed")
+    assert path(window=128, sparse_budget=1024, feat_dim=256) == ("mfma", "mfma")
+    assert path(window=128, sparse_budget=2048, feat_dim=256) == ("generic", "mfma")   # prefill kernels stop at budget 1024
+    assert path(window=100, sparse_budget=128) == ("mixed", "mfma")              # window not a multiple of 64: generic evolution
+    assert path(n_q_heads=16) == ("mfma", "mfma")                                # 8 query heads per kv head (cfg has 2 kv heads)
+    assert path(n_q_heads=32) == ("mfma", "generic")                             # 16: the step kernels take at most 8
+    assert path(dtype=lb.LOLA_F32) == ("generic", "generic")
+    assert path(head_dim=256, feat_dim=256) == ("generic", "generic")
     assert f(C.byref(cfg(query_hide=4)), C.byref(st), vp(fake), vp(fake), vp(fake), vp(fake), vp(fake), vp(fake), None) == -2
 
 
