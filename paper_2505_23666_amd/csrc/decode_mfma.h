@@ -23,6 +23,7 @@
 //   f(ks, e, grp) = 32*ks + 16*(e/4) + 4*grp + e%4
 // so that the C layout of the phi GEMM is directly the B layout of the recall GEMM.
 #pragma once
+#include <type_traits>
 #include "lola_common.h"
 
 namespace lola {
@@ -339,7 +340,7 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
         const int j = 16 * w + (64 * it + lane) / PR, pc = lane % PR;
         *reinterpret_cast<uint4 *>(&PB[j * DH + ((pc ^ (j & (PR - 1))) << 3)]) = wk_ld[it];
     }
-    __syncthreads();
+    lds_barrier();
     // W_k as MFMA A operand (row = projection, k = input index): [projection tile][k-step]
     bf16x8 AW[4][KS];
 #pragma unroll
@@ -347,7 +348,7 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
 #pragma unroll
         for (int ks = 0; ks < KS; ks++)
             AW[mt][ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(&PB[(16 * mt + r16) * DH + (((4 * ks + g4) ^ (r16 & (PR - 1))) << 3)]));
-    __syncthreads();   // every wavefront holds its operands: the staging area may become the feature tile
+    lds_barrier();   // every wavefront holds its operands: the staging area may become the feature tile
     // ---- query rows as MFMA A operand (rows >= G are zero)
     bf16x8 AQ[KS];
 #pragma unroll
@@ -555,15 +556,17 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
         d[0] = bf_lo(p_ld.x); d[1] = bf_hi(p_ld.x); d[2] = bf_lo(p_ld.y); d[3] = bf_hi(p_ld.y);
         d[4] = bf_lo(p_ld.z); d[5] = bf_hi(p_ld.z); d[6] = bf_lo(p_ld.w); d[7] = bf_hi(p_ld.w);
     }
-    // value rows for the read-out are requested as soon as registers allow (after the recall GEMM in steady state);
-    // they go to LDS once the feature tile is free
-    constexpr int NVIT = KPAD * PR / 256;
-    static_assert(KPAD * PR % 256 == 0, "value staging is an exact number of passes");
+    // Value rows for the read-out.  In steady state the cached rows are already in registers (the recall epilogue's
+    // operands, kept until the feature tile is free), so only the rows behind them - the leaving pair, the window, the
+    // zero rows that pad the last k-step - are fetched; while the cache fills, every row is.
+    constexpr int NVIT = KPAD * PR / 256, NWIT = (KPAD - LAM) * PR / 256;
+    static_assert(KPAD * PR % 256 == 0 && (KPAD - LAM) * PR % 256 == 0, "value staging is an exact number of passes");
     uint4 vst[NVIT];
-    auto load_values = [&]() {
+    auto load_values = [&](auto first_key) {
+        constexpr int K0 = decltype(first_key)::value;
 #pragma unroll
-        for (int it = 0; it < NVIT; it++) {
-            const int o = tid + 256 * it, key = o / PR, c8 = o % PR;
+        for (int it = 0; it < (KPAD - K0) * PR / 256; it++) {
+            const int o = tid + 256 * it, key = K0 + o / PR, c8 = o % PR;
             vst[it] = make_uint4(0, 0, 0, 0);
             if (key < NKEY && key != KP) {
                 const bf16_t *src;
@@ -594,7 +597,7 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
             Alo[ct][ks][4 * hf + 2] = (__bf16)(v.z - (float)h2); Alo[ct][ks][4 * hf + 3] = (__bf16)(v.w - (float)h3); }
         LOLA_HREP(LOLA_HSPLIT)
 #undef LOLA_HSPLIT
-        __syncthreads();   // feature vectors and denominators of all eligible pairs are in LDS
+        lds_barrier();   // feature vectors and denominators of all eligible pairs are in LDS
         // Key tiles 0..NKT-1 are the cache slots; tile NKT is the extra tile (column 0: the leaving key, columns 1..G:
         // the queries, whose "recall" numerators are the linear read-out).  C layout: lane (column r16, group g4)
         // holds rows c = 32w + 16ct + 4 g4 + i.
@@ -659,8 +662,8 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
                 if (lane == 0) part[w][KP] = e2;
             }
         }
-        __syncthreads();
-        load_values();
+        lds_barrier();
+        load_values(std::integral_constant<int, LAM>{});
         // ---- stage 3: the pair that leaves the cache: smallest error, ties -> larger token index
         // (every wavefront does the same search, which saves a barrier)
         {
@@ -684,9 +687,28 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
             const uint16_t *bh = drop < LAM ? PB + drop * D + ((chunk ^ (drop & 15)) << 3) + el : PX + (chunk << 3) + el;
             const uint16_t *bl = drop < LAM ? bh + LAM * D : bh + XR * D;
             phif[f] = bf_lo(*bh) + bf_lo(*bl);
-            if (f < DH) vf[f] = drop < LAM ? ldf(sp_v, (size_t)drop * DH + f) : pvf[f];
+            if (f < DH && drop == LAM) vf[f] = pvf[f];
         }
-        __syncthreads();
+        if (drop < LAM) {
+            // the folded slot's value row is among the recall epilogue's operands: the lanes of column drop % 16 hold it
+            // at this wavefront's value columns (no second trip to memory behind the selection)
+            uint2 sel[NCT];
+#pragma unroll
+            for (int ct = 0; ct < NCT; ct++) {
+                sel[ct] = vrec[0][ct];
+#pragma unroll
+                for (int kt = 1; kt < NKT; kt++)
+                    if ((drop >> 4) == kt) sel[ct] = vrec[kt][ct];
+            }
+            if (r16 == (drop & 15)) {
+#pragma unroll
+                for (int ct = 0; ct < NCT; ct++) {
+                    float *d = vf + CW * w + 16 * ct + 4 * g4;
+                    d[0] = bf_lo(sel[ct].x); d[1] = bf_hi(sel[ct].x); d[2] = bf_lo(sel[ct].y); d[3] = bf_hi(sel[ct].y);
+                }
+            }
+        }
+        lds_barrier();
         // the leaving pair takes the freed slot (in-place compaction)
         if (drop < LAM) {
             if (tid < PR) reinterpret_cast<uint4 *>(sp_k + (size_t)drop * DH)[tid] = reinterpret_cast<const uint4 *>(pkb)[tid];
@@ -731,8 +753,8 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
             if (lane == 0) dotqf[r] = acc;
         }
     } else {
-        __syncthreads();   // logits of all wavefronts and the leaving pair's value row are in LDS (the steady path has passed barriers of its own)
-        load_values();
+        lds_barrier();   // logits of all wavefronts and the leaving pair's value row are in LDS (the steady path has passed barriers of its own)
+        load_values(std::integral_constant<int, 0>{});
     }
 #undef LOLA_HDECL
 #undef LOLA_HLOAD
@@ -746,14 +768,31 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     }
 
     // ---- stage 4: value rows into LDS (the feature tile is no longer needed): [key][c], key order = logit order; rows
-    // past the last key are zero.  The cached value row of the dropped slot may be mid-overwrite: its weight is 0.
+    // past the last key are zero.  The dropped slot's row is the old one, or mid-overwrite while the cache fills: its weight is 0.
     // 8-byte piece p of row `key` sits at piece p ^ vswz(key) (a multiple of 4 taken from the row bits that differ
     // between the eight rows two lane groups read at once): the transposing reads below then touch every bank once
     auto vswz = [](int key) { return DH == 128 ? 4 * (key & 7) : 4 * ((key >> 1) & 3); };
+    if (steady) {
+        // cached rows from the registers of the recall epilogue: lane (r16, g4) holds, per key tile and row tile, the
+        // 8-byte piece (CW w + 16 ct) / 4 + g4 of row 16 kt + r16
 #pragma unroll
-    for (int it = 0; it < NVIT; it++) {
-        const int o = tid + 256 * it, key = o / PR, c8 = o % PR;
-        *reinterpret_cast<uint4 *>(Vl + key * VLS + 4 * ((2 * c8) ^ vswz(key))) = vst[it];
+        for (int kt = 0; kt < NKT; kt++)
+#pragma unroll
+            for (int ct = 0; ct < NCT; ct++) {
+                const int key = 16 * kt + r16, pc = (CW / 4) * w + 4 * ct + g4;
+                *reinterpret_cast<uint2 *>(Vl + key * VLS + 4 * (pc ^ vswz(key))) = vrec[kt][ct];
+            }
+#pragma unroll
+        for (int it = 0; it < NWIT; it++) {
+            const int o = tid + 256 * it, key = LAM + o / PR, c8 = o % PR;
+            *reinterpret_cast<uint4 *>(Vl + key * VLS + 4 * ((2 * c8) ^ vswz(key))) = vst[it];
+        }
+    } else {
+#pragma unroll
+        for (int it = 0; it < NVIT; it++) {
+            const int o = tid + 256 * it, key = o / PR, c8 = o % PR;
+            *reinterpret_cast<uint4 *>(Vl + key * VLS + 4 * ((2 * c8) ^ vswz(key))) = vst[it];
+        }
     }
     // the new pair, which takes the ring slot of the pair that left, is requested here and stored at the very end
     // (a store that follows its own load waits for every load the wavefront has in flight: by then there is none)
@@ -789,7 +828,7 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
         sum = wsum(sum);
         if (lane == 0) { psum_s[r] = sum; elin_s[r] = fexp2(-mx * LOG2E); }
     }
-    __syncthreads();
+    lds_barrier();
 
     // ---- stage 5: out[q][c] = sum_key p[q][key] v[key][c] on MFMA: A = weights (rows = queries), B = staged values
     // (column c, k = key); each wavefront owns CW output columns

@@ -545,7 +545,9 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
                 // beforehand: at the compile-time shapes of every key of the pass, at the run-time shapes (per piece,
                 // behind the generic leg) of the pairs that leave the window in each chunk and of the cache slots as
                 // they stand.
-                if (!wide) {
+                // (a compile-time shape whose cache does not stay in LDS takes its features the run-time way)
+                const bool big = !wide && c->sparse_budget > 128;
+                if (!wide && !big) {
                     const dim3 gp((unsigned)(jend - j0), (unsigned)ns);
                     if (c->head_dim == 128) hipLaunchKernelGGL(fast::phi_k_kernel<128>, gp, dim3(256), 0, stream, a);
                     else hipLaunchKernelGGL(fast::phi_k_kernel<64>, gp, dim3(256), 0, stream, a);
@@ -632,6 +634,12 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
                         else { if (c->feat_dim == 256) LOLA_WSCAN(64, 256); else LOLA_WSCAN(64, 128); }
 #undef LOLA_WSCAN
                     } else {
+                    if (big) {
+                        const dim3 gp((unsigned)(a.j1 - a.j0) + (unsigned)(c->sparse_budget / 64), (unsigned)ns);
+                        if (c->head_dim == 128) hipLaunchKernelGGL((fast::phi_wide_kernel<128, 128>), gp, dim3(256), 0, stream, a);
+                        else hipLaunchKernelGGL((fast::phi_wide_kernel<64, 128>), gp, dim3(256), 0, stream, a);
+                        LAUNCH_CHECK();
+                    }
                     if (side && ip > 0 && hipEventRecord(side->fork[ip - 1], stream) != hipSuccess) return LOLA_ERR_HIP;
 #define LOLA_SCAN(LAMV) do { if (c->head_dim == 128) hipLaunchKernelGGL((fast::scan_fast_kernel<LAMV, 128, SCAN_RT128>), gs, dim3(512 / SCAN_RT128), 0, stream, a); \
                              else hipLaunchKernelGGL((fast::scan_fast_kernel<LAMV, 64, 1>), gs, dim3(256), 0, stream, a); } while (0)

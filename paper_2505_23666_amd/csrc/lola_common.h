@@ -43,6 +43,28 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float v) {
 }
 __device__ __forceinline__ void stf(bf16_t *p, size_t i, float v) { p[i].x = f32_to_bf16_bits(v); }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every global load and store the
+// wavefront has in flight (and so does a workgroup fence restricted to LDS once the kernel holds direct global -> LDS
+// loads), which ends all prefetching at each barrier; this form waits for the wavefront's LDS operations alone and
+// leaves its global requests in flight.  The "memory" clobber keeps the compiler from moving memory accesses across
+// it.  It may stand wherever the wavefronts of a workgroup exchange data through LDS alone: data that one wavefront
+// writes to global memory and another reads back in the same launch still needs __syncthreads().  Direct global -> LDS
+// loads are waited for by the wavefront that issued them, with an explicit s_waitcnt, before it enters the barrier.
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// Direct global -> LDS load of 16 bytes per lane (1 KB per wavefront: lane l fills bytes 16 l .. of the block at
+// lds_dst, which must be the same for all lanes), issued as inline assembly.  The compiler orders every LDS read that it
+// cannot prove disjoint behind the direct loads it knows of, which serialises a batch's reads with the requests of
+// the next batch; loads issued here are invisible to that bookkeeping and are waited for by hand (s_waitcnt vmcnt
+// counts them like any other load, in order, so the compiler's own waits only ever become longer, never too short).
+// A kernel that uses this form uses it for all its direct loads: M0 is written here without the compiler knowing.
+__device__ __forceinline__ void lds_dma16(const void *gsrc, void *lds_dst) {
+    const uint32_t l = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)lds_dst);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" :: "s"(l), "v"(gsrc) : "memory");
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
     for (int o = WAVE / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);

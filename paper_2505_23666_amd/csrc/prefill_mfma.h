@@ -496,6 +496,11 @@ __global__ __launch_bounds__(256, 2) void attend_wide_kernel(generic::PrefillArg
 // of the cached keys stay in LDS from chunk to chunk as well (a cache slot keeps its row; an entrant's
 // row is copied into the slot it takes); the features of the 64 pairs that leave the window come from
 // the chunk-parallel feature kernel below and are requested one chunk ahead, like their values.
+// With lambda = 256 the candidates' features do not fit LDS: they stream through two LDS buffers in
+// batches of five tiles, each batch requested (direct global -> LDS loads) while the one before it is worked
+// on; the rows come from the feature kernel of the run-time shapes (phi_wide_kernel: the pairs that leave
+// the window in each chunk and the cache slots as the launch finds them), the compaction keeping the
+// slots' rows current in that global scratch.
 // Per chunk:
 //   1. snapshot of H^T (operand order, high/low parts), s and the cache's row list for the output kernel;
 //   2. recall GEMM P^T = H^T Phi^T for all lambda + 64 candidates, with s riding along as one more row
@@ -572,11 +577,18 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
     constexpr int M = 64, D = 128, C = 64, ETA = 64, NW = DH / (16 * RT), NTH = 64 * NW, KS = DH / 32, PR = DH / 8;
     static_assert(RT == 1 || RT == 2, "row tiles per wavefront");
     static_assert(DH == 64 || DH == 128, "head_dim");
-    constexpr int P = LAM + ETA, NE = LAM + C, NTILE = NE / 16, TB = LAM > 128 ? 10 : 12, RB = TB * 16;
+    constexpr int P = LAM + ETA, NE = LAM + C, NTILE = NE / 16, TB = LAM > 128 ? 5 : 12, RB = TB * 16;
     constexpr int NK = NE / 64, TC = LAM / 16;
     constexpr bool PERSIST = NTILE <= TB;   // one batch: the candidates' features all fit in LDS and the cache's part stays there
+    // Otherwise the batches alternate between two buffers, the next batch's rows being requested while this one is
+    // worked on.  The buffers are two arrays, selected at compile time in a batch loop unrolled by two: a wavefront's
+    // reads of one buffer then do not wait for its direct loads into the other (the compiler orders LDS reads behind
+    // pending direct loads per array).
+    constexpr int NBUFS = PERSIST ? 1 : 2;
     static_assert(NE % 64 == 0, "candidates are selected 64 per register");
+    static_assert(PERSIST || NTILE % (2 * TB) == 0, "an even number of whole batches");
     __shared__ __attribute__((aligned(16))) uint16_t PB[2 * RB * D];    // phi of (a batch of) candidates: high parts, low parts
+    __shared__ __attribute__((aligned(16))) uint16_t PB1[PERSIST ? 8 : 2 * RB * D];   // the second batch buffer
     __shared__ __attribute__((aligned(16))) uint16_t PT[2 * D * C];     // phi^T of the folded pairs [part][f][e']
     __shared__ __attribute__((aligned(16))) uint16_t VT[DH * C];        // v^T of the folded pairs [c][e']
     __shared__ __attribute__((aligned(16))) float s_l[D];
@@ -623,8 +635,9 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
     bool idx_valid = false;     // rows [0, LAM) of cidx hold the cache slots' token indices
     if (tid0 == 0) thr_s = 0;   // published by the barrier that follows the loading of the state
     bool phi_valid = false;     // PERSIST: rows [0, LAM) of PB hold phi of the cache slots, and PHn / vvn the rows requested ahead
-    bool rows_valid = false;    // !PERSIST: rows [0, LAM) of the global feature scratch hold phi of the cache slots (the previous
-                                // chunk of this launch left them there), and the feature kernel's rows of that chunk are the leaving pairs'
+    // !PERSIST: rows [0, LAM) of the global feature scratch hold phi of the cache slots (written by the feature kernel
+    // that runs before this launch, kept current by the compaction), and that kernel's rows of chunk j are phi of the
+    // pairs that leave the window in chunk j
     constexpr int PHN = C * 32 / NTH;   // 16-byte pieces of a chunk's features per thread
     uint4 PHn[PHN];             // this thread's pieces of phi of the pairs that leave the window in the next chunk
     uint2 vvn[4][RT];           // their values at this wavefront's columns
@@ -668,10 +681,10 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
         };
         const bool have_phi = PERSIST && phi_valid;   // the cache's rows are in LDS and the leaving pairs' rows (from the
                                                       // parallel feature kernel) were requested one chunk ahead
-        // !PERSIST: where candidate e's features are once rows_valid holds (operand order, high part then low part)
-        const uint16_t *phk_prev = a.phiK + ((size_t)si * a.S + (size_t)(j - 1 - a.jb)) * C * 2 * D;
+        // !PERSIST: where candidate e's features are (operand order, high part then low part)
+        const uint16_t *phk_cur = a.phiK + ((size_t)si * a.S + (size_t)(j - a.jb)) * C * 2 * D;
         auto phirow = [&](int e) -> const uint16_t * {
-            return (rows_valid && e >= LAM) ? phk_prev + (size_t)(e - LAM) * 2 * D : phiE + (size_t)e * 2 * D;
+            return e >= LAM ? phk_cur + (size_t)(e - LAM) * 2 * D : phiE + (size_t)e * 2 * D;
         };
 
         // ---- 1. operands of the recall GEMM from the fp32 registers (H^T, and s as one more row held by the lanes
@@ -708,10 +721,47 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
         // ---- 2. phi of the candidates and their recall error, in batches of TB tiles.  Global loads of a batch are
         // requested up front: the candidates' values for the recall epilogue, then the rows wanted by the next chunk; the
         // snapshot stores follow, so that they drain while the recall GEMM runs out of LDS and registers.
+        // A cache too large to stay in LDS: a batch's rows come in from the global scratch (cache
+        // slots) and from the feature kernel's output (pairs leaving the window) by direct global -> LDS loads: no
+        // registers, all of a wavefront's loads in flight at once.  One load instruction fills 1 KB of LDS, lane l its
+        // bytes 16 l ..: four rows of one part; a row's 16-byte pieces are XOR-swizzled, so lane l fetches the piece that
+        // belongs in its position.  The candidates' values at this wavefront's columns travel with them, in registers.
+        constexpr int BPP = RB / 4;                          // 1 KB blocks per part (high, low)
+        static_assert(PERSIST || (2 * BPP) % NW == 0, "the wavefronts share a batch's blocks evenly");
+        uint2 vvq[PERSIST ? 1 : TB][RT];
+        auto request_batch = [&](int tb0, uint16_t *dstbuf) {
+#pragma unroll
+            for (int it = 0; it < 2 * BPP / NW; it++) {
+                const int blk = w + NW * it, pt = blk / BPP, rl0 = 4 * (blk % BPP);
+                const int rl = rl0 + (lane >> 4), slot = lane & 15, e = 16 * tb0 + rl;
+                const uint16_t *src = phirow(e) + pt * D + ((slot ^ (rl & 15)) << 3);
+                lds_dma16(src, &dstbuf[pt * RB * D + rl0 * D]);
+            }
+#pragma unroll
+            for (int u = 0; u < (PERSIST ? 1 : TB); u++)
+#pragma unroll
+                for (int rt = 0; rt < RT; rt++)
+                    vvq[u][rt] = *reinterpret_cast<const uint2 *>(vrow(16 * (tb0 + u) + r16) + 16 * (RT * w + rt) + 4 * g4);
+        };
+        if (!PERSIST) request_batch(0, PB);
 #pragma unroll 1
-        for (int t0 = 0; t0 < NTILE; t0 += TB) {
+        for (int tp = 0; tp < NTILE; tp += NBUFS * TB) {
+#pragma unroll
+        for (int hb = 0; hb < NBUFS; hb++) {
+            const int t0 = tp + hb * TB;
             const int t1 = min(NTILE, t0 + TB);
+            uint16_t *PBb = hb ? PB1 : PB, *PBn = hb ? PB : PB1;   // (compile-time choices: the inner loop is unrolled)
             uint2 vv[TB][RT];
+            if (!PERSIST) {
+                // This batch's rows and values (requested one batch ago) have landed; then the next batch is requested
+                // into the other buffer, whose readers passed the barrier that ended the batch before this one.
+                __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+#pragma unroll
+                for (int u = 0; u < TB; u++)
+#pragma unroll
+                    for (int rt = 0; rt < RT; rt++) vv[u][rt] = vvq[PERSIST ? 0 : u][rt];
+                if (t0 + TB < NTILE) request_batch(t0 + TB, PBn);
+            } else {
 #pragma unroll
             for (int u = 0; u < TB; u++) {
 #pragma unroll
@@ -723,31 +773,14 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
                     }
                 }
             }
+            }
             if (have_phi) {   // the rows requested one chunk ago take their place behind the cache's rows
 #pragma unroll
                 for (int it = 0; it < PHN; it++) {
                     const int o = tid + NTH * it, row = o >> 5, pt = (o >> 4) & 1, pc = o & 15;
-                    *reinterpret_cast<uint4 *>(&PB[pt * RB * D + (LAM + row) * D + ((pc ^ (row & 15)) << 3)]) = PHn[it];
+                    *reinterpret_cast<uint4 *>(&PBb[pt * RB * D + (LAM + row) * D + ((pc ^ (row & 15)) << 3)]) = PHn[it];
                 }
-            } else if (!PERSIST && rows_valid) {
-                // a cache too large to stay in LDS: the batch's rows come in from the global scratch (cache slots) and
-                // from the feature kernel's output (pairs leaving the window) by direct global -> LDS loads: no registers,
-                // all of a wavefront's loads in flight at once.  One load instruction fills 1 KB of LDS, lane l its bytes
-                // 16 l ..: four rows of one part; a row's 16-byte pieces are XOR-swizzled, so lane l fetches the piece
-                // that belongs in its position.
-                constexpr int BPP = RB / 4;   // 1 KB blocks per part (high, low)
-#pragma unroll 1
-                for (int blk = w; blk < 2 * BPP; blk += NW) {
-                    const int pt = blk / BPP, rl0 = 4 * (blk % BPP);
-                    const int rl = rl0 + (lane >> 4), slot = lane & 15, e = 16 * t0 + rl;
-                    if (e < 16 * t1) {
-                        const uint16_t *src = phirow(e) + pt * D + ((slot ^ (rl & 15)) << 3);
-                        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                                         (__attribute__((address_space(3))) void *)&PB[pt * RB * D + rl0 * D], 16, 0, 0);
-                    }
-                }
-                __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wavefront's rows have landed (the barrier below publishes them)
-            } else {
+            } else if (PERSIST) {
                 // phi of the batch's tiles (first regular chunk of a launch): wavefront w takes tiles t0 + w, t0 + w + NW, ...
                 // (W_k is read where it is used: this path runs once per launch and must not raise the kernel's register need)
 #pragma unroll 1
@@ -774,12 +807,8 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
 #pragma unroll
                     for (int ks = 0; ks < 4; ks++) {
                         const int addr = rl * D + (((4 * ks + g4) ^ r16) << 3);
-                        *reinterpret_cast<uint4 *>(&PB[addr]) = __builtin_bit_cast(uint4, hi[ks]);
-                        *reinterpret_cast<uint4 *>(&PB[RB * D + addr]) = __builtin_bit_cast(uint4, lo[ks]);
-                        if (!PERSIST) {   // several batches: the fold finds earlier batches' features in global scratch
-                            *reinterpret_cast<uint4 *>(phiE + (size_t)e * 2 * D + ((4 * ks + g4) << 3)) = __builtin_bit_cast(uint4, hi[ks]);
-                            *reinterpret_cast<uint4 *>(phiE + (size_t)e * 2 * D + D + ((4 * ks + g4) << 3)) = __builtin_bit_cast(uint4, lo[ks]);
-                        }
+                        *reinterpret_cast<uint4 *>(&PBb[addr]) = __builtin_bit_cast(uint4, hi[ks]);
+                        *reinterpret_cast<uint4 *>(&PBb[RB * D + addr]) = __builtin_bit_cast(uint4, lo[ks]);
                     }
                 }
             }
@@ -788,7 +817,7 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
                 if (tid < D / 4) reinterpret_cast<float4 *>(a.snapS + sj * D)[tid] = reinterpret_cast<const float4 *>(s_l)[tid];
                 if (tid < LAM) a.snapG[sj * LAM + tid] = sprow_ld;
             }
-            __syncthreads();
+            lds_barrier();
             // recall GEMM for the batch: A = this wavefront's 16 rows of H^T, B = phi from LDS; lane (candidate r16,
             // group g4) holds rows c = 16w + 4 g4 + i and pairs them with the candidate's values at those columns.
             // Tile t's denominators come from wavefront t % 8 (A = s in row 0, zeros below).  Operands of the next
@@ -798,8 +827,8 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
 #pragma unroll
             for (int ks = 0; ks < 4; ks++) {
                 const int addr = r16 * D + (((4 * ks + g4) ^ r16) << 3);
-                Bc[ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(&PB[addr]));
-                Bc[4 + ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(&PB[RB * D + addr]));
+                Bc[ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(&PBb[addr]));
+                Bc[4 + ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(&PBb[RB * D + addr]));
             }
             if constexpr (PIPE) {
                 // One wavefront per SIMD: the error terms of tile u - 1 (vector instructions) are issued between the
@@ -820,8 +849,8 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
 #pragma unroll
                             for (int ks = 0; ks < 4; ks++) {
                                 const int addr = (16 * (u + 1) + r16) * D + (((4 * ks + g4) ^ r16) << 3);
-                                Bn[ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(&PB[addr]));
-                                Bn[4 + ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(&PB[RB * D + addr]));
+                                Bn[ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(&PBb[addr]));
+                                Bn[4 + ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(&PBb[RB * D + addr]));
                             }
                         }
 #pragma unroll
@@ -873,8 +902,8 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
 #pragma unroll
                         for (int ks = 0; ks < 4; ks++) {
                             const int addr = (16 * (u + 1) + r16) * D + (((4 * ks + g4) ^ r16) << 3);
-                            Bn[ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(&PB[addr]));
-                            Bn[4 + ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(&PB[RB * D + addr]));
+                            Bn[ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(&PBb[addr]));
+                            Bn[4 + ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(&PBb[RB * D + addr]));
                         }
                     }
                     f32x4 acc[RT];   // the three products of a k-step go into one accumulator: the large one first
@@ -942,7 +971,8 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
                         }
                 }
             }
-            __syncthreads();
+            lds_barrier();
+        }
         }
 
         // ---- 3. selection: the 64 candidates with the smallest squared error are folded (order: score descending,
@@ -956,7 +986,7 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
             const float sq = fmaxf(fmaf(rd * rd, sa, fmaf(-2.0f * rd, sb, sc)), 0.f);
             skey[e] = __float_as_uint(sq) & 0x7FFFFFFFu;
         }
-        __syncthreads();
+        lds_barrier();
         // One wavefront holds all scores (NK per lane) and finds the 64th smallest by building it bit by bit: a trial
         // value is kept when fewer than 64 scores lie below it (votes counted on the scalar unit).  Scores equal to
         // the threshold are folded too if that makes exactly 64; otherwise (exact ties across the cut) the same search
@@ -1058,7 +1088,7 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
             }
             if (lane == 0) ne_s = nen;
         }
-        __syncthreads();
+        lds_barrier();
         // exactly 64 are folded, so entrants and leavers pair up
         const int ne = ne_s;
 
@@ -1119,7 +1149,7 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
                 }
             }
         }
-        __syncthreads();
+        lds_barrier();
         {
             // compaction, first half: the entrants' rows are requested now and stored after the fold (all reads of
             // the leavers' rows were completed before the barrier above)
@@ -1215,7 +1245,6 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
         }
         idx_valid = true;
         phi_valid = PERSIST;
-        rows_valid = !PERSIST;
         __syncthreads();   // (workgroup scope is enough: only this workgroup reads the stream's memories before the kernel ends)
         if (a.sel_trace) {
             int32_t *tr = a.sel_trace + ((size_t)si * a.n_chunks + j) * LAM;
