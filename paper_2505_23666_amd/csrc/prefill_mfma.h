@@ -1158,6 +1158,7 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
 #pragma unroll
             for (int it = 0; it < CIT; it++) {
                 const int o = tid + NTH * it;
+                cp[it] = make_uint4(0, 0, 0, 0);   // (left unset on some paths, the array is kept in memory instead of registers)
                 if (o < ne * 2 * PR) {
                     const int x = o / (2 * PR), rem = o % (2 * PR);
                     const int e = ecand[x];
@@ -1438,15 +1439,13 @@ __global__ __launch_bounds__(DH * 4) void scan_wide_kernel(generic::PrefillArgs<
             for (int it = 0; it < RB * FR / 512 / NW; it++) {
                 const int i = w + NW * it, g = 512 * i + 8 * lane, row = g / FR, pt = (g % FR) / DF, slot = (g % DF) >> 3;
                 const uint16_t *src = phirow(e0 + row) + pt * DF + ((slot ^ (row & 15)) << 3);
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                                 (__attribute__((address_space(3))) void *)(PBb + 512 * i), 16, 0, 0);
+                lds_dma16(src, PBb + 512 * i);
             }
 #pragma unroll
             for (int it = 0; it < VPB; it++) {
                 const int i = w + NW * it, g = 512 * i + 8 * lane, row = g / DH, slot = (g % DH) >> 3;
                 const bf16_t *src = vrow(e0 + row) + ((slot ^ (row & (PR - 1))) << 3);
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                                 (__attribute__((address_space(3))) void *)(VBb + 512 * i), 16, 0, 0);
+                lds_dma16(src, VBb + 512 * i);
             }
         };
         // (the snapshot's stores are issued ahead of the requests: the waits below count on the requests being the youngest
@@ -1479,7 +1478,7 @@ __global__ __launch_bounds__(DH * 4) void scan_wide_kernel(generic::PrefillArgs<
             if (NBUF >= 4 && ahead >= 2) __builtin_amdgcn_s_waitcnt(0x0F70 | ((2 * LPB) & 15) | (((2 * LPB) >> 4) << 14));
             else if (NBUF >= 3 && ahead == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | (LPB & 15) | ((LPB >> 4) << 14));
             else __builtin_amdgcn_s_waitcnt(0x0F70);
-            __syncthreads();                      // ... and everybody's; the readers of batch b - 1's buffer are done
+            lds_barrier();                        // ... and everybody's; the readers of batch b - 1's buffer are done
             if (b + NBUF - 1 < NBATCH) issue(b + NBUF - 1, buf == 0 ? NBUF - 1 : buf - 1);
             const uint16_t *PBb = pool + buf * BUF, *VBb = PBb + RB * FR;
             const int pb = b & 1;
@@ -1540,7 +1539,7 @@ __global__ __launch_bounds__(DH * 4) void scan_wide_kernel(generic::PrefillArgs<
             }
             buf = buf == NBUF - 1 ? 0 : buf + 1;
         }
-        __syncthreads();
+        lds_barrier();
         if (tid < 3 * RB) {
             const int k = tid / RB, r = tid % RB;
             float sum = 0.f;
@@ -1548,7 +1547,7 @@ __global__ __launch_bounds__(DH * 4) void scan_wide_kernel(generic::PrefillArgs<
             for (int x = 0; x < NW; x++) sum += part[(NBATCH - 1) & 1][k][x][r];
             tot[k][(NBATCH - 1) * RB + r] = sum;
         }
-        __syncthreads();
+        lds_barrier();
         }
 
         // ---- 3. selection: the 64 candidates with the smallest squared error are folded (order: score descending,
@@ -1575,7 +1574,7 @@ __global__ __launch_bounds__(DH * 4) void scan_wide_kernel(generic::PrefillArgs<
             skey[e] = __float_as_uint(sq) & 0x7FFFFFFFu;
         }
         }
-        __syncthreads();
+        lds_barrier();
         if (w == 0 && LAM > 0) {
             // One wavefront holds all scores (up to 17 per lane) and builds the 64th smallest bit by bit: a trial value is
             // kept while fewer than 64 scores lie below it.  Scores equal to the threshold are folded too if that makes
@@ -1633,7 +1632,7 @@ __global__ __launch_bounds__(DH * 4) void scan_wide_kernel(generic::PrefillArgs<
             }
             if (lane == 0) ne_s = nen;
         }
-        __syncthreads();
+        lds_barrier();
         const int ne = ne_s;   // exactly 64 are folded, so entrants and leavers pair up
 
         // ---- 4. fold: H[f][c] += sum_e phi_e[f] v_e[c], s[f] += sum_e phi_e[f] over the 64 folded pairs, whose rows are
@@ -1643,15 +1642,13 @@ __global__ __launch_bounds__(DH * 4) void scan_wide_kernel(generic::PrefillArgs<
         for (int it = 0; it < C * FR / 512 / NW; it++) {
             const int i = w + NW * it, g = 512 * i + 8 * lane, row = g / FR, pt = (g % FR) / DF, slot = (g % DF) >> 3;
             const uint16_t *src = phirow(flist[row]) + pt * DF + ((slot ^ fswz(row)) << 3);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                             (__attribute__((address_space(3))) void *)(FP + 512 * i), 16, 0, 0);
+            lds_dma16(src, FP + 512 * i);
         }
 #pragma unroll
         for (int it = 0; it < C * DH / 512 / NW; it++) {
             const int i = w + NW * it, g = 512 * i + 8 * lane, row = g / DH, slot = (g % DH) >> 3;
             const bf16_t *src = vrow(flist[row]) + ((slot ^ vswz2<PR>(row)) << 3);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                             (__attribute__((address_space(3))) void *)(FV + 512 * i), 16, 0, 0);
+            lds_dma16(src, FV + 512 * i);
         }
         // compaction, first half: the entrants' rows (keys, values, features) are requested now and stored after the fold
         constexpr int CIT = C * 2 * PR / NTH, PIT = C * (FR / 8) / NTH;
@@ -1672,7 +1669,7 @@ __global__ __launch_bounds__(DH * 4) void scan_wide_kernel(generic::PrefillArgs<
             if (o < ne * (FR / 8)) fe[it] = reinterpret_cast<const uint4 *>(phirow(ecand[o / (FR / 8)]))[o % (FR / 8)];
         }
         __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
-        __syncthreads();
+        lds_barrier();
         // contraction slots of lane group g4 in k-step kst: pairs 32 kst + 4 g4 + 0..3, then + 16 (the order in which the
         // transposing read delivers them, the same for both operands)
 #pragma unroll
