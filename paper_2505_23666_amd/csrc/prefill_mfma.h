@@ -687,6 +687,30 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
             return e >= LAM ? phk_cur + (size_t)(e - LAM) * 2 * D : phiE + (size_t)e * 2 * D;
         };
 
+        // A cache too large to stay in LDS: a batch's rows come in from the global scratch (cache
+        // slots) and from the feature kernel's output (pairs leaving the window) by direct global -> LDS loads: no
+        // registers, all of a wavefront's loads in flight at once.  One load instruction fills 1 KB of LDS, lane l its
+        // bytes 16 l ..: four rows of one part; a row's 16-byte pieces are XOR-swizzled, so lane l fetches the piece that
+        // belongs in its position.  The candidates' values at this wavefront's columns travel with them, in registers.
+        constexpr int BPP = RB / 4;                          // 1 KB blocks per part (high, low)
+        static_assert(PERSIST || (2 * BPP) % NW == 0, "the wavefronts share a batch's blocks evenly");
+        uint2 vvq[PERSIST ? 1 : TB][RT];
+        auto request_batch = [&](int tb0, uint16_t *dstbuf) {
+#pragma unroll
+            for (int it = 0; it < 2 * BPP / NW; it++) {
+                const int blk = w + NW * it, pt = blk / BPP, rl0 = 4 * (blk % BPP);
+                const int rl = rl0 + (lane >> 4), slot = lane & 15, e = 16 * tb0 + rl;
+                const uint16_t *src = phirow(e) + pt * D + ((slot ^ (rl & 15)) << 3);
+                lds_dma16(src, &dstbuf[pt * RB * D + rl0 * D]);
+            }
+#pragma unroll
+            for (int u = 0; u < (PERSIST ? 1 : TB); u++)
+#pragma unroll
+                for (int rt = 0; rt < RT; rt++)
+                    vvq[u][rt] = *reinterpret_cast<const uint2 *>(vrow(16 * (tb0 + u) + r16) + 16 * (RT * w + rt) + 4 * g4);
+        };
+        if (!PERSIST) request_batch(0, PB);   // (the chunk's first batch travels while the operands below are made)
+
         // ---- 1. operands of the recall GEMM from the fp32 registers (H^T, and s as one more row held by the lanes
         // of row 0); the snapshot for the output kernel is stored further down
         bf16x8 Ahi[RT][4], Alo[RT][4], Ash[4], Asl[4];
@@ -721,29 +745,6 @@ __global__ __launch_bounds__(DH * 4 / RT, 1) void scan_fast_kernel(generic::Pref
         // ---- 2. phi of the candidates and their recall error, in batches of TB tiles.  Global loads of a batch are
         // requested up front: the candidates' values for the recall epilogue, then the rows wanted by the next chunk; the
         // snapshot stores follow, so that they drain while the recall GEMM runs out of LDS and registers.
-        // A cache too large to stay in LDS: a batch's rows come in from the global scratch (cache
-        // slots) and from the feature kernel's output (pairs leaving the window) by direct global -> LDS loads: no
-        // registers, all of a wavefront's loads in flight at once.  One load instruction fills 1 KB of LDS, lane l its
-        // bytes 16 l ..: four rows of one part; a row's 16-byte pieces are XOR-swizzled, so lane l fetches the piece that
-        // belongs in its position.  The candidates' values at this wavefront's columns travel with them, in registers.
-        constexpr int BPP = RB / 4;                          // 1 KB blocks per part (high, low)
-        static_assert(PERSIST || (2 * BPP) % NW == 0, "the wavefronts share a batch's blocks evenly");
-        uint2 vvq[PERSIST ? 1 : TB][RT];
-        auto request_batch = [&](int tb0, uint16_t *dstbuf) {
-#pragma unroll
-            for (int it = 0; it < 2 * BPP / NW; it++) {
-                const int blk = w + NW * it, pt = blk / BPP, rl0 = 4 * (blk % BPP);
-                const int rl = rl0 + (lane >> 4), slot = lane & 15, e = 16 * tb0 + rl;
-                const uint16_t *src = phirow(e) + pt * D + ((slot ^ (rl & 15)) << 3);
-                lds_dma16(src, &dstbuf[pt * RB * D + rl0 * D]);
-            }
-#pragma unroll
-            for (int u = 0; u < (PERSIST ? 1 : TB); u++)
-#pragma unroll
-                for (int rt = 0; rt < RT; rt++)
-                    vvq[u][rt] = *reinterpret_cast<const uint2 *>(vrow(16 * (tb0 + u) + r16) + 16 * (RT * w + rt) + 4 * g4);
-        };
-        if (!PERSIST) request_batch(0, PB);
 #pragma unroll 1
         for (int tp = 0; tp < NTILE; tp += NBUFS * TB) {
 #pragma unroll
