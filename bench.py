@@ -120,6 +120,35 @@ def extras(torch, wl, lb, dev, only=None):
             f"({ms:.2f} ms), decode {us:.1f} us/step = {res['decode_tokens_per_s_per_layer'] / 1e6:.4f} M tokens/s/layer")
         return res
 
+    def per_chunk(label, eta, lam, D, B=4, Hq=32, Hkv=8, d=128):
+        """Update-only prefill calls of 4 096 and of 8 192 tokens: the difference over the 64 extra chunks is the state
+        evolution's time per regular chunk with nothing else on the chip."""
+        if only and only not in label:
+            return None
+        g = wl.rng(11, 3)
+        mk = lambda *shape: to_dev(wl.store(g.standard_normal(shape, dtype=np.float32), "bf16"))
+        Wk = to_dev(wl.store((g.standard_normal((Hkv, D // 2, d), dtype=np.float32) / np.sqrt(d)).astype(np.float32), "bf16"))
+        lay = lb.LolaLayer(B, Hq, Hkv, d, D, eta, lam, 64, dtype="bf16", out_dtype="f32", device=dev)
+        ms = []
+        for T in (4096, 8192):
+            k, v = mk(B, Hkv, T, d), mk(B, Hkv, T, d)
+            ts = []
+            for r in range(3):
+                lay.reset()
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(); lay.prefill(None, k, v, None, Wk); e1.record()
+                torch.cuda.synchronize()
+                if r:
+                    ts.append(e0.elapsed_time(e1))
+            ms.append(float(np.mean(ts)))
+        us = (ms[1] - ms[0]) * 1e3 / 64
+        res = {"mode": label, "shape": f"B{B} Hq{Hq} Hkv{Hkv} d{d} D{D} eta{eta} lambda{lam} C64", "kernels": lay.lola_path,
+               "update_only_ms_T4096": round(ms[0], 3), "update_only_ms_T8192": round(ms[1], 3), "evolution_us_per_chunk": round(us, 2)}
+        log(f"[extras] {label}: {res['shape']} {res['kernels']}: update-only prefill {ms[0]:.2f} ms at T 4096, {ms[1]:.2f} ms at T 8192 "
+            f"-> {us:.1f} us per regular chunk")
+        return res
+
     rows = []
     s8 = dict(B=4, Hq=32, Hkv=8, d=128, D=128, eta=64, lam=128, Cc=64, T=2048, n_dec=68)
     rows.append(run("8B shape, self-recall error (reference point)", **s8))
@@ -144,6 +173,11 @@ def extras(torch, wl, lb, dev, only=None):
     # head_dim 128, T = 4096, eta = 64, lambda = 128) except for the feature dimension (128 here, 2 d there)
     rows.append(run("layer-latency table shape: batch 2, 32 heads (no grouping), T 4096", B=2, Hq=32, Hkv=32, d=128, D=128, eta=64, lam=128,
                     Cc=64, T=4096, n_dec=36, fold_defer=8))
+    rows.append(per_chunk("state evolution per chunk, eta=lambda=256, D=2d", 256, 256, 256))
+    rows.append(per_chunk("state evolution per chunk, eta=512, lambda=1024, D=2d", 512, 1024, 256))
+    rows.append(per_chunk("state evolution per chunk, eta=128, lambda=512, D=d", 128, 512, 128))
+    rows.append(per_chunk("state evolution per chunk, eta=64, lambda=256, D=d", 64, 256, 128))
+    rows.append(per_chunk("state evolution per chunk, eta=64, lambda=128, D=d", 64, 128, 128))
     return {"metric": "LoLA layer side modes, tokens/s/layer", "data": "synthetic", "dtype": "bf16", "rows": [r for r in rows if r]}
 
 

@@ -1449,23 +1449,6 @@ __global__ __launch_bounds__(DH * 4) void scan_wide_kernel(generic::PrefillArgs<
                 lds_dma16(src, VBb + 512 * i);
             }
         };
-        // (the snapshot's stores are issued ahead of the requests: the waits below count on the requests being the youngest
-        // entries of the in-order memory counter)
-        if (a.want_out) {
-            const size_t sj = (size_t)si * a.S + (j - a.jb);
-            uint16_t *s16 = reinterpret_cast<uint16_t *>(a.snapH) + sj * (2 * DF * DH);
-#pragma unroll
-            for (int ks = 0; ks < KF; ks++) {
-                // one contiguous 1 KB piece per store: [part][row tile][k-step][lane]
-                const int off = ((w * KF + ks) * 64 + lane) << 3;
-                *reinterpret_cast<uint4 *>(s16 + off) = __builtin_bit_cast(uint4, Ahi[ks]);
-                *reinterpret_cast<uint4 *>(s16 + DF * DH + off) = __builtin_bit_cast(uint4, Alo[ks]);
-            }
-            for (int x = tid; x < DF / 4; x += NTH) reinterpret_cast<float4 *>(a.snapS + sj * DF)[x] = reinterpret_cast<const float4 *>(s_l)[x];
-#pragma unroll
-            for (int x = 0; x < NSP; x++)
-                if (tid + NTH * x < LAM) a.snapG[sj * LAM + tid + NTH * x] = sprow_ld[x];
-        }
         if (!SCORED && LAM > 0) {
 #pragma unroll
         for (int b = 0; b < NBUF - 1; b++) issue(b, b);   // (lambda + 64 >= 128 candidates: at least NBUF batches)
@@ -1549,6 +1532,24 @@ __global__ __launch_bounds__(DH * 4) void scan_wide_kernel(generic::PrefillArgs<
             tot[k][(NBATCH - 1) * RB + r] = sum;
         }
         lds_barrier();
+        }
+
+        // The snapshot is stored here, behind the batches: the memory counter is in order, so stores issued ahead of the
+        // batches' requests would stand between every batch and its wait; from here they drain while the selection runs.
+        if (a.want_out) {
+            const size_t sj = (size_t)si * a.S + (j - a.jb);
+            uint16_t *s16 = reinterpret_cast<uint16_t *>(a.snapH) + sj * (2 * DF * DH);
+#pragma unroll
+            for (int ks = 0; ks < KF; ks++) {
+                // one contiguous 1 KB piece per store: [part][row tile][k-step][lane]
+                const int off = ((w * KF + ks) * 64 + lane) << 3;
+                *reinterpret_cast<uint4 *>(s16 + off) = __builtin_bit_cast(uint4, Ahi[ks]);
+                *reinterpret_cast<uint4 *>(s16 + DF * DH + off) = __builtin_bit_cast(uint4, Alo[ks]);
+            }
+            for (int x = tid; x < DF / 4; x += NTH) reinterpret_cast<float4 *>(a.snapS + sj * DF)[x] = reinterpret_cast<const float4 *>(s_l)[x];
+#pragma unroll
+            for (int x = 0; x < NSP; x++)
+                if (tid + NTH * x < LAM) a.snapG[sj * LAM + tid + NTH * x] = sprow_ld[x];
         }
 
         // ---- 3. selection: the 64 candidates with the smallest squared error are folded (order: score descending,
