@@ -156,6 +156,10 @@ def extras(torch, wl, lb, dev, only=None):
                     n_dec=68, fold_defer=8))
     rows.append(run("8B shape, batch 16, deferred folds", B=16, Hq=32, Hkv=8, d=128, D=128, eta=64, lam=128, Cc=64, T=2048, n_dec=68,
                     fold_defer=8))
+    rows.append(run("8B shape, batch 128, deferred folds (two rounds of workgroups per launch)", B=128, Hq=32, Hkv=8, d=128, D=128, eta=64, lam=128,
+                    Cc=64, T=1024, n_dec=68, fold_defer=8))
+    rows.append(run("8B shape, batch 256, deferred folds (four rounds of workgroups per launch)", B=256, Hq=32, Hkv=8, d=128, D=128, eta=64, lam=128,
+                    Cc=64, T=512, n_dec=68, fold_defer=8))
     rows.append(run("8B shape, queries do not read the sparse cache", **s8, query_hide=2))
     rows.append(run("8B shape, queries do not read the hidden state", **s8, query_hide=1, fold_defer=8))
     rows.append(run("8B shape, attention-weight score (kind 4)", **s8, score_kind=4))
