@@ -1966,8 +1966,7 @@ __global__ __launch_bounds__(256) void step_out_wide_kernel(StepOutArgs<TO> a) {
                 int key = 32 * kb + row;
                 if (key >= nk) key = 0;   // weight 0: any readable row will do
                 const bf16_t *vr = key < spc ? sp_v + (size_t)key * DH : win_v + (size_t)(key - spc) * DH;
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(vr + ((slot ^ vswz2<PR>(row)) << 3)),
-                                                 (__attribute__((address_space(3))) void *)(&VS[w][buf][512 * i]), 16, 0, 0);
+                lds_dma16(vr + ((slot ^ vswz2<PR>(row)) << 3), &VS[w][buf][512 * i]);   // (inline assembly: the reads of the other buffer below do not wait for it)
             }
         };
         const int nblk = KPAD / 32;
