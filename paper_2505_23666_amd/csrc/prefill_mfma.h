@@ -72,7 +72,7 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
     for (int ks = 0; ks < KS; ks++) BQ[ks] = ld_bf16x8(qh + (size_t)(qi < cl ? qi : 0) * DH + 32 * ks + 8 * g4);
     if (tid < D / 4) reinterpret_cast<float4 *>(s_l)[tid] = reinterpret_cast<const float4 *>(ssnap)[tid];
     for (int x = tid; x < LAM; x += 256) G_l[x] = Gsnap[x];
-    __syncthreads();
+    lds_barrier();
 
     // ---- softmax part over key blocks of 128 positions
     uint16_t *Kl = L, *Vt = L + DH * 128;   // [key][input piece ^ key % pieces] and [c][key chunk ^ swz(c)]
@@ -116,13 +116,13 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
                 *reinterpret_cast<uint32_t *>(&Vt[c * 128 + ((kchunk ^ ((c ^ (c >> 3)) & 15)) << 3) + kel]) = wv; \
             } }
         LOLA_REP8(LOLA_KVLOAD)
-        __syncthreads();   // previous users of L (H^T, or the previous block) are done
+        lds_barrier();   // previous users of L (H^T, or the previous block) are done
         LOLA_REP8(LOLA_KVSTORE)
 #undef LOLA_KVLOAD
 #undef LOLA_KVSTORE
 #undef LOLA_KVROW
 #undef LOLA_REP8
-        __syncthreads();
+        lds_barrier();
         // S^T = K Q^T for the 8 key tiles of the block; lane (column = query r16, group g4) holds keys 16 mt + 4 g4 + i
         f32x4 sc[8];
         float bmax = mrun;
@@ -173,7 +173,7 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
     // H^T snapshot -> LDS (16-byte pieces XOR-swizzled by the row so that operand reads are conflict free), phi(q),
     // then per value tile lin^T[c][q] = sum_f H^T[c][f] phi(q)[f] and the output
     //   y = (out + exp(-m) lin) / (sum p + exp(-m) phi(q)^T s);  the lane holds columns c = 16 mt + 4 g4 + 0..3 of query qi
-    __syncthreads();   // the last key block has been consumed
+    lds_barrier();   // the last key block has been consumed
 #pragma unroll
     for (int p4 = 0; p4 < DH / 32; p4++) {
         uint4 hv[4];
@@ -216,7 +216,7 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
     split8(&pn[0], Bh[2], Bl[2]); split8(&pn[8], Bh[3], Bl[3]);
     const float el = (a.dm.hide & 1) ? 0.f : fexp2(-mrun);   // restricted query: no hidden-state terms
     const float inv = frcp(fmaf(el, lden, lsum));
-    __syncthreads();   // H^T is in LDS
+    lds_barrier();   // H^T is in LDS
 #pragma unroll
     for (int mt = 0; mt < NCT; mt++) {
         f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acc2 = {0.f, 0.f, 0.f, 0.f};
