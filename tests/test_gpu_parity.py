@@ -405,6 +405,31 @@ def test_8b_shape_outputs_on_the_second_stream():
     lb.lola_release_streams()
 
 
+def test_8b_shape_budget_256_outputs_on_the_second_stream():
+    """Sparse budget 256 at the 8B head shape with the outputs on the second stream: the candidates' features stream
+    through LDS in batches requested one ahead, and every piece of the pass starts with a launch of the feature kernel
+    of the run-time shapes (the pairs that leave the window in its chunks, the cache slots as it finds them).  Two calls
+    with a ragged boundary against the oracle, then the first call again on one stream: bit for bit the same outputs."""
+    sh = wl.scaled(3, lam=256, T=64 * 32 + 37 + 64 * 17)
+    Wq, Wk = wl.weights(sh)
+    q, k, v, _ = wl.sequence_inputs(sh)
+    cut = 64 * 32 + 37
+    kw = dict(prefill_overlap=1)
+    layer, o, rep = P.prefill_parity(sh, q[:, :, :cut], k[:, :, :cut], v[:, :, :cut], Wq, Wk, layer_kw=kw)
+    say("budget 256, two-stream call 1", rep)
+    assert layer.lola_path[0] == "mfma"
+    layer, o, rep = P.prefill_parity(sh, q[:, :, cut:], k[:, :, cut:], v[:, :, cut:], Wq, Wk, layer=layer, oracle=o, layer_kw=kw)
+    say("budget 256, two-stream call 2", rep)
+    dq, dk, dv = P.to_dev(q[:, :, :cut], "bf16"), P.to_dev(k[:, :, :cut], "bf16"), P.to_dev(v[:, :, :cut], "bf16")
+    dWq, dWk = P.w_to_dev(Wq, "bf16"), P.w_to_dev(Wk, "bf16")
+    ref = P.make_layer(sh).prefill(dq, dk, dv, dWq, dWk).clone()
+    two = P.make_layer(sh, **kw)
+    for _ in range(2):
+        two.reset()
+        assert torch.equal(two.prefill(dq, dk, dv, dWq, dWk), ref)
+    torch.cuda.synchronize()
+
+
 def test_two_stream_prefill_from_two_host_threads():
     """Two host threads, each with a layer and a stream of its own, call the prefill at the same time; both calls use
     the library's one second stream and its events.  Each result must equal the one the same call gives alone."""
