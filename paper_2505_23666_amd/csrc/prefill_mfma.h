@@ -2477,8 +2477,7 @@ __global__ __launch_bounds__(64) void scan_nocache_kernel(generic::PrefillArgs<b
         if (!s_role) {
 #pragma unroll
             for (int x = 0; x < 2; x++)
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(vrow(j, lane) + 16 * ct + 8 * x),
-                                                 (__attribute__((address_space(3))) void *)&VS[buf][x * C * 8], 16, 0, 0);
+                lds_dma16(vrow(j, lane) + 16 * ct + 8 * x, &VS[buf][x * C * 8]);
         }
         if (j - 1 >= a.jb) {
             // the feature kernel's rows of chunk j - 1: 32 KB.  An instruction fills 1 KB = two rows; lane l fills part
@@ -2488,9 +2487,7 @@ __global__ __launch_bounds__(64) void scan_nocache_kernel(generic::PrefillArgs<b
 #pragma unroll 8
             for (int i = 0; i < C * 2 * D / 512; i++) {
                 const int row = 2 * i + (lane >> 5);
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)
-                                                     (src + row * 2 * D + ((lane >> 4) & 1) * D + (((lane & 15) ^ fswz(row)) << 3)),
-                                                 (__attribute__((address_space(3))) void *)&PHs[buf][i * 512], 16, 0, 0);
+                lds_dma16(src + row * 2 * D + ((lane >> 4) & 1) * D + (((lane & 15) ^ fswz(row)) << 3), &PHs[buf][i * 512]);
             }
         } else {
             // not covered by the feature kernel: phi of the 64 keys here (Sec. 2.3 eq. feature_map), four tiles of 16
