@@ -268,15 +268,28 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
     // ---- stage 0: loads are requested in the order in which they are consumed (they complete in order): the small
     // per-stream vectors that the first barrier waits for, then the operands of the projections, then the window keys
     const uint4 q_ld = (tid >= 64 && tid < 64 + g * PR) ? reinterpret_cast<const uint4 *>(qg)[tid - 64] : make_uint4(0, 0, 0, 0);
-    const float4 s_ld = tid < D / 4 ? reinterpret_cast<const float4 *>(sg)[tid] : make_float4(0.f, 0.f, 0.f, 0.f);
+    // s and the listed pairs' feature vectors: all lanes of wavefront 0 load (lanes 32 .. 63 the same pieces as 0 .. 31)
+    // inside one wavefront-uniform branch.  Loaded per thread under `tid < D / 4`, the first of these loads was followed
+    // by a wait for everything requested so far (a register copy of its result), which held wavefront 0 for a memory
+    // round trip before it requested its weights and keys.
+    const int wu = __builtin_amdgcn_readfirstlane(w);
+    float4 s_ld = make_float4(0.f, 0.f, 0.f, 0.f);
     float *pphi = nullptr, *pval = nullptr;
     int cnt = 0;
     float4 sp_ld[R > 0 ? R : 1];
+#pragma unroll
+    for (int p = 0; p < (R > 0 ? R : 1); p++) sp_ld[p] = make_float4(0.f, 0.f, 0.f, 0.f);
     if (R > 0) {
         pphi = a.pend_phi + (size_t)si * R * D; pval = a.pend_v + (size_t)si * R * DH;
         cnt = a.pend_count[si];
+    }
+    if (wu == 0) {
+        const int t4 = tid & (D / 4 - 1);
+        s_ld = reinterpret_cast<const float4 *>(sg)[t4];
+        if (R > 0) {
 #pragma unroll
-        for (int p = 0; p < R; p++) sp_ld[p] = tid < D / 4 ? reinterpret_cast<const float4 *>(pphi + p * D)[tid] : make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int p = 0; p < R; p++) sp_ld[p] = reinterpret_cast<const float4 *>(pphi + p * D)[t4];
+        }
     }
     const int idx_ld = tid < LAM ? sp_idx[tid] : 0;
     // W_k crosses the cache hierarchy once per workgroup: each wavefront fetches a quarter (16 projections, 4 KB,
@@ -309,8 +322,9 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
         KN[ks] = ld_bf16x8(knew + 32 * ks + 8 * g4);
     }
     // the value row of the leaving pair (PR threads, 16 bytes each) is wanted much later
-    uint4 p_ld = make_uint4(0, 0, 0, 0);
-    if (popped && tid < PR) p_ld = reinterpret_cast<const uint4 *>(win_v + (size_t)slot * DH)[tid];
+    // (every lane loads its piece of the row, whether or not a pair leaves: a load under a condition, with zeros
+    // otherwise, is followed by a register copy that waits for everything requested so far)
+    const uint4 p_ld = reinterpret_cast<const uint4 *>(win_v + (size_t)slot * DH)[tid & (PR - 1)];
     if (tid < D / 4) {
         float4 sv = s_ld;
         if (R > 0) {
@@ -321,6 +335,16 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
         reinterpret_cast<float4 *>(s_l)[tid] = sv;
     }
     if (tid < LAM) idx_l[tid] = idx_ld;
+    if (tid >= 64 && tid < 64 + g * PR) reinterpret_cast<uint4 *>(qb)[tid - 64] = q_ld;
+    if (tid >= 128 && tid < 128 + 2 * XR * D / 8) reinterpret_cast<uint4 *>(PX)[tid - 128] = make_uint4(0, 0, 0, 0);
+    // W_k staging: row j = projection, 16-byte piece p at position p ^ (j % PR)
+#pragma unroll
+    for (int it = 0; it < KS; it++) {
+        const int j = 16 * w + (64 * it + lane) / PR, pc = lane % PR;
+        *reinterpret_cast<uint4 *>(&PB[j * DH + ((pc ^ (j & (PR - 1))) << 3)]) = wk_ld[it];
+    }
+    lds_barrier();
+    // (behind the barrier: the keys are the last of the loads above, and the barrier needs only the first)
     {
         // the lanes that hold the ring slot's row hand the leaving key over and take the new key
         const bool mine = w < NWT && 16 * w + r16 == slot;
@@ -332,15 +356,6 @@ __global__ __launch_bounds__(256, 2) void decode_fast_kernel(DecodeFastArgs<TO> 
             }
         }
     }
-    if (tid >= 64 && tid < 64 + g * PR) reinterpret_cast<uint4 *>(qb)[tid - 64] = q_ld;
-    if (tid >= 128 && tid < 128 + 2 * XR * D / 8) reinterpret_cast<uint4 *>(PX)[tid - 128] = make_uint4(0, 0, 0, 0);
-    // W_k staging: row j = projection, 16-byte piece p at position p ^ (j % PR)
-#pragma unroll
-    for (int it = 0; it < KS; it++) {
-        const int j = 16 * w + (64 * it + lane) / PR, pc = lane % PR;
-        *reinterpret_cast<uint4 *>(&PB[j * DH + ((pc ^ (j & (PR - 1))) << 3)]) = wk_ld[it];
-    }
-    lds_barrier();
     // W_k as MFMA A operand (row = projection, k = input index): [projection tile][k-step]
     bf16x8 AW[4][KS];
 #pragma unroll
