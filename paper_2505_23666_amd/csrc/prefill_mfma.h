@@ -2097,13 +2097,16 @@ __global__ __launch_bounds__(512) void step_update_wide_kernel(StepUpdateArgs a)
 
     // ---- 1. the state; the leaving pair; the slots' token indices
     float4 hreg[NP][2];
+    auto load_state = [&]() {
 #pragma unroll
-    for (int i = 0; i < NP; i++) {
-        const int idx = w + 8 * i, ct = idx / KF, ks = idx % KF;
-        const float *hp = Hg + (size_t)(16 * ct + r16) * DF + 32 * ks + 4 * g4;
-        hreg[i][0] = *reinterpret_cast<const float4 *>(hp);
-        hreg[i][1] = *reinterpret_cast<const float4 *>(hp + 16);
-    }
+        for (int i = 0; i < NP; i++) {
+            const int idx = w + 8 * i, ct = idx / KF, ks = idx % KF;
+            const float *hp = Hg + (size_t)(16 * ct + r16) * DF + 32 * ks + 4 * g4;
+            hreg[i][0] = *reinterpret_cast<const float4 *>(hp);
+            hreg[i][1] = *reinterpret_cast<const float4 *>(hp + 16);
+        }
+    };
+    load_state();
     if (tid < PR) reinterpret_cast<uint4 *>(pkb)[tid] = reinterpret_cast<const uint4 *>(win_k)[tid];
     else if (tid < 2 * PR) reinterpret_cast<uint4 *>(pvb)[tid - PR] = reinterpret_cast<const uint4 *>(win_v)[tid - PR];
     for (int x = tid; x < DF; x += 512) s_l[x] = sg[x];
@@ -2218,6 +2221,9 @@ __global__ __launch_bounds__(512) void step_update_wide_kernel(StepUpdateArgs a)
         esum = grp_sum(esum);
         if (g4 == 0 && (!tail || r16 == 0)) score[e] = sqrtf(esum);
     }
+    // The fp32 pieces of H^T are read a second time here (from L2) rather than held through the tile loop: there their
+    // 64 registers were spilled, and every reload of a spilled register waits for all outstanding loads.
+    load_state();
     __syncthreads();
     // the leaving pair: this thread's pieces of H^T (row 16 ct + r16, features 32 ks + 4 g4 .. and + 16) times phi
 #pragma unroll
