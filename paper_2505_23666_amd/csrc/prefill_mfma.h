@@ -2136,13 +2136,37 @@ __global__ __launch_bounds__(512) void step_update_wide_kernel(StepUpdateArgs a)
         bf16x8 BK[KS];
 #pragma unroll
         for (int ks = 0; ks < KS; ks++) BK[ks] = ld_bf16x8(kr + 32 * ks + 8 * g4);
+        // The weights come from L2 for every tile; they are requested two projection tiles at a time into two register
+        // sets that are refilled as soon as their products are issued, so that three to four requests' worth of latency
+        // is paid per tile instead of one per product at the end of the compiler's own schedule.
+        auto wld = [&](int mt, int ks) { return ld_bf16x8(Wk + (size_t)(16 * mt + r16) * DH + 32 * ks + 8 * g4); };
+        static_assert(NZT % 4 == 0, "projection tiles are taken four at a time");
+        bf16x8 Wa[2 * KS], Wb[2 * KS];
+#pragma unroll
+        for (int x = 0; x < 2 * KS; x++) Wa[x] = wld(x / KS, x % KS);
+#pragma unroll
+        for (int x = 0; x < 2 * KS; x++) Wb[x] = wld(2 + x / KS, x % KS);
         f32x4 zt[NZT];
 #pragma unroll
-        for (int mt = 0; mt < NZT; mt++) {
-            zt[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        for (int mt = 0; mt < NZT; mt++) zt[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int ks = 0; ks < KS; ks++)
-                zt[mt] = mfma16(ld_bf16x8(Wk + (size_t)(16 * mt + r16) * DH + 32 * ks + 8 * g4), BK[ks], zt[mt]);
+        for (int m0 = 0; m0 < NZT; m0 += 4) {
+#pragma unroll
+            for (int x = 0; x < 2 * KS; x++) zt[m0 + x / KS] = mfma16(Wa[x], BK[x % KS], zt[m0 + x / KS]);
+            __builtin_amdgcn_sched_barrier(0);
+            if (m0 + 4 < NZT) {
+#pragma unroll
+                for (int x = 0; x < 2 * KS; x++) Wa[x] = wld(m0 + 4 + x / KS, x % KS);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int x = 0; x < 2 * KS; x++) zt[m0 + 2 + x / KS] = mfma16(Wb[x], BK[x % KS], zt[m0 + 2 + x / KS]);
+            __builtin_amdgcn_sched_barrier(0);
+            if (m0 + 6 < NZT) {
+#pragma unroll
+                for (int x = 0; x < 2 * KS; x++) Wb[x] = wld(m0 + 6 + x / KS, x % KS);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
         phi_from_z_tiles<NZT>(zt, a.phi_kind, pp, pn);
     };
@@ -2200,9 +2224,17 @@ __global__ __launch_bounds__(512) void step_update_wide_kernel(StepUpdateArgs a)
             split8(&pn[8 * ks], Bh[KF / 2 + ks], Bl[KF / 2 + ks]);
         }
         float esum = 0.f;
+        // the candidate's values at all column tiles are requested together (one round trip instead of one per column
+        // tile) and picked by a chain of selects (indexed by the loop variable, the array would leave the registers)
+        uint2 vva[NCT];
+#pragma unroll
+        for (int c2 = 0; c2 < NCT; c2++) vva[c2] = *reinterpret_cast<const uint2 *>(vr + 16 * c2 + 4 * g4);
 #pragma unroll 2
         for (int ct = 0; ct < NCT; ct++) {
-            const uint2 vv = *reinterpret_cast<const uint2 *>(vr + 16 * ct + 4 * g4);
+            uint2 vv = vva[0];
+#pragma unroll
+            for (int c2 = 1; c2 < NCT; c2++)
+                if (ct == c2) vv = vva[c2];
             f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acc2 = {0.f, 0.f, 0.f, 0.f}, acc3 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < KF; ks++) {
