@@ -1819,17 +1819,33 @@ __global__ __launch_bounds__(256) void step_out_wide_kernel(StepOutArgs<TO> a) {
         bf16x8 AQ[KS];
 #pragma unroll
         for (int ks = 0; ks < KS; ks++) AQ[ks] = r16 < g ? ld_bf16x8(qg + (size_t)r16 * DH + 32 * ks + 8 * g4) : zero_bf16x8();
-        for (int t = w; t < KPAD / 16; t += 4) {
-            const int key = 16 * t + r16;
-            const bool valid = key < nk;
-            const bf16_t *kr = key < spc ? sp_k + (size_t)key * DH : win_k + (size_t)(valid ? key - spc : 0) * DH;
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        // four key tiles per pass, their rows requested together: one tile at a time, every tile cost a round trip
+        constexpr int UT = 4;
+#pragma unroll 1
+        for (int t0 = w; t0 < KPAD / 16; t0 += 4 * UT) {
+            bf16x8 KB[UT][KS];
 #pragma unroll
-            for (int ks = 0; ks < KS; ks++) acc = mfma16(AQ[ks], ld_bf16x8(kr + 32 * ks + 8 * g4), acc);
-            if (g4 < G / 4) {   // rows 4 g4 + i of the tile: the queries
-                const bool hidden = !valid || ((a.hide & 2) && key < spc);   // restricted query: the sparse cache is not read
+            for (int u = 0; u < UT; u++) {
+                const int key = 16 * (t0 + 4 * u) + r16;
+                const bf16_t *kr = key < spc ? sp_k + (size_t)key * DH : win_k + (size_t)(key < nk ? key - spc : 0) * DH;
 #pragma unroll
-                for (int i = 0; i < 4; i++) lg[4 * g4 + i][key] = hidden ? -INFINITY : acc[i] * a.scale;
+                for (int ks = 0; ks < KS; ks++) KB[u][ks] = ld_bf16x8(kr + 32 * ks + 8 * g4);   // (tiles past the last one: any readable row)
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < UT; u++) {
+                const int t = t0 + 4 * u, key = 16 * t + r16;
+                if (t < KPAD / 16) {
+                    const bool valid = key < nk;
+                    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int ks = 0; ks < KS; ks++) acc = mfma16(AQ[ks], KB[u][ks], acc);
+                    if (g4 < G / 4) {   // rows 4 g4 + i of the tile: the queries
+                        const bool hidden = !valid || ((a.hide & 2) && key < spc);   // restricted query: the sparse cache is not read
+#pragma unroll
+                        for (int i = 0; i < 4; i++) lg[4 * g4 + i][key] = hidden ? -INFINITY : acc[i] * a.scale;
+                    }
+                }
             }
         }
     }
@@ -1840,13 +1856,20 @@ __global__ __launch_bounds__(256) void step_out_wide_kernel(StepOutArgs<TO> a) {
         bf16x8 BQ[KS];
 #pragma unroll
         for (int ks = 0; ks < KS; ks++) BQ[ks] = ld_bf16x8(qg + (size_t)qi * DH + 32 * ks + 8 * g4);
+        // all of W_q's operands are requested before the first product (one wavefront per SIMD has the registers:
+        // requested where they are used, they arrive a few at a time, one round trip after the other)
+        bf16x8 WQ[NZT][KS];
+#pragma unroll
+        for (int mt = 0; mt < NZT; mt++)
+#pragma unroll
+            for (int ks = 0; ks < KS; ks++) WQ[mt][ks] = ld_bf16x8(Wq + (size_t)(16 * mt + r16) * DH + 32 * ks + 8 * g4);
+        __builtin_amdgcn_sched_barrier(0);
         f32x4 zt[NZT];
 #pragma unroll
         for (int mt = 0; mt < NZT; mt++) {
             zt[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int ks = 0; ks < KS; ks++)
-                zt[mt] = mfma16(ld_bf16x8(Wq + (size_t)(16 * mt + r16) * DH + 32 * ks + 8 * g4), BQ[ks], zt[mt]);
+            for (int ks = 0; ks < KS; ks++) zt[mt] = mfma16(WQ[mt][ks], BQ[ks], zt[mt]);
         }
         float pp[4 * NZT], pn[4 * NZT];
         phi_from_z_tiles<NZT>(zt, a.phi_kind, pp, pn);
@@ -2015,9 +2038,16 @@ __global__ __launch_bounds__(256) void step_out_wide_kernel(StepOutArgs<TO> a) {
             const int ct = w + 4 * x;
             const float *hrow = Hg + (size_t)(16 * ct + r16) * DF + 4 * g4;
             f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acc2 = {0.f, 0.f, 0.f, 0.f}, acc3 = {0.f, 0.f, 0.f, 0.f};
+            float4 hv[KF][2];   // the row's pieces, requested together
 #pragma unroll
             for (int ks = 0; ks < KF; ks++) {
-                const float4 h0 = *reinterpret_cast<const float4 *>(hrow + 32 * ks), h1 = *reinterpret_cast<const float4 *>(hrow + 32 * ks + 16);
+                hv[ks][0] = *reinterpret_cast<const float4 *>(hrow + 32 * ks);
+                hv[ks][1] = *reinterpret_cast<const float4 *>(hrow + 32 * ks + 16);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int ks = 0; ks < KF; ks++) {
+                const float4 h0 = hv[ks][0], h1 = hv[ks][1];
                 const float x8[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
                 bf16x8 Bh, Bl;
                 split8(x8, Bh, Bl);
