@@ -1945,6 +1945,33 @@ __global__ __launch_bounds__(256) void step_out_wide_kernel(StepOutArgs<TO> a) {
         }
         __syncthreads();   // the logits are overwritten next
     }
+    // the first block of value rows of section 4 is requested here: it lands while the weights are computed (each
+    // wavefront's VS tile is its own, and nothing reads it before section 4)
+    auto stage = [&](int kb, int buf) {
+        // 1 KB per instruction = 2048 / DH rows; lane l fills bytes 16 l ..: the row's piece (l % PR) ^ vswz2(row)
+#pragma unroll
+        for (int i = 0; i < 32 * DH / 512; i++) {
+            const int row = (512 * i + 8 * lane) / DH, slot = lane % PR;
+            int key = 32 * kb + row;
+            if (key >= nk) key = 0;   // weight 0: any readable row will do
+            const bf16_t *vr = key < spc ? sp_v + (size_t)key * DH : win_v + (size_t)(key - spc) * DH;
+            lds_dma16(vr + ((slot ^ vswz2<PR>(row)) << 3), &VS[w][buf][512 * i]);   // (inline assembly: the reads of the other buffer below do not wait for it)
+        }
+    };
+    const int nblk = KPAD / 32;
+    if (w < nblk) stage(w, 0);
+    // and so are this wavefront's rows of H^T for section 5 (one wavefront per SIMD has the registers to hold them)
+    float4 hv[NCT / 4][KF][2];
+#pragma unroll
+    for (int x = 0; x < NCT / 4; x++) {
+        const float *hrow = Hg + (size_t)(16 * (w + 4 * x) + r16) * DF + 4 * g4;
+#pragma unroll
+        for (int ks = 0; ks < KF; ks++) {
+            hv[x][ks][0] = *reinterpret_cast<const float4 *>(hrow + 32 * ks);
+            hv[x][ks][1] = *reinterpret_cast<const float4 *>(hrow + 32 * ks + 16);
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
     // ---- 3. weights of queries w, w + 4, ...: m = max(0, max logit) (the linear terms carry weight e^(-m) <= 1)
 #pragma unroll 1
     for (int qi = w; qi < g; qi += 4) {
@@ -1981,19 +2008,6 @@ __global__ __launch_bounds__(256) void step_out_wide_kernel(StepOutArgs<TO> a) {
         f32x4 acc[NCT];
 #pragma unroll
         for (int ct = 0; ct < NCT; ct++) acc[ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
-        auto stage = [&](int kb, int buf) {
-            // 1 KB per instruction = 2048 / DH rows; lane l fills bytes 16 l ..: the row's piece (l % PR) ^ vswz2(row)
-#pragma unroll
-            for (int i = 0; i < 32 * DH / 512; i++) {
-                const int row = (512 * i + 8 * lane) / DH, slot = lane % PR;
-                int key = 32 * kb + row;
-                if (key >= nk) key = 0;   // weight 0: any readable row will do
-                const bf16_t *vr = key < spc ? sp_v + (size_t)key * DH : win_v + (size_t)(key - spc) * DH;
-                lds_dma16(vr + ((slot ^ vswz2<PR>(row)) << 3), &VS[w][buf][512 * i]);   // (inline assembly: the reads of the other buffer below do not wait for it)
-            }
-        };
-        const int nblk = KPAD / 32;
-        if (w < nblk) stage(w, 0);
         int buf = 0;
 #pragma unroll 1
         for (int kb = w; kb < nblk; kb += 4) {
@@ -2036,18 +2050,10 @@ __global__ __launch_bounds__(256) void step_out_wide_kernel(StepOutArgs<TO> a) {
 #pragma unroll
         for (int x = 0; x < NCT / 4; x++) {
             const int ct = w + 4 * x;
-            const float *hrow = Hg + (size_t)(16 * ct + r16) * DF + 4 * g4;
             f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acc2 = {0.f, 0.f, 0.f, 0.f}, acc3 = {0.f, 0.f, 0.f, 0.f};
-            float4 hv[KF][2];   // the row's pieces, requested together
 #pragma unroll
             for (int ks = 0; ks < KF; ks++) {
-                hv[ks][0] = *reinterpret_cast<const float4 *>(hrow + 32 * ks);
-                hv[ks][1] = *reinterpret_cast<const float4 *>(hrow + 32 * ks + 16);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int ks = 0; ks < KF; ks++) {
-                const float4 h0 = hv[ks][0], h1 = hv[ks][1];
+                const float4 h0 = hv[x][ks][0], h1 = hv[x][ks][1];
                 const float x8[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
                 bf16x8 Bh, Bl;
                 split8(x8, Bh, Bl);
@@ -2113,19 +2119,13 @@ __global__ __launch_bounds__(512) void step_update_wide_kernel(StepUpdateArgs a)
     __shared__ __attribute__((aligned(16))) float phip[DF];   // phi of the leaving pair
     __shared__ float partp[KF][DH];                           // its recall, partial sums over 32 features each
     __shared__ float rdp_s, errp[2];
+    __shared__ __attribute__((aligned(16))) float zp[M];      // its projections
 
     const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, r16 = lane & 15, g4 = lane >> 4;
     const int si = blockIdx.x, h = si % a.Hkv, LAM = a.lam, ETA = a.eta;
-    const int64_t tok = a.st.n_tokens[si];
-    if (!(tok >= (int64_t)ETA && a.st.sp_count[si] == LAM)) return;
-    const int slot = (int)(tok % ETA), pidx = (int)(tok - ETA);
     float *Hg = a.st.H + (size_t)si * DF * DH, *sg = a.st.s + (size_t)si * DF;
-    bf16_t *sp_k = a.st.sp_k + (size_t)si * LAM * DH, *sp_v = a.st.sp_v + (size_t)si * LAM * DH;
-    bf16_t *win_k = a.st.win_k + ((size_t)si * ETA + slot) * DH, *win_v = a.st.win_v + ((size_t)si * ETA + slot) * DH;
-    int32_t *sp_idx = a.st.sp_idx + (size_t)si * LAM;
-    const bf16_t *Wk = a.Wk + (size_t)h * M * DH;
-
-    // ---- 1. the state; the leaving pair; the slots' token indices
+    // ---- 1. the state (requested ahead of the check below: its address does not depend on the counters that the check
+    // has to wait for); the leaving pair; the slots' token indices
     float4 hreg[NP][2];
     auto load_state = [&]() {
 #pragma unroll
@@ -2137,16 +2137,38 @@ __global__ __launch_bounds__(512) void step_update_wide_kernel(StepUpdateArgs a)
         }
     };
     load_state();
-    if (tid < PR) reinterpret_cast<uint4 *>(pkb)[tid] = reinterpret_cast<const uint4 *>(win_k)[tid];
-    else if (tid < 2 * PR) reinterpret_cast<uint4 *>(pvb)[tid - PR] = reinterpret_cast<const uint4 *>(win_v)[tid - PR];
+    int32_t *sp_idx = a.st.sp_idx + (size_t)si * LAM;
     for (int x = tid; x < DF; x += 512) s_l[x] = sg[x];
     for (int e = tid; e < LAM; e += 512) idx_l[e] = sp_idx[e];
+    const int64_t tok = a.st.n_tokens[si];
+    if (!(tok >= (int64_t)ETA && a.st.sp_count[si] == LAM)) return;
+    const int slot = (int)(tok % ETA), pidx = (int)(tok - ETA);
+    bf16_t *sp_k = a.st.sp_k + (size_t)si * LAM * DH, *sp_v = a.st.sp_v + (size_t)si * LAM * DH;
+    bf16_t *win_k = a.st.win_k + ((size_t)si * ETA + slot) * DH, *win_v = a.st.win_v + ((size_t)si * ETA + slot) * DH;
+    const bf16_t *Wk = a.Wk + (size_t)h * M * DH;
+    // the leaving pair's projections W_k^T k: one tile of 16 features per wavefront, its operands requested with the
+    // rest of the start-up loads
+    static_assert(NZT <= 8, "one projection tile per wavefront");
+    bf16x8 zW[KS], zK[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) {
+        zW[ks] = ld_bf16x8(Wk + (size_t)(16 * (w < NZT ? w : 0) + r16) * DH + 32 * ks + 8 * g4);
+        zK[ks] = ld_bf16x8(win_k + 32 * ks + 8 * g4);
+    }
+    if (tid < PR) reinterpret_cast<uint4 *>(pkb)[tid] = reinterpret_cast<const uint4 *>(win_k)[tid];
+    else if (tid < 2 * PR) reinterpret_cast<uint4 *>(pvb)[tid - PR] = reinterpret_cast<const uint4 *>(win_v)[tid - PR];
     if (tid == 0) idx_l[LAM] = pidx;
     float *wsc = nullptr, *sps = nullptr;
     if (SCORED) {
         wsc = a.st.win_score + (size_t)si * ETA + slot; sps = a.st.sp_score + (size_t)si * LAM;
         for (int e = tid; e < LAM; e += 512) score[e] = sps[e];
         if (tid == 0) score[LAM] = wsc[0];
+    }
+    if (!SCORED && w < NZT) {   // (every column of the tile holds the same key: column 0 stores)
+        f32x4 z = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ks++) z = mfma16(zW[ks], zK[ks], z);
+        if (r16 == 0) *reinterpret_cast<f32x4 *>(&zp[16 * w + 4 * g4]) = z;
     }
     if (!SCORED) {
 #pragma unroll
@@ -2160,52 +2182,32 @@ __global__ __launch_bounds__(512) void step_update_wide_kernel(StepUpdateArgs a)
     }
     __syncthreads();
 
-    // phi of the 16 keys a tile's lanes point at (lane (column r16, group g4) reads 16 bytes of its key per k-step):
-    // the lane's features 16 mt + 4 g4 + i of both halves
-    auto phi_tile = [&](const bf16_t *kr, float (&pp)[4 * NZT], float (&pn)[4 * NZT]) {
-        bf16x8 BK[KS];
+    // W_k as wavefront 0 will need it for the features of the folded pair: requested before the arg-min is known, so
+    // that only the pair's key is waited for afterwards
+    bf16x8 WF[NZT][KS];
+    auto preload_w = [&]() {
 #pragma unroll
-        for (int ks = 0; ks < KS; ks++) BK[ks] = ld_bf16x8(kr + 32 * ks + 8 * g4);
-        // The weights come from L2 for every tile; they are requested two projection tiles at a time into two register
-        // sets that are refilled as soon as their products are issued, so that three to four requests' worth of latency
-        // is paid per tile instead of one per product at the end of the compiler's own schedule.
-        auto wld = [&](int mt, int ks) { return ld_bf16x8(Wk + (size_t)(16 * mt + r16) * DH + 32 * ks + 8 * g4); };
-        static_assert(NZT % 4 == 0, "projection tiles are taken four at a time");
-        bf16x8 Wa[2 * KS], Wb[2 * KS];
+        for (int mt = 0; mt < NZT; mt++)
 #pragma unroll
-        for (int x = 0; x < 2 * KS; x++) Wa[x] = wld(x / KS, x % KS);
+            for (int ks = 0; ks < KS; ks++) WF[mt][ks] = zero_bf16x8();
+        if (w == 0) {
 #pragma unroll
-        for (int x = 0; x < 2 * KS; x++) Wb[x] = wld(2 + x / KS, x % KS);
-        f32x4 zt[NZT];
+            for (int mt = 0; mt < NZT; mt++)
 #pragma unroll
-        for (int mt = 0; mt < NZT; mt++) zt[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int m0 = 0; m0 < NZT; m0 += 4) {
-#pragma unroll
-            for (int x = 0; x < 2 * KS; x++) zt[m0 + x / KS] = mfma16(Wa[x], BK[x % KS], zt[m0 + x / KS]);
-            __builtin_amdgcn_sched_barrier(0);
-            if (m0 + 4 < NZT) {
-#pragma unroll
-                for (int x = 0; x < 2 * KS; x++) Wa[x] = wld(m0 + 4 + x / KS, x % KS);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int x = 0; x < 2 * KS; x++) zt[m0 + 2 + x / KS] = mfma16(Wb[x], BK[x % KS], zt[m0 + 2 + x / KS]);
-            __builtin_amdgcn_sched_barrier(0);
-            if (m0 + 6 < NZT) {
-#pragma unroll
-                for (int x = 0; x < 2 * KS; x++) Wb[x] = wld(m0 + 6 + x / KS, x % KS);
-            }
-            __builtin_amdgcn_sched_barrier(0);
+                for (int ks = 0; ks < KS; ks++) WF[mt][ks] = ld_bf16x8(Wk + (size_t)(16 * mt + r16) * DH + 32 * ks + 8 * g4);
         }
-        phi_from_z_tiles<NZT>(zt, a.phi_kind, pp, pn);
+        __builtin_amdgcn_sched_barrier(0);
     };
+    if (SCORED) preload_w();
 
     // ---- 2. self-recall errors
     if (!SCORED) {
-    if (w == 7) {   // the leaving pair's features (every column of the tile holds the same key: column 0 stores)
+    if (w == 7) {   // the leaving pair's features from its projections (every column of the tile holds the same key: column 0 stores)
         float pp[4 * NZT], pn[4 * NZT];
-        phi_tile(reinterpret_cast<const bf16_t *>(pkb), pp, pn);
+        f32x4 zt[NZT];
+#pragma unroll
+        for (int mt = 0; mt < NZT; mt++) zt[mt] = *reinterpret_cast<const f32x4 *>(&zp[16 * mt + 4 * g4]);
+        phi_from_z_tiles<NZT>(zt, a.phi_kind, pp, pn);
         float dn = 0.f;
 #pragma unroll
         for (int mt = 0; mt < NZT; mt++) {
@@ -2226,63 +2228,140 @@ __global__ __launch_bounds__(512) void step_update_wide_kernel(StepUpdateArgs a)
             }
         }
     }
-    const int ntile = LAM / 16;
+    // Two tiles (32 candidates) per pass: every operand of H^T read from LDS and every operand of W_k read from L2
+    // serves both, which halves the two streams that, next to the products themselves, fill the pass (per tile of 16
+    // candidates the recall GEMM reads all 2 D d bytes of the split H^T).
+    const int npair = LAM / 32;
 #pragma unroll 1
-    for (int t = w; t < ntile; t += 8) {
-        const bool tail = false;
-        const int e = 16 * t + r16;
-        const bf16_t *kr = sp_k + (size_t)e * DH;
-        const bf16_t *vr = sp_v + (size_t)e * DH;
-        float pp[4 * NZT], pn[4 * NZT];
-        phi_tile(kr, pp, pn);
-        float dn = 0.f;
-#pragma unroll
-        for (int mt = 0; mt < NZT; mt++) {
-            const float4 sp4 = *reinterpret_cast<const float4 *>(&s_l[16 * mt + 4 * g4]);
-            const float4 sn4 = *reinterpret_cast<const float4 *>(&s_l[M + 16 * mt + 4 * g4]);
-            dn = fmaf(pp[4 * mt], sp4.x, dn); dn = fmaf(pp[4 * mt + 1], sp4.y, dn);
-            dn = fmaf(pp[4 * mt + 2], sp4.z, dn); dn = fmaf(pp[4 * mt + 3], sp4.w, dn);
-            dn = fmaf(pn[4 * mt], sn4.x, dn); dn = fmaf(pn[4 * mt + 1], sn4.y, dn);
-            dn = fmaf(pn[4 * mt + 2], sn4.z, dn); dn = fmaf(pn[4 * mt + 3], sn4.w, dn);
+    for (int tp = w; tp < npair; tp += 8) {
+        // With several passes the two wavefronts of a SIMD take turns at the higher issue priority: left alone, the
+        // older one wins every arbitration and the younger one ends a sixth later (with one pass the default is faster).
+        if (npair > 8) {
+            if (((tp >> 3) + (w >> 2)) & 1) __builtin_amdgcn_s_setprio(1);
+            else __builtin_amdgcn_s_setprio(0);
         }
-        dn = grp_sum(dn);
-        const float rd = dn > 0.f ? 1.0f / dn : 0.f;   // recall = 0 while nothing was folded
-        bf16x8 Bh[KF], Bl[KF];
+        const int e0 = 32 * tp + r16;   // this lane's candidates: e0 and e0 + 16
+        bf16x8 Bh[2][KF], Bl[2][KF];
+        float rd[2];
+        {
+            bf16x8 BK[2][KS];
 #pragma unroll
-        for (int ks = 0; ks < KF / 2; ks++) {
-            split8(&pp[8 * ks], Bh[ks], Bl[ks]);
-            split8(&pn[8 * ks], Bh[KF / 2 + ks], Bl[KF / 2 + ks]);
+            for (int u = 0; u < 2; u++)
+#pragma unroll
+                for (int ks = 0; ks < KS; ks++) BK[u][ks] = ld_bf16x8(sp_k + (size_t)(e0 + 16 * u) * DH + 32 * ks + 8 * g4);
+            // (W_k: two projection tiles at a time into two register sets, refilled as soon as their products are issued)
+            // (addresses as a base in scalar registers plus one 32-bit lane offset, kept apart by an empty asm: the
+            // 64-bit lane addresses the compiler would otherwise hold through the loop do not fit beside the operands)
+            typedef const __attribute__((address_space(1))) bf16x8 *global_b8;
+            const uint64_t Wu = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)((uint64_t)(uintptr_t)Wk >> 32)) << 32) |
+                                (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)Wk);
+            uint32_t lane_off = (uint32_t)(2 * (r16 * DH + 8 * g4));   // bytes
+            asm volatile("" : "+v"(lane_off));
+            auto wld = [&](int mt, int ks) { return *(global_b8)((Wu + 2 * (16 * mt * DH + 32 * ks)) + lane_off); };
+            bf16x8 Wa[2 * KS], Wb[2 * KS];
+#pragma unroll
+            for (int x = 0; x < 2 * KS; x++) Wa[x] = wld(x / KS, x % KS);
+#pragma unroll
+            for (int x = 0; x < 2 * KS; x++) Wb[x] = wld(2 + x / KS, x % KS);
+            __builtin_amdgcn_sched_barrier(0);
+            f32x4 zt[2][NZT];
+#pragma unroll
+            for (int u = 0; u < 2; u++)
+#pragma unroll
+                for (int mt = 0; mt < NZT; mt++) zt[u][mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int m0 = 0; m0 < NZT; m0 += 4) {
+#pragma unroll
+                for (int x = 0; x < 2 * KS; x++) {
+                    zt[0][m0 + x / KS] = mfma16(Wa[x], BK[0][x % KS], zt[0][m0 + x / KS]);
+                    zt[1][m0 + x / KS] = mfma16(Wa[x], BK[1][x % KS], zt[1][m0 + x / KS]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if (m0 + 4 < NZT) {
+#pragma unroll
+                    for (int x = 0; x < 2 * KS; x++) Wa[x] = wld(m0 + 4 + x / KS, x % KS);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int x = 0; x < 2 * KS; x++) {
+                    zt[0][m0 + 2 + x / KS] = mfma16(Wb[x], BK[0][x % KS], zt[0][m0 + 2 + x / KS]);
+                    zt[1][m0 + 2 + x / KS] = mfma16(Wb[x], BK[1][x % KS], zt[1][m0 + 2 + x / KS]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if (m0 + 6 < NZT) {
+#pragma unroll
+                    for (int x = 0; x < 2 * KS; x++) Wb[x] = wld(m0 + 6 + x / KS, x % KS);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int u = 0; u < 2; u++) {
+                float pp[4 * NZT], pn[4 * NZT];
+                phi_from_z_tiles<NZT>(zt[u], a.phi_kind, pp, pn);
+                float dn = 0.f;
+#pragma unroll
+                for (int mt = 0; mt < NZT; mt++) {
+                    const float4 sp4 = *reinterpret_cast<const float4 *>(&s_l[16 * mt + 4 * g4]);
+                    const float4 sn4 = *reinterpret_cast<const float4 *>(&s_l[M + 16 * mt + 4 * g4]);
+                    dn = fmaf(pp[4 * mt], sp4.x, dn); dn = fmaf(pp[4 * mt + 1], sp4.y, dn);
+                    dn = fmaf(pp[4 * mt + 2], sp4.z, dn); dn = fmaf(pp[4 * mt + 3], sp4.w, dn);
+                    dn = fmaf(pn[4 * mt], sn4.x, dn); dn = fmaf(pn[4 * mt + 1], sn4.y, dn);
+                    dn = fmaf(pn[4 * mt + 2], sn4.z, dn); dn = fmaf(pn[4 * mt + 3], sn4.w, dn);
+                }
+                dn = grp_sum(dn);
+                rd[u] = dn > 0.f ? 1.0f / dn : 0.f;   // recall = 0 while nothing was folded
+#pragma unroll
+                for (int ks = 0; ks < KF / 2; ks++) {
+                    split8(&pp[8 * ks], Bh[u][ks], Bl[u][ks]);
+                    split8(&pn[8 * ks], Bh[u][KF / 2 + ks], Bl[u][KF / 2 + ks]);
+                }
+            }
         }
-        float esum = 0.f;
-        // the candidate's values at all column tiles are requested together (one round trip instead of one per column
-        // tile) and picked by a chain of selects (indexed by the loop variable, the array would leave the registers)
-        uint2 vva[NCT];
+        float esum[2] = {0.f, 0.f};
+        // the candidates' values at all column tiles are requested together (one round trip instead of one per column
+        // tile) and picked by a chain of selects (indexed by the loop variable, the arrays would leave the registers)
+        uint2 vva[2][NCT];
 #pragma unroll
-        for (int c2 = 0; c2 < NCT; c2++) vva[c2] = *reinterpret_cast<const uint2 *>(vr + 16 * c2 + 4 * g4);
+        for (int u = 0; u < 2; u++)
+#pragma unroll
+            for (int c2 = 0; c2 < NCT; c2++) vva[u][c2] = *reinterpret_cast<const uint2 *>(sp_v + (size_t)(e0 + 16 * u) * DH + 16 * c2 + 4 * g4);
 #pragma unroll 2
         for (int ct = 0; ct < NCT; ct++) {
-            uint2 vv = vva[0];
+            uint2 vv[2] = {vva[0][0], vva[1][0]};
 #pragma unroll
             for (int c2 = 1; c2 < NCT; c2++)
-                if (ct == c2) vv = vva[c2];
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acc2 = {0.f, 0.f, 0.f, 0.f}, acc3 = {0.f, 0.f, 0.f, 0.f};
+                if (ct == c2) { vv[0] = vva[0][c2]; vv[1] = vva[1][c2]; }
+            f32x4 acc[2], acc2[2], acc3[2];
+#pragma unroll
+            for (int u = 0; u < 2; u++) acc[u] = acc2[u] = acc3[u] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < KF; ks++) {
                 const bf16x8 Ah = as_bf16x8(HA[((ct * KF + ks) * 2 + 0) * 64 + lane]), Al = as_bf16x8(HA[((ct * KF + ks) * 2 + 1) * 64 + lane]);
-                acc = mfma16(Ah, Bh[ks], acc);
-                acc2 = mfma16(Ah, Bl[ks], acc2);
-                acc3 = mfma16(Al, Bh[ks], acc3);
-            }
-            const float v4[4] = {bf_lo(vv.x), bf_hi(vv.x), bf_lo(vv.y), bf_hi(vv.y)};
 #pragma unroll
-            for (int i = 0; i < 4; i++) {
-                const float err = (acc[i] + (acc2[i] + acc3[i])) * rd - v4[i];
-                esum = fmaf(err, err, esum);
+                for (int u = 0; u < 2; u++) {
+                    acc[u] = mfma16(Ah, Bh[u][ks], acc[u]);
+                    acc2[u] = mfma16(Ah, Bl[u][ks], acc2[u]);
+                    acc3[u] = mfma16(Al, Bh[u][ks], acc3[u]);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 2; u++) {
+                const float v4[4] = {bf_lo(vv[u].x), bf_hi(vv[u].x), bf_lo(vv[u].y), bf_hi(vv[u].y)};
+#pragma unroll
+                for (int i = 0; i < 4; i++) {
+                    const float err = (acc[u][i] + (acc2[u][i] + acc3[u][i])) * rd[u] - v4[i];
+                    esum[u] = fmaf(err, err, esum[u]);
+                }
             }
         }
-        esum = grp_sum(esum);
-        if (g4 == 0 && (!tail || r16 == 0)) score[e] = sqrtf(esum);
+#pragma unroll
+        for (int u = 0; u < 2; u++) {
+            const float es = grp_sum(esum[u]);
+            if (g4 == 0) score[e0 + 16 * u] = sqrtf(es);
+        }
     }
+    __builtin_amdgcn_s_setprio(0);
+    preload_w();
     // The fp32 pieces of H^T are read a second time here (from L2) rather than held through the tile loop: there their
     // 64 registers were spilled, and every reload of a spilled register waits for all outstanding loads.
     load_state();
@@ -2331,7 +2410,19 @@ __global__ __launch_bounds__(512) void step_update_wide_kernel(StepUpdateArgs a)
         const bf16_t *kr = drop < LAM ? sp_k + (size_t)drop * DH : reinterpret_cast<const bf16_t *>(pkb);
         const bf16_t *vr = drop < LAM ? sp_v + (size_t)drop * DH : reinterpret_cast<const bf16_t *>(pvb);
         float pp[4 * NZT], pn[4 * NZT];
-        phi_tile(kr, pp, pn);   // every column holds the same key: column 0 stores
+        {   // every column holds the same key: column 0 stores
+            bf16x8 BK[KS];
+#pragma unroll
+            for (int ks = 0; ks < KS; ks++) BK[ks] = ld_bf16x8(kr + 32 * ks + 8 * g4);
+            f32x4 zt[NZT];
+#pragma unroll
+            for (int mt = 0; mt < NZT; mt++) {
+                zt[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < KS; ks++) zt[mt] = mfma16(WF[mt][ks], BK[ks], zt[mt]);
+            }
+            phi_from_z_tiles<NZT>(zt, a.phi_kind, pp, pn);
+        }
         if (r16 == 0) {
 #pragma unroll
             for (int mt = 0; mt < NZT; mt++) {
