@@ -2085,11 +2085,12 @@ __global__ __launch_bounds__(256) void step_out_wide_kernel(StepOutArgs<TO> a) {
 // sparse budgets in multiples of 64 and 128 or 256 features.  One workgroup of eight wavefronts per stream:
 //   1. H^T is read once: every thread keeps its 16-byte-piece pairs as fp32 (they are rewritten by the fold) and leaves
 //      them in LDS split into bf16 high + low parts, in the A-operand order of the recall GEMM;
-//   2. the cache's tiles of 16 candidates are dealt to the wavefronts round-robin: phi of the keys on MFMA (Sec. 2.3
-//      eq. feature_map), kept as B operand, recall against all of H^T from LDS, || recall - v || per candidate to LDS;
-//      the leaving pair, which would be a tile (and a round) of its own, is scored from the fp32 registers instead:
-//      wavefront 7 computes its phi first, and after the tiles every thread multiplies its pieces of H^T with it;
-//   3. wavefront 0: arg-min (ties: the larger token index goes), phi of the folded pair as fp32;
+//   2. the cache's candidates are dealt to the wavefronts round-robin, two tiles of 16 per pass: phi of the keys on MFMA
+//      (Sec. 2.3 eq. feature_map), kept as B operand, recall against all of H^T from LDS, || recall - v || per candidate
+//      to LDS; the leaving pair, which would be a tile (and a round) of its own, is scored from the fp32 registers
+//      instead: its projections are computed one tile of 16 features per wavefront during start-up, wavefront 7 turns
+//      them into phi, and after the tiles every thread multiplies its pieces of H^T with it;
+//   3. wavefront 0: arg-min (ties: the larger token index goes), phi of the folded pair as fp32 (W_k requested ahead);
 //   4. rank-1 fold on the registers, H^T and s written back; the leaving pair takes the folded pair's slot unless it is
 //      the one folded; the new pair takes the ring slot; the token counter advances.
 // Streams that are not in steady state are left untouched (the shape-generic step kernel takes them).
