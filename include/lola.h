@@ -113,7 +113,12 @@ typedef struct {
     float *pend_phi;     /* [B, Hkv, R, D]  phi(k) of the listed pairs, fp32 */
     float *pend_v;       /* [B, Hkv, R, d]  their values, fp32 */
     int32_t *pend_count; /* [B, Hkv]        pairs listed, 0 .. R */
-    /* Query-dependent scores (score_kind != LOLA_SCORE_SRE; NULL otherwise). */
+    /* Query-dependent scores (score_kind != LOLA_SCORE_SRE; NULL otherwise, except that sp_score may be
+     * given with LOLA_SCORE_SRE too: it is then scratch of lola_decode_step, [B, Hkv, lambda] floats
+     * whose contents mean nothing between calls, never read before written, not touched by
+     * lola_state_init.  With it, at the run-time-parameter shapes and when batch * n_kv_heads <= 128
+     * and lambda >= 512, the step scores a stream's cached pairs on several workgroups instead of
+     * one; results are the same bit for bit with and without it). */
     float *win_score;    /* [B, Hkv, eta]     sum gathered so far by the pair in each ring slot */
     float *sp_score;     /* [B, Hkv, lambda]  final sum of the pair in each sparse slot */
 } lola_state;

@@ -143,7 +143,7 @@ class LolaLayer:
 
     def __init__(self, B, Hq, Hkv, d, D, eta, lam, C_, dtype="bf16", out_dtype="f32",
                  phi_kind=LOLA_PHI_SOFTMAX, scale=0.0, fold_defer=0, query_hide=0, score_kind=0,
-                 prefill_overlap=0, device="cuda:0"):
+                 prefill_overlap=0, step_scratch=True, device="cuda:0"):
         self.device = torch.device(device)
         self.dt = LOLA_BF16 if dtype == "bf16" else LOLA_F32
         self.odt = LOLA_BF16 if out_dtype == "bf16" else LOLA_F32
@@ -175,6 +175,11 @@ class LolaLayer:
                   self.pend_phi, self.pend_v, self.pend_count, self.win_score, self.sp_score]
         assert [t.numel() * t.element_size() for t in fields] == fb
         self.st = LolaState(*[t.data_ptr() if t.numel() else None for t in fields])
+        # optional scratch of the generation step when the scores are self-recall errors (see lola.h, sp_score)
+        self.step_scratch = None
+        if step_scratch and not sk and lam > 0:
+            self.step_scratch = torch.empty((B, Hkv, lam), dtype=torch.float32, device=dev)
+            self.st.sp_score = self.step_scratch.data_ptr()
         self.workspace = None
         with torch.cuda.device(self.device):
             lola_state_init(self.cfg, self.st)

@@ -92,7 +92,7 @@ lola_status check_state(const lola_config *c, const lola_state *st) {
     if (c->score_kind != LOLA_SCORE_SRE) {
         if ((c->window > 0 && !st->win_score) || (c->sparse_budget > 0 && !st->sp_score)) return LOLA_ERR_NULL;
         if (misaligned(st->win_score) || misaligned(st->sp_score)) return LOLA_ERR_ALIGN;
-    }
+    } else if (st->sp_score && misaligned(st->sp_score)) return LOLA_ERR_ALIGN;   // (optional scratch of the generation step)
     return LOLA_OK;
 }
 
@@ -292,8 +292,17 @@ lola_status run_decode(const lola_config *c, const lola_state *st, const void *q
             fast::StepUpdateArgs ua;
             ua.st = a.st; ua.k = a.k; ua.v = a.v; ua.Wk = a.Wk;
             ua.Hkv = a.dm.Hkv; ua.lam = a.dm.lam; ua.eta = a.dm.eta; ua.phi_kind = a.dm.phi_kind;
+            // Few streams and several passes over the cached pairs: the scoring is split over `parts` workgroups per
+            // stream (each at least one pass of 256 pairs, all of them resident at once), a second launch does the rest.
+            // The scores travel through sp_score, which a self-recall-error state may carry as scratch.
+            const int ns = a.dm.B * a.dm.Hkv, npass = a.dm.lam / 256;
+            int parts = 1;
+            if (!a.dm.score_kind && st->sp_score && npass >= 2 && 2 * ns <= 256) parts = std::min(npass, 256 / ns);
+            const dim3 grid1(ns, parts);
 #define LOLA_UPD(DHV, DFV) do { if (a.dm.score_kind) hipLaunchKernelGGL((fast::step_update_wide_kernel<DHV, DFV, true>), grid, dim3(512), 0, stream, ua); \
-                                else hipLaunchKernelGGL((fast::step_update_wide_kernel<DHV, DFV, false>), grid, dim3(512), 0, stream, ua); } while (0)
+                                else if (parts == 1) hipLaunchKernelGGL((fast::step_update_wide_kernel<DHV, DFV, false>), grid, dim3(512), 0, stream, ua); \
+                                else { hipLaunchKernelGGL((fast::step_update_wide_kernel<DHV, DFV, false, 1>), grid1, dim3(512), 0, stream, ua); \
+                                       hipLaunchKernelGGL((fast::step_update_wide_kernel<DHV, DFV, false, 2>), grid, dim3(512), 0, stream, ua); } } while (0)
             if (c->head_dim == 128) { if (c->feat_dim == 256) LOLA_UPD(128, 256); else LOLA_UPD(128, 128); }
             else { if (c->feat_dim == 256) LOLA_UPD(64, 256); else LOLA_UPD(64, 128); }
 #undef LOLA_UPD

@@ -2105,8 +2105,14 @@ constexpr int STEP_UPDATE_LAMMAX = 2048;
 // SCORED: the candidates' scores are the query-dependent sums kept in the state (Sec. 4 / appendix "scoring ablation":
 // sp_score per cache slot, the leaving pair's finished sum in its ring slot) instead of self-recall errors: step 2 is
 // skipped, the leaving pair's sum follows it into the cache, the new pair's sum starts at zero.
-template <int DH, int DF, bool SCORED>
+// MODE 0: the whole update by one workgroup per stream.  With few streams most compute units would idle and each
+// workgroup is bounded by its unit's share of the memory system, so the scoring (step 2 for the cached pairs) can be
+// split off: MODE 1 = grid (streams, parts), workgroup (stream, part) scores the passes part, part + parts, ... into
+// sp_score (scratch in this mode) and changes nothing else; MODE 2 = one workgroup per stream reads those scores and does
+// the rest (the leaving pair's score, steps 3 and 4).  The scores are computed by the same instructions in either form.
+template <int DH, int DF, bool SCORED, int MODE = 0>
 __global__ __launch_bounds__(512) void step_update_wide_kernel(StepUpdateArgs a) {
+    static_assert(MODE == 0 || !SCORED, "the split forms score by self-recall error");
     constexpr int M = DF / 2, KS = DH / 32, NZT = M / 16, KF = DF / 32, NCT = DH / 16, NP = NCT * KF / 8, PR = DH / 8;
     constexpr int LAMMAX = STEP_UPDATE_LAMMAX;
     __shared__ __attribute__((aligned(16))) uint4 HA[NCT * KF * 2 * 64];     // [row tile][k-step][part][lane]
@@ -2165,13 +2171,16 @@ __global__ __launch_bounds__(512) void step_update_wide_kernel(StepUpdateArgs a)
         for (int e = tid; e < LAM; e += 512) score[e] = sps[e];
         if (tid == 0) score[LAM] = wsc[0];
     }
-    if (!SCORED && w < NZT) {   // (every column of the tile holds the same key: column 0 stores)
+    float *scr = MODE ? a.st.sp_score + (size_t)si * LAM : nullptr;   // split forms: the cached pairs' scores
+    if (MODE == 2)
+        for (int e = tid; e < LAM; e += 512) score[e] = scr[e];
+    if (!SCORED && MODE != 1 && w < NZT) {   // (every column of the tile holds the same key: column 0 stores)
         f32x4 z = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < KS; ks++) z = mfma16(zW[ks], zK[ks], z);
         if (r16 == 0) *reinterpret_cast<f32x4 *>(&zp[16 * w + 4 * g4]) = z;
     }
-    if (!SCORED) {
+    if (!SCORED && MODE != 2) {
 #pragma unroll
     for (int i = 0; i < NP; i++) {
         const float x8[8] = {hreg[i][0].x, hreg[i][0].y, hreg[i][0].z, hreg[i][0].w, hreg[i][1].x, hreg[i][1].y, hreg[i][1].z, hreg[i][1].w};
@@ -2203,7 +2212,7 @@ __global__ __launch_bounds__(512) void step_update_wide_kernel(StepUpdateArgs a)
 
     // ---- 2. self-recall errors
     if (!SCORED) {
-    if (w == 7) {   // the leaving pair's features from its projections (every column of the tile holds the same key: column 0 stores)
+    if (MODE != 1 && w == 7) {   // the leaving pair's features from its projections (every column of the tile holds the same key: column 0 stores)
         float pp[4 * NZT], pn[4 * NZT];
         f32x4 zt[NZT];
 #pragma unroll
@@ -2232,13 +2241,14 @@ __global__ __launch_bounds__(512) void step_update_wide_kernel(StepUpdateArgs a)
     // Two tiles (32 candidates) per pass: every operand of H^T read from LDS and every operand of W_k read from L2
     // serves both, which halves the two streams that, next to the products themselves, fill the pass (per tile of 16
     // candidates the recall GEMM reads all 2 D d bytes of the split H^T).
-    const int npair = LAM / 32;
+    const int npair = MODE == 2 ? 0 : LAM / 32;
+    const int part = MODE == 1 ? blockIdx.y : 0, nparts = MODE == 1 ? gridDim.y : 1;
 #pragma unroll 1
-    for (int tp = w; tp < npair; tp += 8) {
+    for (int tp = w + 8 * part; tp < npair; tp += 8 * nparts) {
         // With several passes the two wavefronts of a SIMD take turns at the higher issue priority: left alone, the
         // older one wins every arbitration and the younger one ends a sixth later (with one pass the default is faster).
-        if (npair > 8) {
-            if (((tp >> 3) + (w >> 2)) & 1) __builtin_amdgcn_s_setprio(1);
+        if (npair > 8 * nparts) {
+            if (((tp >> 3) / nparts + (w >> 2)) & 1) __builtin_amdgcn_s_setprio(1);
             else __builtin_amdgcn_s_setprio(0);
         }
         const int e0 = 32 * tp + r16;   // this lane's candidates: e0 and e0 + 16
@@ -2358,14 +2368,18 @@ __global__ __launch_bounds__(512) void step_update_wide_kernel(StepUpdateArgs a)
 #pragma unroll
         for (int u = 0; u < 2; u++) {
             const float es = grp_sum(esum[u]);
-            if (g4 == 0) score[e0 + 16 * u] = sqrtf(es);
+            if (g4 == 0) {
+                if (MODE == 1) scr[e0 + 16 * u] = sqrtf(es);
+                else score[e0 + 16 * u] = sqrtf(es);
+            }
         }
     }
+    if (MODE == 1) return;
     __builtin_amdgcn_s_setprio(0);
     preload_w();
     // The fp32 pieces of H^T are read a second time here (from L2) rather than held through the tile loop: there their
     // 64 registers were spilled, and every reload of a spilled register waits for all outstanding loads.
-    load_state();
+    if (MODE != 2) load_state();
     __syncthreads();
     // the leaving pair: this thread's pieces of H^T (row 16 ct + r16, features 32 ks + 4 g4 .. and + 16) times phi
 #pragma unroll

@@ -558,6 +558,33 @@ def test_paper_scale_cache_parameters(eta, lam, chunk):
     assert rep["scored"] >= 5 and rep2["scored"] - rep["scored"] == 3
 
 
+@pytest.mark.parametrize("d,D,eta,lam", [(128, 256, 128, 768), (64, 256, 64, 512), (128, 128, 64, 1024), (64, 128, 128, 512)])
+def test_generation_step_scoring_split_over_workgroups(d, D, eta, lam):
+    """With few streams and a sparse budget of 512 or more the generation step at the run-time shapes scores a stream's
+    cached pairs on several workgroups (the scores pass through the optional scratch in the state) and a second launch
+    selects and folds.  Same prefill, then generation steps on a layer with the scratch and on one without it (one
+    workgroup per stream does everything): outputs and every memory equal bit for bit at every step.  (The split form
+    is the one the paper-scale cases compare with the oracle.)"""
+    sh = wl.Shape("split", "bf16", 2, 4, 2, d, D, T=64 * ((eta + lam) // 64 + 2) + 5, eta=eta, lam=lam, C=64, seed=0)
+    nd = 5
+    q, k, v, Wq, Wk = rand_case(900 + d + D + eta + lam, 2, 4, 2, d, D, sh.T + nd, "bf16")
+    dWq, dWk = P.w_to_dev(Wq, "bf16"), P.w_to_dev(Wk, "bf16")
+    T = sh.T
+    dq, dk, dv = P.to_dev(q[:, :, :T], "bf16"), P.to_dev(k[:, :, :T], "bf16"), P.to_dev(v[:, :, :T], "bf16")
+    lays = [P.make_layer(sh, step_scratch=True), P.make_layer(sh, step_scratch=False)]
+    assert lays[0].step_scratch is not None and lays[1].step_scratch is None
+    for lay in lays:
+        lay.prefill(dq, dk, dv, dWq, dWk)
+    for i in range(nd):
+        sq, sk_, sv = (P.to_dev(np.ascontiguousarray(x[:, :, T + i]), "bf16") for x in (q, k, v))
+        outs = [lay.decode_step(sq, sk_, sv, dWq, dWk) for lay in lays]
+        torch.cuda.synchronize()
+        assert torch.equal(outs[0], outs[1]), i
+        for name in ("H", "s", "win_k", "win_v", "sp_k", "sp_v", "sp_idx", "sp_count", "n_tokens"):
+            assert torch.equal(getattr(lays[0], name), getattr(lays[1], name)), (i, name)
+    say("generation step, scoring split over workgroups", d, D, eta, lam, "equal over", nd, "steps")
+
+
 @pytest.mark.parametrize("d,D,eta,lam,phi_kind", [(128, 256, 128, 192, 0), (128, 128, 128, 64, 1), (64, 128, 192, 320, 0),
                                                   (64, 256, 64, 128, 1), (128, 128, 64, 512, 0), (128, 128, 192, 0, 0), (64, 256, 128, 0, 1)])
 def test_run_time_window_and_budget_on_the_mfma_prefill_kernels(d, D, eta, lam, phi_kind):
