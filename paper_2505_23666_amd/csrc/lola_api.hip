@@ -295,13 +295,20 @@ lola_status run_decode(const lola_config *c, const lola_state *st, const void *q
             // Few streams and several passes over the cached pairs: the scoring is split over `parts` workgroups per
             // stream (each at least one pass of 256 pairs, all of them resident at once), a second launch does the rest.
             // The scores travel through sp_score, which a self-recall-error state may carry as scratch.
+            // Where the compute units suffice for one tile of 16 pairs per wavefront (lambda / 128 workgroups per stream),
+            // the parts take single tiles instead of pairs of tiles.
             const int ns = a.dm.B * a.dm.Hkv, npass = a.dm.lam / 256;
             int parts = 1;
-            if (!a.dm.score_kind && st->sp_score && npass >= 2 && 2 * ns <= 256) parts = std::min(npass, 256 / ns);
+            bool single = false;
+            if (!a.dm.score_kind && st->sp_score && npass >= 2 && 2 * ns <= 256) {
+                single = a.dm.lam % 128 == 0 && ns * (a.dm.lam / 128) <= 256;
+                parts = single ? a.dm.lam / 128 : std::min(npass, 256 / ns);
+            }
             const dim3 grid1(ns, parts);
 #define LOLA_UPD(DHV, DFV) do { if (a.dm.score_kind) hipLaunchKernelGGL((fast::step_update_wide_kernel<DHV, DFV, true>), grid, dim3(512), 0, stream, ua); \
                                 else if (parts == 1) hipLaunchKernelGGL((fast::step_update_wide_kernel<DHV, DFV, false>), grid, dim3(512), 0, stream, ua); \
-                                else { hipLaunchKernelGGL((fast::step_update_wide_kernel<DHV, DFV, false, 1>), grid1, dim3(512), 0, stream, ua); \
+                                else { if (single) hipLaunchKernelGGL((fast::step_update_wide_kernel<DHV, DFV, false, 1, 1>), grid1, dim3(512), 0, stream, ua); \
+                                       else hipLaunchKernelGGL((fast::step_update_wide_kernel<DHV, DFV, false, 1>), grid1, dim3(512), 0, stream, ua); \
                                        hipLaunchKernelGGL((fast::step_update_wide_kernel<DHV, DFV, false, 2>), grid, dim3(512), 0, stream, ua); } } while (0)
             if (c->head_dim == 128) { if (c->feat_dim == 256) LOLA_UPD(128, 256); else LOLA_UPD(128, 128); }
             else { if (c->feat_dim == 256) LOLA_UPD(64, 256); else LOLA_UPD(64, 128); }

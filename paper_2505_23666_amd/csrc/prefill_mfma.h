@@ -2110,9 +2110,12 @@ constexpr int STEP_UPDATE_LAMMAX = 2048;
 // split off: MODE 1 = grid (streams, parts), workgroup (stream, part) scores the passes part, part + parts, ... into
 // sp_score (scratch in this mode) and changes nothing else; MODE 2 = one workgroup per stream reads those scores and does
 // the rest (the leaving pair's score, steps 3 and 4).  The scores are computed by the same instructions in either form.
-template <int DH, int DF, bool SCORED, int MODE = 0>
+// NTP: tiles of 16 candidates a wavefront takes per pass (2: the operands of H^T and W_k serve both; 1 for the score
+// part when there are compute units enough to give every wavefront a single tile).
+template <int DH, int DF, bool SCORED, int MODE = 0, int NTP = 2>
 __global__ __launch_bounds__(512) void step_update_wide_kernel(StepUpdateArgs a) {
     static_assert(MODE == 0 || !SCORED, "the split forms score by self-recall error");
+    static_assert(NTP == 2 || (NTP == 1 && MODE == 1), "single tiles: score part only");
     constexpr int M = DF / 2, KS = DH / 32, NZT = M / 16, KF = DF / 32, NCT = DH / 16, NP = NCT * KF / 8, PR = DH / 8;
     constexpr int LAMMAX = STEP_UPDATE_LAMMAX;
     __shared__ __attribute__((aligned(16))) uint4 HA[NCT * KF * 2 * 64];     // [row tile][k-step][part][lane]
@@ -2241,7 +2244,7 @@ __global__ __launch_bounds__(512) void step_update_wide_kernel(StepUpdateArgs a)
     // Two tiles (32 candidates) per pass: every operand of H^T read from LDS and every operand of W_k read from L2
     // serves both, which halves the two streams that, next to the products themselves, fill the pass (per tile of 16
     // candidates the recall GEMM reads all 2 D d bytes of the split H^T).
-    const int npair = MODE == 2 ? 0 : LAM / 32;
+    const int npair = MODE == 2 ? 0 : LAM / (16 * NTP);   // passes of NTP tiles
     const int part = MODE == 1 ? blockIdx.y : 0, nparts = MODE == 1 ? gridDim.y : 1;
 #pragma unroll 1
     for (int tp = w + 8 * part; tp < npair; tp += 8 * nparts) {
@@ -2251,13 +2254,13 @@ __global__ __launch_bounds__(512) void step_update_wide_kernel(StepUpdateArgs a)
             if (((tp >> 3) / nparts + (w >> 2)) & 1) __builtin_amdgcn_s_setprio(1);
             else __builtin_amdgcn_s_setprio(0);
         }
-        const int e0 = 32 * tp + r16;   // this lane's candidates: e0 and e0 + 16
-        bf16x8 Bh[2][KF], Bl[2][KF];
-        float rd[2];
+        const int e0 = 16 * NTP * tp + r16;   // this lane's candidates: e0 (and e0 + 16)
+        bf16x8 Bh[NTP][KF], Bl[NTP][KF];
+        float rd[NTP];
         {
-            bf16x8 BK[2][KS];
+            bf16x8 BK[NTP][KS];
 #pragma unroll
-            for (int u = 0; u < 2; u++)
+            for (int u = 0; u < NTP; u++)
 #pragma unroll
                 for (int ks = 0; ks < KS; ks++) BK[u][ks] = ld_bf16x8(sp_k + (size_t)(e0 + 16 * u) * DH + 32 * ks + 8 * g4);
             // (W_k: two projection tiles at a time into two register sets, refilled as soon as their products are issued)
@@ -2275,17 +2278,17 @@ __global__ __launch_bounds__(512) void step_update_wide_kernel(StepUpdateArgs a)
 #pragma unroll
             for (int x = 0; x < 2 * KS; x++) Wb[x] = wld(2 + x / KS, x % KS);
             __builtin_amdgcn_sched_barrier(0);
-            f32x4 zt[2][NZT];
+            f32x4 zt[NTP][NZT];
 #pragma unroll
-            for (int u = 0; u < 2; u++)
+            for (int u = 0; u < NTP; u++)
 #pragma unroll
                 for (int mt = 0; mt < NZT; mt++) zt[u][mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int m0 = 0; m0 < NZT; m0 += 4) {
 #pragma unroll
                 for (int x = 0; x < 2 * KS; x++) {
-                    zt[0][m0 + x / KS] = mfma16(Wa[x], BK[0][x % KS], zt[0][m0 + x / KS]);
-                    zt[1][m0 + x / KS] = mfma16(Wa[x], BK[1][x % KS], zt[1][m0 + x / KS]);
+#pragma unroll
+                    for (int u = 0; u < NTP; u++) zt[u][m0 + x / KS] = mfma16(Wa[x], BK[u][x % KS], zt[u][m0 + x / KS]);
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 if (m0 + 4 < NZT) {
@@ -2295,8 +2298,8 @@ __global__ __launch_bounds__(512) void step_update_wide_kernel(StepUpdateArgs a)
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int x = 0; x < 2 * KS; x++) {
-                    zt[0][m0 + 2 + x / KS] = mfma16(Wb[x], BK[0][x % KS], zt[0][m0 + 2 + x / KS]);
-                    zt[1][m0 + 2 + x / KS] = mfma16(Wb[x], BK[1][x % KS], zt[1][m0 + 2 + x / KS]);
+#pragma unroll
+                    for (int u = 0; u < NTP; u++) zt[u][m0 + 2 + x / KS] = mfma16(Wb[x], BK[u][x % KS], zt[u][m0 + 2 + x / KS]);
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 if (m0 + 6 < NZT) {
@@ -2306,7 +2309,7 @@ __global__ __launch_bounds__(512) void step_update_wide_kernel(StepUpdateArgs a)
                 __builtin_amdgcn_sched_barrier(0);
             }
 #pragma unroll
-            for (int u = 0; u < 2; u++) {
+            for (int u = 0; u < NTP; u++) {
                 float pp[4 * NZT], pn[4 * NZT];
                 phi_from_z_tiles<NZT>(zt[u], a.phi_kind, pp, pn);
                 float dn = 0.f;
@@ -2328,35 +2331,40 @@ __global__ __launch_bounds__(512) void step_update_wide_kernel(StepUpdateArgs a)
                 }
             }
         }
-        float esum[2] = {0.f, 0.f};
+        float esum[NTP] = {};
         // the candidates' values at all column tiles are requested together (one round trip instead of one per column
         // tile) and picked by a chain of selects (indexed by the loop variable, the arrays would leave the registers)
-        uint2 vva[2][NCT];
+        uint2 vva[NTP][NCT];
 #pragma unroll
-        for (int u = 0; u < 2; u++)
+        for (int u = 0; u < NTP; u++)
 #pragma unroll
             for (int c2 = 0; c2 < NCT; c2++) vva[u][c2] = *reinterpret_cast<const uint2 *>(sp_v + (size_t)(e0 + 16 * u) * DH + 16 * c2 + 4 * g4);
 #pragma unroll 2
         for (int ct = 0; ct < NCT; ct++) {
-            uint2 vv[2] = {vva[0][0], vva[1][0]};
+            uint2 vv[NTP];
+#pragma unroll
+            for (int u = 0; u < NTP; u++) vv[u] = vva[u][0];
 #pragma unroll
             for (int c2 = 1; c2 < NCT; c2++)
-                if (ct == c2) { vv[0] = vva[0][c2]; vv[1] = vva[1][c2]; }
-            f32x4 acc[2], acc2[2], acc3[2];
+                if (ct == c2) {
 #pragma unroll
-            for (int u = 0; u < 2; u++) acc[u] = acc2[u] = acc3[u] = (f32x4){0.f, 0.f, 0.f, 0.f};
+                    for (int u = 0; u < NTP; u++) vv[u] = vva[u][c2];
+                }
+            f32x4 acc[NTP], acc2[NTP], acc3[NTP];
+#pragma unroll
+            for (int u = 0; u < NTP; u++) acc[u] = acc2[u] = acc3[u] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < KF; ks++) {
                 const bf16x8 Ah = as_bf16x8(HA[((ct * KF + ks) * 2 + 0) * 64 + lane]), Al = as_bf16x8(HA[((ct * KF + ks) * 2 + 1) * 64 + lane]);
 #pragma unroll
-                for (int u = 0; u < 2; u++) {
+                for (int u = 0; u < NTP; u++) {
                     acc[u] = mfma16(Ah, Bh[u][ks], acc[u]);
                     acc2[u] = mfma16(Ah, Bl[u][ks], acc2[u]);
                     acc3[u] = mfma16(Al, Bh[u][ks], acc3[u]);
                 }
             }
 #pragma unroll
-            for (int u = 0; u < 2; u++) {
+            for (int u = 0; u < NTP; u++) {
                 const float v4[4] = {bf_lo(vv[u].x), bf_hi(vv[u].x), bf_lo(vv[u].y), bf_hi(vv[u].y)};
 #pragma unroll
                 for (int i = 0; i < 4; i++) {
@@ -2366,7 +2374,7 @@ __global__ __launch_bounds__(512) void step_update_wide_kernel(StepUpdateArgs a)
             }
         }
 #pragma unroll
-        for (int u = 0; u < 2; u++) {
+        for (int u = 0; u < NTP; u++) {
             const float es = grp_sum(esum[u]);
             if (g4 == 0) {
                 if (MODE == 1) scr[e0 + 16 * u] = sqrtf(es);

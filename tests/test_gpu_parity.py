@@ -558,16 +558,19 @@ def test_paper_scale_cache_parameters(eta, lam, chunk):
     assert rep["scored"] >= 5 and rep2["scored"] - rep["scored"] == 3
 
 
-@pytest.mark.parametrize("d,D,eta,lam", [(128, 256, 128, 768), (64, 256, 64, 512), (128, 128, 64, 1024), (64, 128, 128, 512)])
-def test_generation_step_scoring_split_over_workgroups(d, D, eta, lam):
+@pytest.mark.parametrize("d,D,eta,lam,B,Hkv", [(128, 256, 128, 768, 2, 2), (64, 256, 64, 512, 2, 2), (128, 128, 64, 1024, 2, 2),
+                                               (64, 128, 128, 512, 2, 2), (128, 128, 64, 768, 16, 4), (128, 256, 64, 512, 8, 8)])
+def test_generation_step_scoring_split_over_workgroups(d, D, eta, lam, B, Hkv):
     """With few streams and a sparse budget of 512 or more the generation step at the run-time shapes scores a stream's
     cached pairs on several workgroups (the scores pass through the optional scratch in the state) and a second launch
     selects and folds.  Same prefill, then generation steps on a layer with the scratch and on one without it (one
     workgroup per stream does everything): outputs and every memory equal bit for bit at every step.  (The split form
-    is the one the paper-scale cases compare with the oracle.)"""
-    sh = wl.Shape("split", "bf16", 2, 4, 2, d, D, T=64 * ((eta + lam) // 64 + 2) + 5, eta=eta, lam=lam, C=64, seed=0)
+    is the one the paper-scale cases compare with the oracle.)  With 4 streams every wavefront of the score part takes
+    single tiles of 16 pairs; with 64 streams there are not enough compute units for that and it takes pairs of tiles."""
+    Hq = 2 * Hkv
+    sh = wl.Shape("split", "bf16", B, Hq, Hkv, d, D, T=64 * ((eta + lam) // 64 + 2) + 5, eta=eta, lam=lam, C=64, seed=0)
     nd = 5
-    q, k, v, Wq, Wk = rand_case(900 + d + D + eta + lam, 2, 4, 2, d, D, sh.T + nd, "bf16")
+    q, k, v, Wq, Wk = rand_case(900 + d + D + eta + lam, B, Hq, Hkv, d, D, sh.T + nd, "bf16")
     dWq, dWk = P.w_to_dev(Wq, "bf16"), P.w_to_dev(Wk, "bf16")
     T = sh.T
     dq, dk, dv = P.to_dev(q[:, :, :T], "bf16"), P.to_dev(k[:, :, :T], "bf16"), P.to_dev(v[:, :, :T], "bf16")
