@@ -114,11 +114,12 @@ typedef struct {
     float *pend_v;       /* [B, Hkv, R, d]  their values, fp32 */
     int32_t *pend_count; /* [B, Hkv]        pairs listed, 0 .. R */
     /* Query-dependent scores (score_kind != LOLA_SCORE_SRE; NULL otherwise, except that sp_score may be
-     * given with LOLA_SCORE_SRE too: it is then scratch of lola_decode_step, [B, Hkv, lambda] floats
-     * whose contents mean nothing between calls, never read before written, not touched by
-     * lola_state_init.  With it, at the run-time-parameter shapes and when batch * n_kv_heads <= 128
-     * and lambda >= 512, the step scores a stream's cached pairs on several workgroups instead of
-     * one; results are the same bit for bit with and without it). */
+     * given with LOLA_SCORE_SRE too: it is then scratch of lola_decode_step, lola_step_scratch_bytes(cfg)
+     * bytes whose contents mean nothing between calls, never read before written, not touched by
+     * lola_state_init.  With it, at the run-time-parameter shapes and with few streams (batch *
+     * n_kv_heads <= 128 for the update at lambda >= 512, <= 85 for the outputs at 512 keys or more), the
+     * step spreads a stream's work over several workgroups: the cached pairs' scores (same bits as
+     * without it) and the outputs' sums over the keys (same result up to the order of the fp32 sums). */
     float *win_score;    /* [B, Hkv, eta]     sum gathered so far by the pair in each ring slot */
     float *sp_score;     /* [B, Hkv, lambda]  final sum of the pair in each sparse slot */
 } lola_state;
@@ -127,6 +128,10 @@ typedef struct {
  * option that is off are 0); returns their sum, or 0 if the configuration is invalid or
  * unsupported. */
 size_t lola_state_bytes(const lola_config *cfg, size_t field_bytes[14]);
+
+/* Bytes of the optional scratch of lola_decode_step (lola_state.sp_score with LOLA_SCORE_SRE, see there);
+ * 0 if the configuration is invalid or the step has no use for one. */
+size_t lola_step_scratch_bytes(const lola_config *cfg);
 
 /* Workspace of lola_prefill for T tokens: returns the size with which all chunks are processed in
  * one pass; *min_bytes (host, may be NULL) receives the smallest size accepted (the chunks are then

@@ -20,7 +20,7 @@ LOLA_HIDE_STATE, LOLA_HIDE_SPARSE = 1, 2
 LOLA_SCORE_SRE, LOLA_SCORE_WERR_SQ, LOLA_SCORE_WERR_ABS, LOLA_SCORE_OVEREST, LOLA_SCORE_ATTN = 0, 1, 2, 3, 4
 EXPORTS = ("lola_state_bytes", "lola_prefill_workspace_bytes", "lola_state_init", "lola_state_flush", "lola_prefill",
            "lola_decode_step", "lola_status_str", "lola_kernel_path", "lola_release_streams", "lola_prefill_noalloc",
-           "lola_noalloc_scratch_bytes")
+           "lola_noalloc_scratch_bytes", "lola_step_scratch_bytes")
 
 
 class LolaConfig(C.Structure):
@@ -54,6 +54,8 @@ def lib() -> C.CDLL:
         cfgp, stp = C.POINTER(LolaConfig), C.POINTER(LolaState)
         L.lola_state_bytes.restype = sz
         L.lola_state_bytes.argtypes = [cfgp, C.POINTER(sz)]
+        L.lola_step_scratch_bytes.restype = sz
+        L.lola_step_scratch_bytes.argtypes = [cfgp]
         L.lola_prefill_workspace_bytes.restype = sz
         L.lola_prefill_workspace_bytes.argtypes = [cfgp, i32, i32, C.POINTER(sz)]
         L.lola_state_init.restype = C.c_int
@@ -95,6 +97,10 @@ def lola_state_bytes(cfg: LolaConfig):
     fb = (C.c_size_t * 14)()
     tot = lib().lola_state_bytes(C.byref(cfg), fb)
     return int(tot), [int(x) for x in fb]
+
+
+def lola_step_scratch_bytes(cfg: LolaConfig) -> int:
+    return int(lib().lola_step_scratch_bytes(C.byref(cfg)))
 
 
 def lola_prefill_workspace_bytes(cfg: LolaConfig, T: int, with_outputs: bool = True):
@@ -177,8 +183,9 @@ class LolaLayer:
         self.st = LolaState(*[t.data_ptr() if t.numel() else None for t in fields])
         # optional scratch of the generation step when the scores are self-recall errors (see lola.h, sp_score)
         self.step_scratch = None
-        if step_scratch and not sk and lam > 0:
-            self.step_scratch = torch.empty((B, Hkv, lam), dtype=torch.float32, device=dev)
+        nscr = lola_step_scratch_bytes(self.cfg)
+        if step_scratch and nscr:
+            self.step_scratch = torch.empty((nscr // 4,), dtype=torch.float32, device=dev)
             self.st.sp_score = self.step_scratch.data_ptr()
         self.workspace = None
         with torch.cuda.device(self.device):

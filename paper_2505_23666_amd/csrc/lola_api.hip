@@ -46,6 +46,15 @@ bool wide_decode_ok(const lola_config *c) {
     return wide_step_out_ok(c) && c->sparse_budget >= 64 && c->sparse_budget % 64 == 0 && c->sparse_budget <= fast::STEP_UPDATE_LAMMAX;
 }
 
+// Floats per stream of the generation step's optional scratch: the cached pairs' scores, later the output kernel's
+// shares (both launches of a step use it one after the other).
+size_t step_scratch_floats(const lola_config *c) {
+    if (c->score_kind != LOLA_SCORE_SRE || !wide_step_out_ok(c)) return 0;
+    const int G = c->n_q_heads / c->n_kv_heads <= 4 ? 4 : 8;
+    const size_t shares = (size_t)fast::STEP_OUT_PARTS_MAX * (G * c->head_dim + 2 * G);
+    return std::max(shares, (size_t)c->sparse_budget);
+}
+
 lola_status check_config(const lola_config *c) {
     if (!c) return LOLA_ERR_NULL;
     if (c->dtype != LOLA_F32 && c->dtype != LOLA_BF16) return LOLA_ERR_DTYPE;
@@ -292,6 +301,7 @@ lola_status run_decode(const lola_config *c, const lola_state *st, const void *q
             fast::StepUpdateArgs ua;
             ua.st = a.st; ua.k = a.k; ua.v = a.v; ua.Wk = a.Wk;
             ua.Hkv = a.dm.Hkv; ua.lam = a.dm.lam; ua.eta = a.dm.eta; ua.phi_kind = a.dm.phi_kind;
+            ua.scr_stride = (int)step_scratch_floats(c);
             // Few streams and several passes over the cached pairs: the scoring is split over `parts` workgroups per
             // stream (each at least one pass of 256 pairs, all of them resident at once), a second launch does the rest.
             // The scores travel through sp_score, which a self-recall-error state may carry as scratch.
@@ -332,7 +342,20 @@ lola_status run_decode(const lola_config *c, const lola_state *st, const void *q
                 oa.st = a.st; oa.q = a.q; oa.Wq = a.Wq; oa.Wk = a.Wk; oa.out = (TO *)out; oa.score_kind = a.dm.score_kind;
                 oa.Hq = a.dm.Hq; oa.Hkv = a.dm.Hkv; oa.g = a.dm.g; oa.lam = a.dm.lam; oa.eta = a.dm.eta;
                 oa.phi_kind = a.dm.phi_kind; oa.hide = a.dm.hide; oa.scale = a.dm.scale;
-#define LOLA_OUT(DHV, DFV) do { if (oa.g <= 4) hipLaunchKernelGGL((fast::step_out_wide_kernel<DHV, DFV, TO, 4>), grid, dim3(256), 0, stream, oa); \
+                // Few streams: the keys in shares of at least 8 blocks of 32 on workgroups of their own, the linear part
+                // on another, a small launch adds the shares up (they pass through the state's optional scratch).
+                const int ns = a.dm.B * a.dm.Hkv, nblk = (a.dm.lam + a.dm.eta + 31) / 32;
+                int kparts = 0;
+                if (!a.dm.score_kind && st->sp_score && 3 * ns <= 256 && nblk >= 16)
+                    kparts = std::min(std::min(fast::STEP_OUT_PARTS_MAX - 1, 256 / ns - 1), nblk / 8);
+                oa.part = st->sp_score; oa.part_stride = (int)step_scratch_floats(c);
+                const dim3 gridp(ns, kparts + 1);
+                const int Gv = oa.g <= 4 ? 4 : 8;
+#define LOLA_OUT(DHV, DFV) do { if (kparts >= 2) { \
+                                    if (oa.g <= 4) hipLaunchKernelGGL((fast::step_out_wide_kernel<DHV, DFV, TO, 4, true>), gridp, dim3(256), 0, stream, oa); \
+                                    else hipLaunchKernelGGL((fast::step_out_wide_kernel<DHV, DFV, TO, 8, true>), gridp, dim3(256), 0, stream, oa); \
+                                    hipLaunchKernelGGL((fast::step_out_combine_kernel<TO>), grid, dim3(256), 0, stream, oa, Gv, DHV, kparts + 1); } \
+                                else if (oa.g <= 4) hipLaunchKernelGGL((fast::step_out_wide_kernel<DHV, DFV, TO, 4>), grid, dim3(256), 0, stream, oa); \
                                 else hipLaunchKernelGGL((fast::step_out_wide_kernel<DHV, DFV, TO, 8>), grid, dim3(256), 0, stream, oa); } while (0)
                 if (c->head_dim == 128) { if (c->feat_dim == 256) LOLA_OUT(128, 256); else LOLA_OUT(128, 128); }
                 else { if (c->feat_dim == 256) LOLA_OUT(64, 256); else LOLA_OUT(64, 128); }
@@ -717,6 +740,11 @@ lola_status run_prefill(const lola_config *c, const lola_state *st, const void *
 }  // namespace
 
 extern "C" {
+
+size_t lola_step_scratch_bytes(const lola_config *c) {
+    if (check_config(c) != LOLA_OK) return 0;
+    return step_scratch_floats(c) * (size_t)c->batch * c->n_kv_heads * sizeof(float);
+}
 
 size_t lola_state_bytes(const lola_config *c, size_t fb[14]) {
     if (check_config(c) != LOLA_OK) return 0;

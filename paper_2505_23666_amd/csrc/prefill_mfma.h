@@ -1782,14 +1782,21 @@ struct StepOutArgs {
     TO *out;
     int Hq, Hkv, g, lam, eta, phi_kind, hide, score_kind;
     float scale;
+    float *part;          // SPLIT: partial results [stream][part][G * DH + 2 * G] (scratch)
+    int part_stride;      // floats per stream in `part`
 };
 
 constexpr int STEP_OUT_NKMAX = 3072;
+constexpr int STEP_OUT_PARTS_MAX = 8;
 
 // G = 4 or 8: query rows the kernel is built for (query heads per kv head <= G); the logits of all of them stay in
 // LDS, so the key limit is STEP_OUT_NKMAX * 4 / G.  Lane (column, group g4) of an MFMA result holds rows 4 g4 + i: the
 // queries sit in the lane groups g4 < G / 4.
-template <int DH, int DF, typename TO, int G>
+// SPLIT (few streams: one workgroup per stream is bounded by its compute unit's share of the memory system): grid
+// (streams, parts); part 0 computes the linear part (sections 2 and 5) and no keys, parts 1 .. take the key blocks of 32
+// in equal shares; each leaves (sum w v, m, sum w) of its share in `part` - the linear part as a share with m = 0 - and
+// step_out_combine_kernel adds the shares up under the common maximum.
+template <int DH, int DF, typename TO, int G, bool SPLIT = false>
 __global__ __launch_bounds__(256) void step_out_wide_kernel(StepOutArgs<TO> a) {
     constexpr int M = DF / 2, KS = DH / 32, NZT = M / 16, KF = DF / 32, NCT = DH / 16, PR = DH / 8, NKMAX = STEP_OUT_NKMAX * 4 / G;
     static_assert(G == 4 || G == 8, "query rows");
@@ -1805,6 +1812,11 @@ __global__ __launch_bounds__(256) void step_out_wide_kernel(StepOutArgs<TO> a) {
     const int64_t tok = a.st.n_tokens[si];                    // tokens consumed, this step's included
     const int spc = a.st.sp_count[si];
     const int wn = (int)min((int64_t)ETA, tok), nk = spc + wn, KPAD = (nk + 31) & ~31;
+    // this workgroup's key blocks of 32: [kb0, kb1)
+    const int prt = SPLIT ? blockIdx.y : 0, nkp = SPLIT ? gridDim.y - 1 : 1;
+    const int kb0 = !SPLIT ? 0 : prt == 0 ? 0 : (int)((int64_t)(KPAD / 32) * (prt - 1) / nkp);
+    const int kb1 = !SPLIT ? KPAD / 32 : prt == 0 ? 0 : (int)((int64_t)(KPAD / 32) * prt / nkp);
+    const bool linear = !SPLIT || prt == 0;
     const bf16_t *sp_k = a.st.sp_k + (size_t)si * LAM * DH, *sp_v = a.st.sp_v + (size_t)si * LAM * DH;
     const bf16_t *win_k = a.st.win_k + (size_t)si * ETA * DH, *win_v = a.st.win_v + (size_t)si * ETA * DH;
     const float *Hg = a.st.H + (size_t)si * DF * DH, *sg = a.st.s + (size_t)si * DF;
@@ -1822,7 +1834,7 @@ __global__ __launch_bounds__(256) void step_out_wide_kernel(StepOutArgs<TO> a) {
         // four key tiles per pass, their rows requested together: one tile at a time, every tile cost a round trip
         constexpr int UT = 4;
 #pragma unroll 1
-        for (int t0 = w; t0 < KPAD / 16; t0 += 4 * UT) {
+        for (int t0 = 2 * kb0 + w; t0 < 2 * kb1; t0 += 4 * UT) {
             bf16x8 KB[UT][KS];
 #pragma unroll
             for (int u = 0; u < UT; u++) {
@@ -1835,7 +1847,7 @@ __global__ __launch_bounds__(256) void step_out_wide_kernel(StepOutArgs<TO> a) {
 #pragma unroll
             for (int u = 0; u < UT; u++) {
                 const int t = t0 + 4 * u, key = 16 * t + r16;
-                if (t < KPAD / 16) {
+                if (t < 2 * kb1) {
                     const bool valid = key < nk;
                     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -1851,7 +1863,7 @@ __global__ __launch_bounds__(256) void step_out_wide_kernel(StepOutArgs<TO> a) {
     }
     // ---- 2. phi of queries w, w + 4, ... (Sec. 2.3 eq. feature_map) and phi(q).s
 #pragma unroll 1
-    for (int qi = w; qi < g; qi += 4) {
+    for (int qi = w; qi < (linear ? g : 0); qi += 4) {
         const bf16_t *Wq = a.Wq + ((size_t)h * g + qi) * M * DH;
         bf16x8 BQ[KS];
 #pragma unroll
@@ -1958,17 +1970,22 @@ __global__ __launch_bounds__(256) void step_out_wide_kernel(StepOutArgs<TO> a) {
             lds_dma16(vr + ((slot ^ vswz2<PR>(row)) << 3), &VS[w][buf][512 * i]);   // (inline assembly: the reads of the other buffer below do not wait for it)
         }
     };
-    const int nblk = KPAD / 32;
-    if (w < nblk) stage(w, 0);
+    if (kb0 + w < kb1) stage(kb0 + w, 0);
     // and so are this wavefront's rows of H^T for section 5 (one wavefront per SIMD has the registers to hold them)
     float4 hv[NCT / 4][KF][2];
 #pragma unroll
-    for (int x = 0; x < NCT / 4; x++) {
-        const float *hrow = Hg + (size_t)(16 * (w + 4 * x) + r16) * DF + 4 * g4;
+    for (int x = 0; x < NCT / 4; x++)
 #pragma unroll
-        for (int ks = 0; ks < KF; ks++) {
-            hv[x][ks][0] = *reinterpret_cast<const float4 *>(hrow + 32 * ks);
-            hv[x][ks][1] = *reinterpret_cast<const float4 *>(hrow + 32 * ks + 16);
+        for (int ks = 0; ks < KF; ks++) hv[x][ks][0] = hv[x][ks][1] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (linear) {
+#pragma unroll
+        for (int x = 0; x < NCT / 4; x++) {
+            const float *hrow = Hg + (size_t)(16 * (w + 4 * x) + r16) * DF + 4 * g4;
+#pragma unroll
+            for (int ks = 0; ks < KF; ks++) {
+                hv[x][ks][0] = *reinterpret_cast<const float4 *>(hrow + 32 * ks);
+                hv[x][ks][1] = *reinterpret_cast<const float4 *>(hrow + 32 * ks + 16);
+            }
         }
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -1976,13 +1993,13 @@ __global__ __launch_bounds__(256) void step_out_wide_kernel(StepOutArgs<TO> a) {
 #pragma unroll 1
     for (int qi = w; qi < g; qi += 4) {
         float mx = 0.f;
-        for (int x = lane; x < KPAD / 4; x += 64) {
+        for (int x = 8 * kb0 + lane; x < 8 * kb1; x += 64) {
             const float4 l4 = reinterpret_cast<const float4 *>(lg[qi])[x];
             mx = fmaxf(mx, fmaxf(fmaxf(l4.x, l4.y), fmaxf(l4.z, l4.w)));
         }
         mx = wmax(mx);
         float ps = 0.f;
-        for (int x = lane; x < KPAD / 4; x += 64) {
+        for (int x = 8 * kb0 + lane; x < 8 * kb1; x += 64) {
             const float4 l4 = reinterpret_cast<const float4 *>(lg[qi])[x];
             const float p[4] = {fexp2((l4.x - mx) * LOG2E), fexp2((l4.y - mx) * LOG2E), fexp2((l4.z - mx) * LOG2E), fexp2((l4.w - mx) * LOG2E)};
             uint32_t hi[2], lo[2];
@@ -2010,10 +2027,10 @@ __global__ __launch_bounds__(256) void step_out_wide_kernel(StepOutArgs<TO> a) {
         for (int ct = 0; ct < NCT; ct++) acc[ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
         int buf = 0;
 #pragma unroll 1
-        for (int kb = w; kb < nblk; kb += 4) {
+        for (int kb = kb0 + w; kb < kb1; kb += 4) {
             __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the block has landed (only this wavefront reads it)
             asm volatile("" ::: "memory");
-            if (kb + 4 < nblk) stage(kb + 4, buf ^ 1);
+            if (kb + 4 < kb1) stage(kb + 4, buf ^ 1);
             bf16x8 Ahi = zero_bf16x8(), Alo = zero_bf16x8();
             if (r16 < g) {
                 const uint4 u0 = reinterpret_cast<const uint4 *>(lg[r16])[8 * kb + g4], u1 = reinterpret_cast<const uint4 *>(lg[r16])[8 * kb + 4 + g4];
@@ -2040,7 +2057,7 @@ __global__ __launch_bounds__(256) void step_out_wide_kernel(StepOutArgs<TO> a) {
         }
     }
     // ---- 5. phi(q)^T H: column tiles w, w + 4, ...; A = phi(q) (rows = queries), B = 16 rows of H^T
-    {
+    if (linear) {
         bf16x8 Ahi[KF], Alo[KF];
 #pragma unroll
         for (int ks = 0; ks < KF; ks++) {
@@ -2069,12 +2086,46 @@ __global__ __launch_bounds__(256) void step_out_wide_kernel(StepOutArgs<TO> a) {
     }
     __syncthreads();
     // ---- 6. outputs
+    if (SPLIT) {   // this part's share: numerators, then (m, sum of weights) per query; part 0: the linear part, m = 0
+        float *ps = a.part + (size_t)si * a.part_stride + (size_t)prt * (G * DH + 2 * G);
+        const float elin = (a.hide & 1) ? 0.f : 1.f;   // restricted query: the hidden state is not read
+        for (int o = tid; o < g * DH; o += 256) {
+            const int qi = o / DH, c = o - qi * DH;
+            ps[o] = linear ? elin * lin_l[qi][c] : (outp[0][qi][c] + outp[1][qi][c]) + (outp[2][qi][c] + outp[3][qi][c]);
+        }
+        if (tid < g) {
+            ps[G * DH + 2 * tid] = linear ? 0.f : m_l[tid];
+            ps[G * DH + 2 * tid + 1] = linear ? elin * denq_l[tid] : psum_l[tid];
+        }
+        return;
+    }
     for (int o = tid; o < g * DH; o += 256) {
         const int qi = o / DH, c = o - qi * DH;
         const float elin = (a.hide & 1) ? 0.f : fexp2(-m_l[qi] * LOG2E);   // restricted query: the hidden state is not read
         const float num = (outp[0][qi][c] + outp[1][qi][c]) + (outp[2][qi][c] + outp[3][qi][c]) + elin * lin_l[qi][c];
         const float val = num / (psum_l[qi] + elin * denq_l[qi]);
         stf(a.out, ((size_t)b * a.Hq + (size_t)h * g + qi) * DH + c, val);
+    }
+}
+
+// Sum of the shares left by step_out_wide_kernel<..., SPLIT> (softmax part per key range and the linear part; Sec. 3.1
+// eq. lola_output with the shared normaliser): with M = max over the shares' m,
+// y = sum_p e^(m_p - M) num_p / sum_p e^(m_p - M) den_p.  One workgroup per stream, one thread per (query, column).
+template <typename TO>
+__global__ __launch_bounds__(256) void step_out_combine_kernel(StepOutArgs<TO> a, int G, int DH, int nparts) {
+    const int si = blockIdx.x, b = si / a.Hkv, h = si - b * a.Hkv, g = a.g, PS = G * DH + 2 * G;
+    const float *ps = a.part + (size_t)si * a.part_stride;
+    for (int o = threadIdx.x; o < g * DH; o += 256) {
+        const int qi = o / DH;
+        float mx = 0.f;
+        for (int p = 0; p < nparts; p++) mx = fmaxf(mx, ps[(size_t)p * PS + G * DH + 2 * qi]);
+        float num = 0.f, den = 0.f;
+        for (int p = 0; p < nparts; p++) {
+            const float sc = fexp2((ps[(size_t)p * PS + G * DH + 2 * qi] - mx) * LOG2E);
+            num = fmaf(sc, ps[(size_t)p * PS + o], num);
+            den = fmaf(sc, ps[(size_t)p * PS + G * DH + 2 * qi + 1], den);
+        }
+        stf(a.out, ((size_t)b * a.Hq + (size_t)h * g + qi) * DH + o - qi * DH, num / den);
     }
 }
 
@@ -2098,6 +2149,7 @@ struct StepUpdateArgs {
     State<bf16_t> st;
     const bf16_t *k, *v, *Wk;
     int Hkv, lam, eta, phi_kind;
+    int scr_stride;       // split forms: floats per stream in the scratch (sp_score)
 };
 
 constexpr int STEP_UPDATE_LAMMAX = 2048;
@@ -2174,7 +2226,7 @@ __global__ __launch_bounds__(512) void step_update_wide_kernel(StepUpdateArgs a)
         for (int e = tid; e < LAM; e += 512) score[e] = sps[e];
         if (tid == 0) score[LAM] = wsc[0];
     }
-    float *scr = MODE ? a.st.sp_score + (size_t)si * LAM : nullptr;   // split forms: the cached pairs' scores
+    float *scr = MODE ? a.st.sp_score + (size_t)si * a.scr_stride : nullptr;   // split forms: the cached pairs' scores
     if (MODE == 2)
         for (int e = tid; e < LAM; e += 512) score[e] = scr[e];
     if (!SCORED && MODE != 1 && w < NZT) {   // (every column of the tile holds the same key: column 0 stores)

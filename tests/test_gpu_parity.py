@@ -563,8 +563,10 @@ def test_paper_scale_cache_parameters(eta, lam, chunk):
 def test_generation_step_scoring_split_over_workgroups(d, D, eta, lam, B, Hkv):
     """With few streams and a sparse budget of 512 or more the generation step at the run-time shapes scores a stream's
     cached pairs on several workgroups (the scores pass through the optional scratch in the state) and a second launch
-    selects and folds.  Same prefill, then generation steps on a layer with the scratch and on one without it (one
-    workgroup per stream does everything): outputs and every memory equal bit for bit at every step.  (The split form
+    selects and folds; the output kernel likewise takes the keys in shares on several workgroups and a small launch adds
+    the shares up.  Same prefill, then generation steps on a layer with the scratch and on one without it (one
+    workgroup per stream does everything): every memory equal bit for bit at every step, the outputs equal up to the
+    order of the fp32 sums.  (The split form
     is the one the paper-scale cases compare with the oracle.)  With 4 streams every wavefront of the score part takes
     single tiles of 16 pairs; with 64 streams there are not enough compute units for that and it takes pairs of tiles."""
     Hq = 2 * Hkv
@@ -582,7 +584,8 @@ def test_generation_step_scoring_split_over_workgroups(d, D, eta, lam, B, Hkv):
         sq, sk_, sv = (P.to_dev(np.ascontiguousarray(x[:, :, T + i]), "bf16") for x in (q, k, v))
         outs = [lay.decode_step(sq, sk_, sv, dWq, dWk) for lay in lays]
         torch.cuda.synchronize()
-        assert torch.equal(outs[0], outs[1]), i
+        # (the outputs' sums over the keys are taken in shares with the scratch: same result up to the order of the fp32 sums)
+        assert torch.allclose(outs[0], outs[1], rtol=1e-5, atol=2e-6), (i, float((outs[0] - outs[1]).abs().max()))
         for name in ("H", "s", "win_k", "win_v", "sp_k", "sp_v", "sp_idx", "sp_count", "n_tokens"):
             assert torch.equal(getattr(lays[0], name), getattr(lays[1], name)), (i, name)
     say("generation step, scoring split over workgroups", d, D, eta, lam, "equal over", nd, "steps")
