@@ -2117,14 +2117,27 @@ __global__ __launch_bounds__(256) void step_out_combine_kernel(StepOutArgs<TO> a
     const float *ps = a.part + (size_t)si * a.part_stride;
     for (int o = threadIdx.x; o < g * DH; o += 256) {
         const int qi = o / DH;
-        float mx = 0.f;
-        for (int p = 0; p < nparts; p++) mx = fmaxf(mx, ps[(size_t)p * PS + G * DH + 2 * qi]);
-        float num = 0.f, den = 0.f;
-        for (int p = 0; p < nparts; p++) {
-            const float sc = fexp2((ps[(size_t)p * PS + G * DH + 2 * qi] - mx) * LOG2E);
-            num = fmaf(sc, ps[(size_t)p * PS + o], num);
-            den = fmaf(sc, ps[(size_t)p * PS + G * DH + 2 * qi + 1], den);
+        // (all shares requested before the first is used: one round trip instead of one per share)
+        float mp[STEP_OUT_PARTS_MAX], lp[STEP_OUT_PARTS_MAX], vp[STEP_OUT_PARTS_MAX];
+#pragma unroll
+        for (int p = 0; p < STEP_OUT_PARTS_MAX; p++) {
+            const int pc = p < nparts ? p : 0;
+            mp[p] = ps[(size_t)pc * PS + G * DH + 2 * qi];
+            lp[p] = ps[(size_t)pc * PS + G * DH + 2 * qi + 1];
+            vp[p] = ps[(size_t)pc * PS + o];
         }
+        float mx = 0.f;
+#pragma unroll
+        for (int p = 0; p < STEP_OUT_PARTS_MAX; p++)
+            if (p < nparts) mx = fmaxf(mx, mp[p]);
+        float num = 0.f, den = 0.f;
+#pragma unroll
+        for (int p = 0; p < STEP_OUT_PARTS_MAX; p++)
+            if (p < nparts) {
+                const float sc = fexp2((mp[p] - mx) * LOG2E);
+                num = fmaf(sc, vp[p], num);
+                den = fmaf(sc, lp[p], den);
+            }
         stf(a.out, ((size_t)b * a.Hq + (size_t)h * g + qi) * DH + o - qi * DH, num / den);
     }
 }
