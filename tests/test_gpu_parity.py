@@ -558,6 +558,23 @@ def test_paper_scale_cache_parameters(eta, lam, chunk):
     assert rep["scored"] >= 5 and rep2["scored"] - rep["scored"] == 3
 
 
+def test_run_time_shape_decode_from_cold_start_with_the_work_in_shares():
+    """Generation steps from empty memories at a run-time shape with few streams and the optional scratch: the output
+    kernel takes the keys in shares from the first step on (one key, then ragged shares, most of them empty at first),
+    the update's split forms leave the streams alone while window and cache fill (the shape-generic step takes them),
+    then score in shares once the cache is full; every step against the oracle."""
+    eta, lam = 64, 512
+    sh = wl.Shape("coldwide", "bf16", 1, 4, 2, 128, 256, T=0, eta=eta, lam=lam, C=64, seed=0)
+    n = eta + lam + 12
+    q, k, v, Wq, Wk = rand_case(77, 1, 4, 2, 128, 256, n, "bf16")
+    layer = P.make_layer(sh)
+    assert layer.step_scratch is not None
+    o = P.make_oracle(sh)
+    rep = P.decode_parity(sh, layer, o, *steps(q, k, v, 0, n), Wq, Wk)
+    say("run-time shape cold decode, work in shares", rep)
+    assert rep["scored"] == 2 * 12
+
+
 @pytest.mark.parametrize("d,D,eta,lam,B,Hkv", [(128, 256, 128, 768, 2, 2), (64, 256, 64, 512, 2, 2), (128, 128, 64, 1024, 2, 2),
                                                (64, 128, 128, 512, 2, 2), (128, 128, 64, 768, 16, 4), (128, 256, 64, 512, 8, 8)])
 def test_generation_step_scoring_split_over_workgroups(d, D, eta, lam, B, Hkv):
