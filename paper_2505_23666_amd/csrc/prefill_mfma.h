@@ -2211,7 +2211,7 @@ __global__ __launch_bounds__(512) void step_update_wide_kernel(StepUpdateArgs a)
             hreg[i][1] = *reinterpret_cast<const float4 *>(hp + 16);
         }
     };
-    load_state();
+    if (MODE != 2) load_state();   // (MODE 2 needs the state only behind the first barrier: requested there)
     int32_t *sp_idx = a.st.sp_idx + (size_t)si * LAM;
     for (int x = tid; x < DF; x += 512) s_l[x] = sg[x];
     for (int e = tid; e < LAM; e += 512) idx_l[e] = sp_idx[e];
@@ -2258,7 +2258,14 @@ __global__ __launch_bounds__(512) void step_update_wide_kernel(StepUpdateArgs a)
         HA[((w + 8 * i) * 2 + 1) * 64 + lane] = __builtin_bit_cast(uint4, lo);
     }
     }
-    __syncthreads();
+    if (MODE == 2) {
+        // the state travels while the leaving pair's features are made: requested behind the small loads (whose waits
+        // would otherwise cover it) and not waited for by this barrier
+        load_state();
+        lds_barrier();
+    } else {
+        __syncthreads();
+    }
 
     // W_k as wavefront 0 will need it for the features of the folded pair: requested before the arg-min is known, so
     // that only the pair's key is waited for afterwards
