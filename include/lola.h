@@ -117,9 +117,10 @@ typedef struct {
      * given with LOLA_SCORE_SRE too: it is then scratch of lola_decode_step, lola_step_scratch_bytes(cfg)
      * bytes whose contents mean nothing between calls, never read before written, not touched by
      * lola_state_init.  With it, at the run-time-parameter shapes and with few streams (batch *
-     * n_kv_heads <= 128 for the update at lambda >= 512, <= 85 for the outputs at 512 keys or more), the
+     * n_kv_heads <= 128 for the update at lambda >= 512, <= 85 for the outputs at window + lambda > 480), the
      * step spreads a stream's work over several workgroups: the cached pairs' scores (same bits as
-     * without it) and the outputs' sums over the keys (same result up to the order of the fp32 sums). */
+     * without it) and the outputs' sums over the keys (same result up to the order of the fp32 sums).
+     * Calls on states that share one scratch must not overlap. */
     float *win_score;    /* [B, Hkv, eta]     sum gathered so far by the pair in each ring slot */
     float *sp_score;     /* [B, Hkv, lambda]  final sum of the pair in each sparse slot */
 } lola_state;
