@@ -345,16 +345,21 @@ lola_status run_decode(const lola_config *c, const lola_state *st, const void *q
                 // Few streams: the keys in shares of at least 8 blocks of 32 on workgroups of their own, the linear part
                 // on another, a small launch adds the shares up (they pass through the state's optional scratch).
                 const int ns = a.dm.B * a.dm.Hkv, nblk = (a.dm.lam + a.dm.eta + 31) / 32;
-                int kparts = 0;
-                if (!a.dm.score_kind && st->sp_score && 3 * ns <= 256 && nblk >= 16)
-                    kparts = std::min(std::min(fast::STEP_OUT_PARTS_MAX - 1, 256 / ns - 1), nblk / 8);
-                oa.part = st->sp_score; oa.part_stride = (int)step_scratch_floats(c);
-                const dim3 gridp(ns, kparts + 1);
+                // The linear part reads W_q per query head and all of H^T: one workgroup per query head where the compute
+                // units suffice for that and two shares of keys, else one workgroup for all heads.
+                int kparts = 0, nlin = 1;
+                if (!a.dm.score_kind && st->sp_score && 3 * ns <= 256 && nblk >= 16) {
+                    const int total = std::min(fast::STEP_OUT_PARTS_MAX, 256 / ns);
+                    if (total - a.dm.g >= 2) nlin = a.dm.g;
+                    kparts = std::min(total - nlin, nblk / 8);
+                }
+                oa.part = st->sp_score; oa.part_stride = (int)step_scratch_floats(c); oa.nlin = nlin;
+                const dim3 gridp(ns, kparts + nlin);
                 const int Gv = oa.g <= 4 ? 4 : 8;
 #define LOLA_OUT(DHV, DFV) do { if (kparts >= 2) { \
                                     if (oa.g <= 4) hipLaunchKernelGGL((fast::step_out_wide_kernel<DHV, DFV, TO, 4, true>), gridp, dim3(256), 0, stream, oa); \
                                     else hipLaunchKernelGGL((fast::step_out_wide_kernel<DHV, DFV, TO, 8, true>), gridp, dim3(256), 0, stream, oa); \
-                                    hipLaunchKernelGGL((fast::step_out_combine_kernel<TO>), grid, dim3(256), 0, stream, oa, Gv, DHV, kparts + 1); } \
+                                    hipLaunchKernelGGL((fast::step_out_combine_kernel<TO>), grid, dim3(256), 0, stream, oa, Gv, DHV, kparts + nlin); } \
                                 else if (oa.g <= 4) hipLaunchKernelGGL((fast::step_out_wide_kernel<DHV, DFV, TO, 4>), grid, dim3(256), 0, stream, oa); \
                                 else hipLaunchKernelGGL((fast::step_out_wide_kernel<DHV, DFV, TO, 8>), grid, dim3(256), 0, stream, oa); } while (0)
                 if (c->head_dim == 128) { if (c->feat_dim == 256) LOLA_OUT(128, 256); else LOLA_OUT(128, 128); }

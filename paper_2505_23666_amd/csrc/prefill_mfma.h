@@ -1784,18 +1784,20 @@ struct StepOutArgs {
     float scale;
     float *part;          // SPLIT: partial results [stream][part][G * DH + 2 * G] (scratch)
     int part_stride;      // floats per stream in `part`
+    int nlin;             // SPLIT: parts that take the linear part (1: all query heads; g: one query head each)
 };
 
 constexpr int STEP_OUT_NKMAX = 3072;
-constexpr int STEP_OUT_PARTS_MAX = 8;
+constexpr int STEP_OUT_PARTS_MAX = 16;
 
 // G = 4 or 8: query rows the kernel is built for (query heads per kv head <= G); the logits of all of them stay in
 // LDS, so the key limit is STEP_OUT_NKMAX * 4 / G.  Lane (column, group g4) of an MFMA result holds rows 4 g4 + i: the
 // queries sit in the lane groups g4 < G / 4.
 // SPLIT (few streams: one workgroup per stream is bounded by its compute unit's share of the memory system): grid
-// (streams, parts); part 0 computes the linear part (sections 2 and 5) and no keys, parts 1 .. take the key blocks of 32
-// in equal shares; each leaves (sum w v, m, sum w) of its share in `part` - the linear part as a share with m = 0 - and
-// step_out_combine_kernel adds the shares up under the common maximum.
+// (streams, parts); the first nlin parts compute the linear part (sections 2 and 5: of all query heads, or of query head
+// `part` each - W_q is read per head, H^T by all of them) and no keys, the others take the key blocks of 32 in equal
+// shares; each leaves (sum w v, m, sum w) of its share in `part` - the linear part as a share with m = 0, rows of other
+// heads zero - and step_out_combine_kernel adds the shares up under the common maximum.
 template <int DH, int DF, typename TO, int G, bool SPLIT = false>
 __global__ __launch_bounds__(256) void step_out_wide_kernel(StepOutArgs<TO> a) {
     constexpr int M = DF / 2, KS = DH / 32, NZT = M / 16, KF = DF / 32, NCT = DH / 16, PR = DH / 8, NKMAX = STEP_OUT_NKMAX * 4 / G;
@@ -1813,10 +1815,12 @@ __global__ __launch_bounds__(256) void step_out_wide_kernel(StepOutArgs<TO> a) {
     const int spc = a.st.sp_count[si];
     const int wn = (int)min((int64_t)ETA, tok), nk = spc + wn, KPAD = (nk + 31) & ~31;
     // this workgroup's key blocks of 32: [kb0, kb1)
-    const int prt = SPLIT ? blockIdx.y : 0, nkp = SPLIT ? gridDim.y - 1 : 1;
-    const int kb0 = !SPLIT ? 0 : prt == 0 ? 0 : (int)((int64_t)(KPAD / 32) * (prt - 1) / nkp);
-    const int kb1 = !SPLIT ? KPAD / 32 : prt == 0 ? 0 : (int)((int64_t)(KPAD / 32) * prt / nkp);
-    const bool linear = !SPLIT || prt == 0;
+    const int prt = SPLIT ? blockIdx.y : 0, nlin = SPLIT ? a.nlin : 1, nkp = SPLIT ? gridDim.y - nlin : 1;
+    const bool linear = !SPLIT || prt < nlin;
+    const int kb0 = !SPLIT ? 0 : linear ? 0 : (int)((int64_t)(KPAD / 32) * (prt - nlin) / nkp);
+    const int kb1 = !SPLIT ? KPAD / 32 : linear ? 0 : (int)((int64_t)(KPAD / 32) * (prt - nlin + 1) / nkp);
+    // query heads whose features this workgroup makes: [q0, q1), dealt to the wavefronts from q0 on
+    const int q0 = SPLIT && nlin > 1 ? prt : 0, q1 = !linear ? 0 : SPLIT && nlin > 1 ? prt + 1 : g;
     const bf16_t *sp_k = a.st.sp_k + (size_t)si * LAM * DH, *sp_v = a.st.sp_v + (size_t)si * LAM * DH;
     const bf16_t *win_k = a.st.win_k + (size_t)si * ETA * DH, *win_v = a.st.win_v + (size_t)si * ETA * DH;
     const float *Hg = a.st.H + (size_t)si * DF * DH, *sg = a.st.s + (size_t)si * DF;
@@ -1863,7 +1867,7 @@ __global__ __launch_bounds__(256) void step_out_wide_kernel(StepOutArgs<TO> a) {
     }
     // ---- 2. phi of queries w, w + 4, ... (Sec. 2.3 eq. feature_map) and phi(q).s
 #pragma unroll 1
-    for (int qi = w; qi < (linear ? g : 0); qi += 4) {
+    for (int qi = q0 + w; qi < q1; qi += 4) {
         const bf16_t *Wq = a.Wq + ((size_t)h * g + qi) * M * DH;
         bf16x8 BQ[KS];
 #pragma unroll

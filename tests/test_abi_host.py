@@ -38,12 +38,12 @@ def test_exports_every_declared_symbol(L):
 def test_step_scratch_bytes(L):
     """The generation step's optional scratch: none at the compile-time shapes (one fused kernel) or with
     query-dependent scores (sp_score holds the sums then); at the run-time shapes room for the cached pairs' scores and
-    for eight shares of the outputs per stream."""
+    for sixteen shares of the outputs per stream."""
     assert lb.lola_step_scratch_bytes(cfg()) == 0
     assert lb.lola_step_scratch_bytes(cfg(feat_dim=256, window=256, sparse_budget=256, score_kind=1)) == 0
-    assert lb.lola_step_scratch_bytes(cfg(feat_dim=256, window=256, sparse_budget=256)) == 4 * 8 * (4 * 128 + 8) * 4
-    assert lb.lola_step_scratch_bytes(cfg(head_dim=64, window=128, sparse_budget=2048)) == 4 * 8 * (4 * 64 + 8) * 4
-    assert lb.lola_step_scratch_bytes(cfg(head_dim=64, window=64, sparse_budget=2560)) == 4 * 2560 * 4
+    assert lb.lola_step_scratch_bytes(cfg(feat_dim=256, window=256, sparse_budget=256)) == 4 * 16 * (4 * 128 + 8) * 4
+    assert lb.lola_step_scratch_bytes(cfg(head_dim=64, window=128, sparse_budget=2048)) == 4 * 16 * (4 * 64 + 8) * 4
+    assert lb.lola_step_scratch_bytes(cfg(head_dim=64, window=64, sparse_budget=2560 + 1920)) == 0   # more keys than the output kernel takes
     assert lb.lola_step_scratch_bytes(cfg(head_dim=100)) == 0
 
 
