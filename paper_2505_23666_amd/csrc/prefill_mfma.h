@@ -20,8 +20,9 @@
 //      leaves as bf16 high + low parts in operand order (three MFMAs per product).
 //   3. keys in blocks of 128: positions [0, lambda) sparse cache (gathered by virtual row),
 //      [lambda, lambda + 64) the 64 rows before the chunk, [lambda + 64, lambda + 128) the chunk
-//      itself (causal).  Per block: K and V^T staged in LDS, S^T = K Q^T, running max (started at 0:
-//      the linear terms carry weight exp(-m)), P^T as bf16 high + low parts, out^T += V^T P^T.
+//      itself (causal).  Per block: K and V staged in LDS (both row-major), S^T = K Q^T, running max (started at 0:
+//      the linear terms carry weight exp(-m)), P^T as bf16 high + low parts, out^T += V^T P^T with V^T taken
+//      through the transposing LDS read.
 //   4. y = (out + exp(-m) lin) / (sum p + exp(-m) phi(q)^T s).
 #pragma once
 #include "decode_mfma.h"
@@ -30,9 +31,7 @@
 namespace lola {
 namespace fast {
 
-// position of feature / key index x (0..127) inside a 128-wide operand row: 16-byte chunk and element
-__device__ __forceinline__ int perm_chunk(int x) { return ((x >> 5) << 2) | ((x >> 2) & 3); }
-__device__ __forceinline__ int perm_elem(int x) { return (((x >> 4) & 1) << 2) | (x & 3); }
+template <int PR> __device__ __forceinline__ int vswz2(int row);   // (piece swizzle of row-major value tiles, defined with the other swizzles below)
 
 template <int LAM, int DH, typename TO>
 __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArgs<bf16_t> a) {
@@ -41,7 +40,7 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
     constexpr int P = LAM + ETA;                    // rows of the virtual prefix
     constexpr int NKEYS = LAM + ETA + C;            // key positions
     constexpr int NB = (NKEYS + 127) / 128;         // key blocks
-    __shared__ __attribute__((aligned(16))) uint16_t L[2 * DH * D];   // 64 KB: H^T high/low parts, then K block + V^T block
+    __shared__ __attribute__((aligned(16))) uint16_t L[2 * DH * D];   // 64 KB: H^T high/low parts, then K block + V block
     __shared__ __attribute__((aligned(16))) float s_l[D];
     __shared__ int G_l[LAM > 0 ? LAM : 1];
 
@@ -75,7 +74,7 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
     lds_barrier();
 
     // ---- softmax part over key blocks of 128 positions
-    uint16_t *Kl = L, *Vt = L + DH * 128;   // [key][input piece ^ key % pieces] and [c][key chunk ^ swz(c)]
+    uint16_t *Kl = L, *Vr = L + DH * 128;   // [key][input piece ^ key % pieces] and [key][piece ^ vswz2(key)] (read transposed)
     f32x4 out[NCT];
 #pragma unroll
     for (int mt = 0; mt < NCT; mt++) out[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -84,7 +83,7 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
 #pragma unroll 1
     for (int blk = 0; blk < NB; blk++) {
         // position -> source row (or none).  A thread handles PR / 4 items of the block, each one 16-byte piece of two
-        // neighbouring keys: the transposed values are then written as 32-bit words (two keys of one column)
+        // neighbouring keys; the values stay row-major (the value GEMM reads them through the transposing LDS read)
         // (named scalars: an array held across the barrier would be sent through scratch memory).
 #define LOLA_REP8(X) X(0) X(1) X(2) X(3)   // items beyond 64 * PR / 256 compile to nothing
 #define LOLA_KVROW(pos, vr) { vr = -1; \
@@ -107,14 +106,8 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
             const int o = tid + 256 * it, kk = 2 * (o / PR), ch = o % PR; \
             *reinterpret_cast<uint4 *>(&Kl[kk * DH + ((ch ^ (kk & (PR - 1))) << 3)]) = kreg##it; \
             *reinterpret_cast<uint4 *>(&Kl[(kk + 1) * DH + ((ch ^ ((kk + 1) & (PR - 1))) << 3)]) = kreh##it; \
-            const uint32_t u[4] = {vreg##it.x, vreg##it.y, vreg##it.z, vreg##it.w}; \
-            const uint32_t uh[4] = {vreh##it.x, vreh##it.y, vreh##it.z, vreh##it.w}; \
-            const int kchunk = perm_chunk(kk), kel = perm_elem(kk); \
-            _Pragma("unroll") for (int x = 0; x < 8; x++) { \
-                const int c = 8 * ch + x; \
-                const uint32_t wv = (x & 1) ? ((u[x >> 1] >> 16) | (uh[x >> 1] & 0xFFFF0000u)) : ((u[x >> 1] & 0xFFFFu) | (uh[x >> 1] << 16)); \
-                *reinterpret_cast<uint32_t *>(&Vt[c * 128 + ((kchunk ^ ((c ^ (c >> 3)) & 15)) << 3) + kel]) = wv; \
-            } }
+            *reinterpret_cast<uint4 *>(&Vr[kk * DH + ((ch ^ vswz2<PR>(kk)) << 3)]) = vreg##it; \
+            *reinterpret_cast<uint4 *>(&Vr[(kk + 1) * DH + ((ch ^ vswz2<PR>(kk + 1)) << 3)]) = vreh##it; }
         LOLA_REP8(LOLA_KVLOAD)
         lds_barrier();   // previous users of L (H^T, or the previous block) are done
         LOLA_REP8(LOLA_KVSTORE)
@@ -158,10 +151,15 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
             for (int e = 0; e < 8; e++) { pw[e] = fexp2(sc[2 * s + (e >> 2)][e & 3] - mrun); lsum += pw[e]; }
             bf16x8 Ph, Pl;
             split8(pw, Ph, Pl);
+            // A = V^T of keys 32 s ..: lane (column r16 of tile mt, group g4) holds keys 4 g4 + 0..3 and 16 + 4 g4 + 0..3 (the
+            // order of pw) of its column, through the transposing read of the row-major block
+            const int t0 = 4 * g4 + (r16 >> 2);
+            const uint16_t *vb = &Vr[(32 * s + t0) * DH + 4 * (r16 & 1)];
 #pragma unroll
             for (int mt = 0; mt < NCT; mt++) {
-                const int c = 16 * mt + r16;
-                const bf16x8 Av = as_bf16x8(*reinterpret_cast<const uint4 *>(&Vt[c * 128 + (((4 * s + g4) ^ ((c ^ (c >> 3)) & 15)) << 3)]));
+                const int pc = ((2 * mt + ((r16 & 3) >> 1)) ^ vswz2<PR>(t0)) << 3;
+                const bf16x4 b0 = tr_read(vb + pc), b1 = tr_read(vb + 16 * DH + pc);
+                const bf16x8 Av = __builtin_shufflevector(b0, b1, 0, 1, 2, 3, 4, 5, 6, 7);
                 out[mt] = mfma16(Av, Ph, out[mt]);
                 out[mt] = mfma16(Av, Pl, out[mt]);
             }
@@ -277,7 +275,7 @@ __global__ __launch_bounds__(256, 2) void attend_wide_kernel(generic::PrefillArg
     constexpr int M = DF / 2, C = 64, KS = DH / 32, PR = DH / 8, NCT = DH / 16, NZT = M / 16, KSD = DF / 32, NFH = DF / 128;
     constexpr int MAXLAM = 1024;
     static_assert((DH == 64 || DH == 128) && (DF == 128 || DF == 256), "shape");
-    __shared__ __attribute__((aligned(16))) uint16_t L[2 * DH * 128];   // 64 KB: K block + V^T block, then half of H^T (high/low parts)
+    __shared__ __attribute__((aligned(16))) uint16_t L[2 * DH * 128];   // 64 KB: K block + V block, then half of H^T (high/low parts)
     __shared__ __attribute__((aligned(16))) float s_l[DF];
     __shared__ int G_l[MAXLAM];
 
@@ -320,7 +318,7 @@ __global__ __launch_bounds__(256, 2) void attend_wide_kernel(generic::PrefillArg
     };
 
     // ---- softmax part over key blocks of 128 positions
-    uint16_t *Kl = L, *Vt = L + DH * 128;   // [key][input piece ^ key % pieces] and [c][key chunk ^ swz(c)]
+    uint16_t *Kl = L, *Vr = L + DH * 128;   // [key][input piece ^ key % pieces] and [key][piece ^ vswz2(key)] (read transposed)
     f32x4 out[NCT];
 #pragma unroll
     for (int mt = 0; mt < NCT; mt++) out[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -328,8 +326,8 @@ __global__ __launch_bounds__(256, 2) void attend_wide_kernel(generic::PrefillArg
     const int64_t tq = aj + qi;     // token index of this lane's query
 #pragma unroll 1
     for (int blk = 0; blk < NB; blk++) {
-        // a thread stages PR / 4 items of the block, each one 16-byte piece of two neighbouring keys: the transposed values
-        // are then written as 32-bit words (two keys of one column)
+        // a thread stages PR / 4 items of the block, each one 16-byte piece of two neighbouring keys; the values stay
+        // row-major (the value GEMM reads them through the transposing LDS read)
         constexpr int NIT = PR / 4;
         uint4 kreg[NIT], kreh[NIT], vreg[NIT], vreh[NIT];
 #pragma unroll
@@ -352,15 +350,8 @@ __global__ __launch_bounds__(256, 2) void attend_wide_kernel(generic::PrefillArg
             const int o = tid + 256 * it, kk = 2 * (o / PR), ch = o % PR;
             *reinterpret_cast<uint4 *>(&Kl[kk * DH + ((ch ^ (kk & (PR - 1))) << 3)]) = kreg[it];
             *reinterpret_cast<uint4 *>(&Kl[(kk + 1) * DH + ((ch ^ ((kk + 1) & (PR - 1))) << 3)]) = kreh[it];
-            const uint32_t u[4] = {vreg[it].x, vreg[it].y, vreg[it].z, vreg[it].w};
-            const uint32_t uh[4] = {vreh[it].x, vreh[it].y, vreh[it].z, vreh[it].w};
-            const int kchunk = perm_chunk(kk), kel = perm_elem(kk);
-#pragma unroll
-            for (int x = 0; x < 8; x++) {
-                const int c = 8 * ch + x;
-                const uint32_t wv = (x & 1) ? ((u[x >> 1] >> 16) | (uh[x >> 1] & 0xFFFF0000u)) : ((u[x >> 1] & 0xFFFFu) | (uh[x >> 1] << 16));
-                *reinterpret_cast<uint32_t *>(&Vt[c * 128 + ((kchunk ^ ((c ^ (c >> 3)) & 15)) << 3) + kel]) = wv;
-            }
+            *reinterpret_cast<uint4 *>(&Vr[kk * DH + ((ch ^ vswz2<PR>(kk)) << 3)]) = vreg[it];
+            *reinterpret_cast<uint4 *>(&Vr[(kk + 1) * DH + ((ch ^ vswz2<PR>(kk + 1)) << 3)]) = vreh[it];
         }
         __syncthreads();
         // S^T = K Q^T for the 8 key tiles of the block; lane (column = query r16, group g4) holds keys 16 mt + 4 g4 + i
@@ -397,10 +388,15 @@ __global__ __launch_bounds__(256, 2) void attend_wide_kernel(generic::PrefillArg
             for (int e = 0; e < 8; e++) { pw[e] = fexp2(sc[2 * s + (e >> 2)][e & 3] - mrun); lsum += pw[e]; }
             bf16x8 Ph, Pl;
             split8(pw, Ph, Pl);
+            // A = V^T of keys 32 s ..: lane (column r16 of tile mt, group g4) holds keys 4 g4 + 0..3 and 16 + 4 g4 + 0..3 (the
+            // order of pw) of its column, through the transposing read of the row-major block
+            const int t0 = 4 * g4 + (r16 >> 2);
+            const uint16_t *vb = &Vr[(32 * s + t0) * DH + 4 * (r16 & 1)];
 #pragma unroll
             for (int mt = 0; mt < NCT; mt++) {
-                const int c = 16 * mt + r16;
-                const bf16x8 Av = as_bf16x8(*reinterpret_cast<const uint4 *>(&Vt[c * 128 + (((4 * s + g4) ^ ((c ^ (c >> 3)) & 15)) << 3)]));
+                const int pc = ((2 * mt + ((r16 & 3) >> 1)) ^ vswz2<PR>(t0)) << 3;
+                const bf16x4 b0 = tr_read(vb + pc), b1 = tr_read(vb + 16 * DH + pc);
+                const bf16x8 Av = __builtin_shufflevector(b0, b1, 0, 1, 2, 3, 4, 5, 6, 7);
                 out[mt] = mfma16(Av, Ph, out[mt]);
                 out[mt] = mfma16(Av, Pl, out[mt]);
             }
