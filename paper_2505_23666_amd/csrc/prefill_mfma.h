@@ -43,6 +43,7 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
     __shared__ __attribute__((aligned(16))) uint16_t L[2 * DH * D];   // 64 KB: H^T high/low parts, then K block + V block
     __shared__ __attribute__((aligned(16))) float s_l[D];
     __shared__ int G_l[LAM > 0 ? LAM : 1];
+    __shared__ int gneg_l[4];   // per wavefront: it saw an empty cache slot
 
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r16 = lane & 15, g4 = lane >> 4;
     const int j = a.j0 + blockIdx.x, jj = j - a.jb, hq = blockIdx.y, b = blockIdx.z;
@@ -70,8 +71,14 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) BQ[ks] = ld_bf16x8(qh + (size_t)(qi < cl ? qi : 0) * DH + 32 * ks + 8 * g4);
     if (tid < D / 4) reinterpret_cast<float4 *>(s_l)[tid] = reinterpret_cast<const float4 *>(ssnap)[tid];
-    for (int x = tid; x < LAM; x += 256) G_l[x] = Gsnap[x];
+    bool gneg = false;
+    for (int x = tid; x < LAM; x += 256) { const int gr = Gsnap[x]; G_l[x] = gr; gneg |= gr < 0; }
+    if (lane == 0) gneg_l[w] = 0;
+    if (gneg) gneg_l[w] = 1;   // (after the store of 0 in program order; lanes of one wavefront, same value)
     lds_barrier();
+    // Key blocks that lie in the cache and the window need no masks when every slot is in use, the window is full and the
+    // queries may read the cache: the per-element tests (an LDS read and three compares each) are skipped there.
+    const bool nomask_ok = !(gneg_l[0] | gneg_l[1] | gneg_l[2] | gneg_l[3]) && !(a.dm.hide & 2) && aj >= ETA;
 
     // ---- softmax part over key blocks of 128 positions
     uint16_t *Kl = L, *Vr = L + DH * 128;   // [key][input piece ^ key % pieces] and [key][piece ^ vswz2(key)] (read transposed)
@@ -125,15 +132,20 @@ __global__ __launch_bounds__(256, 2) void attend_fast_kernel(generic::PrefillArg
 #pragma unroll
             for (int ks = 0; ks < KS; ks++)
                 acc = mfma16(as_bf16x8(*reinterpret_cast<const uint4 *>(&Kl[(16 * mt + r16) * DH + (((4 * ks + g4) ^ (r16 & (PR - 1))) << 3)])), BQ[ks], acc);
+            if (nomask_ok && 128 * (blk + 1) <= LAM + ETA) {
 #pragma unroll
-            for (int i = 0; i < 4; i++) {
-                const int pos = 128 * blk + 16 * mt + 4 * g4 + i;
-                bool ok;
-                if (pos < LAM) ok = G_l[pos] >= 0 && !(a.dm.hide & 2);
-                else if (pos < LAM + ETA) ok = aj - ETA + (pos - LAM) >= 0;
-                else ok = pos < NKEYS && (aj + (pos - LAM - ETA)) <= tq;
-                acc[i] = ok ? acc[i] * scale2 : -INFINITY;
-                bmax = fmaxf(bmax, acc[i]);
+                for (int i = 0; i < 4; i++) { acc[i] *= scale2; bmax = fmaxf(bmax, acc[i]); }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; i++) {
+                    const int pos = 128 * blk + 16 * mt + 4 * g4 + i;
+                    bool ok;
+                    if (pos < LAM) ok = G_l[pos] >= 0 && !(a.dm.hide & 2);
+                    else if (pos < LAM + ETA) ok = aj - ETA + (pos - LAM) >= 0;
+                    else ok = pos < NKEYS && (aj + (pos - LAM - ETA)) <= tq;
+                    acc[i] = ok ? acc[i] * scale2 : -INFINITY;
+                    bmax = fmaxf(bmax, acc[i]);
+                }
             }
             sc[mt] = acc;
         }
